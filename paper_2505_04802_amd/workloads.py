@@ -1,0 +1,198 @@
+"""Seeded synthetic workloads: the five benchmark shapes, fields and weights.
+
+This module holds no arithmetic of the method itself.  It only draws the random
+numbers (fields, weights) that both the CPU oracle and the HIP library receive
+as inputs, so the two never need a random generator of their own.
+
+Shapes follow the paper's workloads: coarse multi-variable latitude/longitude
+grids (Table 1), patch size 2 (Sec. 6), and the (embed dim, layers, heads)
+triples of Sec. 5 "Model Configuration".  The public datasets the paper uses are
+replaced by smooth random-Fourier fields standardised per variable.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, asdict, replace
+from typing import Dict
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class ReslimConfig:
+    """One Reslim+TILES problem.  Field names follow the C struct `reslim_config`."""
+    name: str
+    batch: int
+    in_vars: int
+    out_vars: int
+    H: int
+    W: int
+    scale: int
+    patch: int
+    embed_dim: int
+    heads: int
+    mlp_ratio: int
+    depth: int
+    tiles_y: int
+    tiles_x: int
+    halo: int
+    res_idx: int = 0
+    n_res: int = 2
+    dtype: int = 1          # 0 = fp32 debug path, 1 = bf16 operands / fp32 accumulate
+    seed: int = 0
+
+    @property
+    def Hp(self) -> int:
+        return self.H // self.patch
+
+    @property
+    def Wp(self) -> int:
+        return self.W // self.patch
+
+    @property
+    def n_tokens(self) -> int:
+        return self.Hp * self.Wp
+
+    @property
+    def head_dim(self) -> int:
+        return self.embed_dim // self.heads
+
+    @property
+    def head_out(self) -> int:
+        ps = self.patch * self.scale
+        return self.out_vars * ps * ps
+
+    def as_dict(self) -> Dict:
+        return asdict(self)
+
+    def with_(self, **kw) -> "ReslimConfig":
+        return replace(self, **kw)
+
+
+CONFIGS: Dict[str, ReslimConfig] = {
+    # tiny fp32 case the oracle finishes in well under a second
+    "c0": ReslimConfig("c0", batch=1, in_vars=2, out_vars=2, H=32, W=64, scale=4, patch=2,
+                       embed_dim=128, heads=4, mlp_ratio=4, depth=2,
+                       tiles_y=2, tiles_x=2, halo=0, dtype=0),
+    # the configuration the headline metric is quoted on
+    "c1": ReslimConfig("c1", batch=4, in_vars=8, out_vars=8, H=128, W=256, scale=4, patch=2,
+                       embed_dim=512, heads=8, mlp_ratio=4, depth=6,
+                       tiles_y=4, tiles_x=4, halo=2),
+    "c2": ReslimConfig("c2", batch=2, in_vars=16, out_vars=16, H=360, W=720, scale=4, patch=2,
+                       embed_dim=1024, heads=16, mlp_ratio=4, depth=12,
+                       tiles_y=8, tiles_x=8, halo=2),
+    "c3": ReslimConfig("c3", batch=1, in_vars=16, out_vars=16, H=720, W=1440, scale=8, patch=2,
+                       embed_dim=1024, heads=16, mlp_ratio=4, depth=8,
+                       tiles_y=16, tiles_x=16, halo=4),
+    "c4": ReslimConfig("c4", batch=1, in_vars=32, out_vars=32, H=256, W=512, scale=4, patch=2,
+                       embed_dim=4096, heads=32, mlp_ratio=4, depth=4,
+                       tiles_y=4, tiles_x=4, halo=2),
+}
+
+
+# --------------------------------------------------------------------------- bf16
+def round_to_bf16(a: np.ndarray) -> np.ndarray:
+    """Round fp32 values to the nearest bfloat16 (ties to even); result stays fp32."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    u = a.view(np.uint32).astype(np.uint64)
+    lsb = (u >> 16) & 1
+    u = (u + 0x7FFF + lsb) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(a.shape)
+
+
+# --------------------------------------------------------------------------- fields
+def make_fields(cfg: ReslimConfig, batch: int | None = None, n_modes: int = 16,
+                noise_std: float = 0.1) -> np.ndarray:
+    """x[B, V, H, W] fp32: red-spectrum random Fourier modes plus white noise,
+    standardised per variable over (B, H, W)."""
+    B = cfg.batch if batch is None else batch
+    V, H, W = cfg.in_vars, cfg.H, cfg.W
+    rng = np.random.default_rng([cfg.seed, 0])
+    yy = (np.arange(H, dtype=np.float64) / H)[:, None]
+    xx = (np.arange(W, dtype=np.float64) / W)[None, :]
+    out = np.empty((B, V, H, W), dtype=np.float64)
+    for b in range(B):
+        for v in range(V):
+            k = rng.integers(-8, 9, size=n_modes)
+            l = rng.integers(-8, 9, size=n_modes)
+            a = rng.standard_normal(n_modes) / (1.0 + np.sqrt(k * k + l * l))
+            ph = rng.uniform(0.0, 2.0 * np.pi, size=n_modes)
+            f = np.zeros((H, W), dtype=np.float64)
+            for m in range(n_modes):
+                f += a[m] * np.cos(2.0 * np.pi * (k[m] * yy + l[m] * xx) + ph[m])
+            f += noise_std * rng.standard_normal((H, W))
+            out[b, v] = f
+    mean = out.mean(axis=(0, 2, 3), keepdims=True)
+    std = out.std(axis=(0, 2, 3), keepdims=True)
+    return ((out - mean) / std).astype(np.float32)
+
+
+# --------------------------------------------------------------------------- weights
+def _trunc_normal(rng: np.random.Generator, shape, std: float = 0.02) -> np.ndarray:
+    """N(0, std^2) truncated at +-2 std by rejection, fp32."""
+    n = int(np.prod(shape))
+    out = rng.standard_normal(n, dtype=np.float32)
+    bad = np.flatnonzero(np.abs(out) > 2.0)
+    while bad.size:
+        out[bad] = rng.standard_normal(bad.size, dtype=np.float32)
+        bad = bad[np.abs(out[bad]) > 2.0]
+    out *= np.float32(std)
+    return out.reshape(shape)
+
+
+def weight_shapes(cfg: ReslimConfig) -> Dict[str, tuple]:
+    """Names and shapes of every parameter tensor.  Linear maps are stored
+    [out_features, in_features] row-major; per-block tensors are stacked over depth."""
+    V, C, D, L = cfg.in_vars, cfg.out_vars, cfg.embed_dim, cfg.depth
+    p2 = cfg.patch * cfg.patch
+    R = cfg.mlp_ratio * D
+    return {
+        "w_pe": (V, D, p2), "b_pe": (V, D), "var_emb": (V, D),
+        "agg_q0": (D,),
+        "agg_wq": (D, D), "agg_bq": (D,),
+        "agg_wk": (D, D), "agg_bk": (D,),
+        "agg_wv": (D, D), "agg_bv": (D,),
+        "agg_wo": (D, D), "agg_bo": (D,),
+        "pos_emb": (cfg.n_tokens, D), "res_emb": (cfg.n_res, D),
+        "ln1_g": (L, D), "ln1_b": (L, D),
+        "w_qkv": (L, 3 * D, D), "b_qkv": (L, 3 * D),
+        "w_proj": (L, D, D), "b_proj": (L, D),
+        "ln2_g": (L, D), "ln2_b": (L, D),
+        "w_fc1": (L, R, D), "b_fc1": (L, R),
+        "w_fc2": (L, D, R), "b_fc2": (L, D),
+        "lnf_g": (D,), "lnf_b": (D,),
+        "w_head": (cfg.head_out, D), "b_head": (cfg.head_out,),
+        "w_res": (C, C, 3, 3), "b_res": (C,),
+    }
+
+
+# tensors that feed bf16 MFMA operands on the bf16 path and are therefore rounded
+# once here, so that the oracle and the library receive identical values
+_BF16_ROUNDED = ("agg_wo", "w_qkv", "w_proj", "w_fc1", "w_fc2", "w_head")
+
+
+def make_weights(cfg: ReslimConfig, std: float = 0.02) -> Dict[str, np.ndarray]:
+    """All parameters ~ truncated normal(std); LayerNorm gains are 1 + that, so a
+    dropped gain or shift shows up in parity.  `out_var_idx` selects which input
+    variables feed the residual path (identity selection for the five configs)."""
+    rng = np.random.default_rng([cfg.seed, 1])
+    w: Dict[str, np.ndarray] = {}
+    for name, shape in weight_shapes(cfg).items():
+        t = _trunc_normal(rng, shape, std)
+        if name in ("ln1_g", "ln2_g", "lnf_g"):
+            t = (t + np.float32(1.0)).astype(np.float32)
+        if cfg.dtype == 1 and name in _BF16_ROUNDED:
+            t = round_to_bf16(t)
+        w[name] = np.ascontiguousarray(t, dtype=np.float32)
+    w["out_var_idx"] = np.arange(cfg.out_vars, dtype=np.int32) % cfg.in_vars
+    return w
+
+
+def make_qkv(n_rows: int, embed_dim: int, seed: int = 0, peaked: bool = False,
+             bf16: bool = True) -> np.ndarray:
+    """qkv[n_rows, 3*embed_dim] ~ N(0,1) for kernel-level attention tests (logit
+    std about 1); `peaked` scales q and k so the softmax is close to one-hot."""
+    rng = np.random.default_rng([seed, 2])
+    a = rng.standard_normal((n_rows, 3 * embed_dim), dtype=np.float32)
+    if peaked:
+        a[:, : 2 * embed_dim] *= np.float32(3.0)
+    return round_to_bf16(a) if bf16 else a

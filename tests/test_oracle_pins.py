@@ -1,0 +1,343 @@
+"""Pins for the CPU oracle: each function is checked against something other than
+itself -- brute force on tiny inputs, closed forms, special cases that reduce to a
+PyTorch CPU library routine (never used by the oracle or by the HIP path), and the
+figures the paper prints.  CPU only."""
+import itertools
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import reslim_oracle as O
+from paper_2505_04802_amd import workloads as WL
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+torch.set_default_dtype(torch.float64)
+
+
+def T(a):
+    return torch.from_numpy(np.ascontiguousarray(np.asarray(a, np.float64)))
+
+
+def small_cfg(**kw):
+    base = WL.ReslimConfig("t", batch=2, in_vars=3, out_vars=3, H=16, W=24, scale=2, patch=2,
+                           embed_dim=32, heads=4, mlp_ratio=2, depth=2, tiles_y=2, tiles_x=3,
+                           halo=1, dtype=0, seed=3)
+    return base.with_(**kw)
+
+
+def big_weights(cfg, std=0.3):
+    """weights with a visible spread, so softmaxes are far from uniform"""
+    return WL.make_weights(cfg, std=std)
+
+
+# ----------------------------------------------------------------- partition
+def test_partition_bruteforce_small_grids():
+    for Hp, Wp in [(1, 1), (3, 5), (6, 6), (7, 12), (12, 9)]:
+        for Ty, Tx, h in itertools.product(range(1, 5), range(1, 5), range(0, 4)):
+            if Ty > Hp or Tx > Wp:
+                with pytest.raises(ValueError):
+                    O.tiles_partition(Hp, Wp, Ty, Tx, h)
+                continue
+            tiles, g, src, n_h = O.tiles_partition(Hp, Wp, Ty, Tx, h)
+            assert len(tiles) == Ty * Tx and n_h == len(g) == sum(t["n_tok"] for t in tiles)
+            owner = np.full((Hp, Wp), -1)
+            cover = np.zeros((Hp, Wp), int)
+            for ti, t in enumerate(tiles):
+                assert (owner[t["y0"]:t["y1"], t["x0"]:t["x1"]] == -1).all()
+                owner[t["y0"]:t["y1"], t["x0"]:t["x1"]] = ti
+                cover[t["Y0"]:t["Y1"], t["X0"]:t["X1"]] += 1
+                # the halo is exactly `h` wide unless the domain edge clips it
+                assert t["Y0"] == max(0, t["y0"] - h) and t["X1"] == min(Wp, t["x1"] + h)
+                assert t["tok_off"] == sum(u["n_tok"] for u in tiles[:ti])
+                # balanced cut: sizes differ by at most one
+                assert (t["y1"] - t["y0"]) in (Hp // Ty, -(-Hp // Ty))
+            assert (owner >= 0).all()                      # interiors tile the grid
+            # multiplicity of a patch in the gather list = number of haloed boxes over it
+            assert (np.bincount(g, minlength=Hp * Wp).reshape(Hp, Wp) == cover).all()
+            assert (g[src] == np.arange(Hp * Wp)).all()    # scatter map inverts the gather
+            assert len(set(src.tolist())) == Hp * Wp
+            for gidx in range(Hp * Wp):                    # and points inside the owner tile
+                t = tiles[owner[gidx // Wp, gidx % Wp]]
+                assert t["tok_off"] <= src[gidx] < t["tok_off"] + t["n_tok"]
+            if Ty == 1 and Tx == 1:
+                assert n_h == Hp * Wp and (g == np.arange(Hp * Wp)).all()
+
+
+def test_partition_halo_closed_form_and_config_sizes():
+    # when no tile is narrower than the halo, every inner cut line adds 2h rows/cols
+    for Hp, Wp, Ty, Tx, h in [(64, 128, 4, 4, 2), (180, 360, 8, 8, 2), (360, 720, 16, 16, 4),
+                              (128, 256, 4, 4, 2), (16, 32, 2, 2, 0)]:
+        tiles, g, src, n_h = O.tiles_partition(Hp, Wp, Ty, Tx, h)
+        assert n_h == (Hp + 2 * h * (Ty - 1)) * (Wp + 2 * h * (Tx - 1))
+    n_t = [t["n_tok"] for t in O.tiles_partition(180, 360, 8, 8, 2)[0]]
+    assert (min(n_t), max(n_t)) == (24 * 47, 27 * 49)
+
+
+def test_attention_cost_linear_in_tiles():
+    """Sec. 4.2: cost O(N^2/T); with a fixed tile size it grows linearly with N."""
+    base = O.attention_pair_count(O.tiles_partition(8, 8, 1, 1, 0)[0])
+    for k in (2, 3, 4, 6):
+        tiles = O.tiles_partition(8 * k, 8 * k, k, k, 0)[0]
+        assert O.attention_pair_count(tiles) == base * k * k          # linear in N = 64 k^2
+        N = 64 * k * k
+        assert O.attention_pair_count(tiles) == N * N // (k * k)      # N^2 / T
+
+
+def test_paper_token_counts():
+    """Sequence lengths the paper prints (Sec. 6, Table 3) equal H*W*vars/p^2 with
+    2x2 patches; the untiled partition's token count reproduces them."""
+    rows = json.load(open(os.path.join(GOLDEN, "paper_sequence_lengths.json")))["rows"]
+    for r in rows:
+        H, W, C = r["shape"]
+        assert abs(r["tokens_exact"] - r["printed"]) <= r["printed_tolerance"]
+        if H * W <= 720 * 1440:       # the Python-loop partition is only run on the small rows
+            n_h = O.tiles_partition(H // 2, W // 2, 1, 1, 0)[3]
+            assert n_h * C == r["tokens_exact"]
+
+
+# ----------------------------------------------------------------- block pieces
+def test_layer_norm_gelu_linear_vs_library_and_closed_form():
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((7, 48)) * 3 + 1
+    g, b = rng.standard_normal(48), rng.standard_normal(48)
+    assert np.allclose(O.layer_norm(x, g, b), F.layer_norm(T(x), (48,), T(g), T(b), 1e-5).numpy(), atol=1e-12)
+    y = O.layer_norm(x, np.ones(48), np.zeros(48))
+    assert np.allclose(y.mean(-1), 0, atol=1e-12)
+    assert np.allclose(y.var(-1), x.var(-1) / (x.var(-1) + 1e-5), atol=1e-12)
+    assert np.allclose(O.gelu(np.array([0.0, 1.0, -1.0])), [0.0, 0.8413447460685429, -0.15865525393145707], atol=1e-15)
+    assert np.allclose(O.gelu(x), F.gelu(T(x)).numpy(), atol=1e-13)
+    w, bb = rng.standard_normal((5, 48)), rng.standard_normal(5)
+    ref = np.array([[sum(x[i, k] * w[o, k] for k in range(48)) + bb[o] for o in range(5)] for i in range(7)])
+    assert np.allclose(O.linear(x, w, bb), ref, atol=1e-12)
+
+
+def test_self_attention_vs_sdpa_and_special_cases():
+    rng = np.random.default_rng(1)
+    n, D, h = 37, 48, 4
+    q, k, v = (rng.standard_normal((n, D)) for _ in range(3))
+    out = O.self_attention(q, k, v, h)
+    sp = lambda a: T(a).reshape(n, h, D // h).transpose(0, 1)[None]
+    ref = F.scaled_dot_product_attention(sp(q), sp(k), sp(v))[0].transpose(0, 1).reshape(n, D).numpy()
+    assert np.allclose(out, ref, atol=1e-12)
+    # q = 0: uniform softmax, every output row is the column mean of v
+    assert np.allclose(O.self_attention(np.zeros_like(q), k, v, h), np.tile(v.mean(0), (n, 1)), atol=1e-13)
+    # constant v rows: output equals that row
+    vc = np.tile(rng.standard_normal(D), (n, 1))
+    assert np.allclose(O.self_attention(q, k, vc, h), vc, atol=1e-12)
+    # q = k scaled up, distinct rows: softmax is one-hot on the diagonal
+    kk = rng.standard_normal((n, h, D // h))
+    kk = (kk / np.linalg.norm(kk, axis=-1, keepdims=True)).reshape(n, D)   # unit rows per head
+    assert np.allclose(O.self_attention(60 * kk, 60 * kk, v, h), v, atol=1e-9)
+    # permuting the tokens permutes the output
+    perm = rng.permutation(n)
+    assert np.allclose(O.self_attention(q[perm], k[perm], v[perm], h), out[perm], atol=1e-12)
+    assert np.allclose(O.softmax(rng.standard_normal((5, 9)) * 30).sum(-1), 1, atol=1e-14)
+
+
+def test_tiles_attention_equals_masked_global_attention():
+    """Tile-local attention = global attention with -inf between tokens of different
+    tile copies, by brute force over all pairs (tiny grid, with halo duplicates)."""
+    rng = np.random.default_rng(2)
+    for (Hp, Wp, Ty, Tx, h) in [(4, 6, 2, 2, 0), (5, 6, 2, 3, 1), (4, 4, 1, 1, 2)]:
+        tiles, g, src, n_h = O.tiles_partition(Hp, Wp, Ty, Tx, h)
+        D, heads = 8, 2
+        dh = D // heads
+        qkv = rng.standard_normal((1, n_h, 3 * D))
+        out = O.tiles_attention(qkv, tiles, heads)
+        tile_of = np.concatenate([np.full(t["n_tok"], i) for i, t in enumerate(tiles)])
+        for head in range(heads):
+            qs = slice(head * dh, (head + 1) * dh)
+            for i in range(n_h):
+                num = np.zeros(dh)
+                den = 0.0
+                for j in range(n_h):
+                    if tile_of[j] != tile_of[i]:
+                        continue
+                    s = sum(qkv[0, i, head * dh + d] * qkv[0, j, D + head * dh + d] for d in range(dh)) / math.sqrt(dh)
+                    num += math.exp(s) * qkv[0, j, 2 * D + head * dh: 2 * D + (head + 1) * dh]
+                    den += math.exp(s)
+                assert np.allclose(out[0, i, qs], num / den, atol=1e-12)
+        if Ty == Tx == 1:   # one tile over the whole domain = plain global attention
+            assert np.allclose(out[0], O.self_attention(qkv[0, :, :D], qkv[0, :, D:2 * D], qkv[0, :, 2 * D:], heads), atol=1e-14)
+
+
+def test_block_vs_torch_transformer_encoder_layer():
+    """The pre-LN block with erf-GELU is PyTorch's TransformerEncoderLayer(norm_first)."""
+    cfg = small_cfg()
+    w = big_weights(cfg, 0.2)
+    D, R = cfg.embed_dim, cfg.embed_dim * cfg.mlp_ratio
+    layer = torch.nn.TransformerEncoderLayer(D, cfg.heads, R, dropout=0.0, activation="gelu",
+                                             batch_first=True, norm_first=True).double().eval()
+    l = 1
+    with torch.no_grad():
+        layer.self_attn.in_proj_weight.copy_(T(w["w_qkv"][l])); layer.self_attn.in_proj_bias.copy_(T(w["b_qkv"][l]))
+        layer.self_attn.out_proj.weight.copy_(T(w["w_proj"][l])); layer.self_attn.out_proj.bias.copy_(T(w["b_proj"][l]))
+        layer.linear1.weight.copy_(T(w["w_fc1"][l])); layer.linear1.bias.copy_(T(w["b_fc1"][l]))
+        layer.linear2.weight.copy_(T(w["w_fc2"][l])); layer.linear2.bias.copy_(T(w["b_fc2"][l]))
+        layer.norm1.weight.copy_(T(w["ln1_g"][l])); layer.norm1.bias.copy_(T(w["ln1_b"][l]))
+        layer.norm2.weight.copy_(T(w["ln2_g"][l])); layer.norm2.bias.copy_(T(w["ln2_b"][l]))
+        X = np.random.default_rng(5).standard_normal((29, D))
+        ref = layer(T(X)[None])[0].numpy()
+    assert np.allclose(O.block_tokens(X, w, l, cfg.heads), ref, atol=1e-11)
+
+
+# ----------------------------------------------------------------- front end
+def test_patch_embed_is_strided_convolution():
+    cfg = small_cfg()
+    w = big_weights(cfg)
+    x = WL.make_fields(cfg)
+    e = O.patch_embed(x, w, cfg.patch)
+    for v in range(cfg.in_vars):
+        k = T(w["w_pe"][v]).reshape(cfg.embed_dim, 1, cfg.patch, cfg.patch)
+        ref = F.conv2d(T(x[:, v:v + 1]), k, T(w["b_pe"][v]) + T(w["var_emb"][v]), stride=cfg.patch)
+        ref = ref.flatten(2).transpose(1, 2).numpy()       # [B, N, D], n = py*Wp + px
+        assert np.allclose(e[:, :, v, :], ref, atol=1e-12)
+
+
+def test_variable_aggregation_vs_torch_mha_and_closed_forms():
+    cfg = small_cfg()
+    w = big_weights(cfg, 0.4)
+    D, V = cfg.embed_dim, cfg.in_vars
+    rng = np.random.default_rng(7)
+    e = rng.standard_normal((11, V, D))
+    z = O.variable_aggregation(e, w, cfg.heads)
+    q = T(w["agg_q0"]).reshape(1, 1, D).expand(1, 11, D)            # [L=1, batch=11, D]
+    kv = T(e).transpose(0, 1)                                        # [S=V, batch, D]
+    ref, _ = F.multi_head_attention_forward(
+        q, kv, kv, D, cfg.heads,
+        torch.cat([T(w["agg_wq"]), T(w["agg_wk"]), T(w["agg_wv"])]),
+        torch.cat([T(w["agg_bq"]), T(w["agg_bk"]), T(w["agg_bv"])]),
+        None, None, False, 0.0, T(w["agg_wo"]), T(w["agg_bo"]), need_weights=False)
+    assert np.allclose(z, ref[0].numpy(), atol=1e-11)
+    # one variable: the softmax over a single key is 1
+    z1 = O.variable_aggregation(e[:, :1], w, cfg.heads)
+    closed = O.linear(O.linear(e[:, 0], w["agg_wv"], w["agg_bv"]), w["agg_wo"], w["agg_bo"])
+    assert np.allclose(z1, closed, atol=1e-12)
+    # identical variables aggregate to the single-variable result
+    assert np.allclose(O.variable_aggregation(np.repeat(e[:, :1], 4, axis=1), w, cfg.heads), z1, atol=1e-12)
+
+
+def test_embed_tokens_adds_position_and_resolution_rows():
+    cfg = small_cfg()
+    w = big_weights(cfg)
+    x = WL.make_fields(cfg)
+    z = O.embed_tokens(x, w, cfg.patch, cfg.heads, res_idx=1)
+    base = O.variable_aggregation(O.patch_embed(x, w, cfg.patch), w, cfg.heads)
+    assert np.allclose(z - base, (w["pos_emb"].astype(np.float64) + w["res_emb"][1].astype(np.float64))[None], atol=1e-12)
+    # chunking over patch rows changes nothing
+    assert np.array_equal(O.embed_tokens(x, w, cfg.patch, cfg.heads, 1, chunk=1), O.embed_tokens(x, w, cfg.patch, cfg.heads, 1, chunk=10**9)) or \
+        np.allclose(O.embed_tokens(x, w, cfg.patch, cfg.heads, 1, chunk=1), z, atol=1e-13)
+
+
+# ----------------------------------------------------------------- back end
+def test_unpatchify_is_pixel_shuffle_and_inverts_patchify():
+    rng = np.random.default_rng(8)
+    B, Hp, Wp, C, ps = 2, 3, 5, 3, 4
+    P = rng.standard_normal((B, Hp * Wp, C * ps * ps))
+    y = O.unpatchify(P, Hp, Wp, C, ps)
+    ref = F.pixel_shuffle(T(P).reshape(B, Hp, Wp, C * ps * ps).permute(0, 3, 1, 2), ps).numpy()
+    assert np.array_equal(y, ref)
+    back = F.unfold(T(y), ps, stride=ps).transpose(1, 2).numpy()   # [B, N, C*ps*ps], c slowest
+    assert np.array_equal(back, P)
+
+
+def test_bilinear_and_conv_vs_library_and_closed_forms():
+    rng = np.random.default_rng(9)
+    u = rng.standard_normal((3, 7, 10))
+    for s in (2, 4, 8):
+        ref = F.interpolate(T(u)[None], scale_factor=s, mode="bilinear", align_corners=False)[0].numpy()
+        assert np.allclose(O.bilinear_upsample(u, s), ref, atol=1e-13)
+    wgt, b = rng.standard_normal((4, 3, 3, 3)), rng.standard_normal(4)
+    assert np.allclose(O.conv3x3_same(u, wgt, b), F.conv2d(T(u)[None], T(wgt), T(b), padding=1)[0].numpy(), atol=1e-12)
+    # centre-delta kernel, no bias: the residual path is the upsampler alone
+    delta = np.zeros((3, 3, 3, 3)); delta[np.arange(3), np.arange(3), 1, 1] = 1
+    w = dict(out_var_idx=np.arange(3), w_res=delta, b_res=np.zeros(3))
+    assert np.allclose(O.residual_path(u, w, 4), O.bilinear_upsample(u, 4), atol=1e-14)
+    # a constant field stays constant away from the zero-padded rim
+    c = np.full((3, 6, 6), 2.5)
+    w = dict(out_var_idx=np.arange(3), w_res=wgt[:3], b_res=b[:3])
+    r = O.residual_path(c, w, 2)
+    assert np.allclose(r[:, 1:-1, 1:-1], (2.5 * wgt[:3].sum((1, 2, 3)) + b[:3])[:, None, None], atol=1e-12)
+    # a linear ramp is reproduced by bilinear interpolation away from the clamped rim
+    ramp = np.arange(12, dtype=float)[None, None, :] * np.ones((1, 5, 1))
+    up = O.bilinear_upsample(ramp, 4)
+    assert np.allclose(up[0, :, 2:-2], ((np.arange(48) + 0.5) / 4 - 0.5)[None, 2:-2], atol=1e-13)
+    # variable selection picks planes by index
+    w = dict(out_var_idx=np.array([2, 0]), w_res=wgt[:2, :2], b_res=b[:2])
+    assert np.allclose(O.residual_path(u, w, 2), O.conv3x3_same(O.bilinear_upsample(u[[2, 0]], 2), wgt[:2, :2], b[:2]), atol=1e-14)
+
+
+# ----------------------------------------------------------------- whole model
+def test_batched_form_equals_literal_tiling():
+    """Embedding once and gathering tile-major == cutting the field into haloed
+    tiles and running the untiled model on each (Sec. 4.2 taken literally)."""
+    for kw in (dict(), dict(halo=0), dict(tiles_y=3, tiles_x=2, halo=2, H=20), dict(tiles_y=1, tiles_x=1, halo=3)):
+        cfg = small_cfg(**kw)
+        w = big_weights(cfg, 0.15)
+        x = WL.make_fields(cfg)
+        ya, inter = O.reslim_forward(x, w, cfg, return_intermediates=True)
+        yb = O.reslim_forward_literal(x, w, cfg)
+        assert ya.shape == (cfg.batch, cfg.out_vars, cfg.H * cfg.scale, cfg.W * cfg.scale)
+        assert np.allclose(ya, yb, atol=1e-10), kw
+        assert np.allclose(ya, inter["y_main"] + inter["residual"])
+
+
+def test_one_tile_is_the_untiled_model_and_batch_items_are_independent():
+    cfg = small_cfg(tiles_y=1, tiles_x=1, halo=2)
+    w = big_weights(cfg, 0.15)
+    x = WL.make_fields(cfg)
+    y = O.reslim_forward(x, w, cfg)
+    for b in range(cfg.batch):
+        ref = O.untiled_forward(x[b], w, cfg, np.arange(cfg.n_tokens))
+        assert np.allclose(y[b], ref, atol=1e-10)
+    cfg2 = small_cfg()
+    y2 = O.reslim_forward(x, w, cfg2)
+    assert np.allclose(O.reslim_forward(x[1:], w, cfg2)[0], y2[1], atol=1e-12)
+    assert not np.allclose(y2, y, atol=1e-6)        # tiling is an approximation, not a no-op
+
+
+def test_residual_path_independent_of_tiling_when_halo_present():
+    """With a halo of >= 1 patch the upsample+3x3 stencil never reaches a cut edge
+    from an interior pixel, so the residual term equals the untiled one."""
+    cfg = small_cfg(halo=1)
+    w = big_weights(cfg)
+    x = WL.make_fields(cfg)
+    _, a = O.reslim_forward(x, w, cfg, return_intermediates=True)
+    _, b = O.reslim_forward(x, w, cfg.with_(tiles_y=1, tiles_x=1), return_intermediates=True)
+    assert np.allclose(a["residual"], b["residual"], atol=1e-13)
+    _, c = O.reslim_forward(x, w, cfg.with_(halo=0), return_intermediates=True)
+    assert not np.allclose(c["residual"], b["residual"], atol=1e-6)   # seams without a halo
+
+
+def test_zero_head_leaves_bias_pattern_plus_residual():
+    cfg = small_cfg()
+    w = big_weights(cfg)
+    w["w_head"] = np.zeros_like(w["w_head"])
+    x = WL.make_fields(cfg)
+    y, inter = O.reslim_forward(x, w, cfg, return_intermediates=True)
+    ps = cfg.patch * cfg.scale
+    pat = w["b_head"].astype(np.float64).reshape(cfg.out_vars, ps, ps)
+    assert np.allclose(inter["y_main"], np.tile(pat, (1, cfg.Hp, cfg.Wp))[None], atol=1e-14)
+
+
+# ----------------------------------------------------------------- generators
+def test_generators_are_seeded_and_shaped():
+    cfg = WL.CONFIGS["c0"]
+    x = WL.make_fields(cfg)
+    assert x.shape == (1, 2, 32, 64) and x.dtype == np.float32
+    assert np.allclose(x.mean((0, 2, 3)), 0, atol=1e-5) and np.allclose(x.std((0, 2, 3)), 1, atol=1e-4)
+    assert np.array_equal(x, WL.make_fields(cfg))
+    w = WL.make_weights(cfg)
+    assert set(WL.weight_shapes(cfg)) | {"out_var_idx"} == set(w)
+    assert abs(w["w_qkv"]).max() <= 0.04 + 1e-9 and abs(w["ln1_g"] - 1).max() <= 0.04 + 1e-6
+    r = WL.round_to_bf16(np.array([1.0, 1.00390625, 1.01171875, -3.3e38, 1e-40], np.float32))
+    assert np.array_equal(r[:3], np.array([1.0, 1.0, 1.015625], np.float32))     # ties to even
+    tb = torch.from_numpy(np.random.default_rng(0).standard_normal(4096).astype(np.float32))
+    assert np.array_equal(WL.round_to_bf16(tb.numpy()), tb.to(torch.bfloat16).to(torch.float32).numpy())
+    wb = WL.make_weights(WL.CONFIGS["c1"].with_(embed_dim=64, heads=2, depth=1, H=8, W=8, tiles_y=1, tiles_x=1))
+    assert np.array_equal(wb["w_qkv"], WL.round_to_bf16(wb["w_qkv"]))
