@@ -1,0 +1,189 @@
+/* reslim.h -- C ABI of the Reslim ViT forward under TILES for one MI355X (gfx950).
+ *
+ * The operations are those of ORBIT-2 (arXiv 2505.04802): Sec. 4.1 "Reslim
+ * Architecture" (per-variable tokenisation, cross-attention variable aggregation,
+ * resolution embedding, transformer blocks, decoder, residual convolutional path)
+ * and Sec. 4.2 "TILES" (partition into tiles, halo padding, tile-local
+ * self-attention, discard halos and stitch).
+ *
+ * Conventions
+ *  - Every function returns RESLIM_OK (0) or a negative error code; none throws,
+ *    aborts or prints.  reslim_last_error() gives the text of the last failure.
+ *  - "dev" pointers are device (HBM) addresses on the current HIP device, "host"
+ *    pointers are ordinary host memory.  The caller owns every buffer it passes
+ *    (input, output, workspace) and the stream; the library owns only reslim_ctx
+ *    (device copies of the weights, the tile table and the index lists).
+ *  - After reslim_create() no entry point allocates or synchronises: all work is
+ *    enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = default
+ *    stream).  A launch failure is reported as RESLIM_EHIP.
+ *  - Tensors are row-major.  Fields are [batch, variable, latitude, longitude].
+ *  - Activation element type ("act"): float when cfg.dtype == RESLIM_F32,
+ *    bfloat16 (upper 16 bits of an IEEE float) when cfg.dtype == RESLIM_BF16.
+ *    The residual token stream, the input field and the output field are float
+ *    in both modes.
+ *  - Tile-major token order: tokens of tile 0, then tile 1, ... (tiles row-major
+ *    over the tile grid); inside a tile row-major over its haloed box.  n_h is the
+ *    number of such tokens per sample (halo tokens are duplicated).
+ */
+#ifndef RESLIM_H
+#define RESLIM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  RESLIM_OK = 0,
+  RESLIM_EINVAL = -1,     /* null pointer, bad enum, bad layer index             */
+  RESLIM_ESHAPE = -2,     /* sizes that do not divide / do not fit the kernels   */
+  RESLIM_ENOMEM = -3,     /* host or device allocation failed (create only)      */
+  RESLIM_EHIP = -4,       /* a HIP call or kernel launch failed                  */
+  RESLIM_EWORKSPACE = -5  /* workspace missing, misaligned (256 B) or too small  */
+};
+
+enum { RESLIM_F32 = 0, RESLIM_BF16 = 1 };
+
+/* Problem description.  Plain data, caller-owned, copied by reslim_create. */
+typedef struct {
+  int32_t in_vars;    /* V: variables of the coarse input                        */
+  int32_t out_vars;   /* C: variables of the fine output (C <= V)                */
+  int32_t H, W;       /* coarse grid: latitude rows, longitude columns           */
+  int32_t scale;      /* s: fine grid is (s*H) x (s*W)                           */
+  int32_t patch;      /* p: patch edge in coarse pixels (the paper uses 2)       */
+  int32_t embed_dim;  /* D                                                       */
+  int32_t heads;      /* attention heads; head dim dh = D / heads                */
+  int32_t mlp_ratio;  /* r: hidden width of the feed-forward sub-layer is r*D    */
+  int32_t depth;      /* L: transformer blocks                                   */
+  int32_t tiles_y, tiles_x; /* tile grid (Sec. 4.2)                              */
+  int32_t halo;       /* halo width in patches, clipped at the domain edge       */
+  int32_t res_idx;    /* row of the resolution-embedding table to add (Sec. 4.1) */
+  int32_t n_res;      /* rows of that table                                      */
+  int32_t dtype;      /* RESLIM_F32 (debug path) or RESLIM_BF16                  */
+} reslim_config;
+
+/* Parameters, all HOST pointers to float (out_var_idx: int32), row-major, read
+ * during reslim_create only.  Linear maps are [out_features, in_features].
+ * p2 = p*p, R = r*D, N = (H/p)*(W/p), O = C*(p*s)*(p*s). */
+typedef struct {
+  const float *w_pe;      /* [V, D, p2]  patch embedding per variable            */
+  const float *b_pe;      /* [V, D]                                              */
+  const float *var_emb;   /* [V, D]      added to every token of variable v      */
+  const float *agg_q0;    /* [D]         the learned query of the aggregation    */
+  const float *agg_wq, *agg_bq;   /* [D, D], [D]                                 */
+  const float *agg_wk, *agg_bk;
+  const float *agg_wv, *agg_bv;
+  const float *agg_wo, *agg_bo;
+  const float *pos_emb;   /* [N, D]      indexed by global patch position        */
+  const float *res_emb;   /* [n_res, D]                                          */
+  const float *ln1_g, *ln1_b;     /* [L, D]                                      */
+  const float *w_qkv, *b_qkv;     /* [L, 3D, D], [L, 3D]  rows ordered q | k | v */
+  const float *w_proj, *b_proj;   /* [L, D, D], [L, D]                           */
+  const float *ln2_g, *ln2_b;     /* [L, D]                                      */
+  const float *w_fc1, *b_fc1;     /* [L, R, D], [L, R]                           */
+  const float *w_fc2, *b_fc2;     /* [L, D, R], [L, D]                           */
+  const float *lnf_g, *lnf_b;     /* [D]        final LayerNorm                  */
+  const float *w_head, *b_head;   /* [O, D], [O]  O index = (c*ps + i)*ps + j    */
+  const float *w_res, *b_res;     /* [C, C, 3, 3], [C]  residual-path convolution */
+  const int32_t *out_var_idx;     /* [C]  input variable feeding output c        */
+} reslim_weights;
+
+/* One tile of the patch grid, patch units, half-open boxes (Sec. 4.2). */
+typedef struct {
+  int32_t y0, y1, x0, x1;   /* interior: the part of the output this tile owns    */
+  int32_t Y0, Y1, X0, X1;   /* interior widened by the halo, clipped to the grid  */
+  int64_t tok_off;          /* first tile-major token index of this tile          */
+  int32_t n_tok;            /* (Y1-Y0)*(X1-X0)                                    */
+  int32_t _pad;
+} tile_desc;
+
+typedef struct reslim_ctx reslim_ctx;
+
+/* Sec. 4.2, partition + halo + stitch indices.  HOST function, integers only, no
+ * HIP call.  Cuts a patch grid Hp x Wp into Ty x Tx tiles with a balanced split
+ * (tile row i covers patch rows [floor(i*Hp/Ty), floor((i+1)*Hp/Ty))), widens
+ * each by `halo` patches and clips at the domain edge.
+ *   tiles        host [Ty*Tx] out
+ *   gather_idx   host [n_h] out or NULL: global patch id (y*Wp+x) of every
+ *                tile-major token
+ *   interior_src host [Hp*Wp] out or NULL: tile-major index of global patch g in
+ *                the tile whose interior holds it (the stitch map)
+ *   n_h_out      host out or NULL: total tile-major tokens
+ * Call once with gather_idx == NULL to learn n_h.  RESLIM_ESHAPE if Ty > Hp,
+ * Tx > Wp, any size < 1 or halo < 0. */
+int tiles_partition(int32_t Hp, int32_t Wp, int32_t Ty, int32_t Tx, int32_t halo,
+                    tile_desc *tiles, int32_t *gather_idx, int32_t *interior_src,
+                    int64_t *n_h_out);
+
+/* Validates cfg, partitions, copies the weights to the device (rounded to
+ * bfloat16 for the MFMA operands in RESLIM_BF16 mode) and folds the per-variable
+ * tokenisation into the aggregation's key/value maps (Sec. 4.1; exact, since no
+ * non-linearity separates them).  Synchronises the device once.  *out is NULL on
+ * failure.  RESLIM_BF16 needs D % 64 == 0 and dh in {64, 128}. */
+int reslim_create(const reslim_config *cfg, const reslim_weights *w, reslim_ctx **out);
+void reslim_destroy(reslim_ctx *ctx);
+
+/* Text of the most recent error of `ctx`, or of the calling thread's last failed
+ * reslim_create/tiles_partition when ctx is NULL.  Owned by the library. */
+const char *reslim_last_error(const reslim_ctx *ctx);
+
+/* n_h of the context's tiling (tile-major tokens per sample). */
+int reslim_tokens_per_sample(const reslim_ctx *ctx, int64_t *n_h_out);
+
+/* Bytes of 256-byte-aligned device workspace that reslim_forward (the largest
+ * user) needs for `batch` samples; valid for every other entry point too. */
+int reslim_workspace_bytes(const reslim_ctx *ctx, int32_t batch, size_t *out);
+
+/* Sec. 4.1 front end + Sec. 4.2 gather: tokenise each variable, aggregate the
+ * variables by cross-attention, add position and resolution embeddings, copy the
+ * tokens into tile-major order with halo duplication.
+ *   x      dev float [batch, V, H, W]
+ *   tokens dev float [batch, n_h, D] out */
+int reslim_embed_fwd(reslim_ctx *ctx, const float *x, float *tokens, int32_t batch,
+                     void *workspace, size_t ws_bytes, void *hip_stream);
+
+/* Sec. 4.2 tile-local multi-head self-attention: for every sample, tile and head,
+ * softmax(Q K^T / sqrt(dh)) V over the n_t tokens of that tile only (halo tokens
+ * are ordinary queries and keys).
+ *   qkv dev act [batch, n_h, 3, heads, dh]
+ *   out dev act [batch, n_h, heads*dh]     (must not alias qkv) */
+int tiles_attention_fwd(reslim_ctx *ctx, const void *qkv, void *out, int32_t batch,
+                        void *hip_stream);
+
+/* One pre-LayerNorm transformer block `layer` (0-based) on the tile-major stream:
+ * X += proj(tile_attention(qkv(LN1(X)))); X += fc2(gelu(fc1(LN2(X)))).
+ *   x_inout dev float [batch, n_h, D], updated in place */
+int reslim_block_fwd(reslim_ctx *ctx, int32_t layer, float *x_inout, int32_t batch,
+                     void *workspace, size_t ws_bytes, void *hip_stream);
+
+/* Back end: final LayerNorm, halo discarded (interior tokens only), linear
+ * projection to fine pixels, un-patchify and stitch, plus the residual path
+ * (bilinear upsampling by s of the selected input variables and one 3x3
+ * convolution, evaluated per tile on its haloed box) added to it.
+ *   x      dev float [batch, V, H, W]        the same field given to embed
+ *   tokens dev float [batch, n_h, D]
+ *   y      dev float [batch, C, s*H, s*W] out */
+int reslim_head_fwd(reslim_ctx *ctx, const float *x, const float *tokens, float *y,
+                    int32_t batch, void *workspace, size_t ws_bytes, void *hip_stream);
+
+/* The whole forward: embed, `depth` blocks, head.  Coarse multi-variable grid in,
+ * fine grid out. */
+int reslim_forward(reslim_ctx *ctx, const float *x, float *y, int32_t batch,
+                   void *workspace, size_t ws_bytes, void *hip_stream);
+
+/* Algorithmic work of one forward for `batch` samples, for reporting: flop of
+ * the block GEMMs, of tile attention (4*n_t^2*D per tile, block and sample) and
+ * of the head GEMM.  Any pointer may be NULL. */
+int reslim_flop_counts(const reslim_ctx *ctx, int32_t batch, double *gemm_flop,
+                       double *attn_flop, double *head_flop);
+
+/* Tuning hook for benchmarks: pins the tile shape of the bf16 GEMM kernels
+ * (-1 = built-in heuristic, 0 = 256x256, 1 = 256x128, 2 = 128x128).  Process-wide. */
+void reslim_debug_set_gemm_tile(int choice);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RESLIM_H */

@@ -1,0 +1,253 @@
+"""Thin ctypes binding over libreslim.so (declarations: include/reslim.h).
+
+Argument marshalling only -- every step of the forward runs in the library's HIP
+kernels.  PyTorch is used for device memory and the current stream.  There is no
+CPU fallback: a missing library or a missing GPU raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libreslim.so")
+
+RESLIM_OK, RESLIM_EINVAL, RESLIM_ESHAPE, RESLIM_ENOMEM, RESLIM_EHIP, RESLIM_EWORKSPACE = 0, -1, -2, -3, -4, -5
+RESLIM_F32, RESLIM_BF16 = 0, 1
+
+_CONFIG_FIELDS = ["in_vars", "out_vars", "H", "W", "scale", "patch", "embed_dim", "heads", "mlp_ratio",
+                  "depth", "tiles_y", "tiles_x", "halo", "res_idx", "n_res", "dtype"]
+_WEIGHT_FIELDS = ["w_pe", "b_pe", "var_emb", "agg_q0", "agg_wq", "agg_bq", "agg_wk", "agg_bk", "agg_wv",
+                  "agg_bv", "agg_wo", "agg_bo", "pos_emb", "res_emb", "ln1_g", "ln1_b", "w_qkv", "b_qkv",
+                  "w_proj", "b_proj", "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2", "lnf_g", "lnf_b",
+                  "w_head", "b_head", "w_res", "b_res", "out_var_idx"]
+
+EXPORTS = ["tiles_partition", "reslim_create", "reslim_destroy", "reslim_last_error",
+           "reslim_tokens_per_sample", "reslim_workspace_bytes", "reslim_embed_fwd", "tiles_attention_fwd",
+           "reslim_block_fwd", "reslim_head_fwd", "reslim_forward", "reslim_flop_counts",
+           "reslim_debug_set_gemm_tile"]
+
+
+class ReslimConfigC(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in _CONFIG_FIELDS]
+
+
+class ReslimWeightsC(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _WEIGHT_FIELDS]
+
+
+class TileDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("y0", "y1", "x0", "x1", "Y0", "Y1", "X0", "X1")] + \
+               [("tok_off", C.c_int64), ("n_tok", C.c_int32), ("_pad", C.c_int32)]
+
+
+class ReslimError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libreslim error {code}: {msg}")
+        self.code = code
+
+
+_lib: Optional[C.CDLL] = None
+
+
+def load() -> C.CDLL:
+    """dlopen the library and set the prototypes.  Needs no GPU."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built: run `python __graft_entry__.py` (hipcc, gfx950) first")
+    lib = C.CDLL(LIB_PATH)
+    for name in EXPORTS:
+        if not hasattr(lib, name):
+            raise ImportError(f"{LIB_PATH} does not export {name}")
+    vp, i32, i64p, szp = C.c_void_p, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_size_t)
+    lib.tiles_partition.argtypes = [i32, i32, i32, i32, i32, C.POINTER(TileDesc), vp, vp, i64p]
+    lib.reslim_create.argtypes = [C.POINTER(ReslimConfigC), C.POINTER(ReslimWeightsC), C.POINTER(vp)]
+    lib.reslim_destroy.argtypes = [vp]
+    lib.reslim_destroy.restype = None
+    lib.reslim_last_error.argtypes = [vp]
+    lib.reslim_last_error.restype = C.c_char_p
+    lib.reslim_tokens_per_sample.argtypes = [vp, i64p]
+    lib.reslim_workspace_bytes.argtypes = [vp, i32, szp]
+    lib.reslim_embed_fwd.argtypes = [vp, vp, vp, i32, vp, C.c_size_t, vp]
+    lib.tiles_attention_fwd.argtypes = [vp, vp, vp, i32, vp]
+    lib.reslim_block_fwd.argtypes = [vp, i32, vp, i32, vp, C.c_size_t, vp]
+    lib.reslim_head_fwd.argtypes = [vp, vp, vp, vp, i32, vp, C.c_size_t, vp]
+    lib.reslim_forward.argtypes = [vp, vp, vp, i32, vp, C.c_size_t, vp]
+    dp = C.POINTER(C.c_double)
+    lib.reslim_flop_counts.argtypes = [vp, i32, dp, dp, dp]
+    lib.reslim_debug_set_gemm_tile.argtypes = [i32]
+    lib.reslim_debug_set_gemm_tile.restype = None
+    for name in EXPORTS:
+        if name not in ("reslim_destroy", "reslim_last_error", "reslim_debug_set_gemm_tile"):
+            getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, ctx=None):
+    if rc != RESLIM_OK:
+        msg = load().reslim_last_error(ctx)
+        raise ReslimError(rc, msg.decode() if msg else "")
+
+
+# ------------------------------------------------------------------ plain calls
+def tiles_partition(Hp: int, Wp: int, Ty: int, Tx: int, halo: int):
+    """Returns (tiles: list of dict, gather_idx: int32[n_h], interior_src: int32[Hp*Wp], n_h)."""
+    lib = load()
+    n_h = C.c_int64(0)
+    _check(lib.tiles_partition(Hp, Wp, Ty, Tx, halo, None, None, None, C.byref(n_h)))
+    tiles = (TileDesc * (Ty * Tx))()
+    gather = np.empty(n_h.value, np.int32)
+    isrc = np.empty(Hp * Wp, np.int32)
+    _check(lib.tiles_partition(Hp, Wp, Ty, Tx, halo, tiles, gather.ctypes.data, isrc.ctypes.data, None))
+    names = ("y0", "y1", "x0", "x1", "Y0", "Y1", "X0", "X1", "tok_off", "n_tok")
+    return [{n: int(getattr(t, n)) for n in names} for t in tiles], gather, isrc, int(n_h.value)
+
+
+def reslim_debug_set_gemm_tile(choice: int) -> None:
+    load().reslim_debug_set_gemm_tile(choice)
+
+
+def reslim_create(cfg, weights: Dict[str, np.ndarray]) -> int:
+    """cfg: object with the reslim_config fields; weights: name -> contiguous fp32 array."""
+    lib = load()
+    cc = ReslimConfigC(**{n: int(getattr(cfg, n)) for n in _CONFIG_FIELDS})
+    keep = []
+    wc = ReslimWeightsC()
+    for n in _WEIGHT_FIELDS:
+        a = np.ascontiguousarray(weights[n], dtype=np.int32 if n == "out_var_idx" else np.float32)
+        keep.append(a)
+        setattr(wc, n, a.ctypes.data)
+    ctx = C.c_void_p()
+    _check(lib.reslim_create(C.byref(cc), C.byref(wc), C.byref(ctx)))
+    return ctx.value
+
+
+def reslim_destroy(ctx: int) -> None:
+    load().reslim_destroy(ctx)
+
+
+def reslim_tokens_per_sample(ctx: int) -> int:
+    v = C.c_int64()
+    _check(load().reslim_tokens_per_sample(ctx, C.byref(v)), ctx)
+    return v.value
+
+
+def reslim_workspace_bytes(ctx: int, batch: int) -> int:
+    v = C.c_size_t()
+    _check(load().reslim_workspace_bytes(ctx, batch, C.byref(v)), ctx)
+    return v.value
+
+
+def reslim_flop_counts(ctx: int, batch: int):
+    g, a, h = C.c_double(), C.c_double(), C.c_double()
+    _check(load().reslim_flop_counts(ctx, batch, C.byref(g), C.byref(a), C.byref(h)), ctx)
+    return g.value, a.value, h.value
+
+
+def _stream_ptr(stream=None) -> int:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def reslim_embed_fwd(ctx, x, tokens, batch, workspace, stream=None):
+    _check(load().reslim_embed_fwd(ctx, x.data_ptr(), tokens.data_ptr(), batch, workspace.data_ptr(),
+                                   workspace.numel() * workspace.element_size(), _stream_ptr(stream)), ctx)
+
+
+def tiles_attention_fwd(ctx, qkv, out, batch, stream=None):
+    _check(load().tiles_attention_fwd(ctx, qkv.data_ptr(), out.data_ptr(), batch, _stream_ptr(stream)), ctx)
+
+
+def reslim_block_fwd(ctx, layer, x_inout, batch, workspace, stream=None):
+    _check(load().reslim_block_fwd(ctx, layer, x_inout.data_ptr(), batch, workspace.data_ptr(),
+                                   workspace.numel() * workspace.element_size(), _stream_ptr(stream)), ctx)
+
+
+def reslim_head_fwd(ctx, x, tokens, y, batch, workspace, stream=None):
+    _check(load().reslim_head_fwd(ctx, x.data_ptr(), tokens.data_ptr(), y.data_ptr(), batch, workspace.data_ptr(),
+                                  workspace.numel() * workspace.element_size(), _stream_ptr(stream)), ctx)
+
+
+def reslim_forward(ctx, x, y, batch, workspace, stream=None):
+    _check(load().reslim_forward(ctx, x.data_ptr(), y.data_ptr(), batch, workspace.data_ptr(),
+                                 workspace.numel() * workspace.element_size(), _stream_ptr(stream)), ctx)
+
+
+# ------------------------------------------------------------------ convenience holder
+class Reslim:
+    """Owns a reslim_ctx and a workspace tensor; methods take/return torch CUDA tensors."""
+
+    def __init__(self, cfg, weights, max_batch: Optional[int] = None):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("libreslim needs a GPU: there is no CPU path")
+        self.cfg = cfg
+        self.ctx = reslim_create(cfg, weights)
+        self.n_h = reslim_tokens_per_sample(self.ctx)
+        self.max_batch = max_batch or cfg.batch
+        self.ws = torch.empty(reslim_workspace_bytes(self.ctx, self.max_batch), dtype=torch.uint8, device="cuda")
+        assert self.ws.data_ptr() % 256 == 0
+        self.act_dtype = torch.bfloat16 if cfg.dtype == RESLIM_BF16 else torch.float32
+
+    def close(self):
+        if self.ctx:
+            import torch
+            torch.cuda.synchronize()
+            reslim_destroy(self.ctx)
+            self.ctx = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        self.close()
+
+    def _batch(self, t):
+        b = t.shape[0]
+        assert b <= self.max_batch and t.is_cuda and t.is_contiguous()
+        return b
+
+    def embed(self, x):
+        import torch
+        b = self._batch(x)
+        tok = torch.empty((b, self.n_h, self.cfg.embed_dim), dtype=torch.float32, device="cuda")
+        reslim_embed_fwd(self.ctx, x, tok, b, self.ws)
+        return tok
+
+    def attention(self, qkv):
+        import torch
+        b = self._batch(qkv)
+        assert qkv.dtype == self.act_dtype and qkv.shape[1:] == (self.n_h, 3 * self.cfg.embed_dim)
+        out = torch.empty((b, self.n_h, self.cfg.embed_dim), dtype=self.act_dtype, device="cuda")
+        tiles_attention_fwd(self.ctx, qkv, out, b)
+        return out
+
+    def block(self, layer, tokens):
+        b = self._batch(tokens)
+        assert tokens.dtype.is_floating_point and tokens.element_size() == 4
+        reslim_block_fwd(self.ctx, layer, tokens, b, self.ws)
+        return tokens
+
+    def head(self, x, tokens):
+        import torch
+        b = self._batch(x)
+        c = self.cfg
+        y = torch.empty((b, c.out_vars, c.H * c.scale, c.W * c.scale), dtype=torch.float32, device="cuda")
+        reslim_head_fwd(self.ctx, x, tokens, y, b, self.ws)
+        return y
+
+    def forward(self, x, y=None):
+        import torch
+        b = self._batch(x)
+        c = self.cfg
+        if y is None:
+            y = torch.empty((b, c.out_vars, c.H * c.scale, c.W * c.scale), dtype=torch.float32, device="cuda")
+        reslim_forward(self.ctx, x, y, b, self.ws)
+        return y

@@ -1,0 +1,343 @@
+// Tile-local multi-head self-attention (ORBIT-2 Sec. 4.2): for every sample, tile
+// and head, O = softmax(Q K^T / sqrt(dh)) V over the tokens of that tile only.
+// The paper relies on a cache-blocked ("Flash") attention library (Sec. 4.4); the
+// kernel below is written for gfx950 from the arithmetic itself.
+//
+// bf16 kernel.  A work-group owns 128 queries of one (sample, tile, head); each of
+// its four waves owns 32 of them.  Keys/values are visited in blocks of BKV rows,
+// staged in LDS: K row-major, V transposed (so that the PV contraction over keys
+// reads 8 consecutive keys per lane).  Scores are computed TRANSPOSED,
+// S^T = K Q^T, with MFMA 32x32x16: a lane then owns one query column and the
+// softmax row statistics are in-lane reductions plus one exchange between the two
+// lane halves.  The rows of the K operand are loaded in a permuted order chosen so
+// that the accumulator registers of S^T are, without any data movement, the B
+// operand (P^T) of the second MFMA, O^T = V^T P^T.  Online softmax in fp32 with
+// base-2 exponentials; P is rounded to bf16 for PV while the row sum keeps fp32.
+// Work-groups are renumbered so the query blocks that share one K/V set run on one
+// XCD (one L2).
+#include "common.h"
+
+namespace reslim {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+struct AttnArgs {
+  const void *qkv;
+  void *out;
+  const tile_desc *tiles;
+  int T, heads, D, QB, total;
+  int64_t n_h;
+  float scale_log2;   // log2(e) / sqrt(dh)
+};
+
+__device__ __forceinline__ int xcd_remap_attn(int pid, int total) {
+  constexpr int NXCD = 8;
+  const int x = pid % NXCD, local = pid / NXCD;
+  const int q = total / NXCD, r = total % NXCD;
+  return x * q + (x < r ? x : r) + local;
+}
+
+// A-operand row i of the S^T MFMA carries key perm(i) of the 32-key group:
+// swapping bits 2 and 3 makes accumulator registers 8a..8a+7 of lane half `hi`
+// hold the 8 consecutive keys 16a + 8hi + (0..7).
+__device__ __forceinline__ int key_perm(int i) {
+  return (i & 0x13) | ((i & 4) << 1) | ((i & 8) >> 1);
+}
+
+template <int DH, int BKV>
+__global__ __launch_bounds__(256, 2) void tiles_attention_bf16_kernel(AttnArgs a) {
+  constexpr int BQ = 128;
+  constexpr int KP = DH + 8;           // K_lds pitch (bf16)
+  constexpr int VP = BKV + 8;          // Vt_lds pitch (bf16)
+  constexpr int OP = DH + 8;           // O staging pitch
+  constexpr int DC = DH / 8;           // 16-byte chunks per row
+  constexpr int CK = BKV * DC / 256;   // K chunks per thread
+  constexpr int CV = (BKV / 2) * DC / 256;  // V key-pair items per thread
+  constexpr int NKT = BKV / 32, NKS = DH / 16, NDT = DH / 32;
+  static_assert(BKV * DC % 256 == 0 && (BKV / 2) * DC % 256 == 0, "staging split");
+  constexpr int K_BYTES = BKV * KP * 2, V_BYTES = DH * VP * 2, O_BYTES = BQ * OP * 2;
+  constexpr int LDS_BYTES = (K_BYTES + V_BYTES) > O_BYTES ? (K_BYTES + V_BYTES) : O_BYTES;
+  __shared__ __align__(16) unsigned char smem[LDS_BYTES];
+  bf16_t *K_lds = reinterpret_cast<bf16_t *>(smem);
+  bf16_t *Vt_lds = reinterpret_cast<bf16_t *>(smem + K_BYTES);
+  uint32_t *Vt_lds32 = reinterpret_cast<uint32_t *>(smem + K_BYTES);
+  bf16_t *O_lds = reinterpret_cast<bf16_t *>(smem);
+
+  const int logical = xcd_remap_attn(blockIdx.x, a.total);
+  const int qb = logical % a.QB;
+  int rest = logical / a.QB;
+  const int head = rest % a.heads;
+  rest /= a.heads;
+  const int tile = rest % a.T;
+  const int b = rest / a.T;
+  const int n_t = a.tiles[tile].n_tok;
+  const int64_t tok_off = a.tiles[tile].tok_off;
+  const int q0 = qb * BQ;
+  if (q0 >= n_t) return;     // uniform for the whole work-group
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int l32 = lane & 31, hi = lane >> 5;
+  const int ld = 3 * a.D;
+  const bf16_t *base = static_cast<const bf16_t *>(a.qkv) +
+                       (static_cast<size_t>(b) * a.n_h + tok_off) * ld + head * DH;
+  const bf16_t *Kg = base + a.D, *Vg = base + 2 * a.D;
+
+  const bool active = (q0 + wave * 32) < n_t;   // wave-uniform
+  bf16x8 qf[NKS];
+  {
+    const int qrow = min(q0 + wave * 32 + l32, n_t - 1);
+    const bf16_t *qp = base + static_cast<size_t>(qrow) * ld + hi * 8;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
+  }
+
+  u32x4 rk[CK], rv[CV][2];
+  auto prefetch = [&](int kv0) {
+#pragma unroll
+    for (int i = 0; i < CK; ++i) {
+      const int c = t + i * 256, row = c / DC, kc = c % DC;
+      const int key = kv0 + row;
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (key < n_t) v = *reinterpret_cast<const u32x4 *>(Kg + static_cast<size_t>(key) * ld + kc * 8);
+      rk[i] = v;
+    }
+#pragma unroll
+    for (int i = 0; i < CV; ++i) {
+      const int c = t + i * 256, kp = c % (BKV / 2), c8 = c / (BKV / 2);
+      const int key = kv0 + 2 * kp;
+      u32x4 v0 = {0u, 0u, 0u, 0u}, v1 = {0u, 0u, 0u, 0u};
+      if (key < n_t) v0 = *reinterpret_cast<const u32x4 *>(Vg + static_cast<size_t>(key) * ld + c8 * 8);
+      if (key + 1 < n_t) v1 = *reinterpret_cast<const u32x4 *>(Vg + static_cast<size_t>(key + 1) * ld + c8 * 8);
+      rv[i][0] = v0;
+      rv[i][1] = v1;
+    }
+  };
+  auto stage = [&]() {
+#pragma unroll
+    for (int i = 0; i < CK; ++i) {
+      const int c = t + i * 256, row = c / DC, kc = c % DC;
+      *reinterpret_cast<u32x4 *>(K_lds + row * KP + kc * 8) = rk[i];
+    }
+#pragma unroll
+    for (int i = 0; i < CV; ++i) {
+      const int c = t + i * 256, kp = c % (BKV / 2), c8 = c / (BKV / 2);
+      // dword j of a 16-byte chunk holds features 2j (low half) and 2j+1 (high half)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t x0 = rv[i][0][j], x1 = rv[i][1][j];
+        const uint32_t even = (x0 & 0xffffu) | (x1 << 16);          // feature 2j of keys (2kp, 2kp+1)
+        const uint32_t odd = (x0 >> 16) | (x1 & 0xffff0000u);       // feature 2j+1
+        Vt_lds32[(c8 * 8 + 2 * j) * (VP / 2) + kp] = even;
+        Vt_lds32[(c8 * 8 + 2 * j + 1) * (VP / 2) + kp] = odd;
+      }
+    }
+  };
+
+  f32x16 o[NDT];
+#pragma unroll
+  for (int d = 0; d < NDT; ++d)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float c = a.scale_log2;
+
+  const int nkb = (n_t + BKV - 1) / BKV;
+  const int k_frag = key_perm(l32) * KP + hi * 8;
+  const int v_frag = l32 * VP + hi * 8;
+
+  prefetch(0);
+  for (int kb = 0; kb < nkb; ++kb) {
+    const int kv0 = kb * BKV;
+    if (kb > 0) __syncthreads();     // every wave is done reading the previous block
+    stage();
+    __syncthreads();
+    if (kb + 1 < nkb) prefetch(kv0 + BKV);
+    if (!active) continue;
+
+    f32x16 s[NKT];
+#pragma unroll
+    for (int kt = 0; kt < NKT; ++kt) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) {
+        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(K_lds + kt * 32 * KP + k_frag + ks * 16);
+        s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kt], 0, 0, 0);
+      }
+    }
+    if (kv0 + BKV > n_t) {           // ragged last block: keys past the tile end get -inf
+#pragma unroll
+      for (int kt = 0; kt < NKT; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = kv0 + kt * 32 + 16 * (r / 8) + 8 * hi + (r % 8);
+          if (key >= n_t) s[kt][r] = -INFINITY;
+        }
+    }
+    float mx = s[0][0];
+#pragma unroll
+    for (int kt = 0; kt < NKT; ++kt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx);     // finite: every block holds a valid key
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+    const float mc = m_new * c;
+    m_run = m_new;
+    float psum = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < NKT; ++kt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = __builtin_amdgcn_exp2f(fmaf(s[kt][r], c, -mc));
+        s[kt][r] = p;
+        psum += p;
+      }
+    l_run = fmaf(l_run, alpha, psum);
+#pragma unroll
+    for (int d = 0; d < NDT; ++d)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+
+#pragma unroll
+    for (int kt = 0; kt < NKT; ++kt) {
+#pragma unroll
+      for (int h2 = 0; h2 < 2; ++h2) {
+        bf16x8 pf;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pf[e] = static_cast<__bf16>(s[kt][8 * h2 + e]);
+#pragma unroll
+        for (int d = 0; d < NDT; ++d) {
+          const bf16x8 vf = *reinterpret_cast<const bf16x8 *>(Vt_lds + d * 32 * VP + v_frag + kt * 32 + h2 * 16);
+          o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[d], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  // normalise, transpose through LDS, store coalesced
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  const float inv = active ? 1.0f / l_tot : 0.f;
+  __syncthreads();     // K/V staging area is reused for the output tile
+  if (active) {
+#pragma unroll
+    for (int d = 0; d < NDT; ++d)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        // registers 4*r4 .. 4*r4+3 hold features 32d + 8*r4 + 4*hi + (0..3) of query l32
+        bf16x4 tmp;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) tmp[e] = static_cast<__bf16>(o[d][4 * r4 + e] * inv);
+        *reinterpret_cast<u32x2 *>(O_lds + (wave * 32 + l32) * OP + d * 32 + r4 * 8 + hi * 4) =
+            __builtin_bit_cast(u32x2, tmp);
+      }
+  }
+  __syncthreads();
+  bf16_t *outp = static_cast<bf16_t *>(a.out) + (static_cast<size_t>(b) * a.n_h + tok_off) * a.D + head * DH;
+#pragma unroll
+  for (int i = 0; i < BQ * DC / 256; ++i) {
+    const int ch = t + i * 256, row = ch / DC, kc = ch % DC;
+    if (q0 + row < n_t)
+      *reinterpret_cast<u32x4 *>(outp + static_cast<size_t>(q0 + row) * a.D + kc * 8) =
+          *reinterpret_cast<const u32x4 *>(O_lds + row * OP + kc * 8);
+  }
+}
+
+// ------------------------------------------------------------------ fp32 debug path
+// One work-group per (sample, tile-major token, head): scores for all keys of the
+// tile in LDS, two block reductions, then one thread per feature accumulates P V.
+__global__ __launch_bounds__(128) void tiles_attention_f32_kernel(AttnArgs a, int dh, const int32_t *tile_of_tok) {
+  extern __shared__ float sm[];
+  float *sc = sm;              // [max_n_tok]
+  float *qv = sm + a.QB;       // [dh]   (QB carries max_n_tok here)
+  __shared__ float red[128];
+  const int64_t tok = blockIdx.x;
+  const int head = blockIdx.y, b = blockIdx.z;
+  const int tile = tile_of_tok[tok];
+  const int n_t = a.tiles[tile].n_tok;
+  const int64_t tok_off = a.tiles[tile].tok_off;
+  const int ld = 3 * a.D;
+  const float *base = static_cast<const float *>(a.qkv) + (static_cast<size_t>(b) * a.n_h + tok_off) * ld + head * dh;
+  const float *qrow = static_cast<const float *>(a.qkv) + (static_cast<size_t>(b) * a.n_h + tok) * ld + head * dh;
+  const int t = threadIdx.x;
+  for (int d = t; d < dh; d += 128) qv[d] = qrow[d];
+  __syncthreads();
+  const float scale = rsqrtf(static_cast<float>(dh));
+  float mx = -INFINITY;
+  for (int j = t; j < n_t; j += 128) {
+    const float *kr = base + a.D + static_cast<size_t>(j) * ld;
+    float s = 0.f;
+    for (int d = 0; d < dh; ++d) s = fmaf(qv[d], kr[d], s);
+    s *= scale;
+    sc[j] = s;
+    mx = fmaxf(mx, s);
+  }
+  red[t] = mx;
+  __syncthreads();
+  for (int w = 64; w > 0; w >>= 1) {
+    if (t < w) red[t] = fmaxf(red[t], red[t + w]);
+    __syncthreads();
+  }
+  mx = red[0];
+  __syncthreads();
+  float sum = 0.f;
+  for (int j = t; j < n_t; j += 128) {
+    const float p = expf(sc[j] - mx);
+    sc[j] = p;
+    sum += p;
+  }
+  red[t] = sum;
+  __syncthreads();
+  for (int w = 64; w > 0; w >>= 1) {
+    if (t < w) red[t] += red[t + w];
+    __syncthreads();
+  }
+  const float inv = 1.0f / red[0];
+  float *orow = static_cast<float *>(a.out) + (static_cast<size_t>(b) * a.n_h + tok) * a.D + head * dh;
+  for (int d = t; d < dh; d += 128) {
+    const float *vc = base + 2 * a.D + d;
+    float acc = 0.f;
+    for (int j = 0; j < n_t; ++j) acc = fmaf(sc[j], vc[static_cast<size_t>(j) * ld], acc);
+    orow[d] = acc * inv;
+  }
+}
+
+hipError_t attention_init() { return hipSuccess; }
+
+hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *out, int batch, hipStream_t st) {
+  AttnArgs a;
+  a.qkv = qkv;
+  a.out = out;
+  a.tiles = c->d_tiles;
+  a.T = c->T;
+  a.heads = c->cfg.heads;
+  a.D = c->cfg.embed_dim;
+  a.n_h = c->n_h;
+  a.scale_log2 = 1.4426950408889634f / sqrtf(static_cast<float>(c->dh));
+  if (c->cfg.dtype == RESLIM_BF16) {
+    a.QB = (c->max_n_tok + 127) / 128;
+    const int64_t total = static_cast<int64_t>(batch) * c->T * a.heads * a.QB;
+    if (total > INT32_MAX) return hipErrorInvalidValue;
+    a.total = static_cast<int>(total);
+    if (c->dh == 64)
+      tiles_attention_bf16_kernel<64, 128><<<dim3(a.total), dim3(256), 0, st>>>(a);
+    else if (c->dh == 128)
+      tiles_attention_bf16_kernel<128, 64><<<dim3(a.total), dim3(256), 0, st>>>(a);
+    else
+      return hipErrorInvalidValue;
+    return hipGetLastError();
+  }
+  a.QB = c->max_n_tok;
+  a.total = 0;
+  const size_t lds = (static_cast<size_t>(c->max_n_tok) + c->dh) * sizeof(float);
+  if (lds > 60 * 1024 || c->n_h > INT32_MAX) return hipErrorInvalidValue;
+  tiles_attention_f32_kernel<<<dim3(static_cast<unsigned>(c->n_h), a.heads, batch), dim3(128), lds, st>>>(
+      a, c->dh, c->d_tile_of_tok);
+  return hipGetLastError();
+}
+
+}  // namespace reslim

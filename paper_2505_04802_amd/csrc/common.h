@@ -1,0 +1,121 @@
+// Internal declarations shared by the translation units of libreslim.so.
+// Nothing here is part of the C ABI (see include/reslim.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+#include "../../include/reslim.h"
+
+namespace reslim {
+
+typedef uint16_t bf16_t;  // storage type of a bfloat16: the upper half of a float
+
+// ---------------------------------------------------------------- device helpers
+__device__ __forceinline__ float bf16_to_f32(bf16_t h) {
+  return __uint_as_float(static_cast<uint32_t>(h) << 16);
+}
+// round to nearest, ties to even (finite inputs and infinities; NaN stays NaN)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  return __builtin_bit_cast(bf16_t, static_cast<__bf16>(f));   // hardware conversion on gfx950
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return static_cast<uint32_t>(f32_to_bf16(lo)) | (static_cast<uint32_t>(f32_to_bf16(hi)) << 16);
+}
+
+template <class T> struct Act;  // activation element type traits
+template <> struct Act<float> {
+  static __device__ __forceinline__ float load(const float *p) { return *p; }
+  static __device__ __forceinline__ void store(float *p, float v) { *p = v; }
+};
+template <> struct Act<bf16_t> {
+  static __device__ __forceinline__ float load(const bf16_t *p) { return bf16_to_f32(*p); }
+  static __device__ __forceinline__ void store(bf16_t *p, float v) { *p = f32_to_bf16(v); }
+};
+
+// ---------------------------------------------------------------- context
+struct LayerWeights {
+  float *ln1_g, *ln1_b, *ln2_g, *ln2_b;      // [D] fp32
+  void *w_qkv, *w_proj, *w_fc1, *w_fc2;      // act type, [out, in]
+  float *b_qkv, *b_proj, *b_fc1, *b_fc2;     // fp32
+};
+
+}  // namespace reslim
+
+struct reslim_ctx {
+  reslim_config cfg;
+  int device;
+  // derived sizes
+  int Hp, Wp, N, T, dh, R, ps, head_out;
+  int64_t n_h;
+  int max_n_tok;
+  std::vector<tile_desc> tiles;              // host copy
+  // device: tiling
+  tile_desc *d_tiles;                        // [T]
+  int32_t *d_gather, *d_interior_src;        // [n_h], [N]
+  int32_t *d_tile_of_tok;                    // [n_h] tile index of every tile-major token
+  // device: folded front end (fp32)
+  float *d_agg_A;    // [V, heads, p2]  score slope per (variable, head)
+  float *d_agg_a0;   // [V, heads]      score offset
+  float *d_agg_U;    // [V, D, p2]      value slope
+  float *d_agg_c;    // [V, D]          value offset
+  void *d_agg_wo;    // act [D, D]
+  float *d_pos_res;  // [N, D]  pos_emb + res_emb[res_idx] + agg_bo
+  float *d_zero_bias;// [max(3D, R, head_out)] zeros
+  // device: blocks and head
+  std::vector<reslim::LayerWeights> layers;
+  float *d_lnf_g, *d_lnf_b;
+  void *d_w_head;    // act [head_out, D]
+  float *d_b_head;
+  float *d_w_res, *d_b_res;                  // [C, C, 3, 3], [C]
+  int32_t *d_out_var_idx;
+  std::vector<void *> allocs;                // everything to hipFree
+  std::string err;
+};
+
+namespace reslim {
+
+int set_error(reslim_ctx *ctx, int code, const std::string &msg);
+void set_thread_error(const std::string &msg);
+
+inline size_t act_size(const reslim_ctx *c) { return c->cfg.dtype == RESLIM_BF16 ? 2 : 4; }
+inline size_t align256(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
+
+// Workspace carve-up used by block / embed / head / forward.
+struct Workspace {
+  float *X;        // [M, D] residual stream (forward only)
+  void *A;         // act [M, D]
+  void *big;       // act [M, max(3D, R)] or head staging
+  size_t total;
+};
+Workspace plan_workspace(const reslim_ctx *c, int batch, void *base);
+
+// ---- kernels (host launchers; all enqueue on `st` and return hipError_t) ------
+enum Epilogue {
+  EPI_BIAS_ACT = 0,       // out(act)  = acc + bias
+  EPI_BIAS_GELU_ACT = 1,  // out(act)  = gelu(acc + bias)
+  EPI_BIAS_RESADD_F32 = 2,// out(f32) += acc + bias
+  EPI_BIAS_TAB_F32 = 3,   // out(f32)  = acc + tab[m % tab_rows, n]   (bias folded in tab)
+  EPI_BIAS_F32 = 4        // out(f32)  = acc + bias
+};
+// C[M, N] (+)= A[M, K] * W[N, K]^T ; A, W act type (bf16 -> MFMA path, float -> fp32 path)
+hipError_t launch_gemm(int dtype, Epilogue epi, const void *A, const void *W, const float *bias,
+                       void *out, int ldo, const float *tab, int tab_rows, int M, int N, int K,
+                       hipStream_t st);
+hipError_t gemm_init();
+
+hipError_t launch_layernorm(int dtype, const float *x, const int32_t *row_src, int rows_per_sample_out,
+                            int64_t rows_per_sample_in, const float *g, const float *b, void *out,
+                            int64_t rows_out, int D, hipStream_t st);
+hipError_t launch_gather_rows(const float *z, const int32_t *gather, float *X, int batch, int64_t n_h,
+                              int N, int D, hipStream_t st);
+hipError_t launch_embed_agg(const reslim_ctx *c, const float *x, void *o, int batch, hipStream_t st);
+hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *out, int batch,
+                                  hipStream_t st);
+hipError_t attention_init();
+hipError_t launch_residual_unpatchify(const reslim_ctx *c, const float *x, const void *P, int p_is_act,
+                                      float *y, int batch, hipStream_t st);
+
+}  // namespace reslim

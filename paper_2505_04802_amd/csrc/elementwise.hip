@@ -1,0 +1,357 @@
+// Bandwidth-bound kernels of the Reslim forward (ORBIT-2 Sec. 4.1, 4.2):
+//   embed_agg       per-variable tokenisation + cross-attention variable aggregation
+//                   (folded: no non-linearity separates the two, so the scores and
+//                   the values are affine in the p*p pixels of a patch)
+//   gather_rows     tile-major copy with halo duplication (Sec. 4.2)
+//   layernorm       per-token normalisation; optional row map = "discard the halo"
+//   residual_unpatchify  residual path (bilinear upsampling + 3x3 convolution per
+//                   tile on its haloed box) fused with un-patchify, stitch and add
+#include "common.h"
+
+namespace reslim {
+
+// ------------------------------------------------------------------ LayerNorm
+// One wave per token row; the row lives in registers between the two statistics
+// passes (mean, then centred variance) and the normalise pass.
+template <class T, int NV>
+__global__ __launch_bounds__(256) void layernorm_kernel(const float *__restrict__ x, const int32_t *__restrict__ row_src,
+                                                        int rows_per_sample_out, int64_t rows_per_sample_in,
+                                                        const float *__restrict__ g, const float *__restrict__ be,
+                                                        T *__restrict__ out, int64_t rows_out, int D) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  if (row >= rows_out) return;
+  int64_t in_row = row;
+  if (row_src) {
+    const int64_t b = row / rows_per_sample_out;
+    in_row = b * rows_per_sample_in + row_src[row % rows_per_sample_out];
+  }
+  const float4 *xr = reinterpret_cast<const float4 *>(x + in_row * D);
+  const int nv = D / 4;
+  float4 v[NV];
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int k = lane + 64 * i;
+    v[i] = k < nv ? xr[k] : make_float4(0.f, 0.f, 0.f, 0.f);
+    sum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+  const float mean = sum / static_cast<float>(D);
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int k = lane + 64 * i;
+    if (k < nv) {
+      const float a = v[i].x - mean, b = v[i].y - mean, c = v[i].z - mean, d = v[i].w - mean;
+      sq += (a * a + b * b) + (c * c + d * d);
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) sq += __shfl_xor(sq, o);
+  const float rstd = rsqrtf(sq / static_cast<float>(D) + 1e-5f);
+  const float4 *g4 = reinterpret_cast<const float4 *>(g);
+  const float4 *b4 = reinterpret_cast<const float4 *>(be);
+  T *orow = out + row * D;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int k = lane + 64 * i;
+    if (k < nv) {
+      const float4 gg = g4[k], bb = b4[k];
+      const float y0 = (v[i].x - mean) * rstd * gg.x + bb.x;
+      const float y1 = (v[i].y - mean) * rstd * gg.y + bb.y;
+      const float y2 = (v[i].z - mean) * rstd * gg.z + bb.z;
+      const float y3 = (v[i].w - mean) * rstd * gg.w + bb.w;
+      if constexpr (sizeof(T) == 4) {
+        reinterpret_cast<float4 *>(orow)[k] = make_float4(y0, y1, y2, y3);
+      } else {
+        uint2 p;
+        p.x = pack_bf16x2(y0, y1);
+        p.y = pack_bf16x2(y2, y3);
+        reinterpret_cast<uint2 *>(orow)[k] = p;
+      }
+    }
+  }
+}
+
+template <class T>
+static hipError_t launch_ln_t(const float *x, const int32_t *row_src, int rpo, int64_t rpi, const float *g,
+                              const float *b, void *out, int64_t rows_out, int D, hipStream_t st) {
+  const int nv = (D / 4 + 63) / 64;
+  const dim3 grid(static_cast<unsigned>((rows_out + 3) / 4)), blk(256);
+  T *o = static_cast<T *>(out);
+#define RESLIM_LN(NV) layernorm_kernel<T, NV><<<grid, blk, 0, st>>>(x, row_src, rpo, rpi, g, b, o, rows_out, D)
+  if (nv <= 1) RESLIM_LN(1);
+  else if (nv <= 2) RESLIM_LN(2);
+  else if (nv <= 4) RESLIM_LN(4);
+  else if (nv <= 8) RESLIM_LN(8);
+  else if (nv <= 16) RESLIM_LN(16);
+  else if (nv <= 32) RESLIM_LN(32);
+  else return hipErrorInvalidValue;
+#undef RESLIM_LN
+  return hipGetLastError();
+}
+
+hipError_t launch_layernorm(int dtype, const float *x, const int32_t *row_src, int rows_per_sample_out,
+                            int64_t rows_per_sample_in, const float *g, const float *b, void *out,
+                            int64_t rows_out, int D, hipStream_t st) {
+  if (D % 4 != 0 || rows_out <= 0 || (rows_out + 3) / 4 > INT32_MAX) return hipErrorInvalidValue;
+  return dtype == RESLIM_BF16
+             ? launch_ln_t<bf16_t>(x, row_src, rows_per_sample_out, rows_per_sample_in, g, b, out, rows_out, D, st)
+             : launch_ln_t<float>(x, row_src, rows_per_sample_out, rows_per_sample_in, g, b, out, rows_out, D, st);
+}
+
+// ------------------------------------------------------------------ gather
+__global__ __launch_bounds__(256) void gather_rows_kernel(const float4 *__restrict__ z, const int32_t *__restrict__ gather,
+                                                          float4 *__restrict__ X, int64_t n_h, int N, int D4,
+                                                          int64_t total) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int64_t row = i / D4;
+  const int col = static_cast<int>(i % D4);
+  const int64_t b = row / n_h, k = row % n_h;
+  X[i] = z[(b * N + gather[k]) * D4 + col];
+}
+
+hipError_t launch_gather_rows(const float *z, const int32_t *gather, float *X, int batch, int64_t n_h, int N, int D,
+                              hipStream_t st) {
+  if (D % 4 != 0) return hipErrorInvalidValue;
+  const int64_t total = static_cast<int64_t>(batch) * n_h * (D / 4);
+  const int64_t blocks = (total + 255) / 256;
+  if (blocks > INT32_MAX) return hipErrorInvalidValue;
+  gather_rows_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st>>>(
+      reinterpret_cast<const float4 *>(z), gather, reinterpret_cast<float4 *>(X), n_h, N, D / 4, total);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ embed + aggregate
+struct EmbedArgs {
+  const float *x;
+  const float *A, *a0, *U, *c;
+  void *o;
+  int V, H, W, p, Wp, N, D, heads, dh;
+  int64_t BN;   // batch * N patches
+};
+
+template <class T>
+__global__ __launch_bounds__(256) void embed_agg_kernel(EmbedArgs e) {
+  constexpr int TP = 8;                       // patches per work-group
+  extern __shared__ float sm[];
+  const int p2 = e.p * e.p;
+  const int VP2 = e.V * p2;
+  float *pix = sm;                            // [TP][V*p2]
+  float *sc = sm + TP * VP2;                  // [TP][heads][V]
+  const int t = threadIdx.x;
+  const int64_t bn0 = static_cast<int64_t>(blockIdx.x) * TP;
+
+  for (int idx = t; idx < TP * VP2; idx += 256) {
+    const int pi = idx / VP2, rem = idx % VP2, v = rem / p2, i = rem % p2;
+    const int64_t bn = bn0 + pi;
+    float val = 0.f;
+    if (bn < e.BN) {
+      const int64_t b = bn / e.N;
+      const int n = static_cast<int>(bn % e.N);
+      const int py = n / e.Wp, px = n % e.Wp;
+      const int yy = py * e.p + i / e.p, xx = px * e.p + i % e.p;
+      val = e.x[((b * e.V + v) * e.H + yy) * e.W + xx];
+    }
+    pix[idx] = val;
+  }
+  __syncthreads();
+  const int HV = e.heads * e.V;
+  for (int idx = t; idx < TP * HV; idx += 256) {
+    const int pi = idx / HV, rem = idx % HV, g = rem / e.V, v = rem % e.V;
+    const float *Ar = e.A + (static_cast<size_t>(v) * e.heads + g) * p2;
+    const float *px = pix + pi * VP2 + v * p2;
+    float s = e.a0[v * e.heads + g];
+    for (int i = 0; i < p2; ++i) s = fmaf(Ar[i], px[i], s);
+    sc[idx] = s;
+  }
+  __syncthreads();
+  for (int idx = t; idx < TP * e.heads; idx += 256) {
+    float *r = sc + static_cast<size_t>(idx) * e.V;
+    float mx = r[0];
+    for (int v = 1; v < e.V; ++v) mx = fmaxf(mx, r[v]);
+    float sum = 0.f;
+    for (int v = 0; v < e.V; ++v) {
+      const float ex = expf(r[v] - mx);
+      r[v] = ex;
+      sum += ex;
+    }
+    const float inv = 1.0f / sum;
+    for (int v = 0; v < e.V; ++v) r[v] *= inv;
+  }
+  __syncthreads();
+  T *out = static_cast<T *>(e.o);
+  for (int d = t; d < e.D; d += 256) {
+    const int g = d / e.dh;
+    float acc[TP];
+#pragma unroll
+    for (int pi = 0; pi < TP; ++pi) acc[pi] = 0.f;
+    for (int v = 0; v < e.V; ++v) {
+      const float *Ur = e.U + (static_cast<size_t>(v) * e.D + d) * p2;
+      const float cv = e.c[static_cast<size_t>(v) * e.D + d];
+#pragma unroll
+      for (int pi = 0; pi < TP; ++pi) {
+        const float *px = pix + pi * VP2 + v * p2;
+        float val = cv;
+        for (int i = 0; i < p2; ++i) val = fmaf(Ur[i], px[i], val);
+        acc[pi] = fmaf(sc[(pi * e.heads + g) * e.V + v], val, acc[pi]);
+      }
+    }
+#pragma unroll
+    for (int pi = 0; pi < TP; ++pi)
+      if (bn0 + pi < e.BN) Act<T>::store(out + (bn0 + pi) * e.D + d, acc[pi]);
+  }
+}
+
+hipError_t launch_embed_agg(const reslim_ctx *c, const float *x, void *o, int batch, hipStream_t st) {
+  EmbedArgs e;
+  e.x = x; e.A = c->d_agg_A; e.a0 = c->d_agg_a0; e.U = c->d_agg_U; e.c = c->d_agg_c; e.o = o;
+  e.V = c->cfg.in_vars; e.H = c->cfg.H; e.W = c->cfg.W; e.p = c->cfg.patch; e.Wp = c->Wp; e.N = c->N;
+  e.D = c->cfg.embed_dim; e.heads = c->cfg.heads; e.dh = c->dh;
+  e.BN = static_cast<int64_t>(batch) * c->N;
+  const size_t lds = 8ull * (static_cast<size_t>(e.V) * e.p * e.p + static_cast<size_t>(e.heads) * e.V) * sizeof(float);
+  if (lds > 60 * 1024) return hipErrorInvalidValue;
+  const int64_t blocks = (e.BN + 7) / 8;
+  if (blocks > INT32_MAX) return hipErrorInvalidValue;
+  if (c->cfg.dtype == RESLIM_BF16)
+    embed_agg_kernel<bf16_t><<<dim3(static_cast<unsigned>(blocks)), dim3(256), lds, st>>>(e);
+  else
+    embed_agg_kernel<float><<<dim3(static_cast<unsigned>(blocks)), dim3(256), lds, st>>>(e);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ residual path + stitch
+struct ResArgs {
+  const float *x;        // [B, V, H, W]
+  const float *P;        // [B, N, C*ps*ps] head projection of the interior tokens
+  float *y;              // [B, C, s*H, s*W]
+  const tile_desc *tiles;
+  const float *w_res, *b_res;
+  const int32_t *out_var_idx;
+  int V, C, H, W, s, p, ps, Wp, N, head_out;
+  int nbx;               // blocks per tile along x
+};
+
+// A work-group produces a 16 x 64 block of fine pixels inside one tile's interior,
+// for all output variables (8 at a time).  For every input variable the upsampled
+// field U on the block's 18 x 66 neighbourhood is built in LDS -- bilinear with
+// neighbours clamped to the tile's haloed box, zero outside the box (the padding of
+// the convolution) -- and each thread accumulates the 3x3 stencil for 4 adjacent
+// pixels.  The head projection is read in patch order and the sum written in place:
+// un-patchify, stitch and add in one pass.
+__global__ __launch_bounds__(256) void residual_unpatchify_kernel(ResArgs a) {
+  constexpr int BY = 16, BX = 64, WY = BY + 2, WX = BX + 2, WXP = 68, CO = 8;
+  __shared__ float U[WY * WXP];
+  const tile_desc td = a.tiles[blockIdx.y];
+  const int b = blockIdx.z;
+  const int ih = (td.y1 - td.y0) * a.ps, iw = (td.x1 - td.x0) * a.ps;
+  const int iy0 = (blockIdx.x / a.nbx) * BY, ix0 = (blockIdx.x % a.nbx) * BX;
+  if (iy0 >= ih || ix0 >= iw) return;          // uniform
+  const int t = threadIdx.x, ty = t / 16, tx = t % 16;
+  // fine coordinates of the block origin inside the haloed box
+  const int fy0 = (td.y0 - td.Y0) * a.ps + iy0, fx0 = (td.x0 - td.X0) * a.ps + ix0;
+  const int box_fh = (td.Y1 - td.Y0) * a.ps, box_fw = (td.X1 - td.X0) * a.ps;   // fine size of the box
+  const int box_ch = (td.Y1 - td.Y0) * a.p, box_cw = (td.X1 - td.X0) * a.p;     // coarse size of the box
+  const int cy_org = td.Y0 * a.p, cx_org = td.X0 * a.p;
+  const float inv_s = 1.0f / static_cast<float>(a.s);
+  const int sH = a.s * a.H, sW = a.s * a.W;
+  const int iy = iy0 + ty, ix = ix0 + 4 * tx;
+
+  for (int co0 = 0; co0 < a.C; co0 += CO) {
+    float acc[CO][4];
+#pragma unroll
+    for (int o = 0; o < CO; ++o) {
+      const float bv = (co0 + o < a.C) ? a.b_res[co0 + o] : 0.f;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) acc[o][k] = bv;
+    }
+    for (int ci = 0; ci < a.C; ++ci) {
+      const float *xp = a.x + (static_cast<size_t>(b) * a.V + a.out_var_idx[ci]) * a.H * a.W;
+      __syncthreads();
+      for (int idx = t; idx < WY * WX; idx += 256) {
+        const int wy = idx / WX, wx = idx % WX;
+        const int fy = fy0 + wy - 1, fx = fx0 + wx - 1;
+        float val = 0.f;
+        if (fy >= 0 && fy < box_fh && fx >= 0 && fx < box_fw) {
+          const float sy = (static_cast<float>(fy) + 0.5f) * inv_s - 0.5f;
+          const float sx = (static_cast<float>(fx) + 0.5f) * inv_s - 0.5f;
+          const float fly = floorf(sy), flx = floorf(sx);
+          const float wy1 = sy - fly, wx1 = sx - flx;
+          const int y0i = static_cast<int>(fly), x0i = static_cast<int>(flx);
+          const int ya = min(max(y0i, 0), box_ch - 1), yb = min(max(y0i + 1, 0), box_ch - 1);
+          const int xa = min(max(x0i, 0), box_cw - 1), xb = min(max(x0i + 1, 0), box_cw - 1);
+          const float *ra = xp + static_cast<size_t>(cy_org + ya) * a.W + cx_org;
+          const float *rb = xp + static_cast<size_t>(cy_org + yb) * a.W + cx_org;
+          const float top = ra[xa] * (1.0f - wx1) + ra[xb] * wx1;
+          const float bot = rb[xa] * (1.0f - wx1) + rb[xb] * wx1;
+          val = top * (1.0f - wy1) + bot * wy1;
+        }
+        U[wy * WXP + wx] = val;
+      }
+      __syncthreads();
+      float u[3][6];
+#pragma unroll
+      for (int dy = 0; dy < 3; ++dy)
+#pragma unroll
+        for (int dx = 0; dx < 6; ++dx) u[dy][dx] = U[(ty + dy) * WXP + 4 * tx + dx];
+#pragma unroll
+      for (int o = 0; o < CO; ++o) {
+        if (co0 + o < a.C) {
+          const float *wr = a.w_res + (static_cast<size_t>(co0 + o) * a.C + ci) * 9;
+#pragma unroll
+          for (int dy = 0; dy < 3; ++dy)
+#pragma unroll
+            for (int dx = 0; dx < 3; ++dx) {
+              const float w = wr[dy * 3 + dx];
+#pragma unroll
+              for (int k = 0; k < 4; ++k) acc[o][k] = fmaf(w, u[dy][dx + k], acc[o][k]);
+            }
+        }
+      }
+    }
+    if (iy < ih) {
+      const int gy = td.y0 * a.ps + iy;
+      const int py = td.y0 + iy / a.ps, i = iy % a.ps;
+#pragma unroll
+      for (int o = 0; o < CO; ++o) {
+        const int c = co0 + o;
+        if (c >= a.C) break;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int ixk = ix + k;
+          if (ixk < iw) {
+            const int px = td.x0 + ixk / a.ps, j = ixk % a.ps;
+            const size_t n = static_cast<size_t>(py) * a.Wp + px;
+            const float pv = a.P[(static_cast<size_t>(b) * a.N + n) * a.head_out + (static_cast<size_t>(c) * a.ps + i) * a.ps + j];
+            a.y[((static_cast<size_t>(b) * a.C + c) * sH + gy) * sW + td.x0 * a.ps + ixk] = pv + acc[o][k];
+          }
+        }
+      }
+    }
+  }
+}
+
+hipError_t launch_residual_unpatchify(const reslim_ctx *c, const float *x, const void *P, int p_is_act, float *y,
+                                      int batch, hipStream_t st) {
+  (void)p_is_act;
+  ResArgs a;
+  a.x = x; a.P = static_cast<const float *>(P); a.y = y; a.tiles = c->d_tiles;
+  a.w_res = c->d_w_res; a.b_res = c->d_b_res; a.out_var_idx = c->d_out_var_idx;
+  a.V = c->cfg.in_vars; a.C = c->cfg.out_vars; a.H = c->cfg.H; a.W = c->cfg.W; a.s = c->cfg.scale;
+  a.p = c->cfg.patch; a.ps = c->ps; a.Wp = c->Wp; a.N = c->N; a.head_out = c->head_out;
+  int max_ih = 0, max_iw = 0;
+  for (const tile_desc &t : c->tiles) {
+    max_ih = std::max(max_ih, (t.y1 - t.y0) * c->ps);
+    max_iw = std::max(max_iw, (t.x1 - t.x0) * c->ps);
+  }
+  a.nbx = (max_iw + 63) / 64;
+  const int nby = (max_ih + 15) / 16;
+  if (c->T > 65535 || batch > 65535) return hipErrorInvalidValue;
+  residual_unpatchify_kernel<<<dim3(a.nbx * nby, c->T, batch), dim3(256), 0, st>>>(a);
+  return hipGetLastError();
+}
+
+}  // namespace reslim

@@ -1,0 +1,350 @@
+// Dense contractions of the transformer block (ORBIT-2 Sec. 3 / 4.1: the QKV,
+// projection and feed-forward maps, the aggregation's output map and the decoder's
+// linear projection):   C[M, N] (+)= A[M, K] * W[N, K]^T + bias, fused epilogues.
+//
+// bf16 path: gfx950 MFMA 32x32x16 (bf16 in, fp32 accumulate).  A work-group owns a
+// BM x BN tile of C, stages BM x BK and BN x BK operand slabs through LDS (rows
+// padded by 16 B so the 16-byte fragment reads of 16 consecutive rows fall in
+// distinct bank groups), double-buffered with the next slab prefetched into
+// registers while the current one feeds the matrix cores.  Work-groups are
+// renumbered so that each XCD (private L2) receives a contiguous run of tiles, and
+// inside a run tiles are ordered in bands of GROUP_M row-tiles so concurrently
+// resident tiles share A and W slabs.
+// fp32 path (debug): plain LDS-tiled FMA kernel.
+#include "common.h"
+
+namespace reslim {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+struct GemmArgs {
+  const void *A;
+  const void *W;
+  const float *bias;
+  void *out;
+  const float *tab;
+  int ldo, tab_rows;
+  int M, N, K;
+  int grid_m, grid_n;
+};
+
+__device__ __forceinline__ float gelu_erf(float x) {
+  return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f));
+}
+
+template <int EPI>
+__device__ __forceinline__ void epilogue_store(const GemmArgs &g, int m, int n, float v) {
+  // caller guarantees m < M, n < N
+  const size_t o = static_cast<size_t>(m) * g.ldo + n;
+  if constexpr (EPI == EPI_BIAS_ACT) {
+    static_cast<bf16_t *>(g.out)[o] = f32_to_bf16(v + g.bias[n]);
+  } else if constexpr (EPI == EPI_BIAS_GELU_ACT) {
+    static_cast<bf16_t *>(g.out)[o] = f32_to_bf16(gelu_erf(v + g.bias[n]));
+  } else if constexpr (EPI == EPI_BIAS_RESADD_F32) {
+    float *p = static_cast<float *>(g.out) + o;
+    *p = *p + (v + g.bias[n]);
+  } else if constexpr (EPI == EPI_BIAS_TAB_F32) {
+    static_cast<float *>(g.out)[o] = v + g.tab[static_cast<size_t>(m % g.tab_rows) * g.N + n];
+  } else {
+    static_cast<float *>(g.out)[o] = v + g.bias[n];
+  }
+}
+
+// tile id seen by the hardware dispatcher -> tile id in XCD-contiguous order
+__device__ __forceinline__ int xcd_remap(int pid, int total) {
+  constexpr int NXCD = 8;
+  const int x = pid % NXCD, local = pid / NXCD;
+  const int q = total / NXCD, r = total % NXCD;
+  return x * q + (x < r ? x : r) + local;
+}
+
+template <int BM, int BN, int BK, int WM, int WN, int EPI>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g) {
+  constexpr int NT = WM * WN * 64;
+  constexpr int PITCH = BK + 8;           // bf16 elements per LDS row
+  constexpr int TM = BM / WM, TN = BN / WN;
+  constexpr int MI = TM / 32, NI = TN / 32;
+  constexpr int KC = BK / 8;              // 16-byte chunks per slab row
+  constexpr int CA = BM * KC / NT, CB = BN * KC / NT;
+  static_assert(BM * KC % NT == 0 && BN * KC % NT == 0, "slab must split evenly over threads");
+  static_assert(TM % 32 == 0 && TN % 32 == 0 && BK % 16 == 0, "MFMA tiling");
+  constexpr int GROUP_M = 8;
+
+  extern __shared__ __align__(16) unsigned char smem[];
+  bf16_t *As = reinterpret_cast<bf16_t *>(smem);        // [2][BM][PITCH]
+  bf16_t *Bs = As + 2 * BM * PITCH;                      // [2][BN][PITCH]
+
+  const int total = g.grid_m * g.grid_n;
+  int pid = xcd_remap(blockIdx.x, total);
+  const int band = GROUP_M * g.grid_n;
+  const int band_id = pid / band;
+  const int first_m = band_id * GROUP_M;
+  const int band_rows = min(g.grid_m - first_m, GROUP_M);
+  const int tile_m = first_m + (pid % band) % band_rows;
+  const int tile_n = (pid % band) / band_rows;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  const int t = threadIdx.x;
+  const int lane = t & 63, wave = t >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  const int l32 = lane & 31, hi = lane >> 5;
+
+  const bf16_t *A = static_cast<const bf16_t *>(g.A);
+  const bf16_t *W = static_cast<const bf16_t *>(g.W);
+  const int K = g.K;
+
+  // per-thread global source rows (clamped: rows past the edge read valid memory,
+  // their results are never stored)
+  const bf16_t *a_src[CA];
+  const bf16_t *b_src[CB];
+  int a_dst[CA], b_dst[CB];
+#pragma unroll
+  for (int i = 0; i < CA; ++i) {
+    const int c = t + i * NT, row = c / KC, kc = c % KC;
+    const int gm = min(m0 + row, g.M - 1);
+    a_src[i] = A + static_cast<size_t>(gm) * K + kc * 8;
+    a_dst[i] = row * PITCH + kc * 8;
+  }
+#pragma unroll
+  for (int i = 0; i < CB; ++i) {
+    const int c = t + i * NT, row = c / KC, kc = c % KC;
+    const int gn = min(n0 + row, g.N - 1);
+    b_src[i] = W + static_cast<size_t>(gn) * K + kc * 8;
+    b_dst[i] = row * PITCH + kc * 8;
+  }
+
+  u32x4 ra[CA], rb[CB];
+  auto load_global = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < CA; ++i) ra[i] = *reinterpret_cast<const u32x4 *>(a_src[i] + k0);
+#pragma unroll
+    for (int i = 0; i < CB; ++i) rb[i] = *reinterpret_cast<const u32x4 *>(b_src[i] + k0);
+  };
+  auto store_lds = [&](int buf) {
+    bf16_t *as = As + buf * BM * PITCH;
+    bf16_t *bs = Bs + buf * BN * PITCH;
+#pragma unroll
+    for (int i = 0; i < CA; ++i) *reinterpret_cast<u32x4 *>(as + a_dst[i]) = ra[i];
+#pragma unroll
+    for (int i = 0; i < CB; ++i) *reinterpret_cast<u32x4 *>(bs + b_dst[i]) = rb[i];
+  };
+
+  f32x16 acc[MI][NI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nk = K / BK;
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+
+  const int a_frag = (wm * TM + l32) * PITCH + hi * 8;
+  const int b_frag = (wn * TN + l32) * PITCH + hi * 8;
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < nk) load_global((kt + 1) * BK);
+    const bf16_t *as = As + buf * BM * PITCH + a_frag;
+    const bf16_t *bs = Bs + buf * BN * PITCH + b_frag;
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      bf16x8 af[MI], bfr[NI];
+#pragma unroll
+      for (int i = 0; i < MI; ++i) af[i] = *reinterpret_cast<const bf16x8 *>(as + i * 32 * PITCH + kk * 16);
+#pragma unroll
+      for (int j = 0; j < NI; ++j) bfr[j] = *reinterpret_cast<const bf16x8 *>(bs + j * 32 * PITCH + kk * 16);
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) store_lds(buf ^ 1);
+    __syncthreads();
+  }
+
+  // accumulator layout of the 32x32 tile: lane holds column (lane % 32) and rows
+  // 8*(r/4) + 4*(lane/32) + r%4 for r = 0..15
+#pragma unroll
+  for (int i = 0; i < MI; ++i) {
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+      const int n = n0 + wn * TN + j * 32 + l32;
+      if (n >= g.N) continue;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm * TM + i * 32 + 8 * (r / 4) + 4 * hi + (r % 4);
+        if (m < g.M) epilogue_store<EPI>(g, m, n, acc[i][j][r]);
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ fp32 debug path
+template <int EPI>
+__device__ __forceinline__ void epilogue_store_f32(const GemmArgs &g, int m, int n, float v) {
+  const size_t o = static_cast<size_t>(m) * g.ldo + n;
+  float *out = static_cast<float *>(g.out);
+  if constexpr (EPI == EPI_BIAS_ACT || EPI == EPI_BIAS_F32) {
+    out[o] = v + g.bias[n];
+  } else if constexpr (EPI == EPI_BIAS_GELU_ACT) {
+    out[o] = gelu_erf(v + g.bias[n]);
+  } else if constexpr (EPI == EPI_BIAS_RESADD_F32) {
+    out[o] = out[o] + (v + g.bias[n]);
+  } else {
+    out[o] = v + g.tab[static_cast<size_t>(m % g.tab_rows) * g.N + n];
+  }
+}
+
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
+  constexpr int BM = 64, BN = 64, BK = 16;
+  __shared__ float As[BK][BM + 4];
+  __shared__ float Bs[BK][BN + 4];
+  const float *A = static_cast<const float *>(g.A);
+  const float *W = static_cast<const float *>(g.W);
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int t = threadIdx.x, tx = t % 16, ty = t / 16;
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < g.K; k0 += BK) {
+    for (int c = t; c < BM * BK; c += 256) {
+      const int row = c / BK, k = c % BK;
+      const int gm = m0 + row, gk = k0 + k;
+      As[k][row] = (gm < g.M && gk < g.K) ? A[static_cast<size_t>(gm) * g.K + gk] : 0.f;
+      const int gn = n0 + row;
+      Bs[k][row] = (gn < g.N && gk < g.K) ? W[static_cast<size_t>(gn) * g.K + gk] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < BK; ++k) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] = As[k][ty * 4 + i];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) b[j] = Bs[k][tx * 4 + j];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
+      if (m < g.M && n < g.N) epilogue_store_f32<EPI>(g, m, n, acc[i][j]);
+    }
+}
+
+// ------------------------------------------------------------------ launchers
+template <int BM, int BN, int BK, int WM, int WN>
+struct TileCfg {
+  static constexpr int kBM = BM, kBN = BN, kBK = BK, kWM = WM, kWN = WN;
+  static constexpr int kThreads = WM * WN * 64;
+  static constexpr size_t kLds = 2ull * (BM + BN) * (BK + 8) * sizeof(bf16_t);
+};
+
+template <class TC, int EPI>
+static hipError_t set_attr() {
+  return hipFuncSetAttribute(
+      reinterpret_cast<const void *>(&gemm_bf16_kernel<TC::kBM, TC::kBN, TC::kBK, TC::kWM, TC::kWN, EPI>),
+      hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(TC::kLds));
+}
+
+template <class TC, int EPI>
+static hipError_t launch_bf16_tc(GemmArgs g, hipStream_t st) {
+  g.grid_m = (g.M + TC::kBM - 1) / TC::kBM;
+  g.grid_n = (g.N + TC::kBN - 1) / TC::kBN;
+  const int total = g.grid_m * g.grid_n;
+  gemm_bf16_kernel<TC::kBM, TC::kBN, TC::kBK, TC::kWM, TC::kWN, EPI>
+      <<<dim3(total), dim3(TC::kThreads), TC::kLds, st>>>(g);
+  return hipGetLastError();
+}
+
+typedef TileCfg<256, 256, 64, 2, 2> TileBig;     // 128x128 per wave, 144 KB LDS, 1 WG / CU
+typedef TileCfg<256, 128, 64, 2, 2> TileWide;    // 128x64 per wave, 108 KB LDS
+typedef TileCfg<128, 128, 64, 2, 2> TileSmall;   // 64x64 per wave, 72 KB LDS, 2 WG / CU
+
+static int g_gemm_tile_override = -1;   // test / tuning hook: 0 big, 1 wide, 2 small
+
+template <int EPI>
+static hipError_t launch_bf16(GemmArgs g, hipStream_t st) {
+  // pick the largest tile that still yields at least ~2 full rounds of 256 CUs
+  int choice;
+  const long tiles_big = static_cast<long>((g.M + 255) / 256) * ((g.N + 255) / 256);
+  const long tiles_wide = static_cast<long>((g.M + 255) / 256) * ((g.N + 127) / 128);
+  if (tiles_big >= 512) choice = 0;
+  else if (tiles_wide >= 512) choice = 1;
+  else choice = 2;
+  if (g_gemm_tile_override >= 0) choice = g_gemm_tile_override;
+  switch (choice) {
+    case 0: return launch_bf16_tc<TileBig, EPI>(g, st);
+    case 1: return launch_bf16_tc<TileWide, EPI>(g, st);
+    default: return launch_bf16_tc<TileSmall, EPI>(g, st);
+  }
+}
+
+template <int EPI>
+static hipError_t launch_f32(GemmArgs g, hipStream_t st) {
+  dim3 grid((g.N + 63) / 64, (g.M + 63) / 64);
+  gemm_f32_kernel<EPI><<<grid, dim3(256), 0, st>>>(g);
+  return hipGetLastError();
+}
+
+template <int EPI>
+static hipError_t init_epi() {
+  hipError_t e;
+  if ((e = set_attr<TileBig, EPI>()) != hipSuccess) return e;
+  if ((e = set_attr<TileWide, EPI>()) != hipSuccess) return e;
+  return set_attr<TileSmall, EPI>();
+}
+
+hipError_t gemm_init() {
+  hipError_t e;
+  if ((e = init_epi<EPI_BIAS_ACT>()) != hipSuccess) return e;
+  if ((e = init_epi<EPI_BIAS_GELU_ACT>()) != hipSuccess) return e;
+  if ((e = init_epi<EPI_BIAS_RESADD_F32>()) != hipSuccess) return e;
+  if ((e = init_epi<EPI_BIAS_TAB_F32>()) != hipSuccess) return e;
+  return init_epi<EPI_BIAS_F32>();
+}
+
+hipError_t launch_gemm(int dtype, Epilogue epi, const void *A, const void *W, const float *bias,
+                       void *out, int ldo, const float *tab, int tab_rows, int M, int N, int K,
+                       hipStream_t st) {
+  if (M <= 0 || N <= 0 || K <= 0) return hipErrorInvalidValue;
+  GemmArgs g;
+  g.A = A; g.W = W; g.bias = bias; g.out = out; g.tab = tab;
+  g.ldo = ldo; g.tab_rows = tab_rows > 0 ? tab_rows : 1;
+  g.M = M; g.N = N; g.K = K; g.grid_m = g.grid_n = 0;
+  if (dtype == RESLIM_BF16) {
+    if (K % 64 != 0) return hipErrorInvalidValue;   // slabs are 64 deep; create() enforces D % 64 == 0
+    switch (epi) {
+      case EPI_BIAS_ACT: return launch_bf16<EPI_BIAS_ACT>(g, st);
+      case EPI_BIAS_GELU_ACT: return launch_bf16<EPI_BIAS_GELU_ACT>(g, st);
+      case EPI_BIAS_RESADD_F32: return launch_bf16<EPI_BIAS_RESADD_F32>(g, st);
+      case EPI_BIAS_TAB_F32: return launch_bf16<EPI_BIAS_TAB_F32>(g, st);
+      default: return launch_bf16<EPI_BIAS_F32>(g, st);
+    }
+  }
+  switch (epi) {
+    case EPI_BIAS_ACT: return launch_f32<EPI_BIAS_ACT>(g, st);
+    case EPI_BIAS_GELU_ACT: return launch_f32<EPI_BIAS_GELU_ACT>(g, st);
+    case EPI_BIAS_RESADD_F32: return launch_f32<EPI_BIAS_RESADD_F32>(g, st);
+    case EPI_BIAS_TAB_F32: return launch_f32<EPI_BIAS_TAB_F32>(g, st);
+    default: return launch_f32<EPI_BIAS_F32>(g, st);
+  }
+}
+
+}  // namespace reslim
+
+// tuning hook for the benchmark (not part of the documented ABI surface of the
+// method; selects the GEMM tile shape: -1 heuristic, 0 256x256, 1 256x128, 2 128x128)
+extern "C" void reslim_debug_set_gemm_tile(int choice) { reslim::g_gemm_tile_override = choice; }

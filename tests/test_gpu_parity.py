@@ -1,0 +1,222 @@
+"""GPU parity: the HIP library (through the C ABI) against the CPU oracle on the
+same seeded inputs, element by element.
+
+Tolerances (max relative L2 over planes, the bar the benchmark definition sets):
+    fp32 debug path  <= 1e-5
+    bf16 path        <= 2e-2
+Tile partitioning is compared bit-exact in test_abi_cpu.py (host function)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import reslim_oracle as O
+from paper_2505_04802_amd import binding as B
+from paper_2505_04802_amd import workloads as WL
+
+pytestmark = pytest.mark.gpu
+TOL = {0: 1e-5, 1: 2e-2}
+
+
+def cuda(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return t if dtype is None else t.to(dtype)
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def rel(a, ref):
+    a = np.asarray(a, np.float64).ravel()
+    ref = np.asarray(ref, np.float64).ravel()
+    return float(np.linalg.norm(a - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+# small shapes that still span several MFMA tiles, several key blocks and ragged tails
+SMALL_F32 = WL.ReslimConfig("s32", batch=2, in_vars=3, out_vars=2, H=20, W=28, scale=2, patch=2,
+                            embed_dim=48, heads=3, mlp_ratio=2, depth=2, tiles_y=2, tiles_x=3,
+                            halo=1, dtype=0, seed=11)
+SMALL_BF16 = WL.ReslimConfig("sbf", batch=2, in_vars=3, out_vars=3, H=44, W=60, scale=4, patch=2,
+                             embed_dim=128, heads=2, mlp_ratio=4, depth=2, tiles_y=2, tiles_x=2,
+                             halo=2, dtype=1, seed=12)       # dh = 64, n_t = 13*17 .. -> 221..285 tokens
+SMALL_BF16_DH128 = SMALL_BF16.with_(name="sbf128", embed_dim=256, heads=2, H=40, W=48, tiles_y=1, tiles_x=2,
+                                    halo=3, seed=13)        # dh = 128, n_t = 20*15 = 300
+
+
+def weights_for(cfg, std=0.02):
+    w = WL.make_weights(cfg, std=std)
+    if cfg.out_vars < cfg.in_vars:          # exercise a non-identity variable selection
+        w["out_var_idx"] = np.arange(cfg.in_vars - 1, cfg.in_vars - 1 - cfg.out_vars, -1).astype(np.int32)
+    return w
+
+
+# ------------------------------------------------------------------ tile attention
+@pytest.mark.parametrize("cfg", [SMALL_F32, SMALL_BF16, SMALL_BF16_DH128], ids=lambda c: c.name)
+@pytest.mark.parametrize("peaked", [False, True])
+def test_tiles_attention_parity(cfg, peaked):
+    say(f"attention parity {cfg.name} peaked={peaked}")
+    tiles, _, _, n_h = O.tiles_partition(cfg.Hp, cfg.Wp, cfg.tiles_y, cfg.tiles_x, cfg.halo)
+    qkv = WL.make_qkv(cfg.batch * n_h, cfg.embed_dim, seed=5, peaked=peaked, bf16=cfg.dtype == 1)
+    qkv = qkv.reshape(cfg.batch, n_h, 3 * cfg.embed_dim)
+    ref = O.tiles_attention(qkv, tiles, cfg.heads)
+    with B.Reslim(cfg, weights_for(cfg)) as m:
+        assert m.n_h == n_h
+        out = m.attention(cuda(qkv, m.act_dtype)).float().cpu().numpy()
+    assert np.isfinite(out).all()
+    err = O.rel_l2(out, ref)
+    say(f"  rel-L2 {err:.3e}")
+    assert err <= TOL[cfg.dtype]
+    if cfg.dtype == 1:      # element-wise: bf16 output rounding + bf16 P, well inside 3e-2 absolute for |v| ~ 1
+        assert np.abs(out - ref).max() <= 3e-2
+
+
+def test_tiles_attention_special_cases_bf16():
+    """Degenerate inputs with known answers: q = 0 gives the tile's column mean of v,
+    constant v is reproduced, and one tile over the whole grid is global attention."""
+    cfg = SMALL_BF16.with_(tiles_y=1, tiles_x=1, halo=5, batch=1)
+    tiles, _, _, n_h = O.tiles_partition(cfg.Hp, cfg.Wp, 1, 1, 5)
+    D = cfg.embed_dim
+    qkv = WL.make_qkv(n_h, D, seed=6).reshape(1, n_h, 3 * D)
+    with B.Reslim(cfg, weights_for(cfg)) as m:
+        assert m.n_h == cfg.n_tokens
+        z = qkv.copy(); z[..., :D] = 0
+        out = m.attention(cuda(z, torch.bfloat16)).float().cpu().numpy()
+        assert np.abs(out - z[0, :, 2 * D:].mean(0)).max() <= 1e-2
+        cst = qkv.copy(); cst[..., 2 * D:] = WL.round_to_bf16(np.linspace(-2, 2, D, dtype=np.float32))
+        out = m.attention(cuda(cst, torch.bfloat16)).float().cpu().numpy()
+        assert np.abs(out - cst[0, 0, 2 * D:]).max() <= 2e-2
+        out = m.attention(cuda(qkv, torch.bfloat16)).float().cpu().numpy()
+        ref = O.self_attention(qkv[0, :, :D], qkv[0, :, D:2 * D], qkv[0, :, 2 * D:], cfg.heads)
+        assert O.rel_l2(out[0], ref) <= 2e-2
+
+
+# ------------------------------------------------------------------ embed / block / head
+@pytest.mark.parametrize("cfg", [SMALL_F32, SMALL_BF16, SMALL_BF16_DH128], ids=lambda c: c.name)
+def test_stage_by_stage_parity(cfg):
+    """Every entry point against the oracle's intermediate of the same name; the
+    weights are spread wide (std 0.1) so softmaxes and GELUs are far from linear."""
+    say(f"stage parity {cfg.name}")
+    w = weights_for(cfg, std=0.1)
+    x = WL.make_fields(cfg)
+    y_ref, inter = O.reslim_forward(x, w, cfg, return_intermediates=True)
+    tol = TOL[cfg.dtype]
+    with B.Reslim(cfg, w) as m:
+        xd = cuda(x)
+        tok = m.embed(xd)
+        e = O.rel_l2(tok.cpu().numpy(), inter["tokens"]); say(f"  embed rel-L2 {e:.3e}")
+        assert e <= tol
+        # each block from the ORACLE's input, so errors do not compound in this check
+        prev = inter["tokens"]
+        for l in range(cfg.depth):
+            t = cuda(prev.astype(np.float32))
+            m.block(l, t)
+            e = O.rel_l2(t.cpu().numpy(), inter[f"block{l}"]); say(f"  block{l} rel-L2 {e:.3e}")
+            assert e <= tol
+            prev = inter[f"block{l}"]
+        y = m.head(xd, cuda(prev.astype(np.float32))).cpu().numpy()
+        e = O.rel_l2(y, y_ref); say(f"  head rel-L2 {e:.3e}")
+        assert e <= tol
+        e = O.rel_l2(y - inter["residual"], inter["y_main"]); say(f"  head (main path only) rel-L2 {e:.3e}")
+        assert e <= (tol if cfg.dtype else 1e-4)
+        # whole forward
+        y = m.forward(xd).cpu().numpy()
+        e = O.rel_l2(y, y_ref); say(f"  forward rel-L2 {e:.3e}")
+        assert e <= tol
+        y2 = m.forward(xd).cpu().numpy()
+        assert np.array_equal(y, y2)                 # same input, same bits
+
+
+def test_forward_c0_fp32():
+    cfg = WL.CONFIGS["c0"]
+    w, x = WL.make_weights(cfg), WL.make_fields(cfg)
+    ref, inter = O.reslim_forward(x, w, cfg, return_intermediates=True)
+    with B.Reslim(cfg, w) as m:
+        y = m.forward(cuda(x)).cpu().numpy()
+    e = O.rel_l2(y, ref)
+    e_main = O.rel_l2(y - inter["residual"], inter["y_main"])
+    say(f"c0 forward rel-L2 {e:.3e}, main path {e_main:.3e}")
+    assert e <= 1e-5 and e_main <= 1e-4
+
+
+def test_forward_c1_bf16_full_size():
+    """The benchmark configuration at full size, in the launch configuration the
+    benchmark times (batch 4, one forward), whole output against the oracle."""
+    cfg = WL.CONFIGS["c1"]
+    w, x = WL.make_weights(cfg), WL.make_fields(cfg)
+    say("c1: oracle forward (float64, host) ...")
+    ref, inter = O.reslim_forward(x, w, cfg, return_intermediates=True)
+    with B.Reslim(cfg, w) as m:
+        y = m.forward(cuda(x)).cpu().numpy()
+    e = O.rel_l2(y, ref)
+    e_main = O.rel_l2(y - inter["residual"], inter["y_main"])
+    say(f"c1 forward rel-L2 {e:.3e}, main path {e_main:.3e}")
+    assert np.isfinite(y).all() and e <= 2e-2 and e_main <= 2e-2
+
+
+def _sampled_tile_parity(cfg, tile_ids, batch_item=0):
+    """Full-size forward on the GPU; the oracle recomputes single tiles through the
+    whole stack (exact: tiles never interact, Sec. 4.2) and their interiors are compared."""
+    w, x = WL.make_weights(cfg), WL.make_fields(cfg)
+    tiles, _, _, _ = O.tiles_partition(cfg.Hp, cfg.Wp, cfg.tiles_y, cfg.tiles_x, cfg.halo)
+    with B.Reslim(cfg, w) as m:
+        y = m.forward(cuda(x))
+        torch.cuda.synchronize()
+        ps = cfg.patch * cfg.scale
+        worst = 0.0
+        for ti in tile_ids:
+            t = tiles[ti]
+            got = y[batch_item, :, t["y0"] * ps:t["y1"] * ps, t["x0"] * ps:t["x1"] * ps].cpu().numpy()
+            ref = O.forward_tile(x[batch_item], w, cfg, t, cfg.Wp)
+            e = O.rel_l2(got, ref)
+            say(f"  {cfg.name} tile {ti} (n_t={t['n_tok']}): rel-L2 {e:.3e}")
+            assert np.isfinite(got).all()
+            worst = max(worst, e)
+    assert worst <= 2e-2
+
+
+def test_forward_c2_sampled_tiles():
+    cfg = WL.CONFIGS["c2"]
+    _sampled_tile_parity(cfg, [0, 3, 27, 63], batch_item=1)       # corner, edge, interior, far corner
+
+
+def test_forward_c3_sampled_tiles():
+    cfg = WL.CONFIGS["c3"]
+    _sampled_tile_parity(cfg, [0, 8, 136, 255])
+
+
+def test_forward_c4_sampled_tile():
+    cfg = WL.CONFIGS["c4"]
+    _sampled_tile_parity(cfg, [5])                                  # an interior tile, 2448 tokens
+
+
+# ------------------------------------------------------------------ edge cases
+def test_edge_cases_and_errors():
+    cfg = SMALL_BF16
+    w = weights_for(cfg)
+    with B.Reslim(cfg, w) as m:
+        lib = B.load()
+        x = cuda(WL.make_fields(cfg))
+        y = torch.empty((cfg.batch, cfg.out_vars, cfg.H * 4, cfg.W * 4), device="cuda")
+        ws = m.ws
+        st = torch.cuda.current_stream().cuda_stream
+        # empty batch, missing / short / misaligned workspace, bad layer: codes, no launch
+        assert lib.reslim_forward(m.ctx, x.data_ptr(), y.data_ptr(), 0, ws.data_ptr(), ws.numel(), st) == B.RESLIM_ESHAPE
+        assert lib.reslim_forward(m.ctx, x.data_ptr(), y.data_ptr(), 2, None, 0, st) == B.RESLIM_EWORKSPACE
+        assert lib.reslim_forward(m.ctx, x.data_ptr(), y.data_ptr(), 2, ws.data_ptr(), 1024, st) == B.RESLIM_EWORKSPACE
+        assert lib.reslim_forward(m.ctx, x.data_ptr(), y.data_ptr(), 2, ws.data_ptr() + 16, ws.numel() - 16, st) == B.RESLIM_EWORKSPACE
+        assert lib.reslim_block_fwd(m.ctx, cfg.depth, x.data_ptr(), 2, ws.data_ptr(), ws.numel(), st) == B.RESLIM_EINVAL
+        assert b"layer" in lib.reslim_last_error(m.ctx)
+        assert lib.reslim_forward(m.ctx, None, y.data_ptr(), 2, ws.data_ptr(), ws.numel(), st) == B.RESLIM_EINVAL
+        # batch 1 of a batch-2 context equals item 0 of the batch-2 result
+        y2 = m.forward(x).cpu().numpy()
+        y1 = m.forward(x[:1].contiguous()).cpu().numpy()
+        assert np.array_equal(y1[0], y2[0])
+    # one tile with a halo wider than the grid, and a tile grid as fine as the patch grid
+    for kw in (dict(tiles_y=1, tiles_x=1, halo=50), dict(H=8, W=8, tiles_y=4, tiles_x=4, halo=1, batch=1)):
+        c2 = cfg.with_(**kw)
+        w2, x2 = weights_for(c2, 0.1), WL.make_fields(c2)
+        ref = O.reslim_forward(x2, w2, c2)
+        with B.Reslim(c2, w2) as m:
+            e = O.rel_l2(m.forward(cuda(x2)).cpu().numpy(), ref)
+        say(f"  edge {kw}: rel-L2 {e:.3e}")
+        assert e <= 2e-2
