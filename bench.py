@@ -1,0 +1,157 @@
+#!/usr/bin/env python3
+"""Benchmark of the Reslim+TILES forward on one MI355X.
+
+    python bench.py --gpus 1 --steps K --warmup W
+
+A step is one pass of the whole forward (embed, all blocks, head, residual path,
+stitch) over one batch of synthetic fields already resident in HBM.  Prints ONE
+JSON line: whole-job tokens/s (unique coarse tokens, halo copies not counted), the
+roofline position of the dominant kernel measured with HIP events on the launch
+stream, and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see
+# profiles/), keyed by (workload, kernel label); None where not measured.
+MEASURED_TRAFFIC = {}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="c1", help="workload name (c0..c4); the headline metric is quoted on c1")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (developer runs)")
+    ap.add_argument("--gemm-tile", type=int, default=-1, help="pin the bf16 GEMM tile (0/1/2), -1 = heuristic")
+    ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (tiles are batched on one MI355X); "
+              "--gpus must be 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2505_04802_amd import binding as B
+    from paper_2505_04802_amd import workloads as WL
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU path", file=sys.stderr)
+        return 2
+    cfg = WL.CONFIGS[args.config]
+    w = WL.make_weights(cfg)
+    x_host = WL.make_fields(cfg)
+    B.reslim_debug_set_gemm_tile(args.gemm_tile)
+    model = B.Reslim(cfg, w)
+    x = torch.from_numpy(x_host).cuda()
+    y = torch.empty((cfg.batch, cfg.out_vars, cfg.H * cfg.scale, cfg.W * cfg.scale), dtype=torch.float32, device="cuda")
+    K, W = args.steps, args.warmup
+
+    for _ in range(W):
+        model.forward(x, y)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        model.forward(x, y)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / K * 1e3
+    tokens = cfg.batch * cfg.n_tokens
+    value = tokens / (dt / K)
+
+    # ---- per-kernel durations: the same K steps again with every launch bracketed
+    # by HIP events on the launch stream (kept out of the headline timing above)
+    launches_per_step = 3 + 7 * cfg.depth + 3
+    B.reslim_profile_enable(model.ctx, launches_per_step * K)
+    for _ in range(K):
+        model.forward(x, y)
+    torch.cuda.synchronize()
+    recs = B.reslim_profile_read(model.ctx)
+    B.reslim_profile_enable(model.ctx, 0)
+    agg = {}
+    for name, ms, flop, nbytes in recs:
+        a = agg.setdefault(name, dict(calls=0, ms=0.0, flop=flop, bytes=nbytes))
+        a["calls"] += 1
+        a["ms"] += ms
+    kernels = []
+    for name, a in agg.items():
+        avg = a["ms"] / a["calls"]
+        kernels.append(dict(kernel=name, launches_per_step=a["calls"] // K, avg_ms=round(avg, 5),
+                            ms_per_step=round(a["ms"] / K, 5),
+                            tflops=round(a["flop"] / (avg * 1e-3) / 1e12, 2) if a["flop"] else None,
+                            gbs=round(a["bytes"] / (avg * 1e-3) / 1e9, 1)))
+    kernels.sort(key=lambda k: -k["ms_per_step"])
+    dom = kernels[0]
+    a = agg[dom["kernel"]]
+    avg_s = a["ms"] / a["calls"] * 1e-3
+    if a["flop"] > 0:
+        achieved = a["flop"] / avg_s / 1e12
+        roof = dict(bound="mfma", kernel=dom["kernel"], achieved=round(achieved, 2), peak=PEAK_BF16_TFLOPS,
+                    unit="TFLOP/s", frac=round(achieved / PEAK_BF16_TFLOPS, 4),
+                    traffic=MEASURED_TRAFFIC.get((cfg.name, dom["kernel"])), avg_launch_ms=round(avg_s * 1e3, 5),
+                    flop_per_launch=a["flop"])
+    else:
+        achieved = a["bytes"] / avg_s / 1e9
+        roof = dict(bound="hbm", kernel=dom["kernel"], achieved=round(achieved, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                    frac=round(achieved / PEAK_HBM_GBS, 4), traffic=MEASURED_TRAFFIC.get((cfg.name, dom["kernel"])),
+                    avg_launch_ms=round(avg_s * 1e3, 5), bytes_per_launch=a["bytes"])
+    gflop, aflop, hflop = B.reslim_flop_counts(model.ctx, cfg.batch)
+    tflops = (gflop + aflop + hflop) / (dt / K) / 1e12
+    if args.kernels:
+        for k in kernels:
+            print(json.dumps(k), file=sys.stderr)
+    model.close()
+
+    # ---- the CPU oracle on a bounded sample of the same workload (one sample of the batch)
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import reslim_oracle as O
+        if cfg.name in ("c0", "c1"):
+            t0 = time.perf_counter()
+            O.reslim_forward(x_host[:1], w, cfg)
+            ct = time.perf_counter() - t0
+            cpu_tokens, sample = cfg.n_tokens, f"1 of {cfg.batch} samples, full forward"
+        else:   # one tile through the whole stack, scaled by tiles (tiles never interact, Sec. 4.2)
+            tiles = O.tiles_partition(cfg.Hp, cfg.Wp, cfg.tiles_y, cfg.tiles_x, cfg.halo)[0]
+            t = tiles[len(tiles) // 2 + cfg.tiles_x // 2]
+            t0 = time.perf_counter()
+            O.forward_tile(x_host[0], w, cfg, t, cfg.Wp)
+            ct = time.perf_counter() - t0
+            cpu_tokens = (t["y1"] - t["y0"]) * (t["x1"] - t["x0"])
+            sample = f"1 of {len(tiles)} tiles of one sample, full stack (extrapolation linear in tiles)"
+        cpu = dict(value=round(cpu_tokens / ct, 1), unit="tokens/s", cores=os.cpu_count() if not os.environ.get("OMP_NUM_THREADS") else int(os.environ["OMP_NUM_THREADS"]),
+                   kind="oracle", sample=sample, seconds=round(ct, 2))
+
+    out = {
+        "metric": "Reslim+TILES fwd tokens/s", "value": round(value, 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.dtype else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B={cfg.batch} V={cfg.in_vars} {cfg.H}x{cfg.W} x{cfg.scale} -> "
+                               f"{cfg.H * cfg.scale}x{cfg.W * cfg.scale}, p={cfg.patch} D={cfg.embed_dim} "
+                               f"heads={cfg.heads} r={cfg.mlp_ratio} L={cfg.depth} tiles={cfg.tiles_y}x{cfg.tiles_x} "
+                               f"halo={cfg.halo}",
+                   "unique_tokens": tokens, "haloed_tokens": cfg.batch * model.n_h},
+        "tflops": round(tflops, 2), "mfma_frac": round(tflops / PEAK_BF16_TFLOPS, 4),
+        "haloed_tokens_per_s": round(cfg.batch * model.n_h / (dt / K), 1),
+        "roofline": roof, "cpu_baseline": cpu, "kernels": kernels,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -179,6 +179,24 @@ int reslim_forward(reslim_ctx *ctx, const float *x, float *y, int32_t batch,
 int reslim_flop_counts(const reslim_ctx *ctx, int32_t batch, double *gemm_flop,
                        double *attn_flop, double *head_flop);
 
+/* Per-launch timing for benchmarks.  reslim_profile_enable(ctx, n) creates 2*n HIP
+ * events (the only allocation; call it outside timed regions; n = 0 switches
+ * profiling off and frees them).  While on, every kernel launch of the entry
+ * points is bracketed by two event records on the caller's stream, up to n launches
+ * since the last reslim_profile_reset().  reslim_profile_read() waits for the
+ * recorded events and returns, per launch in issue order, a static label, the
+ * elapsed milliseconds and the launch's ALGORITHMIC work: flop (2 per
+ * multiply-add of the contraction, 0 for copies) and bytes (each operand read once,
+ * each result written once).  With out == NULL only the count is returned. */
+typedef struct {
+  const char *name;
+  float ms;
+  double flop, bytes;
+} reslim_profile_record;
+int reslim_profile_enable(reslim_ctx *ctx, int32_t max_records);
+int reslim_profile_reset(reslim_ctx *ctx);
+int reslim_profile_read(reslim_ctx *ctx, reslim_profile_record *out, int32_t max_out, int32_t *n_out);
+
 /* Tuning hook for benchmarks: pins the tile shape of the bf16 GEMM kernels
  * (-1 = built-in heuristic, 0 = 256x256, 1 = 256x128, 2 = 128x128).  Process-wide. */
 void reslim_debug_set_gemm_tile(int choice);

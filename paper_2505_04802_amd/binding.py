@@ -28,7 +28,7 @@ _WEIGHT_FIELDS = ["w_pe", "b_pe", "var_emb", "agg_q0", "agg_wq", "agg_bq", "agg_
 EXPORTS = ["tiles_partition", "reslim_create", "reslim_destroy", "reslim_last_error",
            "reslim_tokens_per_sample", "reslim_workspace_bytes", "reslim_embed_fwd", "tiles_attention_fwd",
            "reslim_block_fwd", "reslim_head_fwd", "reslim_forward", "reslim_flop_counts",
-           "reslim_debug_set_gemm_tile"]
+           "reslim_debug_set_gemm_tile", "reslim_profile_enable", "reslim_profile_reset", "reslim_profile_read"]
 
 
 class ReslimConfigC(C.Structure):
@@ -42,6 +42,10 @@ class ReslimWeightsC(C.Structure):
 class TileDesc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("y0", "y1", "x0", "x1", "Y0", "Y1", "X0", "X1")] + \
                [("tok_off", C.c_int64), ("n_tok", C.c_int32), ("_pad", C.c_int32)]
+
+
+class ProfileRecord(C.Structure):
+    _fields_ = [("name", C.c_char_p), ("ms", C.c_float), ("flop", C.c_double), ("bytes", C.c_double)]
 
 
 class ReslimError(RuntimeError):
@@ -80,6 +84,9 @@ def load() -> C.CDLL:
     lib.reslim_forward.argtypes = [vp, vp, vp, i32, vp, C.c_size_t, vp]
     dp = C.POINTER(C.c_double)
     lib.reslim_flop_counts.argtypes = [vp, i32, dp, dp, dp]
+    lib.reslim_profile_enable.argtypes = [vp, i32]
+    lib.reslim_profile_reset.argtypes = [vp]
+    lib.reslim_profile_read.argtypes = [vp, C.POINTER(ProfileRecord), i32, C.POINTER(i32)]
     lib.reslim_debug_set_gemm_tile.argtypes = [i32]
     lib.reslim_debug_set_gemm_tile.restype = None
     for name in EXPORTS:
@@ -148,6 +155,24 @@ def reslim_flop_counts(ctx: int, batch: int):
     g, a, h = C.c_double(), C.c_double(), C.c_double()
     _check(load().reslim_flop_counts(ctx, batch, C.byref(g), C.byref(a), C.byref(h)), ctx)
     return g.value, a.value, h.value
+
+
+def reslim_profile_enable(ctx: int, max_records: int) -> None:
+    _check(load().reslim_profile_enable(ctx, max_records), ctx)
+
+
+def reslim_profile_reset(ctx: int) -> None:
+    _check(load().reslim_profile_reset(ctx), ctx)
+
+
+def reslim_profile_read(ctx: int):
+    """[(label, ms, flop, bytes)] of the launches since the last reset (waits for them)."""
+    lib = load()
+    n = C.c_int32()
+    _check(lib.reslim_profile_read(ctx, None, 0, C.byref(n)), ctx)
+    recs = (ProfileRecord * max(n.value, 1))()
+    _check(lib.reslim_profile_read(ctx, recs, n.value, C.byref(n)), ctx)
+    return [(recs[i].name.decode(), float(recs[i].ms), recs[i].flop, recs[i].bytes) for i in range(n.value)]
 
 
 def _stream_ptr(stream=None) -> int:

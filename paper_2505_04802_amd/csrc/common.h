@@ -73,6 +73,11 @@ struct reslim_ctx {
   int32_t *d_out_var_idx;
   std::vector<void *> allocs;                // everything to hipFree
   std::string err;
+  // optional per-launch timing (reslim_profile_*): events are created up front
+  bool prof_on = false;
+  std::vector<hipEvent_t> prof_ev;           // 2 per record slot
+  struct ProfRec { const char *name; double flop, bytes; };
+  std::vector<ProfRec> prof_rec;             // records of the launches since the last reset
 };
 
 namespace reslim {
@@ -115,6 +120,7 @@ hipError_t launch_embed_agg(const reslim_ctx *c, const float *x, void *o, int ba
 hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *out, int batch,
                                   hipStream_t st);
 hipError_t attention_init();
+hipError_t elementwise_init();
 hipError_t launch_residual_unpatchify(const reslim_ctx *c, const float *x, const void *P, int p_is_act,
                                       float *y, int batch, hipStream_t st);
 

@@ -97,6 +97,7 @@ extern "C" const char *reslim_last_error(const reslim_ctx *ctx) {
 extern "C" void reslim_destroy(reslim_ctx *ctx) {
   if (!ctx) return;
   for (void *p : ctx->allocs) (void)hipFree(p);
+  for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
   delete ctx;
 }
 
@@ -253,6 +254,7 @@ extern "C" int reslim_create(const reslim_config *cfg, const reslim_weights *w, 
                   std::string("device upload failed: ") + hipGetErrorString(up.err));
     hipError_t e = gemm_init();
     if (e == hipSuccess) e = attention_init();
+    if (e == hipSuccess) e = elementwise_init();
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) return fail(RESLIM_EHIP, std::string("kernel setup failed: ") + hipGetErrorString(e));
   } catch (const std::bad_alloc &) {

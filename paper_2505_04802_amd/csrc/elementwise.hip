@@ -6,6 +6,8 @@
 //   layernorm       per-token normalisation; optional row map = "discard the halo"
 //   residual_unpatchify  residual path (bilinear upsampling + 3x3 convolution per
 //                   tile on its haloed box) fused with un-patchify, stitch and add
+#include <algorithm>
+
 #include "common.h"
 
 namespace reslim {
@@ -134,14 +136,15 @@ struct EmbedArgs {
   int64_t BN;   // batch * N patches
 };
 
-template <class T>
+// P2 = p*p when known at compile time (4 for the paper's 2x2 patches), 0 = run-time.
+template <class T, int P2>
 __global__ __launch_bounds__(256) void embed_agg_kernel(EmbedArgs e) {
-  constexpr int TP = 8;                       // patches per work-group
+  constexpr int TP = 16;                      // patches per work-group
   extern __shared__ float sm[];
-  const int p2 = e.p * e.p;
+  const int p2 = P2 ? P2 : e.p * e.p;
   const int VP2 = e.V * p2;
   float *pix = sm;                            // [TP][V*p2]
-  float *sc = sm + TP * VP2;                  // [TP][heads][V]
+  float *sc = sm + TP * VP2;                  // [TP][heads][V] softmax weights over variables
   const int t = threadIdx.x;
   const int64_t bn0 = static_cast<int64_t>(blockIdx.x) * TP;
 
@@ -159,23 +162,22 @@ __global__ __launch_bounds__(256) void embed_agg_kernel(EmbedArgs e) {
     pix[idx] = val;
   }
   __syncthreads();
-  const int HV = e.heads * e.V;
-  for (int idx = t; idx < TP * HV; idx += 256) {
-    const int pi = idx / HV, rem = idx % HV, g = rem / e.V, v = rem % e.V;
-    const float *Ar = e.A + (static_cast<size_t>(v) * e.heads + g) * p2;
-    const float *px = pix + pi * VP2 + v * p2;
-    float s = e.a0[v * e.heads + g];
-    for (int i = 0; i < p2; ++i) s = fmaf(Ar[i], px[i], s);
-    sc[idx] = s;
-  }
-  __syncthreads();
+  // one thread per (patch, head): scores over the variables, then their softmax
   for (int idx = t; idx < TP * e.heads; idx += 256) {
+    const int pi = idx / e.heads, g = idx % e.heads;
     float *r = sc + static_cast<size_t>(idx) * e.V;
-    float mx = r[0];
-    for (int v = 1; v < e.V; ++v) mx = fmaxf(mx, r[v]);
+    float mx = -INFINITY;
+    for (int v = 0; v < e.V; ++v) {
+      const float *Ar = e.A + (static_cast<size_t>(v) * e.heads + g) * p2;
+      const float *px = pix + pi * VP2 + v * p2;
+      float s = e.a0[v * e.heads + g];
+      for (int i = 0; i < p2; ++i) s = fmaf(Ar[i], px[i], s);
+      r[v] = s;
+      mx = fmaxf(mx, s);
+    }
     float sum = 0.f;
     for (int v = 0; v < e.V; ++v) {
-      const float ex = expf(r[v] - mx);
+      const float ex = __expf(r[v] - mx);
       r[v] = ex;
       sum += ex;
     }
@@ -183,21 +185,36 @@ __global__ __launch_bounds__(256) void embed_agg_kernel(EmbedArgs e) {
     for (int v = 0; v < e.V; ++v) r[v] *= inv;
   }
   __syncthreads();
+  // one thread per feature d: o[pi][d] = sum_v a[pi][head(d)][v] * (c[v][d] + U[v][d][:] . pix[pi][v][:])
   T *out = static_cast<T *>(e.o);
   for (int d = t; d < e.D; d += 256) {
     const int g = d / e.dh;
     float acc[TP];
 #pragma unroll
     for (int pi = 0; pi < TP; ++pi) acc[pi] = 0.f;
-    for (int v = 0; v < e.V; ++v) {
-      const float *Ur = e.U + (static_cast<size_t>(v) * e.D + d) * p2;
-      const float cv = e.c[static_cast<size_t>(v) * e.D + d];
+    if constexpr (P2 == 4) {
+#pragma unroll 4
+      for (int v = 0; v < e.V; ++v) {
+        const float4 u = *reinterpret_cast<const float4 *>(e.U + (static_cast<size_t>(v) * e.D + d) * 4);
+        const float cv = e.c[static_cast<size_t>(v) * e.D + d];
 #pragma unroll
-      for (int pi = 0; pi < TP; ++pi) {
-        const float *px = pix + pi * VP2 + v * p2;
-        float val = cv;
-        for (int i = 0; i < p2; ++i) val = fmaf(Ur[i], px[i], val);
-        acc[pi] = fmaf(sc[(pi * e.heads + g) * e.V + v], val, acc[pi]);
+        for (int pi = 0; pi < TP; ++pi) {
+          const float4 px = *reinterpret_cast<const float4 *>(pix + pi * VP2 + v * 4);
+          const float val = fmaf(u.x, px.x, fmaf(u.y, px.y, fmaf(u.z, px.z, fmaf(u.w, px.w, cv))));
+          acc[pi] = fmaf(sc[(pi * e.heads + g) * e.V + v], val, acc[pi]);
+        }
+      }
+    } else {
+      for (int v = 0; v < e.V; ++v) {
+        const float *Ur = e.U + (static_cast<size_t>(v) * e.D + d) * p2;
+        const float cv = e.c[static_cast<size_t>(v) * e.D + d];
+#pragma unroll
+        for (int pi = 0; pi < TP; ++pi) {
+          const float *px = pix + pi * VP2 + v * p2;
+          float val = cv;
+          for (int i = 0; i < p2; ++i) val = fmaf(Ur[i], px[i], val);
+          acc[pi] = fmaf(sc[(pi * e.heads + g) * e.V + v], val, acc[pi]);
+        }
       }
     }
 #pragma unroll
@@ -206,20 +223,35 @@ __global__ __launch_bounds__(256) void embed_agg_kernel(EmbedArgs e) {
   }
 }
 
+hipError_t elementwise_init() {
+  hipError_t e = hipSuccess;
+  const int lim = 160 * 1024;
+#define RESLIM_ATTR(K) if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(&K), hipFuncAttributeMaxDynamicSharedMemorySize, lim)
+  RESLIM_ATTR((embed_agg_kernel<bf16_t, 4>));
+  RESLIM_ATTR((embed_agg_kernel<bf16_t, 0>));
+  RESLIM_ATTR((embed_agg_kernel<float, 4>));
+  RESLIM_ATTR((embed_agg_kernel<float, 0>));
+#undef RESLIM_ATTR
+  return e;
+}
+
 hipError_t launch_embed_agg(const reslim_ctx *c, const float *x, void *o, int batch, hipStream_t st) {
+  constexpr int TP = 16;
   EmbedArgs e;
   e.x = x; e.A = c->d_agg_A; e.a0 = c->d_agg_a0; e.U = c->d_agg_U; e.c = c->d_agg_c; e.o = o;
   e.V = c->cfg.in_vars; e.H = c->cfg.H; e.W = c->cfg.W; e.p = c->cfg.patch; e.Wp = c->Wp; e.N = c->N;
   e.D = c->cfg.embed_dim; e.heads = c->cfg.heads; e.dh = c->dh;
   e.BN = static_cast<int64_t>(batch) * c->N;
-  const size_t lds = 8ull * (static_cast<size_t>(e.V) * e.p * e.p + static_cast<size_t>(e.heads) * e.V) * sizeof(float);
-  if (lds > 60 * 1024) return hipErrorInvalidValue;
-  const int64_t blocks = (e.BN + 7) / 8;
+  const size_t lds = static_cast<size_t>(TP) * (static_cast<size_t>(e.V) * e.p * e.p + static_cast<size_t>(e.heads) * e.V) * sizeof(float);
+  if (lds > 160 * 1024) return hipErrorInvalidValue;
+  const int64_t blocks = (e.BN + TP - 1) / TP;
   if (blocks > INT32_MAX) return hipErrorInvalidValue;
-  if (c->cfg.dtype == RESLIM_BF16)
-    embed_agg_kernel<bf16_t><<<dim3(static_cast<unsigned>(blocks)), dim3(256), lds, st>>>(e);
-  else
-    embed_agg_kernel<float><<<dim3(static_cast<unsigned>(blocks)), dim3(256), lds, st>>>(e);
+  const dim3 grid(static_cast<unsigned>(blocks)), blk(256);
+  const bool bf = c->cfg.dtype == RESLIM_BF16, p4 = e.p == 2;
+  if (bf && p4) embed_agg_kernel<bf16_t, 4><<<grid, blk, lds, st>>>(e);
+  else if (bf) embed_agg_kernel<bf16_t, 0><<<grid, blk, lds, st>>>(e);
+  else if (p4) embed_agg_kernel<float, 4><<<grid, blk, lds, st>>>(e);
+  else embed_agg_kernel<float, 0><<<grid, blk, lds, st>>>(e);
   return hipGetLastError();
 }
 

@@ -52,13 +52,30 @@ static int hip_fail(reslim_ctx *c, const char *fn, const char *what, hipError_t 
     if (e_ != hipSuccess) return hip_fail(c, fn, what, e_);      \
   } while (0)
 
+// A launch with its algorithmic work attached; when profiling is on the launch is
+// bracketed by two pre-created events on the same stream.
+#define RESLIM_LAUNCH(label, flop_, bytes_, expr)                                      \
+  do {                                                                                 \
+    const size_t slot_ = c->prof_rec.size();                                           \
+    const bool p_ = c->prof_on && 2 * slot_ + 1 < c->prof_ev.size();                   \
+    if (p_) RESLIM_TRY("event", hipEventRecord(c->prof_ev[2 * slot_], st));            \
+    RESLIM_TRY(label, expr);                                                           \
+    if (p_) {                                                                          \
+      RESLIM_TRY("event", hipEventRecord(c->prof_ev[2 * slot_ + 1], st));              \
+      c->prof_rec.push_back({label, static_cast<double>(flop_), static_cast<double>(bytes_)}); \
+    }                                                                                  \
+  } while (0)
+
 static int embed_impl(reslim_ctx *c, const char *fn, const float *x, float *tokens, int batch, const Workspace &w, hipStream_t st) {
   const int D = c->cfg.embed_dim, dt = c->cfg.dtype;
   const int Mi = batch * c->N;
-  RESLIM_TRY("embed_agg", launch_embed_agg(c, x, w.A, batch, st));
-  RESLIM_TRY("aggregation output GEMM",
-             launch_gemm(dt, EPI_BIAS_TAB_F32, w.A, c->d_agg_wo, c->d_zero_bias, w.big, D, c->d_pos_res, c->N, Mi, D, D, st));
-  RESLIM_TRY("gather", launch_gather_rows(static_cast<const float *>(w.big), c->d_gather, tokens, batch, c->n_h, c->N, D, st));
+  const double es = static_cast<double>(act_size(c)), dMi = Mi, dD = D, dM = static_cast<double>(batch) * c->n_h;
+  RESLIM_LAUNCH("embed_agg", 0, 4.0 * batch * c->cfg.in_vars * c->cfg.H * c->cfg.W + dMi * dD * es,
+                launch_embed_agg(c, x, w.A, batch, st));
+  RESLIM_LAUNCH("gemm_agg_out", 2.0 * dMi * dD * dD, dMi * dD * es + dD * dD * es + 4.0 * c->N * dD + 4.0 * dMi * dD,
+                launch_gemm(dt, EPI_BIAS_TAB_F32, w.A, c->d_agg_wo, c->d_zero_bias, w.big, D, c->d_pos_res, c->N, Mi, D, D, st));
+  RESLIM_LAUNCH("gather", 0, 4.0 * dMi * dD + 4.0 * dM * dD,
+                launch_gather_rows(static_cast<const float *>(w.big), c->d_gather, tokens, batch, c->n_h, c->N, D, st));
   return RESLIM_OK;
 }
 
@@ -66,28 +83,80 @@ static int block_impl(reslim_ctx *c, const char *fn, int layer, float *X, int ba
   const int D = c->cfg.embed_dim, R = c->R, dt = c->cfg.dtype;
   const int M = static_cast<int>(batch * c->n_h);
   const LayerWeights &lw = c->layers[layer];
-  RESLIM_TRY("LN1", launch_layernorm(dt, X, nullptr, 0, 0, lw.ln1_g, lw.ln1_b, w.A, M, D, st));
-  RESLIM_TRY("QKV GEMM", launch_gemm(dt, EPI_BIAS_ACT, w.A, lw.w_qkv, lw.b_qkv, w.big, 3 * D, nullptr, 0, M, 3 * D, D, st));
-  RESLIM_TRY("tile attention", launch_tiles_attention(c, w.big, w.A, batch, st));
-  RESLIM_TRY("proj GEMM", launch_gemm(dt, EPI_BIAS_RESADD_F32, w.A, lw.w_proj, lw.b_proj, X, D, nullptr, 0, M, D, D, st));
-  RESLIM_TRY("LN2", launch_layernorm(dt, X, nullptr, 0, 0, lw.ln2_g, lw.ln2_b, w.A, M, D, st));
-  RESLIM_TRY("FC1 GEMM", launch_gemm(dt, EPI_BIAS_GELU_ACT, w.A, lw.w_fc1, lw.b_fc1, w.big, R, nullptr, 0, M, R, D, st));
-  RESLIM_TRY("FC2 GEMM", launch_gemm(dt, EPI_BIAS_RESADD_F32, w.big, lw.w_fc2, lw.b_fc2, X, D, nullptr, 0, M, D, R, st));
+  const double es = static_cast<double>(act_size(c)), dM = M, dD = D, dR = R;
+  double pairs = 0;
+  for (const tile_desc &t : c->tiles) pairs += static_cast<double>(t.n_tok) * t.n_tok;
+  RESLIM_LAUNCH("layernorm", 0, dM * dD * (4.0 + es), launch_layernorm(dt, X, nullptr, 0, 0, lw.ln1_g, lw.ln1_b, w.A, M, D, st));
+  RESLIM_LAUNCH("gemm_qkv", 6.0 * dM * dD * dD, dM * dD * es + 3.0 * dD * dD * es + 3.0 * dM * dD * es,
+                launch_gemm(dt, EPI_BIAS_ACT, w.A, lw.w_qkv, lw.b_qkv, w.big, 3 * D, nullptr, 0, M, 3 * D, D, st));
+  RESLIM_LAUNCH("tiles_attention", 4.0 * pairs * dD * batch, 4.0 * dM * dD * es, launch_tiles_attention(c, w.big, w.A, batch, st));
+  RESLIM_LAUNCH("gemm_proj", 2.0 * dM * dD * dD, dM * dD * es + dD * dD * es + 8.0 * dM * dD,
+                launch_gemm(dt, EPI_BIAS_RESADD_F32, w.A, lw.w_proj, lw.b_proj, X, D, nullptr, 0, M, D, D, st));
+  RESLIM_LAUNCH("layernorm", 0, dM * dD * (4.0 + es), launch_layernorm(dt, X, nullptr, 0, 0, lw.ln2_g, lw.ln2_b, w.A, M, D, st));
+  RESLIM_LAUNCH("gemm_fc1", 2.0 * dM * dD * dR, dM * dD * es + dD * dR * es + dM * dR * es,
+                launch_gemm(dt, EPI_BIAS_GELU_ACT, w.A, lw.w_fc1, lw.b_fc1, w.big, R, nullptr, 0, M, R, D, st));
+  RESLIM_LAUNCH("gemm_fc2", 2.0 * dM * dD * dR, dM * dR * es + dD * dR * es + 8.0 * dM * dD,
+                launch_gemm(dt, EPI_BIAS_RESADD_F32, w.big, lw.w_fc2, lw.b_fc2, X, D, nullptr, 0, M, D, R, st));
   return RESLIM_OK;
 }
 
 static int head_impl(reslim_ctx *c, const char *fn, const float *x, const float *tokens, float *y, int batch, const Workspace &w, hipStream_t st) {
   const int D = c->cfg.embed_dim, dt = c->cfg.dtype;
   const int Mi = batch * c->N;
-  RESLIM_TRY("final LN", launch_layernorm(dt, tokens, c->d_interior_src, c->N, c->n_h, c->d_lnf_g, c->d_lnf_b, w.A, Mi, D, st));
-  RESLIM_TRY("head GEMM", launch_gemm(dt, EPI_BIAS_F32, w.A, c->d_w_head, c->d_b_head, w.big, c->head_out, nullptr, 0, Mi, c->head_out, D, st));
-  RESLIM_TRY("residual path", launch_residual_unpatchify(c, x, w.big, 0, y, batch, st));
+  const double es = static_cast<double>(act_size(c)), dMi = Mi, dD = D, dO = c->head_out;
+  const double fine = static_cast<double>(batch) * c->cfg.out_vars * c->cfg.H * c->cfg.W * c->cfg.scale * c->cfg.scale;
+  RESLIM_LAUNCH("layernorm_final", 0, dMi * dD * (4.0 + es),
+                launch_layernorm(dt, tokens, c->d_interior_src, c->N, c->n_h, c->d_lnf_g, c->d_lnf_b, w.A, Mi, D, st));
+  RESLIM_LAUNCH("gemm_head", 2.0 * dMi * dD * dO, dMi * dD * es + dD * dO * es + 4.0 * dMi * dO,
+                launch_gemm(dt, EPI_BIAS_F32, w.A, c->d_w_head, c->d_b_head, w.big, c->head_out, nullptr, 0, Mi, c->head_out, D, st));
+  RESLIM_LAUNCH("residual_unpatchify", 18.0 * c->cfg.out_vars * fine,
+                4.0 * batch * c->cfg.out_vars * c->cfg.H * c->cfg.W + 4.0 * dMi * dO + 4.0 * fine,
+                launch_residual_unpatchify(c, x, w.big, 0, y, batch, st));
   return RESLIM_OK;
 }
 
 }  // namespace reslim
 
 using namespace reslim;
+
+extern "C" int reslim_profile_enable(reslim_ctx *c, int32_t max_records) {
+  if (!c || max_records < 0) return RESLIM_EINVAL;
+  for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
+  c->prof_ev.clear();
+  c->prof_rec.clear();
+  c->prof_on = max_records > 0;
+  for (int i = 0; i < 2 * max_records; ++i) {
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return set_error(c, RESLIM_EHIP, "reslim_profile_enable: hipEventCreate failed");
+    c->prof_ev.push_back(e);
+  }
+  c->prof_rec.reserve(max_records);
+  return RESLIM_OK;
+}
+
+extern "C" int reslim_profile_reset(reslim_ctx *c) {
+  if (!c) return RESLIM_EINVAL;
+  c->prof_rec.clear();
+  return RESLIM_OK;
+}
+
+extern "C" int reslim_profile_read(reslim_ctx *c, reslim_profile_record *out, int32_t max_out, int32_t *n_out) {
+  if (!c || !n_out) return RESLIM_EINVAL;
+  const int n = static_cast<int>(c->prof_rec.size());
+  *n_out = n;
+  if (!out) return RESLIM_OK;
+  for (int i = 0; i < n && i < max_out; ++i) {
+    if (hipEventSynchronize(c->prof_ev[2 * i + 1]) != hipSuccess) return set_error(c, RESLIM_EHIP, "reslim_profile_read: event sync failed");
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, c->prof_ev[2 * i], c->prof_ev[2 * i + 1]) != hipSuccess)
+      return set_error(c, RESLIM_EHIP, "reslim_profile_read: elapsed time failed");
+    out[i].name = c->prof_rec[i].name;
+    out[i].ms = ms;
+    out[i].flop = c->prof_rec[i].flop;
+    out[i].bytes = c->prof_rec[i].bytes;
+  }
+  return RESLIM_OK;
+}
 
 extern "C" int reslim_tokens_per_sample(const reslim_ctx *ctx, int64_t *n_h_out) {
   if (!ctx || !n_h_out) return RESLIM_EINVAL;

@@ -34,6 +34,21 @@ __device__ __forceinline__ float gelu_erf(float x) {
   return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f));
 }
 
+// erf by the rational-exponential form of Abramowitz & Stegun 7.1.26 (|error| <=
+// 1.5e-7, far below bf16 resolution): 13 plain ALU operations, one reciprocal and
+// one exponential per element instead of the library routine's branches.
+__device__ __forceinline__ float gelu_erf_fast(float x) {
+  const float z = fabsf(x) * 0.70710678118654752440f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
+  float p = fmaf(1.061405429f, t, -1.453152027f);
+  p = fmaf(p, t, 1.421413741f);
+  p = fmaf(p, t, -0.284496736f);
+  p = fmaf(p, t, 0.254829592f);
+  const float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * z * z);
+  const float erf_abs = fmaf(-p * t, e, 1.0f);
+  return 0.5f * x * (1.0f + copysignf(erf_abs, x));
+}
+
 template <int EPI>
 __device__ __forceinline__ void epilogue_store(const GemmArgs &g, int m, int n, float v) {
   // caller guarantees m < M, n < N
@@ -41,7 +56,7 @@ __device__ __forceinline__ void epilogue_store(const GemmArgs &g, int m, int n, 
   if constexpr (EPI == EPI_BIAS_ACT) {
     static_cast<bf16_t *>(g.out)[o] = f32_to_bf16(v + g.bias[n]);
   } else if constexpr (EPI == EPI_BIAS_GELU_ACT) {
-    static_cast<bf16_t *>(g.out)[o] = f32_to_bf16(gelu_erf(v + g.bias[n]));
+    static_cast<bf16_t *>(g.out)[o] = f32_to_bf16(gelu_erf_fast(v + g.bias[n]));
   } else if constexpr (EPI == EPI_BIAS_RESADD_F32) {
     float *p = static_cast<float *>(g.out) + o;
     *p = *p + (v + g.bias[n]);
@@ -60,8 +75,8 @@ __device__ __forceinline__ int xcd_remap(int pid, int total) {
   return x * q + (x < r ? x : r) + local;
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int EPI>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g) {
+template <int BM, int BN, int BK, int WM, int WN, int NBUF, int MINW, int EPI>
+__global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_bf16_kernel(GemmArgs g) {
   constexpr int NT = WM * WN * 64;
   constexpr int PITCH = BK + 8;           // bf16 elements per LDS row
   constexpr int TM = BM / WM, TN = BN / WN;
@@ -73,8 +88,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g) {
   constexpr int GROUP_M = 8;
 
   extern __shared__ __align__(16) unsigned char smem[];
-  bf16_t *As = reinterpret_cast<bf16_t *>(smem);        // [2][BM][PITCH]
-  bf16_t *Bs = As + 2 * BM * PITCH;                      // [2][BN][PITCH]
+  bf16_t *As = reinterpret_cast<bf16_t *>(smem);        // [NBUF][BM][PITCH]
+  bf16_t *Bs = As + NBUF * BM * PITCH;                   // [NBUF][BN][PITCH]
 
   const int total = g.grid_m * g.grid_n;
   int pid = xcd_remap(blockIdx.x, total);
@@ -141,14 +156,25 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g) {
 
   const int nk = K / BK;
   load_global(0);
-  store_lds(0);
-  __syncthreads();
+  if constexpr (NBUF == 2) {
+    store_lds(0);
+    __syncthreads();
+  }
 
   const int a_frag = (wm * TM + l32) * PITCH + hi * 8;
   const int b_frag = (wn * TN + l32) * PITCH + hi * 8;
 
+  // NBUF == 2: one barrier per slab, the next slab is written to the other buffer
+  // after this one has been consumed.  NBUF == 1: half the LDS (two work-groups per
+  // CU overlap each other's barriers and epilogues); the slab is written between two
+  // barriers and the next one is already in flight in registers during the MFMAs.
   for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
+    const int buf = NBUF == 2 ? (kt & 1) : 0;
+    if constexpr (NBUF == 1) {
+      if (kt > 0) __syncthreads();
+      store_lds(0);
+      __syncthreads();
+    }
     if (kt + 1 < nk) load_global((kt + 1) * BK);
     const bf16_t *as = As + buf * BM * PITCH + a_frag;
     const bf16_t *bs = Bs + buf * BN * PITCH + b_frag;
@@ -165,8 +191,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g) {
         for (int j = 0; j < NI; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) store_lds(buf ^ 1);
-    __syncthreads();
+    if constexpr (NBUF == 2) {
+      if (kt + 1 < nk) store_lds(buf ^ 1);
+      __syncthreads();
+    }
   }
 
   // accumulator layout of the 32x32 tile: lane holds column (lane % 32) and rows
@@ -245,17 +273,17 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
 }
 
 // ------------------------------------------------------------------ launchers
-template <int BM, int BN, int BK, int WM, int WN>
+template <int BM, int BN, int BK, int WM, int WN, int NBUF, int MINW>
 struct TileCfg {
-  static constexpr int kBM = BM, kBN = BN, kBK = BK, kWM = WM, kWN = WN;
+  static constexpr int kBM = BM, kBN = BN, kBK = BK, kWM = WM, kWN = WN, kNBUF = NBUF, kMINW = MINW;
   static constexpr int kThreads = WM * WN * 64;
-  static constexpr size_t kLds = 2ull * (BM + BN) * (BK + 8) * sizeof(bf16_t);
+  static constexpr size_t kLds = static_cast<size_t>(NBUF) * (BM + BN) * (BK + 8) * sizeof(bf16_t);
 };
 
 template <class TC, int EPI>
 static hipError_t set_attr() {
   return hipFuncSetAttribute(
-      reinterpret_cast<const void *>(&gemm_bf16_kernel<TC::kBM, TC::kBN, TC::kBK, TC::kWM, TC::kWN, EPI>),
+      reinterpret_cast<const void *>(&gemm_bf16_kernel<TC::kBM, TC::kBN, TC::kBK, TC::kWM, TC::kWN, TC::kNBUF, TC::kMINW, EPI>),
       hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(TC::kLds));
 }
 
@@ -264,14 +292,14 @@ static hipError_t launch_bf16_tc(GemmArgs g, hipStream_t st) {
   g.grid_m = (g.M + TC::kBM - 1) / TC::kBM;
   g.grid_n = (g.N + TC::kBN - 1) / TC::kBN;
   const int total = g.grid_m * g.grid_n;
-  gemm_bf16_kernel<TC::kBM, TC::kBN, TC::kBK, TC::kWM, TC::kWN, EPI>
+  gemm_bf16_kernel<TC::kBM, TC::kBN, TC::kBK, TC::kWM, TC::kWN, TC::kNBUF, TC::kMINW, EPI>
       <<<dim3(total), dim3(TC::kThreads), TC::kLds, st>>>(g);
   return hipGetLastError();
 }
 
-typedef TileCfg<256, 256, 64, 2, 2> TileBig;     // 128x128 per wave, 144 KB LDS, 1 WG / CU
-typedef TileCfg<256, 128, 64, 2, 2> TileWide;    // 128x64 per wave, 108 KB LDS
-typedef TileCfg<128, 128, 64, 2, 2> TileSmall;   // 64x64 per wave, 72 KB LDS, 2 WG / CU
+typedef TileCfg<256, 256, 64, 2, 2, 2, 1> TileBig;     // 128x128 per wave, 144 KB LDS, 1 WG / CU
+typedef TileCfg<256, 128, 64, 2, 2, 1, 2> TileWide;    // 128x64 per wave, 54 KB LDS, 2 WG / CU
+typedef TileCfg<128, 128, 64, 2, 2, 1, 3> TileSmall;   // 64x64 per wave, 36 KB LDS, 3 WG / CU
 
 static int g_gemm_tile_override = -1;   // test / tuning hook: 0 big, 1 wide, 2 small
 
