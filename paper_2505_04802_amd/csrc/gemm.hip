@@ -49,21 +49,50 @@ __device__ __forceinline__ float gelu_erf_fast(float x) {
   return 0.5f * x * (1.0f + copysignf(erf_abs, x));
 }
 
-template <int EPI>
-__device__ __forceinline__ void epilogue_store(const GemmArgs &g, int m, int n, float v) {
-  // caller guarantees m < M, n < N
-  const size_t o = static_cast<size_t>(m) * g.ldo + n;
-  if constexpr (EPI == EPI_BIAS_ACT) {
-    static_cast<bf16_t *>(g.out)[o] = f32_to_bf16(v + g.bias[n]);
-  } else if constexpr (EPI == EPI_BIAS_GELU_ACT) {
-    static_cast<bf16_t *>(g.out)[o] = f32_to_bf16(gelu_erf_fast(v + g.bias[n]));
-  } else if constexpr (EPI == EPI_BIAS_RESADD_F32) {
-    float *p = static_cast<float *>(g.out) + o;
-    *p = *p + (v + g.bias[n]);
-  } else if constexpr (EPI == EPI_BIAS_TAB_F32) {
-    static_cast<float *>(g.out)[o] = v + g.tab[static_cast<size_t>(m % g.tab_rows) * g.N + n];
-  } else {
-    static_cast<float *>(g.out)[o] = v + g.bias[n];
+// Epilogue of one wave: acc[i][j] is the 32x32 block at rows m_base + 32 i, columns
+// n_base + 32 j.  Accumulator layout of the 32x32 MFMA: a lane holds column
+// (lane % 32) and rows 8*(r/4) + 4*(lane/32) + r%4 for r = 0..15, so a store
+// instruction writes two rows of 32 consecutive columns.  The per-column bias is
+// read once per block; full tiles take a path without per-row bounds checks.
+template <int EPI, bool GUARD_M>
+__device__ __forceinline__ void epilogue_block(const GemmArgs &g, const f32x16 &a, int m_first, int n, float bias) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int m = m_first + 8 * (r / 4) + (r % 4);
+    if (GUARD_M && m >= g.M) continue;
+    const size_t o = static_cast<size_t>(m) * g.ldo + n;
+    const float v = a[r];
+    if constexpr (EPI == EPI_BIAS_ACT) {
+      static_cast<bf16_t *>(g.out)[o] = f32_to_bf16(v + bias);
+    } else if constexpr (EPI == EPI_BIAS_GELU_ACT) {
+      static_cast<bf16_t *>(g.out)[o] = f32_to_bf16(gelu_erf_fast(v + bias));
+    } else if constexpr (EPI == EPI_BIAS_RESADD_F32) {
+      float *p = static_cast<float *>(g.out) + o;
+      *p = *p + (v + bias);
+    } else if constexpr (EPI == EPI_BIAS_TAB_F32) {
+      static_cast<float *>(g.out)[o] = v + g.tab[static_cast<size_t>(m % g.tab_rows) * g.N + n];
+    } else {
+      static_cast<float *>(g.out)[o] = v + bias;
+    }
+  }
+}
+
+template <int EPI, int MI, int NI>
+__device__ __forceinline__ void epilogue_wave(const GemmArgs &g, const f32x16 (&acc)[MI][NI], int m_base, int n_base,
+                                              int l32, int hi) {
+  const bool full = m_base + MI * 32 <= g.M;     // wave-uniform
+#pragma unroll
+  for (int j = 0; j < NI; ++j) {
+    const int n = n_base + j * 32 + l32;
+    if (n >= g.N) continue;
+    const float bias = (EPI == EPI_BIAS_TAB_F32) ? 0.f : g.bias[n];
+    if (full) {
+#pragma unroll
+      for (int i = 0; i < MI; ++i) epilogue_block<EPI, false>(g, acc[i][j], m_base + i * 32 + 4 * hi, n, bias);
+    } else {
+#pragma unroll
+      for (int i = 0; i < MI; ++i) epilogue_block<EPI, true>(g, acc[i][j], m_base + i * 32 + 4 * hi, n, bias);
+    }
   }
 }
 
@@ -197,22 +226,10 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_bf16_kernel(GemmArgs 
     }
   }
 
-  // accumulator layout of the 32x32 tile: lane holds column (lane % 32) and rows
-  // 8*(r/4) + 4*(lane/32) + r%4 for r = 0..15
-#pragma unroll
-  for (int i = 0; i < MI; ++i) {
-#pragma unroll
-    for (int j = 0; j < NI; ++j) {
-      const int n = n0 + wn * TN + j * 32 + l32;
-      if (n >= g.N) continue;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * TM + i * 32 + 8 * (r / 4) + 4 * hi + (r % 4);
-        if (m < g.M) epilogue_store<EPI>(g, m, n, acc[i][j][r]);
-      }
-    }
-  }
+  epilogue_wave<EPI, MI, NI>(g, acc, m0 + wm * TM, n0 + wn * TN, l32, hi);
 }
+
+#include "gemm_dl.inc"
 
 // ------------------------------------------------------------------ fp32 debug path
 template <int EPI>
@@ -301,21 +318,26 @@ typedef TileCfg<256, 256, 64, 2, 2, 2, 1> TileBig;     // 128x128 per wave, 144 
 typedef TileCfg<256, 128, 64, 2, 2, 1, 2> TileWide;    // 128x64 per wave, 54 KB LDS, 2 WG / CU
 typedef TileCfg<128, 128, 64, 2, 2, 1, 3> TileSmall;   // 64x64 per wave, 36 KB LDS, 3 WG / CU
 
-static int g_gemm_tile_override = -1;   // test / tuning hook: 0 big, 1 wide, 2 small
+typedef DlCfg<4, 2, 64, 2> DlA;          // persistent 256x256, 8 waves of 64x128, 2 x 64 KB slabs in LDS
+typedef DlCfg<2, 4, 32, 4> DlB;          // same tile, 4 x 32 KB slabs (three in flight)
+
+static int g_gemm_tile_override = -1;   // test / tuning hook: 0 big, 1 wide, 2 small, 3/4 direct-to-LDS
 
 template <int EPI>
 static hipError_t launch_bf16(GemmArgs g, hipStream_t st) {
-  // pick the largest tile that still yields at least ~2 full rounds of 256 CUs
-  int choice;
+  // Measured on MI355X: the persistent direct-to-LDS kernel wins once there are at
+  // least two rounds of 256x256 tiles and either a deep contraction or a light
+  // epilogue; otherwise 128x128 tiles with three work-groups per CU hide the
+  // epilogue (residual read-modify-write, GELU) behind other groups' MFMAs.
   const long tiles_big = static_cast<long>((g.M + 255) / 256) * ((g.N + 255) / 256);
-  const long tiles_wide = static_cast<long>((g.M + 255) / 256) * ((g.N + 127) / 128);
-  if (tiles_big >= 512) choice = 0;
-  else if (tiles_wide >= 512) choice = 1;
-  else choice = 2;
+  int choice = 2;
+  if (tiles_big >= 2L * g_num_cus && (g.K >= 1024 || EPI == EPI_BIAS_ACT)) choice = 3;
   if (g_gemm_tile_override >= 0) choice = g_gemm_tile_override;
   switch (choice) {
     case 0: return launch_bf16_tc<TileBig, EPI>(g, st);
     case 1: return launch_bf16_tc<TileWide, EPI>(g, st);
+    case 3: return launch_bf16_dl<DlA, EPI>(g, st);
+    case 4: return launch_bf16_dl<DlB, EPI>(g, st);
     default: return launch_bf16_tc<TileSmall, EPI>(g, st);
   }
 }
@@ -332,11 +354,16 @@ static hipError_t init_epi() {
   hipError_t e;
   if ((e = set_attr<TileBig, EPI>()) != hipSuccess) return e;
   if ((e = set_attr<TileWide, EPI>()) != hipSuccess) return e;
+  if ((e = set_attr_dl<DlA, EPI>()) != hipSuccess) return e;
+  if ((e = set_attr_dl<DlB, EPI>()) != hipSuccess) return e;
   return set_attr<TileSmall, EPI>();
 }
 
 hipError_t gemm_init() {
   hipError_t e;
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+    g_num_cus = cus;
   if ((e = init_epi<EPI_BIAS_ACT>()) != hipSuccess) return e;
   if ((e = init_epi<EPI_BIAS_GELU_ACT>()) != hipSuccess) return e;
   if ((e = init_epi<EPI_BIAS_RESADD_F32>()) != hipSuccess) return e;
