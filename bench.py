@@ -25,7 +25,15 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see
 # profiles/), keyed by (workload, kernel label); None where not measured.
-MEASURED_TRAFFIC = {}
+# Source: profiles/forward_c1_all_kernels.md (fetched + written, scaled by the copy kernel).
+MEASURED_TRAFFIC = {
+    ("c1", "gemm_fc2"): 425.1e6 + 87.2e6,
+    ("c1", "gemm_fc1"): 152.3e6 + 236.5e6,
+    ("c1", "tiles_attention"): 130.9e6 + 43.6e6,
+    ("c1", "gemm_qkv"): 98.3e6 + 145.7e6,
+    ("c1", "gemm_proj"): 151.1e6 + 87.2e6,
+    ("c1", "layernorm"): 85.7e6 + 42.8e6,
+}
 
 
 def main() -> int:
@@ -37,6 +45,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (developer runs)")
     ap.add_argument("--gemm-tile", type=int, default=-1, help="pin the bf16 GEMM tile (0/1/2), -1 = heuristic")
     ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also launch the library's plain copy kernel on 1 GiB five times (yardstick for rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (tiles are batched on one MI355X); "
@@ -60,6 +70,13 @@ def main() -> int:
     y = torch.empty((cfg.batch, cfg.out_vars, cfg.H * cfg.scale, cfg.W * cfg.scale), dtype=torch.float32, device="cuda")
     K, W = args.steps, args.warmup
 
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            B.reslim_debug_copy(src, dst)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(W):
         model.forward(x, y)
     torch.cuda.synchronize()

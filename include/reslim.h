@@ -197,6 +197,11 @@ int reslim_profile_enable(reslim_ctx *ctx, int32_t max_records);
 int reslim_profile_reset(reslim_ctx *ctx);
 int reslim_profile_read(reslim_ctx *ctx, reslim_profile_record *out, int32_t max_out, int32_t *n_out);
 
+/* Bandwidth yardstick: a plain device-to-device copy kernel (16 bytes per lane) of
+ * `bytes` (a multiple of 16) from src to dst, both dev.  Profilers scale their HBM
+ * byte counters by what they report for this kernel of known size. */
+int reslim_debug_copy(const void *src, void *dst, size_t bytes, void *hip_stream);
+
 /* Tuning hook for benchmarks: pins the tile shape of the bf16 GEMM kernels
  * (-1 = built-in heuristic, 0 = 256x256, 1 = 256x128, 2 = 128x128).  Process-wide. */
 void reslim_debug_set_gemm_tile(int choice);

@@ -28,7 +28,8 @@ _WEIGHT_FIELDS = ["w_pe", "b_pe", "var_emb", "agg_q0", "agg_wq", "agg_bq", "agg_
 EXPORTS = ["tiles_partition", "reslim_create", "reslim_destroy", "reslim_last_error",
            "reslim_tokens_per_sample", "reslim_workspace_bytes", "reslim_embed_fwd", "tiles_attention_fwd",
            "reslim_block_fwd", "reslim_head_fwd", "reslim_forward", "reslim_flop_counts",
-           "reslim_debug_set_gemm_tile", "reslim_profile_enable", "reslim_profile_reset", "reslim_profile_read"]
+           "reslim_debug_set_gemm_tile", "reslim_profile_enable", "reslim_profile_reset", "reslim_profile_read",
+           "reslim_debug_copy"]
 
 
 class ReslimConfigC(C.Structure):
@@ -87,6 +88,7 @@ def load() -> C.CDLL:
     lib.reslim_profile_enable.argtypes = [vp, i32]
     lib.reslim_profile_reset.argtypes = [vp]
     lib.reslim_profile_read.argtypes = [vp, C.POINTER(ProfileRecord), i32, C.POINTER(i32)]
+    lib.reslim_debug_copy.argtypes = [vp, vp, C.c_size_t, vp]
     lib.reslim_debug_set_gemm_tile.argtypes = [i32]
     lib.reslim_debug_set_gemm_tile.restype = None
     for name in EXPORTS:
@@ -155,6 +157,13 @@ def reslim_flop_counts(ctx: int, batch: int):
     g, a, h = C.c_double(), C.c_double(), C.c_double()
     _check(load().reslim_flop_counts(ctx, batch, C.byref(g), C.byref(a), C.byref(h)), ctx)
     return g.value, a.value, h.value
+
+
+def reslim_debug_copy(src, dst, stream=None) -> None:
+    """Plain copy kernel src -> dst (same-size torch CUDA tensors); the profilers' bandwidth yardstick."""
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    _check(load().reslim_debug_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream_ptr(stream)))
 
 
 def reslim_profile_enable(ctx: int, max_records: int) -> None:

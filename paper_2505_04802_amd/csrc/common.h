@@ -121,6 +121,7 @@ hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *ou
                                   hipStream_t st);
 hipError_t attention_init();
 hipError_t elementwise_init();
+hipError_t launch_copy_probe(const void *src, void *dst, size_t bytes, hipStream_t st);
 hipError_t launch_residual_unpatchify(const reslim_ctx *c, const float *x, const void *P, int p_is_act,
                                       float *y, int batch, hipStream_t st);
 

@@ -127,6 +127,21 @@ hipError_t launch_gather_rows(const float *z, const int32_t *gather, float *X, i
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ plain copy (bandwidth yardstick)
+__global__ __launch_bounds__(256) void copy_probe_kernel(const float4 *__restrict__ src, float4 *__restrict__ dst, int64_t n16) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (i < n16) dst[i] = src[i];
+}
+
+hipError_t launch_copy_probe(const void *src, void *dst, size_t bytes, hipStream_t st) {
+  const int64_t n16 = static_cast<int64_t>(bytes / 16);
+  const int64_t blocks = (n16 + 255) / 256;
+  if (bytes % 16 || blocks < 1 || blocks > INT32_MAX) return hipErrorInvalidValue;
+  copy_probe_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st>>>(static_cast<const float4 *>(src),
+                                                                            static_cast<float4 *>(dst), n16);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ embed + aggregate
 struct EmbedArgs {
   const float *x;

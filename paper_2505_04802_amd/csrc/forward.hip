@@ -158,6 +158,11 @@ extern "C" int reslim_profile_read(reslim_ctx *c, reslim_profile_record *out, in
   return RESLIM_OK;
 }
 
+extern "C" int reslim_debug_copy(const void *src, void *dst, size_t bytes, void *hip_stream) {
+  if (!src || !dst || bytes == 0 || bytes % 16) return RESLIM_EINVAL;
+  return launch_copy_probe(src, dst, bytes, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? RESLIM_OK : RESLIM_EHIP;
+}
+
 extern "C" int reslim_tokens_per_sample(const reslim_ctx *ctx, int64_t *n_h_out) {
   if (!ctx || !n_h_out) return RESLIM_EINVAL;
   *n_h_out = ctx->n_h;
