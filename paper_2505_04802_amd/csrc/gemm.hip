@@ -77,9 +77,64 @@ __device__ __forceinline__ void epilogue_block(const GemmArgs &g, const f32x16 &
   }
 }
 
+// Epilogues that read or write fp32 rows (residual read-modify-write, table add)
+// run with the MFMA operand roles swapped: the accumulator block is then C^T, a
+// lane holds one output row (lane % 32) and four consecutive columns per register
+// quad, and the update is a 16-byte load/store per lane (measured 1.85x faster than
+// 4-byte accesses for the read-modify-write).
+template <int EPI>
+__device__ __host__ constexpr bool epi_swapped() {
+  return EPI == EPI_BIAS_RESADD_F32 || EPI == EPI_BIAS_TAB_F32;
+}
+
+template <int EPI, int MI, int NI>
+__device__ __forceinline__ void epilogue_wave_swapped(const GemmArgs &g, const f32x16 (&acc)[MI][NI], int m_base,
+                                                      int n_base, int l32, int hi) {
+  float *out = static_cast<float *>(g.out);
+#pragma unroll
+  for (int i = 0; i < MI; ++i) {
+    const int m = m_base + i * 32 + l32;
+    if (m >= g.M) continue;
+    float *orow = out + static_cast<size_t>(m) * g.ldo;
+    const float *trow = (EPI == EPI_BIAS_TAB_F32) ? g.tab + static_cast<size_t>(m % g.tab_rows) * g.N : nullptr;
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = n_base + j * 32 + 8 * q + 4 * hi;
+        if (n + 3 < g.N) {
+          const float4 add = (EPI == EPI_BIAS_TAB_F32) ? *reinterpret_cast<const float4 *>(trow + n)
+                                                       : *reinterpret_cast<const float4 *>(g.bias + n);
+          float4 v = make_float4(acc[i][j][4 * q] + add.x, acc[i][j][4 * q + 1] + add.y, acc[i][j][4 * q + 2] + add.z,
+                                 acc[i][j][4 * q + 3] + add.w);
+          float4 *p = reinterpret_cast<float4 *>(orow + n);
+          if constexpr (EPI == EPI_BIAS_RESADD_F32) {
+            const float4 x = *p;
+            v.x += x.x; v.y += x.y; v.z += x.z; v.w += x.w;
+          }
+          *p = v;
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (n + e < g.N) {
+              const float add = (EPI == EPI_BIAS_TAB_F32) ? trow[n + e] : g.bias[n + e];
+              float v = acc[i][j][4 * q + e] + add;
+              if constexpr (EPI == EPI_BIAS_RESADD_F32) v += orow[n + e];
+              orow[n + e] = v;
+            }
+        }
+      }
+    }
+  }
+}
+
 template <int EPI, int MI, int NI>
 __device__ __forceinline__ void epilogue_wave(const GemmArgs &g, const f32x16 (&acc)[MI][NI], int m_base, int n_base,
                                               int l32, int hi) {
+  if constexpr (epi_swapped<EPI>()) {
+    epilogue_wave_swapped<EPI, MI, NI>(g, acc, m_base, n_base, l32, hi);
+    return;
+  }
   const bool full = m_base + MI * 32 <= g.M;     // wave-uniform
 #pragma unroll
   for (int j = 0; j < NI; ++j) {
@@ -218,7 +273,8 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_bf16_kernel(GemmArgs 
       for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NI; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = epi_swapped<EPI>() ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0)
+                                         : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
     if constexpr (NBUF == 2) {
       if (kt + 1 < nk) store_lds(buf ^ 1);
