@@ -206,6 +206,11 @@ int reslim_debug_copy(const void *src, void *dst, size_t bytes, void *hip_stream
  * (-1 = built-in heuristic, 0 = 256x256, 1 = 256x128, 2 = 128x128).  Process-wide. */
 void reslim_debug_set_gemm_tile(int choice);
 
+/* Tuning hook: which bf16 tile-attention kernel runs (0 = direct-to-LDS loads with
+ * transposing LDS reads, the default; 1 = register-staged loads with V transposed on
+ * the LDS store).  Process-wide. */
+void reslim_debug_set_attention_variant(int variant);
+
 #ifdef __cplusplus
 }
 #endif

@@ -29,7 +29,7 @@ EXPORTS = ["tiles_partition", "reslim_create", "reslim_destroy", "reslim_last_er
            "reslim_tokens_per_sample", "reslim_workspace_bytes", "reslim_embed_fwd", "tiles_attention_fwd",
            "reslim_block_fwd", "reslim_head_fwd", "reslim_forward", "reslim_flop_counts",
            "reslim_debug_set_gemm_tile", "reslim_profile_enable", "reslim_profile_reset", "reslim_profile_read",
-           "reslim_debug_copy"]
+           "reslim_debug_copy", "reslim_debug_set_attention_variant"]
 
 
 class ReslimConfigC(C.Structure):
@@ -91,8 +91,11 @@ def load() -> C.CDLL:
     lib.reslim_debug_copy.argtypes = [vp, vp, C.c_size_t, vp]
     lib.reslim_debug_set_gemm_tile.argtypes = [i32]
     lib.reslim_debug_set_gemm_tile.restype = None
+    lib.reslim_debug_set_attention_variant.argtypes = [i32]
+    lib.reslim_debug_set_attention_variant.restype = None
     for name in EXPORTS:
-        if name not in ("reslim_destroy", "reslim_last_error", "reslim_debug_set_gemm_tile"):
+        if name not in ("reslim_destroy", "reslim_last_error", "reslim_debug_set_gemm_tile",
+                        "reslim_debug_set_attention_variant"):
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -116,6 +119,10 @@ def tiles_partition(Hp: int, Wp: int, Ty: int, Tx: int, halo: int):
     _check(lib.tiles_partition(Hp, Wp, Ty, Tx, halo, tiles, gather.ctypes.data, isrc.ctypes.data, None))
     names = ("y0", "y1", "x0", "x1", "Y0", "Y1", "X0", "X1", "tok_off", "n_tok")
     return [{n: int(getattr(t, n)) for n in names} for t in tiles], gather, isrc, int(n_h.value)
+
+
+def reslim_debug_set_attention_variant(variant: int) -> None:
+    load().reslim_debug_set_attention_variant(variant)
 
 
 def reslim_debug_set_gemm_tile(choice: int) -> None:

@@ -247,6 +247,215 @@ __global__ __launch_bounds__(256, 2) void tiles_attention_bf16_kernel(AttnArgs a
   }
 }
 
+// ------------------------------------------------------------------ bf16 kernel, second form
+// Same arithmetic and register layout as above, different data movement: K and V
+// blocks go from global memory straight into LDS (global_load_lds_dwordx4), two
+// stages deep with one barrier per block, both ROW-MAJOR with the 16-byte chunks of
+// a row XOR-swizzled (a direct load cannot pad rows).  The V^T operand of
+// O^T = V^T P^T is read with ds_read_b64_tr_b16: within 16 lanes, lane i receives
+// element i of each of the four 16-element rows the lanes 4r..4r+3 point at, i.e.
+// four consecutive keys of feature column i -- the transpose happens in the LDS
+// read, so no staging registers, no packing arithmetic and no transposed stores.
+// Keys past the end of a ragged tile are clamped to the last valid row (finite
+// data; their probabilities are exactly zero).
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+__device__ __forceinline__ void attn_dl_load16(const bf16_t *gsrc, unsigned char *lds_wave_base) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc,
+                                   (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+}
+
+template <int DH, int BKV>
+__global__ __launch_bounds__(256, 2) void tiles_attention_bf16_v2_kernel(AttnArgs a) {
+  constexpr int BQ = 128;
+  constexpr int ROWB = DH * 2;            // bytes per K/V row in LDS
+  constexpr int CPR = DH / 8;             // 16-byte chunks per row (8 or 16)
+  constexpr int RPB = 64 / CPR;           // rows per 1 KiB load block
+  constexpr int TILE_B = BKV * ROWB;
+  constexpr int STAGE = 2 * TILE_B;       // K block then V block
+  constexpr int LPW = TILE_B / 1024 / 4;  // direct loads per wave and operand
+  constexpr int NKT = BKV / 32, NKS = DH / 16, NDT = DH / 32;
+  constexpr int OP = DH + 8, DC = DH / 8;
+  static_assert(TILE_B % 4096 == 0 && BQ * OP * 2 <= 2 * STAGE && 2 * STAGE <= 65536, "LDS plan");
+  __shared__ __align__(1024) unsigned char smem[2 * STAGE];
+  bf16_t *O_lds = reinterpret_cast<bf16_t *>(smem);
+
+  const int logical = xcd_remap_attn(blockIdx.x, a.total);
+  const int qb = logical % a.QB;
+  int rest = logical / a.QB;
+  const int head = rest % a.heads;
+  rest /= a.heads;
+  const int tile = rest % a.T;
+  const int b = rest / a.T;
+  const int n_t = a.tiles[tile].n_tok;
+  const int64_t tok_off = a.tiles[tile].tok_off;
+  const int q0 = qb * BQ;
+  if (q0 >= n_t) return;     // uniform for the whole work-group
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int l32 = lane & 31, hi = lane >> 5;
+  const int ld = 3 * a.D;
+  const bf16_t *base = static_cast<const bf16_t *>(a.qkv) +
+                       (static_cast<size_t>(b) * a.n_h + tok_off) * ld + head * DH;
+  const bf16_t *Kg = base + a.D, *Vg = base + 2 * a.D;
+  auto swz = [](int r) { return CPR == 8 ? ((r & 7) ^ ((r >> 3) & 1)) : (r & 15); };
+
+  const bool active = (q0 + wave * 32) < n_t;   // wave-uniform
+  bf16x8 qf[NKS];
+  {
+    const int qrow = min(q0 + wave * 32 + l32, n_t - 1);
+    const bf16_t *qp = base + static_cast<size_t>(qrow) * ld + hi * 8;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
+  }
+
+  // load side
+  int ld_row[LPW], ld_col[LPW];
+#pragma unroll
+  for (int i = 0; i < LPW; ++i) {
+    ld_row[i] = (wave + 4 * i) * RPB + lane / CPR;
+    ld_col[i] = ((lane % CPR) ^ swz(ld_row[i])) * 8;
+  }
+  auto issue = [&](int kv0, int buf) {
+    unsigned char *sk = smem + buf * STAGE;
+#pragma unroll
+    for (int i = 0; i < LPW; ++i) {
+      const size_t key = static_cast<size_t>(min(kv0 + ld_row[i], n_t - 1));
+      attn_dl_load16(Kg + key * ld + ld_col[i], sk + (wave + 4 * i) * 1024);
+      attn_dl_load16(Vg + key * ld + ld_col[i], sk + TILE_B + (wave + 4 * i) * 1024);
+    }
+  };
+
+  // K fragment: A-operand row l32 carries key key_perm(l32) of its 32-key group
+  const int kr = key_perm(l32);
+  const int k_row = kr * ROWB, k_swz = swz(kr);
+  // V^T fragment through the transposing read: this lane points at key row
+  // 8*hi + 4*e + (lane%16)/4 of a 16-key step and at the 4 features
+  // 32*dt + 16*((lane/16)&1) + 4*(lane%4) .. +3
+  const int L16 = lane & 15;
+  int v_addr[2][NDT];
+#pragma unroll
+  for (int e = 0; e < 2; ++e) {
+    const int vr = 8 * hi + 4 * e + (L16 >> 2);
+#pragma unroll
+    for (int d = 0; d < NDT; ++d) {
+      const int o = 32 * d + 16 * ((lane >> 4) & 1) + 4 * (L16 & 3);
+      v_addr[e][d] = TILE_B + vr * ROWB + (((o >> 3) ^ swz(vr)) << 4) + ((o >> 2) & 1) * 8;
+    }
+  }
+
+  f32x16 o[NDT];
+#pragma unroll
+  for (int d = 0; d < NDT; ++d)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float c = a.scale_log2;
+  const int nkb = (n_t + BKV - 1) / BKV;
+
+  issue(0, 0);
+  for (int kb = 0; kb < nkb; ++kb) {
+    const int kv0 = kb * BKV;
+    __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's part of block kb has landed
+    __syncthreads();                        // ... and everybody's; the other buffer is free
+    if (kb + 1 < nkb) issue(kv0 + BKV, (kb + 1) & 1);
+    if (!active) continue;
+    const unsigned char *st = smem + (kb & 1) * STAGE;
+
+    f32x16 s[NKT];
+#pragma unroll
+    for (int kt = 0; kt < NKT; ++kt) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) {
+        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(st + kt * 32 * ROWB + k_row + (((2 * ks + hi) ^ k_swz) << 4));
+        s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kt], 0, 0, 0);
+      }
+    }
+    if (kv0 + BKV > n_t) {
+#pragma unroll
+      for (int kt = 0; kt < NKT; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = kv0 + kt * 32 + 16 * (r / 8) + 8 * hi + (r % 8);
+          if (key >= n_t) s[kt][r] = -INFINITY;
+        }
+    }
+    float mx = s[0][0];
+#pragma unroll
+    for (int kt = 0; kt < NKT; ++kt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+    const float mc = m_new * c;
+    m_run = m_new;
+    float psum = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < NKT; ++kt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = __builtin_amdgcn_exp2f(fmaf(s[kt][r], c, -mc));
+        s[kt][r] = p;
+        psum += p;
+      }
+    l_run = fmaf(l_run, alpha, psum);
+#pragma unroll
+    for (int d = 0; d < NDT; ++d)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+
+#pragma unroll
+    for (int kt = 0; kt < NKT; ++kt) {
+#pragma unroll
+      for (int h2 = 0; h2 < 2; ++h2) {
+        bf16x8 pf;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pf[e] = static_cast<__bf16>(s[kt][8 * h2 + e]);
+#pragma unroll
+        for (int d = 0; d < NDT; ++d) {
+          const unsigned char *vp = st + (kt * 32 + h2 * 16) * ROWB;
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (s16x4 __attribute__((address_space(3))) *)(vp + v_addr[0][d]));
+          const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (s16x4 __attribute__((address_space(3))) *)(vp + v_addr[1][d]));
+          typedef __attribute__((ext_vector_type(8))) short s16x8;
+          const s16x8 both = __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+          const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
+          o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[d], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  const float inv = active ? 1.0f / l_tot : 0.f;
+  __syncthreads();     // the staging area is reused for the output tile
+  if (active) {
+#pragma unroll
+    for (int d = 0; d < NDT; ++d)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        bf16x4 tmp;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) tmp[e] = static_cast<__bf16>(o[d][4 * r4 + e] * inv);
+        *reinterpret_cast<u32x2 *>(O_lds + (wave * 32 + l32) * OP + d * 32 + r4 * 8 + hi * 4) =
+            __builtin_bit_cast(u32x2, tmp);
+      }
+  }
+  __syncthreads();
+  bf16_t *outp = static_cast<bf16_t *>(a.out) + (static_cast<size_t>(b) * a.n_h + tok_off) * a.D + head * DH;
+#pragma unroll
+  for (int i = 0; i < BQ * DC / 256; ++i) {
+    const int ch = t + i * 256, row = ch / DC, kc = ch % DC;
+    if (q0 + row < n_t)
+      *reinterpret_cast<u32x4 *>(outp + static_cast<size_t>(q0 + row) * a.D + kc * 8) =
+          *reinterpret_cast<const u32x4 *>(O_lds + row * OP + kc * 8);
+  }
+}
+
 // ------------------------------------------------------------------ fp32 debug path
 // One work-group per (sample, tile-major token, head): scores for all keys of the
 // tile in LDS, two block reductions, then one thread per feature accumulates P V.
@@ -306,6 +515,8 @@ __global__ __launch_bounds__(128) void tiles_attention_f32_kernel(AttnArgs a, in
   }
 }
 
+static int g_attn_variant = 0;   // 0: direct-to-LDS + transposing reads, 1: register-staged with V transposed on store
+
 hipError_t attention_init() { return hipSuccess; }
 
 hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *out, int batch, hipStream_t st) {
@@ -323,12 +534,15 @@ hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *ou
     const int64_t total = static_cast<int64_t>(batch) * c->T * a.heads * a.QB;
     if (total > INT32_MAX) return hipErrorInvalidValue;
     a.total = static_cast<int>(total);
-    if (c->dh == 64)
-      tiles_attention_bf16_kernel<64, 128><<<dim3(a.total), dim3(256), 0, st>>>(a);
-    else if (c->dh == 128)
-      tiles_attention_bf16_kernel<128, 64><<<dim3(a.total), dim3(256), 0, st>>>(a);
-    else
+    if (c->dh == 64) {
+      if (g_attn_variant == 1) tiles_attention_bf16_kernel<64, 128><<<dim3(a.total), dim3(256), 0, st>>>(a);
+      else tiles_attention_bf16_v2_kernel<64, 128><<<dim3(a.total), dim3(256), 0, st>>>(a);
+    } else if (c->dh == 128) {
+      if (g_attn_variant == 1) tiles_attention_bf16_kernel<128, 64><<<dim3(a.total), dim3(256), 0, st>>>(a);
+      else tiles_attention_bf16_v2_kernel<128, 64><<<dim3(a.total), dim3(256), 0, st>>>(a);
+    } else {
       return hipErrorInvalidValue;
+    }
     return hipGetLastError();
   }
   a.QB = c->max_n_tok;
@@ -341,3 +555,6 @@ hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *ou
 }
 
 }  // namespace reslim
+
+// tuning hook: 0 = direct-to-LDS kernel (default), 1 = register-staged kernel
+extern "C" void reslim_debug_set_attention_variant(int v) { reslim::g_attn_variant = v; }
