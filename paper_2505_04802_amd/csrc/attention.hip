@@ -265,7 +265,10 @@ __device__ __forceinline__ void attn_dl_load16(const bf16_t *gsrc, unsigned char
                                    (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
 }
 
-template <int DH, int BKV>
+// QS: the caller has already multiplied q by log2(e)/sqrt(dh) (the fused QKV
+// epilogue does, before its single rounding to bf16), so the MFMA output is the
+// base-2 logit itself.
+template <int DH, int BKV, bool QS>
 __global__ __launch_bounds__(256, 2) void tiles_attention_bf16_v2_kernel(AttnArgs a) {
   constexpr int BQ = 128;
   constexpr int ROWB = DH * 2;            // bytes per K/V row in LDS
@@ -344,13 +347,29 @@ __global__ __launch_bounds__(256, 2) void tiles_attention_bf16_v2_kernel(AttnArg
     }
   }
 
-  f32x16 o[NDT];
+  // Softmax bookkeeping with few vector instructions per score (at dh = 64 the fp32
+  // vector pipe, not the matrix pipe, bounds this kernel):
+  //  * every S^T accumulator chain starts from `minit` = -(reference logit of this
+  //    lane's query), so the MFMA already delivers logit - reference;
+  //  * the reference is only moved (and O, L rescaled) when some query of the wave
+  //    meets a logit more than TAU above it -- rare after the first block -- so the
+  //    common block costs one max3 per three scores, one exp2 and half a convert
+  //    per score;
+  //  * the row sums L ride on the matrix pipe: a constant all-ones A operand turns
+  //    O^T = V^T P^T into one more 32-row block whose rows all equal sum_k P.
+  f32x16 o[NDT], lsum, minit;
 #pragma unroll
   for (int d = 0; d < NDT; ++d)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
-  const float c = a.scale_log2;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) { lsum[r] = 0.f; minit[r] = 0.f; }
+  bf16x8 ones;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) ones[e] = static_cast<__bf16>(1.0f);
+  const float c = QS ? 1.0f : a.scale_log2;     // MFMA output -> base-2 logit
+  const float TAU = 10.0f / c;                    // in units of the MFMA output
+  bool have_ref = false;                          // wave-uniform
   const int nkb = (n_t + BKV - 1) / BKV;
 
   issue(0, 0);
@@ -366,14 +385,12 @@ __global__ __launch_bounds__(256, 2) void tiles_attention_bf16_v2_kernel(AttnArg
 #pragma unroll
     for (int kt = 0; kt < NKT; ++kt) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
-#pragma unroll
       for (int ks = 0; ks < NKS; ++ks) {
         const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(st + kt * 32 * ROWB + k_row + (((2 * ks + hi) ^ k_swz) << 4));
-        s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kt], 0, 0, 0);
+        s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? minit : s[kt], 0, 0, 0);
       }
     }
-    if (kv0 + BKV > n_t) {
+    if (kv0 + BKV > n_t) {           // ragged last block: keys past the tile end get -inf
 #pragma unroll
       for (int kt = 0; kt < NKT; ++kt)
 #pragma unroll
@@ -387,25 +404,29 @@ __global__ __launch_bounds__(256, 2) void tiles_attention_bf16_v2_kernel(AttnArg
     for (int kt = 0; kt < NKT; ++kt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-    const float mc = m_new * c;
-    m_run = m_new;
-    float psum = 0.f;
+    mx = fmaxf(mx, __shfl_xor(mx, 32));     // finite: every block holds a valid key
+    if (!have_ref || __any(mx > TAU)) {
+      // move this lane's reference up by d (first block: to the block maximum)
+      const float d = have_ref ? fmaxf(mx, 0.f) : mx;
+      const float alpha = have_ref ? __builtin_amdgcn_exp2f(-d * c) : 0.f;
+#pragma unroll
+      for (int kt = 0; kt < NKT; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[kt][r] -= d;
+#pragma unroll
+      for (int dd = 0; dd < NDT; ++dd)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[dd][r] *= alpha;
+      const float ninit = minit[0] - d;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { lsum[r] *= alpha; minit[r] = ninit; }
+      have_ref = true;
+    }
 #pragma unroll
     for (int kt = 0; kt < NKT; ++kt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(s[kt][r], c, -mc));
-        s[kt][r] = p;
-        psum += p;
-      }
-    l_run = fmaf(l_run, alpha, psum);
-#pragma unroll
-    for (int d = 0; d < NDT; ++d)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+      for (int r = 0; r < 16; ++r)
+        s[kt][r] = __builtin_amdgcn_exp2f(QS ? s[kt][r] : s[kt][r] * c);
 
 #pragma unroll
     for (int kt = 0; kt < NKT; ++kt) {
@@ -414,6 +435,7 @@ __global__ __launch_bounds__(256, 2) void tiles_attention_bf16_v2_kernel(AttnArg
         bf16x8 pf;
 #pragma unroll
         for (int e = 0; e < 8; ++e) pf[e] = static_cast<__bf16>(s[kt][8 * h2 + e]);
+        lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf, lsum, 0, 0, 0);
 #pragma unroll
         for (int d = 0; d < NDT; ++d) {
           const unsigned char *vp = st + (kt * 32 + h2 * 16) * ROWB;
@@ -430,8 +452,8 @@ __global__ __launch_bounds__(256, 2) void tiles_attention_bf16_v2_kernel(AttnArg
     }
   }
 
-  const float l_tot = l_run + __shfl_xor(l_run, 32);
-  const float inv = active ? 1.0f / l_tot : 0.f;
+  // every row of the all-ones block carries the full sum over keys
+  const float inv = active ? 1.0f / lsum[0] : 0.f;
   __syncthreads();     // the staging area is reused for the output tile
   if (active) {
 #pragma unroll
@@ -518,8 +540,10 @@ __global__ __launch_bounds__(128) void tiles_attention_f32_kernel(AttnArgs a, in
 static int g_attn_variant = 0;   // 0: direct-to-LDS + transposing reads, 1: register-staged with V transposed on store
 
 hipError_t attention_init() { return hipSuccess; }
+bool attention_accepts_prescaled_q() { return g_attn_variant == 0; }
 
-hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *out, int batch, hipStream_t st) {
+hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *out, int batch, bool q_prescaled,
+                                  hipStream_t st) {
   AttnArgs a;
   a.qkv = qkv;
   a.out = out;
@@ -530,16 +554,19 @@ hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *ou
   a.n_h = c->n_h;
   a.scale_log2 = 1.4426950408889634f / sqrtf(static_cast<float>(c->dh));
   if (c->cfg.dtype == RESLIM_BF16) {
+    if (q_prescaled && g_attn_variant == 1) return hipErrorInvalidValue;   // the older kernel scales q itself
     a.QB = (c->max_n_tok + 127) / 128;
     const int64_t total = static_cast<int64_t>(batch) * c->T * a.heads * a.QB;
     if (total > INT32_MAX) return hipErrorInvalidValue;
     a.total = static_cast<int>(total);
     if (c->dh == 64) {
       if (g_attn_variant == 1) tiles_attention_bf16_kernel<64, 128><<<dim3(a.total), dim3(256), 0, st>>>(a);
-      else tiles_attention_bf16_v2_kernel<64, 128><<<dim3(a.total), dim3(256), 0, st>>>(a);
+      else if (q_prescaled) tiles_attention_bf16_v2_kernel<64, 128, true><<<dim3(a.total), dim3(256), 0, st>>>(a);
+      else tiles_attention_bf16_v2_kernel<64, 128, false><<<dim3(a.total), dim3(256), 0, st>>>(a);
     } else if (c->dh == 128) {
       if (g_attn_variant == 1) tiles_attention_bf16_kernel<128, 64><<<dim3(a.total), dim3(256), 0, st>>>(a);
-      else tiles_attention_bf16_v2_kernel<128, 64><<<dim3(a.total), dim3(256), 0, st>>>(a);
+      else if (q_prescaled) tiles_attention_bf16_v2_kernel<128, 64, true><<<dim3(a.total), dim3(256), 0, st>>>(a);
+      else tiles_attention_bf16_v2_kernel<128, 64, false><<<dim3(a.total), dim3(256), 0, st>>>(a);
     } else {
       return hipErrorInvalidValue;
     }

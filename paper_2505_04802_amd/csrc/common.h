@@ -103,12 +103,13 @@ enum Epilogue {
   EPI_BIAS_GELU_ACT = 1,  // out(act)  = gelu(acc + bias)
   EPI_BIAS_RESADD_F32 = 2,// out(f32) += acc + bias
   EPI_BIAS_TAB_F32 = 3,   // out(f32)  = acc + tab[m % tab_rows, n]   (bias folded in tab)
-  EPI_BIAS_F32 = 4        // out(f32)  = acc + bias
+  EPI_BIAS_F32 = 4,       // out(f32)  = acc + bias
+  EPI_BIAS_QSCALE_ACT = 5 // out(act)  = (acc + bias) * (n < qcols ? qscale : 1)   (QKV with pre-scaled q)
 };
 // C[M, N] (+)= A[M, K] * W[N, K]^T ; A, W act type (bf16 -> MFMA path, float -> fp32 path)
 hipError_t launch_gemm(int dtype, Epilogue epi, const void *A, const void *W, const float *bias,
                        void *out, int ldo, const float *tab, int tab_rows, int M, int N, int K,
-                       hipStream_t st);
+                       hipStream_t st, float qscale = 1.0f, int qcols = 0);
 hipError_t gemm_init();
 
 hipError_t launch_layernorm(int dtype, const float *x, const int32_t *row_src, int rows_per_sample_out,
@@ -117,8 +118,10 @@ hipError_t launch_layernorm(int dtype, const float *x, const int32_t *row_src, i
 hipError_t launch_gather_rows(const float *z, const int32_t *gather, float *X, int batch, int64_t n_h,
                               int N, int D, hipStream_t st);
 hipError_t launch_embed_agg(const reslim_ctx *c, const float *x, void *o, int batch, hipStream_t st);
-hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *out, int batch,
+// q_prescaled: q already carries the factor log2(e)/sqrt(dh) (bf16 path only)
+hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *out, int batch, bool q_prescaled,
                                   hipStream_t st);
+bool attention_accepts_prescaled_q();
 hipError_t attention_init();
 hipError_t elementwise_init();
 hipError_t launch_copy_probe(const void *src, void *dst, size_t bytes, hipStream_t st);

@@ -1,6 +1,7 @@
 // Entry points that chain the kernels: embed, block, head, forward
 // (ORBIT-2 Sec. 4.1 data flow, applied tile-wise as in Sec. 4.2).
 #include <algorithm>
+#include <cmath>
 
 #include "common.h"
 
@@ -87,9 +88,15 @@ static int block_impl(reslim_ctx *c, const char *fn, int layer, float *X, int ba
   double pairs = 0;
   for (const tile_desc &t : c->tiles) pairs += static_cast<double>(t.n_tok) * t.n_tok;
   RESLIM_LAUNCH("layernorm", 0, dM * dD * (4.0 + es), launch_layernorm(dt, X, nullptr, 0, 0, lw.ln1_g, lw.ln1_b, w.A, M, D, st));
+  // bf16 path: the QKV epilogue multiplies q by log2(e)/sqrt(dh) before its one
+  // rounding to bf16, and the attention kernel then exponentiates in base 2 directly
+  const bool qs = dt == RESLIM_BF16 && attention_accepts_prescaled_q();
+  const float qscale = 1.4426950408889634f / sqrtf(static_cast<float>(c->dh));
   RESLIM_LAUNCH("gemm_qkv", 6.0 * dM * dD * dD, dM * dD * es + 3.0 * dD * dD * es + 3.0 * dM * dD * es,
-                launch_gemm(dt, EPI_BIAS_ACT, w.A, lw.w_qkv, lw.b_qkv, w.big, 3 * D, nullptr, 0, M, 3 * D, D, st));
-  RESLIM_LAUNCH("tiles_attention", 4.0 * pairs * dD * batch, 4.0 * dM * dD * es, launch_tiles_attention(c, w.big, w.A, batch, st));
+                launch_gemm(dt, qs ? EPI_BIAS_QSCALE_ACT : EPI_BIAS_ACT, w.A, lw.w_qkv, lw.b_qkv, w.big, 3 * D, nullptr, 0, M,
+                            3 * D, D, st, qscale, D));
+  RESLIM_LAUNCH("tiles_attention", 4.0 * pairs * dD * batch, 4.0 * dM * dD * es,
+                launch_tiles_attention(c, w.big, w.A, batch, qs, st));
   RESLIM_LAUNCH("gemm_proj", 2.0 * dM * dD * dD, dM * dD * es + dD * dD * es + 8.0 * dM * dD,
                 launch_gemm(dt, EPI_BIAS_RESADD_F32, w.A, lw.w_proj, lw.b_proj, X, D, nullptr, 0, M, D, D, st));
   RESLIM_LAUNCH("layernorm", 0, dM * dD * (4.0 + es), launch_layernorm(dt, X, nullptr, 0, 0, lw.ln2_g, lw.ln2_b, w.A, M, D, st));
@@ -195,7 +202,7 @@ extern "C" int tiles_attention_fwd(reslim_ctx *c, const void *qkv, void *out, in
   if (!qkv || !out) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": null buffer");
   int rc = check_common(c, fn, batch, nullptr, 0, false);
   if (rc != RESLIM_OK) return rc;
-  RESLIM_TRY("launch", launch_tiles_attention(c, qkv, out, batch, static_cast<hipStream_t>(hip_stream)));
+  RESLIM_TRY("launch", launch_tiles_attention(c, qkv, out, batch, false, static_cast<hipStream_t>(hip_stream)));
   return RESLIM_OK;
 }
 

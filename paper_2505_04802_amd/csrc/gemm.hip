@@ -28,6 +28,8 @@ struct GemmArgs {
   int ldo, tab_rows;
   int M, N, K;
   int grid_m, grid_n;
+  float qscale;   // EPI_BIAS_QSCALE_ACT: factor applied to output columns n < qcols
+  int qcols;
 };
 
 __device__ __forceinline__ float gelu_erf(float x) {
@@ -64,6 +66,8 @@ __device__ __forceinline__ void epilogue_block(const GemmArgs &g, const f32x16 &
     const float v = a[r];
     if constexpr (EPI == EPI_BIAS_ACT) {
       static_cast<bf16_t *>(g.out)[o] = f32_to_bf16(v + bias);
+    } else if constexpr (EPI == EPI_BIAS_QSCALE_ACT) {
+      static_cast<bf16_t *>(g.out)[o] = f32_to_bf16((v + bias) * (n < g.qcols ? g.qscale : 1.0f));
     } else if constexpr (EPI == EPI_BIAS_GELU_ACT) {
       static_cast<bf16_t *>(g.out)[o] = f32_to_bf16(gelu_erf_fast(v + bias));
     } else if constexpr (EPI == EPI_BIAS_RESADD_F32) {
@@ -262,19 +266,37 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_bf16_kernel(GemmArgs 
     if (kt + 1 < nk) load_global((kt + 1) * BK);
     const bf16_t *as = As + buf * BM * PITCH + a_frag;
     const bf16_t *bs = Bs + buf * BN * PITCH + b_frag;
+    // register double-buffered fragments: reads of step kk+1 go out right after the
+    // first MFMA of step kk
+    bf16x8 af[2][MI], bfr[2][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i) af[0][i] = *reinterpret_cast<const bf16x8 *>(as + i * 32 * PITCH);
+#pragma unroll
+    for (int j = 0; j < NI; ++j) bfr[0][j] = *reinterpret_cast<const bf16x8 *>(bs + j * 32 * PITCH);
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 af[MI], bfr[NI];
-#pragma unroll
-      for (int i = 0; i < MI; ++i) af[i] = *reinterpret_cast<const bf16x8 *>(as + i * 32 * PITCH + kk * 16);
-#pragma unroll
-      for (int j = 0; j < NI; ++j) bfr[j] = *reinterpret_cast<const bf16x8 *>(bs + j * 32 * PITCH + kk * 16);
+      const int cur = kk & 1, nxt = cur ^ 1;
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < NI; ++j)
-          acc[i][j] = epi_swapped<EPI>() ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0)
-                                         : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < NI; ++j) {
+          acc[i][j] = epi_swapped<EPI>()
+                          ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][j], af[cur][i], acc[i][j], 0, 0, 0)
+                          : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
+          if (i == 0 && j == 0) {
+            __builtin_amdgcn_sched_barrier(0);
+            if (kk + 1 < BK / 16) {
+#pragma unroll
+              for (int i2 = 0; i2 < MI; ++i2)
+                af[nxt][i2] = *reinterpret_cast<const bf16x8 *>(as + i2 * 32 * PITCH + (kk + 1) * 16);
+#pragma unroll
+              for (int j2 = 0; j2 < NI; ++j2)
+                bfr[nxt][j2] = *reinterpret_cast<const bf16x8 *>(bs + j2 * 32 * PITCH + (kk + 1) * 16);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+      __builtin_amdgcn_sched_barrier(0);
     }
     if constexpr (NBUF == 2) {
       if (kt + 1 < nk) store_lds(buf ^ 1);
@@ -292,7 +314,9 @@ template <int EPI>
 __device__ __forceinline__ void epilogue_store_f32(const GemmArgs &g, int m, int n, float v) {
   const size_t o = static_cast<size_t>(m) * g.ldo + n;
   float *out = static_cast<float *>(g.out);
-  if constexpr (EPI == EPI_BIAS_ACT || EPI == EPI_BIAS_F32) {
+  if constexpr (EPI == EPI_BIAS_QSCALE_ACT) {
+    out[o] = (v + g.bias[n]) * (n < g.qcols ? g.qscale : 1.0f);
+  } else if constexpr (EPI == EPI_BIAS_ACT || EPI == EPI_BIAS_F32) {
     out[o] = v + g.bias[n];
   } else if constexpr (EPI == EPI_BIAS_GELU_ACT) {
     out[o] = gelu_erf(v + g.bias[n]);
@@ -387,7 +411,7 @@ static hipError_t launch_bf16(GemmArgs g, hipStream_t st) {
   // epilogue (residual read-modify-write, GELU) behind other groups' MFMAs.
   const long tiles_big = static_cast<long>((g.M + 255) / 256) * ((g.N + 255) / 256);
   int choice = 2;
-  if (tiles_big >= 2L * g_num_cus && (g.K >= 1024 || EPI == EPI_BIAS_ACT)) choice = 3;
+  if (tiles_big >= 2L * g_num_cus && (g.K >= 1024 || EPI == EPI_BIAS_ACT || EPI == EPI_BIAS_QSCALE_ACT)) choice = 3;
   if (g_gemm_tile_override >= 0) choice = g_gemm_tile_override;
   switch (choice) {
     case 0: return launch_bf16_tc<TileBig, EPI>(g, st);
@@ -424,17 +448,19 @@ hipError_t gemm_init() {
   if ((e = init_epi<EPI_BIAS_GELU_ACT>()) != hipSuccess) return e;
   if ((e = init_epi<EPI_BIAS_RESADD_F32>()) != hipSuccess) return e;
   if ((e = init_epi<EPI_BIAS_TAB_F32>()) != hipSuccess) return e;
+  if ((e = init_epi<EPI_BIAS_QSCALE_ACT>()) != hipSuccess) return e;
   return init_epi<EPI_BIAS_F32>();
 }
 
 hipError_t launch_gemm(int dtype, Epilogue epi, const void *A, const void *W, const float *bias,
                        void *out, int ldo, const float *tab, int tab_rows, int M, int N, int K,
-                       hipStream_t st) {
+                       hipStream_t st, float qscale, int qcols) {
   if (M <= 0 || N <= 0 || K <= 0) return hipErrorInvalidValue;
   GemmArgs g;
   g.A = A; g.W = W; g.bias = bias; g.out = out; g.tab = tab;
   g.ldo = ldo; g.tab_rows = tab_rows > 0 ? tab_rows : 1;
   g.M = M; g.N = N; g.K = K; g.grid_m = g.grid_n = 0;
+  g.qscale = qscale; g.qcols = qcols;
   if (dtype == RESLIM_BF16) {
     if (K % 64 != 0) return hipErrorInvalidValue;   // slabs are 64 deep; create() enforces D % 64 == 0
     switch (epi) {
@@ -442,6 +468,7 @@ hipError_t launch_gemm(int dtype, Epilogue epi, const void *A, const void *W, co
       case EPI_BIAS_GELU_ACT: return launch_bf16<EPI_BIAS_GELU_ACT>(g, st);
       case EPI_BIAS_RESADD_F32: return launch_bf16<EPI_BIAS_RESADD_F32>(g, st);
       case EPI_BIAS_TAB_F32: return launch_bf16<EPI_BIAS_TAB_F32>(g, st);
+      case EPI_BIAS_QSCALE_ACT: return launch_bf16<EPI_BIAS_QSCALE_ACT>(g, st);
       default: return launch_bf16<EPI_BIAS_F32>(g, st);
     }
   }
@@ -450,6 +477,7 @@ hipError_t launch_gemm(int dtype, Epilogue epi, const void *A, const void *W, co
     case EPI_BIAS_GELU_ACT: return launch_f32<EPI_BIAS_GELU_ACT>(g, st);
     case EPI_BIAS_RESADD_F32: return launch_f32<EPI_BIAS_RESADD_F32>(g, st);
     case EPI_BIAS_TAB_F32: return launch_f32<EPI_BIAS_TAB_F32>(g, st);
+    case EPI_BIAS_QSCALE_ACT: return launch_f32<EPI_BIAS_QSCALE_ACT>(g, st);
     default: return launch_f32<EPI_BIAS_F32>(g, st);
   }
 }
