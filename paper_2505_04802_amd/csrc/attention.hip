@@ -478,6 +478,253 @@ __global__ __launch_bounds__(256, 2) void tiles_attention_bf16_v2_kernel(AttnArg
   }
 }
 
+// ------------------------------------------------------------------ bf16 kernel, third form
+// The arithmetic, fragment layouts and direct-to-LDS staging of the second form,
+// run by PERSISTENT work-groups: the grid holds two work-groups per compute unit
+// and each walks over its share of the (sample, tile, head, query block) units.
+// The K/V pipeline is flattened over units -- block 0 of the next unit (and its Q
+// fragments) is in flight while the last block of the current one is computed --
+// so the load latency and the launch of a work-group are paid once per work-group
+// instead of once per 128 queries, and no compute unit waits for the dispatcher.
+// Two more changes against the second form:
+//  * V rows use their own chunk swizzle.  The transposing read touches, per 32
+//    lanes, 4 chunks of 4 consecutive rows; rows r and r+2 (dh = 64; all four rows
+//    at dh = 128) would hit the same banks, so the chunk group is moved by row.
+//  * the address of a direct load is one uniform base per block plus a per-lane
+//    32-bit offset (two vector instructions per load pair instead of 64-bit
+//    address arithmetic), and O^T leaves the registers with 8-byte stores, one
+//    query row per lane (no staging, no extra barrier).
+template <int DH, int BKV, bool QS>
+__global__ __launch_bounds__(256, 2) void tiles_attention_bf16_v3_kernel(AttnArgs a) {
+  constexpr int BQ = 128;
+  constexpr int ROWB = DH * 2;            // bytes per K/V row in LDS
+  constexpr int CPR = DH / 8;             // 16-byte chunks per row (8 or 16)
+  constexpr int RPB = 64 / CPR;           // rows per 1 KiB load block
+  constexpr int TILE_B = BKV * ROWB;
+  constexpr int STAGE = 2 * TILE_B;       // K block then V block
+  constexpr int LPW = TILE_B / 1024 / 4;  // direct loads per wave and operand
+  constexpr int NKT = BKV / 32, NKS = DH / 16, NDT = DH / 32;
+  static_assert(TILE_B % 4096 == 0 && 2 * STAGE <= 65536, "LDS plan");
+  __shared__ __align__(1024) unsigned char smem[2 * STAGE];
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int l32 = lane & 31, hi = lane >> 5;
+  const int ld = 3 * a.D;
+  const int G = gridDim.x;
+  auto swzK = [](int r) { return CPR == 8 ? ((r & 7) ^ ((r >> 3) & 1)) : (r & 15); };
+  auto swzV = [](int r) {
+    return CPR == 8 ? ((((r >> 1) & 1) << 2) | (((r >> 3) & 1) << 1)) : (((r & 3) << 2) | (((r >> 3) & 1) << 1));
+  };
+
+  // ---- work units (all of this is uniform over the work-group)
+  struct Unit { int n_t, q0, nkb; const bf16_t *base; bf16_t *out; };
+  auto decode = [&](int vb, Unit &u) -> int {      // first non-empty unit at or after vb (stride G), or >= total
+    while (vb < a.total) {
+      const int logical = xcd_remap_attn(vb, a.total);
+      const int qb = logical % a.QB;
+      int rest = logical / a.QB;
+      const int head = rest % a.heads;
+      rest /= a.heads;
+      const int tile = rest % a.T;
+      const int b = rest / a.T;
+      const int n_t = a.tiles[tile].n_tok;
+      if (qb * BQ < n_t) {
+        const size_t row0 = static_cast<size_t>(b) * a.n_h + a.tiles[tile].tok_off;
+        u.n_t = n_t;
+        u.q0 = qb * BQ;
+        u.nkb = (n_t + BKV - 1) / BKV;
+        u.base = static_cast<const bf16_t *>(a.qkv) + row0 * ld + head * DH;
+        u.out = static_cast<bf16_t *>(a.out) + row0 * a.D + head * DH;
+        return vb;
+      }
+      vb += G;
+    }
+    return vb;
+  };
+  Unit cur, nxt;
+  int vb = decode(blockIdx.x, cur);
+  if (vb >= a.total) return;
+  vb = decode(vb + G, nxt);
+  bool has_next = vb < a.total;
+
+  // ---- load side: lane -> (row of the block, 16-byte chunk), per-lane byte offsets
+  int ld_row[LPW], colK[LPW], colV[LPW];
+#pragma unroll
+  for (int i = 0; i < LPW; ++i) {
+    ld_row[i] = (wave + 4 * i) * RPB + lane / CPR;
+    colK[i] = ((lane % CPR) ^ swzK(ld_row[i])) * 16;
+    colV[i] = ((lane % CPR) ^ swzV(ld_row[i])) * 16 + a.D * 2;
+  }
+  const int ld2 = ld * 2;
+  auto issue = [&](const Unit &u, int kv0, int buf) {
+    unsigned char *sk = smem + buf * STAGE;
+    const unsigned char *gk = reinterpret_cast<const unsigned char *>(u.base + a.D + static_cast<size_t>(kv0) * ld);
+    const int lim = u.n_t - 1 - kv0;     // rows past the tile end re-read its last row (finite, masked later)
+#pragma unroll
+    for (int i = 0; i < LPW; ++i) {
+      const int ro = min(ld_row[i], lim) * ld2;
+      attn_dl_load16(reinterpret_cast<const bf16_t *>(gk + static_cast<uint32_t>(ro + colK[i])), sk + (wave + 4 * i) * 1024);
+      attn_dl_load16(reinterpret_cast<const bf16_t *>(gk + static_cast<uint32_t>(ro + colV[i])),
+                     sk + TILE_B + (wave + 4 * i) * 1024);
+    }
+  };
+  bf16x8 qf[NKS];
+  auto load_q = [&](const Unit &u) {
+    const int qrow = min(u.q0 + wave * 32 + l32, u.n_t - 1);
+    const bf16_t *qp = u.base + static_cast<size_t>(qrow) * ld + hi * 8;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
+  };
+
+  // ---- read side (see the second form)
+  const int kr = key_perm(l32);
+  const int k_row = kr * ROWB, k_swz = swzK(kr);
+  const int L16 = lane & 15;
+  int v_addr[2][NDT];
+#pragma unroll
+  for (int e = 0; e < 2; ++e) {
+    const int vr = 8 * hi + 4 * e + (L16 >> 2);
+#pragma unroll
+    for (int d = 0; d < NDT; ++d) {
+      const int o = 32 * d + 16 * ((lane >> 4) & 1) + 4 * (L16 & 3);
+      v_addr[e][d] = TILE_B + vr * ROWB + (((o >> 3) ^ swzV(vr)) << 4) + ((o >> 2) & 1) * 8;
+    }
+  }
+
+  f32x16 o[NDT], lsum, minit;
+  bf16x8 ones;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) ones[e] = static_cast<__bf16>(1.0f);
+  const float c = QS ? 1.0f : a.scale_log2;     // MFMA output -> base-2 logit
+  const float TAU = 10.0f / c;                    // in units of the MFMA output
+  bool have_ref = false;
+  auto reset = [&]() {
+#pragma unroll
+    for (int d = 0; d < NDT; ++d)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { lsum[r] = 0.f; minit[r] = 0.f; }
+    have_ref = false;
+  };
+  reset();
+  load_q(cur);
+  issue(cur, 0, 0);
+
+  int kb = 0;
+  for (int g = 0;; ++g) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's loads of block g (and earlier stores) are done
+    __syncthreads();                        // ... and everybody's; the other buffer is free
+    const bool last = kb + 1 == cur.nkb;
+    if (!last) issue(cur, (kb + 1) * BKV, (g + 1) & 1);
+    else if (has_next) issue(nxt, 0, (g + 1) & 1);
+    const unsigned char *st = smem + (g & 1) * STAGE;
+    const int kv0 = kb * BKV;
+    const bool active = cur.q0 + wave * 32 < cur.n_t;   // wave-uniform
+
+    f32x16 s[NKT];
+    if (active) {
+      // feature step outermost: consecutive MFMAs belong to different accumulator chains
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) {
+#pragma unroll
+        for (int kt = 0; kt < NKT; ++kt) {
+          const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(st + kt * 32 * ROWB + k_row + (((2 * ks + hi) ^ k_swz) << 4));
+          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? minit : s[kt], 0, 0, 0);
+        }
+      }
+    }
+    // the query fragments are dead after the last block of a unit: fetch the next unit's
+    if (last && has_next) load_q(nxt);
+    if (active) {
+      if (kv0 + BKV > cur.n_t) {           // ragged last block: keys past the tile end get -inf
+#pragma unroll
+        for (int kt = 0; kt < NKT; ++kt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = kv0 + kt * 32 + 16 * (r / 8) + 8 * hi + (r % 8);
+            if (key >= cur.n_t) s[kt][r] = -INFINITY;
+          }
+      }
+      float mx = s[0][0];
+#pragma unroll
+      for (int kt = 0; kt < NKT; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32));     // finite: every block holds a valid key
+      if (!have_ref || __any(mx > TAU)) {
+        // move this lane's reference up by d (first block: to the block maximum)
+        const float d = have_ref ? fmaxf(mx, 0.f) : mx;
+        const float alpha = have_ref ? __builtin_amdgcn_exp2f(-d * c) : 0.f;
+#pragma unroll
+        for (int kt = 0; kt < NKT; ++kt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) s[kt][r] -= d;
+#pragma unroll
+        for (int dd = 0; dd < NDT; ++dd)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[dd][r] *= alpha;
+        const float ninit = minit[0] - d;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { lsum[r] *= alpha; minit[r] = ninit; }
+        have_ref = true;
+      }
+#pragma unroll
+      for (int kt = 0; kt < NKT; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          s[kt][r] = __builtin_amdgcn_exp2f(QS ? s[kt][r] : s[kt][r] * c);
+
+#pragma unroll
+      for (int kt = 0; kt < NKT; ++kt) {
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2) {
+          bf16x8 pf;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) pf[e] = static_cast<__bf16>(s[kt][8 * h2 + e]);
+          lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf, lsum, 0, 0, 0);
+#pragma unroll
+          for (int d = 0; d < NDT; ++d) {
+            const unsigned char *vp = st + (kt * 32 + h2 * 16) * ROWB;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (s16x4 __attribute__((address_space(3))) *)(vp + v_addr[0][d]));
+            const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (s16x4 __attribute__((address_space(3))) *)(vp + v_addr[1][d]));
+            typedef __attribute__((ext_vector_type(8))) short s16x8;
+            const s16x8 both = __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+            const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
+            o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[d], 0, 0, 0);
+          }
+        }
+      }
+    }
+    if (!last) { ++kb; continue; }
+
+    // ---- end of a unit: normalise and store this lane's query row, then move on
+    const int qrow = cur.q0 + wave * 32 + l32;
+    if (active && qrow < cur.n_t) {
+      const float inv = 1.0f / lsum[0];     // every row of the all-ones block carries the full sum over keys
+      bf16_t *op = cur.out + static_cast<size_t>(qrow) * a.D + hi * 4;
+#pragma unroll
+      for (int d = 0; d < NDT; ++d)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          // registers 4*r4 .. 4*r4+3 hold features 32d + 8*r4 + 4*hi + (0..3) of query l32
+          bf16x4 tmp;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) tmp[e] = static_cast<__bf16>(o[d][4 * r4 + e] * inv);
+          *reinterpret_cast<u32x2 *>(op + d * 32 + r4 * 8) = __builtin_bit_cast(u32x2, tmp);
+        }
+    }
+    if (!has_next) break;
+    cur = nxt;
+    vb = decode(vb + G, nxt);
+    has_next = vb < a.total;
+    kb = 0;
+    reset();
+  }
+}
+
 // ------------------------------------------------------------------ fp32 debug path
 // One work-group per (sample, tile-major token, head): scores for all keys of the
 // tile in LDS, two block reductions, then one thread per feature accumulates P V.
@@ -537,10 +784,18 @@ __global__ __launch_bounds__(128) void tiles_attention_f32_kernel(AttnArgs a, in
   }
 }
 
-static int g_attn_variant = 0;   // 0: direct-to-LDS + transposing reads, 1: register-staged with V transposed on store
+// 0: persistent work-groups (third form), 1: register-staged with V transposed on store (first form),
+// 2: one work-group per query block, direct-to-LDS (second form)
+static int g_attn_variant = 0;
+static int g_attn_cus = 0;
 
-hipError_t attention_init() { return hipSuccess; }
-bool attention_accepts_prescaled_q() { return g_attn_variant == 0; }
+hipError_t attention_init() {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  return hipDeviceGetAttribute(&g_attn_cus, hipDeviceAttributeMultiprocessorCount, dev);
+}
+bool attention_accepts_prescaled_q() { return g_attn_variant != 1; }
 
 hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *out, int batch, bool q_prescaled,
                                   hipStream_t st) {
@@ -559,14 +814,21 @@ hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *ou
     const int64_t total = static_cast<int64_t>(batch) * c->T * a.heads * a.QB;
     if (total > INT32_MAX) return hipErrorInvalidValue;
     a.total = static_cast<int>(total);
+    if (a.total == 0) return hipSuccess;
+    const int pg = a.total < 2 * g_attn_cus ? a.total : 2 * g_attn_cus;   // persistent grid: two work-groups per CU
+    if (pg <= 0) return hipErrorInvalidValue;
     if (c->dh == 64) {
       if (g_attn_variant == 1) tiles_attention_bf16_kernel<64, 128><<<dim3(a.total), dim3(256), 0, st>>>(a);
-      else if (q_prescaled) tiles_attention_bf16_v2_kernel<64, 128, true><<<dim3(a.total), dim3(256), 0, st>>>(a);
-      else tiles_attention_bf16_v2_kernel<64, 128, false><<<dim3(a.total), dim3(256), 0, st>>>(a);
+      else if (g_attn_variant == 2 && q_prescaled) tiles_attention_bf16_v2_kernel<64, 128, true><<<dim3(a.total), dim3(256), 0, st>>>(a);
+      else if (g_attn_variant == 2) tiles_attention_bf16_v2_kernel<64, 128, false><<<dim3(a.total), dim3(256), 0, st>>>(a);
+      else if (q_prescaled) tiles_attention_bf16_v3_kernel<64, 128, true><<<dim3(pg), dim3(256), 0, st>>>(a);
+      else tiles_attention_bf16_v3_kernel<64, 128, false><<<dim3(pg), dim3(256), 0, st>>>(a);
     } else if (c->dh == 128) {
       if (g_attn_variant == 1) tiles_attention_bf16_kernel<128, 64><<<dim3(a.total), dim3(256), 0, st>>>(a);
-      else if (q_prescaled) tiles_attention_bf16_v2_kernel<128, 64, true><<<dim3(a.total), dim3(256), 0, st>>>(a);
-      else tiles_attention_bf16_v2_kernel<128, 64, false><<<dim3(a.total), dim3(256), 0, st>>>(a);
+      else if (g_attn_variant == 2 && q_prescaled) tiles_attention_bf16_v2_kernel<128, 64, true><<<dim3(a.total), dim3(256), 0, st>>>(a);
+      else if (g_attn_variant == 2) tiles_attention_bf16_v2_kernel<128, 64, false><<<dim3(a.total), dim3(256), 0, st>>>(a);
+      else if (q_prescaled) tiles_attention_bf16_v3_kernel<128, 64, true><<<dim3(pg), dim3(256), 0, st>>>(a);
+      else tiles_attention_bf16_v3_kernel<128, 64, false><<<dim3(pg), dim3(256), 0, st>>>(a);
     } else {
       return hipErrorInvalidValue;
     }
@@ -583,5 +845,5 @@ hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *ou
 
 }  // namespace reslim
 
-// tuning hook: 0 = direct-to-LDS kernel (default), 1 = register-staged kernel
+// tuning hook: 0 = persistent kernel (default), 1 = register-staged kernel, 2 = one work-group per query block
 extern "C" void reslim_debug_set_attention_variant(int v) { reslim::g_attn_variant = v; }

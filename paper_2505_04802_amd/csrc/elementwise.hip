@@ -280,18 +280,29 @@ struct ResArgs {
   const int32_t *out_var_idx;
   int V, C, H, W, s, p, ps, Wp, N, head_out;
   int nbx;               // blocks per tile along x
+  int cwh, cww;          // coarse window held in LDS per input variable
+  int ci_chunk;          // input variables per pass (<= 8; fewer when the window is large, s = 1)
 };
 
 // A work-group produces a 16 x 64 block of fine pixels inside one tile's interior,
-// for all output variables (8 at a time).  For every input variable the upsampled
-// field U on the block's 18 x 66 neighbourhood is built in LDS -- bilinear with
-// neighbours clamped to the tile's haloed box, zero outside the box (the padding of
-// the convolution) -- and each thread accumulates the 3x3 stencil for 4 adjacent
-// pixels.  The head projection is read in patch order and the sum written in place:
-// un-patchify, stitch and add in one pass.
+// 8 output variables at a time.  For 8 input variables at a time it
+//   1. copies the coarse pixels the block can touch into LDS (a window of about
+//      (16/s + 3) x (64/s + 3) values per variable),
+//   2. builds the upsampled field U on the block's 18 x 66 neighbourhood from that
+//      window -- bilinear with neighbours clamped to the tile's haloed box, zero
+//      outside the box (the padding of the convolution); the per-row and per-column
+//      source indices, weights and masks are tabulated once per block,
+//   3. accumulates the 3x3 stencil, each thread for 4 adjacent pixels.
+// The head projection is then read in patch order (16 bytes per lane: 4 pixels of
+// one patch row) and the sum written in place: un-patchify, stitch and add in one
+// pass with 16-byte loads and stores.
+template <int CI, int CO>
 __global__ __launch_bounds__(256) void residual_unpatchify_kernel(ResArgs a) {
-  constexpr int BY = 16, BX = 64, WY = BY + 2, WX = BX + 2, WXP = 68, CO = 8;
-  __shared__ float U[WY * WXP];
+  constexpr int BY = 16, BX = 64, WY = BY + 2, WX = BX + 2, WXP = 68;
+  __shared__ __align__(16) float U[CI * WY * WXP];
+  __shared__ float row_w[WY], row_m[WY], col_w[WXP], col_m[WXP];
+  __shared__ int row_a[WY], row_b[WY], col_a[WXP], col_b[WXP];
+  extern __shared__ float Cw[];                // [CI][cwh][cww] coarse window
   const tile_desc td = a.tiles[blockIdx.y];
   const int b = blockIdx.z;
   const int ih = (td.y1 - td.y0) * a.ps, iw = (td.x1 - td.x0) * a.ps;
@@ -306,6 +317,44 @@ __global__ __launch_bounds__(256) void residual_unpatchify_kernel(ResArgs a) {
   const float inv_s = 1.0f / static_cast<float>(a.s);
   const int sH = a.s * a.H, sW = a.s * a.W;
   const int iy = iy0 + ty, ix = ix0 + 4 * tx;
+  const int cwh = a.cwh, cww = a.cww;
+
+  // source coordinate of fine pixel f (same arithmetic for rows and columns)
+  auto src = [&](int f, int n_coarse, int &ia, int &ib, float &w1) {
+    const float sc = (static_cast<float>(f) + 0.5f) * inv_s - 0.5f;
+    const float fl = floorf(sc);
+    w1 = sc - fl;
+    const int i0 = static_cast<int>(fl);
+    ia = min(max(i0, 0), n_coarse - 1);
+    ib = min(max(i0 + 1, 0), n_coarse - 1);
+  };
+  // first coarse row / column of the window: the clamped lower neighbour of the first fine row / column
+  int oy, ox;
+  {
+    int ib_;
+    float w_;
+    src(fy0 - 1, box_ch, oy, ib_, w_);
+    src(fx0 - 1, box_cw, ox, ib_, w_);
+  }
+  if (t < WY) {
+    const int fy = fy0 + t - 1;
+    int ia, ib;
+    float w1;
+    src(fy, box_ch, ia, ib, w1);
+    row_a[t] = min(ia - oy, cwh - 1);
+    row_b[t] = min(ib - oy, cwh - 1);
+    row_w[t] = w1;
+    row_m[t] = (fy >= 0 && fy < box_fh) ? 1.0f : 0.0f;
+  } else if (t >= 64 && t < 64 + WX) {
+    const int wx = t - 64, fx = fx0 + wx - 1;
+    int ia, ib;
+    float w1;
+    src(fx, box_cw, ia, ib, w1);
+    col_a[wx] = min(ia - ox, cww - 1);
+    col_b[wx] = min(ib - ox, cww - 1);
+    col_w[wx] = w1;
+    col_m[wx] = (fx >= 0 && fx < box_fw) ? 1.0f : 0.0f;
+  }
 
   for (int co0 = 0; co0 < a.C; co0 += CO) {
     float acc[CO][4];
@@ -315,65 +364,85 @@ __global__ __launch_bounds__(256) void residual_unpatchify_kernel(ResArgs a) {
 #pragma unroll
       for (int k = 0; k < 4; ++k) acc[o][k] = bv;
     }
-    for (int ci = 0; ci < a.C; ++ci) {
-      const float *xp = a.x + (static_cast<size_t>(b) * a.V + a.out_var_idx[ci]) * a.H * a.W;
-      __syncthreads();
-      for (int idx = t; idx < WY * WX; idx += 256) {
-        const int wy = idx / WX, wx = idx % WX;
-        const int fy = fy0 + wy - 1, fx = fx0 + wx - 1;
-        float val = 0.f;
-        if (fy >= 0 && fy < box_fh && fx >= 0 && fx < box_fw) {
-          const float sy = (static_cast<float>(fy) + 0.5f) * inv_s - 0.5f;
-          const float sx = (static_cast<float>(fx) + 0.5f) * inv_s - 0.5f;
-          const float fly = floorf(sy), flx = floorf(sx);
-          const float wy1 = sy - fly, wx1 = sx - flx;
-          const int y0i = static_cast<int>(fly), x0i = static_cast<int>(flx);
-          const int ya = min(max(y0i, 0), box_ch - 1), yb = min(max(y0i + 1, 0), box_ch - 1);
-          const int xa = min(max(x0i, 0), box_cw - 1), xb = min(max(x0i + 1, 0), box_cw - 1);
-          const float *ra = xp + static_cast<size_t>(cy_org + ya) * a.W + cx_org;
-          const float *rb = xp + static_cast<size_t>(cy_org + yb) * a.W + cx_org;
-          const float top = ra[xa] * (1.0f - wx1) + ra[xb] * wx1;
-          const float bot = rb[xa] * (1.0f - wx1) + rb[xb] * wx1;
-          val = top * (1.0f - wy1) + bot * wy1;
-        }
-        U[wy * WXP + wx] = val;
+    for (int ci0 = 0; ci0 < a.C; ci0 += a.ci_chunk) {
+      const int nci = min(a.ci_chunk, a.C - ci0);      // <= CI
+      __syncthreads();                           // previous U / window fully consumed (and tables written)
+      for (int idx = t; idx < nci * cwh * cww; idx += 256) {
+        const int ci = idx / (cwh * cww), r = idx % (cwh * cww);
+        const int wy = r / cww, wx = r % cww;
+        const float *xp = a.x + (static_cast<size_t>(b) * a.V + a.out_var_idx[ci0 + ci]) * a.H * a.W;
+        const int y = min(oy + wy, box_ch - 1), x = min(ox + wx, box_cw - 1);
+        Cw[idx] = xp[static_cast<size_t>(cy_org + y) * a.W + cx_org + x];
       }
       __syncthreads();
-      float u[3][6];
+      for (int e = t; e < WY * WX; e += 256) {
+        const int wy = e / WX, wx = e % WX;
+        const int ya = row_a[wy] * cww, yb = row_b[wy] * cww, xa = col_a[wx], xb = col_b[wx];
+        const float wy1 = row_w[wy], wx1 = col_w[wx], m = row_m[wy] * col_m[wx];
+        for (int ci = 0; ci < nci; ++ci) {
+          const float *cwp = Cw + ci * cwh * cww;
+          const float top = cwp[ya + xa] * (1.0f - wx1) + cwp[ya + xb] * wx1;
+          const float bot = cwp[yb + xa] * (1.0f - wx1) + cwp[yb + xb] * wx1;
+          const float val = top * (1.0f - wy1) + bot * wy1;
+          U[(ci * WY + wy) * WXP + wx] = m != 0.f ? val : 0.f;
+        }
+      }
+      __syncthreads();
+      for (int ci = 0; ci < nci; ++ci) {
+        float u[3][6];
 #pragma unroll
-      for (int dy = 0; dy < 3; ++dy)
+        for (int dy = 0; dy < 3; ++dy) {
+          const float *up = U + (ci * WY + ty + dy) * WXP + 4 * tx;
+          const float4 lo = *reinterpret_cast<const float4 *>(up);
+          const float2 hi2 = *reinterpret_cast<const float2 *>(up + 4);
+          u[dy][0] = lo.x; u[dy][1] = lo.y; u[dy][2] = lo.z; u[dy][3] = lo.w; u[dy][4] = hi2.x; u[dy][5] = hi2.y;
+        }
 #pragma unroll
-        for (int dx = 0; dx < 6; ++dx) u[dy][dx] = U[(ty + dy) * WXP + 4 * tx + dx];
+        for (int o = 0; o < CO; ++o) {
+          if (co0 + o < a.C) {
+            const float *wr = a.w_res + (static_cast<size_t>(co0 + o) * a.C + ci0 + ci) * 9;
 #pragma unroll
-      for (int o = 0; o < CO; ++o) {
-        if (co0 + o < a.C) {
-          const float *wr = a.w_res + (static_cast<size_t>(co0 + o) * a.C + ci) * 9;
+            for (int dy = 0; dy < 3; ++dy)
 #pragma unroll
-          for (int dy = 0; dy < 3; ++dy)
+              for (int dx = 0; dx < 3; ++dx) {
+                const float w = wr[dy * 3 + dx];
 #pragma unroll
-            for (int dx = 0; dx < 3; ++dx) {
-              const float w = wr[dy * 3 + dx];
-#pragma unroll
-              for (int k = 0; k < 4; ++k) acc[o][k] = fmaf(w, u[dy][dx + k], acc[o][k]);
-            }
+                for (int k = 0; k < 4; ++k) acc[o][k] = fmaf(w, u[dy][dx + k], acc[o][k]);
+              }
+          }
         }
       }
     }
     if (iy < ih) {
       const int gy = td.y0 * a.ps + iy;
       const int py = td.y0 + iy / a.ps, i = iy % a.ps;
+      if (a.ps % 4 == 0 && sW % 4 == 0 && ix + 3 < iw) {   // 4 pixels of one patch row: aligned 16-byte load and store
+        const int px = td.x0 + ix / a.ps, j = ix % a.ps;
+        const size_t n = static_cast<size_t>(py) * a.Wp + px;
+        const float *pp = a.P + (static_cast<size_t>(b) * a.N + n) * a.head_out + static_cast<size_t>(i) * a.ps + j;
+        float *yp = a.y + (static_cast<size_t>(b) * a.C * sH + gy) * sW + td.x0 * a.ps + ix;
 #pragma unroll
-      for (int o = 0; o < CO; ++o) {
-        const int c = co0 + o;
-        if (c >= a.C) break;
+        for (int o = 0; o < CO; ++o) {
+          const int c = co0 + o;
+          if (c >= a.C) break;
+          const float4 pv = *reinterpret_cast<const float4 *>(pp + static_cast<size_t>(c) * a.ps * a.ps);
+          *reinterpret_cast<float4 *>(yp + static_cast<size_t>(c) * sH * sW) =
+              make_float4(pv.x + acc[o][0], pv.y + acc[o][1], pv.z + acc[o][2], pv.w + acc[o][3]);
+        }
+      } else {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const int ixk = ix + k;
-          if (ixk < iw) {
-            const int px = td.x0 + ixk / a.ps, j = ixk % a.ps;
-            const size_t n = static_cast<size_t>(py) * a.Wp + px;
-            const float pv = a.P[(static_cast<size_t>(b) * a.N + n) * a.head_out + (static_cast<size_t>(c) * a.ps + i) * a.ps + j];
-            a.y[((static_cast<size_t>(b) * a.C + c) * sH + gy) * sW + td.x0 * a.ps + ixk] = pv + acc[o][k];
+        for (int o = 0; o < CO; ++o) {
+          const int c = co0 + o;
+          if (c >= a.C) break;
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const int ixk = ix + k;
+            if (ixk < iw) {
+              const int px = td.x0 + ixk / a.ps, j = ixk % a.ps;
+              const size_t n = static_cast<size_t>(py) * a.Wp + px;
+              const float pv = a.P[(static_cast<size_t>(b) * a.N + n) * a.head_out + (static_cast<size_t>(c) * a.ps + i) * a.ps + j];
+              a.y[((static_cast<size_t>(b) * a.C + c) * sH + gy) * sW + td.x0 * a.ps + ixk] = pv + acc[o][k];
+            }
           }
         }
       }
@@ -397,7 +466,15 @@ hipError_t launch_residual_unpatchify(const reslim_ctx *c, const float *x, const
   a.nbx = (max_iw + 63) / 64;
   const int nby = (max_ih + 15) / 16;
   if (c->T > 65535 || batch > 65535) return hipErrorInvalidValue;
-  residual_unpatchify_kernel<<<dim3(a.nbx * nby, c->T, batch), dim3(256), 0, st>>>(a);
+  // a block's 18 x 66 fine neighbourhood touches at most this many coarse rows / columns
+  a.cwh = 17 / a.s + 3;
+  a.cww = 65 / a.s + 3;
+  constexpr int CI = 8;
+  const size_t per_var = static_cast<size_t>(a.cwh) * a.cww * sizeof(float);
+  a.ci_chunk = static_cast<int>(std::min<size_t>(CI, (16 * 1024) / per_var));   // 8 for s >= 2, 3 for s = 1
+  if (a.ci_chunk < 1) return hipErrorInvalidValue;
+  const size_t lds = a.ci_chunk * per_var;
+  residual_unpatchify_kernel<CI, 8><<<dim3(a.nbx * nby, c->T, batch), dim3(256), lds, st>>>(a);
   return hipGetLastError();
 }
 
