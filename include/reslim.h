@@ -202,13 +202,16 @@ int reslim_profile_read(reslim_ctx *ctx, reslim_profile_record *out, int32_t max
  * byte counters by what they report for this kernel of known size. */
 int reslim_debug_copy(const void *src, void *dst, size_t bytes, void *hip_stream);
 
-/* Tuning hook for benchmarks: pins the tile shape of the bf16 GEMM kernels
- * (-1 = built-in heuristic, 0 = 256x256, 1 = 256x128, 2 = 128x128).  Process-wide. */
+/* Tuning hook for benchmarks: pins the bf16 GEMM kernel (-1 = built-in heuristic;
+ * one tile per work-group: 0 = 256x256, 1 = 256x128, 2 = 128x128; persistent
+ * direct-to-LDS 256x256: 3 = two 64-deep stages, 4 = four 32-deep stages, 5 = as 3
+ * without splitting the tiles of the last round; add 100 for columns-fastest tile
+ * order in kernels 0..2).  Process-wide. */
 void reslim_debug_set_gemm_tile(int choice);
 
-/* Tuning hook: which bf16 tile-attention kernel runs (0 = direct-to-LDS loads with
- * transposing LDS reads, the default; 1 = register-staged loads with V transposed on
- * the LDS store).  Process-wide. */
+/* Tuning hook: launch shape of the bf16 tile-attention kernel at head dimension 64
+ * (0 = 64-key blocks, three work-groups per compute unit, the default; 1 = 128-key
+ * blocks, two work-groups per compute unit).  Process-wide. */
 void reslim_debug_set_attention_variant(int variant);
 
 #ifdef __cplusplus

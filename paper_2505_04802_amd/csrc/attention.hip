@@ -3,18 +3,16 @@
 // The paper relies on a cache-blocked ("Flash") attention library (Sec. 4.4); the
 // kernel below is written for gfx950 from the arithmetic itself.
 //
-// bf16 kernel.  A work-group owns 128 queries of one (sample, tile, head); each of
-// its four waves owns 32 of them.  Keys/values are visited in blocks of BKV rows,
-// staged in LDS: K row-major, V transposed (so that the PV contraction over keys
-// reads 8 consecutive keys per lane).  Scores are computed TRANSPOSED,
-// S^T = K Q^T, with MFMA 32x32x16: a lane then owns one query column and the
-// softmax row statistics are in-lane reductions plus one exchange between the two
-// lane halves.  The rows of the K operand are loaded in a permuted order chosen so
-// that the accumulator registers of S^T are, without any data movement, the B
-// operand (P^T) of the second MFMA, O^T = V^T P^T.  Online softmax in fp32 with
-// base-2 exponentials; P is rounded to bf16 for PV while the row sum keeps fp32.
-// Work-groups are renumbered so the query blocks that share one K/V set run on one
-// XCD (one L2).
+// bf16 kernel.  The unit of work is 128 queries of one (sample, tile, head); each of
+// the four waves of a work-group owns 32 of them.  Keys/values are visited in blocks
+// of BKV rows that go from global memory straight into LDS.  Scores are computed
+// TRANSPOSED, S^T = K Q^T, with MFMA 32x32x16: a lane then owns one query column
+// and the softmax row statistics are in-lane reductions plus one exchange between
+// the two lane halves.  The rows of the K operand are read in a permuted order
+// chosen so that the accumulator registers of S^T are, without any data movement,
+// the B operand (P^T) of the second MFMA, O^T = V^T P^T.  Online softmax in fp32
+// with base-2 exponentials; P is rounded to bf16 for PV.  Units are numbered so the
+// query blocks that share one K/V set run on one XCD (one L2).
 #include "common.h"
 
 namespace reslim {
@@ -48,454 +46,52 @@ __device__ __forceinline__ int key_perm(int i) {
   return (i & 0x13) | ((i & 4) << 1) | ((i & 8) >> 1);
 }
 
-template <int DH, int BKV>
-__global__ __launch_bounds__(256, 2) void tiles_attention_bf16_kernel(AttnArgs a) {
-  constexpr int BQ = 128;
-  constexpr int KP = DH + 8;           // K_lds pitch (bf16)
-  constexpr int VP = BKV + 8;          // Vt_lds pitch (bf16)
-  constexpr int OP = DH + 8;           // O staging pitch
-  constexpr int DC = DH / 8;           // 16-byte chunks per row
-  constexpr int CK = BKV * DC / 256;   // K chunks per thread
-  constexpr int CV = (BKV / 2) * DC / 256;  // V key-pair items per thread
-  constexpr int NKT = BKV / 32, NKS = DH / 16, NDT = DH / 32;
-  static_assert(BKV * DC % 256 == 0 && (BKV / 2) * DC % 256 == 0, "staging split");
-  constexpr int K_BYTES = BKV * KP * 2, V_BYTES = DH * VP * 2, O_BYTES = BQ * OP * 2;
-  constexpr int LDS_BYTES = (K_BYTES + V_BYTES) > O_BYTES ? (K_BYTES + V_BYTES) : O_BYTES;
-  __shared__ __align__(16) unsigned char smem[LDS_BYTES];
-  bf16_t *K_lds = reinterpret_cast<bf16_t *>(smem);
-  bf16_t *Vt_lds = reinterpret_cast<bf16_t *>(smem + K_BYTES);
-  uint32_t *Vt_lds32 = reinterpret_cast<uint32_t *>(smem + K_BYTES);
-  bf16_t *O_lds = reinterpret_cast<bf16_t *>(smem);
-
-  const int logical = xcd_remap_attn(blockIdx.x, a.total);
-  const int qb = logical % a.QB;
-  int rest = logical / a.QB;
-  const int head = rest % a.heads;
-  rest /= a.heads;
-  const int tile = rest % a.T;
-  const int b = rest / a.T;
-  const int n_t = a.tiles[tile].n_tok;
-  const int64_t tok_off = a.tiles[tile].tok_off;
-  const int q0 = qb * BQ;
-  if (q0 >= n_t) return;     // uniform for the whole work-group
-
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int l32 = lane & 31, hi = lane >> 5;
-  const int ld = 3 * a.D;
-  const bf16_t *base = static_cast<const bf16_t *>(a.qkv) +
-                       (static_cast<size_t>(b) * a.n_h + tok_off) * ld + head * DH;
-  const bf16_t *Kg = base + a.D, *Vg = base + 2 * a.D;
-
-  const bool active = (q0 + wave * 32) < n_t;   // wave-uniform
-  bf16x8 qf[NKS];
-  {
-    const int qrow = min(q0 + wave * 32 + l32, n_t - 1);
-    const bf16_t *qp = base + static_cast<size_t>(qrow) * ld + hi * 8;
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
-  }
-
-  u32x4 rk[CK], rv[CV][2];
-  auto prefetch = [&](int kv0) {
-#pragma unroll
-    for (int i = 0; i < CK; ++i) {
-      const int c = t + i * 256, row = c / DC, kc = c % DC;
-      const int key = kv0 + row;
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (key < n_t) v = *reinterpret_cast<const u32x4 *>(Kg + static_cast<size_t>(key) * ld + kc * 8);
-      rk[i] = v;
-    }
-#pragma unroll
-    for (int i = 0; i < CV; ++i) {
-      const int c = t + i * 256, kp = c % (BKV / 2), c8 = c / (BKV / 2);
-      const int key = kv0 + 2 * kp;
-      u32x4 v0 = {0u, 0u, 0u, 0u}, v1 = {0u, 0u, 0u, 0u};
-      if (key < n_t) v0 = *reinterpret_cast<const u32x4 *>(Vg + static_cast<size_t>(key) * ld + c8 * 8);
-      if (key + 1 < n_t) v1 = *reinterpret_cast<const u32x4 *>(Vg + static_cast<size_t>(key + 1) * ld + c8 * 8);
-      rv[i][0] = v0;
-      rv[i][1] = v1;
-    }
-  };
-  auto stage = [&]() {
-#pragma unroll
-    for (int i = 0; i < CK; ++i) {
-      const int c = t + i * 256, row = c / DC, kc = c % DC;
-      *reinterpret_cast<u32x4 *>(K_lds + row * KP + kc * 8) = rk[i];
-    }
-#pragma unroll
-    for (int i = 0; i < CV; ++i) {
-      const int c = t + i * 256, kp = c % (BKV / 2), c8 = c / (BKV / 2);
-      // dword j of a 16-byte chunk holds features 2j (low half) and 2j+1 (high half)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const uint32_t x0 = rv[i][0][j], x1 = rv[i][1][j];
-        const uint32_t even = (x0 & 0xffffu) | (x1 << 16);          // feature 2j of keys (2kp, 2kp+1)
-        const uint32_t odd = (x0 >> 16) | (x1 & 0xffff0000u);       // feature 2j+1
-        Vt_lds32[(c8 * 8 + 2 * j) * (VP / 2) + kp] = even;
-        Vt_lds32[(c8 * 8 + 2 * j + 1) * (VP / 2) + kp] = odd;
-      }
-    }
-  };
-
-  f32x16 o[NDT];
-#pragma unroll
-  for (int d = 0; d < NDT; ++d)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
-  const float c = a.scale_log2;
-
-  const int nkb = (n_t + BKV - 1) / BKV;
-  const int k_frag = key_perm(l32) * KP + hi * 8;
-  const int v_frag = l32 * VP + hi * 8;
-
-  prefetch(0);
-  for (int kb = 0; kb < nkb; ++kb) {
-    const int kv0 = kb * BKV;
-    if (kb > 0) __syncthreads();     // every wave is done reading the previous block
-    stage();
-    __syncthreads();
-    if (kb + 1 < nkb) prefetch(kv0 + BKV);
-    if (!active) continue;
-
-    f32x16 s[NKT];
-#pragma unroll
-    for (int kt = 0; kt < NKT; ++kt) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(K_lds + kt * 32 * KP + k_frag + ks * 16);
-        s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kt], 0, 0, 0);
-      }
-    }
-    if (kv0 + BKV > n_t) {           // ragged last block: keys past the tile end get -inf
-#pragma unroll
-      for (int kt = 0; kt < NKT; ++kt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = kv0 + kt * 32 + 16 * (r / 8) + 8 * hi + (r % 8);
-          if (key >= n_t) s[kt][r] = -INFINITY;
-        }
-    }
-    float mx = s[0][0];
-#pragma unroll
-    for (int kt = 0; kt < NKT; ++kt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);     // finite: every block holds a valid key
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-    const float mc = m_new * c;
-    m_run = m_new;
-    float psum = 0.f;
-#pragma unroll
-    for (int kt = 0; kt < NKT; ++kt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(s[kt][r], c, -mc));
-        s[kt][r] = p;
-        psum += p;
-      }
-    l_run = fmaf(l_run, alpha, psum);
-#pragma unroll
-    for (int d = 0; d < NDT; ++d)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
-
-#pragma unroll
-    for (int kt = 0; kt < NKT; ++kt) {
-#pragma unroll
-      for (int h2 = 0; h2 < 2; ++h2) {
-        bf16x8 pf;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) pf[e] = static_cast<__bf16>(s[kt][8 * h2 + e]);
-#pragma unroll
-        for (int d = 0; d < NDT; ++d) {
-          const bf16x8 vf = *reinterpret_cast<const bf16x8 *>(Vt_lds + d * 32 * VP + v_frag + kt * 32 + h2 * 16);
-          o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[d], 0, 0, 0);
-        }
-      }
-    }
-  }
-
-  // normalise, transpose through LDS, store coalesced
-  const float l_tot = l_run + __shfl_xor(l_run, 32);
-  const float inv = active ? 1.0f / l_tot : 0.f;
-  __syncthreads();     // K/V staging area is reused for the output tile
-  if (active) {
-#pragma unroll
-    for (int d = 0; d < NDT; ++d)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        // registers 4*r4 .. 4*r4+3 hold features 32d + 8*r4 + 4*hi + (0..3) of query l32
-        bf16x4 tmp;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) tmp[e] = static_cast<__bf16>(o[d][4 * r4 + e] * inv);
-        *reinterpret_cast<u32x2 *>(O_lds + (wave * 32 + l32) * OP + d * 32 + r4 * 8 + hi * 4) =
-            __builtin_bit_cast(u32x2, tmp);
-      }
-  }
-  __syncthreads();
-  bf16_t *outp = static_cast<bf16_t *>(a.out) + (static_cast<size_t>(b) * a.n_h + tok_off) * a.D + head * DH;
-#pragma unroll
-  for (int i = 0; i < BQ * DC / 256; ++i) {
-    const int ch = t + i * 256, row = ch / DC, kc = ch % DC;
-    if (q0 + row < n_t)
-      *reinterpret_cast<u32x4 *>(outp + static_cast<size_t>(q0 + row) * a.D + kc * 8) =
-          *reinterpret_cast<const u32x4 *>(O_lds + row * OP + kc * 8);
-  }
-}
-
-// ------------------------------------------------------------------ bf16 kernel, second form
-// Same arithmetic and register layout as above, different data movement: K and V
-// blocks go from global memory straight into LDS (global_load_lds_dwordx4), two
-// stages deep with one barrier per block, both ROW-MAJOR with the 16-byte chunks of
-// a row XOR-swizzled (a direct load cannot pad rows).  The V^T operand of
-// O^T = V^T P^T is read with ds_read_b64_tr_b16: within 16 lanes, lane i receives
-// element i of each of the four 16-element rows the lanes 4r..4r+3 point at, i.e.
-// four consecutive keys of feature column i -- the transpose happens in the LDS
-// read, so no staging registers, no packing arithmetic and no transposed stores.
-// Keys past the end of a ragged tile are clamped to the last valid row (finite
-// data; their probabilities are exactly zero).
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
+// 64 lanes x 16 bytes from global memory to 1 KiB of LDS starting at lds_wave_base
 __device__ __forceinline__ void attn_dl_load16(const bf16_t *gsrc, unsigned char *lds_wave_base) {
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc,
                                    (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
 }
 
+// ------------------------------------------------------------------ bf16 kernel
+// Data movement.  K and V blocks are loaded with global_load_lds_dwordx4 (no
+// register staging), two stages deep with one barrier per block, both ROW-MAJOR; a
+// direct load cannot pad rows, so the 16-byte chunks of a row are XOR-swizzled on
+// the global-address side.  K rows use swzK (conflict-free for the 16-byte
+// fragment reads, 16 lanes = 256 B per LDS cycle).  The V^T operand is read with
+// ds_read_b64_tr_b16: within 16 lanes, lane i receives element i of each of the
+// four 16-element rows the lanes 4r..4r+3 point at, i.e. four consecutive keys of
+// feature column i -- the transpose happens in the LDS read.  Per 32 lanes that
+// read touches 4 chunks of 4 consecutive rows; rows r and r+2 (dh = 64; all four
+// rows at dh = 128) would hit the same banks, so V rows use their own swizzle swzV
+// that moves the chunk group by row.  The address of a direct load is one uniform
+// base per block plus a per-lane 32-bit offset.  Keys past the end of a ragged tile
+// re-read the last valid row (finite data; their probabilities are exactly zero).
+//
+// Softmax bookkeeping with few vector instructions per score (at dh = 64 the fp32
+// vector pipe, not the matrix pipe, is the scarcer one):
+//  * every S^T accumulator chain starts from `minit` = -(reference logit of this
+//    lane's query), so the MFMA already delivers logit - reference;
+//  * the reference is only moved (and O, L rescaled) when some query of the wave
+//    meets a logit more than TAU above it -- rare after the first block -- so the
+//    common block costs one max3 per three scores, one exp2 and half a convert
+//    per score;
+//  * the row sums L ride on the matrix pipe: a constant all-ones A operand turns
+//    O^T = V^T P^T into one more 32-row block whose rows all equal sum_k P.
 // QS: the caller has already multiplied q by log2(e)/sqrt(dh) (the fused QKV
 // epilogue does, before its single rounding to bf16), so the MFMA output is the
 // base-2 logit itself.
-template <int DH, int BKV, bool QS>
-__global__ __launch_bounds__(256, 2) void tiles_attention_bf16_v2_kernel(AttnArgs a) {
-  constexpr int BQ = 128;
-  constexpr int ROWB = DH * 2;            // bytes per K/V row in LDS
-  constexpr int CPR = DH / 8;             // 16-byte chunks per row (8 or 16)
-  constexpr int RPB = 64 / CPR;           // rows per 1 KiB load block
-  constexpr int TILE_B = BKV * ROWB;
-  constexpr int STAGE = 2 * TILE_B;       // K block then V block
-  constexpr int LPW = TILE_B / 1024 / 4;  // direct loads per wave and operand
-  constexpr int NKT = BKV / 32, NKS = DH / 16, NDT = DH / 32;
-  constexpr int OP = DH + 8, DC = DH / 8;
-  static_assert(TILE_B % 4096 == 0 && BQ * OP * 2 <= 2 * STAGE && 2 * STAGE <= 65536, "LDS plan");
-  __shared__ __align__(1024) unsigned char smem[2 * STAGE];
-  bf16_t *O_lds = reinterpret_cast<bf16_t *>(smem);
-
-  const int logical = xcd_remap_attn(blockIdx.x, a.total);
-  const int qb = logical % a.QB;
-  int rest = logical / a.QB;
-  const int head = rest % a.heads;
-  rest /= a.heads;
-  const int tile = rest % a.T;
-  const int b = rest / a.T;
-  const int n_t = a.tiles[tile].n_tok;
-  const int64_t tok_off = a.tiles[tile].tok_off;
-  const int q0 = qb * BQ;
-  if (q0 >= n_t) return;     // uniform for the whole work-group
-
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int l32 = lane & 31, hi = lane >> 5;
-  const int ld = 3 * a.D;
-  const bf16_t *base = static_cast<const bf16_t *>(a.qkv) +
-                       (static_cast<size_t>(b) * a.n_h + tok_off) * ld + head * DH;
-  const bf16_t *Kg = base + a.D, *Vg = base + 2 * a.D;
-  auto swz = [](int r) { return CPR == 8 ? ((r & 7) ^ ((r >> 3) & 1)) : (r & 15); };
-
-  const bool active = (q0 + wave * 32) < n_t;   // wave-uniform
-  bf16x8 qf[NKS];
-  {
-    const int qrow = min(q0 + wave * 32 + l32, n_t - 1);
-    const bf16_t *qp = base + static_cast<size_t>(qrow) * ld + hi * 8;
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
-  }
-
-  // load side
-  int ld_row[LPW], ld_col[LPW];
-#pragma unroll
-  for (int i = 0; i < LPW; ++i) {
-    ld_row[i] = (wave + 4 * i) * RPB + lane / CPR;
-    ld_col[i] = ((lane % CPR) ^ swz(ld_row[i])) * 8;
-  }
-  auto issue = [&](int kv0, int buf) {
-    unsigned char *sk = smem + buf * STAGE;
-#pragma unroll
-    for (int i = 0; i < LPW; ++i) {
-      const size_t key = static_cast<size_t>(min(kv0 + ld_row[i], n_t - 1));
-      attn_dl_load16(Kg + key * ld + ld_col[i], sk + (wave + 4 * i) * 1024);
-      attn_dl_load16(Vg + key * ld + ld_col[i], sk + TILE_B + (wave + 4 * i) * 1024);
-    }
-  };
-
-  // K fragment: A-operand row l32 carries key key_perm(l32) of its 32-key group
-  const int kr = key_perm(l32);
-  const int k_row = kr * ROWB, k_swz = swz(kr);
-  // V^T fragment through the transposing read: this lane points at key row
-  // 8*hi + 4*e + (lane%16)/4 of a 16-key step and at the 4 features
-  // 32*dt + 16*((lane/16)&1) + 4*(lane%4) .. +3
-  const int L16 = lane & 15;
-  int v_addr[2][NDT];
-#pragma unroll
-  for (int e = 0; e < 2; ++e) {
-    const int vr = 8 * hi + 4 * e + (L16 >> 2);
-#pragma unroll
-    for (int d = 0; d < NDT; ++d) {
-      const int o = 32 * d + 16 * ((lane >> 4) & 1) + 4 * (L16 & 3);
-      v_addr[e][d] = TILE_B + vr * ROWB + (((o >> 3) ^ swz(vr)) << 4) + ((o >> 2) & 1) * 8;
-    }
-  }
-
-  // Softmax bookkeeping with few vector instructions per score (at dh = 64 the fp32
-  // vector pipe, not the matrix pipe, bounds this kernel):
-  //  * every S^T accumulator chain starts from `minit` = -(reference logit of this
-  //    lane's query), so the MFMA already delivers logit - reference;
-  //  * the reference is only moved (and O, L rescaled) when some query of the wave
-  //    meets a logit more than TAU above it -- rare after the first block -- so the
-  //    common block costs one max3 per three scores, one exp2 and half a convert
-  //    per score;
-  //  * the row sums L ride on the matrix pipe: a constant all-ones A operand turns
-  //    O^T = V^T P^T into one more 32-row block whose rows all equal sum_k P.
-  f32x16 o[NDT], lsum, minit;
-#pragma unroll
-  for (int d = 0; d < NDT; ++d)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) { lsum[r] = 0.f; minit[r] = 0.f; }
-  bf16x8 ones;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) ones[e] = static_cast<__bf16>(1.0f);
-  const float c = QS ? 1.0f : a.scale_log2;     // MFMA output -> base-2 logit
-  const float TAU = 10.0f / c;                    // in units of the MFMA output
-  bool have_ref = false;                          // wave-uniform
-  const int nkb = (n_t + BKV - 1) / BKV;
-
-  issue(0, 0);
-  for (int kb = 0; kb < nkb; ++kb) {
-    const int kv0 = kb * BKV;
-    __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's part of block kb has landed
-    __syncthreads();                        // ... and everybody's; the other buffer is free
-    if (kb + 1 < nkb) issue(kv0 + BKV, (kb + 1) & 1);
-    if (!active) continue;
-    const unsigned char *st = smem + (kb & 1) * STAGE;
-
-    f32x16 s[NKT];
-#pragma unroll
-    for (int kt = 0; kt < NKT; ++kt) {
-#pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(st + kt * 32 * ROWB + k_row + (((2 * ks + hi) ^ k_swz) << 4));
-        s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? minit : s[kt], 0, 0, 0);
-      }
-    }
-    if (kv0 + BKV > n_t) {           // ragged last block: keys past the tile end get -inf
-#pragma unroll
-      for (int kt = 0; kt < NKT; ++kt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = kv0 + kt * 32 + 16 * (r / 8) + 8 * hi + (r % 8);
-          if (key >= n_t) s[kt][r] = -INFINITY;
-        }
-    }
-    float mx = s[0][0];
-#pragma unroll
-    for (int kt = 0; kt < NKT; ++kt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));     // finite: every block holds a valid key
-    if (!have_ref || __any(mx > TAU)) {
-      // move this lane's reference up by d (first block: to the block maximum)
-      const float d = have_ref ? fmaxf(mx, 0.f) : mx;
-      const float alpha = have_ref ? __builtin_amdgcn_exp2f(-d * c) : 0.f;
-#pragma unroll
-      for (int kt = 0; kt < NKT; ++kt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[kt][r] -= d;
-#pragma unroll
-      for (int dd = 0; dd < NDT; ++dd)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[dd][r] *= alpha;
-      const float ninit = minit[0] - d;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) { lsum[r] *= alpha; minit[r] = ninit; }
-      have_ref = true;
-    }
-#pragma unroll
-    for (int kt = 0; kt < NKT; ++kt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-        s[kt][r] = __builtin_amdgcn_exp2f(QS ? s[kt][r] : s[kt][r] * c);
-
-#pragma unroll
-    for (int kt = 0; kt < NKT; ++kt) {
-#pragma unroll
-      for (int h2 = 0; h2 < 2; ++h2) {
-        bf16x8 pf;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) pf[e] = static_cast<__bf16>(s[kt][8 * h2 + e]);
-        lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf, lsum, 0, 0, 0);
-#pragma unroll
-        for (int d = 0; d < NDT; ++d) {
-          const unsigned char *vp = st + (kt * 32 + h2 * 16) * ROWB;
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (s16x4 __attribute__((address_space(3))) *)(vp + v_addr[0][d]));
-          const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (s16x4 __attribute__((address_space(3))) *)(vp + v_addr[1][d]));
-          typedef __attribute__((ext_vector_type(8))) short s16x8;
-          const s16x8 both = __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
-          const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
-          o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[d], 0, 0, 0);
-        }
-      }
-    }
-  }
-
-  // every row of the all-ones block carries the full sum over keys
-  const float inv = active ? 1.0f / lsum[0] : 0.f;
-  __syncthreads();     // the staging area is reused for the output tile
-  if (active) {
-#pragma unroll
-    for (int d = 0; d < NDT; ++d)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        bf16x4 tmp;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) tmp[e] = static_cast<__bf16>(o[d][4 * r4 + e] * inv);
-        *reinterpret_cast<u32x2 *>(O_lds + (wave * 32 + l32) * OP + d * 32 + r4 * 8 + hi * 4) =
-            __builtin_bit_cast(u32x2, tmp);
-      }
-  }
-  __syncthreads();
-  bf16_t *outp = static_cast<bf16_t *>(a.out) + (static_cast<size_t>(b) * a.n_h + tok_off) * a.D + head * DH;
-#pragma unroll
-  for (int i = 0; i < BQ * DC / 256; ++i) {
-    const int ch = t + i * 256, row = ch / DC, kc = ch % DC;
-    if (q0 + row < n_t)
-      *reinterpret_cast<u32x4 *>(outp + static_cast<size_t>(q0 + row) * a.D + kc * 8) =
-          *reinterpret_cast<const u32x4 *>(O_lds + row * OP + kc * 8);
-  }
-}
-
-// ------------------------------------------------------------------ bf16 kernel, third form
-// The arithmetic, fragment layouts and direct-to-LDS staging of the second form,
-// run by PERSISTENT work-groups: the grid holds two work-groups per compute unit
-// and each walks over its share of the (sample, tile, head, query block) units.
-// The K/V pipeline is flattened over units -- block 0 of the next unit (and its Q
-// fragments) is in flight while the last block of the current one is computed --
-// so the load latency and the launch of a work-group are paid once per work-group
-// instead of once per 128 queries, and no compute unit waits for the dispatcher.
-// Two more changes against the second form:
-//  * V rows use their own chunk swizzle.  The transposing read touches, per 32
-//    lanes, 4 chunks of 4 consecutive rows; rows r and r+2 (dh = 64; all four rows
-//    at dh = 128) would hit the same banks, so the chunk group is moved by row.
-//  * the address of a direct load is one uniform base per block plus a per-lane
-//    32-bit offset (two vector instructions per load pair instead of 64-bit
-//    address arithmetic), and O^T leaves the registers with 8-byte stores, one
-//    query row per lane (no staging, no extra barrier).
-template <int DH, int BKV, bool QS>
-__global__ __launch_bounds__(256, 2) void tiles_attention_bf16_v3_kernel(AttnArgs a) {
+//
+// Scheduling.  Work-groups are PERSISTENT: the grid holds MINW work-groups per
+// compute unit and each walks over its share of the units.  The K/V pipeline is
+// flattened over units -- block 0 of the next unit (and its Q fragments) is in
+// flight while the last block of the current one is computed.  O^T leaves the
+// registers with 8-byte stores, one query row per lane (no staging, no extra
+// barrier).  Measured on MI355X (c1, dh = 64): 64-key blocks with three waves per
+// SIMD (156 VGPRs) beat 128-key blocks with two (0.097 vs 0.102 ms per launch).
+template <int DH, int BKV, bool QS, int MINW = 2>
+__global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArgs a) {
   constexpr int BQ = 128;
   constexpr int ROWB = DH * 2;            // bytes per K/V row in LDS
   constexpr int CPR = DH / 8;             // 16-byte chunks per row (8 or 16)
@@ -576,7 +172,11 @@ __global__ __launch_bounds__(256, 2) void tiles_attention_bf16_v3_kernel(AttnArg
     for (int ks = 0; ks < NKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
   };
 
-  // ---- read side (see the second form)
+  // ---- read side
+  // K fragment: A-operand row l32 carries key key_perm(l32) of its 32-key group.
+  // V^T fragment through the transposing read: this lane points at key row
+  // 8*hi + 4*e + (lane%16)/4 of a 16-key step and at the 4 features
+  // 32*dt + 16*((lane/16)&1) + 4*(lane%4) .. +3
   const int kr = key_perm(l32);
   const int k_row = kr * ROWB, k_swz = swzK(kr);
   const int L16 = lane & 15;
@@ -784,8 +384,7 @@ __global__ __launch_bounds__(128) void tiles_attention_f32_kernel(AttnArgs a, in
   }
 }
 
-// 0: persistent work-groups (third form), 1: register-staged with V transposed on store (first form),
-// 2: one work-group per query block, direct-to-LDS (second form)
+// 0: 64-key blocks, three work-groups per CU at dh = 64 (default); 1: 128-key blocks, two per CU
 static int g_attn_variant = 0;
 static int g_attn_cus = 0;
 
@@ -795,7 +394,7 @@ hipError_t attention_init() {
   if (e != hipSuccess) return e;
   return hipDeviceGetAttribute(&g_attn_cus, hipDeviceAttributeMultiprocessorCount, dev);
 }
-bool attention_accepts_prescaled_q() { return g_attn_variant != 1; }
+bool attention_accepts_prescaled_q() { return true; }
 
 hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *out, int batch, bool q_prescaled,
                                   hipStream_t st) {
@@ -809,26 +408,23 @@ hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *ou
   a.n_h = c->n_h;
   a.scale_log2 = 1.4426950408889634f / sqrtf(static_cast<float>(c->dh));
   if (c->cfg.dtype == RESLIM_BF16) {
-    if (q_prescaled && g_attn_variant == 1) return hipErrorInvalidValue;   // the older kernel scales q itself
     a.QB = (c->max_n_tok + 127) / 128;
     const int64_t total = static_cast<int64_t>(batch) * c->T * a.heads * a.QB;
     if (total > INT32_MAX) return hipErrorInvalidValue;
     a.total = static_cast<int>(total);
     if (a.total == 0) return hipSuccess;
-    const int pg = a.total < 2 * g_attn_cus ? a.total : 2 * g_attn_cus;   // persistent grid: two work-groups per CU
-    if (pg <= 0) return hipErrorInvalidValue;
-    if (c->dh == 64) {
-      if (g_attn_variant == 1) tiles_attention_bf16_kernel<64, 128><<<dim3(a.total), dim3(256), 0, st>>>(a);
-      else if (g_attn_variant == 2 && q_prescaled) tiles_attention_bf16_v2_kernel<64, 128, true><<<dim3(a.total), dim3(256), 0, st>>>(a);
-      else if (g_attn_variant == 2) tiles_attention_bf16_v2_kernel<64, 128, false><<<dim3(a.total), dim3(256), 0, st>>>(a);
-      else if (q_prescaled) tiles_attention_bf16_v3_kernel<64, 128, true><<<dim3(pg), dim3(256), 0, st>>>(a);
-      else tiles_attention_bf16_v3_kernel<64, 128, false><<<dim3(pg), dim3(256), 0, st>>>(a);
+    if (g_attn_cus <= 0) return hipErrorInvalidValue;
+    const int pg2 = a.total < 2 * g_attn_cus ? a.total : 2 * g_attn_cus;   // persistent grids
+    const int pg3 = a.total < 3 * g_attn_cus ? a.total : 3 * g_attn_cus;
+    if (c->dh == 64 && g_attn_variant == 0) {
+      if (q_prescaled) tiles_attention_bf16_kernel<64, 64, true, 3><<<dim3(pg3), dim3(256), 0, st>>>(a);
+      else tiles_attention_bf16_kernel<64, 64, false, 3><<<dim3(pg3), dim3(256), 0, st>>>(a);
+    } else if (c->dh == 64) {
+      if (q_prescaled) tiles_attention_bf16_kernel<64, 128, true, 2><<<dim3(pg2), dim3(256), 0, st>>>(a);
+      else tiles_attention_bf16_kernel<64, 128, false, 2><<<dim3(pg2), dim3(256), 0, st>>>(a);
     } else if (c->dh == 128) {
-      if (g_attn_variant == 1) tiles_attention_bf16_kernel<128, 64><<<dim3(a.total), dim3(256), 0, st>>>(a);
-      else if (g_attn_variant == 2 && q_prescaled) tiles_attention_bf16_v2_kernel<128, 64, true><<<dim3(a.total), dim3(256), 0, st>>>(a);
-      else if (g_attn_variant == 2) tiles_attention_bf16_v2_kernel<128, 64, false><<<dim3(a.total), dim3(256), 0, st>>>(a);
-      else if (q_prescaled) tiles_attention_bf16_v3_kernel<128, 64, true><<<dim3(pg), dim3(256), 0, st>>>(a);
-      else tiles_attention_bf16_v3_kernel<128, 64, false><<<dim3(pg), dim3(256), 0, st>>>(a);
+      if (q_prescaled) tiles_attention_bf16_kernel<128, 64, true, 2><<<dim3(pg2), dim3(256), 0, st>>>(a);
+      else tiles_attention_bf16_kernel<128, 64, false, 2><<<dim3(pg2), dim3(256), 0, st>>>(a);
     } else {
       return hipErrorInvalidValue;
     }
@@ -845,5 +441,5 @@ hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *ou
 
 }  // namespace reslim
 
-// tuning hook: 0 = persistent kernel (default), 1 = register-staged kernel, 2 = one work-group per query block
+// tuning hook for dh = 64: 0 = 64-key blocks, three work-groups per CU (default), 1 = 128-key blocks, two per CU
 extern "C" void reslim_debug_set_attention_variant(int v) { reslim::g_attn_variant = v; }
