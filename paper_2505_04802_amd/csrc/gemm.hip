@@ -30,7 +30,6 @@ struct GemmArgs {
   int grid_m, grid_n;
   float qscale;   // EPI_BIAS_QSCALE_ACT: factor applied to output columns n < qcols
   int qcols;
-  int full_items, split;   // persistent kernel: whole tiles first, then the rest in `split` parts each
   int col_fast;            // one-tile-per-work-group kernel: tile order inside a band
 };
 
@@ -412,7 +411,7 @@ typedef DlCfg<4, 2, 64, 2> DlA;          // persistent 256x256, 8 waves of 64x12
 typedef DlCfg<2, 4, 32, 4> DlB;          // same tile, 4 x 32 KB slabs (three in flight)
 
 static int g_col_fast = 0;
-static int g_gemm_tile_override = -1;   // test / tuning hook: 0 big, 1 wide, 2 small, 3/4 direct-to-LDS, 5 = 3 without tail split
+static int g_gemm_tile_override = -1;   // test / tuning hook: 0 big, 1 wide, 2 small, 3/4 direct-to-LDS
 
 template <int EPI>
 static hipError_t launch_bf16(GemmArgs g, hipStream_t st) {
@@ -427,9 +426,8 @@ static hipError_t launch_bf16(GemmArgs g, hipStream_t st) {
   switch (choice) {
     case 0: return launch_bf16_tc<TileBig, EPI>(g, st);
     case 1: return launch_bf16_tc<TileWide, EPI>(g, st);
-    case 3: g_dl_split = true; return launch_bf16_dl<DlA, EPI>(g, st);
+    case 3: return launch_bf16_dl<DlA, EPI>(g, st);
     case 4: return launch_bf16_dl<DlB, EPI>(g, st);
-    case 5: g_dl_split = false; return launch_bf16_dl<DlA, EPI>(g, st);   // comparison point: last round unsplit
     default: return launch_bf16_tc<TileSmall, EPI>(g, st);
   }
 }
@@ -471,7 +469,7 @@ hipError_t launch_gemm(int dtype, Epilogue epi, const void *A, const void *W, co
   GemmArgs g;
   g.A = A; g.W = W; g.bias = bias; g.out = out; g.tab = tab;
   g.ldo = ldo; g.tab_rows = tab_rows > 0 ? tab_rows : 1;
-  g.M = M; g.N = N; g.K = K; g.grid_m = g.grid_n = 0; g.full_items = 0; g.split = 1; g.col_fast = g_col_fast;
+  g.M = M; g.N = N; g.K = K; g.grid_m = g.grid_n = 0; g.col_fast = g_col_fast;
   g.qscale = qscale; g.qcols = qcols;
   if (dtype == RESLIM_BF16) {
     if (K % 64 != 0) return hipErrorInvalidValue;   // slabs are 64 deep; create() enforces D % 64 == 0
