@@ -86,6 +86,19 @@ CONFIGS: Dict[str, ReslimConfig] = {
     "c4": ReslimConfig("c4", batch=1, in_vars=32, out_vars=32, H=256, W=512, scale=4, patch=2,
                        embed_dim=4096, heads=32, mlp_ratio=4, depth=4,
                        tiles_y=4, tiles_x=4, halo=2),
+    # The paper's own model sizes (Sec. 5, "Model Configuration") on the 112 -> 28 km task
+    # of Table 1 ([180, 360, 23] in, [720, 1440, 3] out), one hourly sample, 16 tiles
+    # (the tiling of the inference-speed table).  The halo width is not stated: 2 patches.
+    # The 10B model (head dimension 256) is not instantiated.
+    "m9m": ReslimConfig("m9m", batch=1, in_vars=23, out_vars=3, H=180, W=360, scale=4, patch=2,
+                        embed_dim=256, heads=4, mlp_ratio=4, depth=6,
+                        tiles_y=4, tiles_x=4, halo=2),
+    "m126m": ReslimConfig("m126m", batch=1, in_vars=23, out_vars=3, H=180, W=360, scale=4, patch=2,
+                          embed_dim=1024, heads=16, mlp_ratio=4, depth=8,
+                          tiles_y=4, tiles_x=4, halo=2),
+    "m1b": ReslimConfig("m1b", batch=1, in_vars=23, out_vars=3, H=180, W=360, scale=4, patch=2,
+                        embed_dim=3072, heads=24, mlp_ratio=4, depth=8,
+                        tiles_y=4, tiles_x=4, halo=2),
 }
 
 

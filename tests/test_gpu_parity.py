@@ -189,6 +189,13 @@ def test_forward_c4_sampled_tile():
     _sampled_tile_parity(cfg, [5])                                  # an interior tile, 2448 tokens
 
 
+@pytest.mark.parametrize("name,tile_ids", [("m9m", [0, 5, 15]), ("m126m", [0, 6]), ("m1b", [10])])
+def test_forward_paper_model_sizes_sampled_tiles(name, tile_ids):
+    """The paper's 9.5M / 126M / 1B model sizes (Sec. 5) on the [180,360,23] -> [720,1440,3]
+    task, 16 tiles: more input than output variables, head dimensions 64 and 128."""
+    _sampled_tile_parity(WL.CONFIGS[name], tile_ids)
+
+
 # ------------------------------------------------------------------ edge cases
 def test_edge_cases_and_errors():
     cfg = SMALL_BF16
