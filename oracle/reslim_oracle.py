@@ -380,3 +380,51 @@ def rel_l2(a, ref) -> float:
         den = np.sqrt((r2 ** 2).sum(-1))
         return float((num / np.maximum(den, 1e-300)).max())
     return float(np.sqrt(((a - ref) ** 2).sum()) / max(np.sqrt((ref ** 2).sum()), 1e-300))
+
+
+# --------------------------------------------------------------------------- Bayesian training loss
+# Sec. 4.1, "Bayesian Training Loss" (the paper's one equation): a latitude-weighted
+# squared error plus a total-variation prior over each pixel's spatial neighbours,
+#     || y - x ||_D^2  +  sum_k sum_i sum_{j in C(i)} b_ij | x_ki - x_kj | .
+# Readings where the text is silent (listed in the design notes):
+#  * D = diag of cos(latitude of the pixel row), divided by its mean over the rows;
+#    rows are the centres of an equiangular grid between lat_min and lat_max;
+#  * C(i) = the 8 nearest pixels, clipped at the domain edge (no wrap-around);
+#  * b_ij = (1 / distance) / (4 + 4 / sqrt(2)): inversely proportional to the Euclidean
+#    pixel distance, normalised so a full neighbourhood sums to 1 (edge pixels are not
+#    renormalised);
+#  * both terms are averaged over the K N pixel values (the first term is called a
+#    mean squared error), the prior carries an explicit weight (1 in the equation);
+#  * x in the prior is the prediction; every ordered pair (i, j) counts, as the
+#    double sum is written.
+def lat_weights(Hf: int, lat_min: float = -90.0, lat_max: float = 90.0):
+    """cos(latitude) at the Hf row centres, normalised to mean 1."""
+    step = (lat_max - lat_min) / Hf
+    lat = lat_min + (np.arange(Hf, dtype=F64) + 0.5) * step
+    w = np.cos(np.deg2rad(lat))
+    return w / w.mean()
+
+
+def bayes_loss(pred, target, lat_w, tv_weight: float = 1.0):
+    """Returns (total, data term, prior term) for pred, target [B, K, Hf, Wf]."""
+    x = np.asarray(pred, F64)
+    y = np.asarray(target, F64)
+    lw = np.asarray(lat_w, F64)
+    B, K, Hf, Wf = x.shape
+    count = float(B * K * Hf * Wf)
+    data = float((lw[None, None, :, None] * (y - x) ** 2).sum() / count)
+    norm = 4.0 + 4.0 / np.sqrt(2.0)
+    prior = 0.0
+    for dy in (-1, 0, 1):
+        for dx in (-1, 0, 1):
+            if dy == 0 and dx == 0:
+                continue
+            b = (1.0 / np.sqrt(float(dy * dy + dx * dx))) / norm
+            # pixels i = (r, c) whose neighbour j = (r + dy, c + dx) lies inside the grid
+            r0, r1 = max(0, -dy), Hf - max(0, dy)
+            c0, c1 = max(0, -dx), Wf - max(0, dx)
+            if r1 <= r0 or c1 <= c0:
+                continue
+            prior += b * float(np.abs(x[:, :, r0:r1, c0:c1] - x[:, :, r0 + dy:r1 + dy, c0 + dx:c1 + dx]).sum())
+    prior = tv_weight * prior / count
+    return data + prior, data, prior

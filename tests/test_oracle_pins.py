@@ -341,3 +341,60 @@ def test_generators_are_seeded_and_shaped():
     assert np.array_equal(WL.round_to_bf16(tb.numpy()), tb.to(torch.bfloat16).to(torch.float32).numpy())
     wb = WL.make_weights(WL.CONFIGS["c1"].with_(embed_dim=64, heads=2, depth=1, H=8, W=8, tiles_y=1, tiles_x=1))
     assert np.array_equal(wb["w_qkv"], WL.round_to_bf16(wb["w_qkv"]))
+
+
+# ------------------------------------------------------------------ Bayesian loss (Sec. 4.1)
+def _bayes_loss_loops(x, y, lw, lam):
+    """The paper's double sum written as explicit loops over pixels and neighbours."""
+    B, K, H, W = x.shape
+    norm = 4.0 + 4.0 / math.sqrt(2.0)
+    data = prior = 0.0
+    for b in range(B):
+        for k in range(K):
+            for r in range(H):
+                for c in range(W):
+                    data += lw[r] * (y[b, k, r, c] - x[b, k, r, c]) ** 2
+                    for rr in range(max(r - 1, 0), min(r + 2, H)):
+                        for cc in range(max(c - 1, 0), min(c + 2, W)):
+                            if (rr, cc) != (r, c):
+                                prior += abs(x[b, k, r, c] - x[b, k, rr, cc]) / math.hypot(rr - r, cc - c) / norm
+    n = B * K * H * W
+    return data / n + lam * prior / n, data / n, lam * prior / n
+
+
+def test_bayes_loss_matches_explicit_loops():
+    rng = np.random.default_rng(11)
+    x, y = rng.normal(size=(2, 3, 7, 5)), rng.normal(size=(2, 3, 7, 5))
+    lw = O.lat_weights(7, -60.0, 75.0)
+    got = O.bayes_loss(x, y, lw, tv_weight=0.3)
+    ref = _bayes_loss_loops(x, y, lw, 0.3)
+    assert np.allclose(got, ref, rtol=1e-12, atol=0)
+
+
+def test_bayes_loss_closed_forms():
+    H, W = 12, 9
+    lw = O.lat_weights(H)
+    # latitude weights: mean 1, symmetric about the equator, largest at the equator
+    assert abs(lw.mean() - 1.0) < 1e-14 and np.allclose(lw, lw[::-1]) and lw.argmax() in (H // 2 - 1, H // 2)
+    assert np.allclose(lw * np.cos(np.deg2rad(-90 + 0.5 * 180 / H)), lw[0] * np.cos(np.deg2rad(-90 + (np.arange(H) + 0.5) * 180 / H)))
+    # constant prediction: no variation, data term = weighted mean of d^2 = d^2 (weights have mean 1)
+    x = np.full((1, 2, H, W), 0.25)
+    tot, data, prior = O.bayes_loss(x, x + 2.0, lw)
+    assert prior == 0.0 and abs(data - 4.0) < 1e-13 and tot == data
+    # ramp along x with slope a: each horizontal ordered pair contributes b_ax |a|, each diagonal b_diag |a|
+    a = 0.7
+    ramp = np.broadcast_to(a * np.arange(W, dtype=float), (1, 1, H, W))
+    _, data, prior = O.bayes_loss(ramp, ramp, lw)
+    norm = 4 + 4 / math.sqrt(2)
+    horiz = 2 * H * (W - 1)                       # ordered pairs (r,c)->(r,c+-1)
+    diag = 4 * (H - 1) * (W - 1)                  # ordered pairs (r,c)->(r+-1,c+-1)
+    expect = a * (horiz / norm + diag / (math.sqrt(2) * norm)) / (H * W)
+    assert data == 0.0 and abs(prior - expect) < 1e-13
+    # one hot pixel of height h in the interior: 8 neighbours, each ordered pair twice
+    x = np.zeros((1, 1, H, W)); x[0, 0, 5, 4] = 3.0
+    _, _, prior = O.bayes_loss(x, x, lw, tv_weight=2.0)
+    assert abs(prior - 2.0 * 2 * 3.0 * (4 / norm + 4 / (math.sqrt(2) * norm)) / (H * W)) < 1e-13
+    # a corner pixel has 3 neighbours
+    x = np.zeros((1, 1, H, W)); x[0, 0, 0, 0] = 1.0
+    _, _, prior = O.bayes_loss(x, x, lw)
+    assert abs(prior - 2 * (2 / norm + 1 / (math.sqrt(2) * norm)) / (H * W)) < 1e-13
