@@ -197,6 +197,27 @@ int reslim_profile_enable(reslim_ctx *ctx, int32_t max_records);
 int reslim_profile_reset(reslim_ctx *ctx);
 int reslim_profile_read(reslim_ctx *ctx, reslim_profile_record *out, int32_t max_out, int32_t *n_out);
 
+/* Bayesian training loss, forward value only (Sec. 4.1, "Bayesian Training Loss":
+ * latitude-weighted squared error plus a total-variation prior over each pixel's
+ * spatial neighbours, the paper's one equation).
+ *   out3[0] = out3[1] + out3[2]
+ *   out3[1] = mean over (b, k, r, c) of lat_w[r] * (target - pred)^2
+ *   out3[2] = tv_weight * mean over (b, k, i) of sum_{j in C(i)} b_ij |pred_i - pred_j|
+ * C(i) = the 8 nearest pixels inside the Hf x Wf grid (no wrap-around), b_ij =
+ * (1 / Euclidean pixel distance) / (4 + 4 / sqrt 2); every ordered pair counts.
+ * pred, target: dev fp32 [batch, vars, Hf, Wf], row-major; lat_w: dev fp32 [Hf]
+ * (the paper's matrix D: the caller supplies cos(latitude) of each row, normalised as
+ * it sees fit); out3: dev, 3 doubles, 8-byte aligned, written by the last kernel
+ * enqueued; workspace: dev, 8-byte aligned, at least the size reported by
+ * reslim_bayes_loss_workspace_bytes, caller-owned.  No context is needed.  Work is
+ * enqueued on hip_stream, nothing is synchronised.  batch * vars <= 65535.
+ * Errors: RESLIM_EINVAL (null pointer, non-positive size, alignment),
+ * RESLIM_EWORKSPACE (too small), RESLIM_EHIP.  The result is deterministic. */
+int reslim_bayes_loss_workspace_bytes(int32_t batch, int32_t vars, int32_t Hf, int32_t Wf, size_t *out);
+int reslim_bayes_loss_fwd(const float *pred, const float *target, const float *lat_w, int32_t batch,
+                          int32_t vars, int32_t Hf, int32_t Wf, float tv_weight, double *out3,
+                          void *workspace, size_t ws_bytes, void *hip_stream);
+
 /* Bandwidth yardstick: a plain device-to-device copy kernel (16 bytes per lane) of
  * `bytes` (a multiple of 16) from src to dst, both dev.  Profilers scale their HBM
  * byte counters by what they report for this kernel of known size. */

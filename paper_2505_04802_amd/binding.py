@@ -29,7 +29,8 @@ EXPORTS = ["tiles_partition", "reslim_create", "reslim_destroy", "reslim_last_er
            "reslim_tokens_per_sample", "reslim_workspace_bytes", "reslim_embed_fwd", "tiles_attention_fwd",
            "reslim_block_fwd", "reslim_head_fwd", "reslim_forward", "reslim_flop_counts",
            "reslim_debug_set_gemm_tile", "reslim_profile_enable", "reslim_profile_reset", "reslim_profile_read",
-           "reslim_debug_copy", "reslim_debug_set_attention_variant"]
+           "reslim_debug_copy", "reslim_debug_set_attention_variant",
+           "reslim_bayes_loss_workspace_bytes", "reslim_bayes_loss_fwd"]
 
 
 class ReslimConfigC(C.Structure):
@@ -89,6 +90,8 @@ def load() -> C.CDLL:
     lib.reslim_profile_reset.argtypes = [vp]
     lib.reslim_profile_read.argtypes = [vp, C.POINTER(ProfileRecord), i32, C.POINTER(i32)]
     lib.reslim_debug_copy.argtypes = [vp, vp, C.c_size_t, vp]
+    lib.reslim_bayes_loss_workspace_bytes.argtypes = [i32, i32, i32, i32, C.POINTER(C.c_size_t)]
+    lib.reslim_bayes_loss_fwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, C.c_float, vp, vp, C.c_size_t, vp]
     lib.reslim_debug_set_gemm_tile.argtypes = [i32]
     lib.reslim_debug_set_gemm_tile.restype = None
     lib.reslim_debug_set_attention_variant.argtypes = [i32]
@@ -171,6 +174,21 @@ def reslim_debug_copy(src, dst, stream=None) -> None:
     nbytes = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() == nbytes
     _check(load().reslim_debug_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream_ptr(stream)))
+
+
+def reslim_bayes_loss_workspace_bytes(batch: int, n_vars: int, Hf: int, Wf: int) -> int:
+    n = C.c_size_t(0)
+    _check(load().reslim_bayes_loss_workspace_bytes(batch, n_vars, Hf, Wf, C.byref(n)))
+    return int(n.value)
+
+
+def reslim_bayes_loss_fwd(pred, target, lat_w, tv_weight: float, out3, workspace, stream=None) -> None:
+    """pred, target: fp32 CUDA tensors [B, K, Hf, Wf]; lat_w: fp32 CUDA [Hf]; out3: float64 CUDA [3]
+    (total, data term, prior term); workspace: CUDA byte buffer of reslim_bayes_loss_workspace_bytes."""
+    b, k, hf, wf = pred.shape
+    _check(load().reslim_bayes_loss_fwd(pred.data_ptr(), target.data_ptr(), lat_w.data_ptr(), b, k, hf, wf,
+                                        float(tv_weight), out3.data_ptr(), workspace.data_ptr(),
+                                        workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
 
 
 def reslim_profile_enable(ctx: int, max_records: int) -> None:

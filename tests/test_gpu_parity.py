@@ -196,6 +196,43 @@ def test_forward_paper_model_sizes_sampled_tiles(name, tile_ids):
     _sampled_tile_parity(WL.CONFIGS[name], tile_ids)
 
 
+# ------------------------------------------------------------------ Bayesian loss (Sec. 4.1)
+@pytest.mark.parametrize("shape", [(4, 8, 512, 1024), (2, 3, 37, 53), (1, 2, 33, 1027), (1, 1, 1, 1), (1, 1, 1, 9),
+                                   (1, 1, 70, 1), (3, 1, 64, 2048)], ids=str)
+def test_bayes_loss_parity(shape):
+    """fp32 element arithmetic, fp64 accumulation: agrees with the fp64 oracle to 1e-5 relative
+    (a sum of n fp32-rounded terms of one sign carries about 6e-8 relative error per term)."""
+    rng = np.random.default_rng([5, shape[2], shape[3]])
+    pred = rng.normal(size=shape).astype(np.float32)
+    target = (pred + 0.3 * rng.normal(size=shape)).astype(np.float32)
+    lw = O.lat_weights(shape[2], -80.0, 85.0).astype(np.float32)
+    ref = O.bayes_loss(pred, target, lw, tv_weight=0.25)
+    out = torch.zeros(3, dtype=torch.float64, device="cuda")
+    ws = torch.empty(max(B.reslim_bayes_loss_workspace_bytes(*shape), 8), dtype=torch.uint8, device="cuda")
+    p, t, l = cuda(pred), cuda(target), cuda(lw)
+    B.reslim_bayes_loss_fwd(p, t, l, 0.25, out, ws)
+    got = out.cpu().numpy()
+    say(f"bayes loss {shape}: got {got}, oracle {np.array(ref)}")
+    for g, r in zip(got, ref):
+        assert abs(g - r) <= 1e-5 * abs(r) + 1e-12
+    out2 = torch.zeros(3, dtype=torch.float64, device="cuda")
+    B.reslim_bayes_loss_fwd(p, t, l, 0.25, out2, ws)
+    assert torch.equal(out, out2)                                   # deterministic
+    if pred.size >= 1 << 24:                                        # report the achieved bandwidth at full size
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            B.reslim_bayes_loss_fwd(p, t, l, 0.25, out2, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 20
+        say(f"bayes loss {shape}: {ms:.4f} ms per call, {2 * pred.nbytes / ms / 1e6:.0f} GB/s of algorithmic bytes (pred + target once)")
+    small = torch.empty(8, dtype=torch.uint8, device="cuda")
+    if B.reslim_bayes_loss_workspace_bytes(*shape) > 8:
+        with pytest.raises(B.ReslimError):
+            B.reslim_bayes_loss_fwd(p, t, l, 0.25, out, small)
+
+
 # ------------------------------------------------------------------ edge cases
 def test_edge_cases_and_errors():
     cfg = SMALL_BF16
