@@ -43,7 +43,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="c1", help="workload name (c0..c4, or m9m / m126m / m1b: the paper's model sizes); the headline metric is quoted on c1")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (developer runs)")
-    ap.add_argument("--gemm-tile", type=int, default=-1, help="pin the bf16 GEMM tile (0/1/2), -1 = heuristic")
+    ap.add_argument("--gemm-tile", type=int, default=-1, help="pin the bf16 GEMM kernel (2 = 128x128 tiles, 3 = persistent 256x256), -1 = heuristic")
     ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch the library's plain copy kernel on 1 GiB five times (yardstick for rocprofv3 byte counters)")

@@ -223,10 +223,9 @@ int reslim_bayes_loss_fwd(const float *pred, const float *target, const float *l
  * byte counters by what they report for this kernel of known size. */
 int reslim_debug_copy(const void *src, void *dst, size_t bytes, void *hip_stream);
 
-/* Tuning hook for benchmarks: pins the bf16 GEMM kernel (-1 = built-in heuristic;
- * one tile per work-group: 0 = 256x256, 1 = 256x128, 2 = 128x128; persistent
- * direct-to-LDS 256x256: 3 = two 64-deep stages, 4 = four 32-deep stages; add 100 for
- * columns-fastest tile order in kernels 0..2).  Process-wide. */
+/* Tuning hook for benchmarks: pins the bf16 GEMM kernel (-1 = built-in heuristic, 2 =
+ * one 128x128 tile per work-group, 3 = persistent direct-to-LDS 256x256 tiles; add 100
+ * to 2 for columns-fastest tile order; other values act like 2).  Process-wide. */
 void reslim_debug_set_gemm_tile(int choice);
 
 /* Tuning hook: launch shape of the bf16 tile-attention kernel at head dimension 64

@@ -13,6 +13,8 @@
 // the B operand (P^T) of the second MFMA, O^T = V^T P^T.  Online softmax in fp32
 // with base-2 exponentials; P is rounded to bf16 for PV.  Units are numbered so the
 // query blocks that share one K/V set run on one XCD (one L2).
+#include <type_traits>
+
 #include "common.h"
 
 namespace reslim {
@@ -52,6 +54,37 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 __device__ __forceinline__ void attn_dl_load16(const bf16_t *gsrc, unsigned char *lds_wave_base) {
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc,
                                    (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+}
+
+// The V^T fragments of one 32-key group at dh = 64: eight transposing reads issued by
+// hand.  As a compiler builtin the read is preceded by a wait for ALL outstanding
+// vector-memory operations (the compiler cannot tell that the direct-to-LDS loads in
+// flight fill the other stage), which would stall every key block until the next
+// block's prefetch has landed.  The reads are issued in one statement and waited for
+// in a second one, so independent work can be scheduled in between; LDS operations
+// complete in order, so the compiler's own LDS waits stay sufficient.
+struct VFrag64 { uint64_t r[2][2][2]; };      // [16-key half][feature block d][e]
+
+template <int OFF>
+__device__ __forceinline__ void v_frag_issue(VFrag64 &f, const unsigned (&a)[2][2]) {
+  asm volatile(
+      "ds_read_b64_tr_b16 %0, %8 offset:%12\n\t"
+      "ds_read_b64_tr_b16 %1, %9 offset:%12\n\t"
+      "ds_read_b64_tr_b16 %2, %10 offset:%12\n\t"
+      "ds_read_b64_tr_b16 %3, %11 offset:%12\n\t"
+      "ds_read_b64_tr_b16 %4, %8 offset:%13\n\t"
+      "ds_read_b64_tr_b16 %5, %9 offset:%13\n\t"
+      "ds_read_b64_tr_b16 %6, %10 offset:%13\n\t"
+      "ds_read_b64_tr_b16 %7, %11 offset:%13"
+      : "=&v"(f.r[0][0][0]), "=&v"(f.r[0][0][1]), "=&v"(f.r[0][1][0]), "=&v"(f.r[0][1][1]),
+        "=&v"(f.r[1][0][0]), "=&v"(f.r[1][0][1]), "=&v"(f.r[1][1][0]), "=&v"(f.r[1][1][1])
+      : "v"(a[0][0]), "v"(a[1][0]), "v"(a[0][1]), "v"(a[1][1]), "n"(OFF), "n"(OFF + 16 * 128));
+}
+
+__device__ __forceinline__ void v_frag_wait(VFrag64 &f) {
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(f.r[0][0][0]), "+v"(f.r[0][0][1]), "+v"(f.r[0][1][0]), "+v"(f.r[0][1][1]),
+                 "+v"(f.r[1][0][0]), "+v"(f.r[1][0][1]), "+v"(f.r[1][1][0]), "+v"(f.r[1][1][1]));
 }
 
 // ------------------------------------------------------------------ bf16 kernel
@@ -251,7 +284,16 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
       for (int kt = 0; kt < NKT; ++kt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));     // finite: every block holds a valid key
+      {
+        // Exchange between the two lane halves with v_permlane32_swap, not through LDS:
+        // an LDS lane permute makes the wave wait on the LDS counter, and that wait
+        // also covers the direct-to-LDS loads of the next block just issued (measured:
+        // the prefetch stops being asynchronous).  The swap returns (own, partner) in
+        // the lower half and (partner, own) in the upper half.
+        const unsigned u = __builtin_bit_cast(unsigned, mx);
+        const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+        mx = fmaxf(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1]));   // finite: every block holds a valid key
+      }
       if (!have_ref || __any(mx > TAU)) {
         // move this lane's reference up by d (first block: to the block maximum)
         const float d = have_ref ? fmaxf(mx, 0.f) : mx;
@@ -275,25 +317,63 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
         for (int r = 0; r < 16; ++r)
           s[kt][r] = __builtin_amdgcn_exp2f(QS ? s[kt][r] : s[kt][r] * c);
 
+      if constexpr (DH == 64) {
+        // LDS byte addresses of this lane's four fragment pointers in the current stage
+        const unsigned st_off = static_cast<unsigned>(reinterpret_cast<uintptr_t>(
+            (__attribute__((address_space(3))) const unsigned char *)st));
+        unsigned va[2][2];
 #pragma unroll
-      for (int kt = 0; kt < NKT; ++kt) {
+        for (int e = 0; e < 2; ++e)
 #pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2) {
-          bf16x8 pf;
+          for (int d = 0; d < 2; ++d) va[e][d] = st_off + static_cast<unsigned>(v_addr[e][d]);
+        auto group = [&](auto kt_c) {
+          constexpr int kt = decltype(kt_c)::value;
+          VFrag64 vf;
+          v_frag_issue<kt * 32 * ROWB>(vf, va);
+          bf16x8 pf[2];
 #pragma unroll
-          for (int e = 0; e < 8; ++e) pf[e] = static_cast<__bf16>(s[kt][8 * h2 + e]);
-          lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf, lsum, 0, 0, 0);
+          for (int h2 = 0; h2 < 2; ++h2)
 #pragma unroll
-          for (int d = 0; d < NDT; ++d) {
-            const unsigned char *vp = st + (kt * 32 + h2 * 16) * ROWB;
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (s16x4 __attribute__((address_space(3))) *)(vp + v_addr[0][d]));
-            const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (s16x4 __attribute__((address_space(3))) *)(vp + v_addr[1][d]));
-            typedef __attribute__((ext_vector_type(8))) short s16x8;
-            const s16x8 both = __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
-            const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
-            o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[d], 0, 0, 0);
+            for (int e = 0; e < 8; ++e) pf[h2][e] = static_cast<__bf16>(s[kt][8 * h2 + e]);
+          v_frag_wait(vf);
+#pragma unroll
+          for (int h2 = 0; h2 < 2; ++h2) {
+            lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf[h2], lsum, 0, 0, 0);
+#pragma unroll
+            for (int d = 0; d < 2; ++d) {
+              typedef __attribute__((ext_vector_type(2))) uint64_t u64x2;
+              const u64x2 both = {vf.r[h2][d][0], vf.r[h2][d][1]};
+              o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[h2], o[d], 0, 0, 0);
+            }
+          }
+        };
+        group(std::integral_constant<int, 0>{});
+        group(std::integral_constant<int, 1>{});
+        if constexpr (NKT == 4) {
+          group(std::integral_constant<int, 2>{});
+          group(std::integral_constant<int, 3>{});
+        }
+      } else {
+#pragma unroll
+        for (int kt = 0; kt < NKT; ++kt) {
+#pragma unroll
+          for (int h2 = 0; h2 < 2; ++h2) {
+            bf16x8 pf;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pf[e] = static_cast<__bf16>(s[kt][8 * h2 + e]);
+            lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf, lsum, 0, 0, 0);
+#pragma unroll
+            for (int d = 0; d < NDT; ++d) {
+              const unsigned char *vp = st + (kt * 32 + h2 * 16) * ROWB;
+              const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                  (s16x4 __attribute__((address_space(3))) *)(vp + v_addr[0][d]));
+              const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                  (s16x4 __attribute__((address_space(3))) *)(vp + v_addr[1][d]));
+              typedef __attribute__((ext_vector_type(8))) short s16x8;
+              const s16x8 both = __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+              const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
+              o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[d], 0, 0, 0);
+            }
           }
         }
       }

@@ -403,15 +403,12 @@ static hipError_t launch_bf16_tc(GemmArgs g, hipStream_t st) {
   return hipGetLastError();
 }
 
-typedef TileCfg<256, 256, 64, 2, 2, 2, 1> TileBig;     // 128x128 per wave, 144 KB LDS, 1 WG / CU
-typedef TileCfg<256, 128, 64, 2, 2, 1, 2> TileWide;    // 128x64 per wave, 54 KB LDS, 2 WG / CU
 typedef TileCfg<128, 128, 64, 2, 2, 1, 3> TileSmall;   // 64x64 per wave, 36 KB LDS, 3 WG / CU
 
 typedef DlCfg<4, 2, 64, 2> DlA;          // persistent 256x256, 8 waves of 64x128, 2 x 64 KB slabs in LDS
-typedef DlCfg<2, 4, 32, 4> DlB;          // same tile, 4 x 32 KB slabs (three in flight)
 
 static int g_col_fast = 0;
-static int g_gemm_tile_override = -1;   // test / tuning hook: 0 big, 1 wide, 2 small, 3/4 direct-to-LDS
+static int g_gemm_tile_override = -1;   // test / tuning hook: 2 = 128x128 tiles, 3 = persistent direct-to-LDS
 
 template <int EPI>
 static hipError_t launch_bf16(GemmArgs g, hipStream_t st) {
@@ -421,13 +418,12 @@ static hipError_t launch_bf16(GemmArgs g, hipStream_t st) {
   // epilogue (residual read-modify-write, GELU) behind other groups' MFMAs.
   const long tiles_big = static_cast<long>((g.M + 255) / 256) * ((g.N + 255) / 256);
   int choice = 2;
-  if (tiles_big >= 2L * g_num_cus && (g.K >= 1024 || EPI == EPI_BIAS_ACT || EPI == EPI_BIAS_QSCALE_ACT)) choice = 3;
+  const bool light_epilogue = EPI == EPI_BIAS_ACT || EPI == EPI_BIAS_QSCALE_ACT;
+  const bool rmw_epilogue = EPI == EPI_BIAS_RESADD_F32;      // the persistent kernel cannot hide it behind other groups
+  if (tiles_big >= 2L * g_num_cus && (light_epilogue || g.K >= (rmw_epilogue ? 2048 : 1024))) choice = 3;
   if (g_gemm_tile_override >= 0) choice = g_gemm_tile_override;
   switch (choice) {
-    case 0: return launch_bf16_tc<TileBig, EPI>(g, st);
-    case 1: return launch_bf16_tc<TileWide, EPI>(g, st);
     case 3: return launch_bf16_dl<DlA, EPI>(g, st);
-    case 4: return launch_bf16_dl<DlB, EPI>(g, st);
     default: return launch_bf16_tc<TileSmall, EPI>(g, st);
   }
 }
@@ -442,10 +438,7 @@ static hipError_t launch_f32(GemmArgs g, hipStream_t st) {
 template <int EPI>
 static hipError_t init_epi() {
   hipError_t e;
-  if ((e = set_attr<TileBig, EPI>()) != hipSuccess) return e;
-  if ((e = set_attr<TileWide, EPI>()) != hipSuccess) return e;
   if ((e = set_attr_dl<DlA, EPI>()) != hipSuccess) return e;
-  if ((e = set_attr_dl<DlB, EPI>()) != hipSuccess) return e;
   return set_attr<TileSmall, EPI>();
 }
 
@@ -494,8 +487,8 @@ hipError_t launch_gemm(int dtype, Epilogue epi, const void *A, const void *W, co
 
 }  // namespace reslim
 
-// tuning hook for the benchmark (not part of the documented ABI surface of the
-// method; selects the GEMM tile shape: -1 heuristic, 0 256x256, 1 256x128, 2 128x128)
+// tuning hook for the benchmark (not part of the method; selects the bf16 GEMM kernel:
+// -1 heuristic, 2 = 128x128 tiles, 3 = persistent 256x256; +100 = columns-fastest bands)
 extern "C" void reslim_debug_set_gemm_tile(int choice) {
   reslim::g_col_fast = choice >= 100 ? 1 : 0;   // 100 + c: choice c with columns-fastest bands
   reslim::g_gemm_tile_override = choice >= 100 ? choice - 100 : choice;
