@@ -136,7 +136,8 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
   static_assert(TILE_B % 4096 == 0 && 2 * STAGE <= 65536, "LDS plan");
   __shared__ __align__(1024) unsigned char smem[2 * STAGE];
 
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int t = threadIdx.x, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);   // uniform: keeps LDS destinations in scalar registers
   const int l32 = lane & 31, hi = lane >> 5;
   const int ld = 3 * a.D;
   const int G = gridDim.x;
@@ -177,24 +178,33 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
   bool has_next = vb < a.total;
 
   // ---- load side: lane -> (row of the block, 16-byte chunk), per-lane byte offsets
-  int ld_row[LPW], colK[LPW], colV[LPW];
+  int ld_row[LPW], offK[LPW], offV[LPW];
+  const int ld2 = ld * 2;
 #pragma unroll
   for (int i = 0; i < LPW; ++i) {
     ld_row[i] = (wave + 4 * i) * RPB + lane / CPR;
-    colK[i] = ((lane % CPR) ^ swzK(ld_row[i])) * 16;
-    colV[i] = ((lane % CPR) ^ swzV(ld_row[i])) * 16 + a.D * 2;
+    offK[i] = ld_row[i] * ld2 + ((lane % CPR) ^ swzK(ld_row[i])) * 16;
+    offV[i] = ld_row[i] * ld2 + ((lane % CPR) ^ swzV(ld_row[i])) * 16 + a.D * 2;
   }
-  const int ld2 = ld * 2;
   auto issue = [&](const Unit &u, int kv0, int buf) {
     unsigned char *sk = smem + buf * STAGE;
     const unsigned char *gk = reinterpret_cast<const unsigned char *>(u.base + a.D + static_cast<size_t>(kv0) * ld);
-    const int lim = u.n_t - 1 - kv0;     // rows past the tile end re-read its last row (finite, masked later)
+    const int lim = u.n_t - 1 - kv0;
+    if (lim >= BKV - 1) {                // whole block inside the tile (uniform): offsets need no arithmetic
 #pragma unroll
-    for (int i = 0; i < LPW; ++i) {
-      const int ro = min(ld_row[i], lim) * ld2;
-      attn_dl_load16(reinterpret_cast<const bf16_t *>(gk + static_cast<uint32_t>(ro + colK[i])), sk + (wave + 4 * i) * 1024);
-      attn_dl_load16(reinterpret_cast<const bf16_t *>(gk + static_cast<uint32_t>(ro + colV[i])),
-                     sk + TILE_B + (wave + 4 * i) * 1024);
+      for (int i = 0; i < LPW; ++i) {
+        attn_dl_load16(reinterpret_cast<const bf16_t *>(gk + static_cast<uint32_t>(offK[i])), sk + (wave + 4 * i) * 1024);
+        attn_dl_load16(reinterpret_cast<const bf16_t *>(gk + static_cast<uint32_t>(offV[i])),
+                       sk + TILE_B + (wave + 4 * i) * 1024);
+      }
+    } else {                             // rows past the tile end re-read its last row (finite, masked later)
+#pragma unroll
+      for (int i = 0; i < LPW; ++i) {
+        const int back = max(ld_row[i] - lim, 0) * ld2;
+        attn_dl_load16(reinterpret_cast<const bf16_t *>(gk + static_cast<uint32_t>(offK[i] - back)), sk + (wave + 4 * i) * 1024);
+        attn_dl_load16(reinterpret_cast<const bf16_t *>(gk + static_cast<uint32_t>(offV[i] - back)),
+                       sk + TILE_B + (wave + 4 * i) * 1024);
+      }
     }
   };
   bf16x8 qf[NKS];
