@@ -62,8 +62,12 @@ def main() -> int:
         print("bench.py: no GPU visible; there is no CPU path", file=sys.stderr)
         return 2
     cfg = WL.CONFIGS[args.config]
-    w = WL.make_weights(cfg)
+    big = cfg.depth * cfg.embed_dim ** 2 > 1 << 28      # minutes of host work: say what is going on
+    note = (lambda m: print("bench.py: " + m, file=sys.stderr, flush=True)) if big else None
+    w = WL.make_weights(cfg, progress=note)
     x_host = WL.make_fields(cfg)
+    if note:
+        note("creating the context (weights to bf16, upload)")
     B.reslim_debug_set_gemm_tile(args.gemm_tile)
     model = B.Reslim(cfg, w)
     x = torch.from_numpy(x_host).cuda()

@@ -515,6 +515,11 @@ hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *ou
     } else if (c->dh == 128) {
       if (q_prescaled) tiles_attention_bf16_kernel<128, 64, true, 2><<<dim3(pg2), dim3(256), 0, st>>>(a);
       else tiles_attention_bf16_kernel<128, 64, false, 2><<<dim3(pg2), dim3(256), 0, st>>>(a);
+    } else if (c->dh == 256) {
+      // 128 output-accumulator and 64 query-fragment registers per lane: one work-group per CU
+      const int pg1 = a.total < g_attn_cus ? a.total : g_attn_cus;
+      if (q_prescaled) tiles_attention_bf16_kernel<256, 32, true, 1><<<dim3(pg1), dim3(256), 0, st>>>(a);
+      else tiles_attention_bf16_kernel<256, 32, false, 1><<<dim3(pg1), dim3(256), 0, st>>>(a);
     } else {
       return hipErrorInvalidValue;
     }

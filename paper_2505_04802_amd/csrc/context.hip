@@ -79,7 +79,7 @@ static int validate(const reslim_config &g, std::string &why) {
   if (g.dtype == RESLIM_BF16) {
     const int dh = g.embed_dim / g.heads;
     if (g.embed_dim % 64) return bad("bf16 path needs embed_dim % 64 == 0");
-    if (dh != 64 && dh != 128) return bad("bf16 path needs head dim 64 or 128");
+    if (dh != 64 && dh != 128 && dh != 256) return bad("bf16 path needs head dim 64, 128 or 256");
   }
   if (static_cast<int64_t>(g.scale) * g.H > INT32_MAX / 2 || static_cast<int64_t>(g.scale) * g.W > INT32_MAX / 2)
     return bad("fine grid too large");

@@ -89,7 +89,7 @@ CONFIGS: Dict[str, ReslimConfig] = {
     # The paper's own model sizes (Sec. 5, "Model Configuration") on the 112 -> 28 km task
     # of Table 1 ([180, 360, 23] in, [720, 1440, 3] out), one hourly sample, 16 tiles
     # (the tiling of the inference-speed table).  The halo width is not stated: 2 patches.
-    # The 10B model (head dimension 256) is not instantiated.
+    # The 10B model holds 17.7 GB of bf16 weights (35 GB as generated in fp32 on the host).
     "m9m": ReslimConfig("m9m", batch=1, in_vars=23, out_vars=3, H=180, W=360, scale=4, patch=2,
                         embed_dim=256, heads=4, mlp_ratio=4, depth=6,
                         tiles_y=4, tiles_x=4, halo=2),
@@ -99,6 +99,9 @@ CONFIGS: Dict[str, ReslimConfig] = {
     "m1b": ReslimConfig("m1b", batch=1, in_vars=23, out_vars=3, H=180, W=360, scale=4, patch=2,
                         embed_dim=3072, heads=24, mlp_ratio=4, depth=8,
                         tiles_y=4, tiles_x=4, halo=2),
+    "m10b": ReslimConfig("m10b", batch=1, in_vars=23, out_vars=3, H=180, W=360, scale=4, patch=2,
+                         embed_dim=8192, heads=32, mlp_ratio=4, depth=11,
+                         tiles_y=4, tiles_x=4, halo=2),
 }
 
 
@@ -106,10 +109,14 @@ CONFIGS: Dict[str, ReslimConfig] = {
 def round_to_bf16(a: np.ndarray) -> np.ndarray:
     """Round fp32 values to the nearest bfloat16 (ties to even); result stays fp32."""
     a = np.ascontiguousarray(a, dtype=np.float32)
-    u = a.view(np.uint32).astype(np.uint64)
-    lsb = (u >> 16) & 1
-    u = (u + 0x7FFF + lsb) & 0xFFFF0000
-    return u.astype(np.uint32).view(np.float32).reshape(a.shape)
+    out = np.empty(a.size, dtype=np.uint32)
+    flat = a.reshape(-1).view(np.uint32)
+    step = 1 << 26                                   # bounded temporaries for multi-GB tensors
+    for i in range(0, flat.size, step):
+        u = flat[i:i + step].astype(np.uint64)
+        lsb = (u >> 16) & 1
+        out[i:i + step] = ((u + 0x7FFF + lsb) & 0xFFFF0000).astype(np.uint32)
+    return out.view(np.float32).reshape(a.shape)
 
 
 # --------------------------------------------------------------------------- fields
@@ -183,13 +190,17 @@ def weight_shapes(cfg: ReslimConfig) -> Dict[str, tuple]:
 _BF16_ROUNDED = ("agg_wo", "w_qkv", "w_proj", "w_fc1", "w_fc2", "w_head")
 
 
-def make_weights(cfg: ReslimConfig, std: float = 0.02) -> Dict[str, np.ndarray]:
+def make_weights(cfg: ReslimConfig, std: float = 0.02, progress=None) -> Dict[str, np.ndarray]:
     """All parameters ~ truncated normal(std); LayerNorm gains are 1 + that, so a
     dropped gain or shift shows up in parity.  `out_var_idx` selects which input
-    variables feed the residual path (identity selection for the five configs)."""
+    variables feed the residual path (identity selection for the five configs).
+    `progress`, if given, is called with one line of text per tensor (multi-GB models
+    take minutes to generate)."""
     rng = np.random.default_rng([cfg.seed, 1])
     w: Dict[str, np.ndarray] = {}
     for name, shape in weight_shapes(cfg).items():
+        if progress is not None:
+            progress(f"weights: {name} {shape}")
         t = _trunc_normal(rng, shape, std)
         if name in ("ln1_g", "ln2_g", "lnf_g"):
             t = (t + np.float32(1.0)).astype(np.float32)

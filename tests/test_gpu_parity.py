@@ -41,6 +41,8 @@ SMALL_BF16 = WL.ReslimConfig("sbf", batch=2, in_vars=3, out_vars=3, H=44, W=60, 
                              halo=2, dtype=1, seed=12)       # dh = 64, n_t = 13*17 .. -> 221..285 tokens
 SMALL_BF16_DH128 = SMALL_BF16.with_(name="sbf128", embed_dim=256, heads=2, H=40, W=48, tiles_y=1, tiles_x=2,
                                     halo=3, seed=13)        # dh = 128, n_t = 20*15 = 300
+SMALL_BF16_DH256 = SMALL_BF16.with_(name="sbf256", embed_dim=512, heads=2, H=36, W=52, tiles_y=2, tiles_x=1,
+                                    halo=2, seed=14)        # dh = 256 (the 10B model's head size), n_t = 11*26 = 286
 
 
 def weights_for(cfg, std=0.02):
@@ -51,7 +53,7 @@ def weights_for(cfg, std=0.02):
 
 
 # ------------------------------------------------------------------ tile attention
-@pytest.mark.parametrize("cfg", [SMALL_F32, SMALL_BF16, SMALL_BF16_DH128], ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", [SMALL_F32, SMALL_BF16, SMALL_BF16_DH128, SMALL_BF16_DH256], ids=lambda c: c.name)
 @pytest.mark.parametrize("peaked", [False, True])
 def test_tiles_attention_parity(cfg, peaked):
     say(f"attention parity {cfg.name} peaked={peaked}")
@@ -91,7 +93,7 @@ def test_tiles_attention_special_cases_bf16():
 
 
 # ------------------------------------------------------------------ embed / block / head
-@pytest.mark.parametrize("cfg", [SMALL_F32, SMALL_BF16, SMALL_BF16_DH128], ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", [SMALL_F32, SMALL_BF16, SMALL_BF16_DH128, SMALL_BF16_DH256], ids=lambda c: c.name)
 def test_stage_by_stage_parity(cfg):
     """Every entry point against the oracle's intermediate of the same name; the
     weights are spread wide (std 0.1) so softmaxes and GELUs are far from linear."""
@@ -194,6 +196,12 @@ def test_forward_paper_model_sizes_sampled_tiles(name, tile_ids):
     """The paper's 9.5M / 126M / 1B model sizes (Sec. 5) on the [180,360,23] -> [720,1440,3]
     task, 16 tiles: more input than output variables, head dimensions 64 and 128."""
     _sampled_tile_parity(WL.CONFIGS[name], tile_ids)
+
+
+def test_forward_10b_width_one_block_sampled_tile():
+    """The 10B model's width (embed dim 8192, 32 heads of dimension 256) with ONE of its 11
+    blocks, so the oracle stays within a minute; the blocks are copies of the same kernels."""
+    _sampled_tile_parity(WL.CONFIGS["m10b"].with_(name="m10b_L1", depth=1), [9])
 
 
 # ------------------------------------------------------------------ Bayesian loss (Sec. 4.1)
