@@ -27,10 +27,10 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 # profiles/), keyed by (workload, kernel label); None where not measured.
 # Source: profiles/forward_c1_all_kernels.md (fetched + written, scaled by the copy kernel).
 MEASURED_TRAFFIC = {
-    ("c1", "gemm_fc1"): 156.4e6 + 236.8e6,
-    ("c1", "gemm_fc2"): 335.5e6 + 89.7e6,
-    ("c1", "tiles_attention"): 160.7e6 + 43.6e6,
-    ("c1", "gemm_qkv"): 98.3e6 + 147.9e6,
+    ("c1", "gemm_fc1"): 153.8e6 + 238.0e6,
+    ("c1", "gemm_fc2"): 335.8e6 + 89.5e6,
+    ("c1", "tiles_attention"): 159.8e6 + 43.6e6,
+    ("c1", "gemm_qkv"): 98.3e6 + 146.4e6,
     ("c1", "gemm_proj"): 140.6e6 + 90.1e6,
     ("c1", "layernorm"): 85.7e6 + 42.8e6,
 }
