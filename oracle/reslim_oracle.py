@@ -142,6 +142,48 @@ def tiles_attention(qkv, tiles: Sequence[dict], heads: int):
     return out
 
 
+def self_attention_bwd(q, k, v, d_out, heads: int):
+    """Gradient of self_attention (one token set) with respect to q, k, v for an
+    upstream gradient d_out of its output -- the chain rule written out (training of
+    the model of Sec. 4.1 needs it; the paper gives no formula of its own):
+        P = softmax(S), S = Q K^T / sqrt(dh), O = P V
+        dV = P^T dO,   dP = dO V^T,   dS_ij = P_ij (dP_ij - sum_l P_il dP_il),
+        dQ = dS K / sqrt(dh),   dK = dS^T Q / sqrt(dh).
+    Returns (dq, dk, dv), each [n, D]."""
+    q, k, v, d_out = (np.asarray(a, F64) for a in (q, k, v, d_out))
+    n, D = q.shape
+    dh = D // heads
+    dq, dk, dv = np.empty((n, D), F64), np.empty((n, D), F64), np.empty((n, D), F64)
+    sc = 1.0 / math.sqrt(dh)
+    for g in range(heads):
+        c = slice(g * dh, (g + 1) * dh)
+        p = softmax(q[:, c] @ k[:, c].T * sc, axis=-1)
+        dv[:, c] = p.T @ d_out[:, c]
+        dp = d_out[:, c] @ v[:, c].T
+        ds = p * (dp - (p * dp).sum(axis=-1, keepdims=True))
+        dq[:, c] = ds @ k[:, c] * sc
+        dk[:, c] = ds.T @ q[:, c] * sc
+    return dq, dk, dv
+
+
+def tiles_attention_bwd(qkv, d_out, tiles: Sequence[dict], heads: int):
+    """Gradient of tiles_attention: tiles do not interact (Sec. 4.2), so it is the
+    per-tile gradient.  qkv: [B, n_h, 3*D]; d_out: [B, n_h, D]; returns d_qkv
+    [B, n_h, 3*D] with the same (q | k | v) column order."""
+    qkv = np.asarray(qkv, F64)
+    d_out = np.asarray(d_out, F64)
+    B, n_h, D3 = qkv.shape
+    D = D3 // 3
+    d_qkv = np.empty((B, n_h, D3), F64)
+    for b in range(B):
+        for t in tiles:
+            r = slice(t["tok_off"], t["tok_off"] + t["n_tok"])
+            blk = qkv[b, r]
+            dq, dk, dv = self_attention_bwd(blk[:, :D], blk[:, D:2 * D], blk[:, 2 * D:], d_out[b, r], heads)
+            d_qkv[b, r, :D], d_qkv[b, r, D:2 * D], d_qkv[b, r, 2 * D:] = dq, dk, dv
+    return d_qkv
+
+
 def block_tokens(X, w: Dict[str, np.ndarray], layer: int, heads: int):
     """One pre-LN transformer block on ONE token set X[n, D]."""
     X = np.asarray(X, F64)

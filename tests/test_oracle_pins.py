@@ -398,3 +398,41 @@ def test_bayes_loss_closed_forms():
     x = np.zeros((1, 1, H, W)); x[0, 0, 0, 0] = 1.0
     _, _, prior = O.bayes_loss(x, x, lw)
     assert abs(prior - 2 * (2 / norm + 1 / (math.sqrt(2) * norm)) / (H * W)) < 1e-13
+
+
+# ------------------------------------------------------------------ attention gradient
+def test_tiles_attention_bwd_vs_autograd_and_finite_differences():
+    """The hand-written chain rule against PyTorch CPU autograd through its own
+    scaled_dot_product_attention (an independent implementation), against central finite
+    differences of the oracle's forward, and two invariants."""
+    rng = np.random.default_rng(21)
+    heads, D = 3, 24
+    tiles, _, _, n_h = O.tiles_partition(5, 7, 2, 2, 1)
+    qkv = rng.normal(size=(2, n_h, 3 * D))
+    d_out = rng.normal(size=(2, n_h, D))
+    got = O.tiles_attention_bwd(qkv, d_out, tiles, heads)
+    # autograd, tile by tile
+    ref = np.zeros_like(got)
+    for b in range(2):
+        for t in tiles:
+            r = slice(t["tok_off"], t["tok_off"] + t["n_tok"])
+            x = torch.tensor(qkv[b, r], dtype=torch.float64, requires_grad=True)
+            q, k, v = (x[:, i * D:(i + 1) * D].reshape(-1, heads, D // heads).transpose(0, 1) for i in range(3))
+            o = F.scaled_dot_product_attention(q, k, v).transpose(0, 1).reshape(-1, D)
+            o.backward(torch.tensor(d_out[b, r]))
+            ref[b, r] = x.grad.numpy()
+    assert np.allclose(got, ref, rtol=1e-10, atol=1e-12)
+    # finite differences of the oracle's own forward on a few coordinates
+    loss = lambda z: float((O.tiles_attention(z, tiles, heads) * d_out).sum())
+    for idx in [(0, 0, 0), (1, 7, D + 5), (0, n_h - 1, 2 * D + 23), (1, 3, 11)]:
+        zp, zm = qkv.copy(), qkv.copy()
+        zp[idx] += 1e-6
+        zm[idx] -= 1e-6
+        assert abs((loss(zp) - loss(zm)) / 2e-6 - got[idx]) < 1e-6
+    # softmax is shift invariant: the gradient with respect to q is orthogonal to ... the key mean
+    # direction; concretely sum_j dS_ij = 0, so adding a constant vector to every key changes nothing
+    shift = np.zeros_like(qkv)
+    shift[..., D:2 * D] = rng.normal(size=(1, 1, D))
+    assert np.allclose(O.tiles_attention(qkv + shift, tiles, heads), O.tiles_attention(qkv, tiles, heads), atol=1e-10)
+    # dV of a tile depends on d_out only through P^T d_out: zero upstream gradient gives zero
+    assert not O.tiles_attention_bwd(qkv, np.zeros_like(d_out), tiles, heads).any()
