@@ -152,6 +152,13 @@ int reslim_embed_fwd(reslim_ctx *ctx, const float *x, float *tokens, int32_t bat
 int tiles_attention_fwd(reslim_ctx *ctx, const void *qkv, void *out, int32_t batch,
                         void *hip_stream);
 
+/* The same attention, also returning what its gradient needs (training of the
+ * model of Sec. 4.1): lse[b, g, i] = log sum_j exp(q_i . k_j / sqrt(dh)) over the keys
+ * of query i's tile, natural logarithm.
+ *   lse dev float [batch, heads, n_h] out */
+int tiles_attention_fwd_lse(reslim_ctx *ctx, const void *qkv, void *out, float *lse, int32_t batch,
+                            void *hip_stream);
+
 /* One pre-LayerNorm transformer block `layer` (0-based) on the tile-major stream:
  * X += proj(tile_attention(qkv(LN1(X)))); X += fc2(gelu(fc1(LN2(X)))).
  *   x_inout dev float [batch, n_h, D], updated in place */

@@ -142,6 +142,24 @@ def tiles_attention(qkv, tiles: Sequence[dict], heads: int):
     return out
 
 
+def tiles_attention_lse(qkv, tiles: Sequence[dict], heads: int):
+    """Natural log of the softmax denominator of every query and head,
+    log sum_j exp(q_i . k_j / sqrt(dh)) over the keys of query i's tile: [B, heads, n_h]."""
+    qkv = np.asarray(qkv, F64)
+    B, n_h, D3 = qkv.shape
+    D = D3 // 3
+    dh = D // heads
+    out = np.empty((B, heads, n_h), F64)
+    for b in range(B):
+        for t in tiles:
+            r = slice(t["tok_off"], t["tok_off"] + t["n_tok"])
+            for g in range(heads):
+                s = qkv[b, r, g * dh:(g + 1) * dh] @ qkv[b, r, D + g * dh:D + (g + 1) * dh].T / math.sqrt(dh)
+                m = s.max(axis=-1)
+                out[b, g, r] = m + np.log(np.exp(s - m[:, None]).sum(axis=-1))
+    return out
+
+
 def self_attention_bwd(q, k, v, d_out, heads: int):
     """Gradient of self_attention (one token set) with respect to q, k, v for an
     upstream gradient d_out of its output -- the chain rule written out (training of

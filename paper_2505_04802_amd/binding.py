@@ -30,7 +30,7 @@ EXPORTS = ["tiles_partition", "reslim_create", "reslim_destroy", "reslim_last_er
            "reslim_block_fwd", "reslim_head_fwd", "reslim_forward", "reslim_flop_counts",
            "reslim_debug_set_gemm_tile", "reslim_profile_enable", "reslim_profile_reset", "reslim_profile_read",
            "reslim_debug_copy", "reslim_debug_set_attention_variant",
-           "reslim_bayes_loss_workspace_bytes", "reslim_bayes_loss_fwd"]
+           "reslim_bayes_loss_workspace_bytes", "reslim_bayes_loss_fwd", "tiles_attention_fwd_lse"]
 
 
 class ReslimConfigC(C.Structure):
@@ -81,6 +81,7 @@ def load() -> C.CDLL:
     lib.reslim_workspace_bytes.argtypes = [vp, i32, szp]
     lib.reslim_embed_fwd.argtypes = [vp, vp, vp, i32, vp, C.c_size_t, vp]
     lib.tiles_attention_fwd.argtypes = [vp, vp, vp, i32, vp]
+    lib.tiles_attention_fwd_lse.argtypes = [vp, vp, vp, vp, i32, vp]
     lib.reslim_block_fwd.argtypes = [vp, i32, vp, i32, vp, C.c_size_t, vp]
     lib.reslim_head_fwd.argtypes = [vp, vp, vp, vp, i32, vp, C.c_size_t, vp]
     lib.reslim_forward.argtypes = [vp, vp, vp, i32, vp, C.c_size_t, vp]
@@ -218,6 +219,10 @@ def _stream_ptr(stream=None) -> int:
 def reslim_embed_fwd(ctx, x, tokens, batch, workspace, stream=None):
     _check(load().reslim_embed_fwd(ctx, x.data_ptr(), tokens.data_ptr(), batch, workspace.data_ptr(),
                                    workspace.numel() * workspace.element_size(), _stream_ptr(stream)), ctx)
+
+
+def tiles_attention_fwd_lse(ctx, qkv, out, lse, batch, stream=None):
+    _check(load().tiles_attention_fwd_lse(ctx, qkv.data_ptr(), out.data_ptr(), lse.data_ptr(), batch, _stream_ptr(stream)), ctx)
 
 
 def tiles_attention_fwd(ctx, qkv, out, batch, stream=None):

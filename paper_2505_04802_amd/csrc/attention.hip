@@ -32,6 +32,7 @@ struct AttnArgs {
   int T, heads, D, QB, total;
   int64_t n_h;
   float scale_log2;   // log2(e) / sqrt(dh)
+  float *lse;         // optional [batch, heads, n_h]: natural log of each query's softmax denominator
 };
 
 __device__ __forceinline__ int xcd_remap_attn(int pid, int total) {
@@ -147,7 +148,7 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
   };
 
   // ---- work units (all of this is uniform over the work-group)
-  struct Unit { int n_t, q0, nkb; const bf16_t *base; bf16_t *out; };
+  struct Unit { int n_t, q0, nkb; const bf16_t *base; bf16_t *out; float *lse; };
   auto decode = [&](int vb, Unit &u) -> int {      // first non-empty unit at or after vb (stride G), or >= total
     while (vb < a.total) {
       const int logical = xcd_remap_attn(vb, a.total);
@@ -165,6 +166,7 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
         u.nkb = (n_t + BKV - 1) / BKV;
         u.base = static_cast<const bf16_t *>(a.qkv) + row0 * ld + head * DH;
         u.out = static_cast<bf16_t *>(a.out) + row0 * a.D + head * DH;
+        u.lse = a.lse ? a.lse + (static_cast<size_t>(b) * a.heads + head) * a.n_h + a.tiles[tile].tok_off : nullptr;
         return vb;
       }
       vb += G;
@@ -394,6 +396,8 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
     const int qrow = cur.q0 + wave * 32 + l32;
     if (active && qrow < cur.n_t) {
       const float inv = 1.0f / lsum[0];     // every row of the all-ones block carries the full sum over keys
+      // log-sum-exp of the logits (kept for the gradient): reference + log of the sum
+      if (cur.lse && hi == 0) cur.lse[qrow] = (__builtin_amdgcn_logf(lsum[0]) - minit[0] * c) * 0.69314718055994531f;
       bf16_t *op = cur.out + static_cast<size_t>(qrow) * a.D + hi * 4;
 #pragma unroll
       for (int d = 0; d < NDT; ++d)
@@ -465,6 +469,7 @@ __global__ __launch_bounds__(128) void tiles_attention_f32_kernel(AttnArgs a, in
     __syncthreads();
   }
   const float inv = 1.0f / red[0];
+  if (a.lse && t == 0) a.lse[(static_cast<size_t>(b) * a.heads + head) * a.n_h + tok] = mx + logf(red[0]);
   float *orow = static_cast<float *>(a.out) + (static_cast<size_t>(b) * a.n_h + tok) * a.D + head * dh;
   for (int d = t; d < dh; d += 128) {
     const float *vc = base + 2 * a.D + d;
@@ -487,10 +492,11 @@ hipError_t attention_init() {
 bool attention_accepts_prescaled_q() { return true; }
 
 hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *out, int batch, bool q_prescaled,
-                                  hipStream_t st) {
+                                  hipStream_t st, float *lse) {
   AttnArgs a;
   a.qkv = qkv;
   a.out = out;
+  a.lse = lse;
   a.tiles = c->d_tiles;
   a.T = c->T;
   a.heads = c->cfg.heads;

@@ -120,7 +120,7 @@ hipError_t launch_gather_rows(const float *z, const int32_t *gather, float *X, i
 hipError_t launch_embed_agg(const reslim_ctx *c, const float *x, void *o, int batch, hipStream_t st);
 // q_prescaled: q already carries the factor log2(e)/sqrt(dh) (bf16 path only)
 hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *out, int batch, bool q_prescaled,
-                                  hipStream_t st);
+                                  hipStream_t st, float *lse = nullptr);
 bool attention_accepts_prescaled_q();
 hipError_t attention_init();
 hipError_t elementwise_init();

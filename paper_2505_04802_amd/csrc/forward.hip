@@ -206,6 +206,16 @@ extern "C" int tiles_attention_fwd(reslim_ctx *c, const void *qkv, void *out, in
   return RESLIM_OK;
 }
 
+extern "C" int tiles_attention_fwd_lse(reslim_ctx *c, const void *qkv, void *out, float *lse, int32_t batch, void *hip_stream) {
+  const char *fn = "tiles_attention_fwd_lse";
+  if (!c) return RESLIM_EINVAL;
+  if (!qkv || !out || !lse) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": null buffer");
+  int rc = check_common(c, fn, batch, nullptr, 0, false);
+  if (rc != RESLIM_OK) return rc;
+  RESLIM_TRY("launch", launch_tiles_attention(c, qkv, out, batch, false, static_cast<hipStream_t>(hip_stream), lse));
+  return RESLIM_OK;
+}
+
 extern "C" int reslim_embed_fwd(reslim_ctx *c, const float *x, float *tokens, int32_t batch, void *workspace, size_t ws_bytes, void *hip_stream) {
   const char *fn = "reslim_embed_fwd";
   if (!c) return RESLIM_EINVAL;

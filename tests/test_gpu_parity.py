@@ -70,6 +70,17 @@ def test_tiles_attention_parity(cfg, peaked):
     assert err <= TOL[cfg.dtype]
     if cfg.dtype == 1:      # element-wise: bf16 output rounding + bf16 P, well inside 3e-2 absolute for |v| ~ 1
         assert np.abs(out - ref).max() <= 3e-2
+    # the same call with the log-sum-exp output (what the gradient needs)
+    with B.Reslim(cfg, weights_for(cfg)) as m:
+        q_dev = cuda(qkv, m.act_dtype)
+        out2 = torch.empty((cfg.batch, n_h, cfg.embed_dim), dtype=m.act_dtype, device="cuda")
+        lse = torch.full((cfg.batch, cfg.heads, n_h), float("nan"), dtype=torch.float32, device="cuda")
+        B.tiles_attention_fwd_lse(m.ctx, q_dev, out2, lse, cfg.batch)
+        assert np.array_equal(out2.float().cpu().numpy(), out)
+        lse_ref = O.tiles_attention_lse(qkv, tiles, cfg.heads)
+        d = np.abs(lse.cpu().numpy() - lse_ref).max()
+        say(f"  lse max abs error {d:.3e}")
+        assert d <= (2e-2 if cfg.dtype == 1 else 1e-4)      # an absolute error of the LOG of the denominator
 
 
 def test_tiles_attention_special_cases_bf16():
