@@ -159,6 +159,26 @@ int tiles_attention_fwd(reslim_ctx *ctx, const void *qkv, void *out, int32_t bat
 int tiles_attention_fwd_lse(reslim_ctx *ctx, const void *qkv, void *out, float *lse, int32_t batch,
                             void *hip_stream);
 
+/* Gradient of the tile-local attention of Sec. 4.2 (the paper trains the model, Sec. 5;
+ * it prints no formula, this is the chain rule through softmax(Q K^T / sqrt(dh)) V
+ * within each tile; tiles do not interact, so neither do their gradients):
+ *   dV = P^T dO, dP = dO V^T, dS = P o (dP - rowsum(dO o O)),
+ *   dQ = dS K / sqrt(dh), dK = dS^T Q / sqrt(dh),
+ * with P recomputed from q, k and lse.
+ *   qkv   dev act   [batch, n_h, 3, heads, dh]   the forward's input
+ *   out   dev act   [batch, n_h, heads*dh]       the forward's output
+ *   lse   dev float [batch, heads, n_h]          from tiles_attention_fwd_lse
+ *   d_out dev act   [batch, n_h, heads*dh]       gradient of the loss w.r.t. out
+ *   d_qkv dev act   [batch, n_h, 3, heads, dh]   out: gradient w.r.t. qkv, every element
+ *                                                written; must not alias an input
+ *   workspace dev, 256-byte aligned, >= tiles_attention_bwd_workspace_bytes(), caller-owned
+ * Work is enqueued on hip_stream; no allocation, no synchronisation; deterministic.
+ * Errors: RESLIM_EINVAL (null), RESLIM_ESHAPE (batch), RESLIM_EWORKSPACE, RESLIM_EHIP. */
+int tiles_attention_bwd_workspace_bytes(const reslim_ctx *ctx, int32_t batch, size_t *out);
+int tiles_attention_bwd(reslim_ctx *ctx, const void *qkv, const void *out, const float *lse,
+                        const void *d_out, void *d_qkv, int32_t batch, void *workspace,
+                        size_t ws_bytes, void *hip_stream);
+
 /* One pre-LayerNorm transformer block `layer` (0-based) on the tile-major stream:
  * X += proj(tile_attention(qkv(LN1(X)))); X += fc2(gelu(fc1(LN2(X)))).
  *   x_inout dev float [batch, n_h, D], updated in place */

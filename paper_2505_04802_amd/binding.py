@@ -30,7 +30,8 @@ EXPORTS = ["tiles_partition", "reslim_create", "reslim_destroy", "reslim_last_er
            "reslim_block_fwd", "reslim_head_fwd", "reslim_forward", "reslim_flop_counts",
            "reslim_debug_set_gemm_tile", "reslim_profile_enable", "reslim_profile_reset", "reslim_profile_read",
            "reslim_debug_copy", "reslim_debug_set_attention_variant",
-           "reslim_bayes_loss_workspace_bytes", "reslim_bayes_loss_fwd", "tiles_attention_fwd_lse"]
+           "reslim_bayes_loss_workspace_bytes", "reslim_bayes_loss_fwd", "tiles_attention_fwd_lse",
+           "tiles_attention_bwd_workspace_bytes", "tiles_attention_bwd"]
 
 
 class ReslimConfigC(C.Structure):
@@ -82,6 +83,8 @@ def load() -> C.CDLL:
     lib.reslim_embed_fwd.argtypes = [vp, vp, vp, i32, vp, C.c_size_t, vp]
     lib.tiles_attention_fwd.argtypes = [vp, vp, vp, i32, vp]
     lib.tiles_attention_fwd_lse.argtypes = [vp, vp, vp, vp, i32, vp]
+    lib.tiles_attention_bwd_workspace_bytes.argtypes = [vp, i32, szp]
+    lib.tiles_attention_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, C.c_size_t, vp]
     lib.reslim_block_fwd.argtypes = [vp, i32, vp, i32, vp, C.c_size_t, vp]
     lib.reslim_head_fwd.argtypes = [vp, vp, vp, vp, i32, vp, C.c_size_t, vp]
     lib.reslim_forward.argtypes = [vp, vp, vp, i32, vp, C.c_size_t, vp]
@@ -225,6 +228,18 @@ def tiles_attention_fwd_lse(ctx, qkv, out, lse, batch, stream=None):
     _check(load().tiles_attention_fwd_lse(ctx, qkv.data_ptr(), out.data_ptr(), lse.data_ptr(), batch, _stream_ptr(stream)), ctx)
 
 
+def tiles_attention_bwd_workspace_bytes(ctx, batch) -> int:
+    out = C.c_size_t(0)
+    _check(load().tiles_attention_bwd_workspace_bytes(ctx, batch, C.byref(out)), ctx)
+    return out.value
+
+
+def tiles_attention_bwd(ctx, qkv, out, lse, d_out, d_qkv, batch, workspace, stream=None):
+    _check(load().tiles_attention_bwd(ctx, qkv.data_ptr(), out.data_ptr(), lse.data_ptr(), d_out.data_ptr(),
+                                      d_qkv.data_ptr(), batch, workspace.data_ptr(),
+                                      workspace.numel() * workspace.element_size(), _stream_ptr(stream)), ctx)
+
+
 def tiles_attention_fwd(ctx, qkv, out, batch, stream=None):
     _check(load().tiles_attention_fwd(ctx, qkv.data_ptr(), out.data_ptr(), batch, _stream_ptr(stream)), ctx)
 
@@ -292,6 +307,28 @@ class Reslim:
         out = torch.empty((b, self.n_h, self.cfg.embed_dim), dtype=self.act_dtype, device="cuda")
         tiles_attention_fwd(self.ctx, qkv, out, b)
         return out
+
+    def attention_with_lse(self, qkv):
+        """Forward that also returns the log-sum-exp [b, heads, n_h] the gradient needs."""
+        import torch
+        b = self._batch(qkv)
+        assert qkv.dtype == self.act_dtype and qkv.shape[1:] == (self.n_h, 3 * self.cfg.embed_dim)
+        out = torch.empty((b, self.n_h, self.cfg.embed_dim), dtype=self.act_dtype, device="cuda")
+        lse = torch.empty((b, self.cfg.heads, self.n_h), dtype=torch.float32, device="cuda")
+        tiles_attention_fwd_lse(self.ctx, qkv, out, lse, b)
+        return out, lse
+
+    def attention_bwd(self, qkv, out, lse, d_out):
+        """Gradient of the tile attention with respect to qkv."""
+        import torch
+        b = self._batch(qkv)
+        assert qkv.dtype == self.act_dtype and d_out.dtype == self.act_dtype and out.dtype == self.act_dtype
+        assert qkv.shape[1:] == (self.n_h, 3 * self.cfg.embed_dim) and d_out.shape == out.shape == (b, self.n_h, self.cfg.embed_dim)
+        assert all(t.is_contiguous() for t in (qkv, out, lse, d_out))
+        ws = torch.empty(max(tiles_attention_bwd_workspace_bytes(self.ctx, b), 256), dtype=torch.uint8, device="cuda")
+        d_qkv = torch.empty_like(qkv)
+        tiles_attention_bwd(self.ctx, qkv, out, lse, d_out, d_qkv, b, ws)
+        return d_qkv
 
     def block(self, layer, tokens):
         b = self._batch(tokens)

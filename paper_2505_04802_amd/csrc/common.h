@@ -122,10 +122,39 @@ hipError_t launch_embed_agg(const reslim_ctx *c, const float *x, void *o, int ba
 hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *out, int batch, bool q_prescaled,
                                   hipStream_t st, float *lse = nullptr);
 bool attention_accepts_prescaled_q();
+// gradient of tile attention: d_qkv from qkv, the forward's out and lse, and d_out; ws as sized below
+hipError_t launch_tiles_attention_bwd(const reslim_ctx *c, const void *qkv, const void *out, const float *lse,
+                                      const void *dout, void *dqkv, int batch, void *ws, hipStream_t st);
+size_t tiles_attention_bwd_ws_bytes(const reslim_ctx *c, int batch);
+hipError_t attention_bwd_init();
 hipError_t attention_init();
 hipError_t elementwise_init();
 hipError_t launch_copy_probe(const void *src, void *dst, size_t bytes, hipStream_t st);
 hipError_t launch_residual_unpatchify(const reslim_ctx *c, const float *x, const void *P, int p_is_act,
                                       float *y, int batch, hipStream_t st);
 
+// ---- shared by the files that hold entry points -------------------------------
+int check_common(reslim_ctx *c, const char *fn, int batch, const void *ws, size_t ws_bytes, bool need_ws);
+int hip_fail(reslim_ctx *c, const char *fn, const char *what, hipError_t e);
+
 }  // namespace reslim
+
+#define RESLIM_TRY(what, expr)                                   \
+  do {                                                           \
+    hipError_t e_ = (expr);                                      \
+    if (e_ != hipSuccess) return hip_fail(c, fn, what, e_);      \
+  } while (0)
+
+// A launch with its algorithmic work attached; when profiling is on the launch is
+// bracketed by two pre-created events on the same stream.
+#define RESLIM_LAUNCH(label, flop_, bytes_, expr)                                      \
+  do {                                                                                 \
+    const size_t slot_ = c->prof_rec.size();                                           \
+    const bool p_ = c->prof_on && 2 * slot_ + 1 < c->prof_ev.size();                   \
+    if (p_) RESLIM_TRY("event", hipEventRecord(c->prof_ev[2 * slot_], st));            \
+    RESLIM_TRY(label, expr);                                                           \
+    if (p_) {                                                                          \
+      RESLIM_TRY("event", hipEventRecord(c->prof_ev[2 * slot_ + 1], st));              \
+      c->prof_rec.push_back({label, static_cast<double>(flop_), static_cast<double>(bytes_)}); \
+    }                                                                                  \
+  } while (0)

@@ -31,7 +31,12 @@ Workspace plan_workspace(const reslim_ctx *c, int batch, void *base) {
   return w;
 }
 
-static int check_common(reslim_ctx *c, const char *fn, int batch, const void *ws, size_t ws_bytes, bool need_ws) {
+
+int hip_fail(reslim_ctx *c, const char *fn, const char *what, hipError_t e) {
+  return set_error(c, RESLIM_EHIP, std::string(fn) + ": " + what + ": " + hipGetErrorString(e));
+}
+
+int check_common(reslim_ctx *c, const char *fn, int batch, const void *ws, size_t ws_bytes, bool need_ws) {
   if (batch < 1 || batch > 65535) return set_error(c, RESLIM_ESHAPE, std::string(fn) + ": batch must be in [1, 65535]");
   if (static_cast<int64_t>(batch) * c->n_h > INT32_MAX)
     return set_error(c, RESLIM_ESHAPE, std::string(fn) + ": batch * tokens exceeds int32 row indexing");
@@ -42,30 +47,6 @@ static int check_common(reslim_ctx *c, const char *fn, int batch, const void *ws
   }
   return RESLIM_OK;
 }
-
-static int hip_fail(reslim_ctx *c, const char *fn, const char *what, hipError_t e) {
-  return set_error(c, RESLIM_EHIP, std::string(fn) + ": " + what + ": " + hipGetErrorString(e));
-}
-
-#define RESLIM_TRY(what, expr)                                   \
-  do {                                                           \
-    hipError_t e_ = (expr);                                      \
-    if (e_ != hipSuccess) return hip_fail(c, fn, what, e_);      \
-  } while (0)
-
-// A launch with its algorithmic work attached; when profiling is on the launch is
-// bracketed by two pre-created events on the same stream.
-#define RESLIM_LAUNCH(label, flop_, bytes_, expr)                                      \
-  do {                                                                                 \
-    const size_t slot_ = c->prof_rec.size();                                           \
-    const bool p_ = c->prof_on && 2 * slot_ + 1 < c->prof_ev.size();                   \
-    if (p_) RESLIM_TRY("event", hipEventRecord(c->prof_ev[2 * slot_], st));            \
-    RESLIM_TRY(label, expr);                                                           \
-    if (p_) {                                                                          \
-      RESLIM_TRY("event", hipEventRecord(c->prof_ev[2 * slot_ + 1], st));              \
-      c->prof_rec.push_back({label, static_cast<double>(flop_), static_cast<double>(bytes_)}); \
-    }                                                                                  \
-  } while (0)
 
 static int embed_impl(reslim_ctx *c, const char *fn, const float *x, float *tokens, int batch, const Workspace &w, hipStream_t st) {
   const int D = c->cfg.embed_dim, dt = c->cfg.dtype;
