@@ -49,8 +49,8 @@ struct AttnBwdArgs {
   int T, heads, D, QB, total;
   int64_t n_h;
   int64_t aux_stride;    // records per array
-  float c;               // log2(e) / sqrt(dh)
-  float sc;              // 1 / sqrt(dh)
+  float c;               // MFMA output -> base-2 logit: log2(e) / sqrt(dh)   (1 when q is pre-scaled)
+  float scq, sck;        // output factors of dQ and dK: 1 / sqrt(dh) both; with pre-scaled q dK takes ln 2
 };
 
 __device__ __forceinline__ u32x4 split3_bf16(float x) {
@@ -71,7 +71,7 @@ __device__ __forceinline__ float join3_bf16(uint32_t w0, uint32_t w1) {
 template <int DH>
 __global__ __launch_bounds__(256) void attn_bwd_prep_bf16_kernel(const bf16_t *out, const bf16_t *dout, const float *lse,
                                                                  u32x4 *aux, int64_t n_vec, int64_t n_h, int heads,
-                                                                 int D, float sqrt_dh, int64_t aux_stride) {
+                                                                 int D, float lse_factor, int64_t aux_stride) {
   constexpr int LPH = DH / 8;   // lanes per head
   const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
   const bool live = idx < n_vec;
@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256) void attn_bwd_prep_bf16_kernel(const bf16_t *o
     const int64_t row = i / vpr;
     const int head = c8 / LPH;
     const int64_t rec = (row / n_h * heads + head) * n_h + row % n_h;
-    aux[rec] = split3_bf16(-lse[rec] * sqrt_dh);
+    aux[rec] = split3_bf16(-lse[rec] * lse_factor);
     aux[aux_stride + rec] = split3_bf16(-acc);
   }
 }
@@ -104,9 +104,19 @@ __device__ __forceinline__ uint64_t tr_issue(unsigned addr) {
   return r;
 }
 
-template <int DH, int BS, bool KV, int MINW>
+// MODE: 0 = query-stationary, dQ;  1 = key-stationary, dK and dV;  2 = key-stationary, dV only;
+// 3 = key-stationary, dK only (2 + 3 replace 1 where the accumulators of both do not fit the
+// register file next to the stationary fragments: dh = 128).
+// QS: q in qkv already carries the factor log2(e)/sqrt(dh) (as the fused QKV epilogue of the
+// block leaves it): the MFMA output is the base-2 logit itself.
+template <int DH, int BS, int MODE, bool QS, int MINW, int NST>
 __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a) {
-  constexpr int BX = 128;                 // stationary tokens per unit
+  constexpr bool KV = MODE != 0;          // keys stationary
+  constexpr bool DP = MODE != 2;          // dP = dO V^T is needed
+  constexpr bool A1 = MODE != 2;          // accumulator 1: Y1^T dS  (dQ^T | dK^T)
+  constexpr bool A2 = MODE == 1 || MODE == 2;   // accumulator 2: Y2^T P  (dV^T)
+  constexpr int NW = 4;
+  constexpr int BX = 32 * NW;             // stationary tokens per unit: 32 per wave
   constexpr int ROWB = DH * 2;
   constexpr int CPR = DH / 8;
   constexpr int RPB = 64 / CPR;
@@ -114,11 +124,12 @@ __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a)
   constexpr int AUXB = KV ? 2 * BS * 16 : 0;
   constexpr int AUXL = AUXB / 1024;       // wave-loads of the record block
   constexpr int STAGE = 2 * TILE_B + AUXB;
-  constexpr int LPW = TILE_B / 1024 / 4;
+  constexpr int LPW = TILE_B / 1024 / NW;
   constexpr int NKT = BS / 32, NKS = DH / 16, NDT = DH / 32;
   constexpr bool HAND = DH == 64;         // transposing reads issued by hand (see attention_common.h)
-  static_assert(TILE_B % 4096 == 0 && AUXB % 1024 == 0 && 2 * STAGE <= 160 * 1024, "LDS plan");
-  extern __shared__ __align__(1024) unsigned char smem[];   // 2 * STAGE bytes (above 64 KiB at dh = 256)
+  static_assert(TILE_B % (1024 * NW) == 0 && AUXB % 1024 == 0 && NST * STAGE <= 160 * 1024, "LDS plan");
+  static_assert((NST == 2 || NST == 3) && NKT <= 2, "ring of two or three stages of 32 or 64 tokens");
+  extern __shared__ __align__(1024) unsigned char smem[];   // NST * STAGE bytes
 
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -132,13 +143,15 @@ __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a)
     return CPR == 8 ? ((((r >> 1) & 1) << 2) | (((r >> 2) & 1) << 1) | ((r >> 3) & 1)) : (((r & 3) << 2) | ((r >> 2) & 3));
   };
 
+  // A unit = 128 stationary tokens of one (sample, tile, head); everything is uniform over the
+  // work-group and kept as element offsets so that a descriptor costs few scalar registers.
   struct Unit {
     int n_t, r0, nsb;
-    const bf16_t *x1, *x2, *y1, *y2;
-    const u32x4 *aux;     // record 0 of this (sample, head, tile) in array 0
-    bf16_t *o1, *o2;
+    int64_t q_off;      // first element of the tile's q rows of this head in qkv / d_qkv
+    int64_t o_off;      // ... of its rows in d_out
+    int64_t aux_off;    // ... of its records in record array 0
   };
-  auto decode = [&](int vb, Unit &u) -> int {
+  auto decode = [&](int vb, Unit &u) -> int {      // first non-empty unit at or after vb (stride G), or >= total
     while (vb < a.total) {
       const int logical = xcd_remap_attn(vb, a.total);
       const int xb = logical % a.QB;
@@ -149,37 +162,38 @@ __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a)
       const int b = rest / a.T;
       const int n_t = a.tiles[tile].n_tok;
       if (xb * BX < n_t) {
-        const size_t row0 = static_cast<size_t>(b) * a.n_h + a.tiles[tile].tok_off;
-        const bf16_t *q = a.qkv + row0 * ldq + head * DH;
-        const bf16_t *d_o = a.dout + row0 * a.D + head * DH;
-        bf16_t *dq = a.dqkv + row0 * ldq + head * DH;
+        const int64_t row0 = static_cast<int64_t>(b) * a.n_h + a.tiles[tile].tok_off;
         u.n_t = n_t;
         u.r0 = xb * BX;
         u.nsb = (n_t + BS - 1) / BS;
-        u.x1 = KV ? q + a.D : q;
-        u.x2 = KV ? q + 2 * a.D : d_o;
-        u.y1 = KV ? q : q + a.D;
-        u.y2 = KV ? d_o : q + 2 * a.D;
-        u.aux = a.aux + (static_cast<size_t>(b) * a.heads + head) * a.n_h + a.tiles[tile].tok_off;
-        u.o1 = KV ? dq + a.D : dq;
-        u.o2 = dq + 2 * a.D;
+        u.q_off = row0 * ldq + head * DH;
+        u.o_off = row0 * a.D + head * DH;
+        u.aux_off = (static_cast<int64_t>(b) * a.heads + head) * a.n_h + a.tiles[tile].tok_off;
         return vb;
       }
       vb += G;
     }
     return vb;
   };
+  auto x1_of = [&](const Unit &u) { return a.qkv + u.q_off + (KV ? a.D : 0); };
+  auto x2_of = [&](const Unit &u) { return KV ? a.qkv + u.q_off + 2 * a.D : a.dout + u.o_off; };
+  auto y1_of = [&](const Unit &u) { return a.qkv + u.q_off + (KV ? 0 : a.D); };
+  auto y2_of = [&](const Unit &u) { return KV ? a.dout + u.o_off : a.qkv + u.q_off + 2 * a.D; };
   Unit cur, nxt;
   int vb = decode(blockIdx.x, cur);
   if (vb >= a.total) return;
+  // the loads run NST - 1 blocks ahead of the arithmetic, across unit boundaries: a second
+  // cursor walks the same sequence of (unit, block)
+  Unit iu = cur;
+  int ivb = vb, iblk = 0;
   vb = decode(vb + G, nxt);
   bool has_next = vb < a.total;
 
-  // ---- load side
+  // ---- load side: lane -> (row of the block, 16-byte chunk), per-lane byte offsets
   int ld_row[LPW], off1[LPW], off2[LPW];
 #pragma unroll
   for (int i = 0; i < LPW; ++i) {
-    ld_row[i] = (wave + 4 * i) * RPB + lane / CPR;
+    ld_row[i] = (wave + NW * i) * RPB + lane / CPR;
     const int ch = ((lane % CPR) ^ swz(ld_row[i])) * 16;
     off1[i] = ld_row[i] * ldq * 2 + ch;
     off2[i] = ld_row[i] * ldy2 * 2 + ch;
@@ -188,48 +202,49 @@ __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a)
   const int aux_arr = aux_L / BS, aux_row = aux_L % BS;
   auto issue = [&](const Unit &u, int s0, int buf) {
     unsigned char *sb = smem + buf * STAGE;
-    const unsigned char *g1 = reinterpret_cast<const unsigned char *>(u.y1 + static_cast<size_t>(s0) * ldq);
-    const unsigned char *g2 = reinterpret_cast<const unsigned char *>(u.y2 + static_cast<size_t>(s0) * ldy2);
+    const unsigned char *g1 = reinterpret_cast<const unsigned char *>(y1_of(u) + static_cast<size_t>(s0) * ldq);
+    const unsigned char *g2 = reinterpret_cast<const unsigned char *>(y2_of(u) + static_cast<size_t>(s0) * ldy2);
     const int lim = u.n_t - 1 - s0;       // last valid row of this block
-    if (lim >= BS - 1) {
+    if (lim >= BS - 1) {                   // whole block inside the tile (uniform)
 #pragma unroll
       for (int i = 0; i < LPW; ++i) {
-        attn_dl_load16(reinterpret_cast<const bf16_t *>(g1 + static_cast<uint32_t>(off1[i])), sb + (wave + 4 * i) * 1024);
+        attn_dl_load16(reinterpret_cast<const bf16_t *>(g1 + static_cast<uint32_t>(off1[i])), sb + (wave + NW * i) * 1024);
         attn_dl_load16(reinterpret_cast<const bf16_t *>(g2 + static_cast<uint32_t>(off2[i])),
-                       sb + TILE_B + (wave + 4 * i) * 1024);
+                       sb + TILE_B + (wave + NW * i) * 1024);
       }
     } else {                               // rows past the tile end re-read its last row (finite; masked later)
 #pragma unroll
       for (int i = 0; i < LPW; ++i) {
         const int back = max(ld_row[i] - lim, 0);
         attn_dl_load16(reinterpret_cast<const bf16_t *>(g1 + static_cast<uint32_t>(off1[i] - back * ldq * 2)),
-                       sb + (wave + 4 * i) * 1024);
+                       sb + (wave + NW * i) * 1024);
         attn_dl_load16(reinterpret_cast<const bf16_t *>(g2 + static_cast<uint32_t>(off2[i] - back * ldy2 * 2)),
-                       sb + TILE_B + (wave + 4 * i) * 1024);
+                       sb + TILE_B + (wave + NW * i) * 1024);
       }
     }
     if constexpr (KV) {
       if (wave < AUXL) {
         const int row = s0 + min(aux_row, lim);
-        attn_dl_load16(reinterpret_cast<const bf16_t *>(u.aux + aux_arr * a.aux_stride + row), sb + 2 * TILE_B + wave * 1024);
+        attn_dl_load16(reinterpret_cast<const bf16_t *>(a.aux + u.aux_off + aux_arr * a.aux_stride + row),
+                       sb + 2 * TILE_B + wave * 1024);
       }
     }
   };
-  bf16x8 x1f[NKS], x2f[NKS];
+  bf16x8 x1f[NKS], x2f[DP ? NKS : 1];
   f32x16 sinit, dpinit;
   auto load_x = [&](const Unit &u) {
     const int xrow = min(u.r0 + wave * 32 + l32, u.n_t - 1);
-    const bf16_t *p1 = u.x1 + static_cast<size_t>(xrow) * ldq + hi * 8;
-    const bf16_t *p2 = u.x2 + static_cast<size_t>(xrow) * ldx2 + hi * 8;
+    const bf16_t *p1 = x1_of(u) + static_cast<size_t>(xrow) * ldq + hi * 8;
+    const bf16_t *p2 = x2_of(u) + static_cast<size_t>(xrow) * ldx2 + hi * 8;
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
       x1f[ks] = *reinterpret_cast<const bf16x8 *>(p1 + ks * 16);
-      x2f[ks] = *reinterpret_cast<const bf16x8 *>(p2 + ks * 16);
+      if constexpr (DP) x2f[ks] = *reinterpret_cast<const bf16x8 *>(p2 + ks * 16);
     }
     float si = 0.f, di = 0.f;
     if constexpr (!KV) {
-      const u32x2 r0 = *reinterpret_cast<const u32x2 *>(u.aux + xrow);
-      const u32x2 r1 = *reinterpret_cast<const u32x2 *>(u.aux + a.aux_stride + xrow);
+      const u32x2 r0 = *reinterpret_cast<const u32x2 *>(a.aux + u.aux_off + xrow);
+      const u32x2 r1 = *reinterpret_cast<const u32x2 *>(a.aux + u.aux_off + a.aux_stride + xrow);
       si = join3_bf16(r0[0], r0[1]);
       di = join3_bf16(r1[0], r1[1]);
     }
@@ -238,6 +253,9 @@ __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a)
   };
 
   // ---- read side
+  // Row fragment: A-operand row l32 carries streamed token key_perm(l32) of its 32-token group.
+  // Transposed fragment: this lane points at token row 8*hi + 4*e + (lane%16)/4 of a 16-token
+  // step and at the 4 features 32*d + 16*((lane/16)&1) + 4*(lane%4) .. +3.
   const int yr = key_perm(l32);
   const int y_row = yr * ROWB, y_swz = swz(yr);
   const int L16 = lane & 15;
@@ -261,66 +279,103 @@ __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a)
     ones_d[e] = static_cast<__bf16>(e < 3 && hi == 1 ? 1.0f : 0.0f);
   }
 
-  f32x16 acc1[NDT], acc2[KV ? NDT : 1];
+  f32x16 acc1[A1 ? NDT : 1], acc2[A2 ? NDT : 1];
   auto reset = [&]() {
 #pragma unroll
-    for (int d = 0; d < NDT; ++d)
+    for (int d = 0; d < (A1 ? NDT : 1); ++d)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc1[d][r] = 0.f;
 #pragma unroll
-    for (int d = 0; d < (KV ? NDT : 1); ++d)
+    for (int d = 0; d < (A2 ? NDT : 1); ++d)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc2[d][r] = 0.f;
   };
   reset();
   load_x(cur);
-  issue(cur, 0, 0);
+  // issue the next block of the load cursor into stage `buf`; false when the sequence has ended
+  auto issue_next = [&](int buf) -> bool {
+    if (ivb >= a.total) return false;
+    issue(iu, iblk * BS, buf);
+    if (++iblk == iu.nsb) {
+      ivb = decode(ivb + G, iu);
+      iblk = 0;
+    }
+    return true;
+  };
+  constexpr int NLD = 2 * LPW;            // direct loads of one block per wave (+1 in the waves that fetch records)
+  int ahead = 0;                          // blocks in flight beyond the one about to be computed
+  issue_next(0);
+#pragma unroll
+  for (int i = 1; i < NST - 1; ++i) ahead += issue_next(i) ? 1 : 0;
 
-  int sb = 0;
-  for (int g = 0;; ++g) {
-    __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0)
-    __syncthreads();
+  int sb = 0, buf = 0;
+  for (;;) {
+    // block `sb` of `cur` must have landed; younger blocks may stay in flight.  Loads complete in
+    // issue order, so "at most `ahead` blocks' worth outstanding" is enough.
+    if (NST == 2 || ahead == 0) {
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+    } else if (KV && wave < AUXL) {
+      __builtin_amdgcn_s_waitcnt(0x0F70 | ((NLD + 1) & 15) | (((NLD + 1) >> 4) << 14));
+    } else {
+      __builtin_amdgcn_s_waitcnt(0x0F70 | (NLD & 15) | ((NLD >> 4) << 14));
+    }
+    // a bare barrier: __syncthreads() would add a fence that waits for ALL vector-memory operations,
+    // the younger prefetches included.  Every wave has waited for its own direct-to-LDS loads of
+    // this block above, and LDS reads of the stage being refilled finished before its readers arrived.
+    __builtin_amdgcn_s_barrier();           // everybody's part of the block is in LDS; the oldest stage is free
     const bool last = sb + 1 == cur.nsb;
-    if (!last) issue(cur, (sb + 1) * BS, (g + 1) & 1);
-    else if (has_next) issue(nxt, 0, (g + 1) & 1);
-    const unsigned char *st = smem + (g & 1) * STAGE;
+    {
+      int ibuf = buf + NST - 1;
+      if (ibuf >= NST) ibuf -= NST;
+      if (issue_next(ibuf)) { if (NST == 2) ahead = 0; }   // one computed, one issued: `ahead` unchanged
+      else if (ahead > 0) --ahead;
+    }
+    const unsigned char *st = smem + buf * STAGE;
     const int s0 = sb * BS;
     const bool active = cur.r0 + wave * 32 < cur.n_t;
 
-    // one 32-token group of the streamed block at a time: scores, probabilities, then the
-    // two products that consume them (keeps one pair of score accumulators live)
-    auto group = [&](auto kt_c, bool fetch_next) {
+    // The work on one 32-token group of the streamed block, in three phases.
+    const unsigned st_off = static_cast<unsigned>(reinterpret_cast<uintptr_t>(
+        (__attribute__((address_space(3))) const unsigned char *)st));
+    auto scores = [&](auto kt_c, f32x16 &s, f32x16 &dp) {          // matrix pipe
       constexpr int kt = decltype(kt_c)::value;
-      f32x16 s, dp;
 #pragma unroll
       for (int ks = 0; ks < NKS; ++ks) {
         const unsigned char *rp = st + kt * 32 * ROWB + y_row + (((2 * ks + hi) ^ y_swz) << 4);
         const bf16x8 f1 = *reinterpret_cast<const bf16x8 *>(rp);
-        const bf16x8 f2 = *reinterpret_cast<const bf16x8 *>(rp + TILE_B);
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, x1f[ks], ks == 0 ? sinit : s, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2, x2f[ks], ks == 0 ? dpinit : dp, 0, 0, 0);
+        if constexpr (DP) {
+          const bf16x8 f2 = *reinterpret_cast<const bf16x8 *>(rp + TILE_B);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2, x2f[ks], ks == 0 ? dpinit : dp, 0, 0, 0);
+        }
+        // wide heads: keep the scheduler from hoisting every fragment read of the group to its
+        // top (64+ registers of fragments in flight next to the accumulators = spills)
+        if constexpr (DH >= 128) { if (ks % 2 == 1) __builtin_amdgcn_sched_barrier(0); }
       }
       if constexpr (KV) {
         const bf16x8 fa = *reinterpret_cast<const bf16x8 *>(st + aux_addr + kt * 32 * 16);
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, ones_s, s, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, ones_d, dp, 0, 0, 0);
+        if constexpr (DP) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, ones_d, dp, 0, 0, 0);
       }
-      // the stationary fragments are dead after the last scores of a unit: fetch the next unit's
-      if (fetch_next) load_x(nxt);
-      if (s0 + kt * 32 + 32 > cur.n_t) {   // ragged end: streamed tokens past the tile end get probability 0
+    };
+    auto mask = [&](int kt, f32x16 &s) {      // ragged end: streamed tokens past the tile end get probability 0
+      if (s0 + kt * 32 + 32 > cur.n_t) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int row = s0 + kt * 32 + 16 * (r / 8) + 8 * hi + (r % 8);
           if (row >= cur.n_t) s[r] = -INFINITY;
         }
       }
+    };
+    auto probs = [&](f32x16 &s, f32x16 &dp) {                       // vector pipe: s <- P, dp <- dS
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        s[r] = __builtin_amdgcn_exp2f(s[r] * a.c);
-        dp[r] *= s[r];
+        s[r] = __builtin_amdgcn_exp2f(QS ? s[r] : s[r] * a.c);
+        if constexpr (DP) dp[r] *= s[r];
       }
-      const unsigned st_off = static_cast<unsigned>(reinterpret_cast<uintptr_t>(
-          (__attribute__((address_space(3))) const unsigned char *)st));
+    };
+    auto products = [&](auto kt_c, const f32x16 &s, const f32x16 &dp) {   // matrix pipe
+      constexpr int kt = decltype(kt_c)::value;
       auto step = [&](auto h2_c) {
         constexpr int h2 = decltype(h2_c)::value;
         constexpr int ROFF = (kt * 32 + h2 * 16) * ROWB;
@@ -332,27 +387,29 @@ __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a)
           for (int d = 0; d < NDT; ++d)
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
-              r1[d][e] = tr_issue<ROFF>(st_off + static_cast<unsigned>(t_addr[e][d]));
-              if constexpr (KV) r2[d][e] = tr_issue<ROFF + TILE_B>(st_off + static_cast<unsigned>(t_addr[e][d]));
+              if constexpr (A1) r1[d][e] = tr_issue<ROFF>(st_off + static_cast<unsigned>(t_addr[e][d]));
+              if constexpr (A2) r2[d][e] = tr_issue<ROFF + TILE_B>(st_off + static_cast<unsigned>(t_addr[e][d]));
             }
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
-            dsf[e] = static_cast<__bf16>(dp[8 * h2 + e]);
-            if constexpr (KV) pf[e] = static_cast<__bf16>(s[8 * h2 + e]);
+            if constexpr (A1) dsf[e] = static_cast<__bf16>(dp[8 * h2 + e]);
+            if constexpr (A2) pf[e] = static_cast<__bf16>(s[8 * h2 + e]);
           }
           asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
           for (int d = 0; d < NDT; ++d)
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
-              asm volatile("" : "+v"(r1[d][e]));
-              if constexpr (KV) asm volatile("" : "+v"(r2[d][e]));
+              if constexpr (A1) asm volatile("" : "+v"(r1[d][e]));
+              if constexpr (A2) asm volatile("" : "+v"(r2[d][e]));
             }
 #pragma unroll
           for (int d = 0; d < NDT; ++d) {
-            const u64x2 b1 = {r1[d][0], r1[d][1]};
-            acc1[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, b1), dsf, acc1[d], 0, 0, 0);
-            if constexpr (KV) {
+            if constexpr (A1) {
+              const u64x2 b1 = {r1[d][0], r1[d][1]};
+              acc1[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, b1), dsf, acc1[d], 0, 0, 0);
+            }
+            if constexpr (A2) {
               const u64x2 b2 = {r2[d][0], r2[d][1]};
               acc2[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, b2), pf, acc2[d], 0, 0, 0);
             }
@@ -360,26 +417,23 @@ __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a)
         } else {
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
-            dsf[e] = static_cast<__bf16>(dp[8 * h2 + e]);
-            if constexpr (KV) pf[e] = static_cast<__bf16>(s[8 * h2 + e]);
+            if constexpr (A1) dsf[e] = static_cast<__bf16>(dp[8 * h2 + e]);
+            if constexpr (A2) pf[e] = static_cast<__bf16>(s[8 * h2 + e]);
           }
           typedef __attribute__((ext_vector_type(8))) short s16x8;
+          auto tr_frag = [&](int off) {
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(st + off));
+            return lo;
+          };
 #pragma unroll
           for (int d = 0; d < NDT; ++d) {
-            const unsigned char *vp = st + ROFF;
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (s16x4 __attribute__((address_space(3))) *)(vp + t_addr[0][d]));
-            const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (s16x4 __attribute__((address_space(3))) *)(vp + t_addr[1][d]));
-            const s16x8 both = __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
-            acc1[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), dsf, acc1[d], 0, 0, 0);
-            if constexpr (KV) {
-              const s16x4 lo2 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                  (s16x4 __attribute__((address_space(3))) *)(vp + TILE_B + t_addr[0][d]));
-              const s16x4 hi2 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                  (s16x4 __attribute__((address_space(3))) *)(vp + TILE_B + t_addr[1][d]));
-              const s16x8 both2 = __builtin_shufflevector(lo2, hi2, 0, 1, 2, 3, 4, 5, 6, 7);
-              acc2[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both2), pf, acc2[d], 0, 0, 0);
+            if constexpr (A1) {
+              const s16x8 both = __builtin_shufflevector(tr_frag(ROFF + t_addr[0][d]), tr_frag(ROFF + t_addr[1][d]), 0, 1, 2, 3, 4, 5, 6, 7);
+              acc1[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), dsf, acc1[d], 0, 0, 0);
+            }
+            if constexpr (A2) {
+              const s16x8 both = __builtin_shufflevector(tr_frag(ROFF + TILE_B + t_addr[0][d]), tr_frag(ROFF + TILE_B + t_addr[1][d]), 0, 1, 2, 3, 4, 5, 6, 7);
+              acc2[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf, acc2[d], 0, 0, 0);
             }
           }
         }
@@ -387,33 +441,48 @@ __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a)
       step(std::integral_constant<int, 0>{});
       step(std::integral_constant<int, 1>{});
     };
-    static_assert(NKT <= 2, "streamed block of 32 or 64 tokens");
-    const bool fetch = last && has_next;
-    if (active) {
-      const bool two = NKT == 2 && s0 + 32 < cur.n_t;      // the second group holds at least one token
-      group(std::integral_constant<int, 0>{}, fetch && !two);
-      if constexpr (NKT == 2) {
-        if (two) group(std::integral_constant<int, 1>{}, fetch);
+    // One straight path for every block, one 32-token group after the other; a second group
+    // that lies wholly past the tile end (last block only) is computed and masked to zero rather
+    // than skipped.  The next unit's stationary fragments are fetched at ONE place, after the
+    // last scores that use the current ones.
+    const bool ragged = s0 + BS > cur.n_t;
+    f32x16 sA, dA;
+    if constexpr (NKT == 2) {
+      if (active) {
+        scores(std::integral_constant<int, 0>{}, sA, dA);
+        if (ragged) mask(0, sA);
+        probs(sA, dA);
+        products(std::integral_constant<int, 0>{}, sA, dA);
       }
-    } else if (fetch) {
-      load_x(nxt);
     }
+    if (active) scores(std::integral_constant<int, NKT - 1>{}, sA, dA);
+    if (last && has_next) load_x(nxt);
+    if (active) {
+      if (ragged) mask(NKT - 1, sA);
+      probs(sA, dA);
+      products(std::integral_constant<int, NKT - 1>{}, sA, dA);
+    }
+    if (++buf == NST) buf = 0;
     if (!last) { ++sb; continue; }
 
     // ---- end of a unit: scale, round and store this lane's row of each gradient
     const int xrow = cur.r0 + wave * 32 + l32;
     if (active && xrow < cur.n_t) {
-      bf16_t *p1 = cur.o1 + static_cast<size_t>(xrow) * ldq + hi * 4;
-      bf16_t *p2 = cur.o2 + static_cast<size_t>(xrow) * ldq + hi * 4;
+      bf16_t *p1 = a.dqkv + cur.q_off + (KV ? a.D : 0) + static_cast<size_t>(xrow) * ldq + hi * 4;
+      bf16_t *p2 = a.dqkv + cur.q_off + 2 * a.D + static_cast<size_t>(xrow) * ldq + hi * 4;
+      const float sc1 = KV ? a.sck : a.scq;
 #pragma unroll
       for (int d = 0; d < NDT; ++d)
 #pragma unroll
         for (int r4 = 0; r4 < 4; ++r4) {
+          // registers 4*r4 .. 4*r4+3 hold features 32d + 8*r4 + 4*hi + (0..3) of this lane's token
           bf16x4 tmp;
+          if constexpr (A1) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) tmp[e] = static_cast<__bf16>(acc1[d][4 * r4 + e] * a.sc);
-          *reinterpret_cast<u32x2 *>(p1 + d * 32 + r4 * 8) = __builtin_bit_cast(u32x2, tmp);
-          if constexpr (KV) {
+            for (int e = 0; e < 4; ++e) tmp[e] = static_cast<__bf16>(acc1[d][4 * r4 + e] * sc1);
+            *reinterpret_cast<u32x2 *>(p1 + d * 32 + r4 * 8) = __builtin_bit_cast(u32x2, tmp);
+          }
+          if constexpr (A2) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) tmp[e] = static_cast<__bf16>(acc2[d][4 * r4 + e]);
             *reinterpret_cast<u32x2 *>(p2 + d * 32 + r4 * 8) = __builtin_bit_cast(u32x2, tmp);
@@ -421,6 +490,11 @@ __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a)
         }
     }
     if (!has_next) break;
+    // Everything in flight (the next unit's stationary fragments, the result stores, the
+    // prefetched blocks) is waited for here, once per unit: with register loads possibly
+    // pending across the loop edge the compiler would otherwise wait for ALL vector-memory
+    // operations, the prefetch included, before the first fragment use of every block.
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     cur = nxt;
     vb = decode(vb + G, nxt);
     has_next = vb < a.total;
@@ -505,8 +579,8 @@ __global__ __launch_bounds__(128) void attn_bwd_f32_kernel(const float *qkv, con
   }
 }
 
-template <int DH, int BS>
-constexpr int bwd_lds_bytes(bool kv) { return 2 * (2 * BS * DH * 2 + (kv ? 2 * BS * 16 : 0)); }
+template <int DH, int BS, int NST>
+constexpr int bwd_lds_bytes(bool kv) { return NST * (2 * BS * DH * 2 + (kv ? 2 * BS * 16 : 0)); }
 
 static int g_bwd_cus = 0;
 static bool g_bwd_dh256_ok = false;
@@ -517,11 +591,19 @@ hipError_t attention_bwd_init() {
   if (e != hipSuccess) return e;
   e = hipDeviceGetAttribute(&g_bwd_cus, hipDeviceAttributeMultiprocessorCount, dev);
   if (e != hipSuccess) return e;
-  // the key-stationary kernel at dh = 256 needs 66 KiB of LDS, above the default limit of a launch
-  e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<256, 32, true, 1>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, bwd_lds_bytes<256, 32>(true));
-  g_bwd_dh256_ok = e == hipSuccess;
-  if (e != hipSuccess) (void)hipGetLastError();    // not fatal: only the dh = 256 gradient is refused
+  // the kernels at dh = 256 need 96 .. 99 KiB of LDS, above the default limit of a launch
+  g_bwd_dh256_ok = true;
+  const void *big[] = {reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<256, 32, 0, false, 1, 3>),
+                       reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<256, 32, 0, true, 1, 3>),
+                       reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<256, 32, 1, false, 1, 3>),
+                       reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<256, 32, 1, true, 1, 3>)};
+  for (int i = 0; i < 4; ++i) {
+    e = hipFuncSetAttribute(big[i], hipFuncAttributeMaxDynamicSharedMemorySize, bwd_lds_bytes<256, 32, 3>(i >= 2));
+    if (e != hipSuccess) {            // not fatal: only the dh = 256 gradient is refused
+      (void)hipGetLastError();
+      g_bwd_dh256_ok = false;
+    }
+  }
   return hipSuccess;
 }
 
@@ -530,23 +612,44 @@ size_t tiles_attention_bwd_ws_bytes(const reslim_ctx *c, int batch) {
   return c->cfg.dtype == RESLIM_BF16 ? align256(recs * 32) : align256(recs * 4);
 }
 
-template <int DH, int BS, int MINW_Q, int MINW_KV>
-static hipError_t launch_bwd_pair(const AttnBwdArgs &a, hipStream_t st) {
-  const int gq = a.total < MINW_Q * g_bwd_cus ? a.total : MINW_Q * g_bwd_cus;
-  const int gk = a.total < MINW_KV * g_bwd_cus ? a.total : MINW_KV * g_bwd_cus;
-  attn_bwd_bf16_kernel<DH, BS, false, MINW_Q><<<dim3(gq), dim3(256), bwd_lds_bytes<DH, BS>(false), st>>>(a);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  attn_bwd_bf16_kernel<DH, BS, true, MINW_KV><<<dim3(gk), dim3(256), bwd_lds_bytes<DH, BS>(true), st>>>(a);
+template <int DH, int BS, int MODE, bool QS, int MINW, int NST>
+static hipError_t launch_bwd_one(const AttnBwdArgs &a, hipStream_t st) {
+  const int g = a.total < MINW * g_bwd_cus ? a.total : MINW * g_bwd_cus;    // persistent grid
+  attn_bwd_bf16_kernel<DH, BS, MODE, QS, MINW, NST><<<dim3(g), dim3(256), bwd_lds_bytes<DH, BS, NST>(MODE != 0), st>>>(a);
   return hipGetLastError();
 }
 
+// Launch shapes (measured on MI355X): dh = 64: 64-token blocks, three stages; the dQ kernel fits
+// 168 registers = three work-groups per CU, the dK/dV kernel (197) two.  dh = 128: dK and dV in
+// separate passes (their accumulators together with the stationary fragments exceed the register
+// file).  dh = 256: one work-group per CU.
+template <bool QS>
+static hipError_t launch_bwd_all(const AttnBwdArgs &a, int dh, hipStream_t st) {
+  hipError_t e;
+  switch (dh) {
+    case 64:
+      e = launch_bwd_one<64, 64, 0, QS, 3, 3>(a, st);
+      return e != hipSuccess ? e : launch_bwd_one<64, 64, 1, QS, 2, 3>(a, st);
+    case 128:
+      e = launch_bwd_one<128, 32, 0, QS, 2, 3>(a, st);
+      if (e == hipSuccess) e = launch_bwd_one<128, 32, 2, QS, 2, 3>(a, st);
+      return e != hipSuccess ? e : launch_bwd_one<128, 32, 3, QS, 2, 3>(a, st);
+    case 256:
+      if (!g_bwd_dh256_ok) return hipErrorInvalidValue;
+      e = launch_bwd_one<256, 32, 0, QS, 1, 3>(a, st);
+      return e != hipSuccess ? e : launch_bwd_one<256, 32, 1, QS, 1, 3>(a, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
 hipError_t launch_tiles_attention_bwd(const reslim_ctx *c, const void *qkv, const void *out, const float *lse,
-                                      const void *dout, void *dqkv, int batch, void *ws, hipStream_t st) {
+                                      const void *dout, void *dqkv, int batch, void *ws, bool q_prescaled,
+                                      hipStream_t st) {
   const int heads = c->cfg.heads, D = c->cfg.embed_dim, dh = c->dh;
   const int64_t recs = static_cast<int64_t>(batch) * heads * c->n_h;
   if (recs == 0) return hipSuccess;
   if (c->cfg.dtype == RESLIM_BF16) {
+    const float rs = 1.0f / sqrtf(static_cast<float>(dh));
     AttnBwdArgs a;
     a.qkv = static_cast<const bf16_t *>(qkv);
     a.dout = static_cast<const bf16_t *>(dout);
@@ -558,30 +661,31 @@ hipError_t launch_tiles_attention_bwd(const reslim_ctx *c, const void *qkv, cons
     a.D = D;
     a.n_h = c->n_h;
     a.aux_stride = recs;
-    a.c = 1.4426950408889634f / sqrtf(static_cast<float>(dh));
-    a.sc = 1.0f / sqrtf(static_cast<float>(dh));
+    // With q pre-scaled by log2(e)/sqrt(dh) the MFMA output is the base-2 logit; the gradient with
+    // respect to the UNSCALED q keeps the factor 1/sqrt(dh), the one of k becomes ln 2 (k meets the
+    // scaled q).
+    a.c = q_prescaled ? 1.0f : 1.4426950408889634f * rs;
+    a.scq = rs;
+    a.sck = q_prescaled ? 0.69314718055994531f : rs;
     a.QB = (c->max_n_tok + 127) / 128;
     const int64_t total = static_cast<int64_t>(batch) * c->T * heads * a.QB;
     if (total > INT32_MAX || g_bwd_cus <= 0) return hipErrorInvalidValue;
     a.total = static_cast<int>(total);
     const int64_t n_vec = static_cast<int64_t>(batch) * c->n_h * D / 8;
     const unsigned pg = static_cast<unsigned>((n_vec + 255) / 256);
-    const float sq = sqrtf(static_cast<float>(dh));
+    // record 0 holds -lse in the unit of the MFMA output: -lse*sqrt(dh), or -lse*log2(e) for pre-scaled q
+    const float lse_f = q_prescaled ? 1.4426950408889634f : sqrtf(static_cast<float>(dh));
     u32x4 *aux = static_cast<u32x4 *>(ws);
     const bf16_t *o = static_cast<const bf16_t *>(out);
     switch (dh) {
-      case 64: attn_bwd_prep_bf16_kernel<64><<<dim3(pg), dim3(256), 0, st>>>(o, a.dout, lse, aux, n_vec, c->n_h, heads, D, sq, recs); break;
-      case 128: attn_bwd_prep_bf16_kernel<128><<<dim3(pg), dim3(256), 0, st>>>(o, a.dout, lse, aux, n_vec, c->n_h, heads, D, sq, recs); break;
-      case 256: attn_bwd_prep_bf16_kernel<256><<<dim3(pg), dim3(256), 0, st>>>(o, a.dout, lse, aux, n_vec, c->n_h, heads, D, sq, recs); break;
+      case 64: attn_bwd_prep_bf16_kernel<64><<<dim3(pg), dim3(256), 0, st>>>(o, a.dout, lse, aux, n_vec, c->n_h, heads, D, lse_f, recs); break;
+      case 128: attn_bwd_prep_bf16_kernel<128><<<dim3(pg), dim3(256), 0, st>>>(o, a.dout, lse, aux, n_vec, c->n_h, heads, D, lse_f, recs); break;
+      case 256: attn_bwd_prep_bf16_kernel<256><<<dim3(pg), dim3(256), 0, st>>>(o, a.dout, lse, aux, n_vec, c->n_h, heads, D, lse_f, recs); break;
       default: return hipErrorInvalidValue;
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    switch (dh) {
-      case 64: return launch_bwd_pair<64, 64, 2, 2>(a, st);
-      case 128: return launch_bwd_pair<128, 32, 2, 1>(a, st);
-      default: return g_bwd_dh256_ok ? launch_bwd_pair<256, 32, 1, 1>(a, st) : hipErrorInvalidValue;
-    }
+    return q_prescaled ? launch_bwd_all<true>(a, dh, st) : launch_bwd_all<false>(a, dh, st);
   }
   float *delta = static_cast<float *>(ws);
   const size_t lds = (2 * static_cast<size_t>(c->max_n_tok) + 2 * dh) * sizeof(float);

@@ -23,7 +23,7 @@ extern "C" int tiles_attention_bwd(reslim_ctx *c, const void *qkv, const void *o
     return set_error(c, RESLIM_EWORKSPACE, std::string(fn) + ": workspace null or not 256-byte aligned");
   if (ws_bytes < tiles_attention_bwd_ws_bytes(c, batch))
     return set_error(c, RESLIM_EWORKSPACE, std::string(fn) + ": workspace smaller than tiles_attention_bwd_workspace_bytes()");
-  RESLIM_TRY("launch", launch_tiles_attention_bwd(c, qkv, out, lse, d_out, d_qkv, batch, workspace,
+  RESLIM_TRY("launch", launch_tiles_attention_bwd(c, qkv, out, lse, d_out, d_qkv, batch, workspace, false,
                                                   static_cast<hipStream_t>(hip_stream)));
   return RESLIM_OK;
 }

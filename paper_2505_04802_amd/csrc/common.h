@@ -124,7 +124,8 @@ hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *ou
 bool attention_accepts_prescaled_q();
 // gradient of tile attention: d_qkv from qkv, the forward's out and lse, and d_out; ws as sized below
 hipError_t launch_tiles_attention_bwd(const reslim_ctx *c, const void *qkv, const void *out, const float *lse,
-                                      const void *dout, void *dqkv, int batch, void *ws, hipStream_t st);
+                                      const void *dout, void *dqkv, int batch, void *ws, bool q_prescaled,
+                                      hipStream_t st);
 size_t tiles_attention_bwd_ws_bytes(const reslim_ctx *c, int batch);
 hipError_t attention_bwd_init();
 hipError_t attention_init();
