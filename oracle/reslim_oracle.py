@@ -215,6 +215,77 @@ def block_tokens(X, w: Dict[str, np.ndarray], layer: int, heads: int):
     return X + linear(u, w["w_fc2"][layer], w["b_fc2"][layer])
 
 
+# ---- gradients of the block's pieces (the paper trains the model, Sec. 5, and prints no
+# formulas: each function is the chain rule through the forward function of the same name)
+def linear_bwd(x, w, dy):
+    """y = x W^T + b  =>  dx = dy W,  dW = dy^T x,  db = column sums of dy."""
+    x, w, dy = (np.asarray(a, F64) for a in (x, w, dy))
+    return dy @ w, dy.T @ x, dy.sum(axis=0)
+
+
+def layer_norm_bwd(x, gamma, dy, eps: float = 1e-5):
+    """Gradient of layer_norm.  With xh = (x - mu) / sigma, g = gamma * dy and means over the row:
+    dx = (g - mean(g) - xh * mean(g * xh)) / sigma;  dgamma = sum_rows dy * xh;  dbeta = sum_rows dy."""
+    x, gamma, dy = (np.asarray(a, F64) for a in (x, gamma, dy))
+    mu = x.mean(axis=-1, keepdims=True)
+    sig = np.sqrt(((x - mu) ** 2).mean(axis=-1, keepdims=True) + eps)
+    xh = (x - mu) / sig
+    g = dy * gamma
+    dx = (g - g.mean(axis=-1, keepdims=True) - xh * (g * xh).mean(axis=-1, keepdims=True)) / sig
+    return dx, (dy * xh).reshape(-1, x.shape[-1]).sum(axis=0), dy.reshape(-1, x.shape[-1]).sum(axis=0)
+
+
+def gelu_grad(x):
+    """d/dx [x Phi(x)] = Phi(x) + x phi(x), phi the standard normal density."""
+    x = np.asarray(x, F64)
+    return 0.5 * (1.0 + _erf(x / math.sqrt(2.0))) + x * np.exp(-0.5 * x * x) / math.sqrt(2.0 * math.pi)
+
+
+BLOCK_PARAMS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_proj", "b_proj", "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
+
+
+def block_tokens_bwd(X, w: Dict[str, np.ndarray], layer: int, heads: int, d_out):
+    """Gradient of block_tokens (ONE token set) for an upstream gradient d_out of its output:
+    returns (dX, {parameter name: gradient}) with the parameter names of BLOCK_PARAMS.
+    The forward is replayed to get the intermediates, then walked backwards."""
+    X, d_out = np.asarray(X, F64), np.asarray(d_out, F64)
+    D = X.shape[1]
+    a1 = layer_norm(X, w["ln1_g"][layer], w["ln1_b"][layer])
+    qkv = linear(a1, w["w_qkv"][layer], w["b_qkv"][layer])
+    o = self_attention(qkv[:, :D], qkv[:, D:2 * D], qkv[:, 2 * D:], heads)
+    x_mid = X + linear(o, w["w_proj"][layer], w["b_proj"][layer])
+    a2 = layer_norm(x_mid, w["ln2_g"][layer], w["ln2_b"][layer])
+    h = linear(a2, w["w_fc1"][layer], w["b_fc1"][layer])
+    u = gelu(h)
+    g = {}
+    # x_out = x_mid + fc2(u)
+    d_u, g["w_fc2"], g["b_fc2"] = linear_bwd(u, w["w_fc2"][layer], d_out)
+    d_h = d_u * gelu_grad(h)
+    d_a2, g["w_fc1"], g["b_fc1"] = linear_bwd(a2, w["w_fc1"][layer], d_h)
+    d_ln, g["ln2_g"], g["ln2_b"] = layer_norm_bwd(x_mid, w["ln2_g"][layer], d_a2)
+    d_mid = d_out + d_ln
+    # x_mid = X + proj(attention(qkv(ln1(X))))
+    d_o, g["w_proj"], g["b_proj"] = linear_bwd(o, w["w_proj"][layer], d_mid)
+    d_qkv = np.concatenate(self_attention_bwd(qkv[:, :D], qkv[:, D:2 * D], qkv[:, 2 * D:], d_o, heads), axis=1)
+    d_a1, g["w_qkv"], g["b_qkv"] = linear_bwd(a1, w["w_qkv"][layer], d_qkv)
+    d_ln, g["ln1_g"], g["ln1_b"] = layer_norm_bwd(X, w["ln1_g"][layer], d_a1)
+    return d_mid + d_ln, g
+
+
+def reslim_block_bwd(X, tiles: Sequence[dict], w, layer: int, heads: int, d_out):
+    """Gradient of reslim_block on the tile-major stream X[B, n_h, D]: every tile is its own
+    token set (Sec. 4.2), the parameters are shared, so their gradients add over tiles and samples."""
+    X, d_out = np.asarray(X, F64), np.asarray(d_out, F64)
+    dX = np.empty_like(X)
+    grads = None
+    for b in range(X.shape[0]):
+        for t in tiles:
+            r = slice(t["tok_off"], t["tok_off"] + t["n_tok"])
+            dX[b, r], g = block_tokens_bwd(X[b, r], w, layer, heads, d_out[b, r])
+            grads = g if grads is None else {k: grads[k] + g[k] for k in g}
+    return dX, grads
+
+
 def reslim_block(X, tiles: Sequence[dict], w, layer: int, heads: int):
     """One block applied to the tile-major stream X[B, n_h, D]: every tile is its
     own token set (Sec. 4.2)."""

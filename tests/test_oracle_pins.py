@@ -436,3 +436,81 @@ def test_tiles_attention_bwd_vs_autograd_and_finite_differences():
     assert np.allclose(O.tiles_attention(qkv + shift, tiles, heads), O.tiles_attention(qkv, tiles, heads), atol=1e-10)
     # dV of a tile depends on d_out only through P^T d_out: zero upstream gradient gives zero
     assert not O.tiles_attention_bwd(qkv, np.zeros_like(d_out), tiles, heads).any()
+
+
+# ------------------------------------------------------------------ block gradient
+def test_block_pieces_bwd_vs_autograd_and_closed_forms():
+    """linear_bwd, layer_norm_bwd and gelu_grad against PyTorch CPU autograd through its own
+    functional ops, plus closed forms: gelu'(0) = 1/2, gelu'(x) -> 1 / 0 far out, LayerNorm's
+    input gradient is orthogonal to the all-ones vector and to the normalised row."""
+    rng = np.random.default_rng(31)
+    x, wgt, dy = rng.normal(size=(11, 7)), rng.normal(size=(5, 7)), rng.normal(size=(11, 5))
+    xt, wt = torch.tensor(x, requires_grad=True), torch.tensor(wgt, requires_grad=True)
+    bt = torch.zeros(5, dtype=torch.float64, requires_grad=True)
+    F.linear(xt, wt, bt).backward(torch.tensor(dy))
+    dx, dw, db = O.linear_bwd(x, wgt, dy)
+    assert np.allclose(dx, xt.grad.numpy(), atol=1e-12) and np.allclose(dw, wt.grad.numpy(), atol=1e-12)
+    assert np.allclose(db, bt.grad.numpy(), atol=1e-12)
+    gam, dyl = 1 + 0.3 * rng.normal(size=7), rng.normal(size=(11, 7))
+    xt = torch.tensor(x, requires_grad=True)
+    gt, bt = torch.tensor(gam, requires_grad=True), torch.zeros(7, dtype=torch.float64, requires_grad=True)
+    F.layer_norm(xt, (7,), gt, bt, 1e-5).backward(torch.tensor(dyl))
+    dx, dg, dbeta = O.layer_norm_bwd(x, gam, dyl)
+    assert np.allclose(dx, xt.grad.numpy(), atol=1e-12) and np.allclose(dg, gt.grad.numpy(), atol=1e-12)
+    assert np.allclose(dbeta, bt.grad.numpy(), atol=1e-12)
+    assert np.abs(dx.sum(axis=1)).max() < 1e-12
+    xh = (x - x.mean(1, keepdims=True)) / np.sqrt(x.var(1, keepdims=True))
+    assert np.abs((O.layer_norm_bwd(x, gam, dyl, eps=0.0)[0] * xh).sum(axis=1)).max() < 1e-12      # holds for eps = 0
+    z = rng.normal(size=50) * 2
+    zt = torch.tensor(z, requires_grad=True)
+    F.gelu(zt).sum().backward()
+    assert np.allclose(O.gelu_grad(z), zt.grad.numpy(), atol=1e-13)
+    assert abs(O.gelu_grad(0.0) - 0.5) < 1e-15 and abs(O.gelu_grad(12.0) - 1) < 1e-12 and abs(O.gelu_grad(-12.0)) < 1e-12
+
+
+def test_block_bwd_vs_torch_autograd_and_finite_differences():
+    """The block's gradient against PyTorch CPU autograd through TransformerEncoderLayer(norm_first)
+    (an independent implementation of the same block, pinned to the oracle's forward above),
+    for the input and all twelve parameter tensors; the tiled form against per-tile autograd sums;
+    central finite differences of the oracle's own forward on a few coordinates."""
+    cfg = small_cfg()
+    w = big_weights(cfg, 0.2)
+    D, R, l = cfg.embed_dim, cfg.embed_dim * cfg.mlp_ratio, 1
+    layer = torch.nn.TransformerEncoderLayer(D, cfg.heads, R, dropout=0.0, activation="gelu",
+                                             batch_first=True, norm_first=True).double()
+    names = {"w_qkv": layer.self_attn.in_proj_weight, "b_qkv": layer.self_attn.in_proj_bias,
+             "w_proj": layer.self_attn.out_proj.weight, "b_proj": layer.self_attn.out_proj.bias,
+             "w_fc1": layer.linear1.weight, "b_fc1": layer.linear1.bias, "w_fc2": layer.linear2.weight,
+             "b_fc2": layer.linear2.bias, "ln1_g": layer.norm1.weight, "ln1_b": layer.norm1.bias,
+             "ln2_g": layer.norm2.weight, "ln2_b": layer.norm2.bias}
+    assert set(names) == set(O.BLOCK_PARAMS)
+    with torch.no_grad():
+        for k, prm in names.items():
+            prm.copy_(T(w[k][l]))
+    rng = np.random.default_rng(6)
+    tiles, _, _, n_h = O.tiles_partition(5, 6, 2, 2, 1)
+    X, d_out = rng.normal(size=(2, n_h, D)), rng.normal(size=(2, n_h, D))
+    dX, grads = O.reslim_block_bwd(X, tiles, w, l, cfg.heads, d_out)
+    ref_dX = np.zeros_like(X)
+    for b in range(2):
+        for t in tiles:
+            r = slice(t["tok_off"], t["tok_off"] + t["n_tok"])
+            xt = torch.tensor(X[b, r][None], requires_grad=True)
+            layer(xt).backward(torch.tensor(d_out[b, r][None]))      # parameter gradients accumulate over calls
+            ref_dX[b, r] = xt.grad.numpy()[0]
+    assert np.allclose(dX, ref_dX, rtol=1e-9, atol=1e-11)
+    for k, prm in names.items():
+        assert np.allclose(grads[k], prm.grad.numpy(), rtol=1e-9, atol=1e-10), k
+    # finite differences of the oracle's forward: one input coordinate, one weight of each matrix
+    loss = lambda Xv, wv: float((O.reslim_block(Xv, tiles, wv, l, cfg.heads) * d_out).sum())
+    Xp, Xm = X.copy(), X.copy()
+    Xp[1, 3, 2] += 1e-6
+    Xm[1, 3, 2] -= 1e-6
+    assert abs((loss(Xp, w) - loss(Xm, w)) / 2e-6 - dX[1, 3, 2]) < 1e-5
+    for k, idx in (("w_qkv", (D + 1, 2)), ("w_proj", (0, 1)), ("w_fc1", (3, 0)), ("w_fc2", (2, 5)), ("ln1_g", (1,)), ("b_fc1", (4,))):
+        wp = {n: a.copy() for n, a in w.items()}
+        wm = {n: a.copy() for n, a in w.items()}
+        wp[k][(l,) + idx] += 1e-6
+        wm[k][(l,) + idx] -= 1e-6
+        assert abs((loss(X, wp) - loss(X, wm)) / 2e-6 - grads[k][idx]) < 1e-4, k
+
