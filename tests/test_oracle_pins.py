@@ -508,8 +508,8 @@ def test_block_bwd_vs_torch_autograd_and_finite_differences():
     Xm[1, 3, 2] -= 1e-6
     assert abs((loss(Xp, w) - loss(Xm, w)) / 2e-6 - dX[1, 3, 2]) < 1e-5
     for k, idx in (("w_qkv", (D + 1, 2)), ("w_proj", (0, 1)), ("w_fc1", (3, 0)), ("w_fc2", (2, 5)), ("ln1_g", (1,)), ("b_fc1", (4,))):
-        wp = {n: a.copy() for n, a in w.items()}
-        wm = {n: a.copy() for n, a in w.items()}
+        wp = {n: np.asarray(a, np.float64).copy() for n, a in w.items()}      # fp32 storage would round the step
+        wm = {n: np.asarray(a, np.float64).copy() for n, a in w.items()}
         wp[k][(l,) + idx] += 1e-6
         wm[k][(l,) + idx] -= 1e-6
         assert abs((loss(X, wp) - loss(X, wm)) / 2e-6 - grads[k][idx]) < 1e-4, k
