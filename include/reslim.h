@@ -179,6 +179,68 @@ int tiles_attention_bwd(reslim_ctx *ctx, const void *qkv, const void *out, const
                         const void *d_out, void *d_qkv, int32_t batch, void *workspace,
                         size_t ws_bytes, void *hip_stream);
 
+/* ---- Training of a block (the paper trains the model, Sec. 5; it prints no gradient
+ * formulas: everything below is the chain rule through the forward operations of Sec. 3 /
+ * 4.1 / 4.2, tile by tile).  Activations ("act") are float or bfloat16 as cfg.dtype says;
+ * parameter gradients are fp32, WRITTEN (not accumulated) by each call, summed over all
+ * tokens of all tiles and samples in a fixed order (deterministic).  All pointers are device
+ * pointers unless stated; work is enqueued on hip_stream; no allocation, no synchronisation
+ * except in reslim_train_prepare. ---- */
+
+/* Allocates and fills the [in, out] copies of the block weights that the input-gradient
+ * GEMMs read (doubles the block weights' memory).  Call once after reslim_create and before
+ * any other training entry point; synchronises the device.  Idempotent. */
+int reslim_train_prepare(reslim_ctx *ctx);
+
+/* Gradient of the per-token LayerNorm y = (x - mean) / sqrt(var + 1e-5) * gamma + beta over
+ * rows of D = embed_dim elements:  dx = res + (g - mean(g) - xh mean(g xh)) / sigma with
+ * g = gamma dy;  dgamma = sum_rows dy xh;  dbeta = sum_rows dy.
+ *   x float [rows, D]; dy act [rows, D]; gamma float [D]; res float [rows, D] or NULL;
+ *   dx float [rows, D] out; dgamma, dbeta float [D] out;
+ *   workspace: 256-byte aligned, >= min(1024, ceil(rows / 4)) * 2 * D floats. */
+int reslim_layernorm_bwd(reslim_ctx *ctx, const float *x, const void *dy, const float *gamma,
+                         const float *res, float *dx, float *dgamma, float *dbeta, int64_t rows,
+                         void *workspace, size_t ws_bytes, void *hip_stream);
+
+/* Gradient of one linear layer y = x W^T + b of block `layer`; which = 0: qkv (D -> 3D),
+ * 1: proj (D -> D), 2: fc1 (D -> R), 3: fc2 (R -> D), R = mlp_ratio * D:
+ *   dx = dy W (skipped when dx is NULL),  dW = dy^T x,  db = column sums of dy.
+ *   x act [rows, in]; dy act [rows, out]; dx act [rows, in] out; dw float [out, in] out;
+ *   db float [out] out; workspace >= reslim_linear_bwd_workspace_bytes(). */
+int reslim_linear_bwd_workspace_bytes(const reslim_ctx *ctx, int32_t which, int32_t rows, size_t *out);
+int reslim_linear_bwd(reslim_ctx *ctx, int32_t layer, int32_t which, const void *x, const void *dy,
+                      void *dx, float *dw, float *db, int32_t rows, void *workspace, size_t ws_bytes,
+                      void *hip_stream);
+
+/* Gradients of the twelve parameter tensors of one block, device fp32, shapes as in
+ * reslim_weights without the leading depth axis. */
+typedef struct {
+  float *ln1_g, *ln1_b, *w_qkv, *b_qkv, *w_proj, *b_proj;
+  float *ln2_g, *ln2_b, *w_fc1, *b_fc1, *w_fc2, *b_fc2;
+} reslim_block_grads;
+
+/* Sizes of the per-block buffer of saved activations (what reslim_block_fwd_train keeps for
+ * reslim_block_bwd: both LayerNorm outputs, qkv, the attention output and its log-sum-exp,
+ * the stream after the attention half, the feed-forward hidden layer before and after GELU)
+ * and of the scratch either call needs.  Either pointer may be NULL. */
+int reslim_block_train_bytes(const reslim_ctx *ctx, int32_t batch, size_t *saved_bytes, size_t *ws_bytes);
+
+/* reslim_block_fwd that keeps its intermediates: x_out = block(x_in), both float
+ * [batch, n_h, D], not aliased.  saved / workspace: 256-byte aligned, caller-owned. */
+int reslim_block_fwd_train(reslim_ctx *ctx, int32_t layer, const float *x_in, float *x_out, void *saved,
+                           size_t saved_bytes, int32_t batch, void *workspace, size_t ws_bytes,
+                           void *hip_stream);
+
+/* Gradient of that block: from d_x_out (gradient of the loss w.r.t. x_out), the block's input
+ * x_in and the saved buffer of the matching reslim_block_fwd_train call it writes d_x_in
+ * (float [batch, n_h, D], not aliased with d_x_out) and all twelve parameter
+ * gradients.  Errors: RESLIM_EINVAL (null, layer, prepare not called), RESLIM_ESHAPE,
+ * RESLIM_EWORKSPACE, RESLIM_EHIP. */
+int reslim_block_bwd(reslim_ctx *ctx, int32_t layer, const float *x_in, const void *saved,
+                     size_t saved_bytes, const float *d_x_out, float *d_x_in,
+                     const reslim_block_grads *grads, int32_t batch, void *workspace, size_t ws_bytes,
+                     void *hip_stream);
+
 /* One pre-LayerNorm transformer block `layer` (0-based) on the tile-major stream:
  * X += proj(tile_attention(qkv(LN1(X)))); X += fc2(gelu(fc1(LN2(X)))).
  *   x_inout dev float [batch, n_h, D], updated in place */

@@ -31,7 +31,9 @@ EXPORTS = ["tiles_partition", "reslim_create", "reslim_destroy", "reslim_last_er
            "reslim_debug_set_gemm_tile", "reslim_profile_enable", "reslim_profile_reset", "reslim_profile_read",
            "reslim_debug_copy", "reslim_debug_set_attention_variant",
            "reslim_bayes_loss_workspace_bytes", "reslim_bayes_loss_fwd", "tiles_attention_fwd_lse",
-           "tiles_attention_bwd_workspace_bytes", "tiles_attention_bwd"]
+           "tiles_attention_bwd_workspace_bytes", "tiles_attention_bwd",
+           "reslim_train_prepare", "reslim_layernorm_bwd", "reslim_linear_bwd_workspace_bytes", "reslim_linear_bwd",
+           "reslim_block_train_bytes", "reslim_block_fwd_train", "reslim_block_bwd"]
 
 
 class ReslimConfigC(C.Structure):
@@ -45,6 +47,13 @@ class ReslimWeightsC(C.Structure):
 class TileDesc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("y0", "y1", "x0", "x1", "Y0", "Y1", "X0", "X1")] + \
                [("tok_off", C.c_int64), ("n_tok", C.c_int32), ("_pad", C.c_int32)]
+
+
+BLOCK_PARAMS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_proj", "b_proj", "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
+
+
+class BlockGradsC(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in BLOCK_PARAMS]
 
 
 class ProfileRecord(C.Structure):
@@ -86,6 +95,13 @@ def load() -> C.CDLL:
     lib.tiles_attention_bwd_workspace_bytes.argtypes = [vp, i32, szp]
     lib.tiles_attention_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, C.c_size_t, vp]
     lib.reslim_block_fwd.argtypes = [vp, i32, vp, i32, vp, C.c_size_t, vp]
+    lib.reslim_train_prepare.argtypes = [vp]
+    lib.reslim_layernorm_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.c_int64, vp, C.c_size_t, vp]
+    lib.reslim_linear_bwd_workspace_bytes.argtypes = [vp, i32, i32, szp]
+    lib.reslim_linear_bwd.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, i32, vp, C.c_size_t, vp]
+    lib.reslim_block_train_bytes.argtypes = [vp, i32, szp, szp]
+    lib.reslim_block_fwd_train.argtypes = [vp, i32, vp, vp, vp, C.c_size_t, i32, vp, C.c_size_t, vp]
+    lib.reslim_block_bwd.argtypes = [vp, i32, vp, vp, C.c_size_t, vp, vp, C.POINTER(BlockGradsC), i32, vp, C.c_size_t, vp]
     lib.reslim_head_fwd.argtypes = [vp, vp, vp, vp, i32, vp, C.c_size_t, vp]
     lib.reslim_forward.argtypes = [vp, vp, vp, i32, vp, C.c_size_t, vp]
     dp = C.POINTER(C.c_double)
@@ -242,6 +258,51 @@ def tiles_attention_bwd(ctx, qkv, out, lse, d_out, d_qkv, batch, workspace, stre
 
 def tiles_attention_fwd(ctx, qkv, out, batch, stream=None):
     _check(load().tiles_attention_fwd(ctx, qkv.data_ptr(), out.data_ptr(), batch, _stream_ptr(stream)), ctx)
+
+
+def _nbytes(t) -> int:
+    return t.numel() * t.element_size()
+
+
+def reslim_train_prepare(ctx):
+    _check(load().reslim_train_prepare(ctx), ctx)
+
+
+def reslim_layernorm_bwd(ctx, x, dy, gamma, res, dx, dgamma, dbeta, rows, workspace, stream=None):
+    _check(load().reslim_layernorm_bwd(ctx, x.data_ptr(), dy.data_ptr(), gamma.data_ptr(),
+                                       res.data_ptr() if res is not None else None, dx.data_ptr(), dgamma.data_ptr(),
+                                       dbeta.data_ptr(), rows, workspace.data_ptr(), _nbytes(workspace), _stream_ptr(stream)), ctx)
+
+
+def reslim_linear_bwd_workspace_bytes(ctx, which, rows) -> int:
+    out = C.c_size_t(0)
+    _check(load().reslim_linear_bwd_workspace_bytes(ctx, which, rows, C.byref(out)), ctx)
+    return out.value
+
+
+def reslim_linear_bwd(ctx, layer, which, x, dy, dx, dw, db, rows, workspace, stream=None):
+    _check(load().reslim_linear_bwd(ctx, layer, which, x.data_ptr(), dy.data_ptr(), dx.data_ptr() if dx is not None else None,
+                                    dw.data_ptr(), db.data_ptr(), rows, workspace.data_ptr(), _nbytes(workspace),
+                                    _stream_ptr(stream)), ctx)
+
+
+def reslim_block_train_bytes(ctx, batch):
+    a, b = C.c_size_t(0), C.c_size_t(0)
+    _check(load().reslim_block_train_bytes(ctx, batch, C.byref(a), C.byref(b)), ctx)
+    return a.value, b.value
+
+
+def reslim_block_fwd_train(ctx, layer, x_in, x_out, saved, batch, workspace, stream=None):
+    _check(load().reslim_block_fwd_train(ctx, layer, x_in.data_ptr(), x_out.data_ptr(), saved.data_ptr(), _nbytes(saved),
+                                         batch, workspace.data_ptr(), _nbytes(workspace), _stream_ptr(stream)), ctx)
+
+
+def reslim_block_bwd(ctx, layer, x_in, saved, d_x_out, d_x_in, grads, batch, workspace, stream=None):
+    """grads: dict name -> fp32 CUDA tensor for every name in BLOCK_PARAMS (written)."""
+    g = BlockGradsC(**{n: grads[n].data_ptr() for n in BLOCK_PARAMS})
+    _check(load().reslim_block_bwd(ctx, layer, x_in.data_ptr(), saved.data_ptr(), _nbytes(saved), d_x_out.data_ptr(),
+                                   d_x_in.data_ptr(), C.byref(g), batch, workspace.data_ptr(), _nbytes(workspace),
+                                   _stream_ptr(stream)), ctx)
 
 
 def reslim_block_fwd(ctx, layer, x_inout, batch, workspace, stream=None):

@@ -39,6 +39,7 @@ template <> struct Act<bf16_t> {
 struct LayerWeights {
   float *ln1_g, *ln1_b, *ln2_g, *ln2_b;      // [D] fp32
   void *w_qkv, *w_proj, *w_fc1, *w_fc2;      // act type, [out, in]
+  void *wt_qkv = nullptr, *wt_proj = nullptr, *wt_fc1 = nullptr, *wt_fc2 = nullptr;   // [in, out] copies for the input-gradient GEMMs (reslim_train_prepare)
   float *b_qkv, *b_proj, *b_fc1, *b_fc2;     // fp32
 };
 
@@ -128,6 +129,21 @@ hipError_t launch_tiles_attention_bwd(const reslim_ctx *c, const void *qkv, cons
                                       hipStream_t st);
 size_t tiles_attention_bwd_ws_bytes(const reslim_ctx *c, int batch);
 hipError_t attention_bwd_init();
+// ---- training-side kernels
+hipError_t wgrad_init();
+size_t wgrad_ws_bytes(int dtype, int M, int N, int K);
+// dW[N, K] (fp32) = dY[M, N]^T X[M, K]; ws >= wgrad_ws_bytes; zeros: >= 16 zero bytes on the device
+hipError_t launch_wgrad(int dtype, const void *dy, const void *x, float *dw, int M, int N, int K, void *ws,
+                        const void *zeros, hipStream_t st);
+int layernorm_bwd_slabs(int64_t rows);   // partial rows (of 2 D floats) launch_layernorm_bwd writes
+hipError_t launch_layernorm_bwd(int dtype, const float *x, const void *dy, const float *g, const float *res,
+                                float *dx_out, void *act_out, float *partial, float *dgamma, float *dbeta,
+                                int64_t rows, int D, hipStream_t st);
+hipError_t launch_gelu(int dtype, bool bwd, const void *h, const void *dy, void *out, int64_t n, hipStream_t st);
+hipError_t launch_to_act(int dtype, const float *src, void *dst, int64_t n, hipStream_t st);
+int colsum_slabs(int64_t rows);          // partial rows (of N floats) launch_colsum writes
+hipError_t launch_colsum(int dtype, const void *a, float *partial, float *out, int64_t rows, int N, hipStream_t st);
+hipError_t launch_transpose(int dtype, const void *src, void *dst, int R, int C, hipStream_t st);
 hipError_t attention_init();
 hipError_t elementwise_init();
 hipError_t launch_copy_probe(const void *src, void *dst, size_t bytes, hipStream_t st);

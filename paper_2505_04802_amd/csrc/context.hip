@@ -255,6 +255,7 @@ extern "C" int reslim_create(const reslim_config *cfg, const reslim_weights *w, 
     hipError_t e = gemm_init();
     if (e == hipSuccess) e = attention_init();
     if (e == hipSuccess) e = attention_bwd_init();
+    if (e == hipSuccess) e = wgrad_init();
     if (e == hipSuccess) e = elementwise_init();
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) return fail(RESLIM_EHIP, std::string("kernel setup failed: ") + hipGetErrorString(e));

@@ -1,0 +1,330 @@
+// Bandwidth-bound kernels of the block's gradient (training of the model of ORBIT-2
+// Sec. 4.1; the paper prints no formulas, these are the chain rule through the
+// forward kernels of elementwise.hip and the GEMM epilogues):
+//   layernorm_bwd   gradient of the per-token normalisation + partial sums of d gamma, d beta
+//   gelu_fwd/bwd    exact (erf) GELU and its derivative, element by element
+//   colsum          column sums of an activation gradient = gradient of a bias
+//   partial_reduce  fixed-order sum of per-work-group partial rows (deterministic)
+//   to_act          fp32 -> activation type
+//   transpose       weight [out, in] -> [in, out], once, for the input-gradient GEMMs
+#include "common.h"
+
+namespace reslim {
+
+template <class T> struct Vec4;     // four consecutive activation elements
+template <> struct Vec4<float> {
+  static __device__ __forceinline__ float4 load(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+  static __device__ __forceinline__ void store(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
+};
+template <> struct Vec4<bf16_t> {
+  static __device__ __forceinline__ float4 load(const bf16_t *p) {
+    const uint2 r = *reinterpret_cast<const uint2 *>(p);
+    return make_float4(__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xffff0000u), __uint_as_float(r.y << 16),
+                       __uint_as_float(r.y & 0xffff0000u));
+  }
+  static __device__ __forceinline__ void store(bf16_t *p, float4 v) {
+    uint2 r;
+    r.x = pack_bf16x2(v.x, v.y);
+    r.y = pack_bf16x2(v.z, v.w);
+    *reinterpret_cast<uint2 *>(p) = r;
+  }
+};
+
+// ------------------------------------------------------------------ LayerNorm gradient
+// y = xh * gamma + beta, xh = (x - mean) / sigma.  With g = gamma * dy and means over the row:
+//   dx = (g - mean(g) - xh * mean(g * xh)) / sigma,   d gamma = sum_rows dy * xh,   d beta = sum_rows dy.
+// One wave per row as in the forward kernel (statistics recomputed from x, the row stays in
+// registers); a work-group owns a contiguous slab of rows, its four waves keep per-lane sums of
+// dy*xh and dy over their rows, add them through LDS at the end and write ONE partial row pair;
+// partial_reduce adds the slabs in a fixed order.
+//   dx_out = res + dx (res optional: the gradient arriving over the skip connection)
+//   act_out (optional) = dx_out rounded to the activation type (operand of the next GEMMs)
+template <class T, int NV>
+__global__ __launch_bounds__(256) void layernorm_bwd_kernel(const float *__restrict__ x, const T *__restrict__ dy,
+                                                            const float *__restrict__ g, const float *__restrict__ res,
+                                                            float *__restrict__ dx_out, T *__restrict__ act_out,
+                                                            float *__restrict__ partial, int64_t rows, int rows_per_wg,
+                                                            int D) {
+  extern __shared__ float sm[];      // [2][D]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nv = D / 4;
+  const int64_t r0 = static_cast<int64_t>(blockIdx.x) * rows_per_wg;
+  const int64_t r1 = r0 + rows_per_wg < rows ? r0 + rows_per_wg : rows;
+  const float4 *g4 = reinterpret_cast<const float4 *>(g);
+  float4 gam[NV], sg[NV], sb[NV];
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int k = lane + 64 * i;
+    gam[i] = k < nv ? g4[k] : make_float4(0.f, 0.f, 0.f, 0.f);
+    sg[i] = sb[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  const float inv_d = 1.0f / static_cast<float>(D);
+  for (int64_t row = r0 + wave; row < r1; row += 4) {
+    const float4 *xr = reinterpret_cast<const float4 *>(x + row * D);
+    float4 v[NV], d[NV];
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int k = lane + 64 * i;
+      v[i] = k < nv ? xr[k] : make_float4(0.f, 0.f, 0.f, 0.f);
+      d[i] = k < nv ? Vec4<T>::load(dy + row * D + 4 * k) : make_float4(0.f, 0.f, 0.f, 0.f);
+      sum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+    const float mean = sum * inv_d;
+    float sq = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int k = lane + 64 * i;
+      if (k < nv) {
+        v[i].x -= mean; v[i].y -= mean; v[i].z -= mean; v[i].w -= mean;
+        sq += (v[i].x * v[i].x + v[i].y * v[i].y) + (v[i].z * v[i].z + v[i].w * v[i].w);
+      }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sq += __shfl_xor(sq, o);
+    const float rstd = rsqrtf(sq * inv_d + 1e-5f);
+    float m1 = 0.f, m2 = 0.f;      // sums of g and g * xh
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      v[i].x *= rstd; v[i].y *= rstd; v[i].z *= rstd; v[i].w *= rstd;      // xh
+      sg[i].x += d[i].x * v[i].x; sg[i].y += d[i].y * v[i].y; sg[i].z += d[i].z * v[i].z; sg[i].w += d[i].w * v[i].w;
+      sb[i].x += d[i].x; sb[i].y += d[i].y; sb[i].z += d[i].z; sb[i].w += d[i].w;
+      d[i].x *= gam[i].x; d[i].y *= gam[i].y; d[i].z *= gam[i].z; d[i].w *= gam[i].w;  // g
+      m1 += (d[i].x + d[i].y) + (d[i].z + d[i].w);
+      m2 += (d[i].x * v[i].x + d[i].y * v[i].y) + (d[i].z * v[i].z + d[i].w * v[i].w);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      m1 += __shfl_xor(m1, o);
+      m2 += __shfl_xor(m2, o);
+    }
+    m1 *= inv_d;
+    m2 *= inv_d;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int k = lane + 64 * i;
+      if (k < nv) {
+        float4 o4;
+        o4.x = (d[i].x - m1 - v[i].x * m2) * rstd;
+        o4.y = (d[i].y - m1 - v[i].y * m2) * rstd;
+        o4.z = (d[i].z - m1 - v[i].z * m2) * rstd;
+        o4.w = (d[i].w - m1 - v[i].w * m2) * rstd;
+        if (res) {
+          const float4 rr = reinterpret_cast<const float4 *>(res + row * D)[k];
+          o4.x += rr.x; o4.y += rr.y; o4.z += rr.z; o4.w += rr.w;
+        }
+        reinterpret_cast<float4 *>(dx_out + row * D)[k] = o4;
+        if (act_out) Vec4<T>::store(act_out + row * D + 4 * k, o4);
+      }
+    }
+  }
+  // waves 1, 2, 3 hand their sums to wave 0 one after the other (fixed order) through one row pair
+  float4 *box = reinterpret_cast<float4 *>(sm);
+  for (int w = 1; w < 4; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        const int k = lane + 64 * i;
+        if (k < nv) {
+          box[k] = sg[i];
+          box[nv + k] = sb[i];
+        }
+      }
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        const int k = lane + 64 * i;
+        if (k < nv) {
+          const float4 oa = box[k], ob = box[nv + k];
+          sg[i].x += oa.x; sg[i].y += oa.y; sg[i].z += oa.z; sg[i].w += oa.w;
+          sb[i].x += ob.x; sb[i].y += ob.y; sb[i].z += ob.z; sb[i].w += ob.w;
+        }
+      }
+    }
+    __syncthreads();
+  }
+  if (wave == 0) {
+    float4 *pg = reinterpret_cast<float4 *>(partial + static_cast<size_t>(blockIdx.x) * 2 * D);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int k = lane + 64 * i;
+      if (k < nv) {
+        pg[k] = sg[i];
+        pg[nv + k] = sb[i];
+      }
+    }
+  }
+}
+
+// out[j] = sum over p < n_part of partial[p * stride + j], p ascending (deterministic)
+__global__ __launch_bounds__(256) void partial_reduce_kernel(const float *__restrict__ partial, float *__restrict__ out,
+                                                             int n_part, int64_t stride, int64_t n) {
+  const int64_t j = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (j >= n) return;
+  float acc = 0.f;
+  for (int p = 0; p < n_part; ++p) acc += partial[p * stride + j];
+  out[j] = acc;
+}
+
+hipError_t launch_partial_reduce(const float *partial, float *out, int n_part, int64_t stride, int64_t n, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  partial_reduce_kernel<<<dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, st>>>(partial, out, n_part, stride, n);
+  return hipGetLastError();
+}
+
+int layernorm_bwd_slabs(int64_t rows) { return static_cast<int>(rows < 4096 ? (rows + 3) / 4 : 1024); }
+
+template <class T>
+static hipError_t launch_ln_bwd_t(const float *x, const void *dy, const float *g, const float *res, float *dx_out,
+                                  void *act_out, float *partial, float *dgamma, float *dbeta, int64_t rows, int D,
+                                  hipStream_t st) {
+  const int nv = (D / 4 + 63) / 64;
+  int n_wg = layernorm_bwd_slabs(rows);
+  const int rpw = static_cast<int>((rows + n_wg - 1) / n_wg);
+  n_wg = static_cast<int>((rows + rpw - 1) / rpw);
+  const size_t lds = static_cast<size_t>(2) * D * sizeof(float);
+  if (lds > 60 * 1024) return hipErrorInvalidValue;
+  const dim3 grid(n_wg), blk(256);
+  const T *d = static_cast<const T *>(dy);
+  T *ao = static_cast<T *>(act_out);
+#define RESLIM_LNB(NV) layernorm_bwd_kernel<T, NV><<<grid, blk, lds, st>>>(x, d, g, res, dx_out, ao, partial, rows, rpw, D)
+  if (nv <= 1) RESLIM_LNB(1);
+  else if (nv <= 2) RESLIM_LNB(2);
+  else if (nv <= 4) RESLIM_LNB(4);
+  else if (nv <= 8) RESLIM_LNB(8);
+  else if (nv <= 16) RESLIM_LNB(16);      // D = 4096: the row and its sums exceed the register file (slow, correct)
+  else return hipErrorInvalidValue;
+#undef RESLIM_LNB
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  // partial rows are [d gamma | d beta] pairs of 2 D floats
+  e = launch_partial_reduce(partial, dgamma, n_wg, 2 * static_cast<int64_t>(D), D, st);
+  if (e != hipSuccess) return e;
+  return launch_partial_reduce(partial + D, dbeta, n_wg, 2 * static_cast<int64_t>(D), D, st);
+}
+
+// partial: dev float, at least layernorm_bwd_slabs(rows) * 2 * D elements
+hipError_t launch_layernorm_bwd(int dtype, const float *x, const void *dy, const float *g, const float *res,
+                                float *dx_out, void *act_out, float *partial, float *dgamma, float *dbeta,
+                                int64_t rows, int D, hipStream_t st) {
+  if (D % 4 != 0 || rows <= 0) return hipErrorInvalidValue;
+  return dtype == RESLIM_BF16 ? launch_ln_bwd_t<bf16_t>(x, dy, g, res, dx_out, act_out, partial, dgamma, dbeta, rows, D, st)
+                              : launch_ln_bwd_t<float>(x, dy, g, res, dx_out, act_out, partial, dgamma, dbeta, rows, D, st);
+}
+
+// ------------------------------------------------------------------ GELU, element by element
+__device__ __forceinline__ float gelu_f(float v) { return 0.5f * v * (1.0f + erff(v * 0.70710678118654752f)); }
+// d/dv [v Phi(v)] = Phi(v) + v phi(v)
+__device__ __forceinline__ float gelu_grad_f(float v) {
+  return 0.5f * (1.0f + erff(v * 0.70710678118654752f)) + v * 0.3989422804014327f * __expf(-0.5f * v * v);
+}
+
+// BWD = false: out = gelu(h).   BWD = true: out = dy * gelu'(h).
+template <class T, bool BWD>
+__global__ __launch_bounds__(256) void gelu_kernel(const T *__restrict__ h, const T *__restrict__ dy, T *__restrict__ out,
+                                                   int64_t n4) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (i >= n4) return;
+  const float4 v = Vec4<T>::load(h + 4 * i);
+  float4 o;
+  if constexpr (BWD) {
+    const float4 d = Vec4<T>::load(dy + 4 * i);
+    o = make_float4(d.x * gelu_grad_f(v.x), d.y * gelu_grad_f(v.y), d.z * gelu_grad_f(v.z), d.w * gelu_grad_f(v.w));
+  } else {
+    o = make_float4(gelu_f(v.x), gelu_f(v.y), gelu_f(v.z), gelu_f(v.w));
+  }
+  Vec4<T>::store(out + 4 * i, o);
+}
+
+hipError_t launch_gelu(int dtype, bool bwd, const void *h, const void *dy, void *out, int64_t n, hipStream_t st) {
+  if (n % 4 != 0) return hipErrorInvalidValue;
+  const int64_t n4 = n / 4, blocks = (n4 + 255) / 256;
+  if (blocks < 1) return hipSuccess;
+  if (blocks > INT32_MAX) return hipErrorInvalidValue;
+  const dim3 grid(static_cast<unsigned>(blocks)), blk(256);
+  if (dtype == RESLIM_BF16) {
+    if (bwd) gelu_kernel<bf16_t, true><<<grid, blk, 0, st>>>(static_cast<const bf16_t *>(h), static_cast<const bf16_t *>(dy), static_cast<bf16_t *>(out), n4);
+    else gelu_kernel<bf16_t, false><<<grid, blk, 0, st>>>(static_cast<const bf16_t *>(h), nullptr, static_cast<bf16_t *>(out), n4);
+  } else {
+    if (bwd) gelu_kernel<float, true><<<grid, blk, 0, st>>>(static_cast<const float *>(h), static_cast<const float *>(dy), static_cast<float *>(out), n4);
+    else gelu_kernel<float, false><<<grid, blk, 0, st>>>(static_cast<const float *>(h), nullptr, static_cast<float *>(out), n4);
+  }
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ fp32 -> activation type
+template <class T>
+__global__ __launch_bounds__(256) void to_act_kernel(const float *__restrict__ src, T *__restrict__ dst, int64_t n4) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (i < n4) Vec4<T>::store(dst + 4 * i, reinterpret_cast<const float4 *>(src)[i]);
+}
+
+hipError_t launch_to_act(int dtype, const float *src, void *dst, int64_t n, hipStream_t st) {
+  if (n % 4 != 0) return hipErrorInvalidValue;
+  const int64_t n4 = n / 4, blocks = (n4 + 255) / 256;
+  if (blocks < 1) return hipSuccess;
+  if (blocks > INT32_MAX) return hipErrorInvalidValue;
+  if (dtype == RESLIM_BF16) to_act_kernel<bf16_t><<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st>>>(src, static_cast<bf16_t *>(dst), n4);
+  else to_act_kernel<float><<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st>>>(src, static_cast<float *>(dst), n4);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ column sums (bias gradient)
+// grid (column groups of 1024, row slabs); a thread owns 4 consecutive columns of its slab's rows.
+template <class T>
+__global__ __launch_bounds__(256) void colsum_kernel(const T *__restrict__ a, float *__restrict__ partial, int64_t rows,
+                                                     int rows_per_slab, int N) {
+  const int c = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (c >= N) return;
+  const int64_t r0 = static_cast<int64_t>(blockIdx.y) * rows_per_slab;
+  const int64_t r1 = r0 + rows_per_slab < rows ? r0 + rows_per_slab : rows;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int64_t r = r0; r < r1; ++r) {
+    const float4 v = Vec4<T>::load(a + r * N + c);
+    acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+  }
+  *reinterpret_cast<float4 *>(partial + static_cast<size_t>(blockIdx.y) * N + c) = acc;
+}
+
+int colsum_slabs(int64_t rows) { return static_cast<int>(rows < 128 ? 1 : (rows < 128 * 256 ? (rows + 127) / 128 : 256)); }
+
+// partial: dev float, at least colsum_slabs(rows) * N elements
+hipError_t launch_colsum(int dtype, const void *a, float *partial, float *out, int64_t rows, int N, hipStream_t st) {
+  if (N % 4 != 0 || rows <= 0) return hipErrorInvalidValue;
+  int slabs = colsum_slabs(rows);
+  const int rps = static_cast<int>((rows + slabs - 1) / slabs);
+  slabs = static_cast<int>((rows + rps - 1) / rps);
+  const dim3 grid((N / 4 + 255) / 256, slabs), blk(256);
+  if (dtype == RESLIM_BF16) colsum_kernel<bf16_t><<<grid, blk, 0, st>>>(static_cast<const bf16_t *>(a), partial, rows, rps, N);
+  else colsum_kernel<float><<<grid, blk, 0, st>>>(static_cast<const float *>(a), partial, rows, rps, N);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_partial_reduce(partial, out, slabs, N, N, st);
+}
+
+// ------------------------------------------------------------------ weight transpose (once per context)
+template <class T>
+__global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ src, T *__restrict__ dst, int R, int C) {
+  __shared__ T tile[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;      // 32 x 8
+  const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+  for (int j = ty; j < 32; j += 8)
+    if (r0 + j < R && c0 + tx < C) tile[j][tx] = src[static_cast<size_t>(r0 + j) * C + c0 + tx];
+  __syncthreads();
+  for (int j = ty; j < 32; j += 8)
+    if (c0 + j < C && r0 + tx < R) dst[static_cast<size_t>(c0 + j) * R + r0 + tx] = tile[tx][j];
+}
+
+// dst[C, R] = src[R, C]^T
+hipError_t launch_transpose(int dtype, const void *src, void *dst, int R, int C, hipStream_t st) {
+  const dim3 grid((C + 31) / 32, (R + 31) / 32), blk(256);
+  if (dtype == RESLIM_BF16) transpose_kernel<bf16_t><<<grid, blk, 0, st>>>(static_cast<const bf16_t *>(src), static_cast<bf16_t *>(dst), R, C);
+  else transpose_kernel<float><<<grid, blk, 0, st>>>(static_cast<const float *>(src), static_cast<float *>(dst), R, C);
+  return hipGetLastError();
+}
+
+}  // namespace reslim

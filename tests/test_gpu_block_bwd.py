@@ -1,0 +1,114 @@
+"""GPU parity of the training side of a block (through the C ABI) against the CPU oracle's
+chain rule in fp64: the LayerNorm gradient, the gradient of each of the four linear layers
+(input gradient, weight gradient, bias gradient), and the whole block forward-for-training +
+backward (input gradient and all twelve parameter gradients).
+
+Tolerances: fp32 debug path <= 1e-5 (1e-4 for sums over many thousand tokens in fp32),
+bf16 path <= 2e-2, max relative L2 per tensor (the bar of the benchmark definition)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import reslim_oracle as O
+from paper_2505_04802_amd import binding as B
+from paper_2505_04802_amd import workloads as WL
+from test_gpu_parity import SMALL_F32, SMALL_BF16, SMALL_BF16_DH128, TOL, cuda, say, weights_for
+
+pytestmark = pytest.mark.gpu
+CFGS = [SMALL_F32, SMALL_BF16, SMALL_BF16_DH128]
+
+
+def u8(n):
+    return torch.empty(max(n, 256), dtype=torch.uint8, device="cuda")
+
+
+def rnd(shape, seed, bf16):
+    a = np.random.default_rng([seed, 7]).standard_normal(shape, dtype=np.float32)
+    return WL.round_to_bf16(a) if bf16 else a
+
+
+@pytest.mark.parametrize("cfg", CFGS, ids=lambda c: c.name)
+def test_layernorm_bwd_parity(cfg):
+    D, bf = cfg.embed_dim, cfg.dtype == 1
+    rows = 1237                                     # several slabs of rows and a ragged last one
+    x = rnd((rows, D), 1, False) * 1.5 + 0.3
+    dy = rnd((rows, D), 2, bf)
+    res = rnd((rows, D), 3, False)
+    gam = (1 + 0.2 * rnd((D,), 4, False)).astype(np.float32)
+    ref_dx, ref_dg, ref_db = O.layer_norm_bwd(x, gam, dy)
+    with B.Reslim(cfg, weights_for(cfg)) as m:
+        dx = torch.empty((rows, D), dtype=torch.float32, device="cuda")
+        dg, db = torch.empty(D, device="cuda"), torch.empty(D, device="cuda")
+        ws = u8(1024 * 2 * D * 4)
+        B.reslim_layernorm_bwd(m.ctx, cuda(x), cuda(dy, m.act_dtype), cuda(gam), cuda(res), dx, dg, db, rows, ws)
+        torch.cuda.synchronize()
+        for name, got, ref in (("dx", dx, ref_dx + res), ("dgamma", dg, ref_dg), ("dbeta", db, ref_db)):
+            err = O.rel_l2(got.cpu().numpy(), ref)
+            say(f"  layernorm_bwd {cfg.name} {name} rel-L2 {err:.3e}")
+            assert err <= 1e-5, name             # fp32 arithmetic on both paths; dy is the only bf16 input
+        B.reslim_layernorm_bwd(m.ctx, cuda(x), cuda(dy, m.act_dtype), cuda(gam), None, dx, dg, db, rows, ws)
+        assert O.rel_l2(dx.cpu().numpy(), ref_dx) <= 1e-5
+
+
+@pytest.mark.parametrize("cfg", CFGS, ids=lambda c: c.name)
+@pytest.mark.parametrize("which", [0, 1, 2, 3])
+def test_linear_bwd_parity(cfg, which):
+    D, R, bf = cfg.embed_dim, cfg.embed_dim * cfg.mlp_ratio, cfg.dtype == 1
+    n_in, n_out = (R if which == 3 else D), (3 * D, D, R, D)[which]
+    name = ("w_qkv", "w_proj", "w_fc1", "w_fc2")[which]
+    rows = 1000 + 37 * which                        # not a multiple of the token block of the kernels
+    w = weights_for(cfg, std=0.1)
+    x, dy = rnd((rows, n_in), 10 + which, bf), rnd((rows, n_out), 20 + which, bf)
+    ref_dx, ref_dw, ref_db = O.linear_bwd(x, w[name][1], dy)
+    with B.Reslim(cfg, w) as m:
+        B.reslim_train_prepare(m.ctx)
+        dx = torch.empty((rows, n_in), dtype=m.act_dtype, device="cuda")
+        dw = torch.full((n_out, n_in), float("nan"), dtype=torch.float32, device="cuda")
+        db = torch.empty(n_out, dtype=torch.float32, device="cuda")
+        ws = u8(B.reslim_linear_bwd_workspace_bytes(m.ctx, which, rows))
+        B.reslim_linear_bwd(m.ctx, 1, which, cuda(x, m.act_dtype), cuda(dy, m.act_dtype), dx, dw, db, rows, ws)
+        torch.cuda.synchronize()
+        for nm, got, ref, tol in (("dx", dx, ref_dx, TOL[cfg.dtype]), ("dw", dw, ref_dw, 1e-5), ("db", db, ref_db, 1e-5)):
+            err = O.rel_l2(got.float().cpu().numpy(), ref)
+            say(f"  linear_bwd {cfg.name} {name} {nm} rel-L2 {err:.3e}")
+            assert err <= tol, nm                # dw, db: exact products of the given inputs, fp32 sums
+
+
+@pytest.mark.parametrize("cfg", CFGS, ids=lambda c: c.name)
+def test_block_train_parity(cfg):
+    """Forward-for-training and backward of one block on the tile-major stream."""
+    tiles, _, _, n_h = O.tiles_partition(cfg.Hp, cfg.Wp, cfg.tiles_y, cfg.tiles_x, cfg.halo)
+    D, layer = cfg.embed_dim, 1
+    w = weights_for(cfg, std=0.1)                 # wide weights: softmaxes and GELUs far from linear
+    x = rnd((cfg.batch, n_h, D), 30, False)
+    d_out = rnd((cfg.batch, n_h, D), 31, False)
+    ref_out = O.reslim_block(x, tiles, w, layer, cfg.heads)
+    ref_dx, ref_g = O.reslim_block_bwd(x, tiles, w, layer, cfg.heads, d_out)
+    with B.Reslim(cfg, w) as m:
+        B.reslim_train_prepare(m.ctx)
+        sb, wb = B.reslim_block_train_bytes(m.ctx, cfg.batch)
+        saved, ws = u8(sb), u8(wb)
+        x_dev, out = cuda(x), torch.empty((cfg.batch, n_h, D), dtype=torch.float32, device="cuda")
+        B.reslim_block_fwd_train(m.ctx, layer, x_dev, out, saved, cfg.batch, ws)
+        err = O.rel_l2(out.cpu().numpy(), ref_out)
+        say(f"  block_fwd_train {cfg.name} rel-L2 {err:.3e}")
+        assert err <= TOL[cfg.dtype]
+        plain = m.block(layer, x_dev.clone()).cpu().numpy()          # the inference entry point on the same input
+        assert O.rel_l2(out.cpu().numpy(), plain) <= TOL[cfg.dtype]
+        grads = {n: torch.full(np.shape(w[n][layer]), float("nan"), dtype=torch.float32, device="cuda") for n in B.BLOCK_PARAMS}
+        dx = torch.empty_like(out)
+        B.reslim_block_bwd(m.ctx, layer, x_dev, saved, cuda(d_out), dx, grads, cfg.batch, ws)
+        torch.cuda.synchronize()
+        err = O.rel_l2(dx.cpu().numpy(), ref_dx)
+        say(f"  block_bwd {cfg.name} d_x rel-L2 {err:.3e}")
+        assert err <= TOL[cfg.dtype]
+        for n in B.BLOCK_PARAMS:
+            err = O.rel_l2(grads[n].cpu().numpy(), ref_g[n])
+            say(f"  block_bwd {cfg.name} d_{n} rel-L2 {err:.3e}")
+            assert err <= TOL[cfg.dtype], n
+        # determinism: a second backward gives the same bits
+        again = {n: torch.empty_like(grads[n]) for n in B.BLOCK_PARAMS}
+        dx2 = torch.empty_like(dx)
+        B.reslim_block_bwd(m.ctx, layer, x_dev, saved, cuda(d_out), dx2, again, cfg.batch, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(dx, dx2) and all(torch.equal(grads[n], again[n]) for n in B.BLOCK_PARAMS)
