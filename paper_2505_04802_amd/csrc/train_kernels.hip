@@ -160,19 +160,40 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const float *__restr
   }
 }
 
-// out[j] = sum over p < n_part of partial[p * stride + j], p ascending (deterministic)
+// out[j] = sum over p < n_part of partial[p * stride + j] in a fixed order (deterministic).
+// A work-group owns 32 columns; its 8 row groups each add every 8th partial row (four
+// independent running sums per thread keep loads in flight), then the groups are added in order.
 __global__ __launch_bounds__(256) void partial_reduce_kernel(const float *__restrict__ partial, float *__restrict__ out,
                                                              int n_part, int64_t stride, int64_t n) {
-  const int64_t j = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-  if (j >= n) return;
-  float acc = 0.f;
-  for (int p = 0; p < n_part; ++p) acc += partial[p * stride + j];
-  out[j] = acc;
+  __shared__ float sm[8][32];
+  const int col = threadIdx.x & 31, grp = threadIdx.x >> 5;
+  const int64_t j = static_cast<int64_t>(blockIdx.x) * 32 + col;
+  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+  if (j < n) {
+    int p = grp;
+    for (; p + 24 < n_part; p += 32) {
+      a0 += partial[p * stride + j];
+      a1 += partial[(p + 8) * stride + j];
+      a2 += partial[(p + 16) * stride + j];
+      a3 += partial[(p + 24) * stride + j];
+    }
+    for (; p < n_part; p += 8) a0 += partial[p * stride + j];
+  }
+  sm[grp][col] = (a0 + a1) + (a2 + a3);
+  __syncthreads();
+  if (grp == 0 && j < n) {
+    float acc = sm[0][col];
+#pragma unroll
+    for (int g = 1; g < 8; ++g) acc += sm[g][col];
+    out[j] = acc;
+  }
 }
 
 hipError_t launch_partial_reduce(const float *partial, float *out, int n_part, int64_t stride, int64_t n, hipStream_t st) {
   if (n <= 0) return hipSuccess;
-  partial_reduce_kernel<<<dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, st>>>(partial, out, n_part, stride, n);
+  const int64_t blocks = (n + 31) / 32;
+  if (blocks > INT32_MAX) return hipErrorInvalidValue;
+  partial_reduce_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st>>>(partial, out, n_part, stride, n);
   return hipGetLastError();
 }
 
@@ -274,33 +295,63 @@ hipError_t launch_to_act(int dtype, const float *src, void *dst, int64_t n, hipS
 }
 
 // ------------------------------------------------------------------ column sums (bias gradient)
-// grid (column groups of 1024, row slabs); a thread owns 4 consecutive columns of its slab's rows.
+// A thread owns 16 bytes of columns (8 bfloat16 or 4 float); TPR threads cover a row segment of
+// up to 256 * 16 bytes (grid.x segments), the 256 / TPR row lanes of a work-group take the rows
+// of the work-group's slab (grid.y) in turn and are added through LDS in a fixed order.
 template <class T>
 __global__ __launch_bounds__(256) void colsum_kernel(const T *__restrict__ a, float *__restrict__ partial, int64_t rows,
-                                                     int rows_per_slab, int N) {
-  const int c = (blockIdx.x * 256 + threadIdx.x) * 4;
-  if (c >= N) return;
+                                                     int rows_per_slab, int N, int tpr) {
+  constexpr int VEC = 16 / sizeof(T);
+  __shared__ float sm[256 * VEC];
+  const int cg = threadIdx.x % tpr, rl = threadIdx.x / tpr, nrl = 256 / tpr;
+  const int c = (blockIdx.x * tpr + cg) * VEC;
   const int64_t r0 = static_cast<int64_t>(blockIdx.y) * rows_per_slab;
   const int64_t r1 = r0 + rows_per_slab < rows ? r0 + rows_per_slab : rows;
-  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int64_t r = r0; r < r1; ++r) {
-    const float4 v = Vec4<T>::load(a + r * N + c);
-    acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+  float acc[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+  if (c < N) {
+    for (int64_t r = r0 + rl; r < r1; r += nrl) {
+      const uint4 raw = *reinterpret_cast<const uint4 *>(a + r * N + c);
+      if constexpr (sizeof(T) == 2) {
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          acc[2 * e] += __uint_as_float(w[e] << 16);
+          acc[2 * e + 1] += __uint_as_float(w[e] & 0xffff0000u);
+        }
+      } else {
+        acc[0] += __uint_as_float(raw.x); acc[1] += __uint_as_float(raw.y);
+        acc[2] += __uint_as_float(raw.z); acc[3] += __uint_as_float(raw.w);
+      }
+    }
   }
-  *reinterpret_cast<float4 *>(partial + static_cast<size_t>(blockIdx.y) * N + c) = acc;
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) sm[threadIdx.x * VEC + e] = acc[e];
+  __syncthreads();
+  if (rl == 0 && c < N) {
+    for (int g = 1; g < nrl; ++g)
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc[e] += sm[(g * tpr + cg) * VEC + e];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) partial[static_cast<size_t>(blockIdx.y) * N + c + e] = acc[e];
+  }
 }
 
-int colsum_slabs(int64_t rows) { return static_cast<int>(rows < 128 ? 1 : (rows < 128 * 256 ? (rows + 127) / 128 : 256)); }
+int colsum_slabs(int64_t rows) { return static_cast<int>(rows < 32 * 1024 ? (rows + 31) / 32 : 1024); }
 
 // partial: dev float, at least colsum_slabs(rows) * N elements
 hipError_t launch_colsum(int dtype, const void *a, float *partial, float *out, int64_t rows, int N, hipStream_t st) {
-  if (N % 4 != 0 || rows <= 0) return hipErrorInvalidValue;
+  const int vec = dtype == RESLIM_BF16 ? 8 : 4;
+  if (N % vec != 0 || rows <= 0) return hipErrorInvalidValue;
   int slabs = colsum_slabs(rows);
   const int rps = static_cast<int>((rows + slabs - 1) / slabs);
   slabs = static_cast<int>((rows + rps - 1) / rps);
-  const dim3 grid((N / 4 + 255) / 256, slabs), blk(256);
-  if (dtype == RESLIM_BF16) colsum_kernel<bf16_t><<<grid, blk, 0, st>>>(static_cast<const bf16_t *>(a), partial, rows, rps, N);
-  else colsum_kernel<float><<<grid, blk, 0, st>>>(static_cast<const float *>(a), partial, rows, rps, N);
+  int tpr = 256;                               // threads per row segment: a power of two <= 256 covering N / vec
+  while (tpr > 1 && tpr / 2 >= N / vec) tpr /= 2;
+  const dim3 grid((N / vec + tpr - 1) / tpr, slabs), blk(256);
+  if (dtype == RESLIM_BF16) colsum_kernel<bf16_t><<<grid, blk, 0, st>>>(static_cast<const bf16_t *>(a), partial, rows, rps, N, tpr);
+  else colsum_kernel<float><<<grid, blk, 0, st>>>(static_cast<const float *>(a), partial, rows, rps, N, tpr);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   return launch_partial_reduce(partial, out, slabs, N, N, st);

@@ -112,3 +112,34 @@ def test_block_train_parity(cfg):
         B.reslim_block_bwd(m.ctx, layer, x_dev, saved, cuda(d_out), dx2, again, cfg.batch, ws)
         torch.cuda.synchronize()
         assert torch.equal(dx, dx2) and all(torch.equal(grads[n], again[n]) for n in B.BLOCK_PARAMS)
+
+
+def test_block_train_c1_full_size():
+    """The block shape bench.py times (c1: 42,560 tile-major tokens, D = 512, 8 heads, 16 tiles with
+    halo): forward-for-training and backward of one block against the oracle on ALL tokens (the
+    parameter gradients are sums over every token, so nothing can be sampled; the fp64 oracle
+    takes about 15 s for this)."""
+    cfg = WL.CONFIGS["c1"].with_(depth=1)
+    tiles, _, _, n_h = O.tiles_partition(cfg.Hp, cfg.Wp, cfg.tiles_y, cfg.tiles_x, cfg.halo)
+    D = cfg.embed_dim
+    w = WL.make_weights(cfg, std=0.05)
+    x = rnd((cfg.batch, n_h, D), 40, False)
+    d_out = rnd((cfg.batch, n_h, D), 41, False)
+    with B.Reslim(cfg, w) as m:
+        B.reslim_train_prepare(m.ctx)
+        sb, wb = B.reslim_block_train_bytes(m.ctx, cfg.batch)
+        saved, ws = u8(sb), u8(wb)
+        x_dev, out, dx = cuda(x), torch.empty((cfg.batch, n_h, D), device="cuda"), torch.empty((cfg.batch, n_h, D), device="cuda")
+        grads = {n: torch.full(np.shape(w[n][0]), float("nan"), dtype=torch.float32, device="cuda") for n in B.BLOCK_PARAMS}
+        B.reslim_block_fwd_train(m.ctx, 0, x_dev, out, saved, cfg.batch, ws)
+        B.reslim_block_bwd(m.ctx, 0, x_dev, saved, cuda(d_out), dx, grads, cfg.batch, ws)
+        torch.cuda.synchronize()
+        got_out, got_dx = out.cpu().numpy(), dx.cpu().numpy()
+        got_g = {n: grads[n].cpu().numpy() for n in B.BLOCK_PARAMS}
+    say("  oracle ...")
+    ref_out = O.reslim_block(x, tiles, w, 0, cfg.heads)
+    ref_dx, ref_g = O.reslim_block_bwd(x, tiles, w, 0, cfg.heads, d_out)
+    for name, got, ref in [("x_out", got_out, ref_out), ("d_x", got_dx, ref_dx)] + [("d_" + n, got_g[n], ref_g[n]) for n in B.BLOCK_PARAMS]:
+        err = O.rel_l2(got, ref)
+        say(f"  c1 block train {name} rel-L2 {err:.3e}")
+        assert err <= 2e-2, name
