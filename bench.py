@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see
 # profiles/), keyed by (workload, kernel label); None where not measured.
-# Source: profiles/forward_c1_all_kernels.md (fetched + written, scaled by the copy kernel).
+# Source: profiles/forward_and_train_block_c1_all_kernels.md (fetched + written, scaled by the copy kernel).
 MEASURED_TRAFFIC = {
     ("c1", "gemm_fc1"): 153.8e6 + 238.0e6,
     ("c1", "gemm_fc2"): 335.8e6 + 89.5e6,
@@ -34,6 +34,61 @@ MEASURED_TRAFFIC = {
     ("c1", "gemm_proj"): 140.6e6 + 90.1e6,
     ("c1", "layernorm"): 85.7e6 + 42.8e6,
 }
+
+
+def train_block(B, torch, model, cfg, K, verbose):
+    """Times reslim_block_fwd_train + reslim_block_bwd of block 0 on synthetic N(0,1) streams."""
+    D, R = cfg.embed_dim, cfg.embed_dim * cfg.mlp_ratio
+    B.reslim_train_prepare(model.ctx)
+    sb, wb = B.reslim_block_train_bytes(model.ctx, cfg.batch)
+    saved = torch.empty(sb, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(wb, dtype=torch.uint8, device="cuda")
+    g = torch.Generator(device="cpu").manual_seed(0)
+    x = torch.randn((cfg.batch, model.n_h, D), generator=g).cuda()
+    d_out = torch.randn((cfg.batch, model.n_h, D), generator=g).cuda()
+    out, dx = torch.empty_like(x), torch.empty_like(x)
+    shapes = {"ln1_g": (D,), "ln1_b": (D,), "w_qkv": (3 * D, D), "b_qkv": (3 * D,), "w_proj": (D, D), "b_proj": (D,),
+              "ln2_g": (D,), "ln2_b": (D,), "w_fc1": (R, D), "b_fc1": (R,), "w_fc2": (D, R), "b_fc2": (D,)}
+    grads = {n: torch.empty(s, dtype=torch.float32, device="cuda") for n, s in shapes.items()}
+    fwd = lambda: B.reslim_block_fwd_train(model.ctx, 0, x, out, saved, cfg.batch, ws)
+    bwd = lambda: B.reslim_block_bwd(model.ctx, 0, x, saved, d_out, dx, grads, cfg.batch, ws)
+    res = {}
+    for label, fn in (("fwd_train", fwd), ("bwd", bwd)):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K):
+            fn()
+        torch.cuda.synchronize()
+        res[label + "_ms"] = round((time.perf_counter() - t0) / K * 1e3, 4)
+    B.reslim_profile_enable(model.ctx, 32 * K)
+    for _ in range(K):
+        fwd()
+        bwd()
+    torch.cuda.synchronize()
+    agg = {}
+    for name, ms, flop, nbytes in B.reslim_profile_read(model.ctx):
+        a = agg.setdefault(name, dict(calls=0, ms=0.0, flop=0.0, bytes=0.0))
+        a["calls"] += 1
+        a["ms"] += ms
+        a["flop"] += flop
+        a["bytes"] += nbytes
+    B.reslim_profile_enable(model.ctx, 0)
+    ks = []
+    for name, a in agg.items():
+        sec = a["ms"] * 1e-3
+        ks.append(dict(kernel=name, launches=a["calls"] // K, ms=round(a["ms"] / K, 5),
+                       tflops=round(a["flop"] / sec / 1e12, 2) if a["flop"] else None, gbs=round(a["bytes"] / sec / 1e9, 1)))
+    ks.sort(key=lambda k: -k["ms"])
+    flop = sum(a["flop"] for a in agg.values()) / K
+    res["tflops"] = round(flop / ((res["fwd_train_ms"] + res["bwd_ms"]) * 1e-3) / 1e12, 2)
+    res["haloed_tokens_per_s"] = round(cfg.batch * model.n_h / ((res["fwd_train_ms"] + res["bwd_ms"]) * 1e-3), 1)
+    res["kernels"] = ks
+    if verbose:
+        for k in ks:
+            print("train_block " + json.dumps(k), file=sys.stderr)
+    return res
 
 
 def main() -> int:
@@ -45,6 +100,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (developer runs)")
     ap.add_argument("--gemm-tile", type=int, default=-1, help="pin the bf16 GEMM kernel (2 = 128x128 tiles, 3 = persistent 256x256), -1 = heuristic")
     ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
+    ap.add_argument("--no-train-block", action="store_true",
+                    help="skip the extra (untimed in `value`) measurement of one block's training forward + backward")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch the library's plain copy kernel on 1 GiB five times (yardstick for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -134,6 +191,12 @@ def main() -> int:
     if args.kernels:
         for k in kernels:
             print(json.dumps(k), file=sys.stderr)
+
+    # ---- extra, outside `value`: one block's training forward + backward at the same shape
+    # (gradient of tile attention, input- and weight-gradient GEMMs, LayerNorm / GELU gradients)
+    train = None
+    if not args.no_train_block and cfg.depth > 0:
+        train = train_block(B, torch, model, cfg, K, args.kernels)
     model.close()
 
     # ---- the CPU oracle on a bounded sample of the same workload (one sample of the batch)
@@ -168,7 +231,7 @@ def main() -> int:
                    "unique_tokens": tokens, "haloed_tokens": cfg.batch * model.n_h},
         "tflops": round(tflops, 2), "mfma_frac": round(tflops / PEAK_BF16_TFLOPS, 4),
         "haloed_tokens_per_s": round(cfg.batch * model.n_h / (dt / K), 1),
-        "roofline": roof, "cpu_baseline": cpu, "kernels": kernels,
+        "roofline": roof, "cpu_baseline": cpu, "kernels": kernels, "train_block": train,
     }
     print(json.dumps(out))
     return 0
