@@ -38,14 +38,16 @@ def test_layernorm_bwd_parity(cfg):
     ref_dx, ref_dg, ref_db = O.layer_norm_bwd(x, gam, dy)
     with B.Reslim(cfg, weights_for(cfg)) as m:
         dx = torch.empty((rows, D), dtype=torch.float32, device="cuda")
-        dg, db = torch.empty(D, device="cuda"), torch.empty(D, device="cuda")
+        dg, db = (torch.empty(D, dtype=torch.float32, device="cuda") for _ in range(2))
         ws = u8(1024 * 2 * D * 4)
         B.reslim_layernorm_bwd(m.ctx, cuda(x), cuda(dy, m.act_dtype), cuda(gam), cuda(res), dx, dg, db, rows, ws)
         torch.cuda.synchronize()
+        errs = {}
         for name, got, ref in (("dx", dx, ref_dx + res), ("dgamma", dg, ref_dg), ("dbeta", db, ref_db)):
-            err = O.rel_l2(got.cpu().numpy(), ref)
-            say(f"  layernorm_bwd {cfg.name} {name} rel-L2 {err:.3e}")
-            assert err <= 1e-5, name             # fp32 arithmetic on both paths; dy is the only bf16 input
+            errs[name] = O.rel_l2(got.cpu().numpy(), ref)
+            say(f"  layernorm_bwd {cfg.name} {name} rel-L2 {errs[name]:.3e}")
+        # fp32 arithmetic on both paths; dy is the only bf16 input
+        assert max(errs.values()) <= 1e-5, (errs, np.where(np.abs(dg.cpu().numpy() - ref_dg) > 1e-3)[0][:8])
         B.reslim_layernorm_bwd(m.ctx, cuda(x), cuda(dy, m.act_dtype), cuda(gam), None, dx, dg, db, rows, ws)
         assert O.rel_l2(dx.cpu().numpy(), ref_dx) <= 1e-5
 
@@ -129,7 +131,8 @@ def test_block_train_c1_full_size():
         B.reslim_train_prepare(m.ctx)
         sb, wb = B.reslim_block_train_bytes(m.ctx, cfg.batch)
         saved, ws = u8(sb), u8(wb)
-        x_dev, out, dx = cuda(x), torch.empty((cfg.batch, n_h, D), device="cuda"), torch.empty((cfg.batch, n_h, D), device="cuda")
+        x_dev = cuda(x)
+        out, dx = (torch.empty((cfg.batch, n_h, D), dtype=torch.float32, device="cuda") for _ in range(2))
         grads = {n: torch.full(np.shape(w[n][0]), float("nan"), dtype=torch.float32, device="cuda") for n in B.BLOCK_PARAMS}
         B.reslim_block_fwd_train(m.ctx, 0, x_dev, out, saved, cfg.batch, ws)
         B.reslim_block_bwd(m.ctx, 0, x_dev, saved, cuda(d_out), dx, grads, cfg.batch, ws)
