@@ -126,7 +126,7 @@ __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a)
   constexpr int STAGE = 2 * TILE_B + AUXB;
   constexpr int LPW = TILE_B / 1024 / NW;
   constexpr int NKT = BS / 32, NKS = DH / 16, NDT = DH / 32;
-  constexpr bool HAND = DH == 64;         // transposing reads issued by hand (see attention_common.h)
+  constexpr bool HAND = DH <= 128;        // transposing reads issued by hand (see attention_common.h); needs a spill-free kernel
   static_assert(TILE_B % (1024 * NW) == 0 && AUXB % 1024 == 0 && NST * STAGE <= 160 * 1024, "LDS plan");
   static_assert((NST == 2 || NST == 3) && NKT <= 2, "ring of two or three stages of 32 or 64 tokens");
   extern __shared__ __align__(1024) unsigned char smem[];   // NST * STAGE bytes
@@ -622,7 +622,8 @@ static hipError_t launch_bwd_one(const AttnBwdArgs &a, hipStream_t st) {
 // Launch shapes (measured on MI355X): dh = 64: 64-token blocks, three stages; the dQ kernel fits
 // 168 registers = three work-groups per CU, the dK/dV kernel (197) two.  dh = 128: dK and dV in
 // separate passes (their accumulators together with the stationary fragments exceed the register
-// file).  dh = 256: one work-group per CU.
+// file); dQ and dK need ~360 registers and run one work-group per CU without spills (c4: 12.8 ms
+// against 17.4 ms with two spilling work-groups), dV fits two.  dh = 256: one work-group per CU.
 template <bool QS>
 static hipError_t launch_bwd_all(const AttnBwdArgs &a, int dh, hipStream_t st) {
   hipError_t e;
@@ -631,9 +632,9 @@ static hipError_t launch_bwd_all(const AttnBwdArgs &a, int dh, hipStream_t st) {
       e = launch_bwd_one<64, 64, 0, QS, 3, 3>(a, st);
       return e != hipSuccess ? e : launch_bwd_one<64, 64, 1, QS, 2, 3>(a, st);
     case 128:
-      e = launch_bwd_one<128, 32, 0, QS, 2, 3>(a, st);
+      e = launch_bwd_one<128, 32, 0, QS, 1, 3>(a, st);
       if (e == hipSuccess) e = launch_bwd_one<128, 32, 2, QS, 2, 3>(a, st);
-      return e != hipSuccess ? e : launch_bwd_one<128, 32, 3, QS, 2, 3>(a, st);
+      return e != hipSuccess ? e : launch_bwd_one<128, 32, 3, QS, 1, 3>(a, st);
     case 256:
       if (!g_bwd_dh256_ok) return hipErrorInvalidValue;
       e = launch_bwd_one<256, 32, 0, QS, 1, 3>(a, st);
