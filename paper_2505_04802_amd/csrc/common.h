@@ -105,12 +105,16 @@ enum Epilogue {
   EPI_BIAS_RESADD_F32 = 2,// out(f32) += acc + bias
   EPI_BIAS_TAB_F32 = 3,   // out(f32)  = acc + tab[m % tab_rows, n]   (bias folded in tab)
   EPI_BIAS_F32 = 4,       // out(f32)  = acc + bias
-  EPI_BIAS_QSCALE_ACT = 5 // out(act)  = (acc + bias) * (n < qcols ? qscale : 1)   (QKV with pre-scaled q)
+  EPI_BIAS_QSCALE_ACT = 5,// out(act)  = (acc + bias) * (n < qcols ? qscale : 1)   (QKV with pre-scaled q)
+  // training side
+  EPI_BIAS_ACT_GELU2 = 6, // out(act)  = acc + bias;  out2(act) = gelu(acc + bias)    (FC1 keeping both)
+  EPI_BIAS_RES_F32 = 8    // out(f32)  = res[m, n] + acc + bias                       (skip connection from another buffer)
 };
 // C[M, N] (+)= A[M, K] * W[N, K]^T ; A, W act type (bf16 -> MFMA path, float -> fp32 path)
 hipError_t launch_gemm(int dtype, Epilogue epi, const void *A, const void *W, const float *bias,
                        void *out, int ldo, const float *tab, int tab_rows, int M, int N, int K,
-                       hipStream_t st, float qscale = 1.0f, int qcols = 0);
+                       hipStream_t st, float qscale = 1.0f, int qcols = 0, const void *aux = nullptr, void *out2 = nullptr);
+// aux: EPI_BIAS_RES_F32: float [M, ldo] skip input.  out2: EPI_BIAS_ACT_GELU2: act [M, ldo].
 hipError_t gemm_init();
 
 hipError_t launch_layernorm(int dtype, const float *x, const int32_t *row_src, int rows_per_sample_out,

@@ -31,7 +31,10 @@ struct GemmArgs {
   float qscale;   // EPI_BIAS_QSCALE_ACT: factor applied to output columns n < qcols
   int qcols;
   int col_fast;            // one-tile-per-work-group kernel: tile order inside a band
+  const void *aux;         // EPI_BIAS_RES_F32: skip input (fp32), layout of out
+  void *out2;              // EPI_BIAS_ACT_GELU2: second output (act), layout of out
 };
+
 
 __device__ __forceinline__ float gelu_erf(float x) {
   return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f));
@@ -71,9 +74,14 @@ __device__ __forceinline__ void epilogue_block(const GemmArgs &g, const f32x16 &
       static_cast<bf16_t *>(g.out)[o] = f32_to_bf16((v + bias) * (n < g.qcols ? g.qscale : 1.0f));
     } else if constexpr (EPI == EPI_BIAS_GELU_ACT) {
       static_cast<bf16_t *>(g.out)[o] = f32_to_bf16(gelu_erf_fast(v + bias));
+    } else if constexpr (EPI == EPI_BIAS_ACT_GELU2) {
+      static_cast<bf16_t *>(g.out)[o] = f32_to_bf16(v + bias);
+      static_cast<bf16_t *>(g.out2)[o] = f32_to_bf16(gelu_erf_fast(v + bias));
     } else if constexpr (EPI == EPI_BIAS_RESADD_F32) {
       float *p = static_cast<float *>(g.out) + o;
       *p = *p + (v + bias);
+    } else if constexpr (EPI == EPI_BIAS_RES_F32) {
+      static_cast<float *>(g.out)[o] = static_cast<const float *>(g.aux)[o] + (v + bias);
     } else if constexpr (EPI == EPI_BIAS_TAB_F32) {
       static_cast<float *>(g.out)[o] = v + g.tab[static_cast<size_t>(m % g.tab_rows) * g.N + n];
     } else {
@@ -89,7 +97,7 @@ __device__ __forceinline__ void epilogue_block(const GemmArgs &g, const f32x16 &
 // 4-byte accesses for the read-modify-write).
 template <int EPI>
 __device__ __host__ constexpr bool epi_swapped() {
-  return EPI == EPI_BIAS_RESADD_F32 || EPI == EPI_BIAS_TAB_F32;
+  return EPI == EPI_BIAS_RESADD_F32 || EPI == EPI_BIAS_TAB_F32 || EPI == EPI_BIAS_RES_F32;
 }
 
 template <int EPI, int MI, int NI, int MIe = MI, int NIe = NI>
@@ -101,6 +109,8 @@ __device__ __forceinline__ void epilogue_wave_swapped(const GemmArgs &g, const f
     const int m = m_base + i * 32 + l32;
     if (m >= g.M) continue;
     float *orow = out + static_cast<size_t>(m) * g.ldo;
+    // row the skip connection is read from: the output itself (in place) or another buffer
+    const float *rrow = (EPI == EPI_BIAS_RES_F32) ? static_cast<const float *>(g.aux) + static_cast<size_t>(m) * g.ldo : orow;
     const float *trow = (EPI == EPI_BIAS_TAB_F32) ? g.tab + static_cast<size_t>(m % g.tab_rows) * g.N : nullptr;
 #pragma unroll
     for (int j = 0; j < NIe; ++j) {
@@ -113,8 +123,8 @@ __device__ __forceinline__ void epilogue_wave_swapped(const GemmArgs &g, const f
           float4 v = make_float4(acc[i][j][4 * q] + add.x, acc[i][j][4 * q + 1] + add.y, acc[i][j][4 * q + 2] + add.z,
                                  acc[i][j][4 * q + 3] + add.w);
           float4 *p = reinterpret_cast<float4 *>(orow + n);
-          if constexpr (EPI == EPI_BIAS_RESADD_F32) {
-            const float4 x = *p;
+          if constexpr (EPI == EPI_BIAS_RESADD_F32 || EPI == EPI_BIAS_RES_F32) {
+            const float4 x = *reinterpret_cast<const float4 *>(rrow + n);
             v.x += x.x; v.y += x.y; v.z += x.z; v.w += x.w;
           }
           *p = v;
@@ -124,7 +134,7 @@ __device__ __forceinline__ void epilogue_wave_swapped(const GemmArgs &g, const f
             if (n + e < g.N) {
               const float add = (EPI == EPI_BIAS_TAB_F32) ? trow[n + e] : g.bias[n + e];
               float v = acc[i][j][4 * q + e] + add;
-              if constexpr (EPI == EPI_BIAS_RESADD_F32) v += orow[n + e];
+              if constexpr (EPI == EPI_BIAS_RESADD_F32 || EPI == EPI_BIAS_RES_F32) v += rrow[n + e];
               orow[n + e] = v;
             }
         }
@@ -327,6 +337,11 @@ __device__ __forceinline__ void epilogue_store_f32(const GemmArgs &g, int m, int
     out[o] = gelu_erf(v + g.bias[n]);
   } else if constexpr (EPI == EPI_BIAS_RESADD_F32) {
     out[o] = out[o] + (v + g.bias[n]);
+  } else if constexpr (EPI == EPI_BIAS_ACT_GELU2) {
+    out[o] = v + g.bias[n];
+    static_cast<float *>(g.out2)[o] = gelu_erf(v + g.bias[n]);
+  } else if constexpr (EPI == EPI_BIAS_RES_F32) {
+    out[o] = static_cast<const float *>(g.aux)[o] + (v + g.bias[n]);
   } else {
     out[o] = v + g.tab[static_cast<size_t>(m % g.tab_rows) * g.N + n];
   }
@@ -419,7 +434,7 @@ static hipError_t launch_bf16(GemmArgs g, hipStream_t st) {
   const long tiles_big = static_cast<long>((g.M + 255) / 256) * ((g.N + 255) / 256);
   int choice = 2;
   const bool light_epilogue = EPI == EPI_BIAS_ACT || EPI == EPI_BIAS_QSCALE_ACT;
-  const bool rmw_epilogue = EPI == EPI_BIAS_RESADD_F32;      // the persistent kernel cannot hide it behind other groups
+  const bool rmw_epilogue = EPI == EPI_BIAS_RESADD_F32 || EPI == EPI_BIAS_RES_F32;      // the persistent kernel cannot hide it behind other groups
   if (tiles_big >= 2L * g_num_cus && (light_epilogue || g.K >= (rmw_epilogue ? 2048 : 1024))) choice = 3;
   if (g_gemm_tile_override >= 0) choice = g_gemm_tile_override;
   switch (choice) {
@@ -452,18 +467,22 @@ hipError_t gemm_init() {
   if ((e = init_epi<EPI_BIAS_RESADD_F32>()) != hipSuccess) return e;
   if ((e = init_epi<EPI_BIAS_TAB_F32>()) != hipSuccess) return e;
   if ((e = init_epi<EPI_BIAS_QSCALE_ACT>()) != hipSuccess) return e;
+  if ((e = init_epi<EPI_BIAS_ACT_GELU2>()) != hipSuccess) return e;
+  if ((e = init_epi<EPI_BIAS_RES_F32>()) != hipSuccess) return e;
   return init_epi<EPI_BIAS_F32>();
 }
 
 hipError_t launch_gemm(int dtype, Epilogue epi, const void *A, const void *W, const float *bias,
                        void *out, int ldo, const float *tab, int tab_rows, int M, int N, int K,
-                       hipStream_t st, float qscale, int qcols) {
+                       hipStream_t st, float qscale, int qcols, const void *aux, void *out2) {
   if (M <= 0 || N <= 0 || K <= 0) return hipErrorInvalidValue;
   GemmArgs g;
   g.A = A; g.W = W; g.bias = bias; g.out = out; g.tab = tab;
   g.ldo = ldo; g.tab_rows = tab_rows > 0 ? tab_rows : 1;
   g.M = M; g.N = N; g.K = K; g.grid_m = g.grid_n = 0; g.col_fast = g_col_fast;
-  g.qscale = qscale; g.qcols = qcols;
+  g.qscale = qscale; g.qcols = qcols; g.aux = aux; g.out2 = out2;
+  if (epi == EPI_BIAS_RES_F32 && !aux) return hipErrorInvalidValue;
+  if (epi == EPI_BIAS_ACT_GELU2 && !out2) return hipErrorInvalidValue;
   if (dtype == RESLIM_BF16) {
     if (K % 64 != 0) return hipErrorInvalidValue;   // slabs are 64 deep; create() enforces D % 64 == 0
     switch (epi) {
@@ -472,6 +491,8 @@ hipError_t launch_gemm(int dtype, Epilogue epi, const void *A, const void *W, co
       case EPI_BIAS_RESADD_F32: return launch_bf16<EPI_BIAS_RESADD_F32>(g, st);
       case EPI_BIAS_TAB_F32: return launch_bf16<EPI_BIAS_TAB_F32>(g, st);
       case EPI_BIAS_QSCALE_ACT: return launch_bf16<EPI_BIAS_QSCALE_ACT>(g, st);
+      case EPI_BIAS_ACT_GELU2: return launch_bf16<EPI_BIAS_ACT_GELU2>(g, st);
+      case EPI_BIAS_RES_F32: return launch_bf16<EPI_BIAS_RES_F32>(g, st);
       default: return launch_bf16<EPI_BIAS_F32>(g, st);
     }
   }
@@ -481,6 +502,8 @@ hipError_t launch_gemm(int dtype, Epilogue epi, const void *A, const void *W, co
     case EPI_BIAS_RESADD_F32: return launch_f32<EPI_BIAS_RESADD_F32>(g, st);
     case EPI_BIAS_TAB_F32: return launch_f32<EPI_BIAS_TAB_F32>(g, st);
     case EPI_BIAS_QSCALE_ACT: return launch_f32<EPI_BIAS_QSCALE_ACT>(g, st);
+    case EPI_BIAS_ACT_GELU2: return launch_f32<EPI_BIAS_ACT_GELU2>(g, st);
+    case EPI_BIAS_RES_F32: return launch_f32<EPI_BIAS_RES_F32>(g, st);
     default: return launch_f32<EPI_BIAS_F32>(g, st);
   }
 }
