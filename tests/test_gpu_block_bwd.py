@@ -5,6 +5,8 @@ backward (input gradient and all twelve parameter gradients).
 
 Tolerances: fp32 debug path <= 1e-5 (1e-4 for sums over many thousand tokens in fp32),
 bf16 path <= 2e-2, max relative L2 per tensor (the bar of the benchmark definition)."""
+import ctypes
+
 import numpy as np
 import pytest
 import torch
@@ -146,3 +148,58 @@ def test_block_train_c1_full_size():
         err = O.rel_l2(got, ref)
         say(f"  c1 block train {name} rel-L2 {err:.3e}")
         assert err <= 2e-2, name
+
+
+def test_training_entry_point_errors_and_tiny_tiles():
+    """Error codes (no launch happens): training calls before reslim_train_prepare, null buffers,
+    short or misaligned buffers, bad layer; then a tile grid as fine as the patch grid (one-token
+    tiles with halo: every softmax has 1 .. 9 keys) through the whole block gradient."""
+    cfg = SMALL_BF16
+    with B.Reslim(cfg, weights_for(cfg)) as m:
+        lib = B.load()
+        st = torch.cuda.current_stream().cuda_stream
+        n_h, D = m.n_h, cfg.embed_dim
+        x = torch.zeros((cfg.batch, n_h, D), dtype=torch.float32, device="cuda")
+        out, dx = torch.empty_like(x), torch.empty_like(x)
+        sb, wb = B.reslim_block_train_bytes(m.ctx, cfg.batch)
+        saved, ws = u8(sb), u8(wb)
+        args = (x.data_ptr(), out.data_ptr(), saved.data_ptr(), sb, cfg.batch, ws.data_ptr(), wb, st)
+        assert lib.reslim_block_fwd_train(m.ctx, 0, *args) == B.RESLIM_EINVAL
+        assert b"reslim_train_prepare" in lib.reslim_last_error(m.ctx)
+        B.reslim_train_prepare(m.ctx)
+        B.reslim_train_prepare(m.ctx)                                  # idempotent
+        assert lib.reslim_block_fwd_train(m.ctx, cfg.depth, *args) == B.RESLIM_EINVAL
+        assert lib.reslim_block_fwd_train(m.ctx, 0, x.data_ptr(), x.data_ptr(), *args[2:]) == B.RESLIM_EINVAL      # aliased
+        assert lib.reslim_block_fwd_train(m.ctx, 0, x.data_ptr(), out.data_ptr(), saved.data_ptr(), sb - 256, cfg.batch,
+                                          ws.data_ptr(), wb, st) == B.RESLIM_EWORKSPACE
+        assert lib.reslim_block_fwd_train(m.ctx, 0, x.data_ptr(), out.data_ptr(), saved.data_ptr(), sb, cfg.batch,
+                                          ws.data_ptr() + 16, wb - 16, st) == B.RESLIM_EWORKSPACE
+        assert lib.reslim_block_fwd_train(m.ctx, 0, x.data_ptr(), out.data_ptr(), saved.data_ptr(), sb, 0,
+                                          ws.data_ptr(), wb, st) == B.RESLIM_ESHAPE
+        g = B.BlockGradsC()                                            # all twelve pointers null
+        assert lib.reslim_block_bwd(m.ctx, 0, x.data_ptr(), saved.data_ptr(), sb, out.data_ptr(), dx.data_ptr(),
+                                    ctypes.byref(g), cfg.batch, ws.data_ptr(), wb, st) == B.RESLIM_EINVAL
+        assert lib.tiles_attention_bwd(m.ctx, None, None, None, None, None, cfg.batch, ws.data_ptr(), wb, st) == B.RESLIM_EINVAL
+        assert lib.reslim_linear_bwd(m.ctx, 0, 4, x.data_ptr(), x.data_ptr(), None, x.data_ptr(), x.data_ptr(), 8,
+                                     ws.data_ptr(), wb, st) == B.RESLIM_EINVAL
+        assert lib.reslim_layernorm_bwd(m.ctx, x.data_ptr(), x.data_ptr(), x.data_ptr(), None, dx.data_ptr(), dx.data_ptr(),
+                                        dx.data_ptr(), 8, ws.data_ptr(), 64, st) == B.RESLIM_EWORKSPACE
+    tiny = SMALL_BF16.with_(name="tinytiles", H=8, W=12, tiles_y=4, tiles_x=6, halo=1, batch=1)
+    tiles, _, _, n_h = O.tiles_partition(tiny.Hp, tiny.Wp, tiny.tiles_y, tiny.tiles_x, tiny.halo)
+    w = weights_for(tiny, std=0.1)
+    x, d_out = rnd((1, n_h, tiny.embed_dim), 50, False), rnd((1, n_h, tiny.embed_dim), 51, False)
+    ref_dx, ref_g = O.reslim_block_bwd(x, tiles, w, 0, tiny.heads, d_out)
+    with B.Reslim(tiny, w) as m:
+        B.reslim_train_prepare(m.ctx)
+        sb, wb = B.reslim_block_train_bytes(m.ctx, 1)
+        saved, ws = u8(sb), u8(wb)
+        x_dev = cuda(x)
+        out, dx = (torch.empty((1, n_h, tiny.embed_dim), dtype=torch.float32, device="cuda") for _ in range(2))
+        grads = {n: torch.empty(np.shape(w[n][0]), dtype=torch.float32, device="cuda") for n in B.BLOCK_PARAMS}
+        B.reslim_block_fwd_train(m.ctx, 0, x_dev, out, saved, 1, ws)
+        B.reslim_block_bwd(m.ctx, 0, x_dev, saved, cuda(d_out), dx, grads, 1, ws)
+        torch.cuda.synchronize()
+        errs = {"d_x": O.rel_l2(dx.cpu().numpy(), ref_dx)}
+        errs.update({n: O.rel_l2(grads[n].cpu().numpy(), ref_g[n]) for n in B.BLOCK_PARAMS})
+    say(f"  tiny tiles (n_t = {sorted(set(t['n_tok'] for t in tiles))}): worst rel-L2 {max(errs.values()):.3e}")
+    assert max(errs.values()) <= 2e-2, errs
