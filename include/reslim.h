@@ -241,6 +241,23 @@ int reslim_block_bwd(reslim_ctx *ctx, int32_t layer, const float *x_in, const vo
                      const reslim_block_grads *grads, int32_t batch, void *workspace, size_t ws_bytes,
                      void *hip_stream);
 
+/* Dynamic gradient scaling (Sec. 4.4 "Mixed Precision": gradients are taken of a loss multiplied by
+ * a scale S so that small ones survive bfloat16, the scaling is reversed at the parameter update, and
+ * S adapts; the paper names PyTorch's scheme).  The caller multiplies the gradient it feeds into the
+ * backward by S.
+ * reslim_block_grads_unscale: every element of the twelve gradients (device fp32, shapes of
+ *   reslim_block_grads) times inv_scale = 1/S, in place; *found_inf (device int32) is set to 1 when
+ *   any element is then not finite and is otherwise left alone: clear it before the first call of a
+ *   step.  Enqueued on hip_stream.
+ * reslim_grad_scale_update: HOST arithmetic, the schedule of S: a step with found_inf != 0
+ *   multiplies *scale by backoff_factor (0 < . <= 1) and clears *growth_tracker; growth_interval
+ *   clean steps in a row multiply it by growth_factor (>= 1).  PyTorch's defaults: 2, 0.5, 2000.
+ * Errors: RESLIM_EINVAL (null pointer, non-positive or non-finite factor), RESLIM_EHIP. */
+int reslim_block_grads_unscale(reslim_ctx *ctx, const reslim_block_grads *grads, float inv_scale,
+                               int32_t *found_inf, void *hip_stream);
+int reslim_grad_scale_update(float *scale, int32_t *growth_tracker, int32_t found_inf, float growth_factor,
+                             float backoff_factor, int32_t growth_interval);
+
 /* One pre-LayerNorm transformer block `layer` (0-based) on the tile-major stream:
  * X += proj(tile_attention(qkv(LN1(X)))); X += fc2(gelu(fc1(LN2(X)))).
  *   x_inout dev float [batch, n_h, D], updated in place */

@@ -286,6 +286,28 @@ def reslim_block_bwd(X, tiles: Sequence[dict], w, layer: int, heads: int, d_out)
     return dX, grads
 
 
+# ---- dynamic gradient scaling (Sec. 4.4 "Mixed Precision": gradients are taken of a loss multiplied
+# by a scale S so that small ones survive bfloat16, divided by S again at the parameter update, and S
+# adapts: the paper names PyTorch's scheme, whose documented rule is restated here)
+def grads_unscale(grads: Dict[str, np.ndarray], scale: float):
+    """Every gradient divided by the scale, and whether any of them holds a non-finite value."""
+    out = {k: np.asarray(g, F64) / scale for k, g in grads.items()}
+    return out, any(not np.isfinite(g).all() for g in out.values())
+
+
+def grad_scale_update(scale: float, tracker: int, found_inf: bool, growth: float = 2.0, backoff: float = 0.5,
+                      interval: int = 2000):
+    """One step of the scale's schedule: a step with a non-finite gradient multiplies the scale by
+    `backoff` and restarts the count; `interval` clean steps in a row multiply it by `growth`.
+    Returns (scale, tracker)."""
+    if found_inf:
+        return scale * backoff, 0
+    tracker += 1
+    if tracker == interval:
+        return scale * growth, 0
+    return scale, tracker
+
+
 def reslim_block(X, tiles: Sequence[dict], w, layer: int, heads: int):
     """One block applied to the tile-major stream X[B, n_h, D]: every tile is its
     own token set (Sec. 4.2)."""

@@ -33,7 +33,8 @@ EXPORTS = ["tiles_partition", "reslim_create", "reslim_destroy", "reslim_last_er
            "reslim_bayes_loss_workspace_bytes", "reslim_bayes_loss_fwd", "tiles_attention_fwd_lse",
            "tiles_attention_bwd_workspace_bytes", "tiles_attention_bwd",
            "reslim_train_prepare", "reslim_layernorm_bwd", "reslim_linear_bwd_workspace_bytes", "reslim_linear_bwd",
-           "reslim_block_train_bytes", "reslim_block_fwd_train", "reslim_block_bwd"]
+           "reslim_block_train_bytes", "reslim_block_fwd_train", "reslim_block_bwd",
+           "reslim_block_grads_unscale", "reslim_grad_scale_update"]
 
 
 class ReslimConfigC(C.Structure):
@@ -95,6 +96,8 @@ def load() -> C.CDLL:
     lib.tiles_attention_bwd_workspace_bytes.argtypes = [vp, i32, szp]
     lib.tiles_attention_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, C.c_size_t, vp]
     lib.reslim_block_fwd.argtypes = [vp, i32, vp, i32, vp, C.c_size_t, vp]
+    lib.reslim_block_grads_unscale.argtypes = [vp, C.POINTER(BlockGradsC), C.c_float, vp, vp]
+    lib.reslim_grad_scale_update.argtypes = [C.POINTER(C.c_float), C.POINTER(i32), i32, C.c_float, C.c_float, i32]
     lib.reslim_train_prepare.argtypes = [vp]
     lib.reslim_layernorm_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.c_int64, vp, C.c_size_t, vp]
     lib.reslim_linear_bwd_workspace_bytes.argtypes = [vp, i32, i32, szp]
@@ -303,6 +306,19 @@ def reslim_block_bwd(ctx, layer, x_in, saved, d_x_out, d_x_in, grads, batch, wor
     _check(load().reslim_block_bwd(ctx, layer, x_in.data_ptr(), saved.data_ptr(), _nbytes(saved), d_x_out.data_ptr(),
                                    d_x_in.data_ptr(), C.byref(g), batch, workspace.data_ptr(), _nbytes(workspace),
                                    _stream_ptr(stream)), ctx)
+
+
+def reslim_block_grads_unscale(ctx, grads, inv_scale, found_inf, stream=None):
+    """grads: dict of fp32 CUDA tensors (BLOCK_PARAMS), scaled in place; found_inf: int32 CUDA tensor of one element."""
+    g = BlockGradsC(**{n: grads[n].data_ptr() for n in BLOCK_PARAMS})
+    _check(load().reslim_block_grads_unscale(ctx, C.byref(g), inv_scale, found_inf.data_ptr(), _stream_ptr(stream)), ctx)
+
+
+def reslim_grad_scale_update(scale, tracker, found_inf, growth=2.0, backoff=0.5, interval=2000):
+    """Host function: returns the new (scale, tracker)."""
+    s, t = C.c_float(scale), C.c_int32(tracker)
+    _check(load().reslim_grad_scale_update(C.byref(s), C.byref(t), int(bool(found_inf)), growth, backoff, interval))
+    return s.value, t.value
 
 
 def reslim_block_fwd(ctx, layer, x_inout, batch, workspace, stream=None):

@@ -268,3 +268,36 @@ extern "C" int reslim_block_bwd(reslim_ctx *c, int32_t layer, const float *x_in,
   return RESLIM_OK;
 }
 
+// ------------------------------------------------------------------ dynamic gradient scaling (Sec. 4.4)
+extern "C" int reslim_block_grads_unscale(reslim_ctx *c, const reslim_block_grads *grads, float inv_scale,
+                                          int32_t *found_inf, void *hip_stream) {
+  const char *fn = "reslim_block_grads_unscale";
+  if (!c) return RESLIM_EINVAL;
+  if (!grads || !found_inf) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": null argument");
+  if (!(inv_scale > 0.0f) || !std::isfinite(inv_scale)) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": inv_scale must be positive and finite");
+  const int64_t D = c->cfg.embed_dim, R = c->R;
+  float *ptrs[12] = {grads->ln1_g, grads->ln1_b, grads->w_qkv, grads->b_qkv, grads->w_proj, grads->b_proj,
+                     grads->ln2_g, grads->ln2_b, grads->w_fc1, grads->b_fc1, grads->w_fc2, grads->b_fc2};
+  const int64_t sizes[12] = {D, D, 3 * D * D, 3 * D, D * D, D, D, D, R * D, R, D * R, D};
+  for (float *p : ptrs)
+    if (!p) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": null gradient buffer");
+  RESLIM_TRY("launch", launch_unscale_check(ptrs, sizes, 12, inv_scale, found_inf, static_cast<hipStream_t>(hip_stream)));
+  return RESLIM_OK;
+}
+
+// host arithmetic only: the schedule of the scale
+extern "C" int reslim_grad_scale_update(float *scale, int32_t *growth_tracker, int32_t found_inf, float growth_factor,
+                                        float backoff_factor, int32_t growth_interval) {
+  if (!scale || !growth_tracker || !(*scale > 0.0f) || !(growth_factor >= 1.0f) || !(backoff_factor > 0.0f) ||
+      !(backoff_factor <= 1.0f) || growth_interval < 1 || *growth_tracker < 0)
+    return RESLIM_EINVAL;
+  if (found_inf) {
+    *scale *= backoff_factor;
+    *growth_tracker = 0;
+  } else if (++*growth_tracker >= growth_interval) {
+    *scale *= growth_factor;
+    *growth_tracker = 0;
+  }
+  return RESLIM_OK;
+}
+

@@ -148,6 +148,9 @@ hipError_t launch_to_act(int dtype, const float *src, void *dst, int64_t n, hipS
 int colsum_slabs(int64_t rows);          // partial rows (of N floats) launch_colsum writes
 hipError_t launch_colsum(int dtype, const void *a, float *partial, float *out, int64_t rows, int N, hipStream_t st);
 hipError_t launch_transpose(int dtype, const void *src, void *dst, int R, int C, hipStream_t st);
+// every element of `count` (<= 12) fp32 tensors times inv_scale; *flag = 1 when any is not finite
+hipError_t launch_unscale_check(float *const *ptrs, const int64_t *sizes, int count, float inv_scale, int32_t *flag,
+                                hipStream_t st);
 hipError_t attention_init();
 hipError_t elementwise_init();
 hipError_t launch_copy_probe(const void *src, void *dst, size_t bytes, hipStream_t st);

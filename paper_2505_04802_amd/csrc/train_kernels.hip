@@ -357,6 +357,45 @@ hipError_t launch_colsum(int dtype, const void *a, float *partial, float *out, i
   return launch_partial_reduce(partial, out, slabs, N, N, st);
 }
 
+// ------------------------------------------------------------------ gradient unscaling (dynamic gradient scaling)
+// Up to 12 tensors in one launch (blockIdx.y = tensor): every element times inv_scale, and *flag set
+// to 1 when any element is not finite.  The flag is only ever written with 1 (plain vector stores of
+// the same value from several lanes): the caller clears it before the first call of a step.
+struct UnscaleArgs {
+  float *p[12];
+  int64_t n[12];
+  int count;
+};
+__global__ __launch_bounds__(256) void unscale_check_kernel(UnscaleArgs a, float inv_scale, int32_t *flag) {
+  const int which = blockIdx.y;
+  float *p = a.p[which];
+  const int64_t n = a.n[which];
+  bool bad = false;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; i < n; i += static_cast<int64_t>(gridDim.x) * 256) {
+    const float v = p[i] * inv_scale;
+    bad |= !(fabsf(v) <= 3.402823466e38f);      // inf or NaN
+    p[i] = v;
+  }
+  if (bad) *flag = 1;
+}
+
+hipError_t launch_unscale_check(float *const *ptrs, const int64_t *sizes, int count, float inv_scale, int32_t *flag,
+                                hipStream_t st) {
+  if (count < 1 || count > 12) return hipErrorInvalidValue;
+  UnscaleArgs a;
+  int64_t mx = 0;
+  for (int i = 0; i < 12; ++i) {
+    a.p[i] = i < count ? ptrs[i] : nullptr;
+    a.n[i] = i < count ? sizes[i] : 0;
+    if (a.n[i] > mx) mx = a.n[i];
+  }
+  a.count = count;
+  int64_t blocks = (mx + 256 * 8 - 1) / (256 * 8);         // about eight elements per thread in the largest tensor
+  blocks = blocks < 1 ? 1 : (blocks > 4096 ? 4096 : blocks);
+  unscale_check_kernel<<<dim3(static_cast<unsigned>(blocks), count), dim3(256), 0, st>>>(a, inv_scale, flag);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ weight transpose (once per context)
 template <class T>
 __global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ src, T *__restrict__ dst, int R, int C) {

@@ -69,3 +69,22 @@ def test_create_rejects_bad_configs_before_touching_the_gpu():
     assert lib.reslim_create(None, None, None) == B.RESLIM_EINVAL
     assert lib.reslim_workspace_bytes(None, 1, None) == B.RESLIM_EINVAL
     assert lib.reslim_forward(None, None, None, 1, None, 0, None) == B.RESLIM_EINVAL
+
+
+def test_grad_scale_update_host_rule_matches_oracle():
+    """reslim_grad_scale_update is host arithmetic (no GPU): the same sequence of overflow flags through
+    the library and through the oracle's restatement of the rule (itself pinned to PyTorch's GradScaler)."""
+    from oracle import reslim_oracle as O
+    seq = [0, 0, 1, 0, 0, 0, 0, 1, 1, 0, 0, 0, 0, 0, 0, 0]
+    a = b = (65536.0, 0)
+    for f in seq:
+        a = B.reslim_grad_scale_update(a[0], a[1], f, 2.0, 0.5, 3)
+        b = O.grad_scale_update(b[0], b[1], bool(f), 2.0, 0.5, 3)
+        assert a == b
+    lib = B.load()
+    import ctypes as C
+    s, t = C.c_float(1.0), C.c_int32(0)
+    assert lib.reslim_grad_scale_update(None, C.byref(t), 0, 2.0, 0.5, 3) == B.RESLIM_EINVAL
+    assert lib.reslim_grad_scale_update(C.byref(s), C.byref(t), 0, 0.5, 0.5, 3) == B.RESLIM_EINVAL      # growth < 1
+    assert lib.reslim_grad_scale_update(C.byref(s), C.byref(t), 0, 2.0, 0.0, 3) == B.RESLIM_EINVAL      # backoff <= 0
+    assert lib.reslim_grad_scale_update(C.byref(s), C.byref(t), 0, 2.0, 0.5, 0) == B.RESLIM_EINVAL

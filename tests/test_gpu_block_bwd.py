@@ -203,3 +203,42 @@ def test_training_entry_point_errors_and_tiny_tiles():
         errs.update({n: O.rel_l2(grads[n].cpu().numpy(), ref_g[n]) for n in B.BLOCK_PARAMS})
     say(f"  tiny tiles (n_t = {sorted(set(t['n_tok'] for t in tiles))}): worst rel-L2 {max(errs.values()):.3e}")
     assert max(errs.values()) <= 2e-2, errs
+
+
+def test_block_grads_unscale_and_overflow_flag():
+    """Dynamic gradient scaling: a backward on an upstream gradient multiplied by S, unscaled by 1/S,
+    equals the unscaled backward (S a power of two: exact in bf16 and fp32); an infinity planted in
+    one gradient sets the flag, a clean set leaves it alone."""
+    cfg = SMALL_BF16
+    tiles, _, _, n_h = O.tiles_partition(cfg.Hp, cfg.Wp, cfg.tiles_y, cfg.tiles_x, cfg.halo)
+    D, S = cfg.embed_dim, 4096.0
+    w = weights_for(cfg, std=0.1)
+    x, d_out = rnd((cfg.batch, n_h, D), 60, False), rnd((cfg.batch, n_h, D), 61, False)
+    with B.Reslim(cfg, w) as m:
+        B.reslim_train_prepare(m.ctx)
+        sb, wb = B.reslim_block_train_bytes(m.ctx, cfg.batch)
+        saved, ws = u8(sb), u8(wb)
+        x_dev = cuda(x)
+        out, dx = (torch.empty((cfg.batch, n_h, D), dtype=torch.float32, device="cuda") for _ in range(2))
+        g1 = {n: torch.empty(np.shape(w[n][0]), dtype=torch.float32, device="cuda") for n in B.BLOCK_PARAMS}
+        g2 = {n: torch.empty_like(g1[n]) for n in B.BLOCK_PARAMS}
+        flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+        B.reslim_block_fwd_train(m.ctx, 0, x_dev, out, saved, cfg.batch, ws)
+        B.reslim_block_bwd(m.ctx, 0, x_dev, saved, cuda(d_out), dx, g1, cfg.batch, ws)
+        B.reslim_block_bwd(m.ctx, 0, x_dev, saved, cuda(d_out * np.float32(S)), dx, g2, cfg.batch, ws)
+        B.reslim_block_grads_unscale(m.ctx, g2, 1.0 / S, flag)
+        torch.cuda.synchronize()
+        assert int(flag.item()) == 0
+        ref, found = O.grads_unscale({n: g2[n].cpu().numpy() * S for n in B.BLOCK_PARAMS}, S)
+        assert not found
+        for n in B.BLOCK_PARAMS:
+            assert O.rel_l2(g2[n].cpu().numpy(), g1[n].cpu().numpy()) <= 1e-6, n      # same bits up to fp32 sums of scaled terms
+            assert np.allclose(g2[n].cpu().numpy(), ref[n], rtol=1e-6, atol=0)
+        g2["w_fc1"][3, 5] = float("inf")
+        B.reslim_block_grads_unscale(m.ctx, g2, 0.5, flag)
+        torch.cuda.synchronize()
+        assert int(flag.item()) == 1
+        assert O.grads_unscale({n: g2[n].cpu().numpy() for n in B.BLOCK_PARAMS}, 1.0)[1]
+        lib = B.load()
+        g = B.BlockGradsC(**{n: g2[n].data_ptr() for n in B.BLOCK_PARAMS})
+        assert lib.reslim_block_grads_unscale(m.ctx, ctypes.byref(g), 0.0, flag.data_ptr(), None) == B.RESLIM_EINVAL

@@ -514,3 +514,31 @@ def test_block_bwd_vs_torch_autograd_and_finite_differences():
         wm[k][(l,) + idx] -= 1e-6
         assert abs((loss(X, wp) - loss(X, wm)) / 2e-6 - grads[k][idx]) < 1e-4, k
 
+
+def test_gradient_scaling_vs_torch_grad_scaler():
+    """grads_unscale and grad_scale_update against PyTorch's own GradScaler on CPU tensors (the scheme
+    Sec. 4.4 names): the scale after every step of a sequence with overflows, and the unscaled gradients."""
+    seq = [0, 0, 0, 1, 0, 0, 0, 0, 1, 1, 0, 0, 0, 0, 0, 0]
+    sc = torch.amp.GradScaler("cpu", init_scale=1024.0, growth_factor=2.0, backoff_factor=0.5, growth_interval=3)
+    prm = torch.nn.Parameter(torch.tensor([0.5, -2.0, 3.0, 1.0]))
+    opt = torch.optim.SGD([prm], lr=0.0)
+    scale, tracker = 1024.0, 0
+    coef = np.array([1.0, 2.0, -3.0, 0.25])
+    for f in seq:
+        opt.zero_grad()
+        c = torch.tensor(coef)
+        if f:
+            c = c.clone()
+            c[2] = float("inf")
+        sc.scale((prm * c).sum()).backward()
+        scaled = {"p": prm.grad.numpy().copy()}                  # the gradient of the scaled loss
+        sc.unscale_(opt)
+        got, found = O.grads_unscale(scaled, scale)
+        assert found == bool(f)
+        assert np.array_equal(got["p"], prm.grad.numpy())
+        sc.step(opt)
+        sc.update()
+        scale, tracker = O.grad_scale_update(scale, tracker, found, 2.0, 0.5, 3)
+        assert scale == sc.get_scale()
+    assert O.grad_scale_update(8.0, 1999, False) == (16.0, 0) and O.grad_scale_update(8.0, 5, True) == (4.0, 0)
+
