@@ -200,8 +200,10 @@ static WgradPlan wgrad_plan(int M, int N, int K) {
   p.tiles_k = (K + tn - 1) / tn;
   const int tiles = p.tiles_n * p.tiles_k;
   const int cus = g_wgrad_cus > 0 ? g_wgrad_cus : 256;
-  const int target = p.big ? 2 * cus : 4 * cus;       // work-groups wanted
-  int s = (target + tiles - 1) / tiles;
+  // splits so that tiles * splits fills ONE round of resident work-groups without spilling into a
+  // second, nearly empty one (the 8-wave kernel holds one work-group per CU, the 4-wave one four)
+  const int slots = p.big ? cus : 4 * cus;
+  int s = slots / tiles;
   const int max_s = (M + 255) / 256;                  // at least 256 tokens per split
   s = s < 1 ? 1 : (s > max_s ? max_s : s);
   if (s > 64) s = 64;
