@@ -33,6 +33,13 @@ MEASURED_TRAFFIC = {
     ("c1", "gemm_qkv"): 98.3e6 + 146.4e6,
     ("c1", "gemm_proj"): 140.6e6 + 90.1e6,
     ("c1", "layernorm"): 85.7e6 + 42.8e6,
+    # profiles/forward_and_train_block_c2_all_kernels.md
+    ("c2", "gemm_fc1"): 1994.7e6 + 1484.1e6,
+    ("c2", "gemm_fc2"): 2646.8e6 + 695.2e6,
+    ("c2", "gemm_qkv"): 1516.1e6 + 1132.0e6,
+    ("c2", "tiles_attention"): 1928.6e6 + 332.0e6,
+    ("c2", "gemm_proj"): 1614.2e6 + 829.6e6,
+    ("c2", "layernorm"): 656.7e6 + 328.2e6,
 }
 
 
