@@ -18,6 +18,7 @@ namespace reslim {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 struct GemmArgs {
   const void *A;
@@ -40,130 +41,165 @@ __device__ __forceinline__ float gelu_erf(float x) {
   return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f));
 }
 
-// erf by the rational-exponential form of Abramowitz & Stegun 7.1.26 (|error| <=
-// 1.5e-7, far below bf16 resolution): 13 plain ALU operations, one reciprocal and
-// one exponential per element instead of the library routine's branches.
+// GELU for bf16 outputs without the reciprocal and the branches of the library erf:
+// with u = min(|x|, 5), Phi(-u) = 2^P(u) where P is a degree-6 fit of log2 of the
+// normal tail on [0, 5] (interpolated at Chebyshev nodes), and
+// gelu(x) = max(x, 0) - u Phi(-u).  Relative error <= 1.5e-5 of gelu(x) on |x| <= 5
+// and absolute error <= 1.5e-6 beyond, against 2^-9 for the bf16 rounding that
+// follows; 11 vector operations per element, one of them an exponential.
 __device__ __forceinline__ float gelu_erf_fast(float x) {
-  const float z = fabsf(x) * 0.70710678118654752440f;
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
-  float p = fmaf(1.061405429f, t, -1.453152027f);
-  p = fmaf(p, t, 1.421413741f);
-  p = fmaf(p, t, -0.284496736f);
-  p = fmaf(p, t, 0.254829592f);
-  const float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * z * z);
-  const float erf_abs = fmaf(-p * t, e, 1.0f);
-  return 0.5f * x * (1.0f + copysignf(erf_abs, x));
+  const float u = fminf(fabsf(x), 5.0f);
+  float p = fmaf(2.975744064e-05f, u, -7.135751075e-04f);
+  p = fmaf(p, u, 7.775241509e-03f);
+  p = fmaf(p, u, -5.269032717e-02f);
+  p = fmaf(p, u, -4.595123231e-01f);
+  p = fmaf(p, u, -1.150926590e+00f);
+  p = fmaf(p, u, -1.000011683e+00f);
+  return fmaf(-u, __builtin_amdgcn_exp2f(p), fmaxf(x, 0.0f));
 }
 
-// Epilogue of one wave: acc[i][j] is the 32x32 block at rows m_base + 32 i, columns
-// n_base + 32 j.  Accumulator layout of the 32x32 MFMA: a lane holds column
-// (lane % 32) and rows 8*(r/4) + 4*(lane/32) + r%4 for r = 0..15, so a store
-// instruction writes two rows of 32 consecutive columns.  The per-column bias is
-// read once per block; full tiles take a path without per-row bounds checks.
-template <int EPI, bool GUARD_M>
-__device__ __forceinline__ void epilogue_block(const GemmArgs &g, const f32x16 &a, int m_first, int n, float bias) {
-#pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int m = m_first + 8 * (r / 4) + (r % 4);
-    if (GUARD_M && m >= g.M) continue;
-    const size_t o = static_cast<size_t>(m) * g.ldo + n;
-    const float v = a[r];
-    if constexpr (EPI == EPI_BIAS_ACT) {
-      static_cast<bf16_t *>(g.out)[o] = f32_to_bf16(v + bias);
-    } else if constexpr (EPI == EPI_BIAS_QSCALE_ACT) {
-      static_cast<bf16_t *>(g.out)[o] = f32_to_bf16((v + bias) * (n < g.qcols ? g.qscale : 1.0f));
-    } else if constexpr (EPI == EPI_BIAS_GELU_ACT) {
-      static_cast<bf16_t *>(g.out)[o] = f32_to_bf16(gelu_erf_fast(v + bias));
-    } else if constexpr (EPI == EPI_BIAS_ACT_GELU2) {
-      static_cast<bf16_t *>(g.out)[o] = f32_to_bf16(v + bias);
-      static_cast<bf16_t *>(g.out2)[o] = f32_to_bf16(gelu_erf_fast(v + bias));
-    } else if constexpr (EPI == EPI_BIAS_RESADD_F32) {
-      float *p = static_cast<float *>(g.out) + o;
-      *p = *p + (v + bias);
-    } else if constexpr (EPI == EPI_BIAS_RES_F32) {
-      static_cast<float *>(g.out)[o] = static_cast<const float *>(g.aux)[o] + (v + bias);
-    } else if constexpr (EPI == EPI_BIAS_TAB_F32) {
-      static_cast<float *>(g.out)[o] = v + g.tab[static_cast<size_t>(m % g.tab_rows) * g.N + n];
-    } else {
-      static_cast<float *>(g.out)[o] = v + bias;
-    }
-  }
-}
-
-// Epilogues that read or write fp32 rows (residual read-modify-write, table add)
-// run with the MFMA operand roles swapped: the accumulator block is then C^T, a
-// lane holds one output row (lane % 32) and four consecutive columns per register
-// quad, and the update is a 16-byte load/store per lane (measured 1.85x faster than
-// 4-byte accesses for the read-modify-write).
+// Every epilogue runs with the MFMA operand roles swapped: the accumulator block is
+// then C^T, a lane holds one output row (lane % 32) and four consecutive columns per
+// register quad.  fp32 outputs (residual read-modify-write, table add) are updated
+// with one 16-byte load/store per lane (measured 1.85x faster than 4-byte accesses
+// for the read-modify-write).  bf16 outputs go through a 4 KB staging area of the
+// wave in LDS, 32 rows x 64 columns at a time, so that a store instruction writes
+// eight complete 128-byte row segments (16 bytes per lane) instead of 64 partial
+// ones; no barrier is involved, the LDS operations of one wave execute in order.
 template <int EPI>
 __device__ __host__ constexpr bool epi_swapped() {
-  return EPI == EPI_BIAS_RESADD_F32 || EPI == EPI_BIAS_TAB_F32 || EPI == EPI_BIAS_RES_F32;
+  return true;
+}
+template <int EPI>
+__device__ __host__ constexpr bool epi_act_out() {
+  return EPI == EPI_BIAS_ACT || EPI == EPI_BIAS_QSCALE_ACT || EPI == EPI_BIAS_GELU_ACT || EPI == EPI_BIAS_ACT_GELU2;
+}
+constexpr int kEpiStageBytes = 4096;    // per wave
+
+// one value of a bf16-output epilogue (v already carries the bias)
+template <int EPI, bool SECOND>
+__device__ __forceinline__ float epi_act_value(const GemmArgs &g, float v, int n) {
+  if constexpr (EPI == EPI_BIAS_QSCALE_ACT) return v * (n < g.qcols ? g.qscale : 1.0f);
+  if constexpr (EPI == EPI_BIAS_GELU_ACT || (EPI == EPI_BIAS_ACT_GELU2 && SECOND)) return gelu_erf_fast(v);
+  return v;
 }
 
+// Rows m_first .. m_first + 31, columns n_first .. n_first + 32 NB - 1 (NB = 1 or 2
+// accumulator blocks side by side) of a bf16 output.  Staging layout: row r at
+// 128 r bytes, its 16-byte chunk c at position c ^ ((r >> 1) & 7), and the two
+// 8-byte halves of a chunk exchanged where r >= 16: with that the 8-byte writes of
+// 32 lanes (32 rows, one column quad) and the 16-byte reads of 16 lanes (two rows)
+// each touch every bank once.
+template <int EPI, bool SECOND, int NB>
+__device__ __forceinline__ void epilogue_act_stage(const GemmArgs &g, const f32x16 *blk, int m_first, int n_first,
+                                                   int lane, unsigned char *stg) {
+  const int l32 = lane & 31, hi = lane >> 5;
+  bf16_t *out = static_cast<bf16_t *>(SECOND ? g.out2 : g.out);
+  unsigned char *wrow = stg + l32 * 128 + ((hi ^ (l32 >> 4)) << 3);
+  const int wsw = (l32 >> 1) & 7;
+#pragma unroll
+  for (int jj = 0; jj < NB; ++jj) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int n = n_first + jj * 32 + 8 * q + 4 * hi;
+      float4 b = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (n + 3 < g.N) {
+        b = *reinterpret_cast<const float4 *>(g.bias + n);
+      } else {
+        if (n < g.N) b.x = g.bias[n];
+        if (n + 1 < g.N) b.y = g.bias[n + 1];
+        if (n + 2 < g.N) b.z = g.bias[n + 2];
+      }
+      u32x2 pk;
+      pk[0] = pack_bf16x2(epi_act_value<EPI, SECOND>(g, blk[jj][4 * q] + b.x, n),
+                          epi_act_value<EPI, SECOND>(g, blk[jj][4 * q + 1] + b.y, n + 1));
+      pk[1] = pack_bf16x2(epi_act_value<EPI, SECOND>(g, blk[jj][4 * q + 2] + b.z, n + 2),
+                          epi_act_value<EPI, SECOND>(g, blk[jj][4 * q + 3] + b.w, n + 3));
+      *reinterpret_cast<u32x2 *>(wrow + (((jj * 4 + q) ^ wsw) << 4)) = pk;
+    }
+  }
+  // read back row-major: 8 lanes per row (NB = 2) or 4 lanes per row (NB = 1)
+  constexpr int LPR = 4 * NB, RPI = 64 / LPR;      // lanes per row, rows per instruction
+  const int c = lane % LPR, rr = lane / LPR;
+#pragma unroll
+  for (int it = 0; it < 32 / RPI; ++it) {
+    const int r = it * RPI + rr;
+    u32x4 v = *reinterpret_cast<const u32x4 *>(stg + r * 128 + ((c ^ ((r >> 1) & 7)) << 4));
+    if (it * RPI >= 16) v = u32x4{v[2], v[3], v[0], v[1]};
+    const int m = m_first + r, n = n_first + c * 8;
+    if (m >= g.M) continue;
+    bf16_t *o = out + static_cast<size_t>(m) * g.ldo + n;
+    if (n + 7 < g.N) {
+      *reinterpret_cast<u32x4 *>(o) = v;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (n + e < g.N) o[e] = static_cast<bf16_t>(v[e >> 1] >> ((e & 1) * 16));
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);   // keeps the next block's bias loads and arithmetic from being hoisted over this one (registers)
+}
+
+// Only the leading MIe x NIe blocks of acc are written (a wave working on part of a
+// tile fills just those).  stg: this wave's kEpiStageBytes of LDS (bf16 outputs).
 template <int EPI, int MI, int NI, int MIe = MI, int NIe = NI>
-__device__ __forceinline__ void epilogue_wave_swapped(const GemmArgs &g, const f32x16 (&acc)[MI][NI], int m_base,
-                                                      int n_base, int l32, int hi) {
-  float *out = static_cast<float *>(g.out);
+__device__ __forceinline__ void epilogue_wave(const GemmArgs &g, const f32x16 (&acc)[MI][NI], int m_base, int n_base,
+                                              int lane, unsigned char *stg) {
+  const int l32 = lane & 31, hi = lane >> 5;
+  if constexpr (epi_act_out<EPI>()) {
+#pragma unroll
+    for (int i = 0; i < MIe; ++i) {
+#pragma unroll
+      for (int j = 0; j + 1 < NIe; j += 2) {
+        epilogue_act_stage<EPI, false, 2>(g, &acc[i][j], m_base + i * 32, n_base + j * 32, lane, stg);
+        if constexpr (EPI == EPI_BIAS_ACT_GELU2)
+          epilogue_act_stage<EPI, true, 2>(g, &acc[i][j], m_base + i * 32, n_base + j * 32, lane, stg);
+      }
+      if constexpr (NIe % 2 == 1) {
+        epilogue_act_stage<EPI, false, 1>(g, &acc[i][NIe - 1], m_base + i * 32, n_base + (NIe - 1) * 32, lane, stg);
+        if constexpr (EPI == EPI_BIAS_ACT_GELU2)
+          epilogue_act_stage<EPI, true, 1>(g, &acc[i][NIe - 1], m_base + i * 32, n_base + (NIe - 1) * 32, lane, stg);
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < MIe; ++i) {
     const int m = m_base + i * 32 + l32;
     if (m >= g.M) continue;
-    float *orow = out + static_cast<size_t>(m) * g.ldo;
-    // row the skip connection is read from: the output itself (in place) or another buffer
-    const float *rrow = (EPI == EPI_BIAS_RES_F32) ? static_cast<const float *>(g.aux) + static_cast<size_t>(m) * g.ldo : orow;
-    const float *trow = (EPI == EPI_BIAS_TAB_F32) ? g.tab + static_cast<size_t>(m % g.tab_rows) * g.N : nullptr;
+    const size_t row = static_cast<size_t>(m) * g.ldo;
+    {
+      float *orow = static_cast<float *>(g.out) + row;
+      // row the skip connection is read from: the output itself (in place) or another buffer
+      const float *rrow = (EPI == EPI_BIAS_RES_F32) ? static_cast<const float *>(g.aux) + row : orow;
+      const float *trow = (EPI == EPI_BIAS_TAB_F32) ? g.tab + static_cast<size_t>(m % g.tab_rows) * g.N : nullptr;
 #pragma unroll
-    for (int j = 0; j < NIe; ++j) {
+      for (int j = 0; j < NIe; ++j) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int n = n_base + j * 32 + 8 * q + 4 * hi;
-        if (n + 3 < g.N) {
-          const float4 add = (EPI == EPI_BIAS_TAB_F32) ? *reinterpret_cast<const float4 *>(trow + n)
-                                                       : *reinterpret_cast<const float4 *>(g.bias + n);
-          float4 v = make_float4(acc[i][j][4 * q] + add.x, acc[i][j][4 * q + 1] + add.y, acc[i][j][4 * q + 2] + add.z,
-                                 acc[i][j][4 * q + 3] + add.w);
-          float4 *p = reinterpret_cast<float4 *>(orow + n);
-          if constexpr (EPI == EPI_BIAS_RESADD_F32 || EPI == EPI_BIAS_RES_F32) {
-            const float4 x = *reinterpret_cast<const float4 *>(rrow + n);
-            v.x += x.x; v.y += x.y; v.z += x.z; v.w += x.w;
-          }
-          *p = v;
-        } else {
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (n + e < g.N) {
-              const float add = (EPI == EPI_BIAS_TAB_F32) ? trow[n + e] : g.bias[n + e];
-              float v = acc[i][j][4 * q + e] + add;
-              if constexpr (EPI == EPI_BIAS_RESADD_F32 || EPI == EPI_BIAS_RES_F32) v += rrow[n + e];
-              orow[n + e] = v;
+        for (int q = 0; q < 4; ++q) {
+          const int n = n_base + j * 32 + 8 * q + 4 * hi;
+          if (n + 3 < g.N) {
+            const float4 add = (EPI == EPI_BIAS_TAB_F32) ? *reinterpret_cast<const float4 *>(trow + n)
+                                                         : *reinterpret_cast<const float4 *>(g.bias + n);
+            float4 v = make_float4(acc[i][j][4 * q] + add.x, acc[i][j][4 * q + 1] + add.y, acc[i][j][4 * q + 2] + add.z,
+                                   acc[i][j][4 * q + 3] + add.w);
+            if constexpr (EPI == EPI_BIAS_RESADD_F32 || EPI == EPI_BIAS_RES_F32) {
+              const float4 x = *reinterpret_cast<const float4 *>(rrow + n);
+              v.x += x.x; v.y += x.y; v.z += x.z; v.w += x.w;
             }
+            *reinterpret_cast<float4 *>(orow + n) = v;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (n + e < g.N) {
+                const float add = (EPI == EPI_BIAS_TAB_F32) ? trow[n + e] : g.bias[n + e];
+                float v = acc[i][j][4 * q + e] + add;
+                if constexpr (EPI == EPI_BIAS_RESADD_F32 || EPI == EPI_BIAS_RES_F32) v += rrow[n + e];
+                orow[n + e] = v;
+              }
+          }
         }
       }
-    }
-  }
-}
-
-// Only the leading MIe x NIe blocks of acc are written (a wave working on part of a
-// tile fills just those).
-template <int EPI, int MI, int NI, int MIe = MI, int NIe = NI>
-__device__ __forceinline__ void epilogue_wave(const GemmArgs &g, const f32x16 (&acc)[MI][NI], int m_base, int n_base,
-                                              int l32, int hi) {
-  if constexpr (epi_swapped<EPI>()) {
-    epilogue_wave_swapped<EPI, MI, NI, MIe, NIe>(g, acc, m_base, n_base, l32, hi);
-    return;
-  }
-  const bool full = m_base + MIe * 32 <= g.M;     // wave-uniform
-#pragma unroll
-  for (int j = 0; j < NIe; ++j) {
-    const int n = n_base + j * 32 + l32;
-    if (n >= g.N) continue;
-    const float bias = (EPI == EPI_BIAS_TAB_F32) ? 0.f : g.bias[n];
-    if (full) {
-#pragma unroll
-      for (int i = 0; i < MIe; ++i) epilogue_block<EPI, false>(g, acc[i][j], m_base + i * 32 + 4 * hi, n, bias);
-    } else {
-#pragma unroll
-      for (int i = 0; i < MIe; ++i) epilogue_block<EPI, true>(g, acc[i][j], m_base + i * 32 + 4 * hi, n, bias);
     }
   }
 }
@@ -319,7 +355,8 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_bf16_kernel(GemmArgs 
     }
   }
 
-  epilogue_wave<EPI, MI, NI>(g, acc, m0 + wm * TM, n0 + wn * TN, l32, hi);
+  epilogue_wave<EPI, MI, NI>(g, acc, m0 + wm * TM, n0 + wn * TN, lane,
+                             smem + NBUF * (BM + BN) * PITCH * sizeof(bf16_t) + wave * kEpiStageBytes);
 }
 
 #include "gemm_dl.inc"
@@ -394,7 +431,8 @@ template <int BM, int BN, int BK, int WM, int WN, int NBUF, int MINW>
 struct TileCfg {
   static constexpr int kBM = BM, kBN = BN, kBK = BK, kWM = WM, kWN = WN, kNBUF = NBUF, kMINW = MINW;
   static constexpr int kThreads = WM * WN * 64;
-  static constexpr size_t kLds = static_cast<size_t>(NBUF) * (BM + BN) * (BK + 8) * sizeof(bf16_t);
+  // operand slabs + the epilogue's staging area of every wave
+  static constexpr size_t kLds = static_cast<size_t>(NBUF) * (BM + BN) * (BK + 8) * sizeof(bf16_t) + WM * WN * kEpiStageBytes;
 };
 
 template <class TC, int EPI>
@@ -434,8 +472,7 @@ static hipError_t launch_bf16(GemmArgs g, hipStream_t st) {
   const long tiles_big = static_cast<long>((g.M + 255) / 256) * ((g.N + 255) / 256);
   int choice = 2;
   const bool light_epilogue = EPI == EPI_BIAS_ACT || EPI == EPI_BIAS_QSCALE_ACT;
-  const bool rmw_epilogue = EPI == EPI_BIAS_RESADD_F32 || EPI == EPI_BIAS_RES_F32;      // the persistent kernel cannot hide it behind other groups
-  if (tiles_big >= 2L * g_num_cus && (light_epilogue || g.K >= (rmw_epilogue ? 2048 : 1024))) choice = 3;
+  if (tiles_big >= 2L * g_num_cus && (light_epilogue || g.K >= 1024)) choice = 3;
   if (g_gemm_tile_override >= 0) choice = g_gemm_tile_override;
   switch (choice) {
     case 3: return launch_bf16_dl<DlA, EPI>(g, st);
@@ -485,6 +522,7 @@ hipError_t launch_gemm(int dtype, Epilogue epi, const void *A, const void *W, co
   if (epi == EPI_BIAS_ACT_GELU2 && !out2) return hipErrorInvalidValue;
   if (dtype == RESLIM_BF16) {
     if (K % 64 != 0) return hipErrorInvalidValue;   // slabs are 64 deep; create() enforces D % 64 == 0
+    if (ldo % 8 != 0) return hipErrorInvalidValue;  // epilogues store 16 bytes of a row at once
     switch (epi) {
       case EPI_BIAS_ACT: return launch_bf16<EPI_BIAS_ACT>(g, st);
       case EPI_BIAS_GELU_ACT: return launch_bf16<EPI_BIAS_GELU_ACT>(g, st);
