@@ -1,0 +1,215 @@
+"""Pins for the adaptive-spatial-compression oracle (Sec. 4.1, "Adaptive Spatial
+Compression"): every step is checked against something that is not the oracle
+itself - a library routine, a closed form, a hand-derived picture or a brute
+force on a tiny input.  CPU only."""
+import math
+
+import numpy as np
+import pytest
+from scipy import ndimage
+
+from oracle import asc_oracle as A
+from oracle import reslim_oracle as ro
+from paper_2505_04802_amd import workloads as WL
+
+
+def _rand_u8(seed, H=40, W=56, smooth=2.0):
+    r = np.random.default_rng(seed)
+    f = ndimage.gaussian_filter(r.standard_normal((H, W)), smooth)
+    return A.quantise_u8(f.astype(np.float32))
+
+
+def test_quantise_range_and_special_cases():
+    r = np.random.default_rng(0)
+    v = r.standard_normal((16, 24)).astype(np.float32)
+    q = A.quantise_u8(v)
+    assert q.min() == 0 and q.max() == 255
+    # affine in v up to the rounding: |q - exact| <= 0.5 + float32 slack
+    exact = (v.astype(np.float64) - v.min()) * 255.0 / (float(v.max()) - float(v.min()))
+    assert np.abs(q - exact).max() <= 0.5 + 1e-3
+    assert (A.quantise_u8(np.full((4, 4), 3.5, np.float32)) == 0).all()      # constant field
+    # monotone: ordering of the input is never reversed
+    o = np.argsort(v.ravel())
+    assert (np.diff(q.ravel()[o]) >= 0).all()
+
+
+def test_smoothing_against_library_correlation():
+    assert A.SMOOTH_MASK.sum() == 159 and (A.SMOOTH_MASK == A.SMOOTH_MASK.T).all()
+    q = _rand_u8(1)
+    ref = ndimage.correlate(q, A.SMOOTH_MASK, mode="nearest")
+    assert (A.smooth(q) == (ref + 79) // 159).all()
+    assert (A.smooth(np.full((9, 9), 200)) == 200).all()                     # a constant stays
+
+
+def test_sobel_against_library():
+    sm = A.smooth(_rand_u8(2))
+    gx, gy = A.sobel(sm)
+    assert (gx == ndimage.sobel(sm, axis=1, mode="nearest")).all()
+    assert (gy == ndimage.sobel(sm, axis=0, mode="nearest")).all()
+    ramp = np.tile(np.arange(12) * 3, (10, 1))                               # d/dx = 3 -> gx = 8 * 3 inside
+    gx, gy = A.sobel(ramp)
+    assert (gx[:, 1:-1] == 24).all() and (gy == 0).all()
+
+
+def test_sector_against_atan2():
+    r = np.random.default_rng(3)
+    gx = r.integers(-1020, 1021, 20000)
+    gy = r.integers(-1020, 1021, 20000)
+    keep = (gx != 0) | (gy != 0)
+    gx, gy = gx[keep], gy[keep]
+    ang = np.degrees(np.arctan2(gy, gx)) % 180.0                             # direction modulo 180
+    ref = np.select([(ang < 22.5) | (ang >= 157.5), ang < 67.5, ang < 112.5], [0, 1, 2], 3)
+    near = np.abs(((ang - 22.5) % 45.0 + 22.5) % 45.0 - 22.5) < 0.01         # within 0.01 deg of a sector border
+    near |= np.abs((ang - 22.5) % 45.0) < 0.01
+    got = A.sector(gx, gy)
+    assert (got[~near] == ref[~near]).all()
+    # axis-aligned and exactly diagonal gradients
+    assert A.sector(np.array([5]), np.array([0]))[0] == 0 and A.sector(np.array([0]), np.array([-7]))[0] == 2
+    assert A.sector(np.array([4]), np.array([4]))[0] == 1 and A.sector(np.array([4]), np.array([-4]))[0] == 3
+
+
+def test_step_edges_by_hand():
+    """A vertical step gives one column of edge pixels, on the dark side of the step
+    (the tie between the two columns next to the step goes to the left one); a
+    horizontal step one row; an ideal diagonal step the two anti-diagonals next to
+    it (they are not neighbours along the gradient, so both are maxima)."""
+    q = np.zeros((32, 32), np.int64)
+    q[:, 16:] = 255
+    e = A.canny_edges(q, 50, 100)
+    assert e.sum() == 32 and e[:, 15].all()
+    e = A.canny_edges(q.T, 50, 100)
+    assert e.sum() == 32 and e[15, :].all()
+    yy, xx = np.mgrid[0:32, 0:32]
+    e = A.canny_edges(((yy + xx) >= 32) * 255, 50, 100)
+    inner = e[4:28, :]
+    assert ((yy + xx)[4:28][inner] // 1 >= 31).all() and ((yy + xx)[4:28][inner] <= 32).all()
+    assert (inner.sum(axis=1) == 2).all()
+    assert A.canny_edges(np.full((20, 20), 77), 1, 2).sum() == 0             # nothing in a constant field
+
+
+def test_thresholds_and_nms_definition_brute_force():
+    q = _rand_u8(4, 24, 28, 1.5)
+    gx, gy = A.sobel(A.smooth(q))
+    mag = np.abs(gx) + np.abs(gy)
+    low, high = int(np.quantile(mag, 0.5)), int(np.quantile(mag, 0.8))
+    strong, weak = A.candidates(q, low, high)
+    H, W = q.shape
+    step = {0: (0, 1), 1: (1, 1), 2: (1, 0), 3: (1, -1)}
+    for y in range(H):
+        for x in range(W):
+            ang = math.degrees(math.atan2(gy[y, x], gx[y, x])) % 180.0 if mag[y, x] else 0.0
+            k = 0 if (ang < 22.5 or ang >= 157.5) else 1 if ang < 67.5 else 2 if ang < 112.5 else 3
+            dy, dx = step[k]
+            def m(yy, xx):
+                return int(mag[yy, xx]) if 0 <= yy < H and 0 <= xx < W else 0
+            keep = mag[y, x] > m(y - dy, x - dx) and mag[y, x] >= m(y + dy, x + dx)
+            assert bool(weak[y, x]) == (keep and mag[y, x] > low), (y, x)
+            assert bool(strong[y, x]) == (keep and mag[y, x] > high), (y, x)
+    assert (weak | ~strong).all()
+
+
+def test_hysteresis_against_connected_components():
+    r = np.random.default_rng(5)
+    weak = r.random((40, 50)) < 0.35
+    strong = weak & (r.random((40, 50)) < 0.05)
+    lab, n = ndimage.label(weak, structure=np.ones((3, 3), int))
+    keep = np.unique(lab[strong])
+    ref = np.isin(lab, keep[keep > 0])
+    assert (A.hysteresis(strong, weak) == ref).all()
+    # a weak pixel chain reaching a strong pixel survives, an isolated one does not
+    w = np.zeros((5, 9), bool); w[2, 1:6] = True; w[0, 8] = True
+    s = np.zeros_like(w); s[2, 1] = True
+    out = A.hysteresis(s, w)
+    assert out[2, 1:6].all() and not out[0, 8]
+
+
+def _check_tree(edges, leaves, p, max_leaf, min_leaf, tau):
+    H, W = edges.shape
+    Hp, Wp = H // p, W // p
+    cover = np.zeros((Hp, Wp), int)
+    def dens_split(y0, x0, s):
+        cnt = edges[y0 * p:(y0 + s) * p, x0 * p:(x0 + s) * p].sum()
+        return s > min_leaf and np.float32(cnt) > np.float32(np.float32(tau) * np.float32((s * p) ** 2))
+    for (y0, x0, s) in leaves:
+        assert s >= min_leaf and s <= max_leaf and (s & (s - 1)) == 0 and y0 % s == 0 and x0 % s == 0
+        cover[y0:y0 + s, x0:x0 + s] += 1
+        assert not dens_split(y0, x0, s)                        # a leaf does not split
+        a = 2 * s
+        while a <= max_leaf:                                    # every ancestor did
+            assert dens_split(y0 // a * a, x0 // a * a, a)
+            a *= 2
+    assert (cover == 1).all()                                   # a partition of the patch grid
+
+
+def test_quadtree_properties_and_extremes():
+    r = np.random.default_rng(6)
+    p, mx, mn = 2, 8, 1
+    edges = ndimage.gaussian_filter(r.standard_normal((32, 48)), 3.0) > 0.12
+    edges &= r.random(edges.shape) < 0.4
+    for tau in (0.02, 0.08, 0.2):
+        leaves = A.quadtree_leaves(edges, p, mx, mn, tau)
+        _check_tree(edges, leaves, p, mx, mn, tau)
+    none = A.quadtree_leaves(np.zeros((32, 48), bool), p, mx, mn, 0.05)
+    assert none == [(y, x, 8) for y in (0, 8) for x in (0, 8, 16)]           # one leaf per root, row-major
+    full = A.quadtree_leaves(np.ones((32, 48), bool), p, mx, mn, 0.05)
+    assert len(full) == 16 * 24 and all(s == 1 for _, _, s in full)          # identity: one leaf per patch
+    # depth-first NW, NE, SW, SE inside a root
+    assert full[:4] == [(0, 0, 1), (0, 1, 1), (1, 0, 1), (1, 1, 1)]
+    assert full[4] == (0, 2, 1) and full[8] == (2, 0, 1) and full[12] == (2, 2, 1) and full[16] == (0, 4, 1) and full[64] == (0, 8, 1)
+    assert all(s >= 2 for _, _, s in A.quadtree_leaves(np.ones((32, 48), bool), p, mx, 2, 0.05))
+
+
+def test_compress_decompress_means_and_identity():
+    r = np.random.default_rng(7)
+    B, Hp, Wp, D, p = 2, 8, 16, 5, 2
+    imgs = ndimage.gaussian_filter(r.standard_normal((B, Hp * p, Wp * p)), (0, 1.5, 1.5)).astype(np.float32)
+    tab = A.build(imgs, p, 4, 1, 40, 90, 0.06)
+    L = len(tab["leaf_s"])
+    assert tab["sample_off"][0] == 0 and tab["sample_off"][-1] == L
+    assert (tab["leaf_s"] ** 2).sum() == B * Hp * Wp
+    z = r.standard_normal((B, Hp * Wp, D))
+    zc = A.compress(z, tab, Wp)
+    back = A.decompress(zc, tab)
+    for b in range(B):
+        for i in range(tab["sample_off"][b], tab["sample_off"][b + 1]):
+            members = np.nonzero(tab["patch_leaf"][b] == i)[0]
+            assert len(members) == tab["leaf_s"][i] ** 2
+            np.testing.assert_allclose(zc[i], z[b, members].mean(axis=0), rtol=0, atol=1e-14)
+            assert (back[b, members] == zc[i]).all()
+    np.testing.assert_allclose(A.compress(np.ones_like(z), tab, Wp), 1.0, rtol=0, atol=1e-15)
+    ident = A.build(imgs, p, 4, 4, 40, 90, 0.06)                              # min = max: uniform leaves of 4 x 4
+    assert (ident["leaf_s"] == 4).all()
+
+
+def test_forward_with_single_patch_leaves_is_the_uncompressed_model():
+    """Switched off (every leaf one patch) the module is the identity: the
+    compressed forward must reproduce the plain untiled forward."""
+    cfg1 = WL.CONFIGS["c0"].with_(tiles_y=1, tiles_x=1, halo=0, batch=2)
+    w = WL.make_weights(cfg1)
+    x = WL.make_fields(cfg1)
+    Hp, Wp = cfg1.H // cfg1.patch, cfg1.W // cfg1.patch
+    ones = np.ones((cfg1.batch, cfg1.H, cfg1.W), bool)
+    ly, lx, ls, off = [], [], [], [0]
+    patch_leaf = np.empty((cfg1.batch, Hp * Wp), np.int64)
+    for b in range(cfg1.batch):
+        for (y0, x0, s) in A.quadtree_leaves(ones[b], cfg1.patch, 4, 1, 0.5):
+            patch_leaf[b, y0 * Wp + x0] = len(ly)
+            ly.append(y0); lx.append(x0); ls.append(s)
+        off.append(len(ly))
+    tab = dict(leaf_y0=np.array(ly), leaf_x0=np.array(lx), leaf_s=np.array(ls), sample_off=np.array(off), patch_leaf=patch_leaf)
+    y_c = A.forward_compressed(x, w, cfg1, tab)
+    y_ref = ro.reslim_forward(x, w, cfg1)
+    assert ro.rel_l2(y_c, y_ref) < 1e-12
+
+
+def test_image_from_tokens_layout():
+    r = np.random.default_rng(8)
+    B, Hp, Wp, D, p = 1, 3, 4, 6, 2
+    z = r.standard_normal((B, Hp * Wp, D))
+    w_img, b_img = r.standard_normal((p * p, D)), r.standard_normal(p * p)
+    img = A.image_from_tokens(z, w_img, b_img, Hp, Wp, p)
+    for n in (0, 5, 11):
+        for i in range(p):
+            for j in range(p):
+                ref = float(w_img[i * p + j] @ z[0, n] + b_img[i * p + j])
+                assert abs(img[0, (n // Wp) * p + i, (n % Wp) * p + j] - ref) < 1e-12
