@@ -324,6 +324,86 @@ int reslim_bayes_loss_fwd(const float *pred, const float *target, const float *l
                           int32_t vars, int32_t Hf, int32_t Wf, float tv_weight, double *out3,
                           void *workspace, size_t ws_bytes, void *hip_stream);
 
+/* ---- Adaptive spatial compression (Sec. 4.1, "Adaptive Spatial Compression").
+ * The paper maps the aggregated embedding to image space, runs Canny edge
+ * detection on it, splits quadrants of a quad-tree while their edge density is
+ * above a threshold and a minimum patch size is not reached, runs the ViT blocks on
+ * one token per leaf and decompresses before the decoder; its Sec. 4.3 has the CPUs
+ * build the quad-trees while the GPUs compute.  Here: reslim_asc_image (device)
+ * gives the image, reslim_asc_build (host) the leaf table, reslim_asc_plan_create
+ * checks and uploads it, reslim_asc_forward runs the model on the leaves.  The
+ * paper gives no thresholds, filter sizes or merge rule; the readings are stated at
+ * each function.  Compression is not combined with tiling: the context must have
+ * tiles_y = tiles_x = 1 (then halo is irrelevant). */
+typedef struct reslim_asc_plan reslim_asc_plan;
+
+/* HOST function, no HIP call.  images: host fp32 [batch, H, W].  Per sample:
+ *  1. 8-bit image q = clamp(floor((v - min) * (255 / (max - min)) + 0.5), 0, 255),
+ *     float32 operations in exactly this order; a constant field gives q = 0;
+ *  2. Canny in integers: 5x5 smoothing mask {2 4 5 4 2; 4 9 12 9 4; 5 12 15 12 5; ...}
+ *     / 159 with rounding, 3x3 Sobel derivatives, magnitude |gx| + |gy|, direction
+ *     in four sectors split at 22.5 and 67.5 degrees, a pixel survives if its
+ *     magnitude is greater than its neighbour's on the up/left side along the
+ *     gradient and not smaller than the other one's, strong = magnitude >
+ *     canny_high, weak = magnitude > canny_low, edges = strong pixels plus the weak
+ *     ones connected to them (8-neighbourhood); borders replicated for the filters,
+ *     magnitude 0 outside for the suppression;
+ *  3. quad-tree over the patch grid (H/patch x W/patch): roots are max_leaf x
+ *     max_leaf patches in row-major order; a node of side s splits into NW, NE, SW,
+ *     SE iff s > min_leaf and float(edge pixels inside) > tau * float((s*patch)^2);
+ *     leaves are listed depth-first, sample after sample.
+ * Outputs (host, caller-owned, room for batch * (H/patch) * (W/patch) entries each,
+ * sample_off batch + 1): leaf_y0, leaf_x0, leaf_s in patch units; sample_off[b] =
+ * first leaf of sample b; patch_leaf[b, y*Wp + x] = batch-wide index of the leaf
+ * holding that patch; *n_leaves_out = total leaves.
+ * Errors: RESLIM_EINVAL (null pointer, negative or inverted thresholds, tau negative
+ * or not finite, a pixel that is not finite), RESLIM_ESHAPE (leaf sizes not powers
+ * of two, min_leaf > max_leaf, grid not divisible by patch or by max_leaf). */
+int reslim_asc_build(const float *images, int32_t batch, int32_t H, int32_t W, int32_t patch, int32_t max_leaf,
+                     int32_t min_leaf, int32_t canny_low, int32_t canny_high, float tau, int32_t *leaf_y0,
+                     int32_t *leaf_x0, int32_t *leaf_s, int32_t *sample_off, int32_t *patch_leaf,
+                     int64_t *n_leaves_out);
+
+/* HOST: steps 1-2 above for one field; edges_out: host [H*W], 1 where an edge pixel
+ * was found.  For inspection and tests. */
+int reslim_asc_edges(const float *image, int32_t H, int32_t W, int32_t canny_low, int32_t canny_high, uint8_t *edges_out);
+
+/* Checks that the table is what reslim_asc_build produces for this context's grid
+ * (aligned power-of-two squares, every patch of every sample in exactly one leaf,
+ * patch_leaf the inverse map: RESLIM_EINVAL otherwise, the kernels rely on it) and
+ * copies it to the device (allocates; synchronous copies).  All pointers host.
+ * *out is NULL on failure; destroy the plan before its context.  RESLIM_ESHAPE if
+ * the context has more than one tile or embed_dim % 4 != 0. */
+int reslim_asc_plan_create(reslim_ctx *ctx, int32_t batch, const int32_t *leaf_y0, const int32_t *leaf_x0,
+                           const int32_t *leaf_s, int64_t n_leaves, const int32_t *sample_off,
+                           const int32_t *patch_leaf, reslim_asc_plan **out);
+void reslim_asc_plan_destroy(reslim_asc_plan *plan);
+int reslim_asc_plan_info(const reslim_asc_plan *plan, int64_t *n_leaves, int32_t *max_per_sample);
+
+/* Image-space map of the aggregated embedding (reading: one linear map D -> p*p per
+ * token, un-patchified): image[b, py*p + i, px*p + j] = w_img[i*p + j] . tokens[b, py*Wp
+ * + px] + b_img[i*p + j].  tokens: dev fp32 [batch*N, D] (reslim_embed_fwd of a
+ * one-tile context); w_img: dev fp32 [p*p, D]; b_img: dev fp32 [p*p]; image: dev
+ * fp32 [batch, H, W].  fp32 arithmetic.  Enqueued on hip_stream. */
+int reslim_asc_image(reslim_ctx *ctx, const float *tokens, const float *w_img, const float *b_img, float *image,
+                     int32_t batch, void *hip_stream);
+
+/* Compression (reading: a leaf's token is the arithmetic mean of its patches'
+ * aggregated embeddings, position and resolution terms included).  tokens: dev fp32
+ * [batch*N, D] in patch order; tokens_c: dev fp32 [n_leaves, D] out.  fp32 sums in
+ * row-major order over the leaf: deterministic. */
+int reslim_asc_compress(reslim_ctx *ctx, const reslim_asc_plan *plan, const float *tokens, float *tokens_c, void *hip_stream);
+
+/* The forward pass with the compression module switched on: embed, compress, every
+ * block on the leaves (attention among the leaves of one sample), decompress (each
+ * patch takes its leaf's token), final LayerNorm, head, un-patchify + residual path.
+ * x: dev fp32 [batch, V, H, W] with the plan's batch; y: dev fp32 [batch, C, s*H,
+ * s*W]; workspace as for reslim_forward at that batch.  With one patch per leaf the
+ * result equals reslim_forward's.  Errors as reslim_forward, plus RESLIM_EINVAL for
+ * a plan of another context. */
+int reslim_asc_forward(reslim_ctx *ctx, const reslim_asc_plan *plan, const float *x, float *y, void *workspace,
+                       size_t ws_bytes, void *hip_stream);
+
 /* Bandwidth yardstick: a plain device-to-device copy kernel (16 bytes per lane) of
  * `bytes` (a multiple of 16) from src to dst, both dev.  Profilers scale their HBM
  * byte counters by what they report for this kernel of known size. */

@@ -34,7 +34,9 @@ EXPORTS = ["tiles_partition", "reslim_create", "reslim_destroy", "reslim_last_er
            "tiles_attention_bwd_workspace_bytes", "tiles_attention_bwd",
            "reslim_train_prepare", "reslim_layernorm_bwd", "reslim_linear_bwd_workspace_bytes", "reslim_linear_bwd",
            "reslim_block_train_bytes", "reslim_block_fwd_train", "reslim_block_bwd",
-           "reslim_block_grads_unscale", "reslim_grad_scale_update"]
+           "reslim_block_grads_unscale", "reslim_grad_scale_update",
+           "reslim_asc_build", "reslim_asc_edges", "reslim_asc_plan_create", "reslim_asc_plan_destroy",
+           "reslim_asc_plan_info", "reslim_asc_image", "reslim_asc_compress", "reslim_asc_forward"]
 
 
 class ReslimConfigC(C.Structure):
@@ -115,13 +117,22 @@ def load() -> C.CDLL:
     lib.reslim_debug_copy.argtypes = [vp, vp, C.c_size_t, vp]
     lib.reslim_bayes_loss_workspace_bytes.argtypes = [i32, i32, i32, i32, C.POINTER(C.c_size_t)]
     lib.reslim_bayes_loss_fwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, C.c_float, vp, vp, C.c_size_t, vp]
+    lib.reslim_asc_build.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, i32, C.c_float, vp, vp, vp, vp, vp, C.POINTER(C.c_int64)]
+    lib.reslim_asc_edges.argtypes = [vp, i32, i32, i32, i32, vp]
+    lib.reslim_asc_plan_create.argtypes = [vp, i32, vp, vp, vp, C.c_int64, vp, vp, C.POINTER(vp)]
+    lib.reslim_asc_plan_destroy.argtypes = [vp]
+    lib.reslim_asc_plan_destroy.restype = None
+    lib.reslim_asc_plan_info.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(i32)]
+    lib.reslim_asc_image.argtypes = [vp, vp, vp, vp, vp, i32, vp]
+    lib.reslim_asc_compress.argtypes = [vp, vp, vp, vp, vp]
+    lib.reslim_asc_forward.argtypes = [vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.reslim_debug_set_gemm_tile.argtypes = [i32]
     lib.reslim_debug_set_gemm_tile.restype = None
     lib.reslim_debug_set_attention_variant.argtypes = [i32]
     lib.reslim_debug_set_attention_variant.restype = None
     for name in EXPORTS:
         if name not in ("reslim_destroy", "reslim_last_error", "reslim_debug_set_gemm_tile",
-                        "reslim_debug_set_attention_variant"):
+                        "reslim_debug_set_attention_variant", "reslim_asc_plan_destroy"):
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -334,6 +345,67 @@ def reslim_head_fwd(ctx, x, tokens, y, batch, workspace, stream=None):
 def reslim_forward(ctx, x, y, batch, workspace, stream=None):
     _check(load().reslim_forward(ctx, x.data_ptr(), y.data_ptr(), batch, workspace.data_ptr(),
                                  workspace.numel() * workspace.element_size(), _stream_ptr(stream)), ctx)
+
+
+# ------------------------------------------------------------------ adaptive spatial compression
+def reslim_asc_build(images: np.ndarray, patch: int, max_leaf: int, min_leaf: int, canny_low: int, canny_high: int,
+                     tau: float) -> Dict[str, np.ndarray]:
+    """Host function.  images: fp32 [B, H, W].  Returns the leaf table as int32 arrays:
+    leaf_y0, leaf_x0, leaf_s [L], sample_off [B + 1], patch_leaf [B, Hp*Wp]."""
+    images = np.ascontiguousarray(images, np.float32)
+    B, H, W = images.shape
+    cap = max(B * (H // max(patch, 1)) * (W // max(patch, 1)), 1)
+    ly, lx, ls = (np.zeros(cap, np.int32) for _ in range(3))
+    off = np.zeros(B + 1, np.int32)
+    pl = np.zeros(cap, np.int32)
+    n = C.c_int64(0)
+    _check(load().reslim_asc_build(images.ctypes.data, B, H, W, patch, max_leaf, min_leaf, canny_low, canny_high, tau,
+                                   ly.ctypes.data, lx.ctypes.data, ls.ctypes.data, off.ctypes.data, pl.ctypes.data,
+                                   C.byref(n)))
+    L = int(n.value)
+    return dict(leaf_y0=ly[:L].copy(), leaf_x0=lx[:L].copy(), leaf_s=ls[:L].copy(), sample_off=off,
+                patch_leaf=pl.reshape(B, -1))
+
+
+def reslim_asc_edges(image: np.ndarray, canny_low: int, canny_high: int) -> np.ndarray:
+    image = np.ascontiguousarray(image, np.float32)
+    H, W = image.shape
+    out = np.zeros((H, W), np.uint8)
+    _check(load().reslim_asc_edges(image.ctypes.data, H, W, canny_low, canny_high, out.ctypes.data))
+    return out
+
+
+def reslim_asc_plan_create(ctx, batch: int, table: Dict[str, np.ndarray]) -> int:
+    arrs = {k: np.ascontiguousarray(table[k], np.int32) for k in ("leaf_y0", "leaf_x0", "leaf_s", "sample_off", "patch_leaf")}
+    out = C.c_void_p(None)
+    _check(load().reslim_asc_plan_create(ctx, batch, arrs["leaf_y0"].ctypes.data, arrs["leaf_x0"].ctypes.data,
+                                         arrs["leaf_s"].ctypes.data, len(arrs["leaf_s"]), arrs["sample_off"].ctypes.data,
+                                         arrs["patch_leaf"].ctypes.data, C.byref(out)), ctx)
+    return out.value
+
+
+def reslim_asc_plan_destroy(plan) -> None:
+    load().reslim_asc_plan_destroy(plan)
+
+
+def reslim_asc_plan_info(plan):
+    n, m = C.c_int64(0), C.c_int32(0)
+    _check(load().reslim_asc_plan_info(plan, C.byref(n), C.byref(m)))
+    return int(n.value), int(m.value)
+
+
+def reslim_asc_image(ctx, tokens, w_img, b_img, image, batch, stream=None):
+    _check(load().reslim_asc_image(ctx, tokens.data_ptr(), w_img.data_ptr(), b_img.data_ptr(), image.data_ptr(), batch,
+                                   _stream_ptr(stream)), ctx)
+
+
+def reslim_asc_compress(ctx, plan, tokens, tokens_c, stream=None):
+    _check(load().reslim_asc_compress(ctx, plan, tokens.data_ptr(), tokens_c.data_ptr(), _stream_ptr(stream)), ctx)
+
+
+def reslim_asc_forward(ctx, plan, x, y, workspace, stream=None):
+    _check(load().reslim_asc_forward(ctx, plan, x.data_ptr(), y.data_ptr(), workspace.data_ptr(),
+                                     workspace.numel() * workspace.element_size(), _stream_ptr(stream)), ctx)
 
 
 # ------------------------------------------------------------------ convenience holder

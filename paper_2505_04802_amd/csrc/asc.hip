@@ -1,0 +1,218 @@
+// Adaptive spatial compression, device side (ORBIT-2 Sec. 4.1): image-space map of
+// the aggregated embedding, leaf-mean compression of the tokens, the ViT blocks on
+// one token per quad-tree leaf with attention inside each sample, decompression
+// folded into the final LayerNorm's row map, then the usual head and residual path.
+#include <algorithm>
+#include <string>
+#include <vector>
+
+#include "common.h"
+
+struct reslim_asc_plan {
+  reslim_ctx *ctx = nullptr;
+  int batch = 0;
+  int64_t L = 0;                         // leaves of the whole batch
+  std::vector<tile_desc> seq;            // one entry per sample: tok_off, n_tok
+  reslim::SeqGeom geom{};
+  tile_desc *d_seq = nullptr;            // [batch]
+  int32_t *d_seq_of_leaf = nullptr;      // [L]
+  int32_t *d_leaf = nullptr;             // [L][4]: first patch row (b*N + y0*Wp + x0), side, unused, unused
+  int32_t *d_patch_leaf = nullptr;       // [batch * N]
+};
+
+namespace reslim {
+
+// One work-group per leaf: mean over its s x s patch rows, summed in row-major order.
+__global__ __launch_bounds__(256) void asc_compress_kernel(const float *__restrict__ z, const int32_t *__restrict__ leaf,
+                                                           float *__restrict__ out, int Wp, int D) {
+  const int64_t l = blockIdx.x;
+  const int first = leaf[4 * l], s = leaf[4 * l + 1];
+  const float inv = 1.0f / static_cast<float>(s * s);
+  for (int d = threadIdx.x * 4; d < D; d += 1024) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int dy = 0; dy < s; ++dy)
+      for (int dx = 0; dx < s; ++dx) {
+        const float4 v = *reinterpret_cast<const float4 *>(z + (static_cast<size_t>(first) + static_cast<size_t>(dy) * Wp + dx) * D + d);
+        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+      }
+    *reinterpret_cast<float4 *>(out + static_cast<size_t>(l) * D + d) = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
+  }
+}
+
+// One wave per token: p*p dot products of length D, written to the token's pixels.
+__global__ __launch_bounds__(256) void asc_image_kernel(const float *__restrict__ z, const float *__restrict__ w_img,
+                                                        const float *__restrict__ b_img, float *__restrict__ img,
+                                                        int64_t tokens, int N, int Wp, int p, int D, int H, int W) {
+  const int lane = threadIdx.x & 63;
+  const int64_t tok = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  if (tok >= tokens) return;
+  const float *row = z + static_cast<size_t>(tok) * D;
+  const int64_t b = tok / N;
+  const int n = static_cast<int>(tok % N), py = n / Wp, px = n % Wp;
+  for (int o = 0; o < p * p; ++o) {
+    const float *wr = w_img + static_cast<size_t>(o) * D;
+    float acc = 0.f;
+    for (int d = lane; d < D; d += 64) acc = fmaf(wr[d], row[d], acc);
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+    if (lane == 0) img[(static_cast<size_t>(b) * H + py * p + o / p) * W + px * p + o % p] = acc + b_img[o];
+  }
+}
+
+static void asc_free(reslim_asc_plan *pl) {
+  if (!pl) return;
+  if (pl->d_seq) (void)hipFree(pl->d_seq);
+  if (pl->d_seq_of_leaf) (void)hipFree(pl->d_seq_of_leaf);
+  if (pl->d_leaf) (void)hipFree(pl->d_leaf);
+  if (pl->d_patch_leaf) (void)hipFree(pl->d_patch_leaf);
+  delete pl;
+}
+
+static int asc_check(reslim_ctx *c, const reslim_asc_plan *pl, const char *fn) {
+  if (!pl) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": null plan");
+  if (pl->ctx != c) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": plan belongs to another context");
+  return RESLIM_OK;
+}
+
+}  // namespace reslim
+
+using namespace reslim;
+
+extern "C" int reslim_asc_plan_create(reslim_ctx *c, int32_t batch, const int32_t *leaf_y0, const int32_t *leaf_x0,
+                                      const int32_t *leaf_s, int64_t n_leaves, const int32_t *sample_off,
+                                      const int32_t *patch_leaf, reslim_asc_plan **out) {
+  const char *fn = "reslim_asc_plan_create";
+  if (!c) return RESLIM_EINVAL;
+  if (out) *out = nullptr;
+  if (!leaf_y0 || !leaf_x0 || !leaf_s || !sample_off || !patch_leaf || !out)
+    return set_error(c, RESLIM_EINVAL, std::string(fn) + ": null pointer");
+  if (c->T != 1) return set_error(c, RESLIM_ESHAPE, std::string(fn) + ": the context must be created with one tile (compression and tiling are not combined)");
+  const int64_t N = c->N;
+  if (c->cfg.embed_dim % 4) return set_error(c, RESLIM_ESHAPE, std::string(fn) + ": embed_dim must be a multiple of 4");
+  if (batch < 1 || n_leaves < batch || n_leaves > batch * N || batch * N > INT32_MAX)
+    return set_error(c, RESLIM_ESHAPE, std::string(fn) + ": batch or leaf count out of range");
+  // The table must be a partition of every sample's patch grid into aligned squares,
+  // listed sample by sample, and patch_leaf its inverse: the kernels trust it.
+  if (sample_off[0] != 0 || sample_off[batch] != n_leaves) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": sample_off does not span the leaves");
+  std::vector<int32_t> leaf(static_cast<size_t>(n_leaves) * 4, 0), seq_of(static_cast<size_t>(n_leaves));
+  std::vector<tile_desc> seq(batch);
+  int max_n = 0;
+  double pairs = 0;
+  for (int b = 0; b < batch; ++b) {
+    const int64_t lo = sample_off[b], hi = sample_off[b + 1];
+    if (hi <= lo || hi > n_leaves) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": sample_off not increasing");
+    int64_t covered = 0;
+    for (int64_t l = lo; l < hi; ++l) {
+      const int y0 = leaf_y0[l], x0 = leaf_x0[l], s = leaf_s[l];
+      if (s < 1 || (s & (s - 1)) || y0 < 0 || x0 < 0 || y0 % s || x0 % s || y0 + s > c->Hp || x0 + s > c->Wp)
+        return set_error(c, RESLIM_EINVAL, std::string(fn) + ": leaf outside the grid or not an aligned power-of-two square");
+      for (int yy = y0; yy < y0 + s; ++yy)
+        for (int xx = x0; xx < x0 + s; ++xx)
+          if (patch_leaf[b * N + static_cast<int64_t>(yy) * c->Wp + xx] != l)
+            return set_error(c, RESLIM_EINVAL, std::string(fn) + ": patch_leaf disagrees with the leaf list");
+      covered += static_cast<int64_t>(s) * s;
+      leaf[4 * l] = static_cast<int32_t>(b * N + static_cast<int64_t>(y0) * c->Wp + x0);
+      leaf[4 * l + 1] = s;
+      seq_of[l] = b;
+    }
+    if (covered != N) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": leaves of a sample do not cover its grid exactly once");
+    seq[b] = tile_desc{};
+    seq[b].tok_off = lo;
+    seq[b].n_tok = static_cast<int32_t>(hi - lo);
+    max_n = std::max(max_n, seq[b].n_tok);
+    pairs += static_cast<double>(hi - lo) * static_cast<double>(hi - lo);
+  }
+  reslim_asc_plan *pl = new (std::nothrow) reslim_asc_plan;
+  if (!pl) return set_error(c, RESLIM_ENOMEM, std::string(fn) + ": host allocation failed");
+  pl->ctx = c; pl->batch = batch; pl->L = n_leaves; pl->seq = seq;
+  hipError_t e = hipMalloc(reinterpret_cast<void **>(&pl->d_seq), batch * sizeof(tile_desc));
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&pl->d_seq_of_leaf), n_leaves * 4);
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&pl->d_leaf), n_leaves * 16);
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&pl->d_patch_leaf), batch * N * 4);
+  if (e == hipSuccess) e = hipMemcpy(pl->d_seq, seq.data(), batch * sizeof(tile_desc), hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(pl->d_seq_of_leaf, seq_of.data(), n_leaves * 4, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(pl->d_leaf, leaf.data(), n_leaves * 16, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(pl->d_patch_leaf, patch_leaf, batch * N * 4, hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    asc_free(pl);
+    return set_error(c, e == hipErrorOutOfMemory ? RESLIM_ENOMEM : RESLIM_EHIP, std::string(fn) + ": " + hipGetErrorString(e));
+  }
+  pl->geom.d_tiles = pl->d_seq;
+  pl->geom.d_tile_of_tok = pl->d_seq_of_leaf;
+  pl->geom.T = batch;
+  pl->geom.n_h = n_leaves;
+  pl->geom.max_n_tok = max_n;
+  pl->geom.pairs = pairs;
+  *out = pl;
+  return RESLIM_OK;
+}
+
+extern "C" void reslim_asc_plan_destroy(reslim_asc_plan *plan) { asc_free(plan); }
+
+extern "C" int reslim_asc_image(reslim_ctx *c, const float *tokens, const float *w_img, const float *b_img, float *image,
+                                int32_t batch, void *hip_stream) {
+  const char *fn = "reslim_asc_image";
+  if (!c) return RESLIM_EINVAL;
+  if (!tokens || !w_img || !b_img || !image) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": null buffer");
+  if (batch < 1 || static_cast<int64_t>(batch) * c->N > INT32_MAX) return set_error(c, RESLIM_ESHAPE, std::string(fn) + ": batch out of range");
+  const int64_t tokens_n = static_cast<int64_t>(batch) * c->N;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  asc_image_kernel<<<dim3(static_cast<unsigned>((tokens_n + 3) / 4)), dim3(256), 0, st>>>(
+      tokens, w_img, b_img, image, tokens_n, c->N, c->Wp, c->cfg.patch, c->cfg.embed_dim, c->cfg.H, c->cfg.W);
+  RESLIM_TRY("asc_image", hipGetLastError());
+  return RESLIM_OK;
+}
+
+extern "C" int reslim_asc_compress(reslim_ctx *c, const reslim_asc_plan *plan, const float *tokens, float *tokens_c, void *hip_stream) {
+  const char *fn = "reslim_asc_compress";
+  if (!c) return RESLIM_EINVAL;
+  int rc = asc_check(c, plan, fn);
+  if (rc != RESLIM_OK) return rc;
+  if (!tokens || !tokens_c) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": null buffer");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  asc_compress_kernel<<<dim3(static_cast<unsigned>(plan->L)), dim3(256), 0, st>>>(tokens, plan->d_leaf, tokens_c, c->Wp, c->cfg.embed_dim);
+  RESLIM_TRY("asc_compress", hipGetLastError());
+  return RESLIM_OK;
+}
+
+extern "C" int reslim_asc_forward(reslim_ctx *c, const reslim_asc_plan *plan, const float *x, float *y, void *workspace,
+                                  size_t ws_bytes, void *hip_stream) {
+  const char *fn = "reslim_asc_forward";
+  if (!c) return RESLIM_EINVAL;
+  int rc = asc_check(c, plan, fn);
+  if (rc != RESLIM_OK) return rc;
+  if (!x || !y) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": null buffer");
+  const int batch = plan->batch;
+  rc = check_common(c, fn, batch, workspace, ws_bytes, true);
+  if (rc != RESLIM_OK) return rc;
+  const Workspace w = plan_workspace(c, batch, workspace);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int D = c->cfg.embed_dim, dt = c->cfg.dtype;
+  const int Mi = batch * c->N;
+  const double es = static_cast<double>(act_size(c)), dMi = Mi, dD = D, dO = c->head_out, dL = static_cast<double>(plan->L);
+  // embed (w.big <- [Mi, D] fp32), compress into the stream buffer
+  if ((rc = embed_full_impl(c, fn, x, batch, w, st)) != RESLIM_OK) return rc;
+  RESLIM_LAUNCH("asc_compress", 0, 4.0 * dMi * dD + 4.0 * dL * dD,
+                (asc_compress_kernel<<<dim3(static_cast<unsigned>(plan->L)), dim3(256), 0, st>>>(
+                     static_cast<const float *>(w.big), plan->d_leaf, w.X, c->Wp, D),
+                 hipGetLastError()));
+  // blocks on the leaves: the batch is one run of L rows, one attention set per sample
+  for (int l = 0; l < c->cfg.depth; ++l)
+    if ((rc = block_impl(c, fn, l, w.X, 1, w, st, &plan->geom)) != RESLIM_OK) return rc;
+  // decompression = the final LayerNorm reading each patch's row from its leaf
+  RESLIM_LAUNCH("layernorm_final", 0, dMi * dD * (4.0 + es),
+                launch_layernorm(dt, w.X, plan->d_patch_leaf, Mi, plan->L, c->d_lnf_g, c->d_lnf_b, w.A, Mi, D, st));
+  RESLIM_LAUNCH("gemm_head", 2.0 * dMi * dD * dO, dMi * dD * es + dD * dO * es + 4.0 * dMi * dO,
+                launch_gemm(dt, EPI_BIAS_F32, w.A, c->d_w_head, c->d_b_head, w.big, c->head_out, nullptr, 0, Mi, c->head_out, D, st));
+  const double fine = static_cast<double>(batch) * c->cfg.out_vars * c->cfg.H * c->cfg.W * c->cfg.scale * c->cfg.scale;
+  RESLIM_LAUNCH("residual_unpatchify", 18.0 * c->cfg.out_vars * fine,
+                4.0 * batch * c->cfg.out_vars * c->cfg.H * c->cfg.W + 4.0 * dMi * dO + 4.0 * fine,
+                launch_residual_unpatchify(c, x, w.big, 0, y, batch, st));
+  return RESLIM_OK;
+}
+
+extern "C" int reslim_asc_plan_info(const reslim_asc_plan *plan, int64_t *n_leaves, int32_t *max_per_sample) {
+  if (!plan || !n_leaves || !max_per_sample) return RESLIM_EINVAL;
+  *n_leaves = plan->L;
+  *max_per_sample = plan->geom.max_n_tok;
+  return RESLIM_OK;
+}

@@ -422,21 +422,35 @@ hipError_t attention_init() {
 }
 bool attention_accepts_prescaled_q() { return true; }
 
+SeqGeom ctx_geom(const reslim_ctx *c) {
+  SeqGeom g;
+  g.d_tiles = c->d_tiles;
+  g.d_tile_of_tok = c->d_tile_of_tok;
+  g.T = c->T;
+  g.n_h = c->n_h;
+  g.max_n_tok = c->max_n_tok;
+  g.pairs = 0;
+  for (const tile_desc &t : c->tiles) g.pairs += static_cast<double>(t.n_tok) * t.n_tok;
+  return g;
+}
+
 hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *out, int batch, bool q_prescaled,
-                                  hipStream_t st, float *lse) {
+                                  hipStream_t st, float *lse, const SeqGeom *geom) {
+  const SeqGeom own = geom ? *geom : ctx_geom(c);
+  const SeqGeom &sg = own;
   AttnArgs a;
   a.qkv = qkv;
   a.out = out;
   a.lse = lse;
-  a.tiles = c->d_tiles;
-  a.T = c->T;
+  a.tiles = sg.d_tiles;
+  a.T = sg.T;
   a.heads = c->cfg.heads;
   a.D = c->cfg.embed_dim;
-  a.n_h = c->n_h;
+  a.n_h = sg.n_h;
   a.scale_log2 = 1.4426950408889634f / sqrtf(static_cast<float>(c->dh));
   if (c->cfg.dtype == RESLIM_BF16) {
-    a.QB = (c->max_n_tok + 127) / 128;
-    const int64_t total = static_cast<int64_t>(batch) * c->T * a.heads * a.QB;
+    a.QB = (sg.max_n_tok + 127) / 128;
+    const int64_t total = static_cast<int64_t>(batch) * sg.T * a.heads * a.QB;
     if (total > INT32_MAX) return hipErrorInvalidValue;
     a.total = static_cast<int>(total);
     if (a.total == 0) return hipSuccess;
@@ -462,12 +476,12 @@ hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *ou
     }
     return hipGetLastError();
   }
-  a.QB = c->max_n_tok;
+  a.QB = sg.max_n_tok;
   a.total = 0;
-  const size_t lds = (static_cast<size_t>(c->max_n_tok) + c->dh) * sizeof(float);
-  if (lds > 60 * 1024 || c->n_h > INT32_MAX) return hipErrorInvalidValue;
-  tiles_attention_f32_kernel<<<dim3(static_cast<unsigned>(c->n_h), a.heads, batch), dim3(128), lds, st>>>(
-      a, c->dh, c->d_tile_of_tok);
+  const size_t lds = (static_cast<size_t>(sg.max_n_tok) + c->dh) * sizeof(float);
+  if (lds > 60 * 1024 || sg.n_h > INT32_MAX) return hipErrorInvalidValue;
+  tiles_attention_f32_kernel<<<dim3(static_cast<unsigned>(sg.n_h), a.heads, batch), dim3(128), lds, st>>>(
+      a, c->dh, sg.d_tile_of_tok);
   return hipGetLastError();
 }
 

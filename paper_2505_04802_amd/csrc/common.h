@@ -89,6 +89,19 @@ void set_thread_error(const std::string &msg);
 inline size_t act_size(const reslim_ctx *c) { return c->cfg.dtype == RESLIM_BF16 ? 2 : 4; }
 inline size_t align256(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
 
+// Which token rows attend to each other: by default the context's tile table applied
+// to every sample; the compression module supplies one entry per sample of a batch
+// that is then treated as a single "sample" of n_h rows.
+struct SeqGeom {
+  const tile_desc *d_tiles;        // device [T]: tok_off, n_tok used
+  const int32_t *d_tile_of_tok;    // device [n_h]
+  int T;
+  int64_t n_h;
+  int max_n_tok;
+  double pairs;                    // sum over entries of n_tok^2 (flop accounting)
+};
+SeqGeom ctx_geom(const reslim_ctx *c);
+
 // Workspace carve-up used by block / embed / head / forward.
 struct Workspace {
   float *X;        // [M, D] residual stream (forward only)
@@ -97,6 +110,10 @@ struct Workspace {
   size_t total;
 };
 Workspace plan_workspace(const reslim_ctx *c, int batch, void *base);
+// one transformer block on X [batch * geom.n_h, D] in place (geom == nullptr: the context's tiles)
+int block_impl(reslim_ctx *c, const char *fn, int layer, float *X, int batch, const Workspace &w, hipStream_t st,
+               const SeqGeom *geom = nullptr);
+int embed_full_impl(reslim_ctx *c, const char *fn, const float *x, int batch, const Workspace &w, hipStream_t st);
 
 // ---- kernels (host launchers; all enqueue on `st` and return hipError_t) ------
 enum Epilogue {
@@ -125,7 +142,8 @@ hipError_t launch_gather_rows(const float *z, const int32_t *gather, float *X, i
 hipError_t launch_embed_agg(const reslim_ctx *c, const float *x, void *o, int batch, hipStream_t st);
 // q_prescaled: q already carries the factor log2(e)/sqrt(dh) (bf16 path only)
 hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *out, int batch, bool q_prescaled,
-                                  hipStream_t st, float *lse = nullptr);
+                                  hipStream_t st, float *lse = nullptr,
+                                  const SeqGeom *geom = nullptr);
 bool attention_accepts_prescaled_q();
 // gradient of tile attention: d_qkv from qkv, the forward's out and lse, and d_out; ws as sized below
 hipError_t launch_tiles_attention_bwd(const reslim_ctx *c, const void *qkv, const void *out, const float *lse,

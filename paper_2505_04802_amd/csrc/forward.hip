@@ -48,26 +48,37 @@ int check_common(reslim_ctx *c, const char *fn, int batch, const void *ws, size_
   return RESLIM_OK;
 }
 
-static int embed_impl(reslim_ctx *c, const char *fn, const float *x, float *tokens, int batch, const Workspace &w, hipStream_t st) {
+// tokenisation + aggregation + position/resolution terms: w.big <- float [batch * N, D] in patch order
+int embed_full_impl(reslim_ctx *c, const char *fn, const float *x, int batch, const Workspace &w, hipStream_t st) {
   const int D = c->cfg.embed_dim, dt = c->cfg.dtype;
   const int Mi = batch * c->N;
-  const double es = static_cast<double>(act_size(c)), dMi = Mi, dD = D, dM = static_cast<double>(batch) * c->n_h;
+  const double es = static_cast<double>(act_size(c)), dMi = Mi, dD = D;
   RESLIM_LAUNCH("embed_agg", 0, 4.0 * batch * c->cfg.in_vars * c->cfg.H * c->cfg.W + dMi * dD * es,
                 launch_embed_agg(c, x, w.A, batch, st));
   RESLIM_LAUNCH("gemm_agg_out", 2.0 * dMi * dD * dD, dMi * dD * es + dD * dD * es + 4.0 * c->N * dD + 4.0 * dMi * dD,
                 launch_gemm(dt, EPI_BIAS_TAB_F32, w.A, c->d_agg_wo, c->d_zero_bias, w.big, D, c->d_pos_res, c->N, Mi, D, D, st));
+  return RESLIM_OK;
+}
+
+static int embed_impl(reslim_ctx *c, const char *fn, const float *x, float *tokens, int batch, const Workspace &w, hipStream_t st) {
+  const int D = c->cfg.embed_dim;
+  const int Mi = batch * c->N;
+  const double dMi = Mi, dD = D, dM = static_cast<double>(batch) * c->n_h;
+  const int rc = embed_full_impl(c, fn, x, batch, w, st);
+  if (rc != RESLIM_OK) return rc;
   RESLIM_LAUNCH("gather", 0, 4.0 * dMi * dD + 4.0 * dM * dD,
                 launch_gather_rows(static_cast<const float *>(w.big), c->d_gather, tokens, batch, c->n_h, c->N, D, st));
   return RESLIM_OK;
 }
 
-static int block_impl(reslim_ctx *c, const char *fn, int layer, float *X, int batch, const Workspace &w, hipStream_t st) {
+int block_impl(reslim_ctx *c, const char *fn, int layer, float *X, int batch, const Workspace &w, hipStream_t st,
+               const SeqGeom *geom) {
   const int D = c->cfg.embed_dim, R = c->R, dt = c->cfg.dtype;
-  const int M = static_cast<int>(batch * c->n_h);
+  const SeqGeom sg = geom ? *geom : ctx_geom(c);
+  const int M = static_cast<int>(batch * sg.n_h);
   const LayerWeights &lw = c->layers[layer];
   const double es = static_cast<double>(act_size(c)), dM = M, dD = D, dR = R;
-  double pairs = 0;
-  for (const tile_desc &t : c->tiles) pairs += static_cast<double>(t.n_tok) * t.n_tok;
+  const double pairs = sg.pairs;
   RESLIM_LAUNCH("layernorm", 0, dM * dD * (4.0 + es), launch_layernorm(dt, X, nullptr, 0, 0, lw.ln1_g, lw.ln1_b, w.A, M, D, st));
   // bf16 path: the QKV epilogue multiplies q by log2(e)/sqrt(dh) before its one
   // rounding to bf16, and the attention kernel then exponentiates in base 2 directly
@@ -77,7 +88,7 @@ static int block_impl(reslim_ctx *c, const char *fn, int layer, float *X, int ba
                 launch_gemm(dt, qs ? EPI_BIAS_QSCALE_ACT : EPI_BIAS_ACT, w.A, lw.w_qkv, lw.b_qkv, w.big, 3 * D, nullptr, 0, M,
                             3 * D, D, st, qscale, D));
   RESLIM_LAUNCH("tiles_attention", 4.0 * pairs * dD * batch, 4.0 * dM * dD * es,
-                launch_tiles_attention(c, w.big, w.A, batch, qs, st));
+                launch_tiles_attention(c, w.big, w.A, batch, qs, st, nullptr, &sg));
   RESLIM_LAUNCH("gemm_proj", 2.0 * dM * dD * dD, dM * dD * es + dD * dD * es + 8.0 * dM * dD,
                 launch_gemm(dt, EPI_BIAS_RESADD_F32, w.A, lw.w_proj, lw.b_proj, X, D, nullptr, 0, M, D, D, st));
   RESLIM_LAUNCH("layernorm", 0, dM * dD * (4.0 + es), launch_layernorm(dt, X, nullptr, 0, 0, lw.ln2_g, lw.ln2_b, w.A, M, D, st));

@@ -1,0 +1,156 @@
+"""GPU parity of adaptive spatial compression (Sec. 4.1): image-space map,
+leaf-mean compression and the whole forward on the leaves, through the C ABI,
+against the CPU oracle on the same seeded inputs.  The leaf tables come from the
+oracle's own builder (the library's builder is compared with it bit for bit in
+the CPU tests), so no expected value depends on the GPU path.
+
+Tolerances: fp32 path rel-L2 <= 1e-5, bf16 path <= 2e-2 (the forward's bars)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import asc_oracle as A
+from oracle import reslim_oracle as O
+from paper_2505_04802_amd import binding as B
+from paper_2505_04802_amd import workloads as WL
+
+pytestmark = pytest.mark.gpu
+TOL = {0: 1e-5, 1: 2e-2}
+
+ASC_F32 = WL.ReslimConfig("a32", batch=3, in_vars=3, out_vars=2, H=32, W=48, scale=2, patch=2,
+                          embed_dim=48, heads=3, mlp_ratio=2, depth=2, tiles_y=1, tiles_x=1,
+                          halo=0, dtype=0, seed=21)
+ASC_BF16 = WL.ReslimConfig("abf", batch=2, in_vars=3, out_vars=3, H=64, W=96, scale=4, patch=2,
+                           embed_dim=128, heads=2, mlp_ratio=4, depth=2, tiles_y=1, tiles_x=1,
+                           halo=0, dtype=1, seed=22)       # dh = 64; up to 1536 tokens per sample before compression
+ASC_BF16_DH128 = ASC_BF16.with_(name="abf128", embed_dim=256, heads=2, seed=23)
+
+
+def cuda(a, dtype=torch.float32):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda().to(dtype)
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def table_for(cfg, x, max_leaf=8, min_leaf=1, tau=0.05):
+    """Leaf table from the oracle's builder on the first input variable; thresholds at
+    fixed quantiles of that field's own gradient magnitude so that the tree is mixed."""
+    imgs = np.ascontiguousarray(x[:, 0])
+    q = A.quantise_u8(imgs[0])
+    gx, gy = A.sobel(A.smooth(q))
+    mag = np.abs(gx) + np.abs(gy)
+    low, high = int(np.quantile(mag, 0.6)), int(np.quantile(mag, 0.85))
+    return A.build(imgs, cfg.patch, max_leaf, min_leaf, low, high, tau)
+
+
+@pytest.mark.parametrize("cfg", [ASC_F32, ASC_BF16], ids=lambda c: c.name)
+def test_image_and_compress_parity(cfg):
+    say(f"asc image + compress {cfg.name}")
+    r = np.random.default_rng(cfg.seed)
+    D, N, p = cfg.embed_dim, cfg.n_tokens, cfg.patch
+    z = r.standard_normal((cfg.batch, N, D)).astype(np.float32)
+    w_img = (r.standard_normal((p * p, D)) / np.sqrt(D)).astype(np.float32)
+    b_img = r.standard_normal(p * p).astype(np.float32)
+    x = WL.make_fields(cfg)
+    tab = table_for(cfg, x)
+    L = len(tab["leaf_s"])
+    say(f"  {cfg.batch * N} patches -> {L} leaves, per sample {np.diff(tab['sample_off']).tolist()}")
+    assert L < cfg.batch * N and len(set(np.diff(tab["sample_off"]).tolist())) > 1      # compressed, ragged
+    with B.Reslim(cfg, WL.make_weights(cfg)) as m:
+        img = torch.full((cfg.batch, cfg.H, cfg.W), float("nan"), dtype=torch.float32, device="cuda")
+        B.reslim_asc_image(m.ctx, cuda(z), cuda(w_img), cuda(b_img), img, cfg.batch)
+        ref = A.image_from_tokens(z, w_img, b_img, cfg.Hp, cfg.Wp, p)
+        err = O.rel_l2(img.cpu().numpy(), ref)
+        say(f"  image rel-L2 {err:.3e}")
+        assert err <= 1e-6
+        plan = B.reslim_asc_plan_create(m.ctx, cfg.batch, tab)
+        try:
+            assert B.reslim_asc_plan_info(plan) == (L, int(np.diff(tab["sample_off"]).max()))
+            zc = torch.full((L, D), float("nan"), dtype=torch.float32, device="cuda")
+            B.reslim_asc_compress(m.ctx, plan, cuda(z), zc)
+            err = O.rel_l2(zc.cpu().numpy(), A.compress(z, tab, cfg.Wp))
+            say(f"  compress rel-L2 {err:.3e}")
+            assert err <= 1e-6
+        finally:
+            B.reslim_asc_plan_destroy(plan)
+
+
+@pytest.mark.parametrize("cfg", [ASC_F32, ASC_BF16, ASC_BF16_DH128], ids=lambda c: c.name)
+def test_compressed_forward_parity(cfg):
+    say(f"asc forward {cfg.name}")
+    w = WL.make_weights(cfg, std=0.05)
+    x = WL.make_fields(cfg)
+    tab = table_for(cfg, x)
+    L = len(tab["leaf_s"])
+    say(f"  {cfg.batch * cfg.n_tokens} patches -> {L} leaves, per sample {np.diff(tab['sample_off']).tolist()}")
+    ref = A.forward_compressed(x, w, cfg, tab)
+    with B.Reslim(cfg, w) as m:
+        plan = B.reslim_asc_plan_create(m.ctx, cfg.batch, tab)
+        try:
+            y = torch.full((cfg.batch, cfg.out_vars, cfg.H * cfg.scale, cfg.W * cfg.scale), float("nan"),
+                           dtype=torch.float32, device="cuda")
+            B.reslim_asc_forward(m.ctx, plan, cuda(x), y, m.ws)
+            out = y.cpu().numpy()
+        finally:
+            B.reslim_asc_plan_destroy(plan)
+    assert np.isfinite(out).all()
+    err = max(O.rel_l2(out[b, c], ref[b, c]) for b in range(cfg.batch) for c in range(cfg.out_vars))
+    say(f"  max rel-L2 over planes {err:.3e}")
+    assert err <= TOL[cfg.dtype]
+
+
+def test_single_patch_leaves_reproduce_the_plain_forward():
+    """Switched off (one patch per leaf) the module is the identity: the library's
+    compressed forward and its plain forward agree, and both match the oracle."""
+    cfg = ASC_F32
+    w = WL.make_weights(cfg, std=0.05)
+    x = WL.make_fields(cfg)
+    ones = np.ones((cfg.batch, cfg.H, cfg.W), np.float32)
+    r = np.random.default_rng(3)
+    noise = r.standard_normal(ones.shape).astype(np.float32)          # white noise: edges everywhere
+    tab = A.build(noise, cfg.patch, 8, 1, 0, 0, 0.0)
+    if not (tab["leaf_s"] == 1).all():                                 # any patch without an edge pixel keeps its parent
+        tab = A.build(noise, cfg.patch, 1, 1, 0, 0, 0.0)
+    assert (tab["leaf_s"] == 1).all()
+    ref = O.reslim_forward(x, w, cfg)
+    with B.Reslim(cfg, w) as m:
+        plan = B.reslim_asc_plan_create(m.ctx, cfg.batch, tab)
+        try:
+            y = torch.empty((cfg.batch, cfg.out_vars, cfg.H * cfg.scale, cfg.W * cfg.scale), dtype=torch.float32, device="cuda")
+            B.reslim_asc_forward(m.ctx, plan, cuda(x), y, m.ws)
+            plain = m.forward(cuda(x)).cpu().numpy()
+        finally:
+            B.reslim_asc_plan_destroy(plan)
+    assert O.rel_l2(y.cpu().numpy(), ref) <= 1e-5 and O.rel_l2(plain, ref) <= 1e-5
+    assert np.abs(y.cpu().numpy() - plain).max() <= 1e-5
+
+
+def test_plan_errors():
+    cfg = ASC_F32
+    x = WL.make_fields(cfg)
+    tab = table_for(cfg, x)
+    w = WL.make_weights(cfg)
+    with B.Reslim(cfg, w) as m:
+        bad = dict(tab); bad["leaf_s"] = tab["leaf_s"].copy(); bad["leaf_s"][0] *= 2        # overlaps / leaves the grid
+        with pytest.raises(B.ReslimError):
+            B.reslim_asc_plan_create(m.ctx, cfg.batch, bad)
+        bad = dict(tab); bad["patch_leaf"] = tab["patch_leaf"].copy(); bad["patch_leaf"][1, 5] += 1
+        with pytest.raises(B.ReslimError):
+            B.reslim_asc_plan_create(m.ctx, cfg.batch, bad)
+        bad = dict(tab); bad["sample_off"] = tab["sample_off"].copy(); bad["sample_off"][1] += 1   # sample 0 takes a leaf of sample 1
+        with pytest.raises(B.ReslimError):
+            B.reslim_asc_plan_create(m.ctx, cfg.batch, bad)
+        plan = B.reslim_asc_plan_create(m.ctx, cfg.batch, tab)
+        try:
+            with B.Reslim(cfg, w) as other:                                                  # a plan is tied to its context
+                y = torch.empty((cfg.batch, cfg.out_vars, cfg.H * cfg.scale, cfg.W * cfg.scale), dtype=torch.float32, device="cuda")
+                with pytest.raises(B.ReslimError):
+                    B.reslim_asc_forward(other.ctx, plan, cuda(x), y, other.ws)
+        finally:
+            B.reslim_asc_plan_destroy(plan)
+    tiled = cfg.with_(tiles_y=2, tiles_x=2, halo=1)
+    with B.Reslim(tiled, WL.make_weights(tiled)) as m:
+        with pytest.raises(B.ReslimError):
+            B.reslim_asc_plan_create(m.ctx, cfg.batch, tab)
