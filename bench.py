@@ -98,6 +98,49 @@ def train_block(B, torch, model, cfg, K, verbose):
     return res
 
 
+# Adaptive spatial compression (Sec. 4.1; Table 2(b) quotes speed-ups at 8x / 16x / 32x compression
+# on one tile): the workload's grid untiled, quad-trees from the library's host builder on the
+# first input variable.  Parameters chosen so that the c1 fields compress about 8x and 22x.
+ASC_PARAMS = [dict(max_leaf=16, min_leaf=1, canny_low=70, canny_high=140, tau=0.05),
+              dict(max_leaf=16, min_leaf=1, canny_low=80, canny_high=160, tau=0.05)]
+
+
+def asc_leg(B, torch, np, cfg, w, x_host, K):
+    """Forward time with and without compression on the untiled grid (extra measurement, not `value`)."""
+    one = cfg.with_(tiles_y=1, tiles_x=1, halo=0)
+    res = {"workload": f"{cfg.name} grid, one tile: B={one.batch}, {one.n_tokens} patches per sample", "cases": []}
+    with B.Reslim(one, w) as m:
+        x = torch.from_numpy(x_host).cuda()
+        y = torch.empty((one.batch, one.out_vars, one.H * one.scale, one.W * one.scale), dtype=torch.float32, device="cuda")
+
+        def timed(fn):
+            for _ in range(2):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(K):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / K * 1e3
+
+        res["plain_ms"] = round(timed(lambda: B.reslim_forward(m.ctx, x, y, one.batch, m.ws)), 4)
+        imgs = np.ascontiguousarray(x_host[:, 0])
+        for prm in ASC_PARAMS:
+            t0 = time.perf_counter()
+            tab = B.reslim_asc_build(imgs, one.patch, prm["max_leaf"], prm["min_leaf"], prm["canny_low"], prm["canny_high"], prm["tau"])
+            build_ms = (time.perf_counter() - t0) * 1e3
+            plan = B.reslim_asc_plan_create(m.ctx, one.batch, tab)
+            try:
+                ms = timed(lambda: B.reslim_asc_forward(m.ctx, plan, x, y, m.ws))
+            finally:
+                B.reslim_asc_plan_destroy(plan)
+            L = len(tab["leaf_s"])
+            res["cases"].append(dict(params=prm, leaves=L, compression=round(one.batch * one.n_tokens / L, 2),
+                                     leaves_per_sample=np.diff(tab["sample_off"]).tolist(), ms=round(ms, 4),
+                                     speedup=round(res["plain_ms"] / ms, 2), host_builder_ms=round(build_ms, 2)))
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -109,6 +152,8 @@ def main() -> int:
     ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
     ap.add_argument("--no-train-block", action="store_true",
                     help="skip the extra (untimed in `value`) measurement of one block's training forward + backward")
+    ap.add_argument("--no-asc", action="store_true",
+                    help="skip the extra measurement of the forward with adaptive spatial compression (run for c0 and c1 only)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch the library's plain copy kernel on 1 GiB five times (yardstick for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -206,6 +251,11 @@ def main() -> int:
         train = train_block(B, torch, model, cfg, K, args.kernels)
     model.close()
 
+    # ---- extra, outside `value`: the untiled grid with and without adaptive spatial compression
+    asc = None
+    if not args.no_asc and cfg.name in ("c0", "c1"):
+        asc = asc_leg(B, torch, np, cfg, w, x_host, K)
+
     # ---- the CPU oracle on a bounded sample of the same workload (one sample of the batch)
     cpu = None
     if not args.no_cpu_baseline:
@@ -238,7 +288,7 @@ def main() -> int:
                    "unique_tokens": tokens, "haloed_tokens": cfg.batch * model.n_h},
         "tflops": round(tflops, 2), "mfma_frac": round(tflops / PEAK_BF16_TFLOPS, 4),
         "haloed_tokens_per_s": round(cfg.batch * model.n_h / (dt / K), 1),
-        "roofline": roof, "cpu_baseline": cpu, "kernels": kernels, "train_block": train,
+        "roofline": roof, "cpu_baseline": cpu, "kernels": kernels, "train_block": train, "asc": asc,
     }
     print(json.dumps(out))
     return 0

@@ -154,3 +154,35 @@ def test_plan_errors():
     with B.Reslim(tiled, WL.make_weights(tiled)) as m:
         with pytest.raises(B.ReslimError):
             B.reslim_asc_plan_create(m.ctx, cfg.batch, tab)
+
+
+def test_compressed_forward_at_the_benchmark_grid():
+    """The benchmark's compression case: the c1 grid as one tile (8192 patches per
+    sample) with its ~8x quad-tree parameters, two samples, whole output against the
+    oracle; the library's host builder must give the oracle's table."""
+    import bench
+    cfg = WL.CONFIGS["c1"].with_(tiles_y=1, tiles_x=1, halo=0, batch=2)
+    prm = bench.ASC_PARAMS[0]
+    w = WL.make_weights(cfg)
+    x = WL.make_fields(cfg)
+    imgs = np.ascontiguousarray(x[:, 0])
+    say("asc benchmark grid: building the table (oracle and library)")
+    tab = A.build(imgs, cfg.patch, prm["max_leaf"], prm["min_leaf"], prm["canny_low"], prm["canny_high"], prm["tau"])
+    lib = B.reslim_asc_build(imgs, cfg.patch, prm["max_leaf"], prm["min_leaf"], prm["canny_low"], prm["canny_high"], prm["tau"])
+    for k in tab:
+        assert (np.asarray(tab[k]) == np.asarray(lib[k])).all(), k
+    L = len(tab["leaf_s"])
+    say(f"  {cfg.batch * cfg.n_tokens} patches -> {L} leaves, per sample {np.diff(tab['sample_off']).tolist()}; oracle forward ...")
+    ref = A.forward_compressed(x, w, cfg, tab)
+    with B.Reslim(cfg, w) as m:
+        plan = B.reslim_asc_plan_create(m.ctx, cfg.batch, tab)
+        try:
+            y = torch.full((cfg.batch, cfg.out_vars, cfg.H * cfg.scale, cfg.W * cfg.scale), float("nan"),
+                           dtype=torch.float32, device="cuda")
+            B.reslim_asc_forward(m.ctx, plan, cuda(x), y, m.ws)
+            out = y.cpu().numpy()
+        finally:
+            B.reslim_asc_plan_destroy(plan)
+    err = max(O.rel_l2(out[b, c], ref[b, c]) for b in range(cfg.batch) for c in range(cfg.out_vars))
+    say(f"  max rel-L2 over planes {err:.3e}")
+    assert np.isfinite(out).all() and err <= TOL[1]
