@@ -27,12 +27,12 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 # profiles/), keyed by (workload, kernel label); None where not measured.
 # Source: profiles/forward_and_train_block_c1_all_kernels.md (fetched + written, scaled by the copy kernel).
 MEASURED_TRAFFIC = {
-    ("c1", "gemm_fc1"): 153.8e6 + 238.0e6,
+    ("c1", "gemm_fc1"): 147.5e6 + 174.3e6,
     ("c1", "gemm_fc2"): 335.8e6 + 89.5e6,
-    ("c1", "tiles_attention"): 159.8e6 + 43.6e6,
-    ("c1", "gemm_qkv"): 98.3e6 + 146.4e6,
+    ("c1", "tiles_attention"): 160.1e6 + 43.8e6,
+    ("c1", "gemm_qkv"): 98.6e6 + 138.1e6,
     ("c1", "gemm_proj"): 140.6e6 + 90.1e6,
-    ("c1", "layernorm"): 85.7e6 + 42.8e6,
+    ("c1", "layernorm"): 86.0e6 + 42.9e6,
     # profiles/forward_and_train_block_c2_all_kernels.md
     ("c2", "gemm_fc1"): 1994.7e6 + 1484.1e6,
     ("c2", "gemm_fc2"): 2646.8e6 + 695.2e6,
@@ -154,6 +154,8 @@ def main() -> int:
                     help="skip the extra (untimed in `value`) measurement of one block's training forward + backward")
     ap.add_argument("--no-asc", action="store_true",
                     help="skip the extra measurement of the forward with adaptive spatial compression (run for c0 and c1 only)")
+    ap.add_argument("--asc-only", action="store_true",
+                    help="developer runs (profiles): only the compression measurement, printed as its own JSON object")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch the library's plain copy kernel on 1 GiB five times (yardstick for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -178,6 +180,16 @@ def main() -> int:
     if note:
         note("creating the context (weights to bf16, upload)")
     B.reslim_debug_set_gemm_tile(args.gemm_tile)
+    if args.asc_only:
+        if args.copy_probe:
+            a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+            b = torch.empty_like(a)
+            for _ in range(5):
+                B.reslim_debug_copy(a, b)
+            torch.cuda.synchronize()
+            del a, b
+        print(json.dumps(asc_leg(B, torch, np, cfg, w, x_host, args.steps)))
+        return 0
     model = B.Reslim(cfg, w)
     x = torch.from_numpy(x_host).cuda()
     y = torch.empty((cfg.batch, cfg.out_vars, cfg.H * cfg.scale, cfg.W * cfg.scale), dtype=torch.float32, device="cuda")

@@ -390,8 +390,8 @@ int reslim_asc_image(reslim_ctx *ctx, const float *tokens, const float *w_img, c
 
 /* Compression (reading: a leaf's token is the arithmetic mean of its patches'
  * aggregated embeddings, position and resolution terms included).  tokens: dev fp32
- * [batch*N, D] in patch order; tokens_c: dev fp32 [n_leaves, D] out.  fp32 sums in
- * row-major order over the leaf: deterministic. */
+ * [batch*N, D] in patch order; tokens_c: dev fp32 [n_leaves, D] out.  fp32 sums in a
+ * fixed order over the leaf: deterministic. */
 int reslim_asc_compress(reslim_ctx *ctx, const reslim_asc_plan *plan, const float *tokens, float *tokens_c, void *hip_stream);
 
 /* The forward pass with the compression module switched on: embed, compress, every

@@ -22,20 +22,42 @@ struct reslim_asc_plan {
 
 namespace reslim {
 
-// One work-group per leaf: mean over its s x s patch rows, summed in row-major order.
+// One work-group per leaf: mean over its s x s patch rows.  Wave w sums the rows
+// w, w + 4, ... of the leaf (row-major numbering) in increasing order, the four
+// partial sums are added in wave order: a fixed order, so the result is deterministic.
 __global__ __launch_bounds__(256) void asc_compress_kernel(const float *__restrict__ z, const int32_t *__restrict__ leaf,
                                                            float *__restrict__ out, int Wp, int D) {
+  __shared__ float4 part[3][64];
   const int64_t l = blockIdx.x;
   const int first = leaf[4 * l], s = leaf[4 * l + 1];
-  const float inv = 1.0f / static_cast<float>(s * s);
-  for (int d = threadIdx.x * 4; d < D; d += 1024) {
+  const int rows = s * s;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const float inv = 1.0f / static_cast<float>(rows);
+  for (int d0 = 0; d0 < D; d0 += 256) {              // uniform over the work-group
+    const int d = d0 + lane * 4;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int dy = 0; dy < s; ++dy)
-      for (int dx = 0; dx < s; ++dx) {
+    if (d < D) {
+#pragma unroll 4
+      for (int r = wave; r < rows; r += 4) {
+        const int dy = r / s, dx = r - dy * s;
         const float4 v = *reinterpret_cast<const float4 *>(z + (static_cast<size_t>(first) + static_cast<size_t>(dy) * Wp + dx) * D + d);
         acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
       }
-    *reinterpret_cast<float4 *>(out + static_cast<size_t>(l) * D + d) = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
+    }
+    if (rows > 1) {
+      if (wave > 0) part[wave - 1][lane] = acc;
+      __syncthreads();
+      if (wave == 0) {
+#pragma unroll
+        for (int w = 0; w < 3; ++w) {
+          const float4 v = part[w][lane];
+          acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+      }
+      __syncthreads();
+    }
+    if (wave == 0 && d < D)
+      *reinterpret_cast<float4 *>(out + static_cast<size_t>(l) * D + d) = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
   }
 }
 
