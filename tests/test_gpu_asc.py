@@ -186,3 +186,35 @@ def test_compressed_forward_at_the_benchmark_grid():
     err = max(O.rel_l2(out[b, c], ref[b, c]) for b in range(cfg.batch) for c in range(cfg.out_vars))
     say(f"  max rel-L2 over planes {err:.3e}")
     assert np.isfinite(out).all() and err <= TOL[1]
+
+
+@pytest.mark.parametrize("dtype", [0, 1], ids=["f32", "bf16"])
+def test_degenerate_trees(dtype):
+    """One sample whose whole grid is a single leaf (attention over one token) next to
+    one that is split down to single patches, and a uniform tree with min = max."""
+    cfg = WL.ReslimConfig("adeg", batch=2, in_vars=2, out_vars=2, H=32, W=32, scale=2, patch=2,
+                          embed_dim=128, heads=2, mlp_ratio=2, depth=2, tiles_y=1, tiles_x=1,
+                          halo=0, dtype=dtype, seed=31)
+    w = WL.make_weights(cfg, std=0.05)
+    x = WL.make_fields(cfg)
+    r = np.random.default_rng(9)
+    imgs = np.stack([np.full((cfg.H, cfg.W), 1.25, np.float32), r.standard_normal((cfg.H, cfg.W)).astype(np.float32)])
+    for (mx, mn) in ((16, 1), (4, 4)):
+        tab = A.build(imgs, cfg.patch, mx, mn, 0, 0, 0.0)
+        counts = np.diff(tab["sample_off"]).tolist()
+        say(f"asc degenerate {'bf16' if dtype else 'f32'} max {mx} min {mn}: leaves per sample {counts}")
+        if mx == 16:
+            assert counts[0] == 1 and counts[1] > 200
+        ref = A.forward_compressed(x, w, cfg, tab)
+        with B.Reslim(cfg, w) as m:
+            plan = B.reslim_asc_plan_create(m.ctx, cfg.batch, tab)
+            try:
+                y = torch.full((cfg.batch, cfg.out_vars, cfg.H * cfg.scale, cfg.W * cfg.scale), float("nan"),
+                               dtype=torch.float32, device="cuda")
+                B.reslim_asc_forward(m.ctx, plan, cuda(x), y, m.ws)
+                out = y.cpu().numpy()
+            finally:
+                B.reslim_asc_plan_destroy(plan)
+        err = max(O.rel_l2(out[b, c], ref[b, c]) for b in range(cfg.batch) for c in range(cfg.out_vars))
+        say(f"  max rel-L2 over planes {err:.3e}")
+        assert np.isfinite(out).all() and err <= TOL[dtype]
