@@ -84,15 +84,23 @@ __device__ __forceinline__ float epi_act_value(const GemmArgs &g, float v, int n
   return v;
 }
 
+// two floats -> two bf16 in one register (one hardware conversion)
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+  typedef __attribute__((ext_vector_type(2))) float f32x2;
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
+}
+
 // Rows m_first .. m_first + 31, columns n_first .. n_first + 32 NB - 1 (NB = 1 or 2
-// accumulator blocks side by side) of a bf16 output.  Staging layout: row r at
-// 128 r bytes, its 16-byte chunk c at position c ^ ((r >> 1) & 7), and the two
-// 8-byte halves of a chunk exchanged where r >= 16: with that the 8-byte writes of
-// 32 lanes (32 rows, one column quad) and the 16-byte reads of 16 lanes (two rows)
-// each touch every bank once.
+// accumulator blocks side by side) of a bf16 output; bias[jj][q] holds the four
+// bias values of this lane's column quad.  Staging layout: row r at 128 r bytes, its
+// 16-byte chunk c at position c ^ ((r >> 1) & 7), and the two 8-byte halves of a
+// chunk exchanged where r >= 16: with that the 8-byte writes of 32 lanes (32 rows,
+// one column quad) and the 16-byte reads of 16 lanes (two rows) each touch every
+// bank once.  N is a multiple of 8, so a 16-byte piece is inside the row or not at all.
 template <int EPI, bool SECOND, int NB>
-__device__ __forceinline__ void epilogue_act_stage(const GemmArgs &g, const f32x16 *blk, int m_first, int n_first,
-                                                   int lane, unsigned char *stg) {
+__device__ __forceinline__ void epilogue_act_stage(const GemmArgs &g, const f32x16 *blk, const float4 (*bias)[4],
+                                                   int m_first, int n_first, int lane, unsigned char *stg) {
   const int l32 = lane & 31, hi = lane >> 5;
   bf16_t *out = static_cast<bf16_t *>(SECOND ? g.out2 : g.out);
   unsigned char *wrow = stg + l32 * 128 + ((hi ^ (l32 >> 4)) << 3);
@@ -102,63 +110,59 @@ __device__ __forceinline__ void epilogue_act_stage(const GemmArgs &g, const f32x
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int n = n_first + jj * 32 + 8 * q + 4 * hi;
-      float4 b = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (n + 3 < g.N) {
-        b = *reinterpret_cast<const float4 *>(g.bias + n);
-      } else {
-        if (n < g.N) b.x = g.bias[n];
-        if (n + 1 < g.N) b.y = g.bias[n + 1];
-        if (n + 2 < g.N) b.z = g.bias[n + 2];
-      }
+      const float4 b = bias[jj][q];
       u32x2 pk;
-      pk[0] = pack_bf16x2(epi_act_value<EPI, SECOND>(g, blk[jj][4 * q] + b.x, n),
-                          epi_act_value<EPI, SECOND>(g, blk[jj][4 * q + 1] + b.y, n + 1));
-      pk[1] = pack_bf16x2(epi_act_value<EPI, SECOND>(g, blk[jj][4 * q + 2] + b.z, n + 2),
-                          epi_act_value<EPI, SECOND>(g, blk[jj][4 * q + 3] + b.w, n + 3));
+      pk[0] = pack2(epi_act_value<EPI, SECOND>(g, blk[jj][4 * q] + b.x, n),
+                    epi_act_value<EPI, SECOND>(g, blk[jj][4 * q + 1] + b.y, n + 1));
+      pk[1] = pack2(epi_act_value<EPI, SECOND>(g, blk[jj][4 * q + 2] + b.z, n + 2),
+                    epi_act_value<EPI, SECOND>(g, blk[jj][4 * q + 3] + b.w, n + 3));
       *reinterpret_cast<u32x2 *>(wrow + (((jj * 4 + q) ^ wsw) << 4)) = pk;
     }
   }
   // read back row-major: 8 lanes per row (NB = 2) or 4 lanes per row (NB = 1)
   constexpr int LPR = 4 * NB, RPI = 64 / LPR;      // lanes per row, rows per instruction
   const int c = lane % LPR, rr = lane / LPR;
+  const int n = n_first + c * 8;
 #pragma unroll
   for (int it = 0; it < 32 / RPI; ++it) {
     const int r = it * RPI + rr;
     u32x4 v = *reinterpret_cast<const u32x4 *>(stg + r * 128 + ((c ^ ((r >> 1) & 7)) << 4));
     if (it * RPI >= 16) v = u32x4{v[2], v[3], v[0], v[1]};
-    const int m = m_first + r, n = n_first + c * 8;
-    if (m >= g.M) continue;
-    bf16_t *o = out + static_cast<size_t>(m) * g.ldo + n;
-    if (n + 7 < g.N) {
-      *reinterpret_cast<u32x4 *>(o) = v;
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e)
-        if (n + e < g.N) o[e] = static_cast<bf16_t>(v[e >> 1] >> ((e & 1) * 16));
-    }
+    const int m = m_first + r;
+    if (m < g.M && n < g.N) *reinterpret_cast<u32x4 *>(out + static_cast<size_t>(m) * g.ldo + n) = v;
   }
-  __builtin_amdgcn_sched_barrier(0);   // keeps the next block's bias loads and arithmetic from being hoisted over this one (registers)
+  __builtin_amdgcn_sched_barrier(0);   // keeps the next block's arithmetic from being hoisted over this one (registers)
 }
 
 // Only the leading MIe x NIe blocks of acc are written (a wave working on part of a
 // tile fills just those).  stg: this wave's kEpiStageBytes of LDS (bf16 outputs).
+// N is a multiple of 8 (checked at launch): column quads are whole or absent.
 template <int EPI, int MI, int NI, int MIe = MI, int NIe = NI>
 __device__ __forceinline__ void epilogue_wave(const GemmArgs &g, const f32x16 (&acc)[MI][NI], int m_base, int n_base,
                                               int lane, unsigned char *stg) {
   const int l32 = lane & 31, hi = lane >> 5;
+  // the bias of this lane's column quads, fetched once (columns past N: any valid address, never stored)
+  float4 bias[NIe][4];
+  if constexpr (EPI != EPI_BIAS_TAB_F32) {
+#pragma unroll
+    for (int j = 0; j < NIe; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        bias[j][q] = *reinterpret_cast<const float4 *>(g.bias + min(n_base + j * 32 + 8 * q + 4 * hi, g.N - 4));
+  }
   if constexpr (epi_act_out<EPI>()) {
 #pragma unroll
     for (int i = 0; i < MIe; ++i) {
 #pragma unroll
       for (int j = 0; j + 1 < NIe; j += 2) {
-        epilogue_act_stage<EPI, false, 2>(g, &acc[i][j], m_base + i * 32, n_base + j * 32, lane, stg);
+        epilogue_act_stage<EPI, false, 2>(g, &acc[i][j], &bias[j], m_base + i * 32, n_base + j * 32, lane, stg);
         if constexpr (EPI == EPI_BIAS_ACT_GELU2)
-          epilogue_act_stage<EPI, true, 2>(g, &acc[i][j], m_base + i * 32, n_base + j * 32, lane, stg);
+          epilogue_act_stage<EPI, true, 2>(g, &acc[i][j], &bias[j], m_base + i * 32, n_base + j * 32, lane, stg);
       }
       if constexpr (NIe % 2 == 1) {
-        epilogue_act_stage<EPI, false, 1>(g, &acc[i][NIe - 1], m_base + i * 32, n_base + (NIe - 1) * 32, lane, stg);
+        epilogue_act_stage<EPI, false, 1>(g, &acc[i][NIe - 1], &bias[NIe - 1], m_base + i * 32, n_base + (NIe - 1) * 32, lane, stg);
         if constexpr (EPI == EPI_BIAS_ACT_GELU2)
-          epilogue_act_stage<EPI, true, 1>(g, &acc[i][NIe - 1], m_base + i * 32, n_base + (NIe - 1) * 32, lane, stg);
+          epilogue_act_stage<EPI, true, 1>(g, &acc[i][NIe - 1], &bias[NIe - 1], m_base + i * 32, n_base + (NIe - 1) * 32, lane, stg);
       }
     }
     return;
@@ -168,36 +172,26 @@ __device__ __forceinline__ void epilogue_wave(const GemmArgs &g, const f32x16 (&
     const int m = m_base + i * 32 + l32;
     if (m >= g.M) continue;
     const size_t row = static_cast<size_t>(m) * g.ldo;
-    {
-      float *orow = static_cast<float *>(g.out) + row;
-      // row the skip connection is read from: the output itself (in place) or another buffer
-      const float *rrow = (EPI == EPI_BIAS_RES_F32) ? static_cast<const float *>(g.aux) + row : orow;
-      const float *trow = (EPI == EPI_BIAS_TAB_F32) ? g.tab + static_cast<size_t>(m % g.tab_rows) * g.N : nullptr;
+    float *orow = static_cast<float *>(g.out) + row;
+    // row the skip connection is read from: the output itself (in place) or another buffer
+    const float *rrow = (EPI == EPI_BIAS_RES_F32) ? static_cast<const float *>(g.aux) + row : orow;
+    const float *trow = (EPI == EPI_BIAS_TAB_F32) ? g.tab + static_cast<size_t>(m % g.tab_rows) * g.N : nullptr;
 #pragma unroll
-      for (int j = 0; j < NIe; ++j) {
+    for (int j = 0; j < NIe; ++j) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int n = n_base + j * 32 + 8 * q + 4 * hi;
-          if (n + 3 < g.N) {
-            const float4 add = (EPI == EPI_BIAS_TAB_F32) ? *reinterpret_cast<const float4 *>(trow + n)
-                                                         : *reinterpret_cast<const float4 *>(g.bias + n);
-            float4 v = make_float4(acc[i][j][4 * q] + add.x, acc[i][j][4 * q + 1] + add.y, acc[i][j][4 * q + 2] + add.z,
-                                   acc[i][j][4 * q + 3] + add.w);
-            if constexpr (EPI == EPI_BIAS_RESADD_F32 || EPI == EPI_BIAS_RES_F32) {
-              const float4 x = *reinterpret_cast<const float4 *>(rrow + n);
-              v.x += x.x; v.y += x.y; v.z += x.z; v.w += x.w;
-            }
-            *reinterpret_cast<float4 *>(orow + n) = v;
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (n + e < g.N) {
-                const float add = (EPI == EPI_BIAS_TAB_F32) ? trow[n + e] : g.bias[n + e];
-                float v = acc[i][j][4 * q + e] + add;
-                if constexpr (EPI == EPI_BIAS_RESADD_F32 || EPI == EPI_BIAS_RES_F32) v += rrow[n + e];
-                orow[n + e] = v;
-              }
+      for (int q = 0; q < 4; ++q) {
+        const int n = n_base + j * 32 + 8 * q + 4 * hi;
+        if (n < g.N) {
+          float4 add;
+          if constexpr (EPI == EPI_BIAS_TAB_F32) add = *reinterpret_cast<const float4 *>(trow + n);
+          else add = bias[j][q];
+          float4 v = make_float4(acc[i][j][4 * q] + add.x, acc[i][j][4 * q + 1] + add.y, acc[i][j][4 * q + 2] + add.z,
+                                 acc[i][j][4 * q + 3] + add.w);
+          if constexpr (EPI == EPI_BIAS_RESADD_F32 || EPI == EPI_BIAS_RES_F32) {
+            const float4 x = *reinterpret_cast<const float4 *>(rrow + n);
+            v.x += x.x; v.y += x.y; v.z += x.z; v.w += x.w;
           }
+          *reinterpret_cast<float4 *>(orow + n) = v;
         }
       }
     }
@@ -522,7 +516,7 @@ hipError_t launch_gemm(int dtype, Epilogue epi, const void *A, const void *W, co
   if (epi == EPI_BIAS_ACT_GELU2 && !out2) return hipErrorInvalidValue;
   if (dtype == RESLIM_BF16) {
     if (K % 64 != 0) return hipErrorInvalidValue;   // slabs are 64 deep; create() enforces D % 64 == 0
-    if (ldo % 8 != 0) return hipErrorInvalidValue;  // epilogues store 16 bytes of a row at once
+    if (ldo % 8 != 0 || N % 8 != 0) return hipErrorInvalidValue;  // epilogues move 16 bytes of a row at once
     switch (epi) {
       case EPI_BIAS_ACT: return launch_bf16<EPI_BIAS_ACT>(g, st);
       case EPI_BIAS_GELU_ACT: return launch_bf16<EPI_BIAS_GELU_ACT>(g, st);
