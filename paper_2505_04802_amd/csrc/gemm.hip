@@ -98,7 +98,7 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
 // chunk exchanged where r >= 16: with that the 8-byte writes of 32 lanes (32 rows,
 // one column quad) and the 16-byte reads of 16 lanes (two rows) each touch every
 // bank once.  N is a multiple of 8, so a 16-byte piece is inside the row or not at all.
-template <int EPI, bool SECOND, int NB>
+template <int EPI, bool SECOND, bool GUARD, int NB>
 __device__ __forceinline__ void epilogue_act_stage(const GemmArgs &g, const f32x16 *blk, const float4 (*bias)[4],
                                                    int m_first, int n_first, int lane, unsigned char *stg) {
   const int l32 = lane & 31, hi = lane >> 5;
@@ -129,73 +129,94 @@ __device__ __forceinline__ void epilogue_act_stage(const GemmArgs &g, const f32x
     u32x4 v = *reinterpret_cast<const u32x4 *>(stg + r * 128 + ((c ^ ((r >> 1) & 7)) << 4));
     if (it * RPI >= 16) v = u32x4{v[2], v[3], v[0], v[1]};
     const int m = m_first + r;
-    if (m < g.M && n < g.N) *reinterpret_cast<u32x4 *>(out + static_cast<size_t>(m) * g.ldo + n) = v;
+    if (!GUARD || (m < g.M && n < g.N)) *reinterpret_cast<u32x4 *>(out + static_cast<size_t>(m) * g.ldo + n) = v;
   }
   __builtin_amdgcn_sched_barrier(0);   // keeps the next block's arithmetic from being hoisted over this one (registers)
 }
 
-// Only the leading MIe x NIe blocks of acc are written (a wave working on part of a
-// tile fills just those).  stg: this wave's kEpiStageBytes of LDS (bf16 outputs).
-// N is a multiple of 8 (checked at launch): column quads are whole or absent.
-template <int EPI, int MI, int NI, int MIe = MI, int NIe = NI>
-__device__ __forceinline__ void epilogue_wave(const GemmArgs &g, const f32x16 (&acc)[MI][NI], int m_base, int n_base,
-                                              int lane, unsigned char *stg) {
+// GUARD = false: the wave's part of the tile lies inside the output (the common
+// case, decided per wave): no bounds test anywhere.  GUARD = true: rows past M and
+// column quads past N compute on clamped (valid) addresses and skip only the store.
+// Column blocks are taken two at a time; the bias of the lane's eight column quads is
+// fetched once per pair.  N is a multiple of 8: quads are whole or absent.
+template <int EPI, bool GUARD, int MI, int NI, int MIe, int NIe>
+__device__ __forceinline__ void epilogue_wave_impl(const GemmArgs &g, const f32x16 (&acc)[MI][NI], int m_base, int n_base,
+                                                   int lane, unsigned char *stg) {
   const int l32 = lane & 31, hi = lane >> 5;
-  // the bias of this lane's column quads, fetched once (columns past N: any valid address, never stored)
-  float4 bias[NIe][4];
-  if constexpr (EPI != EPI_BIAS_TAB_F32) {
 #pragma unroll
-    for (int j = 0; j < NIe; ++j)
+  for (int j0 = 0; j0 < NIe; j0 += 2) {
+    const int JN = (NIe - j0) < 2 ? (NIe - j0) : 2;      // folds: j0 is a compile-time value after unrolling
+    float4 bias[2][4];
+    if constexpr (EPI != EPI_BIAS_TAB_F32) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
-        bias[j][q] = *reinterpret_cast<const float4 *>(g.bias + min(n_base + j * 32 + 8 * q + 4 * hi, g.N - 4));
-  }
-  if constexpr (epi_act_out<EPI>()) {
+      for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
-    for (int i = 0; i < MIe; ++i) {
-#pragma unroll
-      for (int j = 0; j + 1 < NIe; j += 2) {
-        epilogue_act_stage<EPI, false, 2>(g, &acc[i][j], &bias[j], m_base + i * 32, n_base + j * 32, lane, stg);
-        if constexpr (EPI == EPI_BIAS_ACT_GELU2)
-          epilogue_act_stage<EPI, true, 2>(g, &acc[i][j], &bias[j], m_base + i * 32, n_base + j * 32, lane, stg);
-      }
-      if constexpr (NIe % 2 == 1) {
-        epilogue_act_stage<EPI, false, 1>(g, &acc[i][NIe - 1], &bias[NIe - 1], m_base + i * 32, n_base + (NIe - 1) * 32, lane, stg);
-        if constexpr (EPI == EPI_BIAS_ACT_GELU2)
-          epilogue_act_stage<EPI, true, 1>(g, &acc[i][NIe - 1], &bias[NIe - 1], m_base + i * 32, n_base + (NIe - 1) * 32, lane, stg);
-      }
+        for (int q = 0; q < 4; ++q) {
+          const int n = n_base + (j0 + jj) * 32 + 8 * q + 4 * hi;
+          if (jj < JN) bias[jj][q] = *reinterpret_cast<const float4 *>(g.bias + (GUARD ? min(n, g.N - 4) : n));
+        }
     }
-    return;
-  }
+    if constexpr (epi_act_out<EPI>()) {
 #pragma unroll
-  for (int i = 0; i < MIe; ++i) {
-    const int m = m_base + i * 32 + l32;
-    if (m >= g.M) continue;
-    const size_t row = static_cast<size_t>(m) * g.ldo;
-    float *orow = static_cast<float *>(g.out) + row;
-    // row the skip connection is read from: the output itself (in place) or another buffer
-    const float *rrow = (EPI == EPI_BIAS_RES_F32) ? static_cast<const float *>(g.aux) + row : orow;
-    const float *trow = (EPI == EPI_BIAS_TAB_F32) ? g.tab + static_cast<size_t>(m % g.tab_rows) * g.N : nullptr;
+      for (int i = 0; i < MIe; ++i) {
+        if (JN == 2) {
+          epilogue_act_stage<EPI, false, GUARD, 2>(g, &acc[i][j0], bias, m_base + i * 32, n_base + j0 * 32, lane, stg);
+          if constexpr (EPI == EPI_BIAS_ACT_GELU2)
+            epilogue_act_stage<EPI, true, GUARD, 2>(g, &acc[i][j0], bias, m_base + i * 32, n_base + j0 * 32, lane, stg);
+        } else {
+          epilogue_act_stage<EPI, false, GUARD, 1>(g, &acc[i][j0], bias, m_base + i * 32, n_base + j0 * 32, lane, stg);
+          if constexpr (EPI == EPI_BIAS_ACT_GELU2)
+            epilogue_act_stage<EPI, true, GUARD, 1>(g, &acc[i][j0], bias, m_base + i * 32, n_base + j0 * 32, lane, stg);
+        }
+      }
+    } else {
 #pragma unroll
-    for (int j = 0; j < NIe; ++j) {
+      for (int i = 0; i < MIe; ++i) {
+        const int m = m_base + i * 32 + l32;
+        const bool row_ok = !GUARD || m < g.M;
+        const int mc = GUARD ? min(m, g.M - 1) : m;
+        const size_t row = static_cast<size_t>(mc) * g.ldo;
+        float *orow = static_cast<float *>(g.out) + row;
+        // row the skip connection is read from: the output itself (in place) or another buffer
+        const float *rrow = (EPI == EPI_BIAS_RES_F32) ? static_cast<const float *>(g.aux) + row : orow;
+        const float *trow = (EPI == EPI_BIAS_TAB_F32) ? g.tab + static_cast<size_t>(mc % g.tab_rows) * g.N : nullptr;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int n = n_base + j * 32 + 8 * q + 4 * hi;
-        if (n < g.N) {
-          float4 add;
-          if constexpr (EPI == EPI_BIAS_TAB_F32) add = *reinterpret_cast<const float4 *>(trow + n);
-          else add = bias[j][q];
-          float4 v = make_float4(acc[i][j][4 * q] + add.x, acc[i][j][4 * q + 1] + add.y, acc[i][j][4 * q + 2] + add.z,
-                                 acc[i][j][4 * q + 3] + add.w);
-          if constexpr (EPI == EPI_BIAS_RESADD_F32 || EPI == EPI_BIAS_RES_F32) {
-            const float4 x = *reinterpret_cast<const float4 *>(rrow + n);
-            v.x += x.x; v.y += x.y; v.z += x.z; v.w += x.w;
+        for (int jj = 0; jj < 2; ++jj) {
+          if (jj >= JN) continue;
+          float4 v[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int n = n_base + (j0 + jj) * 32 + 8 * q + 4 * hi;
+            const int nc = GUARD ? min(n, g.N - 4) : n;
+            float4 add;
+            if constexpr (EPI == EPI_BIAS_TAB_F32) add = *reinterpret_cast<const float4 *>(trow + nc);
+            else add = bias[jj][q];
+            const f32x16 &a = acc[i][j0 + jj];
+            v[q] = make_float4(a[4 * q] + add.x, a[4 * q + 1] + add.y, a[4 * q + 2] + add.z, a[4 * q + 3] + add.w);
+            if constexpr (EPI == EPI_BIAS_RESADD_F32 || EPI == EPI_BIAS_RES_F32) {
+              const float4 x = *reinterpret_cast<const float4 *>(rrow + nc);
+              v[q].x += x.x; v[q].y += x.y; v[q].z += x.z; v[q].w += x.w;
+            }
           }
-          *reinterpret_cast<float4 *>(orow + n) = v;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int n = n_base + (j0 + jj) * 32 + 8 * q + 4 * hi;
+            if (row_ok && (!GUARD || n < g.N)) *reinterpret_cast<float4 *>(orow + n) = v[q];
+          }
         }
       }
     }
   }
+}
+
+// Only the leading MIe x NIe blocks of acc are written (a wave working on part of a
+// tile fills just those).  stg: this wave's kEpiStageBytes of LDS (bf16 outputs).
+template <int EPI, int MI, int NI, int MIe = MI, int NIe = NI>
+__device__ __forceinline__ void epilogue_wave(const GemmArgs &g, const f32x16 (&acc)[MI][NI], int m_base, int n_base,
+                                              int lane, unsigned char *stg) {
+  const bool inside = m_base + MIe * 32 <= g.M && n_base + NIe * 32 <= g.N;     // wave-uniform
+  if (inside) epilogue_wave_impl<EPI, false, MI, NI, MIe, NIe>(g, acc, m_base, n_base, lane, stg);
+  else epilogue_wave_impl<EPI, true, MI, NI, MIe, NIe>(g, acc, m_base, n_base, lane, stg);
 }
 
 // tile id seen by the hardware dispatcher -> tile id in XCD-contiguous order
