@@ -27,18 +27,17 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 # profiles/), keyed by (workload, kernel label); None where not measured.
 # Source: profiles/forward_and_train_block_c1_all_kernels.md (fetched + written, scaled by the copy kernel).
 MEASURED_TRAFFIC = {
-    ("c1", "gemm_fc1"): 147.5e6 + 174.3e6,
+    ("c1", "gemm_fc1"): 146.9e6 + 174.3e6,
     ("c1", "gemm_fc2"): 335.8e6 + 89.5e6,
     ("c1", "tiles_attention"): 160.1e6 + 43.8e6,
-    ("c1", "gemm_qkv"): 98.6e6 + 138.1e6,
+    ("c1", "gemm_qkv"): 98.2e6 + 130.7e6,
     ("c1", "gemm_proj"): 140.6e6 + 90.1e6,
     ("c1", "layernorm"): 86.0e6 + 42.9e6,
     # profiles/forward_and_train_block_c2_all_kernels.md
-    ("c2", "gemm_fc1"): 1994.7e6 + 1484.1e6,
+    ("c2", "gemm_fc1"): 1993.6e6 + 1322.3e6,
     ("c2", "gemm_fc2"): 2646.8e6 + 695.2e6,
-    ("c2", "gemm_qkv"): 1516.1e6 + 1132.0e6,
-    ("c2", "tiles_attention"): 1928.6e6 + 332.0e6,
-    ("c2", "gemm_proj"): 1614.2e6 + 829.6e6,
+    ("c2", "gemm_qkv"): 1493.6e6 + 991.7e6,
+    ("c2", "tiles_attention"): 1941.6e6 + 332.0e6,
     ("c2", "layernorm"): 656.7e6 + 328.2e6,
 }
 
