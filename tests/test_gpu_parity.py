@@ -283,3 +283,36 @@ def test_edge_cases_and_errors():
             e = O.rel_l2(m.forward(cuda(x2)).cpu().numpy(), ref)
         say(f"  edge {kw}: rel-L2 {e:.3e}")
         assert e <= 2e-2
+
+
+def test_forward_is_capturable_in_a_hip_graph():
+    """reslim_forward only enqueues kernels on the caller's stream (no allocation, no
+    memset, no synchronisation), so a caller may record it into a HIP graph.  Every
+    replay, with new inputs in the captured buffers and eager work in between, must
+    reproduce the eager result bit for bit."""
+    cfg = SMALL_BF16
+    w = weights_for(cfg)
+    r = np.random.default_rng(5)
+    xs = [WL.make_fields(cfg)] + [r.standard_normal((cfg.batch, cfg.in_vars, cfg.H, cfg.W)).astype(np.float32) for _ in range(2)]
+    with B.Reslim(cfg, w) as m:
+        x = cuda(xs[0], torch.float32)
+        y = torch.empty((cfg.batch, cfg.out_vars, cfg.H * cfg.scale, cfg.W * cfg.scale), dtype=torch.float32, device="cuda")
+        B.reslim_forward(m.ctx, x, y, cfg.batch, m.ws)                 # warm-up outside the capture
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            B.reslim_forward(m.ctx, x, y, cfg.batch, m.ws)
+        torch.cuda.synchronize()
+        for i, xi in enumerate(xs + xs[:1]):
+            say(f"graph replay {i}")
+            x.copy_(cuda(xi, torch.float32))
+            y.fill_(float("nan"))
+            g.replay()
+            torch.cuda.synchronize()
+            got = y.clone()
+            B.reslim_forward(m.ctx, x, y, cfg.batch, m.ws)             # the program's own eager work between replays
+            torch.cuda.synchronize()
+            assert torch.isfinite(got).all() and torch.equal(got, y)
+        assert O.rel_l2(y.cpu().numpy(), O.reslim_forward(xs[0], w, cfg)) <= TOL[1]
