@@ -394,6 +394,28 @@ int reslim_asc_image(reslim_ctx *ctx, const float *tokens, const float *w_img, c
  * fixed order over the leaf: deterministic. */
 int reslim_asc_compress(reslim_ctx *ctx, const reslim_asc_plan *plan, const float *tokens, float *tokens_c, void *hip_stream);
 
+/* Decompression on its own (each patch takes its leaf's row: tokens_c dev fp32
+ * [n_leaves, D] -> tokens dev fp32 [batch*N, D]) and the gradients of the two linear
+ * maps: reslim_asc_compress_bwd gives every patch its leaf's gradient divided by the
+ * leaf's patch count (d_tokens_c [n_leaves, D] -> d_tokens [batch*N, D]);
+ * reslim_asc_decompress_bwd adds up the gradients of a leaf's patches (d_tokens
+ * [batch*N, D] -> d_tokens_c [n_leaves, D], fixed summation order).  All dev fp32. */
+int reslim_asc_decompress(reslim_ctx *ctx, const reslim_asc_plan *plan, const float *tokens_c, float *tokens, void *hip_stream);
+int reslim_asc_compress_bwd(reslim_ctx *ctx, const reslim_asc_plan *plan, const float *d_tokens_c, float *d_tokens, void *hip_stream);
+int reslim_asc_decompress_bwd(reslim_ctx *ctx, const reslim_asc_plan *plan, const float *d_tokens, float *d_tokens_c, void *hip_stream);
+
+/* Training of a block on the leaves (the paper's Table 2(b) quotes TRAINING time per
+ * sample with compression): reslim_block_fwd_train / reslim_block_bwd with the rows
+ * x [n_leaves, D] of a compressed batch and attention among the leaves of one sample.
+ * Arguments, saved-tensor and workspace rules, precision and errors as for those two
+ * calls; sizes from reslim_asc_block_train_bytes; reslim_train_prepare first. */
+int reslim_asc_block_train_bytes(const reslim_ctx *ctx, const reslim_asc_plan *plan, size_t *saved_bytes, size_t *ws_bytes);
+int reslim_asc_block_fwd_train(reslim_ctx *ctx, const reslim_asc_plan *plan, int32_t layer, const float *x_in, float *x_out,
+                               void *saved, size_t saved_bytes, void *workspace, size_t ws_bytes, void *hip_stream);
+int reslim_asc_block_bwd(reslim_ctx *ctx, const reslim_asc_plan *plan, int32_t layer, const float *x_in, const void *saved,
+                         size_t saved_bytes, const float *d_x_out, float *d_x_in, const reslim_block_grads *grads,
+                         void *workspace, size_t ws_bytes, void *hip_stream);
+
 /* The forward pass with the compression module switched on: embed, compress, every
  * block on the leaves (attention among the leaves of one sample), decompress (each
  * patch takes its leaf's token), final LayerNorm, head, un-patchify + residual path.

@@ -242,3 +242,48 @@ def forward_compressed(x, w, cfg, table):
     for b in range(B):
         y[b] += ro.residual_path(x[b], w, s)
     return y
+
+
+# ---------------------------------------------------------------------------
+# Training side: gradients of the two linear maps and of a block on the leaves
+# (chain rule; Table 2(b) of the paper times training with compression)
+# ---------------------------------------------------------------------------
+def compress_bwd(dZc, table, B: int, N: int):
+    """Gradient of `compress`: the mean over a leaf hands 1/(s*s) of the leaf's
+    gradient to each of its patches.  dZc[L, D] -> [B, N, D]."""
+    dZc = np.asarray(dZc, F64)
+    s2 = (np.asarray(table["leaf_s"], F64) ** 2)[:, None]
+    return (dZc / s2)[np.asarray(table["patch_leaf"]).reshape(B, N)]
+
+
+def decompress_bwd(dZ, table):
+    """Gradient of `decompress`: a leaf collects the gradients of all patches that
+    copied it.  dZ[B, N, D] -> [L, D]."""
+    dZ = np.asarray(dZ, F64)
+    out = np.zeros((len(table["leaf_s"]), dZ.shape[2]), F64)
+    np.add.at(out, np.asarray(table["patch_leaf"]).reshape(-1), dZ.reshape(-1, dZ.shape[2]))
+    return out
+
+
+def block_compressed(Xc, table, w, layer: int, heads: int):
+    """One ViT block on the leaves; attention stays inside a sample."""
+    Xc = np.asarray(Xc, F64)
+    out = np.empty_like(Xc)
+    off = table["sample_off"]
+    for b in range(len(off) - 1):
+        out[off[b]:off[b + 1]] = ro.block_tokens(Xc[off[b]:off[b + 1]], w, layer, heads)
+    return out
+
+
+def block_compressed_bwd(Xc, table, w, layer: int, heads: int, d_out):
+    """Gradient of `block_compressed`: (d_Xc, parameter gradients summed over samples)."""
+    Xc = np.asarray(Xc, F64)
+    d_out = np.asarray(d_out, F64)
+    dX = np.empty_like(Xc)
+    grads = None
+    off = table["sample_off"]
+    for b in range(len(off) - 1):
+        dx, g = ro.block_tokens_bwd(Xc[off[b]:off[b + 1]], w, layer, heads, d_out[off[b]:off[b + 1]])
+        dX[off[b]:off[b + 1]] = dx
+        grads = g if grads is None else {k: grads[k] + g[k] for k in g}
+    return dX, grads

@@ -36,7 +36,9 @@ EXPORTS = ["tiles_partition", "reslim_create", "reslim_destroy", "reslim_last_er
            "reslim_block_train_bytes", "reslim_block_fwd_train", "reslim_block_bwd",
            "reslim_block_grads_unscale", "reslim_grad_scale_update",
            "reslim_asc_build", "reslim_asc_edges", "reslim_asc_plan_create", "reslim_asc_plan_destroy",
-           "reslim_asc_plan_info", "reslim_asc_image", "reslim_asc_compress", "reslim_asc_forward"]
+           "reslim_asc_plan_info", "reslim_asc_image", "reslim_asc_compress", "reslim_asc_forward",
+           "reslim_asc_decompress", "reslim_asc_compress_bwd", "reslim_asc_decompress_bwd",
+           "reslim_asc_block_train_bytes", "reslim_asc_block_fwd_train", "reslim_asc_block_bwd"]
 
 
 class ReslimConfigC(C.Structure):
@@ -126,6 +128,11 @@ def load() -> C.CDLL:
     lib.reslim_asc_image.argtypes = [vp, vp, vp, vp, vp, i32, vp]
     lib.reslim_asc_compress.argtypes = [vp, vp, vp, vp, vp]
     lib.reslim_asc_forward.argtypes = [vp, vp, vp, vp, vp, C.c_size_t, vp]
+    for nm in ("reslim_asc_decompress", "reslim_asc_compress_bwd", "reslim_asc_decompress_bwd"):
+        getattr(lib, nm).argtypes = [vp, vp, vp, vp, vp]
+    lib.reslim_asc_block_train_bytes.argtypes = [vp, vp, szp, szp]
+    lib.reslim_asc_block_fwd_train.argtypes = [vp, vp, i32, vp, vp, vp, C.c_size_t, vp, C.c_size_t, vp]
+    lib.reslim_asc_block_bwd.argtypes = [vp, vp, i32, vp, vp, C.c_size_t, vp, vp, C.POINTER(BlockGradsC), vp, C.c_size_t, vp]
     lib.reslim_debug_set_gemm_tile.argtypes = [i32]
     lib.reslim_debug_set_gemm_tile.restype = None
     lib.reslim_debug_set_attention_variant.argtypes = [i32]
@@ -406,6 +413,36 @@ def reslim_asc_compress(ctx, plan, tokens, tokens_c, stream=None):
 def reslim_asc_forward(ctx, plan, x, y, workspace, stream=None):
     _check(load().reslim_asc_forward(ctx, plan, x.data_ptr(), y.data_ptr(), workspace.data_ptr(),
                                      workspace.numel() * workspace.element_size(), _stream_ptr(stream)), ctx)
+
+
+def reslim_asc_decompress(ctx, plan, tokens_c, tokens, stream=None):
+    _check(load().reslim_asc_decompress(ctx, plan, tokens_c.data_ptr(), tokens.data_ptr(), _stream_ptr(stream)), ctx)
+
+
+def reslim_asc_compress_bwd(ctx, plan, d_tokens_c, d_tokens, stream=None):
+    _check(load().reslim_asc_compress_bwd(ctx, plan, d_tokens_c.data_ptr(), d_tokens.data_ptr(), _stream_ptr(stream)), ctx)
+
+
+def reslim_asc_decompress_bwd(ctx, plan, d_tokens, d_tokens_c, stream=None):
+    _check(load().reslim_asc_decompress_bwd(ctx, plan, d_tokens.data_ptr(), d_tokens_c.data_ptr(), _stream_ptr(stream)), ctx)
+
+
+def reslim_asc_block_train_bytes(ctx, plan):
+    a, b = C.c_size_t(0), C.c_size_t(0)
+    _check(load().reslim_asc_block_train_bytes(ctx, plan, C.byref(a), C.byref(b)), ctx)
+    return int(a.value), int(b.value)
+
+
+def reslim_asc_block_fwd_train(ctx, plan, layer, x_in, x_out, saved, workspace, stream=None):
+    _check(load().reslim_asc_block_fwd_train(ctx, plan, layer, x_in.data_ptr(), x_out.data_ptr(), saved.data_ptr(),
+                                             _nbytes(saved), workspace.data_ptr(), _nbytes(workspace), _stream_ptr(stream)), ctx)
+
+
+def reslim_asc_block_bwd(ctx, plan, layer, x_in, saved, d_x_out, d_x_in, grads, workspace, stream=None):
+    g = BlockGradsC(**{n: grads[n].data_ptr() for n in BLOCK_PARAMS})
+    _check(load().reslim_asc_block_bwd(ctx, plan, layer, x_in.data_ptr(), saved.data_ptr(), _nbytes(saved),
+                                       d_x_out.data_ptr(), d_x_in.data_ptr(), C.byref(g), workspace.data_ptr(),
+                                       _nbytes(workspace), _stream_ptr(stream)), ctx)
 
 
 # ------------------------------------------------------------------ convenience holder

@@ -8,23 +8,12 @@
 
 #include "common.h"
 
-struct reslim_asc_plan {
-  reslim_ctx *ctx = nullptr;
-  int batch = 0;
-  int64_t L = 0;                         // leaves of the whole batch
-  std::vector<tile_desc> seq;            // one entry per sample: tok_off, n_tok
-  reslim::SeqGeom geom{};
-  tile_desc *d_seq = nullptr;            // [batch]
-  int32_t *d_seq_of_leaf = nullptr;      // [L]
-  int32_t *d_leaf = nullptr;             // [L][4]: first patch row (b*N + y0*Wp + x0), side, unused, unused
-  int32_t *d_patch_leaf = nullptr;       // [batch * N]
-};
-
 namespace reslim {
 
 // One work-group per leaf: mean over its s x s patch rows.  Wave w sums the rows
 // w, w + 4, ... of the leaf (row-major numbering) in increasing order, the four
 // partial sums are added in wave order: a fixed order, so the result is deterministic.
+template <bool MEAN>   // false: plain sums (the gradient of decompression)
 __global__ __launch_bounds__(256) void asc_compress_kernel(const float *__restrict__ z, const int32_t *__restrict__ leaf,
                                                            float *__restrict__ out, int Wp, int D) {
   __shared__ float4 part[3][64];
@@ -32,7 +21,7 @@ __global__ __launch_bounds__(256) void asc_compress_kernel(const float *__restri
   const int first = leaf[4 * l], s = leaf[4 * l + 1];
   const int rows = s * s;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const float inv = 1.0f / static_cast<float>(rows);
+  const float inv = MEAN ? 1.0f / static_cast<float>(rows) : 1.0f;
   for (int d0 = 0; d0 < D; d0 += 256) {              // uniform over the work-group
     const int d = d0 + lane * 4;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -58,6 +47,29 @@ __global__ __launch_bounds__(256) void asc_compress_kernel(const float *__restri
     }
     if (wave == 0 && d < D)
       *reinterpret_cast<float4 *>(out + static_cast<size_t>(l) * D + d) = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
+  }
+}
+
+// One wave per patch: its leaf's row, optionally divided by the leaf's patch count
+// (decompression, and with the division the gradient of the leaf mean).
+template <bool SCALE>
+__global__ __launch_bounds__(256) void asc_expand_kernel(const float *__restrict__ src, const int32_t *__restrict__ patch_leaf,
+                                                         const int32_t *__restrict__ leaf, float *__restrict__ dst,
+                                                         int64_t patches, int D) {
+  const int lane = threadIdx.x & 63;
+  const int64_t p = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  if (p >= patches) return;
+  const int l = patch_leaf[p];
+  float f = 1.0f;
+  if (SCALE) {
+    const int s = leaf[4 * static_cast<int64_t>(l) + 1];
+    f = 1.0f / static_cast<float>(s * s);
+  }
+  const float4 *in = reinterpret_cast<const float4 *>(src + static_cast<size_t>(l) * D);
+  float4 *out = reinterpret_cast<float4 *>(dst + static_cast<size_t>(p) * D);
+  for (int d = lane; d < D / 4; d += 64) {
+    const float4 v = in[d];
+    out[d] = make_float4(v.x * f, v.y * f, v.z * f, v.w * f);
   }
 }
 
@@ -191,9 +203,41 @@ extern "C" int reslim_asc_compress(reslim_ctx *c, const reslim_asc_plan *plan, c
   if (rc != RESLIM_OK) return rc;
   if (!tokens || !tokens_c) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": null buffer");
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  asc_compress_kernel<<<dim3(static_cast<unsigned>(plan->L)), dim3(256), 0, st>>>(tokens, plan->d_leaf, tokens_c, c->Wp, c->cfg.embed_dim);
+  asc_compress_kernel<true><<<dim3(static_cast<unsigned>(plan->L)), dim3(256), 0, st>>>(tokens, plan->d_leaf, tokens_c, c->Wp, c->cfg.embed_dim);
   RESLIM_TRY("asc_compress", hipGetLastError());
   return RESLIM_OK;
+}
+
+// mode 0: decompression; 1: gradient of compression (leaf gradient / patch count to every patch);
+// 2: gradient of decompression (sum of the patch gradients of a leaf)
+static int asc_move(reslim_ctx *c, const reslim_asc_plan *plan, const char *fn, int mode, const float *src, float *dst, void *hip_stream) {
+  int rc = asc_check(c, plan, fn);
+  if (rc != RESLIM_OK) return rc;
+  if (!src || !dst) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": null buffer");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int D = c->cfg.embed_dim;
+  const int64_t patches = static_cast<int64_t>(plan->batch) * c->N;
+  const dim3 pg(static_cast<unsigned>((patches + 3) / 4));
+  if (mode == 0) asc_expand_kernel<false><<<pg, dim3(256), 0, st>>>(src, plan->d_patch_leaf, plan->d_leaf, dst, patches, D);
+  else if (mode == 1) asc_expand_kernel<true><<<pg, dim3(256), 0, st>>>(src, plan->d_patch_leaf, plan->d_leaf, dst, patches, D);
+  else asc_compress_kernel<false><<<dim3(static_cast<unsigned>(plan->L)), dim3(256), 0, st>>>(src, plan->d_leaf, dst, c->Wp, D);
+  RESLIM_TRY("launch", hipGetLastError());
+  return RESLIM_OK;
+}
+
+extern "C" int reslim_asc_decompress(reslim_ctx *c, const reslim_asc_plan *plan, const float *tokens_c, float *tokens, void *hip_stream) {
+  if (!c) return RESLIM_EINVAL;
+  return asc_move(c, plan, "reslim_asc_decompress", 0, tokens_c, tokens, hip_stream);
+}
+
+extern "C" int reslim_asc_compress_bwd(reslim_ctx *c, const reslim_asc_plan *plan, const float *d_tokens_c, float *d_tokens, void *hip_stream) {
+  if (!c) return RESLIM_EINVAL;
+  return asc_move(c, plan, "reslim_asc_compress_bwd", 1, d_tokens_c, d_tokens, hip_stream);
+}
+
+extern "C" int reslim_asc_decompress_bwd(reslim_ctx *c, const reslim_asc_plan *plan, const float *d_tokens, float *d_tokens_c, void *hip_stream) {
+  if (!c) return RESLIM_EINVAL;
+  return asc_move(c, plan, "reslim_asc_decompress_bwd", 2, d_tokens, d_tokens_c, hip_stream);
 }
 
 extern "C" int reslim_asc_forward(reslim_ctx *c, const reslim_asc_plan *plan, const float *x, float *y, void *workspace,
@@ -214,7 +258,7 @@ extern "C" int reslim_asc_forward(reslim_ctx *c, const reslim_asc_plan *plan, co
   // embed (w.big <- [Mi, D] fp32), compress into the stream buffer
   if ((rc = embed_full_impl(c, fn, x, batch, w, st)) != RESLIM_OK) return rc;
   RESLIM_LAUNCH("asc_compress", 0, 4.0 * dMi * dD + 4.0 * dL * dD,
-                (asc_compress_kernel<<<dim3(static_cast<unsigned>(plan->L)), dim3(256), 0, st>>>(
+                (asc_compress_kernel<true><<<dim3(static_cast<unsigned>(plan->L)), dim3(256), 0, st>>>(
                      static_cast<const float *>(w.big), plan->d_leaf, w.X, c->Wp, D),
                  hipGetLastError()));
   // blocks on the leaves: the batch is one run of L rows, one attention set per sample

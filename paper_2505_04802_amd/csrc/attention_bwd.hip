@@ -607,8 +607,8 @@ hipError_t attention_bwd_init() {
   return hipSuccess;
 }
 
-size_t tiles_attention_bwd_ws_bytes(const reslim_ctx *c, int batch) {
-  const size_t recs = static_cast<size_t>(batch) * c->cfg.heads * c->n_h;
+size_t tiles_attention_bwd_ws_bytes(const reslim_ctx *c, int batch, const SeqGeom *geom) {
+  const size_t recs = static_cast<size_t>(batch) * c->cfg.heads * (geom ? geom->n_h : c->n_h);
   return c->cfg.dtype == RESLIM_BF16 ? align256(recs * 32) : align256(recs * 4);
 }
 
@@ -645,9 +645,10 @@ static hipError_t launch_bwd_all(const AttnBwdArgs &a, int dh, hipStream_t st) {
 
 hipError_t launch_tiles_attention_bwd(const reslim_ctx *c, const void *qkv, const void *out, const float *lse,
                                       const void *dout, void *dqkv, int batch, void *ws, bool q_prescaled,
-                                      hipStream_t st) {
+                                      hipStream_t st, const SeqGeom *geom) {
+  const SeqGeom sg = geom ? *geom : ctx_geom(c);
   const int heads = c->cfg.heads, D = c->cfg.embed_dim, dh = c->dh;
-  const int64_t recs = static_cast<int64_t>(batch) * heads * c->n_h;
+  const int64_t recs = static_cast<int64_t>(batch) * heads * sg.n_h;
   if (recs == 0) return hipSuccess;
   if (c->cfg.dtype == RESLIM_BF16) {
     const float rs = 1.0f / sqrtf(static_cast<float>(dh));
@@ -656,11 +657,11 @@ hipError_t launch_tiles_attention_bwd(const reslim_ctx *c, const void *qkv, cons
     a.dout = static_cast<const bf16_t *>(dout);
     a.aux = static_cast<const u32x4 *>(ws);
     a.dqkv = static_cast<bf16_t *>(dqkv);
-    a.tiles = c->d_tiles;
-    a.T = c->T;
+    a.tiles = sg.d_tiles;
+    a.T = sg.T;
     a.heads = heads;
     a.D = D;
-    a.n_h = c->n_h;
+    a.n_h = sg.n_h;
     a.aux_stride = recs;
     // With q pre-scaled by log2(e)/sqrt(dh) the MFMA output is the base-2 logit; the gradient with
     // respect to the UNSCALED q keeps the factor 1/sqrt(dh), the one of k becomes ln 2 (k meets the
@@ -668,20 +669,20 @@ hipError_t launch_tiles_attention_bwd(const reslim_ctx *c, const void *qkv, cons
     a.c = q_prescaled ? 1.0f : 1.4426950408889634f * rs;
     a.scq = rs;
     a.sck = q_prescaled ? 0.69314718055994531f : rs;
-    a.QB = (c->max_n_tok + 127) / 128;
-    const int64_t total = static_cast<int64_t>(batch) * c->T * heads * a.QB;
+    a.QB = (sg.max_n_tok + 127) / 128;
+    const int64_t total = static_cast<int64_t>(batch) * sg.T * heads * a.QB;
     if (total > INT32_MAX || g_bwd_cus <= 0) return hipErrorInvalidValue;
     a.total = static_cast<int>(total);
-    const int64_t n_vec = static_cast<int64_t>(batch) * c->n_h * D / 8;
+    const int64_t n_vec = static_cast<int64_t>(batch) * sg.n_h * D / 8;
     const unsigned pg = static_cast<unsigned>((n_vec + 255) / 256);
     // record 0 holds -lse in the unit of the MFMA output: -lse*sqrt(dh), or -lse*log2(e) for pre-scaled q
     const float lse_f = q_prescaled ? 1.4426950408889634f : sqrtf(static_cast<float>(dh));
     u32x4 *aux = static_cast<u32x4 *>(ws);
     const bf16_t *o = static_cast<const bf16_t *>(out);
     switch (dh) {
-      case 64: attn_bwd_prep_bf16_kernel<64><<<dim3(pg), dim3(256), 0, st>>>(o, a.dout, lse, aux, n_vec, c->n_h, heads, D, lse_f, recs); break;
-      case 128: attn_bwd_prep_bf16_kernel<128><<<dim3(pg), dim3(256), 0, st>>>(o, a.dout, lse, aux, n_vec, c->n_h, heads, D, lse_f, recs); break;
-      case 256: attn_bwd_prep_bf16_kernel<256><<<dim3(pg), dim3(256), 0, st>>>(o, a.dout, lse, aux, n_vec, c->n_h, heads, D, lse_f, recs); break;
+      case 64: attn_bwd_prep_bf16_kernel<64><<<dim3(pg), dim3(256), 0, st>>>(o, a.dout, lse, aux, n_vec, sg.n_h, heads, D, lse_f, recs); break;
+      case 128: attn_bwd_prep_bf16_kernel<128><<<dim3(pg), dim3(256), 0, st>>>(o, a.dout, lse, aux, n_vec, sg.n_h, heads, D, lse_f, recs); break;
+      case 256: attn_bwd_prep_bf16_kernel<256><<<dim3(pg), dim3(256), 0, st>>>(o, a.dout, lse, aux, n_vec, sg.n_h, heads, D, lse_f, recs); break;
       default: return hipErrorInvalidValue;
     }
     hipError_t e = hipGetLastError();
@@ -689,22 +690,22 @@ hipError_t launch_tiles_attention_bwd(const reslim_ctx *c, const void *qkv, cons
     return q_prescaled ? launch_bwd_all<true>(a, dh, st) : launch_bwd_all<false>(a, dh, st);
   }
   float *delta = static_cast<float *>(ws);
-  const size_t lds = (2 * static_cast<size_t>(c->max_n_tok) + 2 * dh) * sizeof(float);
-  if (lds > 60 * 1024 || c->n_h > INT32_MAX) return hipErrorInvalidValue;
-  const int64_t n = static_cast<int64_t>(batch) * c->n_h * heads;
+  const size_t lds = (2 * static_cast<size_t>(sg.max_n_tok) + 2 * dh) * sizeof(float);
+  if (lds > 60 * 1024 || sg.n_h > INT32_MAX) return hipErrorInvalidValue;
+  const int64_t n = static_cast<int64_t>(batch) * sg.n_h * heads;
   attn_bwd_delta_f32_kernel<<<dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, st>>>(
-      static_cast<const float *>(out), static_cast<const float *>(dout), delta, n, c->n_h, heads, dh);
+      static_cast<const float *>(out), static_cast<const float *>(dout), delta, n, sg.n_h, heads, dh);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const dim3 grid(static_cast<unsigned>(c->n_h), heads, batch);
+  const dim3 grid(static_cast<unsigned>(sg.n_h), heads, batch);
   attn_bwd_f32_kernel<false><<<grid, dim3(128), lds, st>>>(static_cast<const float *>(qkv), static_cast<const float *>(dout),
-                                                         lse, delta, static_cast<float *>(dqkv), c->d_tiles,
-                                                         c->d_tile_of_tok, c->n_h, heads, D, dh, c->max_n_tok);
+                                                         lse, delta, static_cast<float *>(dqkv), sg.d_tiles,
+                                                         sg.d_tile_of_tok, sg.n_h, heads, D, dh, sg.max_n_tok);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   attn_bwd_f32_kernel<true><<<grid, dim3(128), lds, st>>>(static_cast<const float *>(qkv), static_cast<const float *>(dout),
-                                                        lse, delta, static_cast<float *>(dqkv), c->d_tiles,
-                                                        c->d_tile_of_tok, c->n_h, heads, D, dh, c->max_n_tok);
+                                                        lse, delta, static_cast<float *>(dqkv), sg.d_tiles,
+                                                        sg.d_tile_of_tok, sg.n_h, heads, D, dh, sg.max_n_tok);
   return hipGetLastError();
 }
 

@@ -40,8 +40,9 @@ struct TrainSaved {        // what the training forward keeps for the gradient (
   void *ln2, *h, *u;       // act [M, D], [M, R] before GELU, [M, R] after
   size_t total;
 };
-TrainSaved plan_saved(const reslim_ctx *c, int batch, void *base) {
-  const size_t M = static_cast<size_t>(batch) * c->n_h, D = c->cfg.embed_dim, R = c->R, es = act_size(c);
+// n_h: rows per "sample" (the context's tile-major count, or all leaves of a compressed batch with batch = 1)
+TrainSaved plan_saved(const reslim_ctx *c, int batch, void *base, int64_t n_h) {
+  const size_t M = static_cast<size_t>(batch) * n_h, D = c->cfg.embed_dim, R = c->R, es = act_size(c);
   unsigned char *p = static_cast<unsigned char *>(base);
   size_t off = 0;
   auto take = [&](size_t bytes) { unsigned char *q = p + off; off += align256(bytes); return q; };
@@ -49,7 +50,7 @@ TrainSaved plan_saved(const reslim_ctx *c, int batch, void *base) {
   s.ln1 = take(M * D * es);
   s.qkv = take(M * 3 * D * es);
   s.attn = take(M * D * es);
-  s.lse = reinterpret_cast<float *>(take(static_cast<size_t>(batch) * c->cfg.heads * c->n_h * sizeof(float)));
+  s.lse = reinterpret_cast<float *>(take(static_cast<size_t>(batch) * c->cfg.heads * n_h * sizeof(float)));
   s.x_mid = reinterpret_cast<float *>(take(M * D * sizeof(float)));
   s.ln2 = take(M * D * es);
   s.h = take(M * R * es);
@@ -66,8 +67,8 @@ struct TrainWs {           // scratch of the gradient pass
   float *colp, *lnp;       // partial rows of the column sums and of the LayerNorm parameter gradients
   size_t total;
 };
-TrainWs plan_train_ws(const reslim_ctx *c, int batch, void *base) {
-  const size_t M = static_cast<size_t>(batch) * c->n_h, D = c->cfg.embed_dim, R = c->R, es = act_size(c);
+TrainWs plan_train_ws(const reslim_ctx *c, int batch, void *base, const SeqGeom &sg) {
+  const size_t M = static_cast<size_t>(batch) * sg.n_h, D = c->cfg.embed_dim, R = c->R, es = act_size(c);
   const int dt = c->cfg.dtype, Mi = static_cast<int>(M), Di = c->cfg.embed_dim, Ri = c->R;
   unsigned char *p = static_cast<unsigned char *>(base);
   size_t off = 0;
@@ -77,7 +78,7 @@ TrainWs plan_train_ws(const reslim_ctx *c, int batch, void *base) {
   w.b = take(M * D * es);
   w.r = take(M * std::max(3 * D, R) * es);
   w.g = reinterpret_cast<float *>(take(M * D * sizeof(float)));
-  w.attn = take(tiles_attention_bwd_ws_bytes(c, batch));
+  w.attn = take(tiles_attention_bwd_ws_bytes(c, batch, &sg));
   size_t wg = std::max(std::max(wgrad_ws_bytes(dt, Mi, 3 * Di, Di), wgrad_ws_bytes(dt, Mi, Di, Di)),
                        std::max(wgrad_ws_bytes(dt, Mi, Ri, Di), wgrad_ws_bytes(dt, Mi, Di, Ri)));
   w.wgrad = take(std::max<size_t>(wg, 256));
@@ -88,14 +89,14 @@ TrainWs plan_train_ws(const reslim_ctx *c, int batch, void *base) {
 }
 
 int check_train(reslim_ctx *c, const char *fn, int layer, int batch, const void *saved, size_t saved_bytes, const void *ws,
-                size_t ws_bytes) {
+                size_t ws_bytes, const SeqGeom &sg) {
   if (layer < 0 || layer >= c->cfg.depth) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": layer outside [0, depth)");
-  int rc = check_common(c, fn, batch, nullptr, 0, false);
-  if (rc != RESLIM_OK) return rc;
+  if (batch < 1 || static_cast<int64_t>(batch) * sg.n_h > INT32_MAX)
+    return set_error(c, RESLIM_ESHAPE, std::string(fn) + ": batch * tokens must be in [1, 2^31)");
   if (!c->layers[layer].wt_qkv) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": call reslim_train_prepare first");
   if (!saved || (reinterpret_cast<uintptr_t>(saved) & 255) || !ws || (reinterpret_cast<uintptr_t>(ws) & 255))
     return set_error(c, RESLIM_EWORKSPACE, std::string(fn) + ": saved / workspace null or not 256-byte aligned");
-  if (saved_bytes < plan_saved(c, batch, nullptr).total || ws_bytes < plan_train_ws(c, batch, nullptr).total)
+  if (saved_bytes < plan_saved(c, batch, nullptr, sg.n_h).total || ws_bytes < plan_train_ws(c, batch, nullptr, sg).total)
     return set_error(c, RESLIM_EWORKSPACE, std::string(fn) + ": saved / workspace smaller than reslim_block_train_bytes()");
   return RESLIM_OK;
 }
@@ -140,8 +141,8 @@ extern "C" int reslim_train_prepare(reslim_ctx *c) {
 
 extern "C" int reslim_block_train_bytes(const reslim_ctx *c, int32_t batch, size_t *saved_bytes, size_t *ws_bytes) {
   if (!c || batch < 1) return RESLIM_EINVAL;
-  if (saved_bytes) *saved_bytes = plan_saved(c, batch, nullptr).total;
-  if (ws_bytes) *ws_bytes = plan_train_ws(c, batch, nullptr).total;
+  if (saved_bytes) *saved_bytes = plan_saved(c, batch, nullptr, c->n_h).total;
+  if (ws_bytes) *ws_bytes = plan_train_ws(c, batch, nullptr, ctx_geom(c)).total;
   return RESLIM_OK;
 }
 
@@ -189,21 +190,19 @@ extern "C" int reslim_linear_bwd_workspace_bytes(const reslim_ctx *c, int32_t wh
   return RESLIM_OK;
 }
 
-extern "C" int reslim_block_fwd_train(reslim_ctx *c, int32_t layer, const float *x_in, float *x_out, void *saved,
-                                      size_t saved_bytes, int32_t batch, void *workspace, size_t ws_bytes, void *hip_stream) {
-  const char *fn = "reslim_block_fwd_train";
-  if (!c) return RESLIM_EINVAL;
+static int block_fwd_train_impl(reslim_ctx *c, const char *fn, int layer, const float *x_in, float *x_out, void *saved,
+                                size_t saved_bytes, int batch, void *workspace, size_t ws_bytes, void *hip_stream,
+                                const SeqGeom &sg) {
   if (!x_in || !x_out || x_in == x_out) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": null buffer or x_out aliases x_in");
-  int rc = check_train(c, fn, layer, batch, saved, saved_bytes, workspace, ws_bytes);
+  int rc = check_train(c, fn, layer, batch, saved, saved_bytes, workspace, ws_bytes, sg);
   if (rc != RESLIM_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  const TrainSaved s = plan_saved(c, batch, saved);
+  const TrainSaved s = plan_saved(c, batch, saved, sg.n_h);
   const int D = c->cfg.embed_dim, R = c->R, dt = c->cfg.dtype;
-  const int M = static_cast<int>(batch * c->n_h);
+  const int M = static_cast<int>(batch * sg.n_h);
   const LayerWeights &lw = c->layers[layer];
   const double es = static_cast<double>(act_size(c)), dM = M, dD = D, dR = R;
-  double pairs = 0;
-  for (const tile_desc &t : c->tiles) pairs += static_cast<double>(t.n_tok) * t.n_tok;
+  const double pairs = sg.pairs;
   const bool qs = dt == RESLIM_BF16;
   const float qscale = 1.4426950408889634f / sqrtf(static_cast<float>(c->dh));
   RESLIM_LAUNCH("layernorm", 0, dM * dD * (4.0 + es), launch_layernorm(dt, x_in, nullptr, 0, 0, lw.ln1_g, lw.ln1_b, s.ln1, M, D, st));
@@ -211,7 +210,7 @@ extern "C" int reslim_block_fwd_train(reslim_ctx *c, int32_t layer, const float 
                 launch_gemm(dt, qs ? EPI_BIAS_QSCALE_ACT : EPI_BIAS_ACT, s.ln1, lw.w_qkv, lw.b_qkv, s.qkv, 3 * D, nullptr, 0, M,
                             3 * D, D, st, qscale, D));
   RESLIM_LAUNCH("tiles_attention", 4.0 * pairs * dD * batch, 4.0 * dM * dD * es,
-                launch_tiles_attention(c, s.qkv, s.attn, batch, qs, st, s.lse));
+                launch_tiles_attention(c, s.qkv, s.attn, batch, qs, st, s.lse, &sg));
   RESLIM_LAUNCH("gemm_proj", 2.0 * dM * dD * dD, dM * dD * es + dD * dD * es + 8.0 * dM * dD,
                 launch_gemm(dt, EPI_BIAS_RES_F32, s.attn, lw.w_proj, lw.b_proj, s.x_mid, D, nullptr, 0, M, D, D, st, 1.0f, 0, x_in));
   RESLIM_LAUNCH("layernorm", 0, dM * dD * (4.0 + es), launch_layernorm(dt, s.x_mid, nullptr, 0, 0, lw.ln2_g, lw.ln2_b, s.ln2, M, D, st));
@@ -223,26 +222,39 @@ extern "C" int reslim_block_fwd_train(reslim_ctx *c, int32_t layer, const float 
   return RESLIM_OK;
 }
 
-extern "C" int reslim_block_bwd(reslim_ctx *c, int32_t layer, const float *x_in, const void *saved, size_t saved_bytes,
-                                const float *d_x_out, float *d_x_in, const reslim_block_grads *grads, int32_t batch,
-                                void *workspace, size_t ws_bytes, void *hip_stream) {
-  const char *fn = "reslim_block_bwd";
+extern "C" int reslim_block_fwd_train(reslim_ctx *c, int32_t layer, const float *x_in, float *x_out, void *saved,
+                                      size_t saved_bytes, int32_t batch, void *workspace, size_t ws_bytes, void *hip_stream) {
   if (!c) return RESLIM_EINVAL;
+  return block_fwd_train_impl(c, "reslim_block_fwd_train", layer, x_in, x_out, saved, saved_bytes, batch, workspace, ws_bytes,
+                              hip_stream, ctx_geom(c));
+}
+
+extern "C" int reslim_asc_block_fwd_train(reslim_ctx *c, const reslim_asc_plan *plan, int32_t layer, const float *x_in,
+                                          float *x_out, void *saved, size_t saved_bytes, void *workspace, size_t ws_bytes,
+                                          void *hip_stream) {
+  if (!c) return RESLIM_EINVAL;
+  if (!plan || plan->ctx != c) return set_error(c, RESLIM_EINVAL, "reslim_asc_block_fwd_train: null plan or plan of another context");
+  return block_fwd_train_impl(c, "reslim_asc_block_fwd_train", layer, x_in, x_out, saved, saved_bytes, 1, workspace, ws_bytes,
+                              hip_stream, plan->geom);
+}
+
+static int block_bwd_impl(reslim_ctx *c, const char *fn, int layer, const float *x_in, const void *saved, size_t saved_bytes,
+                          const float *d_x_out, float *d_x_in, const reslim_block_grads *grads, int batch, void *workspace,
+                          size_t ws_bytes, void *hip_stream, const SeqGeom &sg) {
   if (!x_in || !d_x_out || !d_x_in || !grads) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": null buffer");
   const float *const *gp = reinterpret_cast<const float *const *>(grads);
   for (int i = 0; i < 12; ++i)
     if (!gp[i]) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": null gradient buffer");
-  int rc = check_train(c, fn, layer, batch, saved, saved_bytes, workspace, ws_bytes);
+  int rc = check_train(c, fn, layer, batch, saved, saved_bytes, workspace, ws_bytes, sg);
   if (rc != RESLIM_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  const TrainSaved s = plan_saved(c, batch, const_cast<void *>(saved));
-  const TrainWs w = plan_train_ws(c, batch, workspace);
+  const TrainSaved s = plan_saved(c, batch, const_cast<void *>(saved), sg.n_h);
+  const TrainWs w = plan_train_ws(c, batch, workspace, sg);
   const int D = c->cfg.embed_dim, R = c->R, dt = c->cfg.dtype;
-  const int M = static_cast<int>(batch * c->n_h);
+  const int M = static_cast<int>(batch * sg.n_h);
   const LayerWeights &lw = c->layers[layer];
   const double es = static_cast<double>(act_size(c)), dM = M, dD = D;
-  double pairs = 0;
-  for (const tile_desc &t : c->tiles) pairs += static_cast<double>(t.n_tok) * t.n_tok;
+  const double pairs = sg.pairs;
   const int64_t MD = static_cast<int64_t>(M) * D;
 
   // x_out = x_mid + fc2(gelu(fc1(ln2(x_mid))))
@@ -260,11 +272,35 @@ extern "C" int reslim_block_bwd(reslim_ctx *c, int32_t layer, const float *x_in,
   rc = linear_bwd_impl(c, fn, s.attn, w.a, lw.wt_proj, w.b, grads->w_proj, grads->b_proj, M, D, D, w.wgrad, w.colp, st);
   if (rc != RESLIM_OK) return rc;
   RESLIM_LAUNCH("tiles_attention_bwd", 10.0 * pairs * dD * batch, 8.0 * dM * dD * es,
-                launch_tiles_attention_bwd(c, s.qkv, s.attn, s.lse, w.b, w.r, batch, w.attn, dt == RESLIM_BF16, st));
+                launch_tiles_attention_bwd(c, s.qkv, s.attn, s.lse, w.b, w.r, batch, w.attn, dt == RESLIM_BF16, st, &sg));
   rc = linear_bwd_impl(c, fn, s.ln1, w.r, lw.wt_qkv, w.a, grads->w_qkv, grads->b_qkv, M, 3 * D, D, w.wgrad, w.colp, st);
   if (rc != RESLIM_OK) return rc;
   RESLIM_LAUNCH("layernorm_bwd", 0, dM * dD * (12.0 + es),
                 launch_layernorm_bwd(dt, x_in, w.a, lw.ln1_g, w.g, d_x_in, nullptr, w.lnp, grads->ln1_g, grads->ln1_b, M, D, st));
+  return RESLIM_OK;
+}
+
+extern "C" int reslim_block_bwd(reslim_ctx *c, int32_t layer, const float *x_in, const void *saved, size_t saved_bytes,
+                                const float *d_x_out, float *d_x_in, const reslim_block_grads *grads, int32_t batch,
+                                void *workspace, size_t ws_bytes, void *hip_stream) {
+  if (!c) return RESLIM_EINVAL;
+  return block_bwd_impl(c, "reslim_block_bwd", layer, x_in, saved, saved_bytes, d_x_out, d_x_in, grads, batch, workspace,
+                        ws_bytes, hip_stream, ctx_geom(c));
+}
+
+extern "C" int reslim_asc_block_bwd(reslim_ctx *c, const reslim_asc_plan *plan, int32_t layer, const float *x_in,
+                                    const void *saved, size_t saved_bytes, const float *d_x_out, float *d_x_in,
+                                    const reslim_block_grads *grads, void *workspace, size_t ws_bytes, void *hip_stream) {
+  if (!c) return RESLIM_EINVAL;
+  if (!plan || plan->ctx != c) return set_error(c, RESLIM_EINVAL, "reslim_asc_block_bwd: null plan or plan of another context");
+  return block_bwd_impl(c, "reslim_asc_block_bwd", layer, x_in, saved, saved_bytes, d_x_out, d_x_in, grads, 1, workspace,
+                        ws_bytes, hip_stream, plan->geom);
+}
+
+extern "C" int reslim_asc_block_train_bytes(const reslim_ctx *c, const reslim_asc_plan *plan, size_t *saved_bytes, size_t *ws_bytes) {
+  if (!c || !plan || plan->ctx != c) return RESLIM_EINVAL;
+  if (saved_bytes) *saved_bytes = plan_saved(c, 1, nullptr, plan->geom.n_h).total;
+  if (ws_bytes) *ws_bytes = plan_train_ws(c, 1, nullptr, plan->geom).total;
   return RESLIM_OK;
 }
 

@@ -148,8 +148,8 @@ bool attention_accepts_prescaled_q();
 // gradient of tile attention: d_qkv from qkv, the forward's out and lse, and d_out; ws as sized below
 hipError_t launch_tiles_attention_bwd(const reslim_ctx *c, const void *qkv, const void *out, const float *lse,
                                       const void *dout, void *dqkv, int batch, void *ws, bool q_prescaled,
-                                      hipStream_t st);
-size_t tiles_attention_bwd_ws_bytes(const reslim_ctx *c, int batch);
+                                      hipStream_t st, const SeqGeom *geom = nullptr);
+size_t tiles_attention_bwd_ws_bytes(const reslim_ctx *c, int batch, const SeqGeom *geom = nullptr);
 hipError_t attention_bwd_init();
 // ---- training-side kernels
 hipError_t wgrad_init();
@@ -180,6 +180,20 @@ int check_common(reslim_ctx *c, const char *fn, int batch, const void *ws, size_
 int hip_fail(reslim_ctx *c, const char *fn, const char *what, hipError_t e);
 
 }  // namespace reslim
+
+// Leaf table of the compression module on the device (one per batch of samples).
+struct reslim_asc_plan {
+  reslim_ctx *ctx = nullptr;
+  int batch = 0;
+  int64_t L = 0;                         // leaves of the whole batch
+  std::vector<tile_desc> seq;            // one entry per sample: tok_off, n_tok
+  reslim::SeqGeom geom{};
+  tile_desc *d_seq = nullptr;            // [batch]
+  int32_t *d_seq_of_leaf = nullptr;      // [L]
+  int32_t *d_leaf = nullptr;             // [L][4]: first patch row (b*N + y0*Wp + x0), side, unused, unused
+  int32_t *d_patch_leaf = nullptr;       // [batch * N]
+};
+
 
 #define RESLIM_TRY(what, expr)                                   \
   do {                                                           \

@@ -218,3 +218,89 @@ def test_degenerate_trees(dtype):
         err = max(O.rel_l2(out[b, c], ref[b, c]) for b in range(cfg.batch) for c in range(cfg.out_vars))
         say(f"  max rel-L2 over planes {err:.3e}")
         assert np.isfinite(out).all() and err <= TOL[dtype]
+
+
+# ------------------------------------------------------------------ training on the leaves
+def _u8(n):
+    return torch.empty(max(int(n), 256), dtype=torch.uint8, device="cuda")
+
+
+@pytest.mark.parametrize("cfg", [ASC_F32, ASC_BF16], ids=lambda c: c.name)
+def test_gradients_of_compress_and_decompress(cfg):
+    r = np.random.default_rng(cfg.seed + 1)
+    D, N = cfg.embed_dim, cfg.n_tokens
+    tab = table_for(cfg, WL.make_fields(cfg))
+    L = len(tab["leaf_s"])
+    zc = r.standard_normal((L, D)).astype(np.float32)
+    g = r.standard_normal((cfg.batch, N, D)).astype(np.float32)
+    with B.Reslim(cfg, WL.make_weights(cfg)) as m:
+        plan = B.reslim_asc_plan_create(m.ctx, cfg.batch, tab)
+        try:
+            full = torch.full((cfg.batch * N, D), float("nan"), dtype=torch.float32, device="cuda")
+            B.reslim_asc_decompress(m.ctx, plan, cuda(zc), full)
+            assert np.array_equal(full.cpu().numpy().reshape(cfg.batch, N, D), A.decompress(zc, tab).astype(np.float32))
+            B.reslim_asc_compress_bwd(m.ctx, plan, cuda(zc), full)
+            err = O.rel_l2(full.cpu().numpy().reshape(cfg.batch, N, D), A.compress_bwd(zc, tab, cfg.batch, N))
+            say(f"  compress_bwd {cfg.name} rel-L2 {err:.3e}")
+            assert err <= 1e-6
+            dc = torch.full((L, D), float("nan"), dtype=torch.float32, device="cuda")
+            B.reslim_asc_decompress_bwd(m.ctx, plan, cuda(g), dc)
+            err = O.rel_l2(dc.cpu().numpy(), A.decompress_bwd(g, tab))
+            say(f"  decompress_bwd {cfg.name} rel-L2 {err:.3e}")
+            assert err <= 1e-6
+        finally:
+            B.reslim_asc_plan_destroy(plan)
+
+
+@pytest.mark.parametrize("cfg", [ASC_F32, ASC_BF16, ASC_BF16_DH128], ids=lambda c: c.name)
+def test_block_training_on_the_leaves(cfg):
+    """Forward-for-training and backward of one block on a compressed batch (ragged
+    per-sample leaf counts) against the oracle: output, input gradient, all twelve
+    parameter gradients; a second backward gives the same bits."""
+    say(f"asc block train {cfg.name}")
+    w = WL.make_weights(cfg, std=0.1)
+    tab = table_for(cfg, WL.make_fields(cfg))
+    L, D, layer = len(tab["leaf_s"]), cfg.embed_dim, 1
+    r = np.random.default_rng(cfg.seed + 2)
+    x = r.standard_normal((L, D)).astype(np.float32)
+    d_out = r.standard_normal((L, D)).astype(np.float32)
+    ref_out = A.block_compressed(x, tab, w, layer, cfg.heads)
+    ref_dx, ref_g = A.block_compressed_bwd(x, tab, w, layer, cfg.heads, d_out)
+    with B.Reslim(cfg, w) as m:
+        B.reslim_train_prepare(m.ctx)
+        plan = B.reslim_asc_plan_create(m.ctx, cfg.batch, tab)
+        try:
+            sb, wb = B.reslim_asc_block_train_bytes(m.ctx, plan)
+            saved, ws = _u8(sb), _u8(wb)
+            x_dev, out = cuda(x), torch.full((L, D), float("nan"), dtype=torch.float32, device="cuda")
+            B.reslim_asc_block_fwd_train(m.ctx, plan, layer, x_dev, out, saved, ws)
+            err = O.rel_l2(out.cpu().numpy(), ref_out)
+            say(f"  x_out rel-L2 {err:.3e}")
+            assert err <= TOL[cfg.dtype]
+            grads = {n: torch.full(np.shape(w[n][layer]), float("nan"), dtype=torch.float32, device="cuda") for n in B.BLOCK_PARAMS}
+            dx = torch.full((L, D), float("nan"), dtype=torch.float32, device="cuda")
+            B.reslim_asc_block_bwd(m.ctx, plan, layer, x_dev, saved, cuda(d_out), dx, grads, ws)
+            torch.cuda.synchronize()
+            err = O.rel_l2(dx.cpu().numpy(), ref_dx)
+            say(f"  d_x rel-L2 {err:.3e}")
+            assert err <= TOL[cfg.dtype]
+            for n in B.BLOCK_PARAMS:
+                err = O.rel_l2(grads[n].cpu().numpy(), ref_g[n])
+                say(f"  d_{n} rel-L2 {err:.3e}")
+                assert err <= TOL[cfg.dtype], n
+            again = {n: torch.empty_like(grads[n]) for n in B.BLOCK_PARAMS}
+            dx2 = torch.empty_like(dx)
+            B.reslim_asc_block_bwd(m.ctx, plan, layer, x_dev, saved, cuda(d_out), dx2, again, ws)
+            torch.cuda.synchronize()
+            assert torch.equal(dx, dx2) and all(torch.equal(grads[n], again[n]) for n in B.BLOCK_PARAMS)
+            # error paths: short buffers, a plan of another context
+            lib = B.load()
+            st = torch.cuda.current_stream().cuda_stream
+            assert lib.reslim_asc_block_fwd_train(m.ctx, plan, layer, x_dev.data_ptr(), out.data_ptr(), saved.data_ptr(),
+                                                  sb - 256, ws.data_ptr(), wb, st) == B.RESLIM_EWORKSPACE
+            with B.Reslim(cfg, w) as other:
+                B.reslim_train_prepare(other.ctx)
+                assert lib.reslim_asc_block_fwd_train(other.ctx, plan, layer, x_dev.data_ptr(), out.data_ptr(),
+                                                      saved.data_ptr(), sb, ws.data_ptr(), wb, st) == B.RESLIM_EINVAL
+        finally:
+            B.reslim_asc_plan_destroy(plan)

@@ -213,3 +213,45 @@ def test_image_from_tokens_layout():
             for j in range(p):
                 ref = float(w_img[i * p + j] @ z[0, n] + b_img[i * p + j])
                 assert abs(img[0, (n // Wp) * p + i, (n % Wp) * p + j] - ref) < 1e-12
+
+
+def test_gradients_of_compress_and_decompress_are_the_adjoint_maps():
+    """compress and decompress are linear: their gradients must be the transposed
+    maps, <A z, g> = <z, A^T g> for arbitrary z and g (to rounding)."""
+    r = np.random.default_rng(11)
+    B, Hp, Wp, D, p = 2, 8, 16, 4, 2
+    imgs = ndimage.gaussian_filter(r.standard_normal((B, Hp * p, Wp * p)), (0, 1.5, 1.5)).astype(np.float32)
+    tab = A.build(imgs, p, 4, 1, 40, 90, 0.06)
+    L, N = len(tab["leaf_s"]), Hp * Wp
+    assert 1 < L < B * N
+    z, g_c = r.standard_normal((B, N, D)), r.standard_normal((L, D))
+    assert abs((A.compress(z, tab, Wp) * g_c).sum() - (z * A.compress_bwd(g_c, tab, B, N)).sum()) < 1e-10
+    zc, g = r.standard_normal((L, D)), r.standard_normal((B, N, D))
+    assert abs((A.decompress(zc, tab) * g).sum() - (zc * A.decompress_bwd(g, tab)).sum()) < 1e-10
+    # decompress after compress keeps leaf means: the composed gradient is the projection again
+    np.testing.assert_allclose(A.compress(A.decompress(zc, tab), tab, Wp), zc, atol=1e-14)
+
+
+def test_block_gradient_on_leaves_by_finite_differences():
+    cfg = WL.CONFIGS["c0"].with_(tiles_y=1, tiles_x=1, halo=0, batch=2, embed_dim=32, heads=2, depth=1, H=16, W=16)
+    w = {k: np.asarray(v, np.float64) for k, v in WL.make_weights(cfg, std=0.2).items()}
+    r = np.random.default_rng(12)
+    tab = dict(sample_off=np.array([0, 5, 12]), leaf_s=np.ones(12, np.int64))
+    X, d_out = r.standard_normal((12, cfg.embed_dim)), r.standard_normal((12, cfg.embed_dim))
+    dX, grads = A.block_compressed_bwd(X, tab, w, 0, cfg.heads, d_out)
+    f = lambda X_, w_: float((A.block_compressed(X_, tab, w_, 0, cfg.heads) * d_out).sum())
+    eps = 1e-6
+    for (i, j) in ((0, 3), (4, 0), (5, 7), (11, 31)):           # both samples, first and last rows
+        Xp, Xm = X.copy(), X.copy(); Xp[i, j] += eps; Xm[i, j] -= eps
+        assert abs((f(Xp, w) - f(Xm, w)) / (2 * eps) - dX[i, j]) < 1e-6 * max(1.0, abs(dX[i, j]))
+    for name, idx in (("w_qkv", (0, 5, 3)), ("b_fc1", (0, 7)), ("ln1_g", (0, 2)), ("w_fc2", (0, 3, 9))):
+        wp, wm = dict(w), dict(w)
+        wp[name] = w[name].copy(); wm[name] = w[name].copy()
+        wp[name][idx] += eps; wm[name][idx] -= eps
+        fd = (f(X, wp) - f(X, wm)) / (2 * eps)
+        assert abs(fd - grads[name][idx[1:]]) < 1e-6 * max(1.0, abs(fd)), name
+    # attention never crosses a sample: the gradient of sample 0's rows ignores sample 1's upstream gradient
+    d2 = d_out.copy(); d2[5:] = 0.0
+    dX2, _ = A.block_compressed_bwd(X, tab, w, 0, cfg.heads, d2)
+    np.testing.assert_allclose(dX2[:5], dX[:5], atol=1e-14)
+    assert np.abs(dX2[5:]).max() == 0.0
