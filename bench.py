@@ -123,20 +123,51 @@ def asc_leg(B, torch, np, cfg, w, x_host, K):
             return (time.perf_counter() - t0) / K * 1e3
 
         res["plain_ms"] = round(timed(lambda: B.reslim_forward(m.ctx, x, y, one.batch, m.ws)), 4)
+        # one block's training step (forward-for-training + backward) on N(0,1) rows, plain and on the leaves
+        B.reslim_train_prepare(m.ctx)
+        D, R = one.embed_dim, one.embed_dim * one.mlp_ratio
+        shapes = {"ln1_g": (D,), "ln1_b": (D,), "w_qkv": (3 * D, D), "b_qkv": (3 * D,), "w_proj": (D, D), "b_proj": (D,),
+                  "ln2_g": (D,), "ln2_b": (D,), "w_fc1": (R, D), "b_fc1": (R,), "w_fc2": (D, R), "b_fc2": (D,)}
+        grads = {n: torch.empty(sh, dtype=torch.float32, device="cuda") for n, sh in shapes.items()}
+        gen = torch.Generator().manual_seed(7)
+
+        def train_step_ms(rows, fwd, bwd, sb, wb):
+            saved = torch.empty(max(sb, 256), dtype=torch.uint8, device="cuda")
+            wsb = torch.empty(max(wb, 256), dtype=torch.uint8, device="cuda")
+            xi = torch.randn((rows, D), generator=gen).cuda()
+            do = torch.randn((rows, D), generator=gen).cuda()
+            xo, dxi = torch.empty_like(xi), torch.empty_like(xi)
+
+            def step():
+                fwd(xi, xo, saved, wsb)
+                bwd(xi, saved, do, dxi, wsb)
+            return timed(step)
+
+        sb, wb = B.reslim_block_train_bytes(m.ctx, one.batch)
+        res["plain_train_block_ms"] = round(train_step_ms(
+            one.batch * m.n_h,
+            lambda xi, xo, sv, wk: B.reslim_block_fwd_train(m.ctx, 0, xi, xo, sv, one.batch, wk),
+            lambda xi, sv, do, dxi, wk: B.reslim_block_bwd(m.ctx, 0, xi, sv, do, dxi, grads, one.batch, wk), sb, wb), 4)
         imgs = np.ascontiguousarray(x_host[:, 0])
         for prm in ASC_PARAMS:
             t0 = time.perf_counter()
             tab = B.reslim_asc_build(imgs, one.patch, prm["max_leaf"], prm["min_leaf"], prm["canny_low"], prm["canny_high"], prm["tau"])
             build_ms = (time.perf_counter() - t0) * 1e3
             plan = B.reslim_asc_plan_create(m.ctx, one.batch, tab)
+            L = len(tab["leaf_s"])
             try:
                 ms = timed(lambda: B.reslim_asc_forward(m.ctx, plan, x, y, m.ws))
+                sb, wb = B.reslim_asc_block_train_bytes(m.ctx, plan)
+                tms = train_step_ms(
+                    L, lambda xi, xo, sv, wk: B.reslim_asc_block_fwd_train(m.ctx, plan, 0, xi, xo, sv, wk),
+                    lambda xi, sv, do, dxi, wk: B.reslim_asc_block_bwd(m.ctx, plan, 0, xi, sv, do, dxi, grads, wk), sb, wb)
             finally:
                 B.reslim_asc_plan_destroy(plan)
-            L = len(tab["leaf_s"])
             res["cases"].append(dict(params=prm, leaves=L, compression=round(one.batch * one.n_tokens / L, 2),
                                      leaves_per_sample=np.diff(tab["sample_off"]).tolist(), ms=round(ms, 4),
-                                     speedup=round(res["plain_ms"] / ms, 2), host_builder_ms=round(build_ms, 2)))
+                                     speedup=round(res["plain_ms"] / ms, 2), train_block_ms=round(tms, 4),
+                                     train_block_speedup=round(res["plain_train_block_ms"] / tms, 2),
+                                     host_builder_ms=round(build_ms, 2)))
     return res
 
 
