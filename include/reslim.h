@@ -121,7 +121,8 @@ int tiles_partition(int32_t Hp, int32_t Wp, int32_t Ty, int32_t Tx, int32_t halo
  * bfloat16 for the MFMA operands in RESLIM_BF16 mode) and folds the per-variable
  * tokenisation into the aggregation's key/value maps (Sec. 4.1; exact, since no
  * non-linearity separates them).  Synchronises the device once.  *out is NULL on
- * failure.  RESLIM_BF16 needs D % 64 == 0 and dh in {64, 128}. */
+ * failure.  RESLIM_BF16 needs D % 64 == 0, dh in {64, 128, 256} and
+ * out_vars * (patch * scale)^2 % 8 == 0. */
 int reslim_create(const reslim_config *cfg, const reslim_weights *w, reslim_ctx **out);
 void reslim_destroy(reslim_ctx *ctx);
 

@@ -80,6 +80,8 @@ static int validate(const reslim_config &g, std::string &why) {
     const int dh = g.embed_dim / g.heads;
     if (g.embed_dim % 64) return bad("bf16 path needs embed_dim % 64 == 0");
     if (dh != 64 && dh != 128 && dh != 256) return bad("bf16 path needs head dim 64, 128 or 256");
+    const int64_t ps = static_cast<int64_t>(g.patch) * g.scale;
+    if ((g.out_vars * ps * ps) % 8) return bad("bf16 path needs out_vars * (patch * scale)^2 % 8 == 0 (the GEMM epilogues move 8 columns at a time)");
   }
   if (static_cast<int64_t>(g.scale) * g.H > INT32_MAX / 2 || static_cast<int64_t>(g.scale) * g.W > INT32_MAX / 2)
     return bad("fine grid too large");

@@ -316,3 +316,17 @@ def test_forward_is_capturable_in_a_hip_graph():
             torch.cuda.synchronize()
             assert torch.isfinite(got).all() and torch.equal(got, y)
         assert O.rel_l2(y.cpu().numpy(), O.reslim_forward(xs[0], w, cfg)) <= TOL[1]
+
+
+def test_create_refuses_a_head_the_bf16_epilogues_cannot_store():
+    """out_vars * (patch * scale)^2 must be a multiple of 8 on the bf16 path (16-byte
+    row pieces in the GEMM epilogues); the fp32 path takes the same shape."""
+    cfg = SMALL_BF16.with_(scale=1, out_vars=1, in_vars=3)            # head width 4
+    with pytest.raises(B.ReslimError):
+        B.Reslim(cfg, weights_for(cfg))
+    ok = cfg.with_(dtype=0, embed_dim=48, heads=3)
+    w = weights_for(ok)
+    x = WL.make_fields(ok)
+    with B.Reslim(ok, w) as m:
+        y = m.forward(cuda(x, torch.float32)).cpu().numpy()
+    assert O.rel_l2(y, O.reslim_forward(x, w, ok)) <= TOL[0]
