@@ -200,36 +200,62 @@ __global__ __launch_bounds__(256) void embed_agg_kernel(EmbedArgs e) {
     for (int v = 0; v < e.V; ++v) r[v] *= inv;
   }
   __syncthreads();
-  // one thread per feature d: o[pi][d] = sum_v a[pi][head(d)][v] * (c[v][d] + U[v][d][:] . pix[pi][v][:])
+  // o[pi][d] = sum_v a[pi][head(d)][v] * (c[v][d] + U[v][d][:] . pix[pi][v][:])
   T *out = static_cast<T *>(e.o);
+  if constexpr (P2 == 4) {
+    if (e.dh % 4 == 0) {
+      // A work item is four adjacent features (one head) of four patches: the pixel and
+      // weight reads from LDS (broadcast over the wave) are shared by 16 outputs.
+      constexpr int PPI = 4;
+      const int Q = e.D / 4;
+      for (int item = t; item < Q * (TP / PPI); item += 256) {
+        const int dq = item % Q, p0 = (item / Q) * PPI;
+        const int d = dq * 4, g = d / e.dh;
+        float acc[PPI][4];
+#pragma unroll
+        for (int pi = 0; pi < PPI; ++pi)
+#pragma unroll
+          for (int k = 0; k < 4; ++k) acc[pi][k] = 0.f;
+        for (int v = 0; v < e.V; ++v) {
+          const float4 *up = reinterpret_cast<const float4 *>(e.U + (static_cast<size_t>(v) * e.D + d) * 4);
+          const float4 u0 = up[0], u1 = up[1], u2 = up[2], u3 = up[3];
+          const float4 cv = *reinterpret_cast<const float4 *>(e.c + static_cast<size_t>(v) * e.D + d);
+#pragma unroll
+          for (int pi = 0; pi < PPI; ++pi) {
+            const float4 px = *reinterpret_cast<const float4 *>(pix + (p0 + pi) * VP2 + v * 4);
+            const float a = sc[((p0 + pi) * e.heads + g) * e.V + v];
+            acc[pi][0] = fmaf(a, fmaf(u0.x, px.x, fmaf(u0.y, px.y, fmaf(u0.z, px.z, fmaf(u0.w, px.w, cv.x)))), acc[pi][0]);
+            acc[pi][1] = fmaf(a, fmaf(u1.x, px.x, fmaf(u1.y, px.y, fmaf(u1.z, px.z, fmaf(u1.w, px.w, cv.y)))), acc[pi][1]);
+            acc[pi][2] = fmaf(a, fmaf(u2.x, px.x, fmaf(u2.y, px.y, fmaf(u2.z, px.z, fmaf(u2.w, px.w, cv.z)))), acc[pi][2]);
+            acc[pi][3] = fmaf(a, fmaf(u3.x, px.x, fmaf(u3.y, px.y, fmaf(u3.z, px.z, fmaf(u3.w, px.w, cv.w)))), acc[pi][3]);
+          }
+        }
+#pragma unroll
+        for (int pi = 0; pi < PPI; ++pi)
+          if (bn0 + p0 + pi < e.BN) {
+            T *o = out + (bn0 + p0 + pi) * e.D + d;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) Act<T>::store(o + k, acc[pi][k]);
+          }
+      }
+      return;
+    }
+  }
+  // general shapes: one thread per feature d
   for (int d = t; d < e.D; d += 256) {
     const int g = d / e.dh;
     float acc[TP];
 #pragma unroll
     for (int pi = 0; pi < TP; ++pi) acc[pi] = 0.f;
-    if constexpr (P2 == 4) {
-#pragma unroll 4
-      for (int v = 0; v < e.V; ++v) {
-        const float4 u = *reinterpret_cast<const float4 *>(e.U + (static_cast<size_t>(v) * e.D + d) * 4);
-        const float cv = e.c[static_cast<size_t>(v) * e.D + d];
+    for (int v = 0; v < e.V; ++v) {
+      const float *Ur = e.U + (static_cast<size_t>(v) * e.D + d) * p2;
+      const float cv = e.c[static_cast<size_t>(v) * e.D + d];
 #pragma unroll
-        for (int pi = 0; pi < TP; ++pi) {
-          const float4 px = *reinterpret_cast<const float4 *>(pix + pi * VP2 + v * 4);
-          const float val = fmaf(u.x, px.x, fmaf(u.y, px.y, fmaf(u.z, px.z, fmaf(u.w, px.w, cv))));
-          acc[pi] = fmaf(sc[(pi * e.heads + g) * e.V + v], val, acc[pi]);
-        }
-      }
-    } else {
-      for (int v = 0; v < e.V; ++v) {
-        const float *Ur = e.U + (static_cast<size_t>(v) * e.D + d) * p2;
-        const float cv = e.c[static_cast<size_t>(v) * e.D + d];
-#pragma unroll
-        for (int pi = 0; pi < TP; ++pi) {
-          const float *px = pix + pi * VP2 + v * p2;
-          float val = cv;
-          for (int i = 0; i < p2; ++i) val = fmaf(Ur[i], px[i], val);
-          acc[pi] = fmaf(sc[(pi * e.heads + g) * e.V + v], val, acc[pi]);
-        }
+      for (int pi = 0; pi < TP; ++pi) {
+        const float *px = pix + pi * VP2 + v * p2;
+        float val = cv;
+        for (int i = 0; i < p2; ++i) val = fmaf(Ur[i], px[i], val);
+        acc[pi] = fmaf(sc[(pi * e.heads + g) * e.V + v], val, acc[pi]);
       }
     }
 #pragma unroll
