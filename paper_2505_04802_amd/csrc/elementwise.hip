@@ -234,8 +234,14 @@ __global__ __launch_bounds__(256) void embed_agg_kernel(EmbedArgs e) {
         for (int pi = 0; pi < PPI; ++pi)
           if (bn0 + p0 + pi < e.BN) {
             T *o = out + (bn0 + p0 + pi) * e.D + d;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) Act<T>::store(o + k, acc[pi][k]);
+            if constexpr (sizeof(T) == 2) {
+              uint2 pk;
+              pk.x = pack_bf16x2(acc[pi][0], acc[pi][1]);
+              pk.y = pack_bf16x2(acc[pi][2], acc[pi][3]);
+              *reinterpret_cast<uint2 *>(o) = pk;
+            } else {
+              *reinterpret_cast<float4 *>(o) = make_float4(acc[pi][0], acc[pi][1], acc[pi][2], acc[pi][3]);
+            }
           }
       }
       return;
