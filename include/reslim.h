@@ -350,16 +350,18 @@ typedef struct reslim_asc_plan reslim_asc_plan;
  *     ones connected to them (8-neighbourhood); borders replicated for the filters,
  *     magnitude 0 outside for the suppression;
  *  3. quad-tree over the patch grid (H/patch x W/patch): roots are max_leaf x
- *     max_leaf patches in row-major order; a node of side s splits into NW, NE, SW,
- *     SE iff s > min_leaf and float(edge pixels inside) > tau * float((s*patch)^2);
- *     leaves are listed depth-first, sample after sample.
+ *     max_leaf patches in row-major order (the grid is thought padded to a multiple
+ *     of max_leaf; a node wholly in the padding is dropped, one that sticks out of
+ *     the grid always splits); a node inside the grid of side s splits into NW, NE,
+ *     SW, SE iff s > min_leaf and float(edge pixels inside) > tau *
+ *     float((s*patch)^2); leaves are listed depth-first, sample after sample.
  * Outputs (host, caller-owned, room for batch * (H/patch) * (W/patch) entries each,
  * sample_off batch + 1): leaf_y0, leaf_x0, leaf_s in patch units; sample_off[b] =
  * first leaf of sample b; patch_leaf[b, y*Wp + x] = batch-wide index of the leaf
  * holding that patch; *n_leaves_out = total leaves.
  * Errors: RESLIM_EINVAL (null pointer, negative or inverted thresholds, tau negative
  * or not finite, a pixel that is not finite), RESLIM_ESHAPE (leaf sizes not powers
- * of two, min_leaf > max_leaf, grid not divisible by patch or by max_leaf). */
+ * of two, min_leaf > max_leaf, H or W not divisible by patch). */
 int reslim_asc_build(const float *images, int32_t batch, int32_t H, int32_t W, int32_t patch, int32_t max_leaf,
                      int32_t min_leaf, int32_t canny_low, int32_t canny_high, float tau, int32_t *leaf_y0,
                      int32_t *leaf_x0, int32_t *leaf_s, int32_t *sample_off, int32_t *patch_leaf,

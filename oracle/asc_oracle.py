@@ -26,9 +26,11 @@ paper for each of them, pinned against the definitions they reduce to):
     over the 8-neighbourhood; image borders by replication for the two filters,
     pixels outside count as magnitude 0 in the suppression;
   * quad-tree: roots are max_leaf x max_leaf blocks of patches in row-major
-    order; a node of side s patches splits iff s > min_leaf and
-    float32(count) > float32(tau) * float32(area in pixels); children in the
-    order NW, NE, SW, SE, leaves listed depth-first;
+    order, the grid padded (conceptually, with nothing in the padding) to a
+    multiple of max_leaf; a node wholly outside the grid is dropped, a node that
+    sticks out of it always splits, a node inside it of side s patches splits iff
+    s > min_leaf and float32(count) > float32(tau) * float32(area in pixels);
+    children in the order NW, NE, SW, SE, leaves listed depth-first;
   * a leaf's token is the arithmetic mean of the aggregated embeddings (position
     and resolution terms included) of its patches; decompression gives every
     patch its leaf's token.
@@ -154,15 +156,17 @@ def quadtree_leaves(edges, p: int, max_leaf: int, min_leaf: int, tau: float):
     """edges[H, W] (one sample) -> list of leaves (y0, x0, s) in patch units."""
     H, W = edges.shape
     Hp, Wp = H // p, W // p
-    assert Hp % max_leaf == 0 and Wp % max_leaf == 0
     e = np.asarray(edges, np.int64)
     tau32 = np.float32(tau)
     leaves = []
 
     def visit(y0, x0, s):
+        if y0 >= Hp or x0 >= Wp:
+            return                                             # wholly in the padding
+        inside = y0 + s <= Hp and x0 + s <= Wp
         cnt = int(e[y0 * p:(y0 + s) * p, x0 * p:(x0 + s) * p].sum())
         area = (s * p) * (s * p)
-        if s > min_leaf and np.float32(cnt) > np.float32(tau32 * np.float32(area)):
+        if not inside or (s > min_leaf and np.float32(cnt) > np.float32(tau32 * np.float32(area))):
             h = s // 2
             visit(y0, x0, h)
             visit(y0, x0 + h, h)

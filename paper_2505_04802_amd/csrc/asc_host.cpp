@@ -110,7 +110,7 @@ void canny(const std::vector<int32_t> &q, int H, int W, int low, int high, std::
 
 struct TreeBuilder {
   const std::vector<int64_t> &sat;   // summed-area table of edge counts per patch, (Hp+1) x (Wp+1)
-  int Wp, p, min_leaf;
+  int Hp, Wp, p, min_leaf;
   float tau;
   int32_t *ly, *lx, *ls, *patch_leaf;
   int64_t n;                          // leaves written so far (batch-wide)
@@ -120,9 +120,11 @@ struct TreeBuilder {
     return sat[(y0 + s) * w + x0 + s] - sat[y0 * w + x0 + s] - sat[(y0 + s) * w + x0] + sat[y0 * w + x0];
   }
   void visit(int y0, int x0, int s) {
+    if (y0 >= Hp || x0 >= Wp) return;                     // wholly in the padding of a ragged grid
+    const bool inside = y0 + s <= Hp && x0 + s <= Wp;     // a node that sticks out always splits
     const float area = static_cast<float>(static_cast<int64_t>(s) * p * s * p);
     const float bound = tau * area;
-    if (s > min_leaf && static_cast<float>(count(y0, x0, s)) > bound) {
+    if (!inside || (s > min_leaf && static_cast<float>(count(y0, x0, s)) > bound)) {
       const int h = s / 2;
       visit(y0, x0, h);
       visit(y0, x0 + h, h);
@@ -150,7 +152,7 @@ extern "C" int reslim_asc_build(const float *images, int32_t batch, int32_t H, i
     return RESLIM_EINVAL;
   if (!pow2(max_leaf) || !pow2(min_leaf) || min_leaf > max_leaf || H % patch || W % patch) return RESLIM_ESHAPE;
   const int Hp = H / patch, Wp = W / patch;
-  if (Hp % max_leaf || Wp % max_leaf || static_cast<int64_t>(batch) * Hp * Wp > INT32_MAX) return RESLIM_ESHAPE;
+  if (static_cast<int64_t>(batch) * Hp * Wp > INT32_MAX) return RESLIM_ESHAPE;
   const size_t npix = static_cast<size_t>(H) * W, N = static_cast<size_t>(Hp) * Wp;
   std::vector<int32_t> q;
   std::vector<uint8_t> edges;
@@ -169,7 +171,7 @@ extern "C" int reslim_asc_build(const float *images, int32_t batch, int32_t H, i
           for (int j = 0; j < patch; ++j) c += edges[static_cast<size_t>(py * patch + i) * W + px * patch + j];
         sat[(py + 1) * w + px + 1] = c + sat[py * w + px + 1] + sat[(py + 1) * w + px] - sat[py * w + px];
       }
-    TreeBuilder tb{sat, Wp, patch, min_leaf, tau, leaf_y0, leaf_x0, leaf_s, patch_leaf + b * N, n};
+    TreeBuilder tb{sat, Hp, Wp, patch, min_leaf, tau, leaf_y0, leaf_x0, leaf_s, patch_leaf + b * N, n};
     for (int ry = 0; ry < Hp; ry += max_leaf)
       for (int rx = 0; rx < Wp; rx += max_leaf) tb.visit(ry, rx, max_leaf);
     n = tb.n;

@@ -23,6 +23,8 @@ def fields(seed, B_, H, W, smooth):
     (2, (1, 32, 32), 4, 4, 1, 40, 90, 0.10, 1.0),
     (3, (2, 40, 56), 1, 8, 1, 30, 70, 0.08, 2.5),       # patch 1: 40 x 56 grid, roots of 8
     (4, (1, 96, 160), 2, 16, 1, 25, 50, 0.04, 4.0),
+    (5, (2, 36, 60), 2, 8, 1, 20, 60, 0.05, 2.0),        # 18 x 30 patches: no multiple of the root size
+    (6, (1, 180, 360), 2, 16, 2, 30, 70, 0.05, 3.0),     # the paper's 112 km grid: 90 x 180 patches
 ])
 def test_builder_matches_oracle(seed, shape, patch, mx, mn, low, high, tau, smooth):
     imgs = fields(seed, *shape, smooth)
@@ -61,8 +63,8 @@ def test_builder_extremes_and_errors():
     assert (same["leaf_s"] == 4).all()
     with pytest.raises(B.ReslimError):
         B.reslim_asc_build(step, 2, 3, 1, 10, 20, 0.01)              # not a power of two
-    with pytest.raises(B.ReslimError):
-        B.reslim_asc_build(step, 2, 16, 1, 10, 20, 0.01)             # 8 x 16 grid not divisible by 16
+    big = B.reslim_asc_build(step, 2, 16, 1, 10, 20, 0.01)           # 8 x 16 patches under roots of 16: they stick out and split
+    assert (big["leaf_s"] ** 2).sum() == 8 * 16 and big["leaf_s"].max() == 8
     with pytest.raises(B.ReslimError):
         B.reslim_asc_build(step, 2, 4, 1, 30, 20, 0.01)              # low > high
     with pytest.raises(B.ReslimError):

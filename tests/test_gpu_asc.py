@@ -24,6 +24,9 @@ ASC_BF16 = WL.ReslimConfig("abf", batch=2, in_vars=3, out_vars=3, H=64, W=96, sc
                            embed_dim=128, heads=2, mlp_ratio=4, depth=2, tiles_y=1, tiles_x=1,
                            halo=0, dtype=1, seed=22)       # dh = 64; up to 1536 tokens per sample before compression
 ASC_BF16_DH128 = ASC_BF16.with_(name="abf128", embed_dim=256, heads=2, seed=23)
+# grids that are no multiple of the root size (18 x 30 and 22 x 38 patches under roots of 8)
+ASC_F32_RAGGED = ASC_F32.with_(name="a32r", H=36, W=60, seed=24)
+ASC_BF16_RAGGED = ASC_BF16.with_(name="abfr", H=44, W=76, seed=25)
 
 
 def cuda(a, dtype=torch.float32):
@@ -77,7 +80,7 @@ def test_image_and_compress_parity(cfg):
             B.reslim_asc_plan_destroy(plan)
 
 
-@pytest.mark.parametrize("cfg", [ASC_F32, ASC_BF16, ASC_BF16_DH128], ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", [ASC_F32, ASC_BF16, ASC_BF16_DH128, ASC_F32_RAGGED, ASC_BF16_RAGGED], ids=lambda c: c.name)
 def test_compressed_forward_parity(cfg):
     say(f"asc forward {cfg.name}")
     w = WL.make_weights(cfg, std=0.05)

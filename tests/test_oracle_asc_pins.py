@@ -128,10 +128,13 @@ def _check_tree(edges, leaves, p, max_leaf, min_leaf, tau):
     Hp, Wp = H // p, W // p
     cover = np.zeros((Hp, Wp), int)
     def dens_split(y0, x0, s):
+        if y0 + s > Hp or x0 + s > Wp:
+            return True                                         # sticks out of a ragged grid: always splits
         cnt = edges[y0 * p:(y0 + s) * p, x0 * p:(x0 + s) * p].sum()
         return s > min_leaf and np.float32(cnt) > np.float32(np.float32(tau) * np.float32((s * p) ** 2))
     for (y0, x0, s) in leaves:
-        assert s >= min_leaf and s <= max_leaf and (s & (s - 1)) == 0 and y0 % s == 0 and x0 % s == 0
+        assert s >= 1 and s <= max_leaf and (s & (s - 1)) == 0 and y0 % s == 0 and x0 % s == 0
+        assert y0 + s <= Hp and x0 + s <= Wp
         cover[y0:y0 + s, x0:x0 + s] += 1
         assert not dens_split(y0, x0, s)                        # a leaf does not split
         a = 2 * s
@@ -157,6 +160,16 @@ def test_quadtree_properties_and_extremes():
     assert full[:4] == [(0, 0, 1), (0, 1, 1), (1, 0, 1), (1, 1, 1)]
     assert full[4] == (0, 2, 1) and full[8] == (2, 0, 1) and full[12] == (2, 2, 1) and full[16] == (0, 4, 1) and full[64] == (0, 8, 1)
     assert all(s >= 2 for _, _, s in A.quadtree_leaves(np.ones((32, 48), bool), p, mx, 2, 0.05))
+    # a grid that is no multiple of the root size (18 x 30 patches, roots of 8): the paper's 90 x 180
+    # patch grid is of this kind; nodes that stick out split, what lies inside follows the density rule
+    ragged = edges[:36, :60]
+    for tau in (0.02, 0.2, 2.0):
+        leaves = A.quadtree_leaves(ragged, p, mx, mn, tau)
+        _check_tree(ragged, leaves, p, mx, mn, tau)
+    no_edges = A.quadtree_leaves(np.zeros((36, 60), bool), p, mx, mn, 0.05)
+    assert sum(s * s for _, _, s in no_edges) == 18 * 30
+    assert [l for l in no_edges if l[2] == 8] == [(y, x, 8) for y in (0, 8) for x in (0, 8, 16)]
+    assert (16, 0, 2) in no_edges and (0, 24, 4) in no_edges and (16, 28, 2) in no_edges and all(s < 8 for y, x, s in no_edges if y >= 16 or x >= 24)
 
 
 def test_compress_decompress_means_and_identity():
