@@ -307,3 +307,36 @@ def test_block_training_on_the_leaves(cfg):
                                                       saved.data_ptr(), sb, ws.data_ptr(), wb, st) == B.RESLIM_EINVAL
         finally:
             B.reslim_asc_plan_destroy(plan)
+
+
+def test_compressed_forward_at_the_papers_grid():
+    """Table 2(b)'s own workload: the 9.5M model on the 112 km grid ([180, 360, 23] in,
+    90 x 180 patches, no multiple of the root size) as one tile, the benchmark's ~7x
+    quad-tree; whole output against the oracle, library builder against the oracle's."""
+    import bench
+    cfg = WL.CONFIGS["m9m"].with_(tiles_y=1, tiles_x=1, halo=0)
+    prm = bench.ASC_PARAMS_BY_WORKLOAD["m9m"][0]
+    w = WL.make_weights(cfg)
+    x = WL.make_fields(cfg)
+    imgs = np.ascontiguousarray(x[:, 0])
+    args = (cfg.patch, prm["max_leaf"], prm["min_leaf"], prm["canny_low"], prm["canny_high"], prm["tau"])
+    tab = A.build(imgs, *args)
+    lib = B.reslim_asc_build(imgs, *args)
+    for k in tab:
+        assert (np.asarray(tab[k]) == np.asarray(lib[k])).all(), k
+    L = len(tab["leaf_s"])
+    say(f"asc paper grid: {cfg.n_tokens} patches -> {L} leaves; oracle forward ...")
+    assert 4 * L < cfg.n_tokens
+    ref = A.forward_compressed(x, w, cfg, tab)
+    with B.Reslim(cfg, w) as m:
+        plan = B.reslim_asc_plan_create(m.ctx, cfg.batch, tab)
+        try:
+            y = torch.full((cfg.batch, cfg.out_vars, cfg.H * cfg.scale, cfg.W * cfg.scale), float("nan"),
+                           dtype=torch.float32, device="cuda")
+            B.reslim_asc_forward(m.ctx, plan, cuda(x), y, m.ws)
+            out = y.cpu().numpy()
+        finally:
+            B.reslim_asc_plan_destroy(plan)
+    err = max(O.rel_l2(out[b, c], ref[b, c]) for b in range(cfg.batch) for c in range(cfg.out_vars))
+    say(f"  max rel-L2 over planes {err:.3e}")
+    assert np.isfinite(out).all() and err <= TOL[1]
