@@ -6,8 +6,7 @@ with the HIP library and is imported only by tests, the smoke check and the
 benchmark's CPU-baseline leg.  Library primitives used as steps: `@` (matmul),
 `np.exp`, `scipy.special.erf`.
 
-Where the paper is silent the reading taken is stated beside the function (the
-full list sits in the design notes).  Parts whose *choice of operation* the paper
+Where the paper is silent the reading taken is stated beside the function.  Parts whose *choice of operation* the paper
 does not fix (the residual path's upsampler and kernel, the decoder reduced to a
 linear projection) are "parity unpinned" against the paper; they are pinned only
 against textbook definitions (bilinear interpolation, zero-padded correlation).
@@ -539,7 +538,7 @@ def rel_l2(a, ref) -> float:
 # Sec. 4.1, "Bayesian Training Loss" (the paper's one equation): a latitude-weighted
 # squared error plus a total-variation prior over each pixel's spatial neighbours,
 #     || y - x ||_D^2  +  sum_k sum_i sum_{j in C(i)} b_ij | x_ki - x_kj | .
-# Readings where the text is silent (listed in the design notes):
+# Readings where the text is silent:
 #  * D = diag of cos(latitude of the pixel row), divided by its mean over the rows;
 #    rows are the centres of an equiangular grid between lat_min and lat_max;
 #  * C(i) = the 8 nearest pixels, clipped at the domain edge (no wrap-around);
