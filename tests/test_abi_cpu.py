@@ -61,6 +61,7 @@ def test_create_rejects_bad_configs_before_touching_the_gpu():
     for kw, code in [(dict(H=33), B.RESLIM_ESHAPE), (dict(heads=3), B.RESLIM_ESHAPE),
                      (dict(out_vars=3), B.RESLIM_ESHAPE), (dict(res_idx=5), B.RESLIM_ESHAPE),
                      (dict(dtype=7), B.RESLIM_EINVAL), (dict(dtype=1), B.RESLIM_ESHAPE),   # dh = 32 on the bf16 path
+                     (dict(dtype=1, heads=2, scale=1, out_vars=1), B.RESLIM_ESHAPE),          # bf16 head narrower than 8 columns
                      (dict(scale=0), B.RESLIM_ESHAPE)]:
         with pytest.raises(B.ReslimError) as e:
             B.reslim_create(base.with_(**kw), w)
