@@ -73,3 +73,25 @@ def test_builder_extremes_and_errors():
     bad[0, 3, 3] = np.inf
     with pytest.raises(B.ReslimError):
         B.reslim_asc_build(bad, 2, 4, 1, 10, 20, 0.01)
+
+
+def test_builder_matches_oracle_on_random_shapes():
+    """Forty seeded draws of grid shape (mostly no multiple of the root size), patch
+    size, leaf bounds, thresholds and field smoothness: identical tables."""
+    r = np.random.default_rng(2024)
+    for trial in range(40):
+        patch = int(r.choice([1, 2, 4]))
+        Hp, Wp = int(r.integers(3, 40)), int(r.integers(3, 56))
+        mx = int(r.choice([1, 2, 4, 8, 16]))
+        mn = int(r.choice([m for m in (1, 2, 4, 8, 16) if m <= mx]))
+        low = int(r.integers(0, 80))
+        high = low + int(r.integers(0, 120))
+        tau = float(r.choice([0.0, 0.01, 0.05, 0.2, 1.0]))
+        Bn = int(r.integers(1, 4))
+        imgs = fields(1000 + trial, Bn, Hp * patch, Wp * patch, float(r.uniform(0.5, 4.0)))
+        if trial % 7 == 0:
+            imgs[0] = 1.0                                                  # a constant sample among the others
+        got = B.reslim_asc_build(imgs, patch, mx, mn, low, high, tau)
+        ref = A.build(imgs, patch, mx, mn, low, high, tau)
+        for k in KEYS:
+            assert np.array_equal(np.asarray(got[k]), np.asarray(ref[k])), (trial, k, Hp, Wp, patch, mx, mn, low, high, tau)
