@@ -47,6 +47,7 @@ struct AttnBwdArgs {
   bf16_t *dqkv;          // [B, n_h, 3, heads, dh]
   const tile_desc *tiles;
   int T, heads, D, QB, total;
+  int part;              // which 1/NSPLIT of the head's features this launch accumulates and writes
   int64_t n_h;
   int64_t aux_stride;    // records per array
   float c;               // MFMA output -> base-2 logit: log2(e) / sqrt(dh)   (1 when q is pre-scaled)
@@ -109,7 +110,10 @@ __device__ __forceinline__ uint64_t tr_issue(unsigned addr) {
 // register file next to the stationary fragments: dh = 128).
 // QS: q in qkv already carries the factor log2(e)/sqrt(dh) (as the fused QKV epilogue of the
 // block leaves it): the MFMA output is the base-2 logit itself.
-template <int DH, int BS, int MODE, bool QS, int MINW, int NST>
+// NSPLIT: a launch accumulates only DH / NSPLIT of the head's output features (a.part says which)
+// and recomputes the scores for each part; for heads whose full accumulators do not fit the
+// register file next to the stationary fragments (dh = 256).
+template <int DH, int BS, int MODE, bool QS, int MINW, int NST, int NSPLIT = 1>
 __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a) {
   constexpr bool KV = MODE != 0;          // keys stationary
   constexpr bool DP = MODE != 2;          // dP = dO V^T is needed
@@ -125,7 +129,7 @@ __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a)
   constexpr int AUXL = AUXB / 1024;       // wave-loads of the record block
   constexpr int STAGE = 2 * TILE_B + AUXB;
   constexpr int LPW = TILE_B / 1024 / NW;
-  constexpr int NKT = BS / 32, NKS = DH / 16, NDT = DH / 32;
+  constexpr int NKT = BS / 32, NKS = DH / 16, NDT = DH / 32 / NSPLIT;   // NDT: 32-feature blocks of the accumulators
   constexpr bool HAND = DH <= 128;        // transposing reads issued by hand (see attention_common.h); needs a spill-free kernel
   static_assert(TILE_B % (1024 * NW) == 0 && AUXB % 1024 == 0 && NST * STAGE <= 160 * 1024, "LDS plan");
   static_assert((NST == 2 || NST == 3) && NKT <= 2, "ring of two or three stages of 32 or 64 tokens");
@@ -265,7 +269,7 @@ __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a)
     const int vr = 8 * hi + 4 * e + (L16 >> 2);
 #pragma unroll
     for (int d = 0; d < NDT; ++d) {
-      const int o = 32 * d + 16 * ((lane >> 4) & 1) + 4 * (L16 & 3);
+      const int o = 32 * (d + a.part * NDT) + 16 * ((lane >> 4) & 1) + 4 * (L16 & 3);
       t_addr[e][d] = vr * ROWB + (((o >> 3) ^ swz(vr)) << 4) + ((o >> 2) & 1) * 8;
     }
   }
@@ -468,8 +472,8 @@ __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a)
     // ---- end of a unit: scale, round and store this lane's row of each gradient
     const int xrow = cur.r0 + wave * 32 + l32;
     if (active && xrow < cur.n_t) {
-      bf16_t *p1 = a.dqkv + cur.q_off + (KV ? a.D : 0) + static_cast<size_t>(xrow) * ldq + hi * 4;
-      bf16_t *p2 = a.dqkv + cur.q_off + 2 * a.D + static_cast<size_t>(xrow) * ldq + hi * 4;
+      bf16_t *p1 = a.dqkv + cur.q_off + (KV ? a.D : 0) + static_cast<size_t>(xrow) * ldq + hi * 4 + a.part * NDT * 32;
+      bf16_t *p2 = a.dqkv + cur.q_off + 2 * a.D + static_cast<size_t>(xrow) * ldq + hi * 4 + a.part * NDT * 32;
       const float sc1 = KV ? a.sck : a.scq;
 #pragma unroll
       for (int d = 0; d < NDT; ++d)
@@ -593,11 +597,13 @@ hipError_t attention_bwd_init() {
   if (e != hipSuccess) return e;
   // the kernels at dh = 256 need 96 .. 99 KiB of LDS, above the default limit of a launch
   g_bwd_dh256_ok = true;
-  const void *big[] = {reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<256, 32, 0, false, 1, 3>),
-                       reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<256, 32, 0, true, 1, 3>),
-                       reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<256, 32, 1, false, 1, 3>),
-                       reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<256, 32, 1, true, 1, 3>)};
-  for (int i = 0; i < 4; ++i) {
+  const void *big[] = {reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<256, 32, 0, false, 1, 3, 2>),
+                       reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<256, 32, 0, true, 1, 3, 2>),
+                       reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<256, 32, 2, false, 1, 3, 2>),
+                       reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<256, 32, 2, true, 1, 3, 2>),
+                       reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<256, 32, 3, false, 1, 3, 2>),
+                       reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<256, 32, 3, true, 1, 3, 2>)};
+  for (int i = 0; i < 6; ++i) {
     e = hipFuncSetAttribute(big[i], hipFuncAttributeMaxDynamicSharedMemorySize, bwd_lds_bytes<256, 32, 3>(i >= 2));
     if (e != hipSuccess) {            // not fatal: only the dh = 256 gradient is refused
       (void)hipGetLastError();
@@ -612,18 +618,25 @@ size_t tiles_attention_bwd_ws_bytes(const reslim_ctx *c, int batch, const SeqGeo
   return c->cfg.dtype == RESLIM_BF16 ? align256(recs * 32) : align256(recs * 4);
 }
 
-template <int DH, int BS, int MODE, bool QS, int MINW, int NST>
-static hipError_t launch_bwd_one(const AttnBwdArgs &a, hipStream_t st) {
-  const int g = a.total < MINW * g_bwd_cus ? a.total : MINW * g_bwd_cus;    // persistent grid
-  attn_bwd_bf16_kernel<DH, BS, MODE, QS, MINW, NST><<<dim3(g), dim3(256), bwd_lds_bytes<DH, BS, NST>(MODE != 0), st>>>(a);
-  return hipGetLastError();
+template <int DH, int BS, int MODE, bool QS, int MINW, int NST, int NSPLIT = 1>
+static hipError_t launch_bwd_one(const AttnBwdArgs &a0, hipStream_t st) {
+  const int g = a0.total < MINW * g_bwd_cus ? a0.total : MINW * g_bwd_cus;    // persistent grid
+  AttnBwdArgs a = a0;
+  for (a.part = 0; a.part < NSPLIT; ++a.part) {
+    attn_bwd_bf16_kernel<DH, BS, MODE, QS, MINW, NST, NSPLIT><<<dim3(g), dim3(256), bwd_lds_bytes<DH, BS, NST>(MODE != 0), st>>>(a);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 // Launch shapes (measured on MI355X): dh = 64: 64-token blocks, three stages; the dQ kernel fits
 // 168 registers = three work-groups per CU, the dK/dV kernel (197) two.  dh = 128: dK and dV in
 // separate passes (their accumulators together with the stationary fragments exceed the register
 // file); dQ and dK need ~360 registers and run one work-group per CU without spills (c4: 12.8 ms
-// against 17.4 ms with two spilling work-groups), dV fits two.  dh = 256: one work-group per CU.
+// against 17.4 ms with two spilling work-groups), dV fits two.  dh = 256: the same three passes, each
+// once per half of the head's features (353 .. 458 registers, no spills, one work-group per CU; the
+// 10B model's block: 13.5 ms against 40.5 ms for unsplit passes that spilled 130 .. 145 registers).
 template <bool QS>
 static hipError_t launch_bwd_all(const AttnBwdArgs &a, int dh, hipStream_t st) {
   hipError_t e;
@@ -637,8 +650,9 @@ static hipError_t launch_bwd_all(const AttnBwdArgs &a, int dh, hipStream_t st) {
       return e != hipSuccess ? e : launch_bwd_one<128, 32, 3, QS, 1, 3>(a, st);
     case 256:
       if (!g_bwd_dh256_ok) return hipErrorInvalidValue;
-      e = launch_bwd_one<256, 32, 0, QS, 1, 3>(a, st);
-      return e != hipSuccess ? e : launch_bwd_one<256, 32, 1, QS, 1, 3>(a, st);
+      e = launch_bwd_one<256, 32, 0, QS, 1, 3, 2>(a, st);
+      if (e == hipSuccess) e = launch_bwd_one<256, 32, 2, QS, 1, 3, 2>(a, st);
+      return e != hipSuccess ? e : launch_bwd_one<256, 32, 3, QS, 1, 3, 2>(a, st);
     default: return hipErrorInvalidValue;
   }
 }

@@ -160,6 +160,105 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const float *__restr
   }
 }
 
+// Sum of one value per thread over the 256 threads of a work-group, in a fixed order, the same in
+// every thread.  box: four floats of LDS that no other reduction still in flight uses.
+__device__ __forceinline__ float wg_sum(float v, float *box, int lane, int wave) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  if (lane == 0) box[wave] = v;
+  __syncthreads();
+  return (box[0] + box[1]) + (box[2] + box[3]);
+}
+
+// The same gradient for wide rows (D above 2048), where one wave can no longer keep a row, its
+// gradient and the column sums in registers: the whole work-group takes one row at a time, thread t
+// owns the float4 columns t, t + 256, ... and keeps their sums of dy*xh and dy over the slab's rows,
+// so the partial row pair is written straight from registers.  The four reductions of a row use
+// four boxes in turn; a box is written again only after three later barriers.
+template <class T, int NVT>
+__global__ __launch_bounds__(256) void layernorm_bwd_wide_kernel(const float *__restrict__ x, const T *__restrict__ dy,
+                                                                 const float *__restrict__ g, const float *__restrict__ res,
+                                                                 float *__restrict__ dx_out, T *__restrict__ act_out,
+                                                                 float *__restrict__ partial, int64_t rows,
+                                                                 int rows_per_wg, int D) {
+  __shared__ float box[4][4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nv = D / 4;
+  const int64_t r0 = static_cast<int64_t>(blockIdx.x) * rows_per_wg;
+  const int64_t r1 = r0 + rows_per_wg < rows ? r0 + rows_per_wg : rows;
+  const float4 *g4 = reinterpret_cast<const float4 *>(g);
+  const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+  float4 gam[NVT], sg[NVT], sb[NVT];
+#pragma unroll
+  for (int i = 0; i < NVT; ++i) {
+    const int k = static_cast<int>(threadIdx.x) + 256 * i;
+    gam[i] = k < nv ? g4[k] : zero;
+    sg[i] = sb[i] = zero;
+  }
+  const float inv_d = 1.0f / static_cast<float>(D);
+  for (int64_t row = r0; row < r1; ++row) {
+    const float4 *xr = reinterpret_cast<const float4 *>(x + row * D);
+    float4 v[NVT], d[NVT];
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < NVT; ++i) {
+      const int k = static_cast<int>(threadIdx.x) + 256 * i;
+      v[i] = k < nv ? xr[k] : zero;
+      d[i] = k < nv ? Vec4<T>::load(dy + row * D + 4 * k) : zero;
+      sum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+    }
+    const float mean = wg_sum(sum, box[0], lane, wave) * inv_d;
+    float sq = 0.f;
+#pragma unroll
+    for (int i = 0; i < NVT; ++i) {
+      const int k = static_cast<int>(threadIdx.x) + 256 * i;
+      if (k < nv) {
+        v[i].x -= mean; v[i].y -= mean; v[i].z -= mean; v[i].w -= mean;
+        sq += (v[i].x * v[i].x + v[i].y * v[i].y) + (v[i].z * v[i].z + v[i].w * v[i].w);
+      }
+    }
+    const float rstd = rsqrtf(wg_sum(sq, box[1], lane, wave) * inv_d + 1e-5f);
+    float m1 = 0.f, m2 = 0.f;      // sums of g and g * xh
+#pragma unroll
+    for (int i = 0; i < NVT; ++i) {
+      v[i].x *= rstd; v[i].y *= rstd; v[i].z *= rstd; v[i].w *= rstd;      // xh
+      sg[i].x += d[i].x * v[i].x; sg[i].y += d[i].y * v[i].y; sg[i].z += d[i].z * v[i].z; sg[i].w += d[i].w * v[i].w;
+      sb[i].x += d[i].x; sb[i].y += d[i].y; sb[i].z += d[i].z; sb[i].w += d[i].w;
+      d[i].x *= gam[i].x; d[i].y *= gam[i].y; d[i].z *= gam[i].z; d[i].w *= gam[i].w;  // g
+      m1 += (d[i].x + d[i].y) + (d[i].z + d[i].w);
+      m2 += (d[i].x * v[i].x + d[i].y * v[i].y) + (d[i].z * v[i].z + d[i].w * v[i].w);
+    }
+    m1 = wg_sum(m1, box[2], lane, wave) * inv_d;
+    m2 = wg_sum(m2, box[3], lane, wave) * inv_d;
+#pragma unroll
+    for (int i = 0; i < NVT; ++i) {
+      const int k = static_cast<int>(threadIdx.x) + 256 * i;
+      if (k < nv) {
+        float4 o4;
+        o4.x = (d[i].x - m1 - v[i].x * m2) * rstd;
+        o4.y = (d[i].y - m1 - v[i].y * m2) * rstd;
+        o4.z = (d[i].z - m1 - v[i].z * m2) * rstd;
+        o4.w = (d[i].w - m1 - v[i].w * m2) * rstd;
+        if (res) {
+          const float4 rr = reinterpret_cast<const float4 *>(res + row * D)[k];
+          o4.x += rr.x; o4.y += rr.y; o4.z += rr.z; o4.w += rr.w;
+        }
+        reinterpret_cast<float4 *>(dx_out + row * D)[k] = o4;
+        if (act_out) Vec4<T>::store(act_out + row * D + 4 * k, o4);
+      }
+    }
+  }
+  float4 *pg = reinterpret_cast<float4 *>(partial + static_cast<size_t>(blockIdx.x) * 2 * D);
+#pragma unroll
+  for (int i = 0; i < NVT; ++i) {
+    const int k = static_cast<int>(threadIdx.x) + 256 * i;
+    if (k < nv) {
+      pg[k] = sg[i];
+      pg[nv + k] = sb[i];
+    }
+  }
+}
+
 // out[j] = sum over p < n_part of partial[p * stride + j] in a fixed order (deterministic).
 // A work-group owns 32 columns; its 8 row groups each add every 8th partial row (four
 // independent running sums per thread keep loads in flight), then the groups are added in order.
@@ -197,6 +296,9 @@ hipError_t launch_partial_reduce(const float *partial, float *out, int n_part, i
   return hipGetLastError();
 }
 
+// rows of 64 float4 from which the work-group-per-row kernel takes over (D above 1024 .. 2048)
+constexpr int kLnBwdWideFrom = 5;
+
 int layernorm_bwd_slabs(int64_t rows) { return static_cast<int>(rows < 4096 ? (rows + 3) / 4 : 1024); }
 
 template <class T>
@@ -208,18 +310,22 @@ static hipError_t launch_ln_bwd_t(const float *x, const void *dy, const float *g
   const int rpw = static_cast<int>((rows + n_wg - 1) / n_wg);
   n_wg = static_cast<int>((rows + rpw - 1) / rpw);
   const size_t lds = static_cast<size_t>(2) * D * sizeof(float);
-  if (lds > 60 * 1024) return hipErrorInvalidValue;
   const dim3 grid(n_wg), blk(256);
   const T *d = static_cast<const T *>(dy);
   T *ao = static_cast<T *>(act_out);
 #define RESLIM_LNB(NV) layernorm_bwd_kernel<T, NV><<<grid, blk, lds, st>>>(x, d, g, res, dx_out, ao, partial, rows, rpw, D)
+#define RESLIM_LNW(NVT) layernorm_bwd_wide_kernel<T, NVT><<<grid, blk, 0, st>>>(x, d, g, res, dx_out, ao, partial, rows, rpw, D)
   if (nv <= 1) RESLIM_LNB(1);
   else if (nv <= 2) RESLIM_LNB(2);
   else if (nv <= 4) RESLIM_LNB(4);
-  else if (nv <= 8) RESLIM_LNB(8);
-  else if (nv <= 16) RESLIM_LNB(16);      // D = 4096: the row and its sums exceed the register file (slow, correct)
-  else return hipErrorInvalidValue;
+  else if (nv < kLnBwdWideFrom) RESLIM_LNB(8);
+  else if (nv <= 8) RESLIM_LNW(2);        // a work-group per row from here on: thread t owns columns t, t + 256, ...
+  else if (nv <= 16) RESLIM_LNW(4);
+  else if (nv <= 32) RESLIM_LNW(8);
+  else if (nv <= 64) RESLIM_LNW(16);
+  else return hipErrorInvalidValue;       // D above 16384
 #undef RESLIM_LNB
+#undef RESLIM_LNW
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   // partial rows are [d gamma | d beta] pairs of 2 D floats

@@ -18,6 +18,13 @@ from test_gpu_parity import SMALL_F32, SMALL_BF16, SMALL_BF16_DH128, TOL, cuda, 
 
 pytestmark = pytest.mark.gpu
 CFGS = [SMALL_F32, SMALL_BF16, SMALL_BF16_DH128]
+# wide rows: from 1280 columns on a whole work-group takes a row of the LayerNorm gradient; 1280 and
+# 2304 leave the last column group of a thread partly empty, 3072 and 8192 are the 1B and 10B widths
+WIDE_LN = [SMALL_BF16_DH128.with_(name=f"w{d}", embed_dim=d, heads=h, depth=1, mlp_ratio=1, batch=1)
+           for d, h in ((1280, 10), (2304, 18), (3072, 24), (8192, 32))]
+WIDE_LN.append(SMALL_F32.with_(name="w2304_f32", embed_dim=2304, heads=18, depth=1, mlp_ratio=1, batch=1))
+WIDE_BLOCK = [SMALL_BF16_DH128.with_(name="w3072_block", embed_dim=3072, heads=24, depth=1, batch=1),
+              SMALL_BF16_DH128.with_(name="w8192_block", embed_dim=8192, heads=32, depth=1, mlp_ratio=1, batch=1)]
 
 
 def u8(n):
@@ -29,10 +36,10 @@ def rnd(shape, seed, bf16):
     return WL.round_to_bf16(a) if bf16 else a
 
 
-@pytest.mark.parametrize("cfg", CFGS, ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", CFGS + WIDE_LN, ids=lambda c: c.name)
 def test_layernorm_bwd_parity(cfg):
     D, bf = cfg.embed_dim, cfg.dtype == 1
-    rows = 1237                                     # several slabs of rows and a ragged last one
+    rows = 1237 if D <= 4096 else 4099              # several slabs of rows and a ragged last one
     x = rnd((rows, D), 1, False) * 1.5 + 0.3
     dy = rnd((rows, D), 2, bf)
     res = rnd((rows, D), 3, False)
@@ -78,12 +85,14 @@ def test_linear_bwd_parity(cfg, which):
             assert err <= tol, nm                # dw, db: exact products of the given inputs, fp32 sums
 
 
-@pytest.mark.parametrize("cfg", CFGS, ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", CFGS + WIDE_BLOCK, ids=lambda c: c.name)
 def test_block_train_parity(cfg):
     """Forward-for-training and backward of one block on the tile-major stream."""
     tiles, _, _, n_h = O.tiles_partition(cfg.Hp, cfg.Wp, cfg.tiles_y, cfg.tiles_x, cfg.halo)
-    D, layer = cfg.embed_dim, 1
-    w = weights_for(cfg, std=0.1)                 # wide weights: softmaxes and GELUs far from linear
+    D, layer = cfg.embed_dim, cfg.depth - 1
+    # wide weights: softmaxes and GELUs far from linear (scaled down with the width, so that the
+    # pre-activations keep that spread)
+    w = weights_for(cfg, std=0.1 if D <= 256 else 0.1 * (256.0 / D) ** 0.5)
     x = rnd((cfg.batch, n_h, D), 30, False)
     d_out = rnd((cfg.batch, n_h, D), 31, False)
     ref_out = O.reslim_block(x, tiles, w, layer, cfg.heads)
