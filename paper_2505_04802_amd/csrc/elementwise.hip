@@ -77,6 +77,74 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float *__restrict_
   }
 }
 
+// Rows wider than 4096 columns: a whole work-group per row, thread t owns the float4 columns
+// t, t + 256, ... (a wave would need 128+ registers for the row alone).
+template <class T, int NVT>
+__global__ __launch_bounds__(256) void layernorm_wide_kernel(const float *__restrict__ x, const int32_t *__restrict__ row_src,
+                                                             int rows_per_sample_out, int64_t rows_per_sample_in,
+                                                             const float *__restrict__ g, const float *__restrict__ be,
+                                                             T *__restrict__ out, int D) {
+  __shared__ float box[2][4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t row = blockIdx.x;
+  int64_t in_row = row;
+  if (row_src) {
+    const int64_t b = row / rows_per_sample_out;
+    in_row = b * rows_per_sample_in + row_src[row % rows_per_sample_out];
+  }
+  const float4 *xr = reinterpret_cast<const float4 *>(x + in_row * D);
+  const int nv = D / 4;
+  float4 v[NVT];
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < NVT; ++i) {
+    const int k = static_cast<int>(threadIdx.x) + 256 * i;
+    v[i] = k < nv ? xr[k] : make_float4(0.f, 0.f, 0.f, 0.f);
+    sum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+  if (lane == 0) box[0][wave] = sum;
+  __syncthreads();
+  const float mean = ((box[0][0] + box[0][1]) + (box[0][2] + box[0][3])) / static_cast<float>(D);
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < NVT; ++i) {
+    const int k = static_cast<int>(threadIdx.x) + 256 * i;
+    if (k < nv) {
+      const float a = v[i].x - mean, b = v[i].y - mean, c = v[i].z - mean, d = v[i].w - mean;
+      sq += (a * a + b * b) + (c * c + d * d);
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) sq += __shfl_xor(sq, o);
+  if (lane == 0) box[1][wave] = sq;
+  __syncthreads();
+  const float rstd = rsqrtf(((box[1][0] + box[1][1]) + (box[1][2] + box[1][3])) / static_cast<float>(D) + 1e-5f);
+  const float4 *g4 = reinterpret_cast<const float4 *>(g);
+  const float4 *b4 = reinterpret_cast<const float4 *>(be);
+  T *orow = out + row * D;
+#pragma unroll
+  for (int i = 0; i < NVT; ++i) {
+    const int k = static_cast<int>(threadIdx.x) + 256 * i;
+    if (k < nv) {
+      const float4 gg = g4[k], bb = b4[k];
+      const float y0 = (v[i].x - mean) * rstd * gg.x + bb.x;
+      const float y1 = (v[i].y - mean) * rstd * gg.y + bb.y;
+      const float y2 = (v[i].z - mean) * rstd * gg.z + bb.z;
+      const float y3 = (v[i].w - mean) * rstd * gg.w + bb.w;
+      if constexpr (sizeof(T) == 4) {
+        reinterpret_cast<float4 *>(orow)[k] = make_float4(y0, y1, y2, y3);
+      } else {
+        uint2 p;
+        p.x = pack_bf16x2(y0, y1);
+        p.y = pack_bf16x2(y2, y3);
+        reinterpret_cast<uint2 *>(orow)[k] = p;
+      }
+    }
+  }
+}
+
 template <class T>
 static hipError_t launch_ln_t(const float *x, const int32_t *row_src, int rpo, int64_t rpi, const float *g,
                               const float *b, void *out, int64_t rows_out, int D, hipStream_t st) {
@@ -89,8 +157,15 @@ static hipError_t launch_ln_t(const float *x, const int32_t *row_src, int rpo, i
   else if (nv <= 4) RESLIM_LN(4);
   else if (nv <= 8) RESLIM_LN(8);
   else if (nv <= 16) RESLIM_LN(16);
-  else if (nv <= 32) RESLIM_LN(32);
-  else return hipErrorInvalidValue;
+  else {
+    if (rows_out > INT32_MAX) return hipErrorInvalidValue;
+    const dim3 wgrid(static_cast<unsigned>(rows_out));
+#define RESLIM_LNW(NVT) layernorm_wide_kernel<T, NVT><<<wgrid, blk, 0, st>>>(x, row_src, rpo, rpi, g, b, o, D)
+    if (nv <= 32) RESLIM_LNW(8);
+    else if (nv <= 64) RESLIM_LNW(16);
+    else return hipErrorInvalidValue;     // D above 16384
+#undef RESLIM_LNW
+  }
 #undef RESLIM_LN
   return hipGetLastError();
 }
