@@ -130,6 +130,7 @@ __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a)
   constexpr int STAGE = 2 * TILE_B + AUXB;
   constexpr int LPW = TILE_B / 1024 / NW;
   constexpr int NKT = BS / 32, NKS = DH / 16, NDT = DH / 32 / NSPLIT;   // NDT: 32-feature blocks of the accumulators
+  constexpr bool PP = NKT == 2 && DH >= 128;   // wide heads with 64-token blocks: two groups in flight per wave
   constexpr bool HAND = DH <= 128;        // transposing reads issued by hand (see attention_common.h); needs a spill-free kernel
   static_assert(TILE_B % (1024 * NW) == 0 && AUXB % 1024 == 0 && NST * STAGE <= 160 * 1024, "LDS plan");
   static_assert((NST == 2 || NST == 3) && NKT <= 2, "ring of two or three stages of 32 or 64 tokens");
@@ -341,20 +342,46 @@ __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a)
     // The work on one 32-token group of the streamed block, in three phases.
     const unsigned st_off = static_cast<unsigned>(reinterpret_cast<uintptr_t>(
         (__attribute__((address_space(3))) const unsigned char *)st));
-    auto scores = [&](auto kt_c, f32x16 &s, f32x16 &dp) {          // matrix pipe
+    // `between(i)`, i < 16: vector work of ANOTHER group placed behind the MFMAs of this one, so
+    // that one wave keeps both pipes busy (wide heads run a single wave per SIMD)
+    auto scores = [&](auto kt_c, f32x16 &s, f32x16 &dp, auto between) {          // matrix pipe
       constexpr int kt = decltype(kt_c)::value;
+      if constexpr (DH >= 128) {
+        // wide heads: the fragment reads run PF steps ahead of the MFMAs that use them, in a ring
+        // of PF + 1 register sets, and a scheduling barrier per step keeps that order (left to
+        // itself the compiler either waits for every read right before its MFMA or hoists all
+        // reads of the group to its top: 64+ registers of fragments next to the accumulators)
+        constexpr int PF = 2;
+        bf16x8 f1[PF + 1], f2[DP ? PF + 1 : 1];
+        auto fetch = [&](int ks) {
+          const unsigned char *rp = st + kt * 32 * ROWB + y_row + (((2 * ks + hi) ^ y_swz) << 4);
+          f1[ks % (PF + 1)] = *reinterpret_cast<const bf16x8 *>(rp);
+          if constexpr (DP) f2[ks % (PF + 1)] = *reinterpret_cast<const bf16x8 *>(rp + TILE_B);
+        };
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) {
-        const unsigned char *rp = st + kt * 32 * ROWB + y_row + (((2 * ks + hi) ^ y_swz) << 4);
-        const bf16x8 f1 = *reinterpret_cast<const bf16x8 *>(rp);
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, x1f[ks], ks == 0 ? sinit : s, 0, 0, 0);
-        if constexpr (DP) {
-          const bf16x8 f2 = *reinterpret_cast<const bf16x8 *>(rp + TILE_B);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2, x2f[ks], ks == 0 ? dpinit : dp, 0, 0, 0);
+        for (int ks = 0; ks < PF; ++ks) fetch(ks);
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+          if (ks + PF < NKS) fetch(ks + PF);
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1[ks % (PF + 1)], x1f[ks], ks == 0 ? sinit : s, 0, 0, 0);
+          if constexpr (DP) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2[ks % (PF + 1)], x2f[ks], ks == 0 ? dpinit : dp, 0, 0, 0);
+#pragma unroll
+          for (int i = ks * 16 / NKS; i < (ks + 1) * 16 / NKS; ++i) between(i);
+          __builtin_amdgcn_sched_barrier(0);
         }
-        // wide heads: keep the scheduler from hoisting every fragment read of the group to its
-        // top (64+ registers of fragments in flight next to the accumulators = spills)
-        if constexpr (DH >= 128) { if (ks % 2 == 1) __builtin_amdgcn_sched_barrier(0); }
+      } else {
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+          const unsigned char *rp = st + kt * 32 * ROWB + y_row + (((2 * ks + hi) ^ y_swz) << 4);
+          const bf16x8 f1 = *reinterpret_cast<const bf16x8 *>(rp);
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1, x1f[ks], ks == 0 ? sinit : s, 0, 0, 0);
+          if constexpr (DP) {
+            const bf16x8 f2 = *reinterpret_cast<const bf16x8 *>(rp + TILE_B);
+            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f2, x2f[ks], ks == 0 ? dpinit : dp, 0, 0, 0);
+          }
+#pragma unroll
+          for (int i = ks * 16 / NKS; i < (ks + 1) * 16 / NKS; ++i) between(i);
+        }
       }
       if constexpr (KV) {
         const bf16x8 fa = *reinterpret_cast<const bf16x8 *>(st + aux_addr + kt * 32 * 16);
@@ -371,14 +398,16 @@ __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a)
         }
       }
     };
-    auto probs = [&](f32x16 &s, f32x16 &dp) {                       // vector pipe: s <- P, dp <- dS
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        s[r] = __builtin_amdgcn_exp2f(QS ? s[r] : s[r] * a.c);
-        if constexpr (DP) dp[r] *= s[r];
-      }
+    auto prob1 = [&](f32x16 &s, f32x16 &dp, int r) {                // vector pipe: s <- P, dp <- dS
+      s[r] = __builtin_amdgcn_exp2f(QS ? s[r] : s[r] * a.c);
+      if constexpr (DP) dp[r] *= s[r];
     };
-    auto products = [&](auto kt_c, const f32x16 &s, const f32x16 &dp) {   // matrix pipe
+    auto probs = [&](f32x16 &s, f32x16 &dp) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) prob1(s, dp, r);
+    };
+    auto nothing = [](int) {};
+    auto products = [&](auto kt_c, const f32x16 &s, const f32x16 &dp, auto between) {   // matrix pipe
       constexpr int kt = decltype(kt_c)::value;
       auto step = [&](auto h2_c) {
         constexpr int h2 = decltype(h2_c)::value;
@@ -417,6 +446,8 @@ __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a)
               const u64x2 b2 = {r2[d][0], r2[d][1]};
               acc2[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, b2), pf, acc2[d], 0, 0, 0);
             }
+#pragma unroll
+            for (int i = (h2 * NDT + d) * 8 / NDT; i < (h2 * NDT + d + 1) * 8 / NDT; ++i) between(i);
           }
         } else {
 #pragma unroll
@@ -439,6 +470,8 @@ __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a)
               const s16x8 both = __builtin_shufflevector(tr_frag(ROFF + TILE_B + t_addr[0][d]), tr_frag(ROFF + TILE_B + t_addr[1][d]), 0, 1, 2, 3, 4, 5, 6, 7);
               acc2[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf, acc2[d], 0, 0, 0);
             }
+#pragma unroll
+            for (int i = (h2 * NDT + d) * 8 / NDT; i < (h2 * NDT + d + 1) * 8 / NDT; ++i) between(i);
           }
         }
       };
@@ -451,20 +484,36 @@ __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a)
     // last scores that use the current ones.
     const bool ragged = s0 + BS > cur.n_t;
     f32x16 sA, dA;
-    if constexpr (NKT == 2) {
+    if constexpr (PP) {
+      // two groups in flight: the exponentials of one sit between the MFMAs of the other
+      f32x16 sB, dB;
       if (active) {
-        scores(std::integral_constant<int, 0>{}, sA, dA);
+        scores(std::integral_constant<int, 0>{}, sA, dA, nothing);
         if (ragged) mask(0, sA);
-        probs(sA, dA);
-        products(std::integral_constant<int, 0>{}, sA, dA);
+        scores(std::integral_constant<int, 1>{}, sB, dB, [&](int i) { prob1(sA, dA, i); });
       }
-    }
-    if (active) scores(std::integral_constant<int, NKT - 1>{}, sA, dA);
-    if (last && has_next) load_x(nxt);
-    if (active) {
-      if (ragged) mask(NKT - 1, sA);
-      probs(sA, dA);
-      products(std::integral_constant<int, NKT - 1>{}, sA, dA);
+      if (last && has_next) load_x(nxt);
+      if (active) {
+        if (ragged) mask(1, sB);
+        products(std::integral_constant<int, 0>{}, sA, dA, [&](int i) { prob1(sB, dB, i); });
+        products(std::integral_constant<int, 1>{}, sB, dB, nothing);
+      }
+    } else {
+      if constexpr (NKT == 2) {
+        if (active) {
+          scores(std::integral_constant<int, 0>{}, sA, dA, nothing);
+          if (ragged) mask(0, sA);
+          probs(sA, dA);
+          products(std::integral_constant<int, 0>{}, sA, dA, nothing);
+        }
+      }
+      if (active) scores(std::integral_constant<int, NKT - 1>{}, sA, dA, nothing);
+      if (last && has_next) load_x(nxt);
+      if (active) {
+        if (ragged) mask(NKT - 1, sA);
+        probs(sA, dA);
+        products(std::integral_constant<int, NKT - 1>{}, sA, dA, nothing);
+      }
     }
     if (++buf == NST) buf = 0;
     if (!last) { ++sb; continue; }
@@ -587,7 +636,7 @@ template <int DH, int BS, int NST>
 constexpr int bwd_lds_bytes(bool kv) { return NST * (2 * BS * DH * 2 + (kv ? 2 * BS * 16 : 0)); }
 
 static int g_bwd_cus = 0;
-static bool g_bwd_dh256_ok = false;
+static bool g_bwd_big_ok = false;
 
 hipError_t attention_bwd_init() {
   int dev = 0;
@@ -595,19 +644,22 @@ hipError_t attention_bwd_init() {
   if (e != hipSuccess) return e;
   e = hipDeviceGetAttribute(&g_bwd_cus, hipDeviceAttributeMultiprocessorCount, dev);
   if (e != hipSuccess) return e;
-  // the kernels at dh = 256 need 96 .. 99 KiB of LDS, above the default limit of a launch
-  g_bwd_dh256_ok = true;
-  const void *big[] = {reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<256, 32, 0, false, 1, 3, 2>),
-                       reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<256, 32, 0, true, 1, 3, 2>),
-                       reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<256, 32, 2, false, 1, 3, 2>),
-                       reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<256, 32, 2, true, 1, 3, 2>),
-                       reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<256, 32, 3, false, 1, 3, 2>),
-                       reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<256, 32, 3, true, 1, 3, 2>)};
-  for (int i = 0; i < 6; ++i) {
-    e = hipFuncSetAttribute(big[i], hipFuncAttributeMaxDynamicSharedMemorySize, bwd_lds_bytes<256, 32, 3>(i >= 2));
-    if (e != hipSuccess) {            // not fatal: only the dh = 256 gradient is refused
+  // kernels whose LDS ring exceeds the default limit of a launch (64 KiB)
+  g_bwd_big_ok = true;
+  struct Big { const void *fn; int bytes; };
+  const Big big[] = {
+#define RESLIM_BIG(DH, BS, MODE, NST, NSPLIT)                                                                       \
+  {reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<DH, BS, MODE, false, 1, NST, NSPLIT>), bwd_lds_bytes<DH, BS, NST>(MODE != 0)}, \
+  {reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<DH, BS, MODE, true, 1, NST, NSPLIT>), bwd_lds_bytes<DH, BS, NST>(MODE != 0)},
+      RESLIM_BIG(128, 64, 0, 3, 1) RESLIM_BIG(128, 64, 3, 3, 1)
+      RESLIM_BIG(256, 32, 0, 3, 2) RESLIM_BIG(256, 32, 2, 3, 2) RESLIM_BIG(256, 32, 3, 3, 2)
+#undef RESLIM_BIG
+  };
+  for (const Big &k : big) {
+    e = hipFuncSetAttribute(k.fn, hipFuncAttributeMaxDynamicSharedMemorySize, k.bytes);
+    if (e != hipSuccess) {            // not fatal: only the gradient at head dimensions 128 and 256 is refused
       (void)hipGetLastError();
-      g_bwd_dh256_ok = false;
+      g_bwd_big_ok = false;
     }
   }
   return hipSuccess;
@@ -645,11 +697,12 @@ static hipError_t launch_bwd_all(const AttnBwdArgs &a, int dh, hipStream_t st) {
       e = launch_bwd_one<64, 64, 0, QS, 3, 3>(a, st);
       return e != hipSuccess ? e : launch_bwd_one<64, 64, 1, QS, 2, 3>(a, st);
     case 128:
-      e = launch_bwd_one<128, 32, 0, QS, 1, 3>(a, st);
+      if (!g_bwd_big_ok) return hipErrorInvalidValue;
+      e = launch_bwd_one<128, 64, 0, QS, 1, 3>(a, st);
       if (e == hipSuccess) e = launch_bwd_one<128, 32, 2, QS, 2, 3>(a, st);
-      return e != hipSuccess ? e : launch_bwd_one<128, 32, 3, QS, 1, 3>(a, st);
+      return e != hipSuccess ? e : launch_bwd_one<128, 64, 3, QS, 1, 3>(a, st);
     case 256:
-      if (!g_bwd_dh256_ok) return hipErrorInvalidValue;
+      if (!g_bwd_big_ok) return hipErrorInvalidValue;
       e = launch_bwd_one<256, 32, 0, QS, 1, 3, 2>(a, st);
       if (e == hipSuccess) e = launch_bwd_one<256, 32, 2, QS, 1, 3, 2>(a, st);
       return e != hipSuccess ? e : launch_bwd_one<256, 32, 3, QS, 1, 3, 2>(a, st);
