@@ -201,12 +201,34 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
     f32x16 s[NKT];
     if (active) {
       // feature step outermost: consecutive MFMAs belong to different accumulator chains
+      if constexpr (DH <= 128) {
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) {
+        for (int ks = 0; ks < NKS; ++ks) {
 #pragma unroll
-        for (int kt = 0; kt < NKT; ++kt) {
-          const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(st + kt * 32 * ROWB + k_row + (((2 * ks + hi) ^ k_swz) << 4));
-          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? minit : s[kt], 0, 0, 0);
+          for (int kt = 0; kt < NKT; ++kt) {
+            const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(st + kt * 32 * ROWB + k_row + (((2 * ks + hi) ^ k_swz) << 4));
+            s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? minit : s[kt], 0, 0, 0);
+          }
+        }
+      } else {
+        // dh = 256 runs one wave per SIMD: the fragment reads go PF steps ahead of the MFMAs that
+        // use them (ring of PF + 1 register sets; a scheduling barrier per step keeps that order),
+        // so a wave hides its own LDS latency (1.87 -> 1.75 ms for the 10B model's block; with the
+        // two waves per SIMD of dh = 128 the same ring gains nothing)
+        constexpr int PF = 2, NSTEP = NKS * NKT;
+        bf16x8 kf[PF + 1];
+        auto fetch = [&](int i) {
+          const int ks = i / NKT, kt = i % NKT;
+          kf[i % (PF + 1)] = *reinterpret_cast<const bf16x8 *>(st + kt * 32 * ROWB + k_row + (((2 * ks + hi) ^ k_swz) << 4));
+        };
+#pragma unroll
+        for (int i = 0; i < PF; ++i) fetch(i);
+#pragma unroll
+        for (int i = 0; i < NSTEP; ++i) {
+          if (i + PF < NSTEP) fetch(i + PF);
+          const int ks = i / NKT, kt = i % NKT;
+          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i % (PF + 1)], qf[ks], ks == 0 ? minit : s[kt], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
     }
@@ -296,7 +318,7 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
           group(std::integral_constant<int, 2>{});
           group(std::integral_constant<int, 3>{});
         }
-      } else {
+      } else if constexpr (DH <= 128) {
 #pragma unroll
         for (int kt = 0; kt < NKT; ++kt) {
 #pragma unroll
@@ -318,6 +340,33 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
               o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[d], 0, 0, 0);
             }
           }
+        }
+      } else {
+        // the same ring for the transposed V fragments of P V: step = (key group, half, feature block)
+        constexpr int PF = 2, NSTEP = NKT * 2 * NDT;
+        typedef __attribute__((ext_vector_type(8))) short s16x8;
+        s16x4 vlo[PF + 1], vhi[PF + 1];
+        auto fetch = [&](int i) {
+          const int d = i % NDT, h2 = (i / NDT) % 2, kt = i / (2 * NDT);
+          const unsigned char *vp = st + (kt * 32 + h2 * 16) * ROWB;
+          vlo[i % (PF + 1)] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(vp + v_addr[0][d]));
+          vhi[i % (PF + 1)] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(vp + v_addr[1][d]));
+        };
+#pragma unroll
+        for (int i = 0; i < PF; ++i) fetch(i);
+        bf16x8 pf;
+#pragma unroll
+        for (int i = 0; i < NSTEP; ++i) {
+          if (i + PF < NSTEP) fetch(i + PF);
+          const int d = i % NDT, h2 = (i / NDT) % 2, kt = i / (2 * NDT);
+          if (d == 0) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pf[e] = static_cast<__bf16>(s[kt][8 * h2 + e]);
+            lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf, lsum, 0, 0, 0);
+          }
+          const s16x8 both = __builtin_shufflevector(vlo[i % (PF + 1)], vhi[i % (PF + 1)], 0, 1, 2, 3, 4, 5, 6, 7);
+          o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf, o[d], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
     }

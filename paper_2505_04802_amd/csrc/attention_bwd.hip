@@ -652,7 +652,7 @@ hipError_t attention_bwd_init() {
   {reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<DH, BS, MODE, false, 1, NST, NSPLIT>), bwd_lds_bytes<DH, BS, NST>(MODE != 0)}, \
   {reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<DH, BS, MODE, true, 1, NST, NSPLIT>), bwd_lds_bytes<DH, BS, NST>(MODE != 0)},
       RESLIM_BIG(128, 64, 0, 3, 1) RESLIM_BIG(128, 64, 3, 3, 1)
-      RESLIM_BIG(256, 32, 0, 3, 2) RESLIM_BIG(256, 32, 2, 3, 2) RESLIM_BIG(256, 32, 3, 3, 2)
+      RESLIM_BIG(256, 64, 0, 2, 2) RESLIM_BIG(256, 32, 2, 3, 2) RESLIM_BIG(256, 64, 3, 2, 2)
 #undef RESLIM_BIG
   };
   for (const Big &k : big) {
@@ -685,10 +685,11 @@ static hipError_t launch_bwd_one(const AttnBwdArgs &a0, hipStream_t st) {
 // Launch shapes (measured on MI355X): dh = 64: 64-token blocks, three stages; the dQ kernel fits
 // 168 registers = three work-groups per CU, the dK/dV kernel (197) two.  dh = 128: dK and dV in
 // separate passes (their accumulators together with the stationary fragments exceed the register
-// file); dQ and dK need ~360 registers and run one work-group per CU without spills (c4: 12.8 ms
-// against 17.4 ms with two spilling work-groups), dV fits two.  dh = 256: the same three passes, each
-// once per half of the head's features (353 .. 458 registers, no spills, one work-group per CU; the
-// 10B model's block: 13.5 ms against 40.5 ms for unsplit passes that spilled 130 .. 145 registers).
+// file); dQ and dK take 64-token blocks with two 32-token groups in flight (~410 registers, one
+// work-group per CU, no spills; c4: 9.9 ms against 13.1 ms with 32-token blocks and 17.4 ms with
+// two spilling work-groups), dV fits two work-groups.  dh = 256: the same three passes, each once
+// per half of the head's features (no spills apart from three registers in the dQ pass; the 10B
+// model's block: 9.6 ms against 40.5 ms for unsplit passes that spilled 130 .. 145 registers).
 template <bool QS>
 static hipError_t launch_bwd_all(const AttnBwdArgs &a, int dh, hipStream_t st) {
   hipError_t e;
@@ -703,9 +704,9 @@ static hipError_t launch_bwd_all(const AttnBwdArgs &a, int dh, hipStream_t st) {
       return e != hipSuccess ? e : launch_bwd_one<128, 64, 3, QS, 1, 3>(a, st);
     case 256:
       if (!g_bwd_big_ok) return hipErrorInvalidValue;
-      e = launch_bwd_one<256, 32, 0, QS, 1, 3, 2>(a, st);
+      e = launch_bwd_one<256, 64, 0, QS, 1, 2, 2>(a, st);
       if (e == hipSuccess) e = launch_bwd_one<256, 32, 2, QS, 1, 3, 2>(a, st);
-      return e != hipSuccess ? e : launch_bwd_one<256, 32, 3, QS, 1, 3, 2>(a, st);
+      return e != hipSuccess ? e : launch_bwd_one<256, 64, 3, QS, 1, 2, 2>(a, st);
     default: return hipErrorInvalidValue;
   }
 }
