@@ -307,6 +307,56 @@ __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a)
     }
     return true;
   };
+  // The same in two steps, for the kernels that keep two groups in flight: plan_next() picks the
+  // block and moves the cursor, issue_part(i) sends this wave's i-th pair of direct loads (the
+  // record load rides with pair 0).  A wave's burst of loads stalls it while the CU's load queue
+  // is full; spread between the MFMAs of the first score product they cost nothing.  Blocks that
+  // cross the tile end, and waves without stationary tokens, keep the burst.
+  struct Pending {
+    const unsigned char *g1, *g2;
+    const u32x4 *aux;
+    unsigned char *sb;
+    int lim;
+  } pend;
+  auto plan_next = [&](int buf) -> bool {
+    if (ivb >= a.total) return false;
+    const int s0 = iblk * BS;
+    pend.sb = smem + buf * STAGE;
+    pend.g1 = reinterpret_cast<const unsigned char *>(y1_of(iu) + static_cast<size_t>(s0) * ldq);
+    pend.g2 = reinterpret_cast<const unsigned char *>(y2_of(iu) + static_cast<size_t>(s0) * ldy2);
+    pend.aux = a.aux + iu.aux_off + s0;
+    pend.lim = iu.n_t - 1 - s0;
+    if (++iblk == iu.nsb) {
+      ivb = decode(ivb + G, iu);
+      iblk = 0;
+    }
+    return true;
+  };
+  auto issue_part = [&](int i) {          // only for blocks wholly inside the tile
+    attn_dl_load16(reinterpret_cast<const bf16_t *>(pend.g1 + static_cast<uint32_t>(off1[i])), pend.sb + (wave + NW * i) * 1024);
+    attn_dl_load16(reinterpret_cast<const bf16_t *>(pend.g2 + static_cast<uint32_t>(off2[i])),
+                   pend.sb + TILE_B + (wave + NW * i) * 1024);
+    if constexpr (KV) {
+      if (i == 0 && wave < AUXL)
+        attn_dl_load16(reinterpret_cast<const bf16_t *>(pend.aux + aux_arr * a.aux_stride + aux_row),
+                       pend.sb + 2 * TILE_B + wave * 1024);
+    }
+  };
+  auto issue_planned_burst = [&]() {      // any block: rows past the tile end re-read its last row
+#pragma unroll
+    for (int i = 0; i < LPW; ++i) {
+      const int back = max(ld_row[i] - pend.lim, 0);
+      attn_dl_load16(reinterpret_cast<const bf16_t *>(pend.g1 + static_cast<uint32_t>(off1[i] - back * ldq * 2)),
+                     pend.sb + (wave + NW * i) * 1024);
+      attn_dl_load16(reinterpret_cast<const bf16_t *>(pend.g2 + static_cast<uint32_t>(off2[i] - back * ldy2 * 2)),
+                     pend.sb + TILE_B + (wave + NW * i) * 1024);
+    }
+    if constexpr (KV) {
+      if (wave < AUXL)
+        attn_dl_load16(reinterpret_cast<const bf16_t *>(pend.aux + aux_arr * a.aux_stride + min(aux_row, pend.lim)),
+                       pend.sb + 2 * TILE_B + wave * 1024);
+    }
+  };
   constexpr int NLD = 2 * LPW;            // direct loads of one block per wave (+1 in the waves that fetch records)
   int ahead = 0;                          // blocks in flight beyond the one about to be computed
   issue_next(0);
@@ -329,15 +379,24 @@ __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a)
     // this block above, and LDS reads of the stage being refilled finished before its readers arrived.
     __builtin_amdgcn_s_barrier();           // everybody's part of the block is in LDS; the oldest stage is free
     const bool last = sb + 1 == cur.nsb;
+    const bool active = cur.r0 + wave * 32 < cur.n_t;
+    bool spread = false;                    // this wave sends the next block's loads between its MFMAs
     {
       int ibuf = buf + NST - 1;
       if (ibuf >= NST) ibuf -= NST;
-      if (issue_next(ibuf)) { if (NST == 2) ahead = 0; }   // one computed, one issued: `ahead` unchanged
+      bool issued;
+      if constexpr (PP) {
+        issued = plan_next(ibuf);
+        spread = issued && active && pend.lim >= BS - 1;
+        if (issued && !spread) issue_planned_burst();
+      } else {
+        issued = issue_next(ibuf);
+      }
+      if (issued) { if (NST == 2) ahead = 0; }   // one computed, one issued: `ahead` unchanged
       else if (ahead > 0) --ahead;
     }
     const unsigned char *st = smem + buf * STAGE;
     const int s0 = sb * BS;
-    const bool active = cur.r0 + wave * 32 < cur.n_t;
 
     // The work on one 32-token group of the streamed block, in three phases.
     const unsigned st_off = static_cast<unsigned>(reinterpret_cast<uintptr_t>(
@@ -488,7 +547,9 @@ __global__ __launch_bounds__(256, MINW) void attn_bwd_bf16_kernel(AttnBwdArgs a)
       // two groups in flight: the exponentials of one sit between the MFMAs of the other
       f32x16 sB, dB;
       if (active) {
-        scores(std::integral_constant<int, 0>{}, sA, dA, nothing);
+        scores(std::integral_constant<int, 0>{}, sA, dA, [&](int i) {
+          if (spread && i % (16 / LPW) == 0) issue_part(i / (16 / LPW));
+        });
         if (ragged) mask(0, sA);
         scores(std::integral_constant<int, 1>{}, sB, dB, [&](int i) { prob1(sA, dA, i); });
       }
