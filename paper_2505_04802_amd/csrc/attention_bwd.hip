@@ -106,8 +106,8 @@ __device__ __forceinline__ uint64_t tr_issue(unsigned addr) {
 }
 
 // MODE: 0 = query-stationary, dQ;  1 = key-stationary, dK and dV;  2 = key-stationary, dV only;
-// 3 = key-stationary, dK only (2 + 3 replace 1 where the accumulators of both do not fit the
-// register file next to the stationary fragments: dh = 128).
+// 3 = key-stationary, dK only (2 + 3 can replace 1 where the accumulators of both do not fit the
+// register file next to the stationary fragments; no launch shape in use needs them).
 // QS: q in qkv already carries the factor log2(e)/sqrt(dh) (as the fused QKV epilogue of the
 // block leaves it): the MFMA output is the base-2 logit itself.
 // NSPLIT: a launch accumulates only DH / NSPLIT of the head's output features (a.part says which)
@@ -712,8 +712,8 @@ hipError_t attention_bwd_init() {
 #define RESLIM_BIG(DH, BS, MODE, NST, NSPLIT)                                                                       \
   {reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<DH, BS, MODE, false, 1, NST, NSPLIT>), bwd_lds_bytes<DH, BS, NST>(MODE != 0)}, \
   {reinterpret_cast<const void *>(&attn_bwd_bf16_kernel<DH, BS, MODE, true, 1, NST, NSPLIT>), bwd_lds_bytes<DH, BS, NST>(MODE != 0)},
-      RESLIM_BIG(128, 64, 0, 3, 1) RESLIM_BIG(128, 64, 3, 3, 1)
-      RESLIM_BIG(256, 64, 0, 2, 2) RESLIM_BIG(256, 32, 2, 3, 2) RESLIM_BIG(256, 64, 3, 2, 2)
+      RESLIM_BIG(128, 64, 0, 3, 1) RESLIM_BIG(128, 64, 3, 3, 1) RESLIM_BIG(128, 64, 1, 3, 1)
+      RESLIM_BIG(256, 32, 0, 3, 1) RESLIM_BIG(256, 32, 1, 3, 2)
 #undef RESLIM_BIG
   };
   for (const Big &k : big) {
@@ -743,14 +743,15 @@ static hipError_t launch_bwd_one(const AttnBwdArgs &a0, hipStream_t st) {
   return hipSuccess;
 }
 
-// Launch shapes (measured on MI355X): dh = 64: 64-token blocks, three stages; the dQ kernel fits
-// 168 registers = three work-groups per CU, the dK/dV kernel (197) two.  dh = 128: dK and dV in
-// separate passes (their accumulators together with the stationary fragments exceed the register
-// file); dQ and dK take 64-token blocks with two 32-token groups in flight (~410 registers, one
-// work-group per CU, no spills; c4: 9.9 ms against 13.1 ms with 32-token blocks and 17.4 ms with
-// two spilling work-groups), dV fits two work-groups.  dh = 256: the same three passes, each once
-// per half of the head's features (no spills apart from three registers in the dQ pass; the 10B
-// model's block: 9.6 ms against 40.5 ms for unsplit passes that spilled 130 .. 145 registers).
+// Launch shapes (measured on MI355X; the file is built with MFMA operands in ordinary vector
+// registers, see the build script): dh = 64: 64-token blocks, three stages; the dQ kernel fits 168
+// registers = three work-groups per CU, the dK/dV kernel (197) two.  dh = 128: one work-group per
+// CU, 64-token blocks with two 32-token groups in flight; dQ ~350 registers, dK and dV together
+// ~510, no spills (c4: 7.1 ms; 13.1 ms with 32-token blocks, separate dK and dV passes and
+// accumulator-register MFMAs; 17.4 ms with two spilling work-groups).  dh = 256: dQ unsplit on
+// 32-token blocks (15 registers spilled, still faster than two spill-free half passes), dK and dV
+// together, once per half of the head's features (505 registers, no spills).  The 10B model's
+// block: 6.6 ms, against 40.5 ms for unsplit dQ and dK/dV passes that spilled 130 .. 145 registers.
 template <bool QS>
 static hipError_t launch_bwd_all(const AttnBwdArgs &a, int dh, hipStream_t st) {
   hipError_t e;
@@ -761,13 +762,11 @@ static hipError_t launch_bwd_all(const AttnBwdArgs &a, int dh, hipStream_t st) {
     case 128:
       if (!g_bwd_big_ok) return hipErrorInvalidValue;
       e = launch_bwd_one<128, 64, 0, QS, 1, 3>(a, st);
-      if (e == hipSuccess) e = launch_bwd_one<128, 32, 2, QS, 2, 3>(a, st);
-      return e != hipSuccess ? e : launch_bwd_one<128, 64, 3, QS, 1, 3>(a, st);
+      return e != hipSuccess ? e : launch_bwd_one<128, 64, 1, QS, 1, 3>(a, st);
     case 256:
       if (!g_bwd_big_ok) return hipErrorInvalidValue;
-      e = launch_bwd_one<256, 64, 0, QS, 1, 2, 2>(a, st);
-      if (e == hipSuccess) e = launch_bwd_one<256, 32, 2, QS, 1, 3, 2>(a, st);
-      return e != hipSuccess ? e : launch_bwd_one<256, 64, 3, QS, 1, 2, 2>(a, st);
+      e = launch_bwd_one<256, 32, 0, QS, 1, 3, 1>(a, st);
+      return e != hipSuccess ? e : launch_bwd_one<256, 32, 1, QS, 1, 3, 2>(a, st);
     default: return hipErrorInvalidValue;
   }
 }
