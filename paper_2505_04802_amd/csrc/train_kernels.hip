@@ -259,41 +259,57 @@ __global__ __launch_bounds__(256) void layernorm_bwd_wide_kernel(const float *__
   }
 }
 
-// out[j] = sum over p < n_part of partial[p * stride + j] in a fixed order (deterministic).
-// A work-group owns 32 columns; its 8 row groups each add every 8th partial row (four
+// out[j] = sum over p < n_part of partial[p * stride + j] in a fixed order (deterministic); columns
+// from `split` on go to out2[j - split] (two results that share partial rows, one launch).
+// A work-group owns 32 columns; its NG row groups each add every NG-th partial row (four
 // independent running sums per thread keep loads in flight), then the groups are added in order.
-__global__ __launch_bounds__(256) void partial_reduce_kernel(const float *__restrict__ partial, float *__restrict__ out,
-                                                             int n_part, int64_t stride, int64_t n) {
-  __shared__ float sm[8][32];
+// NG = 32 (1024 threads) where there are few columns and many partial rows: column sums of
+// activations have 16 .. 64 column blocks, far too few work-groups to hide the latency of 1024
+// dependent row loads behind one another (c1: 14 us per launch with NG = 8).
+template <int NG>
+__global__ __launch_bounds__(NG * 32) void partial_reduce_kernel(const float *__restrict__ partial, float *__restrict__ out,
+                                                                 float *__restrict__ out2, int64_t split, int n_part,
+                                                                 int64_t stride, int64_t n) {
+  __shared__ float sm[NG][32];
   const int col = threadIdx.x & 31, grp = threadIdx.x >> 5;
   const int64_t j = static_cast<int64_t>(blockIdx.x) * 32 + col;
   float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
   if (j < n) {
     int p = grp;
-    for (; p + 24 < n_part; p += 32) {
+    for (; p + 3 * NG < n_part; p += 4 * NG) {
       a0 += partial[p * stride + j];
-      a1 += partial[(p + 8) * stride + j];
-      a2 += partial[(p + 16) * stride + j];
-      a3 += partial[(p + 24) * stride + j];
+      a1 += partial[(p + NG) * stride + j];
+      a2 += partial[(p + 2 * NG) * stride + j];
+      a3 += partial[(p + 3 * NG) * stride + j];
     }
-    for (; p < n_part; p += 8) a0 += partial[p * stride + j];
+    for (; p < n_part; p += NG) a0 += partial[p * stride + j];
   }
   sm[grp][col] = (a0 + a1) + (a2 + a3);
   __syncthreads();
   if (grp == 0 && j < n) {
     float acc = sm[0][col];
 #pragma unroll
-    for (int g = 1; g < 8; ++g) acc += sm[g][col];
-    out[j] = acc;
+    for (int g = 1; g < NG; ++g) acc += sm[g][col];
+    if (j < split) out[j] = acc;
+    else out2[j - split] = acc;
   }
 }
 
-hipError_t launch_partial_reduce(const float *partial, float *out, int n_part, int64_t stride, int64_t n, hipStream_t st) {
+// out2 / split: see the kernel; pass nullptr / n for a single result
+static hipError_t launch_partial_reduce2(const float *partial, float *out, float *out2, int64_t split, int n_part,
+                                         int64_t stride, int64_t n, hipStream_t st) {
   if (n <= 0) return hipSuccess;
   const int64_t blocks = (n + 31) / 32;
   if (blocks > INT32_MAX) return hipErrorInvalidValue;
-  partial_reduce_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st>>>(partial, out, n_part, stride, n);
+  if (blocks < 512 && n_part >= 128)
+    partial_reduce_kernel<32><<<dim3(static_cast<unsigned>(blocks)), dim3(1024), 0, st>>>(partial, out, out2, split, n_part, stride, n);
+  else
+    partial_reduce_kernel<8><<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st>>>(partial, out, out2, split, n_part, stride, n);
   return hipGetLastError();
+}
+
+hipError_t launch_partial_reduce(const float *partial, float *out, int n_part, int64_t stride, int64_t n, hipStream_t st) {
+  return launch_partial_reduce2(partial, out, nullptr, n, n_part, stride, n, st);
 }
 
 // rows of 64 float4 from which the work-group-per-row kernel takes over (D above 1024 .. 2048)
@@ -329,9 +345,7 @@ static hipError_t launch_ln_bwd_t(const float *x, const void *dy, const float *g
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   // partial rows are [d gamma | d beta] pairs of 2 D floats
-  e = launch_partial_reduce(partial, dgamma, n_wg, 2 * static_cast<int64_t>(D), D, st);
-  if (e != hipSuccess) return e;
-  return launch_partial_reduce(partial + D, dbeta, n_wg, 2 * static_cast<int64_t>(D), D, st);
+  return launch_partial_reduce2(partial, dgamma, dbeta, D, n_wg, 2 * static_cast<int64_t>(D), 2 * static_cast<int64_t>(D), st);
 }
 
 // partial: dev float, at least layernorm_bwd_slabs(rows) * 2 * D elements
