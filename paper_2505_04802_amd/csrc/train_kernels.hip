@@ -295,12 +295,42 @@ __global__ __launch_bounds__(NG * 32) void partial_reduce_kernel(const float *__
   }
 }
 
+// Few partial rows, many columns (the split-K slices of a weight gradient): a thread owns four
+// adjacent columns and adds the rows in order, 16-byte loads, no LDS.
+__global__ __launch_bounds__(256) void partial_reduce_wide_kernel(const float4 *__restrict__ partial, float4 *__restrict__ out,
+                                                                  int n_part, int64_t stride4, int64_t n4) {
+  const int64_t j = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (j >= n4) return;
+  float4 acc = partial[j];
+  int p = 1;
+  for (; p + 3 < n_part; p += 4) {           // four loads in flight, added in row order
+    const float4 v0 = partial[p * stride4 + j], v1 = partial[(p + 1) * stride4 + j];
+    const float4 v2 = partial[(p + 2) * stride4 + j], v3 = partial[(p + 3) * stride4 + j];
+    acc.x += v0.x; acc.y += v0.y; acc.z += v0.z; acc.w += v0.w;
+    acc.x += v1.x; acc.y += v1.y; acc.z += v1.z; acc.w += v1.w;
+    acc.x += v2.x; acc.y += v2.y; acc.z += v2.z; acc.w += v2.w;
+    acc.x += v3.x; acc.y += v3.y; acc.z += v3.z; acc.w += v3.w;
+  }
+  for (; p < n_part; ++p) {
+    const float4 v = partial[p * stride4 + j];
+    acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+  }
+  out[j] = acc;
+}
+
 // out2 / split: see the kernel; pass nullptr / n for a single result
 static hipError_t launch_partial_reduce2(const float *partial, float *out, float *out2, int64_t split, int n_part,
                                          int64_t stride, int64_t n, hipStream_t st) {
   if (n <= 0) return hipSuccess;
   const int64_t blocks = (n + 31) / 32;
   if (blocks > INT32_MAX) return hipErrorInvalidValue;
+  if (!out2 && n_part >= 1 && n_part <= 64 && n >= 65536 && n % 4 == 0 && stride % 4 == 0 &&
+      reinterpret_cast<uintptr_t>(partial) % 16 == 0 && reinterpret_cast<uintptr_t>(out) % 16 == 0) {
+    const int64_t n4 = n / 4;
+    partial_reduce_wide_kernel<<<dim3(static_cast<unsigned>((n4 + 255) / 256)), dim3(256), 0, st>>>(
+        reinterpret_cast<const float4 *>(partial), reinterpret_cast<float4 *>(out), n_part, stride / 4, n4);
+    return hipGetLastError();
+  }
   if (blocks < 512 && n_part >= 128)
     partial_reduce_kernel<32><<<dim3(static_cast<unsigned>(blocks)), dim3(1024), 0, st>>>(partial, out, out2, split, n_part, stride, n);
   else
