@@ -90,32 +90,40 @@ def test_tiles_attention_bwd_ragged_and_tiny_tiles():
         assert np.isfinite(got).all() and err <= TOL[cfg.dtype]
 
 
-def test_tiles_attention_bwd_c1_full_size_sampled_tiles():
-    """The shape bench.py times (c1: 4 x 16 tiles x 8 heads, 612..720 tokens per tile):
-    the oracle recomputes sampled (sample, tile) pairs (exact: tiles do not interact),
-    and two properties are checked over the whole output: sum_i dq_i . q_i = sum_j dk_j . k_j
-    per (sample, tile, head) (both equal sum_ij dS_ij S_ij), and determinism."""
-    cfg = WL.CONFIGS["c1"]
+FULL_SIZE = [("c1", ((0, 0), (1, 5), (3, 15), (2, 10))),      # dh 64: the shape bench.py times
+             ("c4", ((0, 0), (0, 9))),                          # dh 128, 2448 tokens per interior tile
+             ("m10b", ((0, 5), (0, 15)))]                       # dh 256 (the 10B model's heads)
+
+
+@pytest.mark.parametrize("name,pairs", FULL_SIZE, ids=[n for n, _ in FULL_SIZE])
+def test_tiles_attention_bwd_full_size_sampled_tiles(name, pairs):
+    """Full-size shapes (c1: 4 x 16 tiles x 8 heads, 612..720 tokens per tile; c4 and the 10B
+    model: one sample, 16 tiles, 32 heads of dimension 128 / 256): the oracle recomputes sampled
+    (sample, tile) pairs (exact: tiles do not interact), and two properties are checked over the
+    whole output: sum_i dq_i . q_i = sum_j dk_j . k_j per (sample, tile, head) (both equal
+    sum_ij dS_ij S_ij), and determinism."""
+    cfg = WL.CONFIGS[name]
     tiles, _, _, n_h = O.tiles_partition(cfg.Hp, cfg.Wp, cfg.tiles_y, cfg.tiles_x, cfg.halo)
     qkv, d_out = _inputs(cfg, n_h, False, seed=9)
     D, dh = cfg.embed_dim, cfg.embed_dim // cfg.heads
-    one = cfg.with_(depth=1)          # the attention entry points do not use the block weights
+    one = cfg.with_(depth=1, mlp_ratio=1)   # the attention entry points do not use the block weights
     with B.Reslim(one, WL.make_weights(one)) as m:
         got = _run(m, qkv, d_out)
         again = _run(m, qkv, d_out)
     assert np.array_equal(got, again)
-    for b, t in ((0, 0), (1, 5), (3, 15), (2, 10)):
+    for b, t in pairs:
         tl = tiles[t]
         r = slice(tl["tok_off"], tl["tok_off"] + tl["n_tok"])
         dq, dk, dv = O.self_attention_bwd(qkv[b, r, :D], qkv[b, r, D:2 * D], qkv[b, r, 2 * D:], d_out[b, r], cfg.heads)
-        for name, a, ref in (("dq", got[b, r, :D], dq), ("dk", got[b, r, D:2 * D], dk), ("dv", got[b, r, 2 * D:], dv)):
+        for gname, a, ref in (("dq", got[b, r, :D], dq), ("dk", got[b, r, D:2 * D], dk), ("dv", got[b, r, 2 * D:], dv)):
             err = O.rel_l2(a, ref)
-            say(f"  sample {b} tile {t} {name} rel-L2 {err:.3e}")
+            say(f"  {name} sample {b} tile {t} {gname} rel-L2 {err:.3e}")
             assert err <= 2e-2
-    q64, g64 = qkv.astype(np.float64), got.astype(np.float64)
     worst = 0.0
     for tl in tiles:
         r = slice(tl["tok_off"], tl["tok_off"] + tl["n_tok"])
+        q64, g64 = qkv[:, r].astype(np.float64), got[:, r].astype(np.float64)
+        r = slice(None)
         a = (g64[:, r, :D] * q64[:, r, :D]).reshape(cfg.batch, -1, cfg.heads, dh).sum(axis=(1, 3))
         c = (g64[:, r, D:2 * D] * q64[:, r, D:2 * D]).reshape(cfg.batch, -1, cfg.heads, dh).sum(axis=(1, 3))
         n = np.sqrt((g64[:, r, :D] ** 2).reshape(cfg.batch, -1, cfg.heads, dh).sum(axis=(1, 3)) *
