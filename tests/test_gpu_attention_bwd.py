@@ -11,6 +11,7 @@ import torch
 from oracle import reslim_oracle as O
 from paper_2505_04802_amd import binding as B
 from paper_2505_04802_amd import workloads as WL
+from parity_checks import GRAD_BF16, assert_parity
 from test_gpu_parity import SMALL_F32, SMALL_BF16, SMALL_BF16_DH128, SMALL_BF16_DH256, TOL, cuda, say, weights_for
 
 pytestmark = pytest.mark.gpu
@@ -44,9 +45,7 @@ def test_tiles_attention_bwd_parity(cfg, peaked):
     assert np.isfinite(got).all()
     D = cfg.embed_dim
     for name, sl in (("dq", slice(0, D)), ("dk", slice(D, 2 * D)), ("dv", slice(2 * D, 3 * D))):
-        err = O.rel_l2(got[..., sl], ref[..., sl])
-        say(f"  {name} rel-L2 {err:.3e}")
-        assert err <= TOL[cfg.dtype], name
+        assert_parity(got[..., sl], ref[..., sl], TOL[cfg.dtype], name, say, **(GRAD_BF16 if cfg.dtype else {}))
 
 
 def test_tiles_attention_bwd_special_cases():
@@ -85,9 +84,7 @@ def test_tiles_attention_bwd_ragged_and_tiny_tiles():
         ref = O.tiles_attention_bwd(qkv, d_out, tiles, cfg.heads)
         with B.Reslim(cfg, weights_for(cfg)) as m:
             got = _run(m, qkv, d_out)
-        err = O.rel_l2(got, ref)
-        say(f"  {cfg.name} rel-L2 {err:.3e}")
-        assert np.isfinite(got).all() and err <= TOL[cfg.dtype]
+        assert_parity(got, ref, TOL[cfg.dtype], cfg.name, say, **(GRAD_BF16 if cfg.dtype else {}))
 
 
 FULL_SIZE = [("c1", ((0, 0), (1, 5), (3, 15), (2, 10))),      # dh 64: the shape bench.py times
@@ -116,9 +113,7 @@ def test_tiles_attention_bwd_full_size_sampled_tiles(name, pairs):
         r = slice(tl["tok_off"], tl["tok_off"] + tl["n_tok"])
         dq, dk, dv = O.self_attention_bwd(qkv[b, r, :D], qkv[b, r, D:2 * D], qkv[b, r, 2 * D:], d_out[b, r], cfg.heads)
         for gname, a, ref in (("dq", got[b, r, :D], dq), ("dk", got[b, r, D:2 * D], dk), ("dv", got[b, r, 2 * D:], dv)):
-            err = O.rel_l2(a, ref)
-            say(f"  {name} sample {b} tile {t} {gname} rel-L2 {err:.3e}")
-            assert err <= 2e-2
+            assert_parity(a, ref, 2e-2, f"{name} sample {b} tile {t} {gname}", say, **GRAD_BF16)
     worst = 0.0
     for tl in tiles:
         r = slice(tl["tok_off"], tl["tok_off"] + tl["n_tok"])

@@ -14,6 +14,7 @@ import torch
 from oracle import reslim_oracle as O
 from paper_2505_04802_amd import binding as B
 from paper_2505_04802_amd import workloads as WL
+from parity_checks import GRAD_BF16, assert_parity
 from test_gpu_parity import SMALL_F32, SMALL_BF16, SMALL_BF16_DH128, TOL, cuda, say, weights_for
 
 pytestmark = pytest.mark.gpu
@@ -80,9 +81,8 @@ def test_linear_bwd_parity(cfg, which):
         B.reslim_linear_bwd(m.ctx, 1, which, cuda(x, m.act_dtype), cuda(dy, m.act_dtype), dx, dw, db, rows, ws)
         torch.cuda.synchronize()
         for nm, got, ref, tol in (("dx", dx, ref_dx, TOL[cfg.dtype]), ("dw", dw, ref_dw, 1e-5), ("db", db, ref_db, 1e-5)):
-            err = O.rel_l2(got.float().cpu().numpy(), ref)
-            say(f"  linear_bwd {cfg.name} {name} {nm} rel-L2 {err:.3e}")
-            assert err <= tol, nm                # dw, db: exact products of the given inputs, fp32 sums
+            # dw, db: exact products of the given inputs, fp32 sums
+            assert_parity(got.float().cpu().numpy(), ref, tol, f"linear_bwd {cfg.name} {name} {nm}", say)
 
 
 @pytest.mark.parametrize("cfg", CFGS + WIDE_BLOCK, ids=lambda c: c.name)
@@ -103,22 +103,17 @@ def test_block_train_parity(cfg):
         saved, ws = u8(sb), u8(wb)
         x_dev, out = cuda(x), torch.empty((cfg.batch, n_h, D), dtype=torch.float32, device="cuda")
         B.reslim_block_fwd_train(m.ctx, layer, x_dev, out, saved, cfg.batch, ws)
-        err = O.rel_l2(out.cpu().numpy(), ref_out)
-        say(f"  block_fwd_train {cfg.name} rel-L2 {err:.3e}")
-        assert err <= TOL[cfg.dtype]
+        assert_parity(out.cpu().numpy(), ref_out, TOL[cfg.dtype], f"block_fwd_train {cfg.name}", say)
         plain = m.block(layer, x_dev.clone()).cpu().numpy()          # the inference entry point on the same input
         assert O.rel_l2(out.cpu().numpy(), plain) <= TOL[cfg.dtype]
         grads = {n: torch.full(np.shape(w[n][layer]), float("nan"), dtype=torch.float32, device="cuda") for n in B.BLOCK_PARAMS}
         dx = torch.empty_like(out)
         B.reslim_block_bwd(m.ctx, layer, x_dev, saved, cuda(d_out), dx, grads, cfg.batch, ws)
         torch.cuda.synchronize()
-        err = O.rel_l2(dx.cpu().numpy(), ref_dx)
-        say(f"  block_bwd {cfg.name} d_x rel-L2 {err:.3e}")
-        assert err <= TOL[cfg.dtype]
+        extra = GRAD_BF16 if cfg.dtype else {}
+        assert_parity(dx.cpu().numpy(), ref_dx, TOL[cfg.dtype], f"block_bwd {cfg.name} d_x", say, **extra)
         for n in B.BLOCK_PARAMS:
-            err = O.rel_l2(grads[n].cpu().numpy(), ref_g[n])
-            say(f"  block_bwd {cfg.name} d_{n} rel-L2 {err:.3e}")
-            assert err <= TOL[cfg.dtype], n
+            assert_parity(grads[n].cpu().numpy(), ref_g[n], TOL[cfg.dtype], f"block_bwd {cfg.name} d_{n}", say, **extra)
         # determinism: a second backward gives the same bits
         again = {n: torch.empty_like(grads[n]) for n in B.BLOCK_PARAMS}
         dx2 = torch.empty_like(dx)
@@ -154,9 +149,7 @@ def test_block_train_c1_full_size():
     ref_out = O.reslim_block(x, tiles, w, 0, cfg.heads)
     ref_dx, ref_g = O.reslim_block_bwd(x, tiles, w, 0, cfg.heads, d_out)
     for name, got, ref in [("x_out", got_out, ref_out), ("d_x", got_dx, ref_dx)] + [("d_" + n, got_g[n], ref_g[n]) for n in B.BLOCK_PARAMS]:
-        err = O.rel_l2(got, ref)
-        say(f"  c1 block train {name} rel-L2 {err:.3e}")
-        assert err <= 2e-2, name
+        assert_parity(got, ref, 2e-2, f"c1 block train {name}", say, **({} if name == "x_out" else GRAD_BF16))
 
 
 def test_training_entry_point_errors_and_tiny_tiles():

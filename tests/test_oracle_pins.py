@@ -139,6 +139,91 @@ def test_self_attention_vs_sdpa_and_special_cases():
     assert np.allclose(O.softmax(rng.standard_normal((5, 9)) * 30).sum(-1), 1, atol=1e-14)
 
 
+def test_tiles_attention_lse_vs_logsumexp_brute_force_and_value_columns():
+    """The log-sum-exp the attention gradient starts from, pinned three ways: torch.logsumexp over
+    logits built pair by pair in Python loops (per tile, so a wrong tile range, scale or base
+    shows), recovery from the attention output itself (with value columns e_j the output row of
+    query i IS its softmax row, and -log of the entry at the arg-max key plus that logit is the
+    log-sum-exp), and closed forms."""
+    rng = np.random.default_rng(21)
+    for (Hp, Wp, Ty, Tx, h) in [(5, 6, 2, 3, 1), (4, 4, 1, 1, 2), (3, 7, 3, 2, 0)]:
+        tiles, g, src, n_h = O.tiles_partition(Hp, Wp, Ty, Tx, h)
+        D, heads = 12, 3
+        dh = D // heads
+        qkv = 1.5 * rng.standard_normal((2, n_h, 3 * D))
+        lse = O.tiles_attention_lse(qkv, tiles, heads)
+        assert lse.shape == (2, heads, n_h)
+        for b in range(2):
+            for t in tiles:
+                lo, n = t["tok_off"], t["n_tok"]
+                for head in range(heads):
+                    logits = torch.empty((n, n))
+                    for i in range(n):
+                        for j in range(n):
+                            logits[i, j] = sum(qkv[b, lo + i, head * dh + d] * qkv[b, lo + j, D + head * dh + d]
+                                               for d in range(dh)) / math.sqrt(dh)
+                    ref = torch.logsumexp(logits, dim=1).numpy()
+                    assert np.allclose(lse[b, head, lo:lo + n], ref, atol=1e-12)
+    # recovery from self_attention: one head of width n, values = identity, so out[i, j] = P[i, j]
+    n = 9
+    q, k = rng.standard_normal((n, n)), rng.standard_normal((n, n))
+    P = O.self_attention(q, k, np.eye(n), heads=1)
+    S = q @ k.T / math.sqrt(n)
+    j = S.argmax(axis=1)
+    rec = S[np.arange(n), j] - np.log(P[np.arange(n), j])
+    one_tile = [dict(tok_off=0, n_tok=n)]
+    got = O.tiles_attention_lse(np.concatenate([q, k, np.eye(n)], axis=1)[None], one_tile, heads=1)
+    assert np.allclose(got[0, 0], rec, atol=1e-12)
+    # closed forms: q = 0 -> log(n_t) for every query of a tile; one-token tiles -> the logit itself
+    tiles, _, _, n_h = O.tiles_partition(4, 6, 2, 2, 1)
+    qkv = rng.standard_normal((1, n_h, 3 * 8))
+    qkv[:, :, :8] = 0.0
+    lse = O.tiles_attention_lse(qkv, tiles, 2)
+    for t in tiles:
+        assert np.allclose(lse[0, :, t["tok_off"]:t["tok_off"] + t["n_tok"]], math.log(t["n_tok"]), atol=1e-14)
+    tiles1, _, _, n1 = O.tiles_partition(2, 3, 2, 3, 0)
+    qkv = rng.standard_normal((1, n1, 3 * 4))
+    lse = O.tiles_attention_lse(qkv, tiles1, 1)
+    assert np.allclose(lse[0, 0], (qkv[0, :, :4] * qkv[0, :, 4:8]).sum(-1) / 2.0, atol=1e-14)
+    # a large common shift of the logits must not overflow: lse(q * c) with huge c stays finite
+    big = O.tiles_attention_lse(np.concatenate([400 * q, k, np.eye(n)], axis=1)[None], one_tile, heads=1)
+    assert np.isfinite(big).all()
+
+
+def test_rel_l2_on_hand_made_arrays():
+    """The checker every parity assertion goes through, on arrays whose per-plane answers are known:
+    the maximum over planes (all axes but the last two), not a norm over the whole array."""
+    # 2-D: one plane = the whole array; (3,4) vs (0,0)+ref: ||a-ref|| = 5, ||ref|| = 10
+    ref = np.array([[6.0, 0.0], [0.0, 8.0]])
+    a = ref + np.array([[3.0, 0.0], [0.0, 4.0]])
+    assert O.rel_l2(a, ref) == pytest.approx(0.5, abs=1e-15)
+    assert O.rel_l2(ref, ref) == 0.0
+    # 1-D
+    assert O.rel_l2(np.array([1.0, 2.0, 2.0 + 3.0]), np.array([1.0, 2.0, 2.0])) == pytest.approx(1.0, abs=1e-15)
+    # 3-D: planes [0] exact, [1] off by 10 % of its norm, [2] off by 1 %: the answer is 0.1, while a
+    # norm over the whole array would give a smaller number (plane 0 is made large on purpose)
+    r3 = np.zeros((3, 2, 2))
+    r3[0] = 1000.0
+    r3[1] = [[3.0, 0.0], [4.0, 0.0]]
+    r3[2] = [[0.0, 5.0], [0.0, 12.0]]
+    a3 = r3.copy()
+    a3[1, 0, 1] += 0.5                       # ||ref[1]|| = 5
+    a3[2, 1, 0] += 0.13                      # ||ref[2]|| = 13
+    assert O.rel_l2(a3, r3) == pytest.approx(0.1, abs=1e-15)
+    whole = np.linalg.norm(a3 - r3) / np.linalg.norm(r3)
+    assert whole < 1e-3
+    # 4-D [B, C, H, W]: planes are (b, c) pairs; put the error in the LAST plane and in the FIRST
+    r4 = np.ones((2, 3, 4, 5))
+    for where in [(1, 2), (0, 0)]:
+        a4 = r4.copy()
+        a4[where][3, 4] += 2.0               # ||ref plane|| = sqrt(20)
+        assert O.rel_l2(a4, r4) == pytest.approx(2.0 / math.sqrt(20.0), abs=1e-15)
+    # the first argument is the value under test, the second the reference (not symmetric)
+    assert O.rel_l2(2 * r4, r4) == pytest.approx(1.0) and O.rel_l2(r4, 2 * r4) == pytest.approx(0.5)
+    # float32 input is compared in float64
+    assert O.rel_l2(np.float32([[1.0, 1.0]]), np.array([[1.0, 1.0 + 1e-12]])) > 0.0
+
+
 def test_tiles_attention_equals_masked_global_attention():
     """Tile-local attention = global attention with -inf between tokens of different
     tile copies, by brute force over all pairs (tiny grid, with halo duplicates)."""
