@@ -174,12 +174,128 @@ def asc_leg(B, torch, np, cfg, w, x_host, K):
     return res
 
 
+def measure(B, torch, cfg, w, x_host, K, W, verbose, want_train, note):
+    """W warm-up + K timed forwards of one workload, then the same K steps again with every launch
+    bracketed by HIP events on the launch stream.  Returns (result dict, open model)."""
+    model = B.Reslim(cfg, w)
+    x = torch.from_numpy(x_host).cuda()
+    y = torch.empty((cfg.batch, cfg.out_vars, cfg.H * cfg.scale, cfg.W * cfg.scale), dtype=torch.float32, device="cuda")
+    for _ in range(W):
+        model.forward(x, y)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        model.forward(x, y)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / K * 1e3
+    tokens = cfg.batch * cfg.n_tokens
+
+    # ---- per-kernel durations (kept out of the headline timing above)
+    launches_per_step = 3 + 7 * cfg.depth + 3
+    B.reslim_profile_enable(model.ctx, launches_per_step * K)
+    for _ in range(K):
+        model.forward(x, y)
+    torch.cuda.synchronize()
+    recs = B.reslim_profile_read(model.ctx)
+    B.reslim_profile_enable(model.ctx, 0)
+    agg = {}
+    for name, ms, flop, nbytes in recs:
+        a = agg.setdefault(name, dict(calls=0, ms=0.0, flop=flop, bytes=nbytes))
+        a["calls"] += 1
+        a["ms"] += ms
+    kernels = []
+    for name, a in agg.items():
+        avg = a["ms"] / a["calls"]
+        tfl = a["flop"] / (avg * 1e-3) / 1e12 if a["flop"] else None
+        gbs = a["bytes"] / (avg * 1e-3) / 1e9
+        kernels.append(dict(kernel=name, launches_per_step=a["calls"] // K, avg_ms=round(avg, 5),
+                            ms_per_step=round(a["ms"] / K, 5),
+                            tflops=round(tfl, 2) if tfl else None, gbs=round(gbs, 1),
+                            bound="mfma" if tfl else "hbm",
+                            frac=round(tfl / PEAK_BF16_TFLOPS, 4) if tfl else round(gbs / PEAK_HBM_GBS, 4)))
+    kernels.sort(key=lambda k: -k["ms_per_step"])
+    dom = kernels[0]
+    a = agg[dom["kernel"]]
+    avg_s = a["ms"] / a["calls"] * 1e-3
+    if a["flop"] > 0:
+        achieved = a["flop"] / avg_s / 1e12
+        roof = dict(bound="mfma", kernel=dom["kernel"], achieved=round(achieved, 2), peak=PEAK_BF16_TFLOPS,
+                    unit="TFLOP/s", frac=round(achieved / PEAK_BF16_TFLOPS, 4),
+                    traffic=MEASURED_TRAFFIC.get((cfg.name, dom["kernel"])), avg_launch_ms=round(avg_s * 1e3, 5),
+                    flop_per_launch=a["flop"])
+    else:
+        achieved = a["bytes"] / avg_s / 1e9
+        roof = dict(bound="hbm", kernel=dom["kernel"], achieved=round(achieved, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                    frac=round(achieved / PEAK_HBM_GBS, 4), traffic=MEASURED_TRAFFIC.get((cfg.name, dom["kernel"])),
+                    avg_launch_ms=round(avg_s * 1e3, 5), bytes_per_launch=a["bytes"])
+    gflop, aflop, hflop = B.reslim_flop_counts(model.ctx, cfg.batch)
+    tflops = (gflop + aflop + hflop) / (dt / K) / 1e12
+    if verbose:
+        for k in kernels:
+            print(cfg.name + " " + json.dumps(k), file=sys.stderr)
+    res = {
+        "value": round(tokens / (dt / K), 1), "ms_per_step": round(ms_per_step, 4),
+        "dtype": "bf16" if cfg.dtype else "f32",
+        "config": {"workload": f"{cfg.name}: B={cfg.batch} V={cfg.in_vars} {cfg.H}x{cfg.W} x{cfg.scale} -> "
+                               f"{cfg.H * cfg.scale}x{cfg.W * cfg.scale}, p={cfg.patch} D={cfg.embed_dim} "
+                               f"heads={cfg.heads} r={cfg.mlp_ratio} L={cfg.depth} tiles={cfg.tiles_y}x{cfg.tiles_x} "
+                               f"halo={cfg.halo}",
+                   "unique_tokens": tokens, "haloed_tokens": cfg.batch * model.n_h},
+        "tflops": round(tflops, 2), "mfma_frac": round(tflops / PEAK_BF16_TFLOPS, 4),
+        "haloed_tokens_per_s": round(cfg.batch * model.n_h / (dt / K), 1),
+        "roofline": roof, "kernels": kernels,
+    }
+    # ---- extra, outside `value`: one block's training forward + backward at the same shape
+    # (gradient of tile attention, input- and weight-gradient GEMMs, LayerNorm / GELU gradients)
+    res["train_block"] = train_block(B, torch, model, cfg, K, verbose) if want_train and cfg.depth > 0 else None
+    model.close()
+    del x, y
+    torch.cuda.empty_cache()
+    return res
+
+
+def cpu_oracle(cfg, w, x_host):
+    """The CPU oracle, as it stands, on a bounded sample of the workload (about 10-30 s of host work)."""
+    from oracle import reslim_oracle as O
+    if cfg.name in ("c0", "c1"):
+        t0 = time.perf_counter()
+        O.reslim_forward(x_host[:1], w, cfg)
+        ct = time.perf_counter() - t0
+        cpu_tokens, sample = cfg.n_tokens, f"1 of {cfg.batch} samples, full forward"
+    else:   # whole tiles through the whole stack, scaled by tiles (tiles never interact, Sec. 4.2)
+        tiles = O.tiles_partition(cfg.Hp, cfg.Wp, cfg.tiles_y, cfg.tiles_x, cfg.halo)[0]
+        T = len(tiles)
+        picks = [0, cfg.tiles_x // 2, T // 2 + cfg.tiles_x // 2] if cfg.embed_dim <= 1024 else [T // 2 + cfg.tiles_x // 2]
+        cpu_tokens, ct = 0, 0.0
+        for i in picks:
+            t = tiles[i]
+            t0 = time.perf_counter()
+            O.forward_tile(x_host[0], w, cfg, t, cfg.Wp)
+            ct += time.perf_counter() - t0
+            cpu_tokens += (t["y1"] - t["y0"]) * (t["x1"] - t["x0"])
+        sample = (f"tiles {picks} (corner, edge, interior) of the {T} tiles of one sample, full stack; "
+                  f"unique tokens of those tiles / their time (extrapolation linear in tiles)")
+    cores = int(os.environ["OMP_NUM_THREADS"]) if os.environ.get("OMP_NUM_THREADS") else os.cpu_count()
+    return dict(value=round(cpu_tokens / ct, 1), unit="tokens/s", cores=cores, kind="oracle", sample=sample,
+                seconds=round(ct, 2))
+
+
+HEADLINE = "c3"      # the largest of the five benchmark workloads that one GPU holds: the headline is quoted on it
+OTHERS = ("c0", "c1", "c2", "c4")
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="c1", help="workload name (c0..c4, or m9m / m126m / m1b: the paper's model sizes); the headline metric is quoted on c1")
+    ap.add_argument("--config", default=HEADLINE,
+                    help="workload the line is quoted on (c0..c4, or m9m / m126m / m1b / m10b: the paper's model sizes); "
+                         "default: c3, the largest of the five benchmark workloads")
+    ap.add_argument("--others", default=None,
+                    help="comma-separated workloads measured as well and reported under `other_workloads` "
+                         "(default: c0,c1,c2,c4 when --config is c3, else none; 'none' switches them off)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (developer runs)")
     ap.add_argument("--gemm-tile", type=int, default=-1, help="pin the bf16 GEMM kernel (2 = 128x128 tiles, 3 = persistent 256x256), -1 = heuristic")
     ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
@@ -205,14 +321,21 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; there is no CPU path", file=sys.stderr)
         return 2
-    cfg = WL.CONFIGS[args.config]
-    big = cfg.depth * cfg.embed_dim ** 2 > 1 << 28      # minutes of host work: say what is going on
-    note = (lambda m: print("bench.py: " + m, file=sys.stderr, flush=True)) if big else None
-    w = WL.make_weights(cfg, progress=note)
-    x_host = WL.make_fields(cfg)
-    if note:
-        note("creating the context (weights to bf16, upload)")
+    note = lambda m: print("bench.py: " + m, file=sys.stderr, flush=True)
+    if args.others is None:
+        others = OTHERS if args.config == HEADLINE else ()
+    else:
+        others = tuple(n for n in args.others.split(",") if n and n != "none")
+    K, W = args.steps, args.warmup
     B.reslim_debug_set_gemm_tile(args.gemm_tile)
+
+    def inputs(cfg):
+        note(f"{cfg.name}: generating weights and fields on the host")
+        big = cfg.depth * cfg.embed_dim ** 2 > 1 << 28
+        return WL.make_weights(cfg, progress=note if big else None), WL.make_fields(cfg)
+
+    cfg = WL.CONFIGS[args.config]
+    w, x_host = inputs(cfg)
     if args.asc_only:
         if args.copy_probe:
             a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
@@ -221,13 +344,8 @@ def main() -> int:
                 B.reslim_debug_copy(a, b)
             torch.cuda.synchronize()
             del a, b
-        print(json.dumps(asc_leg(B, torch, np, cfg, w, x_host, args.steps)))
+        print(json.dumps(asc_leg(B, torch, np, cfg, w, x_host, K)))
         return 0
-    model = B.Reslim(cfg, w)
-    x = torch.from_numpy(x_host).cuda()
-    y = torch.empty((cfg.batch, cfg.out_vars, cfg.H * cfg.scale, cfg.W * cfg.scale), dtype=torch.float32, device="cuda")
-    K, W = args.steps, args.warmup
-
     if args.copy_probe:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB
         dst = torch.empty_like(src)
@@ -235,105 +353,41 @@ def main() -> int:
             B.reslim_debug_copy(src, dst)
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(W):
-        model.forward(x, y)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(K):
-        model.forward(x, y)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / K * 1e3
-    tokens = cfg.batch * cfg.n_tokens
-    value = tokens / (dt / K)
-
-    # ---- per-kernel durations: the same K steps again with every launch bracketed
-    # by HIP events on the launch stream (kept out of the headline timing above)
-    launches_per_step = 3 + 7 * cfg.depth + 3
-    B.reslim_profile_enable(model.ctx, launches_per_step * K)
-    for _ in range(K):
-        model.forward(x, y)
-    torch.cuda.synchronize()
-    recs = B.reslim_profile_read(model.ctx)
-    B.reslim_profile_enable(model.ctx, 0)
-    agg = {}
-    for name, ms, flop, nbytes in recs:
-        a = agg.setdefault(name, dict(calls=0, ms=0.0, flop=flop, bytes=nbytes))
-        a["calls"] += 1
-        a["ms"] += ms
-    kernels = []
-    for name, a in agg.items():
-        avg = a["ms"] / a["calls"]
-        kernels.append(dict(kernel=name, launches_per_step=a["calls"] // K, avg_ms=round(avg, 5),
-                            ms_per_step=round(a["ms"] / K, 5),
-                            tflops=round(a["flop"] / (avg * 1e-3) / 1e12, 2) if a["flop"] else None,
-                            gbs=round(a["bytes"] / (avg * 1e-3) / 1e9, 1)))
-    kernels.sort(key=lambda k: -k["ms_per_step"])
-    dom = kernels[0]
-    a = agg[dom["kernel"]]
-    avg_s = a["ms"] / a["calls"] * 1e-3
-    if a["flop"] > 0:
-        achieved = a["flop"] / avg_s / 1e12
-        roof = dict(bound="mfma", kernel=dom["kernel"], achieved=round(achieved, 2), peak=PEAK_BF16_TFLOPS,
-                    unit="TFLOP/s", frac=round(achieved / PEAK_BF16_TFLOPS, 4),
-                    traffic=MEASURED_TRAFFIC.get((cfg.name, dom["kernel"])), avg_launch_ms=round(avg_s * 1e3, 5),
-                    flop_per_launch=a["flop"])
-    else:
-        achieved = a["bytes"] / avg_s / 1e9
-        roof = dict(bound="hbm", kernel=dom["kernel"], achieved=round(achieved, 1), peak=PEAK_HBM_GBS, unit="GB/s",
-                    frac=round(achieved / PEAK_HBM_GBS, 4), traffic=MEASURED_TRAFFIC.get((cfg.name, dom["kernel"])),
-                    avg_launch_ms=round(avg_s * 1e3, 5), bytes_per_launch=a["bytes"])
-    gflop, aflop, hflop = B.reslim_flop_counts(model.ctx, cfg.batch)
-    tflops = (gflop + aflop + hflop) / (dt / K) / 1e12
-    if args.kernels:
-        for k in kernels:
-            print(json.dumps(k), file=sys.stderr)
-
-    # ---- extra, outside `value`: one block's training forward + backward at the same shape
-    # (gradient of tile attention, input- and weight-gradient GEMMs, LayerNorm / GELU gradients)
-    train = None
-    if not args.no_train_block and cfg.depth > 0:
-        train = train_block(B, torch, model, cfg, K, args.kernels)
-    model.close()
+    note(f"{cfg.name}: {W} warm-up + {K} timed steps, then {K} steps with per-launch events")
+    head = measure(B, torch, cfg, w, x_host, K, W, args.kernels, not args.no_train_block, note)
 
     # ---- extra, outside `value`: the untiled grid with and without adaptive spatial compression
     asc = None
     if not args.no_asc and cfg.name in ("c0", "c1", "m9m"):
         asc = asc_leg(B, torch, np, cfg, w, x_host, K)
 
-    # ---- the CPU oracle on a bounded sample of the same workload (one sample of the batch)
+    # ---- the CPU oracle on a bounded sample of the headline workload
     cpu = None
     if not args.no_cpu_baseline:
-        from oracle import reslim_oracle as O
-        if cfg.name in ("c0", "c1"):
-            t0 = time.perf_counter()
-            O.reslim_forward(x_host[:1], w, cfg)
-            ct = time.perf_counter() - t0
-            cpu_tokens, sample = cfg.n_tokens, f"1 of {cfg.batch} samples, full forward"
-        else:   # one tile through the whole stack, scaled by tiles (tiles never interact, Sec. 4.2)
-            tiles = O.tiles_partition(cfg.Hp, cfg.Wp, cfg.tiles_y, cfg.tiles_x, cfg.halo)[0]
-            t = tiles[len(tiles) // 2 + cfg.tiles_x // 2]
-            t0 = time.perf_counter()
-            O.forward_tile(x_host[0], w, cfg, t, cfg.Wp)
-            ct = time.perf_counter() - t0
-            cpu_tokens = (t["y1"] - t["y0"]) * (t["x1"] - t["x0"])
-            sample = f"1 of {len(tiles)} tiles of one sample, full stack (extrapolation linear in tiles)"
-        cpu = dict(value=round(cpu_tokens / ct, 1), unit="tokens/s", cores=os.cpu_count() if not os.environ.get("OMP_NUM_THREADS") else int(os.environ["OMP_NUM_THREADS"]),
-                   kind="oracle", sample=sample, seconds=round(ct, 2))
+        note(f"{cfg.name}: CPU oracle on a sample of the workload")
+        cpu = cpu_oracle(cfg, w, x_host)
+    del w, x_host
+
+    # ---- the other benchmark workloads, same procedure, reported beside the headline
+    other = {}
+    for name in others:
+        ocfg = WL.CONFIGS[name]
+        ow, ox = inputs(ocfg)
+        note(f"{name}: {W} warm-up + {K} timed steps, then {K} steps with per-launch events")
+        r = measure(B, torch, ocfg, ow, ox, K, W, args.kernels, False, note)
+        if name == "c1" and not args.no_asc:
+            r["asc"] = asc_leg(B, torch, np, ocfg, ow, ox, K)
+        other[name] = r
+        del ow, ox
 
     out = {
-        "metric": "Reslim+TILES fwd tokens/s", "value": round(value, 1), "unit": "tokens/s",
-        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.dtype else "f32",
-        "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: B={cfg.batch} V={cfg.in_vars} {cfg.H}x{cfg.W} x{cfg.scale} -> "
-                               f"{cfg.H * cfg.scale}x{cfg.W * cfg.scale}, p={cfg.patch} D={cfg.embed_dim} "
-                               f"heads={cfg.heads} r={cfg.mlp_ratio} L={cfg.depth} tiles={cfg.tiles_y}x{cfg.tiles_x} "
-                               f"halo={cfg.halo}",
-                   "unique_tokens": tokens, "haloed_tokens": cfg.batch * model.n_h},
-        "tflops": round(tflops, 2), "mfma_frac": round(tflops / PEAK_BF16_TFLOPS, 4),
-        "haloed_tokens_per_s": round(cfg.batch * model.n_h / (dt / K), 1),
-        "roofline": roof, "cpu_baseline": cpu, "kernels": kernels, "train_block": train, "asc": asc,
+        "metric": "Reslim+TILES fwd tokens/s", "value": head["value"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": head["dtype"],
+        "data": "synthetic", "config": head["config"],
+        "tflops": head["tflops"], "mfma_frac": head["mfma_frac"], "haloed_tokens_per_s": head["haloed_tokens_per_s"],
+        "roofline": head["roofline"], "cpu_baseline": cpu, "kernels": head["kernels"],
+        "train_block": head["train_block"], "asc": asc, "other_workloads": other,
     }
     print(json.dumps(out))
     return 0
