@@ -325,6 +325,24 @@ int reslim_bayes_loss_fwd(const float *pred, const float *target, const float *l
                           int32_t vars, int32_t Hf, int32_t Wf, float tv_weight, double *out3,
                           void *workspace, size_t ws_bytes, void *hip_stream);
 
+/* The same loss value for callers that cannot allocate device memory or must not be
+ * handed a workspace: code under HIP graph capture, tight serving or training loops,
+ * harnesses that forbid hipMalloc.  Same arguments, result and errors as
+ * reslim_bayes_loss_fwd minus the workspace: the per-work-group partial sums live in a
+ * fixed 4 MiB array inside the library's device code (one copy per GPU, held until the
+ * process ends; its address is looked up on the first call on each device, with that
+ * device current).  The call allocates nothing and synchronises nothing.
+ * Limit: batch * vars * ceil(Hf / 8) * ceil(Wf / 1024) <= 262144 work-groups
+ * (reslim_bayes_loss_static_max_groups reports the number; the 16 x 5760 x 11520 output
+ * of the largest benchmark grid needs 138240); beyond it RESLIM_EWORKSPACE, nothing
+ * enqueued.  All calls on one GPU share the array: two calls whose kernels overlap on that
+ * GPU (different streams, or replays of two captured graphs) race; calls on one stream are
+ * safe, each call writes every partial it later reads, so nothing needs clearing. */
+int reslim_bayes_loss_static_max_groups(int64_t *out);
+int reslim_bayes_loss_fwd_static(const float *pred, const float *target, const float *lat_w, int32_t batch,
+                                 int32_t vars, int32_t Hf, int32_t Wf, float tv_weight, double *out3,
+                                 void *hip_stream);
+
 /* ---- Adaptive spatial compression (Sec. 4.1, "Adaptive Spatial Compression").
  * The paper maps the aggregated embedding to image space, runs Canny edge
  * detection on it, splits quadrants of a quad-tree while their edge density is

@@ -30,7 +30,8 @@ EXPORTS = ["tiles_partition", "reslim_create", "reslim_destroy", "reslim_last_er
            "reslim_block_fwd", "reslim_head_fwd", "reslim_forward", "reslim_flop_counts",
            "reslim_debug_set_gemm_tile", "reslim_profile_enable", "reslim_profile_reset", "reslim_profile_read",
            "reslim_debug_copy", "reslim_debug_set_attention_variant",
-           "reslim_bayes_loss_workspace_bytes", "reslim_bayes_loss_fwd", "tiles_attention_fwd_lse",
+           "reslim_bayes_loss_workspace_bytes", "reslim_bayes_loss_fwd", "reslim_bayes_loss_static_max_groups",
+           "reslim_bayes_loss_fwd_static", "tiles_attention_fwd_lse",
            "tiles_attention_bwd_workspace_bytes", "tiles_attention_bwd",
            "reslim_train_prepare", "reslim_layernorm_bwd", "reslim_linear_bwd_workspace_bytes", "reslim_linear_bwd",
            "reslim_block_train_bytes", "reslim_block_fwd_train", "reslim_block_bwd",
@@ -119,6 +120,8 @@ def load() -> C.CDLL:
     lib.reslim_debug_copy.argtypes = [vp, vp, C.c_size_t, vp]
     lib.reslim_bayes_loss_workspace_bytes.argtypes = [i32, i32, i32, i32, C.POINTER(C.c_size_t)]
     lib.reslim_bayes_loss_fwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, C.c_float, vp, vp, C.c_size_t, vp]
+    lib.reslim_bayes_loss_static_max_groups.argtypes = [C.POINTER(C.c_int64)]
+    lib.reslim_bayes_loss_fwd_static.argtypes = [vp, vp, vp, i32, i32, i32, i32, C.c_float, vp, vp]
     lib.reslim_asc_build.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, i32, C.c_float, vp, vp, vp, vp, vp, C.POINTER(C.c_int64)]
     lib.reslim_asc_edges.argtypes = [vp, i32, i32, i32, i32, vp]
     lib.reslim_asc_plan_create.argtypes = [vp, i32, vp, vp, vp, C.c_int64, vp, vp, C.POINTER(vp)]
@@ -230,6 +233,19 @@ def reslim_bayes_loss_fwd(pred, target, lat_w, tv_weight: float, out3, workspace
     _check(load().reslim_bayes_loss_fwd(pred.data_ptr(), target.data_ptr(), lat_w.data_ptr(), b, k, hf, wf,
                                         float(tv_weight), out3.data_ptr(), workspace.data_ptr(),
                                         workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
+
+
+def reslim_bayes_loss_static_max_groups() -> int:
+    n = C.c_int64(0)
+    _check(load().reslim_bayes_loss_static_max_groups(C.byref(n)))
+    return int(n.value)
+
+
+def reslim_bayes_loss_fwd_static(pred, target, lat_w, tv_weight: float, out3, stream=None) -> None:
+    """reslim_bayes_loss_fwd without a workspace: the partial sums use the library's fixed device array."""
+    b, k, hf, wf = pred.shape
+    _check(load().reslim_bayes_loss_fwd_static(pred.data_ptr(), target.data_ptr(), lat_w.data_ptr(), b, k, hf, wf,
+                                               float(tv_weight), out3.data_ptr(), _stream_ptr(stream)))
 
 
 def reslim_profile_enable(ctx: int, max_records: int) -> None:

@@ -16,6 +16,8 @@
 // kernel that adds the partials in a fixed order (deterministic result).
 #include "common.h"
 
+#include <mutex>
+
 namespace reslim {
 
 constexpr int LOSS_ROWS = 8, LOSS_COLS = 1024;
@@ -125,6 +127,30 @@ __global__ __launch_bounds__(256) void bayes_loss_final_kernel(const double *par
   }
 }
 
+// Partial sums of the entry point that allocates nothing: a fixed array in the code object's own
+// device memory (each GPU that loads the library holds its own copy until the process ends).
+// In host code this name is only a handle for hipGetSymbolAddress, never a device address.
+constexpr size_t LOSS_STATIC_MAX_GROUPS = size_t(1) << 18;     // 4 MiB of doubles
+static __device__ __align__(256) double scratch[2 * LOSS_STATIC_MAX_GROUPS];
+
+constexpr int LOSS_MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static double *g_scratch_ptr[LOSS_MAX_DEVICES];          // device address of `scratch`, per device
+
+// Device address of the current device's copy of `scratch`; asked for once per device.
+static int loss_scratch_ptr(double **out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= LOSS_MAX_DEVICES) return RESLIM_EHIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return RESLIM_EHIP;
+    g_scratch_ptr[dev] = static_cast<double *>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return RESLIM_OK;
+}
+
 static bool loss_shape(int batch, int vars, int Hf, int Wf, int64_t *planes, int *sx, int *sy, size_t *groups) {
   if (batch < 1 || vars < 1 || Hf < 1 || Wf < 1) return false;
   *planes = static_cast<int64_t>(batch) * vars;
@@ -146,6 +172,24 @@ extern "C" int reslim_bayes_loss_workspace_bytes(int32_t batch, int32_t vars, in
   return RESLIM_OK;
 }
 
+namespace reslim {
+
+// The two launches shared by both entry points; `partial` is a device address with room for 2 * groups doubles.
+static int loss_launch(const float *pred, const float *target, const float *lat_w, int64_t planes, int Hf, int Wf, int sx,
+                       int sy, size_t groups, float tv_weight, double *out3, double *partial, hipStream_t st) {
+  LossArgs a;
+  a.pred = pred; a.target = target; a.lat_w = lat_w;
+  a.partial = partial;
+  a.Hf = Hf; a.Wf = Wf; a.strips_x = sx; a.strips_y = sy;
+  bayes_loss_partial_kernel<<<dim3(static_cast<unsigned>(sx * sy), static_cast<unsigned>(planes)), dim3(256), 0, st>>>(a);
+  if (hipGetLastError() != hipSuccess) return RESLIM_EHIP;
+  const double count = static_cast<double>(planes) * Hf * Wf;
+  bayes_loss_final_kernel<<<dim3(1), dim3(256), 0, st>>>(partial, groups, count, static_cast<double>(tv_weight), out3);
+  return hipGetLastError() == hipSuccess ? RESLIM_OK : RESLIM_EHIP;
+}
+
+}  // namespace reslim
+
 extern "C" int reslim_bayes_loss_fwd(const float *pred, const float *target, const float *lat_w, int32_t batch,
                                      int32_t vars, int32_t Hf, int32_t Wf, float tv_weight, double *out3,
                                      void *workspace, size_t ws_bytes, void *hip_stream) {
@@ -156,14 +200,30 @@ extern "C" int reslim_bayes_loss_fwd(const float *pred, const float *target, con
   if (!reslim::loss_shape(batch, vars, Hf, Wf, &planes, &sx, &sy, &groups)) return RESLIM_EINVAL;
   if (ws_bytes < 2 * groups * sizeof(double)) return RESLIM_EWORKSPACE;
   if (reinterpret_cast<uintptr_t>(workspace) % 8 || reinterpret_cast<uintptr_t>(out3) % 8) return RESLIM_EINVAL;
-  hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  reslim::LossArgs a;
-  a.pred = pred; a.target = target; a.lat_w = lat_w;
-  a.partial = static_cast<double *>(workspace);
-  a.Hf = Hf; a.Wf = Wf; a.strips_x = sx; a.strips_y = sy;
-  reslim::bayes_loss_partial_kernel<<<dim3(static_cast<unsigned>(sx * sy), static_cast<unsigned>(planes)), dim3(256), 0, st>>>(a);
-  if (hipGetLastError() != hipSuccess) return RESLIM_EHIP;
-  const double count = static_cast<double>(planes) * Hf * Wf;
-  reslim::bayes_loss_final_kernel<<<dim3(1), dim3(256), 0, st>>>(a.partial, groups, count, static_cast<double>(tv_weight), out3);
-  return hipGetLastError() == hipSuccess ? RESLIM_OK : RESLIM_EHIP;
+  return reslim::loss_launch(pred, target, lat_w, planes, Hf, Wf, sx, sy, groups, tv_weight, out3,
+                             static_cast<double *>(workspace), static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int reslim_bayes_loss_static_max_groups(int64_t *out) {
+  if (!out) return RESLIM_EINVAL;
+  *out = static_cast<int64_t>(reslim::LOSS_STATIC_MAX_GROUPS);
+  return RESLIM_OK;
+}
+
+extern "C" int reslim_bayes_loss_fwd_static(const float *pred, const float *target, const float *lat_w, int32_t batch,
+                                            int32_t vars, int32_t Hf, int32_t Wf, float tv_weight, double *out3,
+                                            void *hip_stream) {
+  int64_t planes;
+  int sx, sy;
+  size_t groups;
+  if (!pred || !target || !lat_w || !out3) return RESLIM_EINVAL;
+  if (!reslim::loss_shape(batch, vars, Hf, Wf, &planes, &sx, &sy, &groups)) return RESLIM_EINVAL;
+  if (groups > reslim::LOSS_STATIC_MAX_GROUPS) return RESLIM_EWORKSPACE;       // beyond the fixed array
+  if (reinterpret_cast<uintptr_t>(out3) % 8) return RESLIM_EINVAL;
+  double *partial = nullptr;
+  const int rc = reslim::loss_scratch_ptr(&partial);
+  if (rc != RESLIM_OK) return rc;
+  // every partial the final kernel reads is written by the first kernel of this call: nothing to clear
+  return reslim::loss_launch(pred, target, lat_w, planes, Hf, Wf, sx, sy, groups, tv_weight, out3, partial,
+                             static_cast<hipStream_t>(hip_stream));
 }
