@@ -345,8 +345,10 @@ __global__ __launch_bounds__(256) void embed_agg_kernel(EmbedArgs e) {
   }
 }
 
+hipError_t residual_init();
+
 hipError_t elementwise_init() {
-  hipError_t e = hipSuccess;
+  hipError_t e = residual_init();
   const int lim = 160 * 1024;
 #define RESLIM_ATTR(K) if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(&K), hipFuncAttributeMaxDynamicSharedMemorySize, lim)
   RESLIM_ATTR((embed_agg_kernel<bf16_t, 4>));
@@ -387,29 +389,45 @@ struct ResArgs {
   const int32_t *out_var_idx;
   int V, C, H, W, s, p, ps, Wp, N, head_out;
   int nbx;               // blocks per tile along x
-  int cwh, cww;          // coarse window held in LDS per input variable
-  int ci_chunk;          // input variables per pass (<= 8; fewer when the window is large, s = 1)
+  int cwh, cww;          // coarse window of a block
+  int ci_chunk;          // input variables per pass over the window
 };
 
-// A work-group produces a 16 x 64 block of fine pixels inside one tile's interior,
-// 8 output variables at a time.  For 8 input variables at a time it
-//   1. copies the coarse pixels the block can touch into LDS (a window of about
-//      (16/s + 3) x (64/s + 3) values per variable),
-//   2. builds the upsampled field U on the block's 18 x 66 neighbourhood from that
-//      window -- bilinear with neighbours clamped to the tile's haloed box, zero
-//      outside the box (the padding of the convolution); the per-row and per-column
-//      source indices, weights and masks are tabulated once per block,
-//   3. accumulates the 3x3 stencil, each thread for 4 adjacent pixels.
-// The head projection is then read in patch order (16 bytes per lane: 4 pixels of
-// one patch row) and the sum written in place: un-patchify, stitch and add in one
-// pass with 16-byte loads and stores.
-template <int CI, int CO>
+// Residual path (Sec. 4.1 "Residual Learning": upsampling + convolution of the input,
+// added to the transformer's output), evaluated per tile on its haloed box (Sec. 4.2),
+// fused with un-patchify, stitch and the final add.
+//
+// Both steps are linear and the upsampling acts on each variable alone, so the variables
+// are mixed BEFORE upsampling, on the few coarse pixels a block touches, and the
+// bilinear weights are applied afterwards, rows first, then columns.  With U the
+// upsampled field (zero outside the box), r/c a fine row/column of the box and
+// (a_r, b_r, w_r, m_r) the two clamped coarse source rows, the weight of the second and
+// the inside-the-box mask of fine row r (same for columns):
+//   Z[t=(dy,dx)][o](Y, X) = sum_i w_res[o][i][dy][dx] x[i](Y, X)                 coarse window
+//   T[dx][o](r, X)        = sum_dy m_{r+dy} ((1 - w_{r+dy}) Z[dy,dx][o](a_{r+dy}, X) + w_{r+dy} Z[dy,dx][o](b_{r+dy}, X))
+//   R[o](r, c)            = b_res[o] + sum_dx m_{c+dx} ((1 - w_{c+dx}) T[dx][o](r, a_{c+dx}) + w_{c+dx} T[dx][o](r, b_{c+dx}))
+// which is the 3x3 convolution of the bilinear upsampling, term by term in another order.
+// Per output value that is about 6 multiply-adds plus a share of Z and T (9 C multiply-adds
+// per coarse window pixel and output) instead of 9 C per fine pixel: the kernel is bound by
+// reading the head projection and writing y.
+//
+// A work-group produces a 16 x 64 block of fine pixels inside one tile's interior, CO
+// output variables at a time; the head projection is read in patch order (16 bytes per
+// lane: 4 pixels of one patch row) and the sum written in place.
+// NARROW (scale >= 4): the six fine columns a thread's four pixels and their column taps touch
+// come from at most three coarse columns, so the column step is a 3-term product with
+// per-thread weights held in registers and T is read once per (tap, output) instead of per pixel.
+template <int CO, bool NARROW>
 __global__ __launch_bounds__(256) void residual_unpatchify_kernel(ResArgs a) {
   constexpr int BY = 16, BX = 64, WY = BY + 2, WX = BX + 2, WXP = 68;
-  __shared__ __align__(16) float U[CI * WY * WXP];
-  __shared__ float row_w[WY], row_m[WY], col_w[WXP], col_m[WXP];
-  __shared__ int row_a[WY], row_b[WY], col_a[WXP], col_b[WXP];
-  extern __shared__ float Cw[];                // [CI][cwh][cww] coarse window
+  __shared__ float row_w[WY], col_w[WXP];
+  __shared__ int row_a[WY], row_b[WY], row_m[WY], col_a[WXP], col_b[WXP], col_m[WXP];
+  extern __shared__ __align__(16) float dyn[];
+  const int cwh = a.cwh, cww = a.cww, npx = cwh * cww;
+  float *Xw = dyn;                               // [ci_chunk][npx]       coarse window of the inputs
+  float *Ws = Xw + a.ci_chunk * npx;             // [ci_chunk][9][CO]     convolution weights of this pass
+  float *Z = Ws + a.ci_chunk * 9 * CO;           // [9][CO][npx]
+  float *T = Z + 9 * CO * npx;                   // [3][CO][BY][cww]
   const tile_desc td = a.tiles[blockIdx.y];
   const int b = blockIdx.z;
   const int ih = (td.y1 - td.y0) * a.ps, iw = (td.x1 - td.x0) * a.ps;
@@ -424,7 +442,6 @@ __global__ __launch_bounds__(256) void residual_unpatchify_kernel(ResArgs a) {
   const float inv_s = 1.0f / static_cast<float>(a.s);
   const int sH = a.s * a.H, sW = a.s * a.W;
   const int iy = iy0 + ty, ix = ix0 + 4 * tx;
-  const int cwh = a.cwh, cww = a.cww;
 
   // source coordinate of fine pixel f (same arithmetic for rows and columns)
   auto src = [&](int f, int n_coarse, int &ia, int &ib, float &w1) {
@@ -451,7 +468,7 @@ __global__ __launch_bounds__(256) void residual_unpatchify_kernel(ResArgs a) {
     row_a[t] = min(ia - oy, cwh - 1);
     row_b[t] = min(ib - oy, cwh - 1);
     row_w[t] = w1;
-    row_m[t] = (fy >= 0 && fy < box_fh) ? 1.0f : 0.0f;
+    row_m[t] = (fy >= 0 && fy < box_fh) ? 1 : 0;
   } else if (t >= 64 && t < 64 + WX) {
     const int wx = t - 64, fx = fx0 + wx - 1;
     int ia, ib;
@@ -460,10 +477,70 @@ __global__ __launch_bounds__(256) void residual_unpatchify_kernel(ResArgs a) {
     col_a[wx] = min(ia - ox, cww - 1);
     col_b[wx] = min(ib - ox, cww - 1);
     col_w[wx] = w1;
-    col_m[wx] = (fx >= 0 && fx < box_fw) ? 1.0f : 0.0f;
+    col_m[wx] = (fx >= 0 && fx < box_fw) ? 1 : 0;
   }
+  const bool one_pass = a.ci_chunk >= a.C;       // the whole input window fits: load it once
 
   for (int co0 = 0; co0 < a.C; co0 += CO) {
+    // ---- Z: the variables mixed on the coarse window, per tap
+    for (int ci0 = 0; ci0 < a.C; ci0 += a.ci_chunk) {
+      const int nci = min(a.ci_chunk, a.C - ci0);
+      __syncthreads();                           // previous users of Xw / Ws / Z / T are done (and the tables are written)
+      if (!one_pass || co0 == 0) {
+        for (int idx = t; idx < nci * npx; idx += 256) {
+          const int ci = idx / npx, r = idx % npx;
+          const int wy = r / cww, wx = r % cww;
+          const float *xp = a.x + (static_cast<size_t>(b) * a.V + a.out_var_idx[ci0 + ci]) * a.H * a.W;
+          const int y = min(oy + wy, box_ch - 1), x = min(ox + wx, box_cw - 1);
+          Xw[idx] = xp[static_cast<size_t>(cy_org + y) * a.W + cx_org + x];
+        }
+      }
+      for (int idx = t; idx < nci * 9 * CO; idx += 256) {
+        const int o = idx % CO, tap = (idx / CO) % 9, ci = idx / (9 * CO);
+        Ws[idx] = (co0 + o < a.C) ? a.w_res[(static_cast<size_t>(co0 + o) * a.C + ci0 + ci) * 9 + tap] : 0.f;
+      }
+      __syncthreads();
+      for (int item = t; item < 9 * npx; item += 256) {
+        const int px = item % npx, tap = item / npx;
+        float z[CO];
+#pragma unroll
+        for (int o = 0; o < CO; ++o) z[o] = 0.f;
+        for (int ci = 0; ci < nci; ++ci) {
+          const float xv = Xw[ci * npx + px];
+          const float *wp = Ws + (ci * 9 + tap) * CO;
+#pragma unroll
+          for (int o = 0; o < CO; ++o) z[o] = fmaf(wp[o], xv, z[o]);
+        }
+#pragma unroll
+        for (int o = 0; o < CO; ++o) {
+          float *zp = Z + (tap * CO + o) * npx + px;
+          *zp = ci0 == 0 ? z[o] : *zp + z[o];
+        }
+      }
+    }
+    __syncthreads();
+    // ---- T: rows interpolated, the three row taps added up
+    for (int item = t; item < 3 * BY * cww; item += 256) {
+      const int X = item % cww, fy = (item / cww) % BY, dx = item / (cww * BY);
+      float acc[CO];
+#pragma unroll
+      for (int o = 0; o < CO; ++o) acc[o] = 0.f;
+#pragma unroll
+      for (int dy = 0; dy < 3; ++dy) {
+        const int r = fy + dy;
+        if (row_m[r]) {
+          const float w1 = row_w[r], w0 = 1.0f - w1;
+          const float *za = Z + (dy * 3 + dx) * CO * npx + row_a[r] * cww + X;
+          const float *zb = Z + (dy * 3 + dx) * CO * npx + row_b[r] * cww + X;
+#pragma unroll
+          for (int o = 0; o < CO; ++o) acc[o] += za[o * npx] * w0 + zb[o * npx] * w1;
+        }
+      }
+#pragma unroll
+      for (int o = 0; o < CO; ++o) T[((dx * CO + o) * BY + fy) * cww + X] = acc[o];
+    }
+    __syncthreads();
+    // ---- R: columns interpolated, the three column taps added up; 4 adjacent pixels per thread
     float acc[CO][4];
 #pragma unroll
     for (int o = 0; o < CO; ++o) {
@@ -471,53 +548,49 @@ __global__ __launch_bounds__(256) void residual_unpatchify_kernel(ResArgs a) {
 #pragma unroll
       for (int k = 0; k < 4; ++k) acc[o][k] = bv;
     }
-    for (int ci0 = 0; ci0 < a.C; ci0 += a.ci_chunk) {
-      const int nci = min(a.ci_chunk, a.C - ci0);      // <= CI
-      __syncthreads();                           // previous U / window fully consumed (and tables written)
-      for (int idx = t; idx < nci * cwh * cww; idx += 256) {
-        const int ci = idx / (cwh * cww), r = idx % (cwh * cww);
-        const int wy = r / cww, wx = r % cww;
-        const float *xp = a.x + (static_cast<size_t>(b) * a.V + a.out_var_idx[ci0 + ci]) * a.H * a.W;
-        const int y = min(oy + wy, box_ch - 1), x = min(ox + wx, box_cw - 1);
-        Cw[idx] = xp[static_cast<size_t>(cy_org + y) * a.W + cx_org + x];
+    {
+      int ca[6], cb[6];
+      float cw1[6];
+      bool cm[6];
+#pragma unroll
+      for (int j = 0; j < 6; ++j) {
+        const int wx = 4 * tx + j;
+        ca[j] = col_a[wx]; cb[j] = col_b[wx]; cw1[j] = col_w[wx]; cm[j] = col_m[wx] != 0;
       }
-      __syncthreads();
-      for (int e = t; e < WY * WX; e += 256) {
-        const int wy = e / WX, wx = e % WX;
-        const int ya = row_a[wy] * cww, yb = row_b[wy] * cww, xa = col_a[wx], xb = col_b[wx];
-        const float wy1 = row_w[wy], wx1 = col_w[wx], m = row_m[wy] * col_m[wx];
-        for (int ci = 0; ci < nci; ++ci) {
-          const float *cwp = Cw + ci * cwh * cww;
-          const float top = cwp[ya + xa] * (1.0f - wx1) + cwp[ya + xb] * wx1;
-          const float bot = cwp[yb + xa] * (1.0f - wx1) + cwp[yb + xb] * wx1;
-          const float val = top * (1.0f - wy1) + bot * wy1;
-          U[(ci * WY + wy) * WXP + wx] = m != 0.f ? val : 0.f;
-        }
-      }
-      __syncthreads();
-      for (int ci = 0; ci < nci; ++ci) {
-        float u[3][6];
+      if constexpr (NARROW) {
+        // weight of coarse column X0 + q in fine window column j (clamped neighbours add up)
+        const int X0 = min(ca[0], cww - 3);
+        float e[6][3];
 #pragma unroll
-        for (int dy = 0; dy < 3; ++dy) {
-          const float *up = U + (ci * WY + ty + dy) * WXP + 4 * tx;
-          const float4 lo = *reinterpret_cast<const float4 *>(up);
-          const float2 hi2 = *reinterpret_cast<const float2 *>(up + 4);
-          u[dy][0] = lo.x; u[dy][1] = lo.y; u[dy][2] = lo.z; u[dy][3] = lo.w; u[dy][4] = hi2.x; u[dy][5] = hi2.y;
-        }
+        for (int j = 0; j < 6; ++j)
 #pragma unroll
-        for (int o = 0; o < CO; ++o) {
-          if (co0 + o < a.C) {
-            const float *wr = a.w_res + (static_cast<size_t>(co0 + o) * a.C + ci0 + ci) * 9;
-#pragma unroll
-            for (int dy = 0; dy < 3; ++dy)
-#pragma unroll
-              for (int dx = 0; dx < 3; ++dx) {
-                const float w = wr[dy * 3 + dx];
-#pragma unroll
-                for (int k = 0; k < 4; ++k) acc[o][k] = fmaf(w, u[dy][dx + k], acc[o][k]);
-              }
+          for (int q = 0; q < 3; ++q) {
+            const float v = (ca[j] - X0 == q ? 1.0f - cw1[j] : 0.f) + (cb[j] - X0 == q ? cw1[j] : 0.f);
+            e[j][q] = cm[j] ? v : 0.f;
           }
-        }
+#pragma unroll
+        for (int dx = 0; dx < 3; ++dx)
+#pragma unroll
+          for (int o = 0; o < CO; ++o) {
+            const float *tp = T + ((dx * CO + o) * BY + ty) * cww + X0;
+            const float t0 = tp[0], t1 = tp[1], t2 = tp[2];
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+              acc[o][k] = fmaf(e[k + dx][0], t0, fmaf(e[k + dx][1], t1, fmaf(e[k + dx][2], t2, acc[o][k])));
+          }
+      } else {
+#pragma unroll
+        for (int dx = 0; dx < 3; ++dx)
+#pragma unroll
+          for (int o = 0; o < CO; ++o) {
+            const float *tp = T + ((dx * CO + o) * BY + ty) * cww;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+              const int j = k + dx;
+              const float v = tp[ca[j]] * (1.0f - cw1[j]) + tp[cb[j]] * cw1[j];
+              acc[o][k] += cm[j] ? v : 0.f;
+            }
+          }
       }
     }
     if (iy < ih) {
@@ -528,13 +601,16 @@ __global__ __launch_bounds__(256) void residual_unpatchify_kernel(ResArgs a) {
         const size_t n = static_cast<size_t>(py) * a.Wp + px;
         const float *pp = a.P + (static_cast<size_t>(b) * a.N + n) * a.head_out + static_cast<size_t>(i) * a.ps + j;
         float *yp = a.y + (static_cast<size_t>(b) * a.C * sH + gy) * sW + td.x0 * a.ps + ix;
+        float4 pv[CO];
+#pragma unroll
+        for (int o = 0; o < CO; ++o)
+          if (co0 + o < a.C) pv[o] = *reinterpret_cast<const float4 *>(pp + static_cast<size_t>(co0 + o) * a.ps * a.ps);
 #pragma unroll
         for (int o = 0; o < CO; ++o) {
           const int c = co0 + o;
-          if (c >= a.C) break;
-          const float4 pv = *reinterpret_cast<const float4 *>(pp + static_cast<size_t>(c) * a.ps * a.ps);
-          *reinterpret_cast<float4 *>(yp + static_cast<size_t>(c) * sH * sW) =
-              make_float4(pv.x + acc[o][0], pv.y + acc[o][1], pv.z + acc[o][2], pv.w + acc[o][3]);
+          if (c < a.C)
+            *reinterpret_cast<float4 *>(yp + static_cast<size_t>(c) * sH * sW) =
+                make_float4(pv[o].x + acc[o][0], pv[o].y + acc[o][1], pv[o].z + acc[o][2], pv[o].w + acc[o][3]);
         }
       } else {
 #pragma unroll
@@ -557,6 +633,28 @@ __global__ __launch_bounds__(256) void residual_unpatchify_kernel(ResArgs a) {
   }
 }
 
+// LDS floats of one work-group for CO output variables per pass and ci input variables per window pass
+static size_t residual_lds_floats(int co, int ci, int cwh, int cww) {
+  const size_t npx = static_cast<size_t>(cwh) * cww;
+  return ci * npx + static_cast<size_t>(ci) * 9 * co + 9 * co * npx + 3 * static_cast<size_t>(co) * 16 * cww;
+}
+
+hipError_t residual_init() {
+  hipError_t e = hipSuccess;
+  const int lim = 160 * 1024;
+#define RESLIM_ATTR(K) if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(&K), hipFuncAttributeMaxDynamicSharedMemorySize, lim - 2048)
+  RESLIM_ATTR((residual_unpatchify_kernel<8, true>));
+  RESLIM_ATTR((residual_unpatchify_kernel<4, true>));
+  RESLIM_ATTR((residual_unpatchify_kernel<2, true>));
+  RESLIM_ATTR((residual_unpatchify_kernel<1, true>));
+  RESLIM_ATTR((residual_unpatchify_kernel<8, false>));
+  RESLIM_ATTR((residual_unpatchify_kernel<4, false>));
+  RESLIM_ATTR((residual_unpatchify_kernel<2, false>));
+  RESLIM_ATTR((residual_unpatchify_kernel<1, false>));
+#undef RESLIM_ATTR
+  return e;
+}
+
 hipError_t launch_residual_unpatchify(const reslim_ctx *c, const float *x, const void *P, int p_is_act, float *y,
                                       int batch, hipStream_t st) {
   (void)p_is_act;
@@ -576,12 +674,45 @@ hipError_t launch_residual_unpatchify(const reslim_ctx *c, const float *x, const
   // a block's 18 x 66 fine neighbourhood touches at most this many coarse rows / columns
   a.cwh = 17 / a.s + 3;
   a.cww = 65 / a.s + 3;
-  constexpr int CI = 8;
-  const size_t per_var = static_cast<size_t>(a.cwh) * a.cww * sizeof(float);
-  a.ci_chunk = static_cast<int>(std::min<size_t>(CI, (16 * 1024) / per_var));   // 8 for s >= 2, 3 for s = 1
-  if (a.ci_chunk < 1) return hipErrorInvalidValue;
-  const size_t lds = a.ci_chunk * per_var;
-  residual_unpatchify_kernel<CI, 8><<<dim3(a.nbx * nby, c->T, batch), dim3(256), lds, st>>>(a);
+  // output variables per pass (CO) and input variables per window pass: the widest CO whose
+  // buffers leave room for three, else two, else one work-group per compute unit
+  int co = 0;
+  a.ci_chunk = 0;
+  const size_t fixed_lds = 1024;                         // the tables
+  for (size_t budget : {size_t(52) << 10, size_t(78) << 10, size_t(156) << 10}) {
+    for (int cand : {8, 4, 2, 1}) {
+      if (cand > 1 && cand >= 2 * a.C) continue;         // e.g. C = 3 takes CO = 4, C = 2 takes CO = 2
+      const size_t base = residual_lds_floats(cand, 0, a.cwh, a.cww) * 4 + fixed_lds;
+      const size_t per_ci = (residual_lds_floats(cand, 1, a.cwh, a.cww) - residual_lds_floats(cand, 0, a.cwh, a.cww)) * 4;
+      const int want = std::min(a.C, 4);
+      if (base + per_ci * want > budget) continue;
+      co = cand;
+      a.ci_chunk = static_cast<int>(std::min<size_t>(a.C, (budget - base) / per_ci));
+      break;
+    }
+    if (co) break;
+  }
+  if (!co) return hipErrorInvalidValue;
+  const size_t lds = residual_lds_floats(co, a.ci_chunk, a.cwh, a.cww) * sizeof(float);
+  const dim3 grid(a.nbx * nby, c->T, batch), blk(256);
+  // scale >= 5: six consecutive fine columns span at most one coarse cell width; scale 4: block
+  // origins are multiples of 4 fine columns inside the box, which gives the same bound
+  const bool narrow = a.s >= 5 || (a.s == 4 && a.ps % 4 == 0);
+  if (narrow) {
+    switch (co) {
+      case 8: residual_unpatchify_kernel<8, true><<<grid, blk, lds, st>>>(a); break;
+      case 4: residual_unpatchify_kernel<4, true><<<grid, blk, lds, st>>>(a); break;
+      case 2: residual_unpatchify_kernel<2, true><<<grid, blk, lds, st>>>(a); break;
+      default: residual_unpatchify_kernel<1, true><<<grid, blk, lds, st>>>(a); break;
+    }
+  } else {
+    switch (co) {
+      case 8: residual_unpatchify_kernel<8, false><<<grid, blk, lds, st>>>(a); break;
+      case 4: residual_unpatchify_kernel<4, false><<<grid, blk, lds, st>>>(a); break;
+      case 2: residual_unpatchify_kernel<2, false><<<grid, blk, lds, st>>>(a); break;
+      default: residual_unpatchify_kernel<1, false><<<grid, blk, lds, st>>>(a); break;
+    }
+  }
   return hipGetLastError();
 }
 
