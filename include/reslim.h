@@ -452,14 +452,17 @@ int reslim_asc_forward(reslim_ctx *ctx, const reslim_asc_plan *plan, const float
  * byte counters by what they report for this kernel of known size. */
 int reslim_debug_copy(const void *src, void *dst, size_t bytes, void *hip_stream);
 
-/* Tuning hook for benchmarks: pins the bf16 GEMM kernel (-1 = built-in heuristic, 2 =
- * one 128x128 tile per work-group, 3 = persistent direct-to-LDS 256x256 tiles; add 100
- * to 2 for columns-fastest tile order; other values act like 2).  Process-wide. */
+/* Tuning hook for benchmarks and tests: pins the bf16 GEMM kernel (-1 = built-in heuristic,
+ * 2 = one 128x128 tile per work-group, 3 = persistent direct-to-LDS 256x256 tiles; add 100
+ * to 2 for columns-fastest tile order; other values act like 2).  A plain process-wide
+ * variable read at every launch: not thread-safe, not part of the method; set it while no
+ * other thread is inside the library and restore -1 afterwards. */
 void reslim_debug_set_gemm_tile(int choice);
 
-/* Tuning hook: launch shape of the bf16 tile-attention kernel at head dimension 64
- * (0 = 64-key blocks, three work-groups per compute unit, the default; 1 = 128-key
- * blocks, two work-groups per compute unit).  Process-wide. */
+/* Tuning hook for benchmarks and tests: launch shape of the bf16 tile-attention kernel at
+ * head dimension 64 (0 = 64-key blocks, three work-groups per compute unit, the default;
+ * 1 = 128-key blocks, two work-groups per compute unit).  Process-wide and not thread-safe,
+ * like the hook above. */
 void reslim_debug_set_attention_variant(int variant);
 
 #ifdef __cplusplus

@@ -67,10 +67,6 @@ __device__ __forceinline__ float gelu_erf_fast(float x) {
 // eight complete 128-byte row segments (16 bytes per lane) instead of 64 partial
 // ones; no barrier is involved, the LDS operations of one wave execute in order.
 template <int EPI>
-__device__ __host__ constexpr bool epi_swapped() {
-  return true;
-}
-template <int EPI>
 __device__ __host__ constexpr bool epi_act_out() {
   return EPI == EPI_BIAS_ACT || EPI == EPI_BIAS_QSCALE_ACT || EPI == EPI_BIAS_GELU_ACT || EPI == EPI_BIAS_ACT_GELU2;
 }
@@ -346,9 +342,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void gemm_bf16_kernel(GemmArgs 
       for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
-          acc[i][j] = epi_swapped<EPI>()
-                          ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][j], af[cur][i], acc[i][j], 0, 0, 0)
-                          : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][j], af[cur][i], acc[i][j], 0, 0, 0);   // operands swapped: the block is C^T
           if (i == 0 && j == 0) {
             __builtin_amdgcn_sched_barrier(0);
             if (kk + 1 < BK / 16) {

@@ -101,6 +101,60 @@ def test_tiles_attention_special_cases_bf16():
         assert O.rel_l2(out[0], ref) <= 2e-2
 
 
+# ------------------------------------------------------------------ kernels the heuristics do not pick at small sizes
+@pytest.fixture
+def kernel_hooks():
+    """The two process-wide tuning hooks, restored to the built-in choice whatever the test does."""
+    yield B
+    B.reslim_debug_set_gemm_tile(-1)
+    B.reslim_debug_set_attention_variant(0)
+
+
+@pytest.mark.parametrize("tile", [2, 3, 102], ids=["tiles128", "persistent256", "tiles128_columns_fastest"])
+@pytest.mark.parametrize("cfg", [SMALL_BF16, SMALL_BF16.with_(name="sbf_d64", embed_dim=64, heads=1, mlp_ratio=3)],
+                         ids=lambda c: c.name)
+def test_forced_gemm_kernels_on_small_ragged_shapes(kernel_hooks, cfg, tile):
+    """Each bf16 GEMM kernel forced on shapes the heuristic would give to another one: about a
+    thousand rows (no multiple of 128 or 256), outputs 128, 384 and 512 columns wide (64, 192 at
+    embed dim 64: no multiple of 256, so the persistent kernel's column guard and its half-empty
+    tiles run), contraction lengths 64 .. 512.  One block from the oracle's input, every epilogue
+    (q-scaled bf16, residual add, GELU), then the head GEMM through the whole forward."""
+    say(f"forced GEMM kernel {tile} on {cfg.name}")
+    w = weights_for(cfg, std=0.1)
+    x = WL.make_fields(cfg)
+    y_ref, inter = O.reslim_forward(x, w, cfg, return_intermediates=True)
+    with B.Reslim(cfg, w) as m:
+        kernel_hooks.reslim_debug_set_gemm_tile(tile)
+        prev = inter["tokens"]
+        for l in range(cfg.depth):
+            t = cuda(prev.astype(np.float32))
+            m.block(l, t)
+            assert_parity(t.cpu().numpy(), inter[f"block{l}"], TOL[1], f"block{l}", say)
+            prev = inter[f"block{l}"]
+        assert_parity(m.forward(cuda(x)).cpu().numpy(), y_ref, TOL[1], "forward", say)
+        kernel_hooks.reslim_debug_set_gemm_tile(-1)
+        t = cuda(inter["tokens"].astype(np.float32))
+        m.block(0, t)
+        assert_parity(t.cpu().numpy(), inter["block0"], TOL[1], "block0, built-in choice", say)
+
+
+@pytest.mark.parametrize("variant", [0, 1], ids=["keys64_x3", "keys128_x2"])
+@pytest.mark.parametrize("peaked", [False, True])
+def test_attention_launch_shapes_dh64(kernel_hooks, variant, peaked):
+    """Both launch shapes of the head-dimension-64 kernel (64-key blocks with three work-groups per
+    compute unit, 128-key blocks with two) on ragged tiles (221 .. 285 tokens: the last key block
+    is masked in both), normal and peaked logits."""
+    cfg = SMALL_BF16
+    tiles, _, _, n_h = O.tiles_partition(cfg.Hp, cfg.Wp, cfg.tiles_y, cfg.tiles_x, cfg.halo)
+    qkv = WL.make_qkv(cfg.batch * n_h, cfg.embed_dim, seed=15, peaked=peaked).reshape(cfg.batch, n_h, 3 * cfg.embed_dim)
+    ref = O.tiles_attention(qkv, tiles, cfg.heads)
+    with B.Reslim(cfg, weights_for(cfg)) as m:
+        kernel_hooks.reslim_debug_set_attention_variant(variant)
+        out = m.attention(cuda(qkv, m.act_dtype)).float().cpu().numpy()
+    assert_parity(out, ref, TOL[1], f"attention variant {variant} peaked={peaked}", say)
+    assert np.abs(out - ref).max() <= 3e-2
+
+
 # ------------------------------------------------------------------ embed / block / head
 @pytest.mark.parametrize("cfg", [SMALL_F32, SMALL_BF16, SMALL_BF16_DH128, SMALL_BF16_DH256], ids=lambda c: c.name)
 def test_stage_by_stage_parity(cfg):
