@@ -291,3 +291,102 @@ def block_compressed_bwd(Xc, table, w, layer: int, heads: int, d_out):
         dX[off[b]:off[b + 1]] = dx
         grads = g if grads is None else {k: grads[k] + g[k] for k in g}
     return dX, grads
+
+
+# ---------------------------------------------------------------------------
+# Compression combined with TILES (Table 3 of the paper runs "4x compression, 16 tiles")
+# ---------------------------------------------------------------------------
+# The paper does not say how the two combine.  Reading: TILES cuts the field into haloed
+# boxes and downscales each box "separately" (Sec. 4.2), so each box is compressed
+# separately too, exactly as a whole sample is in the untiled case: the 8-bit image, the
+# edge map and the quad-tree of a tile are those of its haloed box cut out of the field
+# (roots anchored at the box's first patch; a box that is no multiple of the root size is a
+# ragged grid as above).  A leaf never straddles a box edge, halo patches are compressed
+# with their box like any other patch, and after decompression the halo is discarded as in
+# plain TILES: an interior patch takes the token of its leaf in the tile that owns it.
+# parity unpinned against the paper; pinned by: one tile = forward_compressed, one patch
+# per leaf = the plain tiled forward, literal form = batched form.
+def build_tiles(images, p: int, tiles, max_leaf: int, min_leaf: int, low: int, high: int, tau: float, Wp: int):
+    """images[B, H, W] float32, tiles from reslim_oracle.tiles_partition -> dict with the
+    leaf table of the batch in GLOBAL patch coordinates: leaf_y0, leaf_x0, leaf_s [L];
+    sample_off [B*T + 1], one entry per (sample, tile) sequence, sample-major;
+    patch_leaf [B, Hp*Wp]: for each patch the leaf (batch-wide index) that holds it in the
+    tile whose interior owns it."""
+    images = np.asarray(images, np.float32)
+    B, H, W = images.shape
+    Hp = H // p
+    ly, lx, ls, off = [], [], [], [0]
+    patch_leaf = np.full((B, Hp * Wp), -1, np.int64)
+    for b in range(B):
+        for t in tiles:
+            crop = images[b, t["Y0"] * p:t["Y1"] * p, t["X0"] * p:t["X1"] * p]
+            leaves = quadtree_leaves(canny_edges(quantise_u8(crop), low, high), p, max_leaf, min_leaf, tau)
+            for (y0, x0, s) in leaves:
+                idx = len(ly)
+                gy, gx = y0 + t["Y0"], x0 + t["X0"]
+                ly.append(gy); lx.append(gx); ls.append(s)
+                for yy in range(max(gy, t["y0"]), min(gy + s, t["y1"])):
+                    for xx in range(max(gx, t["x0"]), min(gx + s, t["x1"])):
+                        patch_leaf[b, yy * Wp + xx] = idx
+            off.append(len(ly))
+    assert (patch_leaf >= 0).all()
+    return dict(leaf_y0=np.array(ly, np.int64), leaf_x0=np.array(lx, np.int64), leaf_s=np.array(ls, np.int64),
+                sample_off=np.array(off, np.int64), patch_leaf=patch_leaf)
+
+
+def compress_tiles(z, table, Wp: int, T: int):
+    """z[B, N, D] -> [L, D]: mean over each leaf's patches; sequence q belongs to sample q // T."""
+    z = np.asarray(z, F64)
+    out = np.empty((len(table["leaf_s"]), z.shape[2]), F64)
+    off = table["sample_off"]
+    for q in range(len(off) - 1):
+        b = q // T
+        for i in range(int(off[q]), int(off[q + 1])):
+            y0, x0, s = int(table["leaf_y0"][i]), int(table["leaf_x0"][i]), int(table["leaf_s"][i])
+            rows = [yy * Wp + xx for yy in range(y0, y0 + s) for xx in range(x0, x0 + s)]
+            out[i] = z[b, rows, :].sum(axis=0) / float(s * s)
+    return out
+
+
+def forward_compressed_tiles(x, w, cfg, table):
+    """Batched form of the tiled forward with compression: embed once, one leaf set per
+    (sample, tile), blocks with attention inside a leaf set, each patch decompressed from
+    the tile that owns it, final LayerNorm, head, residual path per tile."""
+    x = np.asarray(x, F64)
+    B, V, H, W = x.shape
+    p, s, C = cfg.patch, cfg.scale, cfg.out_vars
+    Hp, Wp = H // p, W // p
+    ps = p * s
+    tiles = ro.tiles_partition(Hp, Wp, cfg.tiles_y, cfg.tiles_x, cfg.halo)[0]
+    z = ro.embed_tokens(x, w, p, cfg.heads, cfg.res_idx)
+    Xc = blocks_compressed(compress_tiles(z, table, Wp, len(tiles)), table, w, cfg)
+    Xn = ro.layer_norm(decompress(Xc, table), w["lnf_g"], w["lnf_b"])
+    y = ro.unpatchify(ro.head_project(Xn, w), Hp, Wp, C, ps)
+    for t in tiles:
+        iy0, ix0 = (t["y0"] - t["Y0"]) * ps, (t["x0"] - t["X0"]) * ps
+        hy, hx = (t["y1"] - t["y0"]) * ps, (t["x1"] - t["x0"]) * ps
+        for b in range(B):
+            r = ro.residual_path(x[b, :, t["Y0"] * p:t["Y1"] * p, t["X0"] * p:t["X1"] * p], w, s)
+            y[b, :, t["y0"] * ps:t["y1"] * ps, t["x0"] * ps:t["x1"] * ps] += r[:, iy0:iy0 + hy, ix0:ix0 + hx]
+    return y
+
+
+def forward_compressed_tile_literal(x_b, image_b, w, cfg, tile: dict, Wp: int, max_leaf: int, min_leaf: int,
+                                    low: int, high: int, tau: float):
+    """Literal form for one tile of one sample: cut the haloed box out of the field (and out
+    of the image the detector looks at), run the UNTILED compressed model on the cut with
+    position rows taken at the global positions, discard the halo.  Returns the fine interior."""
+    p, s, C = cfg.patch, cfg.scale, cfg.out_vars
+    ps = p * s
+    t = tile
+    box = np.asarray(x_b, F64)[:, t["Y0"] * p:t["Y1"] * p, t["X0"] * p:t["X1"] * p]
+    crop = np.asarray(image_b, np.float32)[t["Y0"] * p:t["Y1"] * p, t["X0"] * p:t["X1"] * p]
+    hp, wp = t["Y1"] - t["Y0"], t["X1"] - t["X0"]
+    table = build(crop[None], p, max_leaf, min_leaf, low, high, tau)
+    pos_rows = np.array([y * Wp + xx for y in range(t["Y0"], t["Y1"]) for xx in range(t["X0"], t["X1"])])
+    z = ro.embed_tokens(box[None], w, p, cfg.heads, cfg.res_idx, pos_rows=pos_rows)
+    Xc = blocks_compressed(compress(z, table, wp), table, w, cfg)
+    Xn = ro.layer_norm(decompress(Xc, table), w["lnf_g"], w["lnf_b"])
+    y = ro.unpatchify(ro.head_project(Xn, w), hp, wp, C, ps)[0] + ro.residual_path(box, w, s)
+    iy0, ix0 = (t["y0"] - t["Y0"]) * ps, (t["x0"] - t["X0"]) * ps
+    return y[:, iy0:iy0 + (t["y1"] - t["y0"]) * ps, ix0:ix0 + (t["x1"] - t["x0"]) * ps]

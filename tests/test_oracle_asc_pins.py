@@ -10,6 +10,7 @@ from scipy import ndimage
 
 from oracle import asc_oracle as A
 from oracle import reslim_oracle as ro
+O = ro
 from paper_2505_04802_amd import workloads as WL
 
 
@@ -268,3 +269,90 @@ def test_block_gradient_on_leaves_by_finite_differences():
     dX2, _ = A.block_compressed_bwd(X, tab, w, 0, cfg.heads, d2)
     np.testing.assert_allclose(dX2[:5], dX[:5], atol=1e-14)
     assert np.abs(dX2[5:]).max() == 0.0
+
+
+# ----------------------------------------------------------------- compression combined with TILES
+def _tiled_case(seed=21, tiles_y=2, tiles_x=3, halo=1, H=24, W=40, depth=2):
+    cfg = WL.ReslimConfig("asc_tiles", batch=2, in_vars=3, out_vars=2, H=H, W=W, scale=2, patch=2, embed_dim=16, heads=2,
+                          mlp_ratio=2, depth=depth, tiles_y=tiles_y, tiles_x=tiles_x, halo=halo, dtype=0, seed=seed)
+    w = WL.make_weights(cfg, std=0.3)
+    x = WL.make_fields(cfg)
+    tiles = O.tiles_partition(cfg.Hp, cfg.Wp, tiles_y, tiles_x, halo)[0]
+    return cfg, w, x, tiles
+
+
+PRM = dict(max_leaf=4, min_leaf=1, low=30, high=70, tau=0.08)
+
+
+def test_tiled_table_is_a_partition_of_every_haloed_box():
+    cfg, w, x, tiles = _tiled_case()
+    tab = A.build_tiles(x[:, 0], cfg.patch, tiles, Wp=cfg.Wp, **PRM)
+    off = tab["sample_off"]
+    assert len(off) == cfg.batch * len(tiles) + 1 and off[0] == 0 and off[-1] == len(tab["leaf_s"])
+    some_merged = False
+    for q in range(len(off) - 1):
+        b, t = q // len(tiles), tiles[q % len(tiles)]
+        cover = np.zeros((cfg.Hp, cfg.Wp), int)
+        for i in range(off[q], off[q + 1]):
+            y0, x0, s = tab["leaf_y0"][i], tab["leaf_x0"][i], tab["leaf_s"][i]
+            assert s & (s - 1) == 0 and (y0 - t["Y0"]) % s == 0 and (x0 - t["X0"]) % s == 0      # aligned to the box
+            assert t["Y0"] <= y0 and y0 + s <= t["Y1"] and t["X0"] <= x0 and x0 + s <= t["X1"]   # never straddles it
+            cover[y0:y0 + s, x0:x0 + s] += 1
+            some_merged |= s > 1
+        want = np.zeros_like(cover)
+        want[t["Y0"]:t["Y1"], t["X0"]:t["X1"]] = 1
+        assert (cover == want).all()
+        # interior patches point at a leaf of their own tile that holds them
+        for yy in range(t["y0"], t["y1"]):
+            for xx in range(t["x0"], t["x1"]):
+                i = tab["patch_leaf"][b, yy * cfg.Wp + xx]
+                assert off[q] <= i < off[q + 1]
+                assert tab["leaf_y0"][i] <= yy < tab["leaf_y0"][i] + tab["leaf_s"][i]
+                assert tab["leaf_x0"][i] <= xx < tab["leaf_x0"][i] + tab["leaf_s"][i]
+    assert some_merged and len(tab["leaf_s"]) < cfg.batch * sum(t["n_tok"] for t in tiles)
+
+
+def test_tiled_compressed_forward_batched_equals_literal():
+    """The table-driven form the library follows against the literal one: cut each haloed box
+    out of the field, run the untiled compressed model on it, keep the interior."""
+    cfg, w, x, tiles = _tiled_case()
+    tab = A.build_tiles(x[:, 0], cfg.patch, tiles, Wp=cfg.Wp, **PRM)
+    y = A.forward_compressed_tiles(x, w, cfg, tab)
+    ps = cfg.patch * cfg.scale
+    for b in range(cfg.batch):
+        for t in tiles:
+            lit = A.forward_compressed_tile_literal(x[b], x[b, 0], w, cfg, t, cfg.Wp, **PRM)
+            np.testing.assert_allclose(y[b, :, t["y0"] * ps:t["y1"] * ps, t["x0"] * ps:t["x1"] * ps], lit, atol=1e-10)
+
+
+def test_tiled_compressed_forward_special_cases():
+    # one tile: the tiled functions ARE the untiled compressed forward
+    cfg, w, x, tiles = _tiled_case(tiles_y=1, tiles_x=1, halo=3)
+    tab1 = A.build_tiles(x[:, 0], cfg.patch, tiles, Wp=cfg.Wp, **PRM)
+    tab0 = A.build(x[:, 0], cfg.patch, PRM["max_leaf"], PRM["min_leaf"], PRM["low"], PRM["high"], PRM["tau"])
+    for k in tab0:
+        assert np.array_equal(tab0[k], tab1[k]), k
+    np.testing.assert_allclose(A.forward_compressed_tiles(x, w, cfg, tab1), A.forward_compressed(x, w, cfg, tab0), atol=1e-12)
+    # one patch per leaf (thresholds nothing passes, minimum = maximum = 1): the plain tiled forward
+    cfg, w, x, tiles = _tiled_case()
+    tab = A.build_tiles(x[:, 0], cfg.patch, tiles, 1, 1, 30, 70, 0.08, Wp=cfg.Wp)
+    assert len(tab["leaf_s"]) == cfg.batch * sum(t["n_tok"] for t in tiles) and (tab["leaf_s"] == 1).all()
+    np.testing.assert_allclose(A.forward_compressed_tiles(x, w, cfg, tab), O.reslim_forward(x, w, cfg), atol=1e-12)
+    # the order of leaves inside a (sample, tile) sequence is the tile-major token order in that case
+    g = O.tiles_partition(cfg.Hp, cfg.Wp, cfg.tiles_y, cfg.tiles_x, cfg.halo)[1]
+    n_h = len(g)
+    rows = tab["leaf_y0"] * cfg.Wp + tab["leaf_x0"]
+    assert np.array_equal(rows[:n_h], g) and np.array_equal(rows[n_h:], g)
+    # tiles do not interact: changing the field inside one tile's interior, away from every halo,
+    # leaves the other tiles' outputs untouched
+    cfg, w, x, tiles = _tiled_case(tiles_y=1, tiles_x=2, halo=1, H=16, W=64)
+    tab = A.build_tiles(x[:, 0], cfg.patch, tiles, Wp=cfg.Wp, **PRM)
+    y = A.forward_compressed_tiles(x, w, cfg, tab)
+    x2 = x.copy()
+    x2[:, :, :, :8] += 1.0                                             # far inside tile 0 (its halo ends at column 34)
+    tab2 = A.build_tiles(x2[:, 0], cfg.patch, tiles, Wp=cfg.Wp, **PRM)
+    y2 = A.forward_compressed_tiles(x2, w, cfg, tab2)
+    ps = cfg.patch * cfg.scale
+    t1 = tiles[1]
+    np.testing.assert_allclose(y2[..., t1["x0"] * ps:], y[..., t1["x0"] * ps:], atol=1e-12)
+    assert np.abs(y2[..., :8 * cfg.scale] - y[..., :8 * cfg.scale]).max() > 1e-3
