@@ -352,8 +352,9 @@ int reslim_bayes_loss_fwd_static(const float *pred, const float *target, const f
  * gives the image, reslim_asc_build (host) the leaf table, reslim_asc_plan_create
  * checks and uploads it, reslim_asc_forward runs the model on the leaves.  The
  * paper gives no thresholds, filter sizes or merge rule; the readings are stated at
- * each function.  Compression is not combined with tiling: the context must have
- * tiles_y = tiles_x = 1 (then halo is irrelevant). */
+ * each function.  With a tiled context every (sample, tile) pair has its own leaf set
+ * (reslim_asc_build_tiles); the gradients of compression and decompression
+ * (reslim_asc_compress_bwd, reslim_asc_decompress_bwd) need a one-tile context. */
 typedef struct reslim_asc_plan reslim_asc_plan;
 
 /* HOST function, no HIP call.  images: host fp32 [batch, H, W].  Per sample:
@@ -385,18 +386,39 @@ int reslim_asc_build(const float *images, int32_t batch, int32_t H, int32_t W, i
                      int32_t *leaf_x0, int32_t *leaf_s, int32_t *sample_off, int32_t *patch_leaf,
                      int64_t *n_leaves_out);
 
+/* HOST function, no HIP call: compression combined with TILES (Sec. 4.2; the paper's
+ * Table 3 runs both together and does not say how they combine).  Reading: every
+ * (sample, tile) pair is compressed on its own -- steps 1-3 above applied to the tile's
+ * haloed box cut out of images[b] (the 8-bit range, the filters' replicated borders and
+ * the quad-tree roots all belong to the box; a box that is no multiple of max_leaf is a
+ * ragged grid), so no leaf straddles a box edge and halo patches are compressed with
+ * their box.  tiles_y, tiles_x, halo as in reslim_config (tiles_partition gives the
+ * boxes).  Outputs, room for batch * n_h entries each (n_h = tile-major tokens per
+ * sample): leaf_y0, leaf_x0 in GRID patch coordinates, leaf_s; seq_off [batch * T + 1]:
+ * first leaf of sequence b * T + t; patch_leaf [batch, Hp * Wp]: for each patch the leaf
+ * that holds it in the tile whose interior owns it (what decompression reads).
+ * With one tile the result is reslim_asc_build's.  Errors as reslim_asc_build, plus
+ * RESLIM_ESHAPE for a tile grid tiles_partition refuses. */
+int reslim_asc_build_tiles(const float *images, int32_t batch, int32_t H, int32_t W, int32_t patch, int32_t tiles_y,
+                           int32_t tiles_x, int32_t halo, int32_t max_leaf, int32_t min_leaf, int32_t canny_low,
+                           int32_t canny_high, float tau, int32_t *leaf_y0, int32_t *leaf_x0, int32_t *leaf_s,
+                           int32_t *seq_off, int32_t *patch_leaf, int64_t *n_leaves_out);
+
 /* HOST: steps 1-2 above for one field; edges_out: host [H*W], 1 where an edge pixel
  * was found.  For inspection and tests. */
 int reslim_asc_edges(const float *image, int32_t H, int32_t W, int32_t canny_low, int32_t canny_high, uint8_t *edges_out);
 
-/* Checks that the table is what reslim_asc_build produces for this context's grid
- * (aligned power-of-two squares, every patch of every sample in exactly one leaf,
- * patch_leaf the inverse map: RESLIM_EINVAL otherwise, the kernels rely on it) and
- * copies it to the device (allocates; synchronous copies).  All pointers host.
- * *out is NULL on failure; destroy the plan before its context.  RESLIM_ESHAPE if
- * the context has more than one tile or embed_dim % 4 != 0. */
+/* Checks that the table is what reslim_asc_build (one tile) or reslim_asc_build_tiles
+ * produces for this context's grid and tiling -- per (sample, tile) sequence: power-of-two
+ * squares aligned to the tile's haloed box, inside it, covering each of its patches exactly
+ * once; patch_leaf naming, for every patch, the leaf of the owning tile that holds it:
+ * RESLIM_EINVAL otherwise, the kernels rely on it -- and copies it to the device
+ * (allocates; synchronous copies).  All pointers host; sample_off has n_sequences + 1
+ * entries and n_sequences must be batch * T (T tiles of the context; sequences
+ * sample-major).  *out is NULL on failure; destroy the plan before its context.
+ * RESLIM_ESHAPE if n_sequences != batch * T or embed_dim % 4 != 0. */
 int reslim_asc_plan_create(reslim_ctx *ctx, int32_t batch, const int32_t *leaf_y0, const int32_t *leaf_x0,
-                           const int32_t *leaf_s, int64_t n_leaves, const int32_t *sample_off,
+                           const int32_t *leaf_s, int64_t n_leaves, const int32_t *sample_off, int64_t n_sequences,
                            const int32_t *patch_leaf, reslim_asc_plan **out);
 void reslim_asc_plan_destroy(reslim_asc_plan *plan);
 int reslim_asc_plan_info(const reslim_asc_plan *plan, int64_t *n_leaves, int32_t *max_per_sample);

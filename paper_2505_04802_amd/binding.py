@@ -36,7 +36,7 @@ EXPORTS = ["tiles_partition", "reslim_create", "reslim_destroy", "reslim_last_er
            "reslim_train_prepare", "reslim_layernorm_bwd", "reslim_linear_bwd_workspace_bytes", "reslim_linear_bwd",
            "reslim_block_train_bytes", "reslim_block_fwd_train", "reslim_block_bwd",
            "reslim_block_grads_unscale", "reslim_grad_scale_update",
-           "reslim_asc_build", "reslim_asc_edges", "reslim_asc_plan_create", "reslim_asc_plan_destroy",
+           "reslim_asc_build", "reslim_asc_build_tiles", "reslim_asc_edges", "reslim_asc_plan_create", "reslim_asc_plan_destroy",
            "reslim_asc_plan_info", "reslim_asc_image", "reslim_asc_compress", "reslim_asc_forward",
            "reslim_asc_decompress", "reslim_asc_compress_bwd", "reslim_asc_decompress_bwd",
            "reslim_asc_block_train_bytes", "reslim_asc_block_fwd_train", "reslim_asc_block_bwd"]
@@ -123,8 +123,10 @@ def load() -> C.CDLL:
     lib.reslim_bayes_loss_static_max_groups.argtypes = [C.POINTER(C.c_int64)]
     lib.reslim_bayes_loss_fwd_static.argtypes = [vp, vp, vp, i32, i32, i32, i32, C.c_float, vp, vp]
     lib.reslim_asc_build.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, i32, C.c_float, vp, vp, vp, vp, vp, C.POINTER(C.c_int64)]
+    lib.reslim_asc_build_tiles.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, i32, i32, i32, i32, C.c_float, vp, vp, vp, vp, vp,
+                                           C.POINTER(C.c_int64)]
     lib.reslim_asc_edges.argtypes = [vp, i32, i32, i32, i32, vp]
-    lib.reslim_asc_plan_create.argtypes = [vp, i32, vp, vp, vp, C.c_int64, vp, vp, C.POINTER(vp)]
+    lib.reslim_asc_plan_create.argtypes = [vp, i32, vp, vp, vp, C.c_int64, vp, C.c_int64, vp, C.POINTER(vp)]
     lib.reslim_asc_plan_destroy.argtypes = [vp]
     lib.reslim_asc_plan_destroy.restype = None
     lib.reslim_asc_plan_info.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(i32)]
@@ -390,6 +392,30 @@ def reslim_asc_build(images: np.ndarray, patch: int, max_leaf: int, min_leaf: in
                 patch_leaf=pl.reshape(B, -1))
 
 
+def reslim_asc_build_tiles(images: np.ndarray, patch: int, tiles_y: int, tiles_x: int, halo: int, max_leaf: int, min_leaf: int,
+                           canny_low: int, canny_high: int, tau: float) -> Dict[str, np.ndarray]:
+    """Host function: reslim_asc_build per (sample, tile) on the tile's haloed box.  Returns the table of
+    reslim_asc_build with leaf coordinates on the whole grid and sample_off [B * T + 1] (one entry per
+    (sample, tile) sequence)."""
+    images = np.ascontiguousarray(images, np.float32)
+    B, H, W = images.shape
+    Hp, Wp = H // max(patch, 1), W // max(patch, 1)
+    n_h = C.c_int64(0)
+    if Hp >= 1 and Wp >= 1 and tiles_y >= 1 and tiles_x >= 1:
+        _check(load().tiles_partition(Hp, Wp, tiles_y, tiles_x, halo, (TileDesc * (tiles_y * tiles_x))(), None, None, C.byref(n_h)))
+    cap = max(B * int(n_h.value), 1)
+    ly, lx, ls = (np.zeros(cap, np.int32) for _ in range(3))
+    off = np.zeros(B * max(tiles_y * tiles_x, 1) + 1, np.int32)
+    pl = np.zeros(max(B * Hp * Wp, 1), np.int32)
+    n = C.c_int64(0)
+    _check(load().reslim_asc_build_tiles(images.ctypes.data, B, H, W, patch, tiles_y, tiles_x, halo, max_leaf, min_leaf,
+                                         canny_low, canny_high, tau, ly.ctypes.data, lx.ctypes.data, ls.ctypes.data,
+                                         off.ctypes.data, pl.ctypes.data, C.byref(n)))
+    L = int(n.value)
+    return dict(leaf_y0=ly[:L].copy(), leaf_x0=lx[:L].copy(), leaf_s=ls[:L].copy(), sample_off=off,
+                patch_leaf=pl.reshape(B, -1))
+
+
 def reslim_asc_edges(image: np.ndarray, canny_low: int, canny_high: int) -> np.ndarray:
     image = np.ascontiguousarray(image, np.float32)
     H, W = image.shape
@@ -403,7 +429,7 @@ def reslim_asc_plan_create(ctx, batch: int, table: Dict[str, np.ndarray]) -> int
     out = C.c_void_p(None)
     _check(load().reslim_asc_plan_create(ctx, batch, arrs["leaf_y0"].ctypes.data, arrs["leaf_x0"].ctypes.data,
                                          arrs["leaf_s"].ctypes.data, len(arrs["leaf_s"]), arrs["sample_off"].ctypes.data,
-                                         arrs["patch_leaf"].ctypes.data, C.byref(out)), ctx)
+                                         len(arrs["sample_off"]) - 1, arrs["patch_leaf"].ctypes.data, C.byref(out)), ctx)
     return out.value
 
 

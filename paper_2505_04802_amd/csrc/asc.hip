@@ -112,57 +112,71 @@ static int asc_check(reslim_ctx *c, const reslim_asc_plan *pl, const char *fn) {
 using namespace reslim;
 
 extern "C" int reslim_asc_plan_create(reslim_ctx *c, int32_t batch, const int32_t *leaf_y0, const int32_t *leaf_x0,
-                                      const int32_t *leaf_s, int64_t n_leaves, const int32_t *sample_off,
+                                      const int32_t *leaf_s, int64_t n_leaves, const int32_t *sample_off, int64_t n_sequences,
                                       const int32_t *patch_leaf, reslim_asc_plan **out) {
   const char *fn = "reslim_asc_plan_create";
   if (!c) return RESLIM_EINVAL;
   if (out) *out = nullptr;
   if (!leaf_y0 || !leaf_x0 || !leaf_s || !sample_off || !patch_leaf || !out)
     return set_error(c, RESLIM_EINVAL, std::string(fn) + ": null pointer");
-  if (c->T != 1) return set_error(c, RESLIM_ESHAPE, std::string(fn) + ": the context must be created with one tile (compression and tiling are not combined)");
   const int64_t N = c->N;
+  const int T = c->T;
+  const int64_t n_seq = static_cast<int64_t>(batch) * T;
   if (c->cfg.embed_dim % 4) return set_error(c, RESLIM_ESHAPE, std::string(fn) + ": embed_dim must be a multiple of 4");
-  if (batch < 1 || n_leaves < batch || n_leaves > batch * N || batch * N > INT32_MAX)
+  if (n_sequences != n_seq)
+    return set_error(c, RESLIM_ESHAPE, std::string(fn) + ": the table must hold one sequence per (sample, tile) of this context");
+  if (batch < 1 || n_seq > INT32_MAX || n_leaves < n_seq || n_leaves > batch * c->n_h || batch * N > INT32_MAX || batch * c->n_h > INT32_MAX)
     return set_error(c, RESLIM_ESHAPE, std::string(fn) + ": batch or leaf count out of range");
-  // The table must be a partition of every sample's patch grid into aligned squares,
-  // listed sample by sample, and patch_leaf its inverse: the kernels trust it.
-  if (sample_off[0] != 0 || sample_off[batch] != n_leaves) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": sample_off does not span the leaves");
+  // Per (sample, tile) sequence the leaves must partition the tile's haloed box into squares
+  // aligned to the box, and patch_leaf must name, for every patch, its leaf in the tile that
+  // owns it: the kernels trust the table.
+  if (sample_off[0] != 0 || sample_off[n_seq] != n_leaves) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": sample_off does not span the leaves");
   std::vector<int32_t> leaf(static_cast<size_t>(n_leaves) * 4, 0), seq_of(static_cast<size_t>(n_leaves));
-  std::vector<tile_desc> seq(batch);
+  std::vector<tile_desc> seq(n_seq);
+  std::vector<int32_t> owner;                  // leaf of every box patch of the sequence at hand
   int max_n = 0;
   double pairs = 0;
-  for (int b = 0; b < batch; ++b) {
-    const int64_t lo = sample_off[b], hi = sample_off[b + 1];
+  for (int64_t q = 0; q < n_seq; ++q) {
+    const int64_t b = q / T;
+    const tile_desc &td = c->tiles[q % T];
+    const int hp = td.Y1 - td.Y0, wp = td.X1 - td.X0;
+    const int64_t lo = sample_off[q], hi = sample_off[q + 1];
     if (hi <= lo || hi > n_leaves) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": sample_off not increasing");
-    int64_t covered = 0;
+    owner.assign(static_cast<size_t>(hp) * wp, -1);
     for (int64_t l = lo; l < hi; ++l) {
       const int y0 = leaf_y0[l], x0 = leaf_x0[l], s = leaf_s[l];
-      if (s < 1 || (s & (s - 1)) || y0 < 0 || x0 < 0 || y0 % s || x0 % s || y0 + s > c->Hp || x0 + s > c->Wp)
-        return set_error(c, RESLIM_EINVAL, std::string(fn) + ": leaf outside the grid or not an aligned power-of-two square");
+      if (s < 1 || (s & (s - 1)) || y0 < td.Y0 || x0 < td.X0 || (y0 - td.Y0) % s || (x0 - td.X0) % s || y0 + s > td.Y1 || x0 + s > td.X1)
+        return set_error(c, RESLIM_EINVAL, std::string(fn) + ": leaf outside its box or not an aligned power-of-two square");
       for (int yy = y0; yy < y0 + s; ++yy)
-        for (int xx = x0; xx < x0 + s; ++xx)
-          if (patch_leaf[b * N + static_cast<int64_t>(yy) * c->Wp + xx] != l)
-            return set_error(c, RESLIM_EINVAL, std::string(fn) + ": patch_leaf disagrees with the leaf list");
-      covered += static_cast<int64_t>(s) * s;
+        for (int xx = x0; xx < x0 + s; ++xx) {
+          int32_t &o = owner[static_cast<size_t>(yy - td.Y0) * wp + (xx - td.X0)];
+          if (o != -1) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": two leaves of a sequence overlap");
+          o = static_cast<int32_t>(l);
+        }
       leaf[4 * l] = static_cast<int32_t>(b * N + static_cast<int64_t>(y0) * c->Wp + x0);
       leaf[4 * l + 1] = s;
-      seq_of[l] = b;
+      seq_of[l] = static_cast<int32_t>(q);
     }
-    if (covered != N) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": leaves of a sample do not cover its grid exactly once");
-    seq[b] = tile_desc{};
-    seq[b].tok_off = lo;
-    seq[b].n_tok = static_cast<int32_t>(hi - lo);
-    max_n = std::max(max_n, seq[b].n_tok);
+    for (int32_t o : owner)
+      if (o == -1) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": leaves of a sequence do not cover its box");
+    for (int yy = td.y0; yy < td.y1; ++yy)
+      for (int xx = td.x0; xx < td.x1; ++xx)
+        if (patch_leaf[b * N + static_cast<int64_t>(yy) * c->Wp + xx] != owner[static_cast<size_t>(yy - td.Y0) * wp + (xx - td.X0)])
+          return set_error(c, RESLIM_EINVAL, std::string(fn) + ": patch_leaf disagrees with the leaf list");
+    seq[q] = tile_desc{};
+    seq[q].tok_off = lo;
+    seq[q].n_tok = static_cast<int32_t>(hi - lo);
+    max_n = std::max(max_n, seq[q].n_tok);
     pairs += static_cast<double>(hi - lo) * static_cast<double>(hi - lo);
   }
   reslim_asc_plan *pl = new (std::nothrow) reslim_asc_plan;
   if (!pl) return set_error(c, RESLIM_ENOMEM, std::string(fn) + ": host allocation failed");
   pl->ctx = c; pl->batch = batch; pl->L = n_leaves; pl->seq = seq;
-  hipError_t e = hipMalloc(reinterpret_cast<void **>(&pl->d_seq), batch * sizeof(tile_desc));
+  hipError_t e = hipMalloc(reinterpret_cast<void **>(&pl->d_seq), n_seq * sizeof(tile_desc));
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&pl->d_seq_of_leaf), n_leaves * 4);
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&pl->d_leaf), n_leaves * 16);
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&pl->d_patch_leaf), batch * N * 4);
-  if (e == hipSuccess) e = hipMemcpy(pl->d_seq, seq.data(), batch * sizeof(tile_desc), hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(pl->d_seq, seq.data(), n_seq * sizeof(tile_desc), hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy(pl->d_seq_of_leaf, seq_of.data(), n_leaves * 4, hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy(pl->d_leaf, leaf.data(), n_leaves * 16, hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy(pl->d_patch_leaf, patch_leaf, batch * N * 4, hipMemcpyHostToDevice);
@@ -172,7 +186,7 @@ extern "C" int reslim_asc_plan_create(reslim_ctx *c, int32_t batch, const int32_
   }
   pl->geom.d_tiles = pl->d_seq;
   pl->geom.d_tile_of_tok = pl->d_seq_of_leaf;
-  pl->geom.T = batch;
+  pl->geom.T = static_cast<int>(n_seq);
   pl->geom.n_h = n_leaves;
   pl->geom.max_n_tok = max_n;
   pl->geom.pairs = pairs;
@@ -214,6 +228,9 @@ static int asc_move(reslim_ctx *c, const reslim_asc_plan *plan, const char *fn, 
   int rc = asc_check(c, plan, fn);
   if (rc != RESLIM_OK) return rc;
   if (!src || !dst) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": null buffer");
+  // with tiles a patch sits in the leaves of several boxes and a leaf decompresses only into its
+  // tile's interior: the two gradient maps below assume one leaf per patch
+  if (mode != 0 && c->T != 1) return set_error(c, RESLIM_ESHAPE, std::string(fn) + ": needs a context with one tile");
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const int D = c->cfg.embed_dim;
   const int64_t patches = static_cast<int64_t>(plan->batch) * c->N;

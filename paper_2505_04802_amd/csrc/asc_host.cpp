@@ -181,6 +181,68 @@ extern "C" int reslim_asc_build(const float *images, int32_t batch, int32_t H, i
   return RESLIM_OK;
 }
 
+// Compression combined with TILES: every (sample, tile) pair is compressed on its own, on the
+// tile's haloed box cut out of the field, exactly as reslim_asc_build treats a whole sample.
+extern "C" int reslim_asc_build_tiles(const float *images, int32_t batch, int32_t H, int32_t W, int32_t patch,
+                                      int32_t tiles_y, int32_t tiles_x, int32_t halo, int32_t max_leaf, int32_t min_leaf,
+                                      int32_t canny_low, int32_t canny_high, float tau, int32_t *leaf_y0, int32_t *leaf_x0,
+                                      int32_t *leaf_s, int32_t *seq_off, int32_t *patch_leaf, int64_t *n_leaves_out) {
+  if (!images || !leaf_y0 || !leaf_x0 || !leaf_s || !seq_off || !patch_leaf || !n_leaves_out) return RESLIM_EINVAL;
+  if (batch < 1 || H < 1 || W < 1 || patch < 1 || canny_low < 0 || canny_high < canny_low || !(tau >= 0.0f) || !std::isfinite(tau))
+    return RESLIM_EINVAL;
+  if (!pow2(max_leaf) || !pow2(min_leaf) || min_leaf > max_leaf || H % patch || W % patch) return RESLIM_ESHAPE;
+  const int Hp = H / patch, Wp = W / patch;
+  if (tiles_y < 1 || tiles_x < 1) return RESLIM_ESHAPE;
+  const int T = tiles_y * tiles_x;
+  std::vector<tile_desc> tiles(T);
+  int64_t n_h = 0;
+  const int rc = tiles_partition(Hp, Wp, tiles_y, tiles_x, halo, tiles.data(), nullptr, nullptr, &n_h);
+  if (rc != RESLIM_OK) return rc;
+  if (static_cast<int64_t>(batch) * n_h > INT32_MAX) return RESLIM_ESHAPE;
+  const size_t npix = static_cast<size_t>(H) * W, N = static_cast<size_t>(Hp) * Wp;
+  std::vector<float> crop;
+  std::vector<int32_t> q, local;
+  std::vector<uint8_t> edges;
+  std::vector<int64_t> sat;
+  int64_t n = 0;
+  seq_off[0] = 0;
+  for (int b = 0; b < batch; ++b)
+    for (int t = 0; t < T; ++t) {
+      const tile_desc &td = tiles[t];
+      const int hp = td.Y1 - td.Y0, wp = td.X1 - td.X0, ch = hp * patch, cw = wp * patch;
+      crop.resize(static_cast<size_t>(ch) * cw);
+      for (int y = 0; y < ch; ++y)
+        std::copy_n(images + b * npix + static_cast<size_t>(td.Y0 * patch + y) * W + td.X0 * patch, cw, crop.begin() + static_cast<size_t>(y) * cw);
+      if (!quantise(crop.data(), crop.size(), q)) return RESLIM_EINVAL;
+      canny(q, ch, cw, canny_low, canny_high, edges);
+      const size_t w = static_cast<size_t>(wp) + 1;
+      sat.assign((hp + 1) * w, 0);
+      for (int py = 0; py < hp; ++py)
+        for (int px = 0; px < wp; ++px) {
+          int64_t c = 0;
+          for (int i = 0; i < patch; ++i)
+            for (int j = 0; j < patch; ++j) c += edges[static_cast<size_t>(py * patch + i) * cw + px * patch + j];
+          sat[(py + 1) * w + px + 1] = c + sat[py * w + px + 1] + sat[(py + 1) * w + px] - sat[py * w + px];
+        }
+      local.assign(static_cast<size_t>(hp) * wp, -1);
+      const int64_t first = n;
+      TreeBuilder tb{sat, hp, wp, patch, min_leaf, tau, leaf_y0, leaf_x0, leaf_s, local.data(), n};
+      for (int ry = 0; ry < hp; ry += max_leaf)
+        for (int rx = 0; rx < wp; rx += max_leaf) tb.visit(ry, rx, max_leaf);
+      n = tb.n;
+      for (int64_t l = first; l < n; ++l) {          // box coordinates -> grid coordinates
+        leaf_y0[l] += td.Y0;
+        leaf_x0[l] += td.X0;
+      }
+      for (int yy = td.y0; yy < td.y1; ++yy)         // the tile's interior patches decompress from its own leaves
+        for (int xx = td.x0; xx < td.x1; ++xx)
+          patch_leaf[b * N + static_cast<size_t>(yy) * Wp + xx] = local[static_cast<size_t>(yy - td.Y0) * wp + (xx - td.X0)];
+      seq_off[static_cast<size_t>(b) * T + t + 1] = static_cast<int32_t>(n);
+    }
+  *n_leaves_out = n;
+  return RESLIM_OK;
+}
+
 // Canny edge map of one 8-bit-quantised field, for inspection and tests: edges [H*W] 0/1
 extern "C" int reslim_asc_edges(const float *image, int32_t H, int32_t W, int32_t canny_low, int32_t canny_high, uint8_t *edges_out) {
   if (!image || !edges_out || H < 1 || W < 1 || canny_low < 0 || canny_high < canny_low) return RESLIM_EINVAL;

@@ -95,3 +95,37 @@ def test_builder_matches_oracle_on_random_shapes():
         ref = A.build(imgs, patch, mx, mn, low, high, tau)
         for k in KEYS:
             assert np.array_equal(np.asarray(got[k]), np.asarray(ref[k])), (trial, k, Hp, Wp, patch, mx, mn, low, high, tau)
+
+
+# ----------------------------------------------------------------- compression combined with TILES (host builder)
+@pytest.mark.parametrize("seed,shape,patch,ty,tx,halo,mx,mn,low,high,tau,smooth", [
+    (10, (2, 48, 80), 2, 2, 3, 1, 4, 1, 20, 60, 0.05, 2.0),
+    (11, (1, 64, 64), 2, 4, 4, 2, 8, 1, 15, 40, 0.03, 3.0),
+    (12, (3, 30, 44), 1, 3, 2, 3, 8, 2, 25, 70, 0.06, 1.5),       # boxes that are no multiple of the root size
+    (13, (1, 180, 360), 2, 4, 4, 2, 16, 1, 30, 70, 0.05, 3.0),    # the paper's 112 km grid with its 16 tiles
+    (14, (2, 32, 48), 2, 1, 1, 5, 8, 1, 20, 60, 0.05, 2.0),       # one tile: the untiled builder
+])
+def test_tiled_builder_matches_oracle(seed, shape, patch, ty, tx, halo, mx, mn, low, high, tau, smooth):
+    from oracle import reslim_oracle as O
+    imgs = fields(seed, *shape, smooth)
+    Hp, Wp = shape[1] // patch, shape[2] // patch
+    tiles = O.tiles_partition(Hp, Wp, ty, tx, halo)[0]
+    got = B.reslim_asc_build_tiles(imgs, patch, ty, tx, halo, mx, mn, low, high, tau)
+    ref = A.build_tiles(imgs, patch, tiles, mx, mn, low, high, tau, Wp=Wp)
+    for k in KEYS:
+        assert np.asarray(got[k]).shape == np.asarray(ref[k]).shape, k
+        assert (np.asarray(got[k]) == np.asarray(ref[k])).all(), k
+    if ty == tx == 1:
+        one = B.reslim_asc_build(imgs, patch, mx, mn, low, high, tau)
+        for k in KEYS:
+            assert np.array_equal(one[k], got[k]), k
+
+
+def test_tiled_builder_errors():
+    imgs = fields(20, 1, 16, 24, 2.0)
+    with pytest.raises(B.ReslimError):
+        B.reslim_asc_build_tiles(imgs, 2, 9, 1, 1, 4, 1, 10, 20, 0.05)     # more tile rows than patch rows
+    with pytest.raises(B.ReslimError):
+        B.reslim_asc_build_tiles(imgs, 2, 2, 2, -1, 4, 1, 10, 20, 0.05)    # negative halo
+    with pytest.raises(B.ReslimError):
+        B.reslim_asc_build_tiles(imgs, 2, 2, 2, 1, 3, 1, 10, 20, 0.05)     # leaf bound not a power of two

@@ -340,3 +340,110 @@ def test_compressed_forward_at_the_papers_grid():
     err = max(O.rel_l2(out[b, c], ref[b, c]) for b in range(cfg.batch) for c in range(cfg.out_vars))
     say(f"  max rel-L2 over planes {err:.3e}")
     assert np.isfinite(out).all() and err <= TOL[1]
+
+
+# ------------------------------------------------------------------ compression combined with TILES
+from parity_checks import assert_parity
+
+TILED_F32 = ASC_F32.with_(name="a32t", tiles_y=2, tiles_x=3, halo=1, seed=41)
+TILED_BF16 = ASC_BF16.with_(name="abft", tiles_y=2, tiles_x=2, halo=2, seed=42)
+TILED_BF16_RAGGED = ASC_BF16_RAGGED.with_(name="abftr", tiles_y=3, tiles_x=2, halo=3, seed=43)
+
+
+def tiled_table_for(cfg, x, max_leaf=8, min_leaf=1, tau=0.05):
+    tiles = O.tiles_partition(cfg.Hp, cfg.Wp, cfg.tiles_y, cfg.tiles_x, cfg.halo)[0]
+    imgs = np.ascontiguousarray(x[:, 0])
+    gx, gy = A.sobel(A.smooth(A.quantise_u8(imgs[0])))
+    mag = np.abs(gx) + np.abs(gy)
+    low, high = int(np.quantile(mag, 0.6)), int(np.quantile(mag, 0.85))
+    return A.build_tiles(imgs, cfg.patch, tiles, max_leaf, min_leaf, low, high, tau, Wp=cfg.Wp), tiles, (low, high)
+
+
+@pytest.mark.parametrize("cfg", [TILED_F32, TILED_BF16, TILED_BF16_RAGGED], ids=lambda c: c.name)
+def test_tiled_compressed_forward_parity(cfg):
+    """Every (sample, tile) pair compressed on its own haloed box, attention among the leaves of one
+    box, interior patches decompressed from their own tile: whole output against the oracle; the
+    library's host builder must give the oracle's table."""
+    say(f"asc + tiles forward {cfg.name}")
+    w = WL.make_weights(cfg, std=0.05)
+    x = WL.make_fields(cfg)
+    tab, tiles, (low, high) = tiled_table_for(cfg, x)
+    lib = B.reslim_asc_build_tiles(np.ascontiguousarray(x[:, 0]), cfg.patch, cfg.tiles_y, cfg.tiles_x, cfg.halo, 8, 1, low, high, 0.05)
+    for k in tab:
+        assert np.array_equal(np.asarray(tab[k]), np.asarray(lib[k])), k
+    L, n_h = len(tab["leaf_s"]), sum(t["n_tok"] for t in tiles)
+    per_seq = np.diff(tab["sample_off"])
+    say(f"  {cfg.batch * n_h} haloed patches -> {L} leaves, per (sample, tile) {per_seq.tolist()}")
+    assert L < cfg.batch * n_h and len(set(per_seq.tolist())) > 1
+    ref = A.forward_compressed_tiles(x, w, cfg, tab)
+    with B.Reslim(cfg, w) as m:
+        plan = B.reslim_asc_plan_create(m.ctx, cfg.batch, tab)
+        try:
+            assert B.reslim_asc_plan_info(plan) == (L, int(per_seq.max()))
+            y = torch.full((cfg.batch, cfg.out_vars, cfg.H * cfg.scale, cfg.W * cfg.scale), float("nan"),
+                           dtype=torch.float32, device="cuda")
+            B.reslim_asc_forward(m.ctx, plan, cuda(x), y, m.ws)
+            out = y.cpu().numpy()
+            B.reslim_asc_forward(m.ctx, plan, cuda(x), y, m.ws)
+            assert np.array_equal(out, y.cpu().numpy())               # same input, same bits
+        finally:
+            B.reslim_asc_plan_destroy(plan)
+    assert_parity(out, ref, TOL[cfg.dtype], "tiled compressed forward", say)
+
+
+def test_tiled_single_patch_leaves_reproduce_the_plain_tiled_forward():
+    cfg = TILED_BF16
+    w = WL.make_weights(cfg, std=0.05)
+    x = WL.make_fields(cfg)
+    tiles = O.tiles_partition(cfg.Hp, cfg.Wp, cfg.tiles_y, cfg.tiles_x, cfg.halo)[0]
+    tab = A.build_tiles(np.ascontiguousarray(x[:, 0]), cfg.patch, tiles, 1, 1, 10, 20, 0.05, Wp=cfg.Wp)
+    assert (tab["leaf_s"] == 1).all()
+    with B.Reslim(cfg, w) as m:
+        plan = B.reslim_asc_plan_create(m.ctx, cfg.batch, tab)
+        try:
+            y = torch.empty((cfg.batch, cfg.out_vars, cfg.H * cfg.scale, cfg.W * cfg.scale), dtype=torch.float32, device="cuda")
+            B.reslim_asc_forward(m.ctx, plan, cuda(x), y, m.ws)
+            plain = m.forward(cuda(x)).cpu().numpy()
+        finally:
+            B.reslim_asc_plan_destroy(plan)
+    # the same rows through the same kernels: the leaf mean of one patch and the row maps are exact
+    assert np.array_equal(y.cpu().numpy(), plain)
+    assert_parity(plain, O.reslim_forward(x, w, cfg), TOL[1], "plain tiled forward", say)
+
+
+def test_tiled_plan_errors():
+    cfg = TILED_F32
+    x = WL.make_fields(cfg)
+    tab, tiles, _ = tiled_table_for(cfg, x)
+    with B.Reslim(cfg, WL.make_weights(cfg)) as m:
+        lib = B.load()
+        # a leaf moved across its box edge, two leaves swapped between sequences, a hole, a wrong owner
+        q1 = int(tab["sample_off"][1])
+        bad = {k: np.array(v, copy=True) for k, v in tab.items()}
+        bad["leaf_x0"][q1] -= int(bad["leaf_s"][q1])                     # first leaf of tile 1 pushed out of its box
+        with pytest.raises(B.ReslimError):
+            B.reslim_asc_plan_create(m.ctx, cfg.batch, bad)
+        bad = {k: np.array(v, copy=True) for k, v in tab.items()}
+        bad["leaf_y0"][0], bad["leaf_x0"][0] = bad["leaf_y0"][1], bad["leaf_x0"][1]
+        bad["leaf_s"][0] = bad["leaf_s"][1]                              # leaf 0 duplicates leaf 1: overlap and hole
+        with pytest.raises(B.ReslimError):
+            B.reslim_asc_plan_create(m.ctx, cfg.batch, bad)
+        bad = {k: np.array(v, copy=True) for k, v in tab.items()}
+        t1 = tiles[1]
+        g = t1["y0"] * cfg.Wp + t1["x0"]                                 # an interior patch of tile 1 ...
+        bad["patch_leaf"][0, g] = 0                                      # ... decompressed from a leaf of tile 0
+        with pytest.raises(B.ReslimError):
+            B.reslim_asc_plan_create(m.ctx, cfg.batch, bad)
+        one = A.build(np.ascontiguousarray(x[:, 0]), cfg.patch, 8, 1, 20, 60, 0.05)     # an untiled table
+        with pytest.raises(B.ReslimError):
+            B.reslim_asc_plan_create(m.ctx, cfg.batch, one)
+        plan = B.reslim_asc_plan_create(m.ctx, cfg.batch, tab)
+        try:
+            L, D = len(tab["leaf_s"]), cfg.embed_dim
+            a = torch.zeros((L, D), dtype=torch.float32, device="cuda")
+            b = torch.zeros((cfg.batch * cfg.n_tokens, D), dtype=torch.float32, device="cuda")
+            assert lib.reslim_asc_compress_bwd(m.ctx, plan, a.data_ptr(), b.data_ptr(), None) == B.RESLIM_ESHAPE
+            assert lib.reslim_asc_decompress_bwd(m.ctx, plan, b.data_ptr(), a.data_ptr(), None) == B.RESLIM_ESHAPE
+            B.reslim_asc_decompress(m.ctx, plan, a, b)                    # the forward map itself is fine
+        finally:
+            B.reslim_asc_plan_destroy(plan)
