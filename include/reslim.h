@@ -259,6 +259,74 @@ int reslim_block_grads_unscale(reslim_ctx *ctx, const reslim_block_grads *grads,
 int reslim_grad_scale_update(float *scale, int32_t *growth_tracker, int32_t found_inf, float growth_factor,
                              float backoff_factor, int32_t growth_interval);
 
+/* ---- Gradients of the whole model for one training step (the paper trains the model, Sec. 5,
+ * with the loss of Sec. 4.1 and bfloat16 + gradient scaling, Sec. 4.4; it prints no gradient
+ * formula: all of this is the chain rule through the forward operations).  Precision as for the
+ * block gradient: gradients that feed a GEMM are rounded to the activation type, sums are fp32,
+ * parameter gradients are fp32, WRITTEN (not accumulated), summed in a fixed order. ---- */
+
+/* Device fp32 gradient buffers, one per parameter tensor, shapes as in reslim_weights (per-block
+ * tensors stacked over depth; out_var_idx is a selection, not a parameter). */
+typedef struct {
+  float *w_pe, *b_pe, *var_emb, *agg_q0, *agg_wq, *agg_bq, *agg_wk, *agg_bk, *agg_wv, *agg_bv, *agg_wo, *agg_bo,
+        *pos_emb, *res_emb;                                         /* front end */
+  float *ln1_g, *ln1_b, *w_qkv, *b_qkv, *w_proj, *b_proj, *ln2_g, *ln2_b, *w_fc1, *b_fc1, *w_fc2, *b_fc2;   /* blocks */
+  float *lnf_g, *lnf_b, *w_head, *b_head, *w_res, *b_res;          /* back end */
+} reslim_grads;
+
+/* reslim_train_prepare plus what the two ends of the model need: device copies of the unfolded
+ * front-end parameters (weights: HOST pointers as given to reslim_create, read during this call
+ * only), [in, out] copies of the head's and the aggregation's output maps, and the list of
+ * tile-major copies of every patch.  Allocates and synchronises; idempotent.  RESLIM_ESHAPE on the
+ * bfloat16 path unless out_vars * (patch * scale)^2 is a multiple of 64. */
+int reslim_train_prepare_model(reslim_ctx *ctx, const reslim_weights *weights);
+
+/* Gradient of the loss of reslim_bayes_loss_fwd (its total) with respect to pred, times `upstream`
+ * (the loss scale of Sec. 4.4, or 1):
+ *   d_pred[b,k,r,c] = upstream * (2 lat_w[r] (pred - target) / n
+ *                                 + 2 tv_weight / n * sum_{j in C(i)} b_ij sign(pred_i - pred_j)),
+ * n = all pixel values; every ordered pair of the prior's double sum contains pixel i twice, hence
+ * the factor 2; sign(0) = 0 (the subgradient taken where |.| has no derivative).
+ * All pointers dev fp32, shapes as in reslim_bayes_loss_fwd; d_pred must not alias pred.
+ * batch * vars <= 65535, Hf <= 65535.  Errors: RESLIM_EINVAL, RESLIM_EHIP. */
+int reslim_bayes_loss_bwd(const float *pred, const float *target, const float *lat_w, int32_t batch, int32_t vars,
+                          int32_t Hf, int32_t Wf, float tv_weight, float upstream, float *d_pred, void *hip_stream);
+
+/* Back end backwards (reslim_head_fwd's gradient): from d_y (dev fp32 [batch, C, s*H, s*W]), the
+ * field x and the stream `tokens` (dev fp32 [batch, n_h, D]) that went into reslim_head_fwd it writes
+ * d_tokens (dev fp32 [batch, n_h, D]: the final LayerNorm's input gradient on interior tokens, zero on
+ * halo copies, whose outputs Sec. 4.2 discards) and grads->lnf_g, lnf_b, w_head, b_head, w_res, b_res
+ * (the other fields of grads are not touched).  workspace: 256-byte aligned, >=
+ * reslim_head_bwd_workspace_bytes.  Needs reslim_train_prepare_model, scale >= 2. */
+int reslim_head_bwd_workspace_bytes(const reslim_ctx *ctx, int32_t batch, size_t *out);
+int reslim_head_bwd(reslim_ctx *ctx, const float *x, const float *tokens, const float *d_y, float *d_tokens,
+                    const reslim_grads *grads, int32_t batch, void *workspace, size_t ws_bytes, void *hip_stream);
+
+/* Front end backwards (reslim_embed_fwd's gradient): from d_tokens (dev fp32 [batch, n_h, D], the
+ * gradient of the tile-major stream) and the field x it writes the fourteen front-end gradients of
+ * grads (w_pe .. res_emb): a patch adds up the gradients of its halo copies; rows of res_emb the
+ * forward did not read get zero; agg_bk gets what the arithmetic leaves of an exactly zero gradient
+ * (a key bias shifts all variables' logits alike).  workspace >= reslim_embed_bwd_workspace_bytes. */
+int reslim_embed_bwd_workspace_bytes(const reslim_ctx *ctx, int32_t batch, size_t *out);
+int reslim_embed_bwd(reslim_ctx *ctx, const float *x, const float *d_tokens, const reslim_grads *grads, int32_t batch,
+                     void *workspace, size_t ws_bytes, void *hip_stream);
+
+/* One training step without the parameter update: forward keeping every block's intermediates,
+ * loss, backward through the whole model.
+ *   x dev fp32 [batch, V, H, W]; target dev fp32 [batch, C, s*H, s*W]; lat_w dev fp32 [s*H];
+ *   y dev fp32 [batch, C, s*H, s*W] out (the prediction); loss3 dev, 3 doubles out (total, data,
+ *   prior: unscaled); grads: all 32 gradients, multiplied by loss_scale (divide with
+ *   reslim_grads_unscale); saved / workspace: 256-byte aligned, >= reslim_train_step_bytes.
+ * Everything is enqueued on hip_stream; nothing is allocated or synchronised; deterministic.
+ * Errors: RESLIM_EINVAL (null, prepare not called, bad scale), RESLIM_ESHAPE, RESLIM_EWORKSPACE, RESLIM_EHIP. */
+int reslim_train_step_bytes(const reslim_ctx *ctx, int32_t batch, size_t *saved_bytes, size_t *ws_bytes);
+int reslim_train_step_grads(reslim_ctx *ctx, const float *x, const float *target, const float *lat_w, float tv_weight,
+                            float loss_scale, float *y, double *loss3, const reslim_grads *grads, int32_t batch,
+                            void *saved, size_t saved_bytes, void *workspace, size_t ws_bytes, void *hip_stream);
+
+/* reslim_block_grads_unscale for all 32 gradients of the model. */
+int reslim_grads_unscale(reslim_ctx *ctx, const reslim_grads *grads, float inv_scale, int32_t *found_inf, void *hip_stream);
+
 /* One pre-LayerNorm transformer block `layer` (0-based) on the tile-major stream:
  * X += proj(tile_attention(qkv(LN1(X)))); X += fc2(gelu(fc1(LN2(X)))).
  *   x_inout dev float [batch, n_h, D], updated in place */

@@ -159,8 +159,9 @@ def embed_tokens_bwd(x, w, patch: int, heads: int, res_idx: int, d_z):
 def reslim_loss_and_grads(x, target, w, cfg, lat_w, tv_weight: float = 1.0):
     """One training step's forward and backward: returns ((total, data, prior), gradients of every
     parameter tensor by name, intermediates) for the batch x[B, V, H, W] with targets
-    target[B, C, s*H, s*W].  Intermediates: "y", "d_y", "d_P" (head projection), "d_tokens_out"
-    (tile-major stream after the last block), "d_tokens_in" (before the first), "d_z" (patch order)."""
+    target[B, C, s*H, s*W].  Intermediates: "y", "d_y", "d_P" (head projection), "tokens_out" and
+    "d_tokens_out" (tile-major stream after the last block and its gradient), "d_tokens_in" (gradient
+    of the stream before the first block), "d_z" (patch order)."""
     x = np.asarray(x, F64)
     B, V, H, W = x.shape
     p, s, C = cfg.patch, cfg.scale, cfg.out_vars
@@ -206,7 +207,7 @@ def reslim_loss_and_grads(x, target, w, cfg, lat_w, tv_weight: float = 1.0):
     d_Xn = np.zeros_like(Xn)
     d_Xn[:, interior_src, :] = d_int.reshape(B, N, -1)               # the halo's outputs are discarded: zero gradient
     d_X, g["lnf_g"], g["lnf_b"] = ro.layer_norm_bwd(stream[-1], w["lnf_g"], d_Xn)
-    inter = {"y": y, "d_y": d_y, "d_P": d_P, "d_tokens_out": d_X.copy()}
+    inter = {"y": y, "d_y": d_y, "d_P": d_P, "tokens_out": stream[-1], "d_tokens_out": d_X.copy()}
     for name in ro.BLOCK_PARAMS:
         g[name] = np.zeros_like(np.asarray(w[name], F64))
     for layer in reversed(range(cfg.depth)):

@@ -36,6 +36,9 @@ EXPORTS = ["tiles_partition", "reslim_create", "reslim_destroy", "reslim_last_er
            "reslim_train_prepare", "reslim_layernorm_bwd", "reslim_linear_bwd_workspace_bytes", "reslim_linear_bwd",
            "reslim_block_train_bytes", "reslim_block_fwd_train", "reslim_block_bwd",
            "reslim_block_grads_unscale", "reslim_grad_scale_update",
+           "reslim_train_prepare_model", "reslim_bayes_loss_bwd", "reslim_head_bwd_workspace_bytes", "reslim_head_bwd",
+           "reslim_embed_bwd_workspace_bytes", "reslim_embed_bwd", "reslim_train_step_bytes", "reslim_train_step_grads",
+           "reslim_grads_unscale",
            "reslim_asc_build", "reslim_asc_build_tiles", "reslim_asc_edges", "reslim_asc_plan_create", "reslim_asc_plan_destroy",
            "reslim_asc_plan_info", "reslim_asc_image", "reslim_asc_compress", "reslim_asc_forward",
            "reslim_asc_decompress", "reslim_asc_compress_bwd", "reslim_asc_decompress_bwd",
@@ -60,6 +63,14 @@ BLOCK_PARAMS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_proj", "b_proj", "ln2_g",
 
 class BlockGradsC(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in BLOCK_PARAMS]
+
+
+MODEL_PARAMS = ("w_pe", "b_pe", "var_emb", "agg_q0", "agg_wq", "agg_bq", "agg_wk", "agg_bk", "agg_wv", "agg_bv", "agg_wo", "agg_bo",
+                "pos_emb", "res_emb") + BLOCK_PARAMS + ("lnf_g", "lnf_b", "w_head", "b_head", "w_res", "b_res")
+
+
+class GradsC(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in MODEL_PARAMS]
 
 
 class ProfileRecord(C.Structure):
@@ -104,6 +115,16 @@ def load() -> C.CDLL:
     lib.reslim_block_grads_unscale.argtypes = [vp, C.POINTER(BlockGradsC), C.c_float, vp, vp]
     lib.reslim_grad_scale_update.argtypes = [C.POINTER(C.c_float), C.POINTER(i32), i32, C.c_float, C.c_float, i32]
     lib.reslim_train_prepare.argtypes = [vp]
+    lib.reslim_train_prepare_model.argtypes = [vp, C.POINTER(ReslimWeightsC)]
+    lib.reslim_bayes_loss_bwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, C.c_float, C.c_float, vp, vp]
+    lib.reslim_head_bwd_workspace_bytes.argtypes = [vp, i32, szp]
+    lib.reslim_embed_bwd_workspace_bytes.argtypes = [vp, i32, szp]
+    lib.reslim_head_bwd.argtypes = [vp, vp, vp, vp, vp, C.POINTER(GradsC), i32, vp, C.c_size_t, vp]
+    lib.reslim_embed_bwd.argtypes = [vp, vp, vp, C.POINTER(GradsC), i32, vp, C.c_size_t, vp]
+    lib.reslim_train_step_bytes.argtypes = [vp, i32, szp, szp]
+    lib.reslim_train_step_grads.argtypes = [vp, vp, vp, vp, C.c_float, C.c_float, vp, vp, C.POINTER(GradsC), i32, vp, C.c_size_t,
+                                            vp, C.c_size_t, vp]
+    lib.reslim_grads_unscale.argtypes = [vp, C.POINTER(GradsC), C.c_float, vp, vp]
     lib.reslim_layernorm_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.c_int64, vp, C.c_size_t, vp]
     lib.reslim_linear_bwd_workspace_bytes.argtypes = [vp, i32, i32, szp]
     lib.reslim_linear_bwd.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, i32, vp, C.c_size_t, vp]
@@ -305,6 +326,70 @@ def _nbytes(t) -> int:
 
 def reslim_train_prepare(ctx):
     _check(load().reslim_train_prepare(ctx), ctx)
+
+
+def reslim_train_prepare_model(ctx, weights: Dict[str, np.ndarray]) -> None:
+    keep = []
+    wc = ReslimWeightsC()
+    for n in _WEIGHT_FIELDS:
+        a = np.ascontiguousarray(weights[n], dtype=np.int32 if n == "out_var_idx" else np.float32)
+        keep.append(a)
+        setattr(wc, n, a.ctypes.data)
+    _check(load().reslim_train_prepare_model(ctx, C.byref(wc)), ctx)
+
+
+def _grads_c(grads) -> "GradsC":
+    """grads: name -> fp32 CUDA tensor; names that are absent become null pointers."""
+    return GradsC(**{n: (grads[n].data_ptr() if n in grads else None) for n in MODEL_PARAMS})
+
+
+def reslim_bayes_loss_bwd(pred, target, lat_w, tv_weight: float, upstream: float, d_pred, stream=None) -> None:
+    b, k, hf, wf = pred.shape
+    _check(load().reslim_bayes_loss_bwd(pred.data_ptr(), target.data_ptr(), lat_w.data_ptr(), b, k, hf, wf, float(tv_weight),
+                                        float(upstream), d_pred.data_ptr(), _stream_ptr(stream)))
+
+
+def reslim_head_bwd_workspace_bytes(ctx, batch: int) -> int:
+    n = C.c_size_t(0)
+    _check(load().reslim_head_bwd_workspace_bytes(ctx, batch, C.byref(n)), ctx)
+    return int(n.value)
+
+
+def reslim_embed_bwd_workspace_bytes(ctx, batch: int) -> int:
+    n = C.c_size_t(0)
+    _check(load().reslim_embed_bwd_workspace_bytes(ctx, batch, C.byref(n)), ctx)
+    return int(n.value)
+
+
+def reslim_head_bwd(ctx, x, tokens, d_y, d_tokens, grads, batch: int, workspace, stream=None) -> None:
+    g = _grads_c(grads)
+    _check(load().reslim_head_bwd(ctx, x.data_ptr(), tokens.data_ptr(), d_y.data_ptr(), d_tokens.data_ptr(), C.byref(g), batch,
+                                  workspace.data_ptr(), _nbytes(workspace), _stream_ptr(stream)), ctx)
+
+
+def reslim_embed_bwd(ctx, x, d_tokens, grads, batch: int, workspace, stream=None) -> None:
+    g = _grads_c(grads)
+    _check(load().reslim_embed_bwd(ctx, x.data_ptr(), d_tokens.data_ptr(), C.byref(g), batch, workspace.data_ptr(),
+                                   _nbytes(workspace), _stream_ptr(stream)), ctx)
+
+
+def reslim_train_step_bytes(ctx, batch: int):
+    a, b = C.c_size_t(0), C.c_size_t(0)
+    _check(load().reslim_train_step_bytes(ctx, batch, C.byref(a), C.byref(b)), ctx)
+    return int(a.value), int(b.value)
+
+
+def reslim_train_step_grads(ctx, x, target, lat_w, tv_weight: float, loss_scale: float, y, loss3, grads, batch: int, saved,
+                            workspace, stream=None) -> None:
+    g = _grads_c(grads)
+    _check(load().reslim_train_step_grads(ctx, x.data_ptr(), target.data_ptr(), lat_w.data_ptr(), float(tv_weight), float(loss_scale),
+                                          y.data_ptr(), loss3.data_ptr(), C.byref(g), batch, saved.data_ptr(), _nbytes(saved),
+                                          workspace.data_ptr(), _nbytes(workspace), _stream_ptr(stream)), ctx)
+
+
+def reslim_grads_unscale(ctx, grads, inv_scale: float, found_inf, stream=None) -> None:
+    g = _grads_c(grads)
+    _check(load().reslim_grads_unscale(ctx, C.byref(g), float(inv_scale), found_inf.data_ptr(), _stream_ptr(stream)), ctx)
 
 
 def reslim_layernorm_bwd(ctx, x, dy, gamma, res, dx, dgamma, dbeta, rows, workspace, stream=None):

@@ -43,6 +43,15 @@ struct LayerWeights {
   float *b_qkv, *b_proj, *b_fc1, *b_fc2;     // fp32
 };
 
+// What the whole-model gradient needs beside the inference context (reslim_train_prepare_model)
+struct TrainModel {
+  bool ready = false;
+  float *w_pe = nullptr, *b_pe = nullptr, *var_emb = nullptr, *q0 = nullptr;     // unfolded front end, fp32
+  float *wq = nullptr, *bq = nullptr, *wk = nullptr, *bk = nullptr, *wv = nullptr, *bv = nullptr;
+  void *wt_head = nullptr, *wt_agg_wo = nullptr;                                 // act [D, head_out], [D, D]: [in, out] copies
+  int32_t *copy_off = nullptr, *copy_idx = nullptr;                              // tile-major copies of every patch: [N + 1], [n_h]
+};
+
 }  // namespace reslim
 
 struct reslim_ctx {
@@ -72,6 +81,7 @@ struct reslim_ctx {
   float *d_b_head;
   float *d_w_res, *d_b_res;                  // [C, C, 3, 3], [C]
   int32_t *d_out_var_idx;
+  reslim::TrainModel train;
   std::vector<void *> allocs;                // everything to hipFree
   std::string err;
   // optional per-launch timing (reslim_profile_*): events are created up front
