@@ -104,6 +104,62 @@ def train_block(B, torch, model, cfg, K, verbose):
     return res
 
 
+def train_step(B, torch, np, model, cfg, w, x_host, K, verbose):
+    """Times reslim_train_step_grads: forward keeping intermediates, Bayesian loss, backward through the whole
+    model (all 32 parameter gradients), the loss scaled by 1024 (Sec. 4.4) and the gradients unscaled again."""
+    B.reslim_train_prepare_model(model.ctx, w)
+    sb, wb = B.reslim_train_step_bytes(model.ctx, cfg.batch)
+    saved = torch.empty(sb, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(wb, dtype=torch.uint8, device="cuda")
+    sH, sW = cfg.H * cfg.scale, cfg.W * cfg.scale
+    x = torch.from_numpy(x_host).cuda()
+    g = torch.Generator(device="cuda").manual_seed(1)
+    target = torch.randn((cfg.batch, cfg.out_vars, sH, sW), generator=g, device="cuda")
+    lat = np.cos(np.deg2rad(-90.0 + (np.arange(sH) + 0.5) * 180.0 / sH))
+    lat_w = torch.from_numpy((lat / lat.mean()).astype(np.float32)).cuda()
+    y = torch.empty_like(target)
+    loss3 = torch.zeros(3, dtype=torch.float64, device="cuda")
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    grads = {n: torch.empty(np.shape(w[n]), dtype=torch.float32, device="cuda") for n in B.MODEL_PARAMS}
+
+    def step():
+        B.reslim_train_step_grads(model.ctx, x, target, lat_w, 1.0, 1024.0, y, loss3, grads, cfg.batch, saved, ws)
+        B.reslim_grads_unscale(model.ctx, grads, 1.0 / 1024.0, flag)
+
+    for _ in range(2):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / K * 1e3
+    B.reslim_profile_enable(model.ctx, 4096)
+    step()
+    torch.cuda.synchronize()
+    agg = {}
+    for name, kms, flop, nbytes in B.reslim_profile_read(model.ctx):
+        a = agg.setdefault(name, dict(calls=0, ms=0.0, flop=0.0, bytes=0.0))
+        a["calls"] += 1
+        a["ms"] += kms
+        a["flop"] += flop
+        a["bytes"] += nbytes
+    B.reslim_profile_enable(model.ctx, 0)
+    ks = [dict(kernel=n, launches=a["calls"], ms=round(a["ms"], 5),
+               tflops=round(a["flop"] / (a["ms"] * 1e-3) / 1e12, 2) if a["flop"] and a["ms"] > 0 else None,
+               gbs=round(a["bytes"] / (a["ms"] * 1e-3) / 1e9, 1) if a["ms"] > 0 else None) for n, a in agg.items()]
+    ks.sort(key=lambda k: -k["ms"])
+    gflop, aflop, hflop = B.reslim_flop_counts(model.ctx, cfg.batch)
+    flop = 3.0 * (gflop + hflop) + 3.5 * aflop          # forward + input and weight gradients; attention gradient 2.5 x forward
+    if verbose:
+        for k in ks:
+            print("train_step " + json.dumps(k), file=sys.stderr)
+    return dict(ms_per_step=round(ms, 4), unique_tokens_per_s=round(cfg.batch * cfg.n_tokens / (ms * 1e-3), 1),
+                tflops=round(flop / (ms * 1e-3) / 1e12, 2), mfma_frac=round(flop / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                loss=[float(v) for v in loss3.cpu()], found_inf=int(flag.item()), saved_gb=round(sb / 1e9, 2),
+                workspace_gb=round(wb / 1e9, 2), kernels=ks)
+
+
 # Adaptive spatial compression (Sec. 4.1; Table 2(b) quotes speed-ups at 8x / 16x / 32x compression
 # on one tile): the workload's grid untiled, quad-trees from the library's host builder on the
 # first input variable.  Parameters chosen so that the c1 fields compress about 8x and 22x, and the
@@ -215,7 +271,7 @@ def asc_leg(B, torch, np, cfg, w, x_host, K):
     return res
 
 
-def measure(B, torch, cfg, w, x_host, K, W, verbose, want_train, note):
+def measure(B, torch, cfg, w, x_host, K, W, verbose, want_train, note, want_step=False):
     """W warm-up + K timed forwards of one workload, then the same K steps again with every launch
     bracketed by HIP events on the launch stream.  Returns (result dict, open model)."""
     model = B.Reslim(cfg, w)
@@ -290,7 +346,15 @@ def measure(B, torch, cfg, w, x_host, K, W, verbose, want_train, note):
     # ---- extra, outside `value`: one block's training forward + backward at the same shape
     # (gradient of tile attention, input- and weight-gradient GEMMs, LayerNorm / GELU gradients)
     res["train_block"] = train_block(B, torch, model, cfg, K, verbose) if want_train and cfg.depth > 0 else None
+    del x, y
+    torch.cuda.empty_cache()
+    res["train_step"] = None
+    if want_step and cfg.dtype == 1 and cfg.depth > 0:
+        import numpy as np
+        note(f"{cfg.name}: whole training step (forward, loss, all gradients)")
+        res["train_step"] = train_step(B, torch, np, model, cfg, w, x_host, max(2, K // 4), verbose)
     model.close()
+    x = y = None
     del x, y
     torch.cuda.empty_cache()
     return res
@@ -342,6 +406,8 @@ def main() -> int:
     ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
     ap.add_argument("--no-train-block", action="store_true",
                     help="skip the extra (untimed in `value`) measurement of one block's training forward + backward")
+    ap.add_argument("--no-train-step", action="store_true",
+                    help="skip the extra measurement of reslim_train_step_grads (whole-model training step)")
     ap.add_argument("--no-asc", action="store_true",
                     help="skip the extra measurement of the forward with adaptive spatial compression (run for c0, c1 and m9m only)")
     ap.add_argument("--asc-only", action="store_true",
@@ -395,7 +461,7 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
     note(f"{cfg.name}: {W} warm-up + {K} timed steps, then {K} steps with per-launch events")
-    head = measure(B, torch, cfg, w, x_host, K, W, args.kernels, not args.no_train_block, note)
+    head = measure(B, torch, cfg, w, x_host, K, W, args.kernels, not args.no_train_block, note, not args.no_train_step)
 
     # ---- extra, outside `value`: the untiled grid with and without adaptive spatial compression
     asc = None
@@ -415,7 +481,7 @@ def main() -> int:
         ocfg = WL.CONFIGS[name]
         ow, ox = inputs(ocfg)
         note(f"{name}: {W} warm-up + {K} timed steps, then {K} steps with per-launch events")
-        r = measure(B, torch, ocfg, ow, ox, K, W, args.kernels, False, note)
+        r = measure(B, torch, ocfg, ow, ox, K, W, args.kernels, False, note, name == "c1" and not args.no_train_step)
         if name == "c1" and not args.no_asc:
             r["asc"] = asc_leg(B, torch, np, ocfg, ow, ox, K)
         other[name] = r
@@ -428,7 +494,7 @@ def main() -> int:
         "data": "synthetic", "config": head["config"],
         "tflops": head["tflops"], "mfma_frac": head["mfma_frac"], "haloed_tokens_per_s": head["haloed_tokens_per_s"],
         "roofline": head["roofline"], "cpu_baseline": cpu, "kernels": head["kernels"],
-        "train_block": head["train_block"], "asc": asc, "other_workloads": other,
+        "train_block": head["train_block"], "train_step": head["train_step"], "asc": asc, "other_workloads": other,
     }
     print(json.dumps(out))
     return 0

@@ -87,10 +87,12 @@ __global__ __launch_bounds__(256) void scatter_interior_kernel(const float *__re
 // 16 x 64 blocks of fine pixels (every block of every tile interior of every sample, dealt out in
 // turn); per block it builds the upsampled field U on the block's 18 x 66 neighbourhood for 8 input
 // variables at a time -- bilinear, neighbours clamped to the tile's haloed box, zero outside the
-// box -- and loads 8 output variables of the upstream gradient; thread t owns the products
-// (o, i, tap) = t, t + 256, ... of that 8 x 8 x 9 set and adds the block's 1024 pixels to its
-// accumulators in LDS (one owner per accumulator: a fixed order, no atomics).  One partial row
-// of 9 C C + C sums per work-group; a fixed-order reduction follows.
+// box -- and loads 8 output variables of the upstream gradient.  A thread owns one (output, input)
+// pair and four of the block's sixteen pixel rows: it walks along each row with the 3 x 3
+// neighbourhood of U in registers (three new values per pixel) and adds the nine taps' products; the
+// four row groups of a pair are added in order into the pair's accumulators in LDS (one owner per
+// accumulator: a fixed order, no atomics).  One partial row of 9 C C + C sums per work-group; a
+// fixed-order reduction follows.
 struct ResGradArgs {
   const float *x, *dy;
   float *partial;
@@ -102,9 +104,10 @@ struct ResGradArgs {
 };
 
 __global__ __launch_bounds__(256) void residual_wgrad_kernel(ResGradArgs a) {
-  constexpr int BY = 16, BX = 64, WY = BY + 2, WX = BX + 2, WXP = 68, CI = 8, CO = 8;
-  __shared__ __align__(16) float U[CI * WY * WXP];
-  __shared__ __align__(16) float G[CO * BY * BX];
+  constexpr int BY = 16, BX = 64, WY = BY + 2, WX = BX + 2, WXP = 69, CI = 8, CO = 8;   // odd row pitch: fewer bank conflicts
+  __shared__ float U[CI * WY * WXP];
+  __shared__ float G[CO * BY * BX];
+  __shared__ float part[256 * 9], bpart[256];
   __shared__ float row_w[WY], col_w[WXP];
   __shared__ int row_a[WY], row_b[WY], row_m[WY], col_a[WXP], col_b[WXP], col_m[WXP];
   extern __shared__ float dynr[];
@@ -201,22 +204,50 @@ __global__ __launch_bounds__(256) void residual_wgrad_kernel(ResGradArgs a) {
           }
         }
         __syncthreads();
-        for (int item = t; item < nco * nci * 9; item += 256) {
-          const int tap = item % 9, ci = (item / 9) % nci, o = item / (9 * nci);
-          const int dy = tap / 3, dx = tap % 3;
-          const float *gp = G + o * BY * BX;
-          const float *up = U + (ci * WY + dy) * WXP + dx;
-          float s = 0.f;
-          for (int yy = 0; yy < BY; ++yy)
-#pragma unroll 8
-            for (int xx = 0; xx < BX; ++xx) s = fmaf(gp[yy * BX + xx], up[yy * WXP + xx], s);
-          acc[((co0 + o) * a.C + ci0 + ci) * 9 + tap] += s;
+        {
+          const int rg = t & 3, ci = (t >> 2) & 7, o = t >> 5;
+          float s9[9];
+#pragma unroll
+          for (int k = 0; k < 9; ++k) s9[k] = 0.f;
+          if (o < nco && ci < nci) {
+            for (int yy = rg * 4; yy < rg * 4 + 4; ++yy) {
+              const float *gp = G + (o * BY + yy) * BX;
+              const float *u0 = U + (ci * WY + yy) * WXP, *u1 = u0 + WXP, *u2 = u1 + WXP;
+              float a0 = u0[0], a1 = u0[1], b0 = u1[0], b1 = u1[1], c0 = u2[0], c1 = u2[1];
+#pragma unroll 4
+              for (int xx = 0; xx < BX; ++xx) {
+                const float a2 = u0[xx + 2], b2 = u1[xx + 2], c2 = u2[xx + 2], gv = gp[xx];
+                s9[0] = fmaf(gv, a0, s9[0]); s9[1] = fmaf(gv, a1, s9[1]); s9[2] = fmaf(gv, a2, s9[2]);
+                s9[3] = fmaf(gv, b0, s9[3]); s9[4] = fmaf(gv, b1, s9[4]); s9[5] = fmaf(gv, b2, s9[5]);
+                s9[6] = fmaf(gv, c0, s9[6]); s9[7] = fmaf(gv, c1, s9[7]); s9[8] = fmaf(gv, c2, s9[8]);
+                a0 = a1; a1 = a2; b0 = b1; b1 = b2; c0 = c1; c1 = c2;
+              }
+            }
+          }
+#pragma unroll
+          for (int k = 0; k < 9; ++k) part[t * 9 + k] = s9[k];
+          __syncthreads();
+          if (rg == 0 && o < nco && ci < nci) {
+            float *ap = acc + ((co0 + o) * a.C + ci0 + ci) * 9;
+#pragma unroll
+            for (int k = 0; k < 9; ++k)
+              ap[k] += (part[t * 9 + k] + part[(t + 1) * 9 + k]) + (part[(t + 2) * 9 + k] + part[(t + 3) * 9 + k]);
+          }
         }
-        if (ci0 == 0 && t < nco) {
-          const float *gp = G + t * BY * BX;
+        if (ci0 == 0) {                           // bias gradient: 32 threads per output, 32 pixels each, added in order
+          const int o = t >> 5, l = t & 31;
           float s = 0.f;
-          for (int e = 0; e < BY * BX; ++e) s += gp[e];
-          acc[9 * a.C * a.C + co0 + t] += s;
+          if (o < nco) {
+            const float *gp = G + o * BY * BX + l * 32;
+            for (int e = 0; e < 32; ++e) s += gp[e];
+          }
+          bpart[t] = s;
+          __syncthreads();
+          if (t < nco) {
+            float tot = 0.f;
+            for (int e = 0; e < 32; ++e) tot += bpart[t * 32 + e];
+            acc[9 * a.C * a.C + co0 + t] += tot;
+          }
         }
       }
     }
@@ -276,10 +307,9 @@ struct AggBwdArgs {
   int64_t BN;
 };
 
-template <typename T>
+template <typename T, int TP>
 __global__ __launch_bounds__(256) void agg_scores_bwd_kernel(AggBwdArgs e) {
-  constexpr int TP = 16;
-  extern __shared__ float smg[];
+  extern __shared__ __align__(16) float smg[];
   const int p2 = e.p * e.p, VP2 = e.V * p2, HV = e.heads * e.V;
   float *pix = smg;                        // [TP][V*p2]
   float *sc = pix + TP * VP2;              // [TP][heads][V] softmax weights
@@ -320,22 +350,51 @@ __global__ __launch_bounds__(256) void agg_scores_bwd_kernel(AggBwdArgs e) {
     const float inv = 1.0f / sum;
     for (int v = 0; v < e.V; ++v) r[v] *= inv;
   }
-  // d_a: one thread per (token, head, variable), features of the head in increasing order
+  // d_a[token, head, variable] = sum over the head's features d of d_o[token, d] * val[token, variable, d].
+  // Head by head: the head's slice of the value tables (U: V x dh x p2, c: V x dh) and of d_o
+  // (TP x dh) is staged in LDS, then one thread per (token, variable) walks the dh features in
+  // increasing order (a fixed order; the staged operands are read by many threads each).
   const T *dop = static_cast<const T *>(e.d_o);
-  for (int idx = t; idx < TP * HV; idx += 256) {
-    const int pi = idx / HV, g = (idx / e.V) % e.heads, v = idx % e.V;
-    const int64_t bn = bn0 + pi;
-    float s = 0.f;
-    if (bn < e.BN) {
-      const float *px = pix + pi * VP2 + v * p2;
-      for (int d = g * e.dh; d < (g + 1) * e.dh; ++d) {
-        const float *Ur = e.U + (static_cast<size_t>(v) * e.D + d) * p2;
-        float val = e.c[static_cast<size_t>(v) * e.D + d];
-        for (int i = 0; i < p2; ++i) val = fmaf(Ur[i], px[i], val);
-        s = fmaf(Act<T>::load(dop + bn * e.D + d), val, s);
-      }
+  float *Ug = da + TP * HV;                // [V][dh][p2]
+  float *cg = Ug + e.V * e.dh * p2;        // [V][dh]
+  float *og = cg + e.V * e.dh;             // [TP][dh]
+  for (int g = 0; g < e.heads; ++g) {
+    __syncthreads();                       // the previous head's slices are consumed (first pass: pix and sc are written)
+    for (int idx = t; idx < e.V * e.dh * p2; idx += 256) {
+      const int v = idx / (e.dh * p2), r = idx % (e.dh * p2);
+      Ug[idx] = e.U[(static_cast<size_t>(v) * e.D + g * e.dh) * p2 + r];
     }
-    da[idx] = s;
+    for (int idx = t; idx < e.V * e.dh; idx += 256) {
+      const int v = idx / e.dh, d = idx % e.dh;
+      cg[idx] = e.c[static_cast<size_t>(v) * e.D + g * e.dh + d];
+    }
+    for (int idx = t; idx < TP * e.dh; idx += 256) {
+      const int pi = idx / e.dh, d = idx % e.dh;
+      const int64_t bn = bn0 + pi;
+      og[idx] = bn < e.BN ? Act<T>::load(dop + bn * e.D + g * e.dh + d) : 0.f;
+    }
+    __syncthreads();
+    for (int idx = t; idx < TP * e.V; idx += 256) {
+      const int pi = idx / e.V, v = idx % e.V;
+      const float *px = pix + pi * VP2 + v * p2;
+      const float *Ur = Ug + v * e.dh * p2, *cr = cg + v * e.dh, *orow = og + pi * e.dh;
+      float s = 0.f;
+      if (p2 == 4) {
+        const float4 p4 = *reinterpret_cast<const float4 *>(px);
+        for (int d = 0; d < e.dh; ++d) {
+          const float4 u = *reinterpret_cast<const float4 *>(Ur + d * 4);
+          const float val = fmaf(u.x, p4.x, fmaf(u.y, p4.y, fmaf(u.z, p4.z, fmaf(u.w, p4.w, cr[d]))));
+          s = fmaf(orow[d], val, s);
+        }
+      } else {
+        for (int d = 0; d < e.dh; ++d) {
+          float val = cr[d];
+          for (int i = 0; i < p2; ++i) val = fmaf(Ur[d * p2 + i], px[i], val);
+          s = fmaf(orow[d], val, s);
+        }
+      }
+      da[(pi * e.heads + g) * e.V + v] = s;
+    }
   }
   __syncthreads();
   for (int idx = t; idx < TP * e.heads; idx += 256) {
@@ -688,12 +747,20 @@ static int embed_bwd_impl(reslim_ctx *c, const char *fn, const float *x, const f
   e.x = x; e.A = c->d_agg_A; e.a0 = c->d_agg_a0; e.U = c->d_agg_U; e.c = c->d_agg_c; e.d_o = w.d_o; e.a_out = w.a; e.ds_out = w.ds;
   e.V = V; e.H = c->cfg.H; e.W = c->cfg.W; e.p = p; e.Wp = c->Wp; e.N = c->N; e.D = D; e.heads = heads; e.dh = dh; e.BN = Mi;
   {
-    const size_t lds = static_cast<size_t>(16) * (static_cast<size_t>(V) * p2 + 2 * static_cast<size_t>(heads) * V) * sizeof(float);
-    if (lds > 60 * 1024) return set_error(c, RESLIM_ESHAPE, std::string(fn) + ": too many variables x heads for the aggregation gradient");
-    const dim3 grid(static_cast<unsigned>((Mi + 15) / 16));
+    auto lds_for = [&](int tp) {
+      return (static_cast<size_t>(tp) * (static_cast<size_t>(V) * p2 + 2 * static_cast<size_t>(heads) * V) +
+              static_cast<size_t>(V) * dh * (p2 + 1) + static_cast<size_t>(tp) * dh) * sizeof(float);
+    };
+    const int tp = lds_for(16) <= 64 * 1024 ? 16 : 4;      // tokens per work-group: fewer where variables x heads is large
+    const size_t lds = lds_for(tp);
+    if (lds > 150 * 1024) return set_error(c, RESLIM_ESHAPE, std::string(fn) + ": too many variables x heads for the aggregation gradient");
+    const dim3 grid(static_cast<unsigned>((Mi + tp - 1) / tp));
     const double fl = 2.0 * dMi * V * dD * (p2 + 1);
-    if (dt == RESLIM_BF16) RESLIM_LAUNCH("agg_scores_bwd", fl, dMi * dD * es + 8.0 * dMi * heads * V, (agg_scores_bwd_kernel<bf16_t><<<grid, dim3(256), lds, st>>>(e), hipGetLastError()));
-    else RESLIM_LAUNCH("agg_scores_bwd", fl, dMi * dD * es + 8.0 * dMi * heads * V, (agg_scores_bwd_kernel<float><<<grid, dim3(256), lds, st>>>(e), hipGetLastError()));
+    const double by = dMi * dD * es + 8.0 * dMi * heads * V;
+    if (dt == RESLIM_BF16 && tp == 16) RESLIM_LAUNCH("agg_scores_bwd", fl, by, (agg_scores_bwd_kernel<bf16_t, 16><<<grid, dim3(256), lds, st>>>(e), hipGetLastError()));
+    else if (dt == RESLIM_BF16) RESLIM_LAUNCH("agg_scores_bwd", fl, by, (agg_scores_bwd_kernel<bf16_t, 4><<<grid, dim3(256), lds, st>>>(e), hipGetLastError()));
+    else if (tp == 16) RESLIM_LAUNCH("agg_scores_bwd", fl, by, (agg_scores_bwd_kernel<float, 16><<<grid, dim3(256), lds, st>>>(e), hipGetLastError()));
+    else RESLIM_LAUNCH("agg_scores_bwd", fl, by, (agg_scores_bwd_kernel<float, 4><<<grid, dim3(256), lds, st>>>(e), hipGetLastError()));
   }
   {
     if (p2 != 4 && p2 != 1 && p2 != 16) return set_error(c, RESLIM_ESHAPE, std::string(fn) + ": the aggregation gradient is built for patch sizes 1, 2 and 4");
@@ -779,11 +846,24 @@ extern "C" int reslim_bayes_loss_bwd(const float *pred, const float *target, con
   return hipGetLastError() == hipSuccess ? RESLIM_OK : RESLIM_EHIP;
 }
 
+static hipError_t train_model_init() {
+  hipError_t e = hipSuccess;
+  const int lim = 150 * 1024;
+#define RESLIM_ATTR(K) if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(&K), hipFuncAttributeMaxDynamicSharedMemorySize, lim)
+  RESLIM_ATTR((agg_scores_bwd_kernel<bf16_t, 16>));
+  RESLIM_ATTR((agg_scores_bwd_kernel<bf16_t, 4>));
+  RESLIM_ATTR((agg_scores_bwd_kernel<float, 16>));
+  RESLIM_ATTR((agg_scores_bwd_kernel<float, 4>));
+#undef RESLIM_ATTR
+  return e;
+}
+
 extern "C" int reslim_train_prepare_model(reslim_ctx *c, const reslim_weights *wts) {
   const char *fn = "reslim_train_prepare_model";
   if (!c) return RESLIM_EINVAL;
   if (!wts) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": null weights");
   if (c->train.ready) return RESLIM_OK;
+  RESLIM_TRY("kernel setup", train_model_init());
   const int D = c->cfg.embed_dim, V = c->cfg.in_vars, p2 = c->cfg.patch * c->cfg.patch, dt = c->cfg.dtype;
   if (dt == RESLIM_BF16 && c->head_out % 64 != 0)
     return set_error(c, RESLIM_ESHAPE, std::string(fn) + ": out_vars * (patch * scale)^2 must be a multiple of 64 on the bfloat16 path (contraction length of the head's input gradient)");

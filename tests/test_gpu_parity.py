@@ -210,10 +210,11 @@ def test_forward_c1_bf16_full_size():
     assert_parity(y - inter["residual"], inter["y_main"], 2e-2, "c1 main path", say)
 
 
-def _sampled_tile_parity(cfg, tile_ids, batch_item=0):
+def _sampled_tile_parity(cfg, tile_ids, batch_item=0, w=None):
     """Full-size forward on the GPU; the oracle recomputes single tiles through the
     whole stack (exact: tiles never interact, Sec. 4.2) and their interiors are compared."""
-    w, x = WL.make_weights(cfg), WL.make_fields(cfg)
+    w = WL.make_weights(cfg) if w is None else w
+    x = WL.make_fields(cfg)
     tiles, _, _, _ = O.tiles_partition(cfg.Hp, cfg.Wp, cfg.tiles_y, cfg.tiles_x, cfg.halo)
     with B.Reslim(cfg, w) as m:
         y = m.forward(cuda(x))
@@ -257,6 +258,25 @@ def test_forward_10b_width_one_block_sampled_tile():
     """The 10B model's width (embed dim 8192, 32 heads of dimension 256) with ONE of its 11
     blocks, so the oracle stays within a minute; the blocks are copies of the same kernels."""
     _sampled_tile_parity(WL.CONFIGS["m10b"].with_(name="m10b_L1", depth=1), [9])
+
+
+def test_forward_10b_model_at_its_real_depth_sampled_tile():
+    """The 10B model of Sec. 5 at all 11 blocks (17.7 GB of bf16 weights on the device) on one tile
+    through the whole stack.  Drawing 35 GB of truncated normals takes many minutes on the host, so
+    one block is drawn with the seeded generator and the other ten are that block's tensors rolled
+    along their output axis by a different amount each (every block distinct, every value already a
+    bf16 number): layer offsets beyond 2^31 elements and the error growth over the real depth are
+    what this checks."""
+    one = WL.CONFIGS["m10b"].with_(name="m10b_L1", depth=1)
+    cfg = WL.CONFIGS["m10b"]
+    say("m10b: weights of one block ...")
+    w = dict(WL.make_weights(one))
+    for name in O.BLOCK_PARAMS:
+        base = w[name][0]
+        w[name] = np.stack([np.roll(base, 37 * l + 5 * l * l, axis=0) for l in range(cfg.depth)])
+    assert not np.array_equal(w["w_fc1"][3], w["w_fc1"][7])
+    say("m10b: forward with 11 blocks, then the oracle on tile 6 ...")
+    _sampled_tile_parity(cfg, [6], w=w)
 
 
 # ------------------------------------------------------------------ Bayesian loss (Sec. 4.1)
