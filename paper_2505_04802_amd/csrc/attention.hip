@@ -65,6 +65,7 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
   constexpr int STAGE = 2 * TILE_B;       // K block then V block
   constexpr int LPW = TILE_B / 1024 / 4;  // direct loads per wave and operand
   constexpr int NKT = BKV / 32, NKS = DH / 16, NDT = DH / 32;
+  constexpr bool PIPE = DH == 64 && NKT == 2;   // second key group's softmax woven into the first group's P V
   static_assert(TILE_B % 4096 == 0 && 2 * STAGE <= 65536, "LDS plan");
   __shared__ __align__(1024) unsigned char smem[2 * STAGE];
 
@@ -282,14 +283,73 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
         for (int r = 0; r < 16; ++r) { lsum[r] *= alpha; minit[r] = ninit; }
         have_ref = true;
       }
+      if constexpr (!PIPE) {
 #pragma unroll
-      for (int kt = 0; kt < NKT; ++kt)
+        for (int kt = 0; kt < NKT; ++kt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-          s[kt][r] = __builtin_amdgcn_exp2f(QS ? s[kt][r] : s[kt][r] * c);
+          for (int r = 0; r < 16; ++r)
+            s[kt][r] = __builtin_amdgcn_exp2f(QS ? s[kt][r] : s[kt][r] * c);
+      }
 
       __builtin_amdgcn_s_setprio(1);
-      if constexpr (DH == 64) {
+      if constexpr (PIPE) {
+        // The exponentials and conversions of the second 32-key group are placed between the
+        // matrix instructions of the first group's P V product: a wave issues in order, so its own
+        // vector work only overlaps its matrix work when the two are interleaved in the stream.
+        const unsigned st_off = static_cast<unsigned>(reinterpret_cast<uintptr_t>(
+            (__attribute__((address_space(3))) const unsigned char *)st));
+        unsigned va[2][2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+#pragma unroll
+          for (int d = 0; d < 2; ++d) va[e][d] = st_off + static_cast<unsigned>(v_addr[e][d]);
+        typedef __attribute__((ext_vector_type(2))) uint64_t u64x2;
+        // the first group's V reads are issued ahead of its exponentials, which cover their latency
+        VFrag64 vf0, vf1;
+        v_frag_issue<0>(vf0, va);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[0][r] = __builtin_amdgcn_exp2f(QS ? s[0][r] : s[0][r] * c);
+        bf16x8 pf0[2], pf1[2];
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) pf0[h2][e] = static_cast<__bf16>(s[0][8 * h2 + e]);
+        v_frag_wait(vf0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2) {
+          lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf0[h2], lsum, 0, 0, 0);
+#pragma unroll
+          for (int d = 0; d < 2; ++d) {
+            const u64x2 both = {vf0.r[h2][d][0], vf0.r[h2][d][1]};
+            o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf0[h2], o[d], 0, 0, 0);
+          }
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[1][r] = __builtin_amdgcn_exp2f(QS ? s[1][r] : s[1][r] * c);
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) pf1[h2][e] = static_cast<__bf16>(s[1][8 * h2 + e]);
+        // one matrix instruction, then four vector instructions, six times (16 exponentials + 8 conversions)
+#pragma unroll
+        for (int i = 0; i < 6; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        v_frag_issue<32 * ROWB>(vf1, va);
+        v_frag_wait(vf1);
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2) {
+          lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf1[h2], lsum, 0, 0, 0);
+#pragma unroll
+          for (int d = 0; d < 2; ++d) {
+            const u64x2 both = {vf1.r[h2][d][0], vf1.r[h2][d][1]};
+            o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf1[h2], o[d], 0, 0, 0);
+          }
+        }
+      } else if constexpr (DH == 64) {
         // LDS byte addresses of this lane's four fragment pointers in the current stage
         const unsigned st_off = static_cast<unsigned>(reinterpret_cast<uintptr_t>(
             (__attribute__((address_space(3))) const unsigned char *)st));
