@@ -42,8 +42,9 @@ namespace reslim {
 //    meets a logit more than TAU above it -- rare after the first block -- so the
 //    common block costs one max3 per three scores, one exp2 and half a convert
 //    per score;
-//  * the row sums L ride on the matrix pipe: a constant all-ones A operand turns
-//    O^T = V^T P^T into one more 32-row block whose rows all equal sum_k P.
+//  * the row sums L come from the bf16 probabilities the P V product uses, two per
+//    v_dot2c_f32_bf16 into one register per lane (a block of ones through the matrix
+//    pipe gives the same sums for a fifth of the matrix instructions at dh = 64).
 // QS: the caller has already multiplied q by log2(e)/sqrt(dh) (the fused QKV
 // epilogue does, before its single rounding to bf16), so the MFMA output is the
 // base-2 logit itself.
@@ -168,10 +169,22 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
     }
   }
 
-  f32x16 o[NDT], lsum, minit;
-  bf16x8 ones;
+  f32x16 o[NDT], minit;
+  // Sum of this lane's probabilities (its query, its half of the keys), taken from the same bf16
+  // values the P V product uses, two per instruction (v_dot2c_f32_bf16 against a pair of ones).
+  // A block of ones through the matrix unit gives the same sums but costs a fifth of the matrix
+  // instructions at head dimension 64 and sixteen registers; the two key halves meet at the end.
+  float lsum;
+  auto rowsum = [](const bf16x8 &p, float acc) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const bf16x2 one2 = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
 #pragma unroll
-  for (int e = 0; e < 8; ++e) ones[e] = static_cast<__bf16>(1.0f);
+    for (int i = 0; i < 4; ++i) {
+      const bf16x2 pr = {p[2 * i], p[2 * i + 1]};
+      acc = __builtin_amdgcn_fdot2_f32_bf16(pr, one2, acc, false);
+    }
+    return acc;
+  };
   const float c = QS ? 1.0f : a.scale_log2;     // MFMA output -> base-2 logit
   const float TAU = 10.0f / c;                    // in units of the MFMA output
   bool have_ref = false;
@@ -181,7 +194,8 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { lsum[r] = 0.f; minit[r] = 0.f; }
+    for (int r = 0; r < 16; ++r) minit[r] = 0.f;
+    lsum = 0.f;
     have_ref = false;
   };
   reset();
@@ -260,11 +274,10 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
         // Exchange between the two lane halves with v_permlane32_swap, not through LDS:
         // an LDS lane permute makes the wave wait on the LDS counter, and that wait
         // also covers the direct-to-LDS loads of the next block just issued (measured:
-        // the prefetch stops being asynchronous).  The swap returns (own, partner) in
-        // the lower half and (partner, own) in the upper half.
-        const unsigned u = __builtin_bit_cast(unsigned, mx);
-        const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-        mx = fmaxf(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1]));   // finite: every block holds a valid key
+        // the prefetch stops being asynchronous).
+        unsigned m_lo, m_up;
+        lane_pair_exchange(__builtin_bit_cast(unsigned, mx), m_lo, m_up);
+        mx = fmaxf(__builtin_bit_cast(float, m_lo), __builtin_bit_cast(float, m_up));   // finite: every block holds a valid key
       }
       if (!have_ref || __any(mx > TAU)) {
         // move this lane's reference up by d (first block: to the block maximum)
@@ -280,7 +293,8 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
           for (int r = 0; r < 16; ++r) o[dd][r] *= alpha;
         const float ninit = minit[0] - d;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { lsum[r] *= alpha; minit[r] = ninit; }
+        for (int r = 0; r < 16; ++r) minit[r] = ninit;
+        lsum *= alpha;
         have_ref = true;
       }
       if constexpr (!PIPE) {
@@ -315,10 +329,11 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
 #pragma unroll
           for (int e = 0; e < 8; ++e) pf0[h2][e] = static_cast<__bf16>(s[0][8 * h2 + e]);
         v_frag_wait(vf0);
+        v_frag_issue<32 * ROWB>(vf1, va);     // in flight under the whole first group
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int h2 = 0; h2 < 2; ++h2) {
-          lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf0[h2], lsum, 0, 0, 0);
+          lsum = rowsum(pf0[h2], lsum);
 #pragma unroll
           for (int d = 0; d < 2; ++d) {
             const u64x2 both = {vf0.r[h2][d][0], vf0.r[h2][d][1]};
@@ -331,18 +346,17 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
         for (int h2 = 0; h2 < 2; ++h2)
 #pragma unroll
           for (int e = 0; e < 8; ++e) pf1[h2][e] = static_cast<__bf16>(s[1][8 * h2 + e]);
-        // one matrix instruction, then four vector instructions, six times (16 exponentials + 8 conversions)
+        // one matrix instruction, then six vector instructions, four times (16 exponentials + 8 conversions)
 #pragma unroll
-        for (int i = 0; i < 6; ++i) {
+        for (int i = 0; i < 4; ++i) {
           __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
-        v_frag_issue<32 * ROWB>(vf1, va);
         v_frag_wait(vf1);
 #pragma unroll
         for (int h2 = 0; h2 < 2; ++h2) {
-          lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf1[h2], lsum, 0, 0, 0);
+          lsum = rowsum(pf1[h2], lsum);
 #pragma unroll
           for (int d = 0; d < 2; ++d) {
             const u64x2 both = {vf1.r[h2][d][0], vf1.r[h2][d][1]};
@@ -370,7 +384,7 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
           v_frag_wait(vf);
 #pragma unroll
           for (int h2 = 0; h2 < 2; ++h2) {
-            lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf[h2], lsum, 0, 0, 0);
+            lsum = rowsum(pf[h2], lsum);
 #pragma unroll
             for (int d = 0; d < 2; ++d) {
               typedef __attribute__((ext_vector_type(2))) uint64_t u64x2;
@@ -393,7 +407,7 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
             bf16x8 pf;
 #pragma unroll
             for (int e = 0; e < 8; ++e) pf[e] = static_cast<__bf16>(s[kt][8 * h2 + e]);
-            lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf, lsum, 0, 0, 0);
+            lsum = rowsum(pf, lsum);
 #pragma unroll
             for (int d = 0; d < NDT; ++d) {
               const unsigned char *vp = st + (kt * 32 + h2 * 16) * ROWB;
@@ -429,7 +443,7 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
           if (d == 0) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) pf[e] = static_cast<__bf16>(s[kt][8 * h2 + e]);
-            lsum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf, lsum, 0, 0, 0);
+            lsum = rowsum(pf, lsum);
           }
           const s16x8 both = __builtin_shufflevector(vlo[i % (PF + 1)], vhi[i % (PF + 1)], 0, 1, 2, 3, 4, 5, 6, 7);
           o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf, o[d], 0, 0, 0);
@@ -443,9 +457,13 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
     // ---- end of a unit: normalise and store this lane's query row, then move on
     const int qrow = cur.q0 + wave * 32 + l32;
     if (active && qrow < cur.n_t) {
-      const float inv = 1.0f / lsum[0];     // every row of the all-ones block carries the full sum over keys
+      // lanes l and l + 32 hold the two key halves of query l: full sum = own + partner
+      unsigned l_lo, l_up;
+      lane_pair_exchange(__builtin_bit_cast(unsigned, lsum), l_lo, l_up);
+      const float ltot = __builtin_bit_cast(float, l_lo) + __builtin_bit_cast(float, l_up);
+      const float inv = 1.0f / ltot;
       // log-sum-exp of the logits (kept for the gradient): reference + log of the sum
-      if (cur.lse && hi == 0) cur.lse[qrow] = (__builtin_amdgcn_logf(lsum[0]) - minit[0] * c) * 0.69314718055994531f;
+      if (cur.lse && hi == 0) cur.lse[qrow] = (__builtin_amdgcn_logf(ltot) - minit[0] * c) * 0.69314718055994531f;
       bf16_t *op = cur.out + static_cast<size_t>(qrow) * a.D + hi * 4;
 #pragma unroll
       for (int d = 0; d < NDT; ++d)

@@ -76,4 +76,17 @@ __device__ __forceinline__ void v_frag_wait(VFrag64 &f) {
                  "+v"(f.r[1][0][0]), "+v"(f.r[1][0][1]), "+v"(f.r[1][1][0]), "+v"(f.r[1][1][1]));
 }
 
+// Exchange between lanes l and l + 32: both get (value of lane l, value of lane l + 32).
+// v_permlane32_swap swaps the upper half of its first register with the lower half of its
+// second; given two copies of v that leaves the lower lanes' values in both halves of the first
+// and the upper lanes' values in both halves of the second.  Inline assembly, because the
+// compiler builtin for this instruction hands back its first result for both (checked on the
+// device: the sum of the two results came out as twice the first); the waits before and after
+// are the ones the compiler places around the instruction itself.
+__device__ __forceinline__ void lane_pair_exchange(unsigned v, unsigned &from_lower, unsigned &from_upper) {
+  from_lower = v;
+  from_upper = v;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(from_lower), "+v"(from_upper));
+}
+
 }  // namespace reslim

@@ -155,6 +155,34 @@ def test_attention_launch_shapes_dh64(kernel_hooks, variant, peaked):
     assert np.abs(out - ref).max() <= 3e-2
 
 
+@pytest.mark.parametrize("cfg", [SMALL_BF16, SMALL_BF16_DH128, SMALL_BF16_DH256], ids=lambda c: c.name)
+@pytest.mark.parametrize("octet", [0, 1], ids=["first_octets", "second_octets"])
+def test_attention_large_logits_in_one_key_octet(cfg, octet):
+    """The running reference logit of a query must see all of its keys.  Here the keys whose
+    position in the tile falls in one half of each group of 16 (positions 16 j + 8 octet .. + 7)
+    carry logits 184 binary orders of magnitude above the others: a reference taken from the
+    other keys alone makes exp2(logit - reference) overflow to infinity, so any finite output
+    that matches the oracle shows that the maximum covers both halves.  (The bf16 kernel keeps
+    the two halves of a group in lanes l and l + 32 and exchanges their maxima.)  The inputs are
+    rounded to bf16 before either side sees them."""
+    tiles, _, _, n_h = O.tiles_partition(cfg.Hp, cfg.Wp, cfg.tiles_y, cfg.tiles_x, cfg.halo)
+    D, dh = cfg.embed_dim, cfg.embed_dim // cfg.heads
+    qkv = (0.25 * WL.make_qkv(cfg.batch * n_h, D, seed=21)).reshape(cfg.batch, n_h, 3 * D).astype(np.float32)
+    for t in tiles:
+        pos = np.arange(t["n_tok"])
+        big = np.where((pos % 16) // 8 == octet, 16.0, -16.0).astype(np.float32)
+        r = slice(t["tok_off"], t["tok_off"] + t["n_tok"])
+        for g in range(cfg.heads):
+            qkv[:, r, g * dh] = 8.0 * np.sqrt(dh)          # q . k / sqrt(dh) = 8 * (+-16) = +-128
+            qkv[:, r, D + g * dh] = big[None, :]
+    qkv = WL.round_to_bf16(qkv)
+    ref = O.tiles_attention(qkv, tiles, cfg.heads)
+    with B.Reslim(cfg, weights_for(cfg)) as m:
+        out = m.attention(cuda(qkv, m.act_dtype)).float().cpu().numpy()
+    assert np.isfinite(out).all(), "overflow: the reference logit missed the large keys"
+    assert_parity(out, ref, TOL[1], f"attention {cfg.name}, large logits in octet {octet}", say)
+
+
 # ------------------------------------------------------------------ embed / block / head
 @pytest.mark.parametrize("cfg", [SMALL_F32, SMALL_BF16, SMALL_BF16_DH128, SMALL_BF16_DH256], ids=lambda c: c.name)
 def test_stage_by_stage_parity(cfg):
