@@ -83,16 +83,26 @@ __global__ __launch_bounds__(256) void scatter_interior_kernel(const float *__re
   for (int d = lane; d < D / 4; d += 64) out[d] = own ? in[d] : make_float4(0.f, 0.f, 0.f, 0.f);
 }
 
-// Gradient of the residual path's 3x3 convolution (weights and bias).  A work-group walks over
-// 16 x 64 blocks of fine pixels (every block of every tile interior of every sample, dealt out in
-// turn); per block it builds the upsampled field U on the block's 18 x 66 neighbourhood for 8 input
-// variables at a time -- bilinear, neighbours clamped to the tile's haloed box, zero outside the
-// box -- and loads 8 output variables of the upstream gradient.  A thread owns one (output, input)
-// pair and four of the block's sixteen pixel rows: it walks along each row with the 3 x 3
-// neighbourhood of U in registers (three new values per pixel) and adds the nine taps' products; the
-// four row groups of a pair are added in order into the pair's accumulators in LDS (one owner per
-// accumulator: a fixed order, no atomics).  One partial row of 9 C C + C sums per work-group; a
-// fixed-order reduction follows.
+// Gradient of the residual path's 3x3 convolution (weights and bias).  The forward evaluates
+// R = b + sum over taps (dy, dx) and inputs i of w[o][i][dy][dx] U_i(r + dy, c + dx), U_i the bilinear
+// upsampling of input i on the tile's haloed box (neighbours clamped to the box, zero outside it).
+// U is linear in the coarse pixels, so with G_o the upstream gradient on a block of fine pixels
+//   dw[o][i][dy][dx] = sum_{r,c} G_o(r, c) U_i(r + dy, c + dx) = sum_{Y,X} x_i(Y, X) Q[o][dy][dx](Y, X),
+//   Q[o][dy][dx](Y, X) = sum_{r,c} G_o(r, c) RW[dy](Y, r) CW[dx](X, c),
+// where RW[dy](Y, r) is the weight with which coarse row Y enters fine row r + dy (two non-zeros per
+// fine row, zero for rows outside the box) and CW the same for columns: the upsampling transposed,
+// rows first (P = RW G), then columns (Q = P CW^T), then one small product with the coarse window.
+// That is 9 (C + about 2) multiply-adds per coarse-window pixel and output plus about 12 per fine pixel
+// and output, instead of 9 C per fine pixel and output for the product with U written out, in fp32
+// throughout.
+//
+// A work-group walks over 16 x 64 blocks of fine pixels (every block of every tile interior of every
+// sample, dealt out in turn), CO = 4 OPT outputs per pass.  Row step: a thread owns one fine column
+// and OPT outputs; for each coarse row it runs over the fine rows that touch it.  Column step: one
+// thread per value of Q, over the fine columns that touch its coarse column.  Last step: one thread
+// per (output, input) pair, nine sums over the window, added to the pair's accumulators in LDS (one
+// owner per accumulator: a fixed order, no atomics).  One partial row of 9 C C + C sums per
+// work-group; a fixed-order reduction follows.
 struct ResGradArgs {
   const float *x, *dy;
   float *partial;
@@ -103,20 +113,39 @@ struct ResGradArgs {
   int cwh, cww;
 };
 
+constexpr size_t kResGradLds = 150 * 1024;        // dynamic LDS the kernel may ask for
+// floats of dynamic LDS for CO outputs per pass
+static size_t residual_wgrad_lds_floats(int C, int CO, int cwh, int cww) {
+  const size_t npx = static_cast<size_t>(cwh) * cww;
+  const size_t gq = std::max<size_t>(static_cast<size_t>(CO) * 16 * 64, (static_cast<size_t>(CO) * 9 * npx + 3) / 4 * 4);
+  return gq + static_cast<size_t>(CO) * 3 * cwh * 64 + 3 * cwh * 16 + 3 * cww * 64 + C * npx + 9 * C * C + C + 6 * cww + 4;
+}
+
+// OPT: outputs per thread in the row step (CO = 4 OPT per pass).  NIT: the column step covers 4 NIT
+// fine columns from the first one that touches a coarse column (a coarse column is touched by fewer
+// than 2 s + 1 fine columns); a block where some run is longer takes all 64 columns instead.
+template <int OPT, int NIT>
 __global__ __launch_bounds__(256) void residual_wgrad_kernel(ResGradArgs a) {
-  constexpr int BY = 16, BX = 64, WY = BY + 2, WX = BX + 2, WXP = 69, CI = 8, CO = 8;   // odd row pitch: fewer bank conflicts
-  __shared__ float U[CI * WY * WXP];
-  __shared__ float G[CO * BY * BX];
-  __shared__ float part[256 * 9], bpart[256];
+  constexpr int BY = 16, BX = 64, WY = BY + 2, WX = BX + 2, WXP = 68, CO = 4 * OPT;
   __shared__ float row_w[WY], col_w[WXP];
   __shared__ int row_a[WY], row_b[WY], row_m[WY], col_a[WXP], col_b[WXP], col_m[WXP];
-  extern __shared__ float dynr[];
-  float *Cw = dynr;                               // [CI][cwh][cww] coarse window
-  float *acc = Cw + CI * a.cwh * a.cww;           // [9 C C + C] accumulators of this work-group
-  const int t = threadIdx.x;
+  __shared__ int var_idx[64];
+  __shared__ int long_run;
+  extern __shared__ __align__(16) float dynr[];
+  const int cwh = a.cwh, cww = a.cww, npx = cwh * cww, qw = 3 * cww;
+  const int gq = max(CO * BY * BX, (CO * 9 * npx + 3) / 4 * 4);   // a multiple of four: P and CW are read 16 bytes at a time
+  float *G = dynr;                                // [CO][BY][BX] upstream gradient of the block ...
+  float *Q = dynr;                                // ... later [CO][3][cwh][3][cww] (G is no longer needed by then)
+  float *P = dynr + gq;                           // [CO][3][cwh][BX]
+  float *RW = P + CO * 3 * cwh * BX;              // [3][cwh][BY]
+  float *CW = RW + 3 * cwh * BY;                  // [3][cww][BX]
+  float *Cw = CW + 3 * cww * BX;                  // [C][npx] coarse window of the inputs
+  float *acc = Cw + a.C * npx;                    // [9 C C + C] accumulators of this work-group
+  int *xlo = reinterpret_cast<int *>(acc + 9 * a.C * a.C + a.C), *xhi = xlo + qw;     // [3][cww] fine columns that touch coarse column X under tap dx
+  const int t = threadIdx.x, lane = t & 63, og = t >> 6;
   const int n_acc = 9 * a.C * a.C + a.C;
   for (int i = t; i < n_acc; i += 256) acc[i] = 0.f;
-  const int cwh = a.cwh, cww = a.cww;
+  if (t < a.C) var_idx[t] = a.out_var_idx[t];
   const float inv_s = 1.0f / static_cast<float>(a.s);
   const int sH = a.s * a.H, sW = a.s * a.W;
   const int64_t blocks = static_cast<int64_t>(a.nbx) * a.nby * a.T * a.batch;
@@ -147,7 +176,7 @@ __global__ __launch_bounds__(256) void residual_wgrad_kernel(ResGradArgs a) {
       src(fy0 - 1, box_ch, oy, ib_, w_);
       src(fx0 - 1, box_cw, ox, ib_, w_);
     }
-    __syncthreads();                              // the previous block's tables and tiles are no longer read
+    __syncthreads();                              // the previous block's tables and arrays are no longer read
     if (t < WY) {
       const int fy = fy0 + t - 1;
       int ia, ib;
@@ -167,88 +196,164 @@ __global__ __launch_bounds__(256) void residual_wgrad_kernel(ResGradArgs a) {
       col_w[wx] = w1;
       col_m[wx] = (fx >= 0 && fx < box_fw) ? 1 : 0;
     }
+    if (t == 255) long_run = 0;
+    if (t < qw) { xlo[t] = BX; xhi[t] = -1; }     // qw <= 3 * 68 < 256
+    // coarse window of every input
+    for (int idx = t; idx < a.C * npx; idx += 256) {
+      const int ci = idx / npx, r = idx % npx;
+      const int wy = r / cww, wx = r % cww;
+      const float *xp = a.x + (static_cast<size_t>(b) * a.V + var_idx[ci]) * a.H * a.W;
+      const int y = min(oy + wy, box_ch - 1), x = min(ox + wx, box_cw - 1);
+      Cw[idx] = xp[static_cast<size_t>(cy_org + y) * a.W + cx_org + x];
+    }
+    __syncthreads();
+    // transposed interpolation weights: RW[dy][Y][r] and CW[dx][X][c], window row r + dy / column c + dx
+    for (int idx = t; idx < 3 * cwh * BY; idx += 256) {
+      const int r = idx % BY, Y = (idx / BY) % cwh, dy = idx / (BY * cwh), wr = r + dy;
+      const float w1 = row_w[wr];
+      RW[idx] = row_m[wr] ? (row_a[wr] == Y ? 1.0f - w1 : 0.f) + (row_b[wr] == Y ? w1 : 0.f) : 0.f;
+    }
+    for (int idx = t; idx < 3 * cww * BX; idx += 256) {
+      const int cc = idx % BX, e = idx / BX, X = e % cww, dx = e / cww, wc = cc + dx;
+      const float w1 = col_w[wc];
+      const float v = col_m[wc] ? (col_a[wc] == X ? 1.0f - w1 : 0.f) + (col_b[wc] == X ? w1 : 0.f) : 0.f;
+      CW[idx] = v;
+      if (v != 0.f) {
+        atomicMin(&xlo[e], cc);
+        atomicMax(&xhi[e], cc);
+      }
+    }
+    __syncthreads();
+    if (t < qw) {
+      const int lo = min(xlo[t] & ~3, BX - 4 * NIT);            // 16-byte aligned start of the window of 4 NIT columns
+      if (xhi[t] >= lo + 4 * NIT) long_run = 1;
+      xlo[t] = lo;
+    }
     for (int co0 = 0; co0 < a.C; co0 += CO) {
       const int nco = min(CO, a.C - co0);
-      __syncthreads();                            // G of the previous pass consumed (and the tables written)
-      // upstream gradient of the block, zero past the interior's edge
-      for (int e = t; e < nco * BY * BX; e += 256) {
-        const int o = e / (BY * BX), yy = (e / BX) % BY, xx = e % BX;
+      __syncthreads();                            // Q of the previous pass consumed (and the run tables written)
+      // upstream gradient of the block, zero past the interior's edge and for outputs past the last
+      for (int e = t; e < CO * BY * BX / 4; e += 256) {
+        const int o = e / (BY * BX / 4), yy = (e / (BX / 4)) % BY, xx = 4 * (e % (BX / 4));
         const int iy = iy0 + yy, ix = ix0 + xx;
-        float v = 0.f;
-        if (iy < ih && ix < iw)
-          v = a.dy[((static_cast<size_t>(b) * a.C + co0 + o) * sH + td.y0 * a.ps + iy) * sW + td.x0 * a.ps + ix];
-        G[e] = v;
-      }
-      // bias gradient: thread o adds the block's pixels of output o (after the barrier below)
-      for (int ci0 = 0; ci0 < a.C; ci0 += CI) {
-        const int nci = min(CI, a.C - ci0);
-        __syncthreads();                          // U / Cw of the previous pass consumed, G written
-        for (int idx = t; idx < nci * cwh * cww; idx += 256) {
-          const int ci = idx / (cwh * cww), r = idx % (cwh * cww);
-          const int wy = r / cww, wx = r % cww;
-          const float *xp = a.x + (static_cast<size_t>(b) * a.V + a.out_var_idx[ci0 + ci]) * a.H * a.W;
-          const int y = min(oy + wy, box_ch - 1), x = min(ox + wx, box_cw - 1);
-          Cw[idx] = xp[static_cast<size_t>(cy_org + y) * a.W + cx_org + x];
-        }
-        __syncthreads();
-        for (int e = t; e < WY * WX; e += 256) {
-          const int wy = e / WX, wx = e % WX;
-          const int ya = row_a[wy] * cww, yb = row_b[wy] * cww, xa = col_a[wx], xb = col_b[wx];
-          const float wy1 = row_w[wy], wx1 = col_w[wx];
-          const bool m = row_m[wy] && col_m[wx];
-          for (int ci = 0; ci < nci; ++ci) {
-            const float *cwp = Cw + ci * cwh * cww;
-            const float top = cwp[ya + xa] * (1.0f - wx1) + cwp[ya + xb] * wx1;
-            const float bot = cwp[yb + xa] * (1.0f - wx1) + cwp[yb + xb] * wx1;
-            U[(ci * WY + wy) * WXP + wx] = m ? top * (1.0f - wy1) + bot * wy1 : 0.f;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (o < nco && iy < ih) {
+          const float *gp = a.dy + ((static_cast<size_t>(b) * a.C + co0 + o) * sH + td.y0 * a.ps + iy) * sW + td.x0 * a.ps + ix;
+          if (ix + 3 < iw && (reinterpret_cast<uintptr_t>(gp) & 15) == 0) {
+            v = *reinterpret_cast<const float4 *>(gp);
+          } else {
+            if (ix < iw) v.x = gp[0];
+            if (ix + 1 < iw) v.y = gp[1];
+            if (ix + 2 < iw) v.z = gp[2];
+            if (ix + 3 < iw) v.w = gp[3];
           }
         }
-        __syncthreads();
-        {
-          const int rg = t & 3, ci = (t >> 2) & 7, o = t >> 5;
-          float s9[9];
+        *reinterpret_cast<float4 *>(G + (o * BY + yy) * BX + xx) = v;
+      }
+      __syncthreads();
+      // rows: P[o][dy][Y][c] = sum_r RW[dy][Y][r] G[o][r][c]; the bias gradient is the plain sum of G.
+      // A thread keeps its column of G for its OPT outputs in registers over all coarse rows.
+      {
+        float gcol[OPT][BY], bs[OPT];
 #pragma unroll
-          for (int k = 0; k < 9; ++k) s9[k] = 0.f;
-          if (o < nco && ci < nci) {
-            for (int yy = rg * 4; yy < rg * 4 + 4; ++yy) {
-              const float *gp = G + (o * BY + yy) * BX;
-              const float *u0 = U + (ci * WY + yy) * WXP, *u1 = u0 + WXP, *u2 = u1 + WXP;
-              float a0 = u0[0], a1 = u0[1], b0 = u1[0], b1 = u1[1], c0 = u2[0], c1 = u2[1];
-#pragma unroll 4
-              for (int xx = 0; xx < BX; ++xx) {
-                const float a2 = u0[xx + 2], b2 = u1[xx + 2], c2 = u2[xx + 2], gv = gp[xx];
-                s9[0] = fmaf(gv, a0, s9[0]); s9[1] = fmaf(gv, a1, s9[1]); s9[2] = fmaf(gv, a2, s9[2]);
-                s9[3] = fmaf(gv, b0, s9[3]); s9[4] = fmaf(gv, b1, s9[4]); s9[5] = fmaf(gv, b2, s9[5]);
-                s9[6] = fmaf(gv, c0, s9[6]); s9[7] = fmaf(gv, c1, s9[7]); s9[8] = fmaf(gv, c2, s9[8]);
-                a0 = a1; a1 = a2; b0 = b1; b1 = b2; c0 = c1; c1 = c2;
-              }
+        for (int j = 0; j < OPT; ++j) {
+          bs[j] = 0.f;
+#pragma unroll
+          for (int r = 0; r < BY; ++r) {
+            gcol[j][r] = G[((og * OPT + j) * BY + r) * BX + lane];
+            bs[j] += gcol[j][r];
+          }
+        }
+        for (int Y = 0; Y < cwh; ++Y) {
+          float s3[OPT][3];
+#pragma unroll
+          for (int j = 0; j < OPT; ++j) s3[j][0] = s3[j][1] = s3[j][2] = 0.f;
+#pragma unroll
+          for (int r = 0; r < BY; ++r) {
+            const float c0 = RW[Y * BY + r], c1 = RW[(cwh + Y) * BY + r], c2 = RW[(2 * cwh + Y) * BY + r];
+#pragma unroll
+            for (int j = 0; j < OPT; ++j) {
+              s3[j][0] = fmaf(gcol[j][r], c0, s3[j][0]);
+              s3[j][1] = fmaf(gcol[j][r], c1, s3[j][1]);
+              s3[j][2] = fmaf(gcol[j][r], c2, s3[j][2]);
             }
           }
 #pragma unroll
-          for (int k = 0; k < 9; ++k) part[t * 9 + k] = s9[k];
-          __syncthreads();
-          if (rg == 0 && o < nco && ci < nci) {
-            float *ap = acc + ((co0 + o) * a.C + ci0 + ci) * 9;
+          for (int j = 0; j < OPT; ++j)
 #pragma unroll
-            for (int k = 0; k < 9; ++k)
-              ap[k] += (part[t * 9 + k] + part[(t + 1) * 9 + k]) + (part[(t + 2) * 9 + k] + part[(t + 3) * 9 + k]);
+            for (int d = 0; d < 3; ++d) P[(((og * OPT + j) * 3 + d) * cwh + Y) * BX + lane] = s3[j][d];
+        }
+        // a wave holds one group of OPT outputs: add its 64 columns, lane 0 owns the accumulators
+#pragma unroll
+        for (int j = 0; j < OPT; ++j) {
+          float v = bs[j];
+          for (int w = 1; w < 64; w <<= 1) v += __shfl_xor(v, w);
+          if (lane == 0 && og * OPT + j < nco) acc[9 * a.C * a.C + co0 + og * OPT + j] += v;
+        }
+      }
+      __syncthreads();                            // P written, G no longer read: Q may overwrite it
+      // columns: Q[row = (o, dy, Y)][dx][X] = sum_c CW[dx][X][c] P[row][c] over the window of columns that
+      // holds the run of (dx, X) (the weights outside a run are zero)
+      {
+        const int nrows = CO * 3 * cwh, rstep = 256 / qw;
+        const int e = t % qw, r0 = t / qw;        // a thread keeps its (dx, X); threads past the last multiple of qw rest
+        const bool whole = long_run != 0;         // uniform
+        const float4 *cp = reinterpret_cast<const float4 *>(CW + e * BX);
+        if (r0 < rstep && !whole) {
+          const int lo4 = xlo[e] >> 2;
+          float4 cw4[NIT];
+#pragma unroll
+          for (int i = 0; i < NIT; ++i) cw4[i] = cp[lo4 + i];
+          for (int row = r0; row < nrows; row += rstep) {
+            const float4 *pp = reinterpret_cast<const float4 *>(P + row * BX) + lo4;
+            float sum = 0.f;
+#pragma unroll
+            for (int i = 0; i < NIT; ++i) {
+              const float4 pv = pp[i];
+              sum = fmaf(pv.x, cw4[i].x, sum);
+              sum = fmaf(pv.y, cw4[i].y, sum);
+              sum = fmaf(pv.z, cw4[i].z, sum);
+              sum = fmaf(pv.w, cw4[i].w, sum);
+            }
+            Q[row * qw + e] = sum;
+          }
+        } else if (r0 < rstep) {
+          for (int row = r0; row < nrows; row += rstep) {
+            const float4 *pp = reinterpret_cast<const float4 *>(P + row * BX);
+            float sum = 0.f;
+#pragma unroll
+            for (int i = 0; i < BX / 4; ++i) {
+              const float4 pv = pp[i], cv = cp[i];
+              sum = fmaf(pv.x, cv.x, sum);
+              sum = fmaf(pv.y, cv.y, sum);
+              sum = fmaf(pv.z, cv.z, sum);
+              sum = fmaf(pv.w, cv.w, sum);
+            }
+            Q[row * qw + e] = sum;
           }
         }
-        if (ci0 == 0) {                           // bias gradient: 32 threads per output, 32 pixels each, added in order
-          const int o = t >> 5, l = t & 31;
-          float s = 0.f;
-          if (o < nco) {
-            const float *gp = G + o * BY * BX + l * 32;
-            for (int e = 0; e < 32; ++e) s += gp[e];
-          }
-          bpart[t] = s;
-          __syncthreads();
-          if (t < nco) {
-            float tot = 0.f;
-            for (int e = 0; e < 32; ++e) tot += bpart[t * 32 + e];
-            acc[9 * a.C * a.C + co0 + t] += tot;
+      }
+      __syncthreads();
+      // window: dw[o][i][dy][dx] += sum_{Y,X} x_i(Y, X) Q[(o, dy, Y)][dx][X]
+      for (int pr = t; pr < nco * a.C; pr += 256) {
+        const int o = pr / a.C, ci = pr % a.C;
+        const float *xw = Cw + ci * npx;
+        float s9[9];
+#pragma unroll
+        for (int k = 0; k < 9; ++k) s9[k] = 0.f;
+        for (int Y = 0; Y < cwh; ++Y) {
+          const float *q0 = Q + ((o * 3 + 0) * cwh + Y) * qw, *q1 = Q + ((o * 3 + 1) * cwh + Y) * qw, *q2 = Q + ((o * 3 + 2) * cwh + Y) * qw;
+#pragma unroll 4
+          for (int X = 0; X < cww; ++X) {
+            const float xv = xw[Y * cww + X];
+            s9[0] = fmaf(xv, q0[X], s9[0]); s9[1] = fmaf(xv, q0[cww + X], s9[1]); s9[2] = fmaf(xv, q0[2 * cww + X], s9[2]);
+            s9[3] = fmaf(xv, q1[X], s9[3]); s9[4] = fmaf(xv, q1[cww + X], s9[4]); s9[5] = fmaf(xv, q1[2 * cww + X], s9[5]);
+            s9[6] = fmaf(xv, q2[X], s9[6]); s9[7] = fmaf(xv, q2[cww + X], s9[7]); s9[8] = fmaf(xv, q2[2 * cww + X], s9[8]);
           }
         }
+        float *ap = acc + ((co0 + o) * a.C + ci) * 9;
+#pragma unroll
+        for (int k = 0; k < 9; ++k) ap[k] += s9[k];
       }
     }
   }
@@ -677,10 +782,24 @@ static int head_bwd_impl(reslim_ctx *c, const char *fn, const float *x, const fl
     a.cwh = 17 / a.s + 3;
     a.cww = 65 / a.s + 3;
     const int n_acc = 9 * C * C + C;
-    const size_t lds = (static_cast<size_t>(8) * a.cwh * a.cww + n_acc) * sizeof(float);
-    if (lds > 60 * 1024) return set_error(c, RESLIM_ESHAPE, std::string(fn) + ": residual-path gradient needs scale >= 2 and out_vars <= 32");
-    RESLIM_LAUNCH("residual_wgrad", 18.0 * C * fine, 4.0 * fine + 4.0 * batch * C * c->cfg.H * c->cfg.W,
-                  (residual_wgrad_kernel<<<dim3(w.res_wg), dim3(256), lds, st>>>(a), hipGetLastError()));
+    // as many outputs per pass as fit beside the other arrays in 150 KB of LDS
+    int co = C > 8 ? 16 : C > 4 ? 8 : 4;
+    while (co > 4 && residual_wgrad_lds_floats(C, co, a.cwh, a.cww) * sizeof(float) > kResGradLds) co /= 2;
+    const size_t lds = residual_wgrad_lds_floats(C, co, a.cwh, a.cww) * sizeof(float);
+    if (lds > kResGradLds)
+      return set_error(c, RESLIM_ESHAPE, std::string(fn) + ": the residual-path gradient's arrays do not fit in LDS (scale too small or too many variables)");
+    const double win = static_cast<double>(a.cwh) * a.cww * a.nbx * a.nby * c->T * batch;   // coarse-window pixels over all blocks
+    const double res_flop = 2.0 * (12.0 * fine + 9.0 * (C + 2.0) * C * win);
+    // columns per run of the column step: 4 NIT >= 2 s + 3 (a run is shorter than 2 s + 1, plus alignment)
+    const int nit = a.s <= 4 ? 3 : a.s <= 8 ? 5 : 16;
+    hipError_t le = hipSuccess;
+#define RESLIM_RESGRAD(O, N) (residual_wgrad_kernel<O, N><<<dim3(w.res_wg), dim3(256), lds, st>>>(a), hipGetLastError())
+    RESLIM_LAUNCH("residual_wgrad", res_flop, 4.0 * fine + 4.0 * batch * C * c->cfg.H * c->cfg.W,
+                  (le = co == 16 ? (nit == 3 ? RESLIM_RESGRAD(4, 3) : nit == 5 ? RESLIM_RESGRAD(4, 5) : RESLIM_RESGRAD(4, 16))
+                      : co == 8  ? (nit == 3 ? RESLIM_RESGRAD(2, 3) : nit == 5 ? RESLIM_RESGRAD(2, 5) : RESLIM_RESGRAD(2, 16))
+                                 : (nit == 3 ? RESLIM_RESGRAD(1, 3) : nit == 5 ? RESLIM_RESGRAD(1, 5) : RESLIM_RESGRAD(1, 16)),
+                   le));
+#undef RESLIM_RESGRAD
     RESLIM_LAUNCH("partial_reduce", 0, 4.0 * w.res_wg * n_acc, launch_partial_reduce(w.resp, g->w_res, w.res_wg, n_acc, 9 * C * C, st));
     RESLIM_LAUNCH("partial_reduce", 0, 4.0 * w.res_wg * C, launch_partial_reduce(w.resp + 9 * C * C, g->b_res, w.res_wg, n_acc, C, st));
   }
@@ -854,6 +973,15 @@ static hipError_t train_model_init() {
   RESLIM_ATTR((agg_scores_bwd_kernel<bf16_t, 4>));
   RESLIM_ATTR((agg_scores_bwd_kernel<float, 16>));
   RESLIM_ATTR((agg_scores_bwd_kernel<float, 4>));
+  RESLIM_ATTR((residual_wgrad_kernel<4, 3>));
+  RESLIM_ATTR((residual_wgrad_kernel<4, 5>));
+  RESLIM_ATTR((residual_wgrad_kernel<4, 16>));
+  RESLIM_ATTR((residual_wgrad_kernel<2, 3>));
+  RESLIM_ATTR((residual_wgrad_kernel<2, 5>));
+  RESLIM_ATTR((residual_wgrad_kernel<2, 16>));
+  RESLIM_ATTR((residual_wgrad_kernel<1, 3>));
+  RESLIM_ATTR((residual_wgrad_kernel<1, 5>));
+  RESLIM_ATTR((residual_wgrad_kernel<1, 16>));
 #undef RESLIM_ATTR
   return e;
 }
