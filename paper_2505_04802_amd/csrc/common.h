@@ -50,6 +50,9 @@ struct TrainModel {
   float *wq = nullptr, *bq = nullptr, *wk = nullptr, *bk = nullptr, *wv = nullptr, *bv = nullptr;
   void *wt_head = nullptr, *wt_agg_wo = nullptr;                                 // act [D, head_out], [D, D]: [in, out] copies
   int32_t *copy_off = nullptr, *copy_idx = nullptr;                              // tile-major copies of every patch: [N + 1], [n_h]
+  void *w_vtab = nullptr;      // act [n_e, D]: value table by (head, variable, pixel | offset), zero outside the head's features
+  float *zero_e = nullptr;     // [n_e] zeros
+  int n_e = 0;                 // heads * V * (p2 + 1) rounded up to a multiple of 8
 };
 
 }  // namespace reslim

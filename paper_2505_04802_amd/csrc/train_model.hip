@@ -404,15 +404,36 @@ __global__ __launch_bounds__(256) void fill_kernel(float *p, int64_t n, float v)
 // the variables a[g, v] (recomputed as in the forward) and the gradient of its logits
 //   d_s[g, v] = a[g, v] (d_a[g, v] - sum_v' a[g, v'] d_a[g, v']),  d_a[g, v] = sum_{d in head g} d_o[d] val[v, d],
 //   val[v, d] = U[v, d, :] . pixels_v + c[v, d].
+// The sums over the head's features do not depend on the pixels:
+//   d_a[g, v] = sum_i pixels_v[i] E[(g, v, i)] + E[(g, v, p2)],  E[(g, v, j)] = sum_{d in head g} d_o[d] (U[v, d, j] | c[v, d]),
+// so E = d_o W^T is one GEMM over all tokens with the block-structured table W[(g, v, j), d] (zero
+// where d is outside head g: the matrix unit does heads times the needed products and is still far
+// quicker than the vector units on the plain form), and this kernel only combines E with the pixels.
 struct AggBwdArgs {
   const float *x, *A, *a0, *U, *c;
   const void *d_o;            // act [BN, D]
+  const float *E;             // [BN, ne] rows (g, v, j), j <= p2
   float *a_out, *ds_out;      // [BN, heads, V]
-  int V, H, W, p, Wp, N, D, heads, dh;
+  int V, H, W, p, Wp, N, D, heads, dh, ne;
   int64_t BN;
 };
 
-template <typename T, int TP>
+// W[(g * V + v) * (p2 + 1) + j][d] = U[v][d][j] (j < p2) or c[v][d] (j = p2) for d in head g, else 0; rows past the last: 0
+template <typename T>
+__global__ __launch_bounds__(256) void agg_value_table_kernel(const float *__restrict__ U, const float *__restrict__ cc, T *__restrict__ Wt,
+                                                              int V, int D, int dh, int p2, int rows, int ne) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (i >= static_cast<int64_t>(ne) * D) return;
+  const int d = static_cast<int>(i % D), r = static_cast<int>(i / D);
+  float val = 0.f;
+  if (r < rows) {
+    const int j = r % (p2 + 1), gv = r / (p2 + 1), v = gv % V, g = gv / V;
+    if (d / dh == g) val = j < p2 ? U[(static_cast<size_t>(v) * D + d) * p2 + j] : cc[static_cast<size_t>(v) * D + d];
+  }
+  Act<T>::store(Wt + i, val);
+}
+
+template <int TP>
 __global__ __launch_bounds__(256) void agg_scores_bwd_kernel(AggBwdArgs e) {
   extern __shared__ __align__(16) float smg[];
   const int p2 = e.p * e.p, VP2 = e.V * p2, HV = e.heads * e.V;
@@ -455,51 +476,18 @@ __global__ __launch_bounds__(256) void agg_scores_bwd_kernel(AggBwdArgs e) {
     const float inv = 1.0f / sum;
     for (int v = 0; v < e.V; ++v) r[v] *= inv;
   }
-  // d_a[token, head, variable] = sum over the head's features d of d_o[token, d] * val[token, variable, d].
-  // Head by head: the head's slice of the value tables (U: V x dh x p2, c: V x dh) and of d_o
-  // (TP x dh) is staged in LDS, then one thread per (token, variable) walks the dh features in
-  // increasing order (a fixed order; the staged operands are read by many threads each).
-  const T *dop = static_cast<const T *>(e.d_o);
-  float *Ug = da + TP * HV;                // [V][dh][p2]
-  float *cg = Ug + e.V * e.dh * p2;        // [V][dh]
-  float *og = cg + e.V * e.dh;             // [TP][dh]
-  for (int g = 0; g < e.heads; ++g) {
-    __syncthreads();                       // the previous head's slices are consumed (first pass: pix and sc are written)
-    for (int idx = t; idx < e.V * e.dh * p2; idx += 256) {
-      const int v = idx / (e.dh * p2), r = idx % (e.dh * p2);
-      Ug[idx] = e.U[(static_cast<size_t>(v) * e.D + g * e.dh) * p2 + r];
-    }
-    for (int idx = t; idx < e.V * e.dh; idx += 256) {
-      const int v = idx / e.dh, d = idx % e.dh;
-      cg[idx] = e.c[static_cast<size_t>(v) * e.D + g * e.dh + d];
-    }
-    for (int idx = t; idx < TP * e.dh; idx += 256) {
-      const int pi = idx / e.dh, d = idx % e.dh;
-      const int64_t bn = bn0 + pi;
-      og[idx] = bn < e.BN ? Act<T>::load(dop + bn * e.D + g * e.dh + d) : 0.f;
-    }
-    __syncthreads();
-    for (int idx = t; idx < TP * e.V; idx += 256) {
-      const int pi = idx / e.V, v = idx % e.V;
+  // d_a[token, head, variable]: consecutive threads read consecutive (p2 + 1)-float groups of a row of E
+  for (int idx = t; idx < TP * HV; idx += 256) {
+    const int pi = idx / HV, gv = idx % HV, v = gv % e.V;
+    const int64_t bn = bn0 + pi;
+    float s = 0.f;
+    if (bn < e.BN) {
+      const float *er = e.E + bn * e.ne + static_cast<size_t>(gv) * (p2 + 1);
       const float *px = pix + pi * VP2 + v * p2;
-      const float *Ur = Ug + v * e.dh * p2, *cr = cg + v * e.dh, *orow = og + pi * e.dh;
-      float s = 0.f;
-      if (p2 == 4) {
-        const float4 p4 = *reinterpret_cast<const float4 *>(px);
-        for (int d = 0; d < e.dh; ++d) {
-          const float4 u = *reinterpret_cast<const float4 *>(Ur + d * 4);
-          const float val = fmaf(u.x, p4.x, fmaf(u.y, p4.y, fmaf(u.z, p4.z, fmaf(u.w, p4.w, cr[d]))));
-          s = fmaf(orow[d], val, s);
-        }
-      } else {
-        for (int d = 0; d < e.dh; ++d) {
-          float val = cr[d];
-          for (int i = 0; i < p2; ++i) val = fmaf(Ur[d * p2 + i], px[i], val);
-          s = fmaf(orow[d], val, s);
-        }
-      }
-      da[(pi * e.heads + g) * e.V + v] = s;
+      s = er[p2];
+      for (int i = 0; i < p2; ++i) s = fmaf(px[i], er[i], s);
     }
+    da[idx] = s;
   }
   __syncthreads();
   for (int idx = t; idx < TP * e.heads; idx += 256) {
@@ -697,12 +685,17 @@ static HeadWs plan_head_ws(const reslim_ctx *c, int batch, void *base) {
   return w;
 }
 
+// rows of the value table of the aggregation gradient's GEMM: (head, variable, pixel | offset), a multiple of 8
+static int agg_table_rows(const reslim_ctx *c) {
+  return (c->cfg.heads * c->cfg.in_vars * (c->cfg.patch * c->cfg.patch + 1) + 7) / 8 * 8;
+}
 struct EmbedWs {
   float *dz;                 // [Mi, D]
   void *dz_act, *o, *d_o;    // act [Mi, D]: gradient of the aggregated tokens, aggregated values, their gradient
   void *wgrad;
   float *colp;
   float *a, *ds;             // [Mi, heads, V]
+  float *E;                  // [Mi, n_e] d_o times the block-structured value table
   float *pU, *pA;            // partial rows of the folded tables' gradients
   float *tU, *tA;            // reduced tables [V, D, p2 + 1], [V, heads, p2 + 1]
   float *dU, *dc, *dA, *da0; // split
@@ -725,6 +718,7 @@ static EmbedWs plan_embed_ws(const reslim_ctx *c, int batch, void *base) {
   w.colp = reinterpret_cast<float *>(take(static_cast<size_t>(colsum_slabs(Mi)) * D * 4));
   w.a = reinterpret_cast<float *>(take(Mi * heads * V * 4));
   w.ds = reinterpret_cast<float *>(take(Mi * heads * V * 4));
+  w.E = reinterpret_cast<float *>(take(Mi * static_cast<size_t>(agg_table_rows(c)) * 4));
   // slabs of tokens: about 2048 work-groups in the value-table pass, at least 64 tokens per slab
   const size_t per = ((D + 255) / 256) * ((V + 7) / 8);
   size_t su = std::max<size_t>(1, std::min<size_t>(256, 2048 / per));
@@ -866,20 +860,22 @@ static int embed_bwd_impl(reslim_ctx *c, const char *fn, const float *x, const f
   e.x = x; e.A = c->d_agg_A; e.a0 = c->d_agg_a0; e.U = c->d_agg_U; e.c = c->d_agg_c; e.d_o = w.d_o; e.a_out = w.a; e.ds_out = w.ds;
   e.V = V; e.H = c->cfg.H; e.W = c->cfg.W; e.p = p; e.Wp = c->Wp; e.N = c->N; e.D = D; e.heads = heads; e.dh = dh; e.BN = Mi;
   {
+    const TrainModel &tmm = c->train;
+    const double dNe = tmm.n_e;
+    RESLIM_LAUNCH("gemm_agg_dvalues", 2.0 * dMi * dNe * dD, dMi * dD * es + dNe * dD * es + 4.0 * dMi * dNe,
+                  launch_gemm(dt, EPI_BIAS_F32, w.d_o, tmm.w_vtab, tmm.zero_e, w.E, tmm.n_e, nullptr, 0, Mi, tmm.n_e, D, st));
+    e.E = w.E; e.ne = tmm.n_e;
     auto lds_for = [&](int tp) {
-      return (static_cast<size_t>(tp) * (static_cast<size_t>(V) * p2 + 2 * static_cast<size_t>(heads) * V) +
-              static_cast<size_t>(V) * dh * (p2 + 1) + static_cast<size_t>(tp) * dh) * sizeof(float);
+      return static_cast<size_t>(tp) * (static_cast<size_t>(V) * p2 + 2 * static_cast<size_t>(heads) * V) * sizeof(float);
     };
     const int tp = lds_for(16) <= 64 * 1024 ? 16 : 4;      // tokens per work-group: fewer where variables x heads is large
     const size_t lds = lds_for(tp);
     if (lds > 150 * 1024) return set_error(c, RESLIM_ESHAPE, std::string(fn) + ": too many variables x heads for the aggregation gradient");
     const dim3 grid(static_cast<unsigned>((Mi + tp - 1) / tp));
-    const double fl = 2.0 * dMi * V * dD * (p2 + 1);
-    const double by = dMi * dD * es + 8.0 * dMi * heads * V;
-    if (dt == RESLIM_BF16 && tp == 16) RESLIM_LAUNCH("agg_scores_bwd", fl, by, (agg_scores_bwd_kernel<bf16_t, 16><<<grid, dim3(256), lds, st>>>(e), hipGetLastError()));
-    else if (dt == RESLIM_BF16) RESLIM_LAUNCH("agg_scores_bwd", fl, by, (agg_scores_bwd_kernel<bf16_t, 4><<<grid, dim3(256), lds, st>>>(e), hipGetLastError()));
-    else if (tp == 16) RESLIM_LAUNCH("agg_scores_bwd", fl, by, (agg_scores_bwd_kernel<float, 16><<<grid, dim3(256), lds, st>>>(e), hipGetLastError()));
-    else RESLIM_LAUNCH("agg_scores_bwd", fl, by, (agg_scores_bwd_kernel<float, 4><<<grid, dim3(256), lds, st>>>(e), hipGetLastError()));
+    const double fl = 2.0 * dMi * heads * V * (2.0 * p2 + 3.0);
+    const double by = 4.0 * dMi * dNe + 8.0 * dMi * heads * V;
+    if (tp == 16) RESLIM_LAUNCH("agg_scores_bwd", fl, by, (agg_scores_bwd_kernel<16><<<grid, dim3(256), lds, st>>>(e), hipGetLastError()));
+    else RESLIM_LAUNCH("agg_scores_bwd", fl, by, (agg_scores_bwd_kernel<4><<<grid, dim3(256), lds, st>>>(e), hipGetLastError()));
   }
   {
     if (p2 != 4 && p2 != 1 && p2 != 16) return set_error(c, RESLIM_ESHAPE, std::string(fn) + ": the aggregation gradient is built for patch sizes 1, 2 and 4");
@@ -969,10 +965,8 @@ static hipError_t train_model_init() {
   hipError_t e = hipSuccess;
   const int lim = 150 * 1024;
 #define RESLIM_ATTR(K) if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(&K), hipFuncAttributeMaxDynamicSharedMemorySize, lim)
-  RESLIM_ATTR((agg_scores_bwd_kernel<bf16_t, 16>));
-  RESLIM_ATTR((agg_scores_bwd_kernel<bf16_t, 4>));
-  RESLIM_ATTR((agg_scores_bwd_kernel<float, 16>));
-  RESLIM_ATTR((agg_scores_bwd_kernel<float, 4>));
+  RESLIM_ATTR(agg_scores_bwd_kernel<16>);
+  RESLIM_ATTR(agg_scores_bwd_kernel<4>);
   RESLIM_ATTR((residual_wgrad_kernel<4, 3>));
   RESLIM_ATTR((residual_wgrad_kernel<4, 5>));
   RESLIM_ATTR((residual_wgrad_kernel<4, 16>));
@@ -1047,6 +1041,26 @@ extern "C" int reslim_train_prepare_model(reslim_ctx *c, const reslim_weights *w
       tm.copy_off = static_cast<int32_t *>(d0);
       tm.copy_idx = static_cast<int32_t *>(d1);
     }
+  }
+  // the value table by (head, variable, pixel | offset) for the GEMM of the aggregation gradient
+  if (e == hipSuccess) {
+    const int rows = c->cfg.heads * V * (p2 + 1);
+    tm.n_e = agg_table_rows(c);
+    void *dw = nullptr, *dz = nullptr;
+    const size_t es = dt == RESLIM_BF16 ? 2 : 4;
+    e = hipMalloc(&dw, static_cast<size_t>(tm.n_e) * D * es);
+    if (e == hipSuccess) { c->allocs.push_back(dw); e = hipMalloc(&dz, static_cast<size_t>(tm.n_e) * 4); }
+    if (e == hipSuccess) { c->allocs.push_back(dz); e = hipMemset(dz, 0, static_cast<size_t>(tm.n_e) * 4); }
+    if (e == hipSuccess) {
+      const dim3 grid(static_cast<unsigned>((static_cast<int64_t>(tm.n_e) * D + 255) / 256));
+      if (dt == RESLIM_BF16)
+        agg_value_table_kernel<bf16_t><<<grid, dim3(256)>>>(c->d_agg_U, c->d_agg_c, static_cast<bf16_t *>(dw), V, D, c->dh, p2, rows, tm.n_e);
+      else
+        agg_value_table_kernel<float><<<grid, dim3(256)>>>(c->d_agg_U, c->d_agg_c, static_cast<float *>(dw), V, D, c->dh, p2, rows, tm.n_e);
+      e = hipGetLastError();
+    }
+    tm.w_vtab = dw;
+    tm.zero_e = static_cast<float *>(dz);
   }
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) return set_error(c, e == hipErrorOutOfMemory ? RESLIM_ENOMEM : RESLIM_EHIP, std::string(fn) + ": " + hipGetErrorString(e));
