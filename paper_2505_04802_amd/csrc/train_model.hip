@@ -14,6 +14,7 @@
 // Mixed precision as in the block gradient: gradients that feed a GEMM are rounded to the
 // activation type, sums are fp32, parameter gradients are fp32 and WRITTEN in a fixed summation
 // order (deterministic).
+#include <type_traits>
 #include <algorithm>
 #include <cmath>
 #include <string>
@@ -65,6 +66,35 @@ __global__ __launch_bounds__(256) void patchify_act_kernel(const float *__restri
   const int64_t b = bn / N;
   const int n = static_cast<int>(bn % N), py = n / Wp, px = n % Wp;
   Act<T>::store(dP + e, dy[((b * C + c) * sH + py * ps + i) * sW + px * ps + j]);
+}
+
+// The same for patch sides that are multiples of four: a thread moves four neighbours of a fine row.
+// Threads run over (four pixels, four patches side by side, patch row) fastest, so a wave reads
+// whole 128-byte lines of a fine row and writes 128 contiguous bytes of each of its four patches.
+template <typename T>
+__global__ __launch_bounds__(256) void patchify_act4_kernel(const float *__restrict__ dy, T *__restrict__ dP, int64_t total4,
+                                                            int Hp, int Wp, int C, int ps, int sH, int sW) {
+  int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (e >= total4) return;
+  const int q = ps / 4, wq = (Wp + 3) / 4;
+  const int j4 = static_cast<int>(e % q); e /= q;
+  const int pxl = static_cast<int>(e % 4); e /= 4;
+  const int i = static_cast<int>(e % ps); e /= ps;
+  const int c = static_cast<int>(e % C); e /= C;
+  const int pxh = static_cast<int>(e % wq); e /= wq;
+  const int py = static_cast<int>(e % Hp);
+  const int64_t b = e / Hp;
+  const int px = pxh * 4 + pxl;
+  if (px >= Wp) return;
+  const float4 v = *reinterpret_cast<const float4 *>(dy + ((b * C + c) * sH + py * ps + i) * sW + px * ps + 4 * j4);
+  T *o = dP + ((b * Hp + py) * static_cast<int64_t>(Wp) + px) * (static_cast<int64_t>(C) * ps * ps) + (c * ps + i) * ps + 4 * j4;
+  if constexpr (std::is_same<T, float>::value) {
+    *reinterpret_cast<float4 *>(o) = v;
+  } else {
+    const uint32_t lo = static_cast<uint32_t>(f32_to_bf16(v.x)) | (static_cast<uint32_t>(f32_to_bf16(v.y)) << 16);
+    const uint32_t hi = static_cast<uint32_t>(f32_to_bf16(v.z)) | (static_cast<uint32_t>(f32_to_bf16(v.w)) << 16);
+    *reinterpret_cast<uint2 *>(o) = make_uint2(lo, hi);
+  }
 }
 
 // rows of the tile-major stream: an interior token takes its row of src[b, patch], a halo copy zero
@@ -759,9 +789,18 @@ static int head_bwd_impl(reslim_ctx *c, const char *fn, const float *x, const fl
   {
     const int64_t total = static_cast<int64_t>(Mi) * c->head_out;
     const dim3 grid(static_cast<unsigned>((total + 255) / 256));
-    if (dt == RESLIM_BF16)
+    const int64_t total4 = static_cast<int64_t>(batch) * c->Hp * ((c->Wp + 3) / 4) * C * c->ps * 4 * (c->ps / 4);
+    const dim3 grid4(static_cast<unsigned>((total4 + 255) / 256));
+    const bool vec = c->ps % 4 == 0 && sW % 4 == 0 && (reinterpret_cast<uintptr_t>(d_y) & 15) == 0;
+    if (dt == RESLIM_BF16 && vec)
+      RESLIM_LAUNCH("patchify_grad", 0, 4.0 * fine + es * fine,
+                    (patchify_act4_kernel<bf16_t><<<grid4, dim3(256), 0, st>>>(d_y, static_cast<bf16_t *>(w.dP), total4, c->Hp, c->Wp, C, c->ps, sH, sW), hipGetLastError()));
+    else if (dt == RESLIM_BF16)
       RESLIM_LAUNCH("patchify_grad", 0, 4.0 * fine + es * fine,
                     (patchify_act_kernel<bf16_t><<<grid, dim3(256), 0, st>>>(d_y, static_cast<bf16_t *>(w.dP), total, c->N, c->Wp, C, c->ps, sH, sW), hipGetLastError()));
+    else if (vec)
+      RESLIM_LAUNCH("patchify_grad", 0, 8.0 * fine,
+                    (patchify_act4_kernel<float><<<grid4, dim3(256), 0, st>>>(d_y, static_cast<float *>(w.dP), total4, c->Hp, c->Wp, C, c->ps, sH, sW), hipGetLastError()));
     else
       RESLIM_LAUNCH("patchify_grad", 0, 8.0 * fine,
                     (patchify_act_kernel<float><<<grid, dim3(256), 0, st>>>(d_y, static_cast<float *>(w.dP), total, c->N, c->Wp, C, c->ps, sH, sW), hipGetLastError()));
