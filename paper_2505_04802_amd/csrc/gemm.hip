@@ -72,10 +72,12 @@ __device__ __host__ constexpr bool epi_act_out() {
 }
 constexpr int kEpiStageBytes = 4096;    // per wave
 
-// one value of a bf16-output epilogue (v already carries the bias)
+// one value of a bf16-output epilogue (v already carries the bias); sc: the factor of the value's
+// block of 32 columns (EPI_BIAS_QSCALE_ACT: qcols is a multiple of 32, so a block is scaled as a
+// whole and the factor is one scalar per block, not a register per column)
 template <int EPI, bool SECOND>
-__device__ __forceinline__ float epi_act_value(const GemmArgs &g, float v, int n) {
-  if constexpr (EPI == EPI_BIAS_QSCALE_ACT) return v * (n < g.qcols ? g.qscale : 1.0f);
+__device__ __forceinline__ float epi_act_value(float v, float sc) {
+  if constexpr (EPI == EPI_BIAS_QSCALE_ACT) return v * sc;
   if constexpr (EPI == EPI_BIAS_GELU_ACT || (EPI == EPI_BIAS_ACT_GELU2 && SECOND)) return gelu_erf_fast(v);
   return v;
 }
@@ -103,15 +105,13 @@ __device__ __forceinline__ void epilogue_act_stage(const GemmArgs &g, const f32x
   const int wsw = (l32 >> 1) & 7;
 #pragma unroll
   for (int jj = 0; jj < NB; ++jj) {
+    const float sc = (EPI == EPI_BIAS_QSCALE_ACT && n_first + jj * 32 < g.qcols) ? g.qscale : 1.0f;   // uniform
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      const int n = n_first + jj * 32 + 8 * q + 4 * hi;
       const float4 b = bias[jj][q];
       u32x2 pk;
-      pk[0] = pack2(epi_act_value<EPI, SECOND>(g, blk[jj][4 * q] + b.x, n),
-                    epi_act_value<EPI, SECOND>(g, blk[jj][4 * q + 1] + b.y, n + 1));
-      pk[1] = pack2(epi_act_value<EPI, SECOND>(g, blk[jj][4 * q + 2] + b.z, n + 2),
-                    epi_act_value<EPI, SECOND>(g, blk[jj][4 * q + 3] + b.w, n + 3));
+      pk[0] = pack2(epi_act_value<EPI, SECOND>(blk[jj][4 * q] + b.x, sc), epi_act_value<EPI, SECOND>(blk[jj][4 * q + 1] + b.y, sc));
+      pk[1] = pack2(epi_act_value<EPI, SECOND>(blk[jj][4 * q + 2] + b.z, sc), epi_act_value<EPI, SECOND>(blk[jj][4 * q + 3] + b.w, sc));
       *reinterpret_cast<u32x2 *>(wrow + (((jj * 4 + q) ^ wsw) << 4)) = pk;
     }
   }
@@ -532,6 +532,7 @@ hipError_t launch_gemm(int dtype, Epilogue epi, const void *A, const void *W, co
   if (dtype == RESLIM_BF16) {
     if (K % 64 != 0) return hipErrorInvalidValue;   // slabs are 64 deep; create() enforces D % 64 == 0
     if (ldo % 8 != 0 || N % 8 != 0) return hipErrorInvalidValue;  // epilogues move 16 bytes of a row at once
+    if (epi == EPI_BIAS_QSCALE_ACT && qcols % 32 != 0) return hipErrorInvalidValue;   // one factor per block of 32 columns
     switch (epi) {
       case EPI_BIAS_ACT: return launch_bf16<EPI_BIAS_ACT>(g, st);
       case EPI_BIAS_GELU_ACT: return launch_bf16<EPI_BIAS_GELU_ACT>(g, st);
