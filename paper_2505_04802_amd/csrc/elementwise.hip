@@ -481,7 +481,10 @@ __global__ __launch_bounds__(256) void residual_unpatchify_kernel(ResArgs a) {
   }
   const bool one_pass = a.ci_chunk >= a.C;       // the whole input window fits: load it once
 
+  // 4 pixels of one patch row: aligned 16-byte load and store
+  const bool vec4 = iy < ih && a.ps % 4 == 0 && sW % 4 == 0 && ix + 3 < iw;
   for (int co0 = 0; co0 < a.C; co0 += CO) {
+    float4 pv[CO];
     // ---- Z: the variables mixed on the coarse window, per tap
     for (int ci0 = 0; ci0 < a.C; ci0 += a.ci_chunk) {
       const int nci = min(a.ci_chunk, a.C - ci0);
@@ -500,6 +503,15 @@ __global__ __launch_bounds__(256) void residual_unpatchify_kernel(ResArgs a) {
         Ws[idx] = (co0 + o < a.C) ? a.w_res[(static_cast<size_t>(co0 + o) * a.C + ci0 + ci) * 9 + tap] : 0.f;
       }
       __syncthreads();
+      // The head projection of this thread's pixels is requested now, behind the window's own loads
+      // (vector-memory results are waited for in issue order): it arrives while the window is worked on.
+      if (vec4 && ci0 == 0) {
+        const int py = td.y0 + iy / a.ps, i = iy % a.ps, px = td.x0 + ix / a.ps, j = ix % a.ps;
+        const float *pp = a.P + (static_cast<size_t>(b) * a.N + static_cast<size_t>(py) * a.Wp + px) * a.head_out + static_cast<size_t>(i) * a.ps + j;
+#pragma unroll
+        for (int o = 0; o < CO; ++o)
+          if (co0 + o < a.C) pv[o] = *reinterpret_cast<const float4 *>(pp + static_cast<size_t>(co0 + o) * a.ps * a.ps);
+      }
       for (int item = t; item < 9 * npx; item += 256) {
         const int px = item % npx, tap = item / npx;
         float z[CO];
@@ -596,15 +608,8 @@ __global__ __launch_bounds__(256) void residual_unpatchify_kernel(ResArgs a) {
     if (iy < ih) {
       const int gy = td.y0 * a.ps + iy;
       const int py = td.y0 + iy / a.ps, i = iy % a.ps;
-      if (a.ps % 4 == 0 && sW % 4 == 0 && ix + 3 < iw) {   // 4 pixels of one patch row: aligned 16-byte load and store
-        const int px = td.x0 + ix / a.ps, j = ix % a.ps;
-        const size_t n = static_cast<size_t>(py) * a.Wp + px;
-        const float *pp = a.P + (static_cast<size_t>(b) * a.N + n) * a.head_out + static_cast<size_t>(i) * a.ps + j;
+      if (vec4) {
         float *yp = a.y + (static_cast<size_t>(b) * a.C * sH + gy) * sW + td.x0 * a.ps + ix;
-        float4 pv[CO];
-#pragma unroll
-        for (int o = 0; o < CO; ++o)
-          if (co0 + o < a.C) pv[o] = *reinterpret_cast<const float4 *>(pp + static_cast<size_t>(co0 + o) * a.ps * a.ps);
 #pragma unroll
         for (int o = 0; o < CO; ++o) {
           const int c = co0 + o;
