@@ -53,7 +53,10 @@ int embed_full_impl(reslim_ctx *c, const char *fn, const float *x, int batch, co
   const int D = c->cfg.embed_dim, dt = c->cfg.dtype;
   const int Mi = batch * c->N;
   const double es = static_cast<double>(act_size(c)), dMi = Mi, dD = D;
-  RESLIM_LAUNCH("embed_agg", 0, 4.0 * batch * c->cfg.in_vars * c->cfg.H * c->cfg.W + dMi * dD * es,
+  // scores and values are affine in the p x p pixels of a patch: (p^2 + 1) multiply-adds per (variable, head) and per
+  // (variable, feature), then the weighted sum over the variables
+  RESLIM_LAUNCH("embed_agg", 2.0 * dMi * c->cfg.in_vars * ((c->cfg.patch * c->cfg.patch + 1.0) * (dD + c->cfg.heads) + dD),
+                4.0 * batch * c->cfg.in_vars * c->cfg.H * c->cfg.W + dMi * dD * es,
                 launch_embed_agg(c, x, w.A, batch, st));
   RESLIM_LAUNCH("gemm_agg_out", 2.0 * dMi * dD * dD, dMi * dD * es + dD * dD * es + 4.0 * c->N * dD + 4.0 * dMi * dD,
                 launch_gemm(dt, EPI_BIAS_TAB_F32, w.A, c->d_agg_wo, c->d_zero_bias, w.big, D, c->d_pos_res, c->N, Mi, D, D, st));
