@@ -42,12 +42,12 @@ MEASURED_TRAFFIC = {
     ("c2", "tiles_attention"): 1941.6e6 + 332.0e6,
     ("c2", "layernorm"): 656.7e6 + 328.2e6,
     # profiles/forward_c3_all_kernels.md (FC2 and the projection share one kernel symbol: no separate figure)
-    ("c3", "gemm_fc1"): 4986.2e6 + 3303.0e6,
-    ("c3", "gemm_qkv"): 3772.2e6 + 2477.3e6,
-    ("c3", "tiles_attention"): 7759.0e6 + 826.7e6,
+    ("c3", "gemm_fc1"): 4970.3e6 + 3303.0e6,
+    ("c3", "gemm_qkv"): 3795.8e6 + 2477.3e6,
+    ("c3", "tiles_attention"): 7878.3e6 + 827.1e6,
     ("c3", "layernorm"): 1617.4e6 + 808.4e6,
-    ("c3", "residual_unpatchify"): 4857.2e6 + 4246.7e6,
-    ("c3", "gemm_head"): 3292.0e6 + 4251.1e6,
+    ("c3", "residual_unpatchify"): 4859.7e6 + 4246.7e6,
+    ("c3", "gemm_head"): 3265.9e6 + 4252.9e6,
 }
 
 
