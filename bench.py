@@ -31,15 +31,15 @@ ALU_BOUND = ("embed_agg",)      # kernels whose time is plain fp32 vector arithm
 MEASURED_TRAFFIC = {
     ("c1", "gemm_fc1"): 146.9e6 + 174.3e6,
     ("c1", "gemm_fc2"): 335.8e6 + 89.5e6,
-    ("c1", "tiles_attention"): 160.1e6 + 43.8e6,
-    ("c1", "gemm_qkv"): 98.2e6 + 130.7e6,
+    ("c1", "tiles_attention"): 161.7e6 + 43.8e6,
+    ("c1", "gemm_qkv"): 98.1e6 + 130.7e6,
     ("c1", "gemm_proj"): 140.6e6 + 90.1e6,
     ("c1", "layernorm"): 86.0e6 + 42.9e6,
     # profiles/forward_and_train_block_c2_all_kernels.md
-    ("c2", "gemm_fc1"): 1993.6e6 + 1322.3e6,
+    ("c2", "gemm_fc1"): 1994.0e6 + 1322.3e6,
     ("c2", "gemm_fc2"): 2646.8e6 + 695.2e6,
-    ("c2", "gemm_qkv"): 1493.6e6 + 991.7e6,
-    ("c2", "tiles_attention"): 1941.6e6 + 332.0e6,
+    ("c2", "gemm_qkv"): 1497.8e6 + 991.7e6,
+    ("c2", "tiles_attention"): 1979.2e6 + 332.2e6,
     ("c2", "layernorm"): 656.7e6 + 328.2e6,
     # profiles/forward_c3_all_kernels.md (FC2 and the projection share one kernel symbol: no separate figure)
     ("c3", "gemm_fc1"): 4970.3e6 + 3303.0e6,
