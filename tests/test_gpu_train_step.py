@@ -23,6 +23,12 @@ TRAIN_F32 = WL.ReslimConfig("tr32", batch=2, in_vars=3, out_vars=2, H=24, W=40, 
 TRAIN_BF16 = WL.ReslimConfig("trbf", batch=2, in_vars=3, out_vars=3, H=44, W=60, scale=4, patch=2, embed_dim=128, heads=2,
                              mlp_ratio=4, depth=2, tiles_y=2, tiles_x=2, halo=2, dtype=1, seed=52)          # head width 192
 TRAIN_BF16_DH128 = TRAIN_BF16.with_(name="trbf128", embed_dim=256, heads=2, in_vars=5, out_vars=4, seed=53)   # head width 256
+# the headline workload's residual-path geometry (scale 8, 16 variables: 16 outputs per pass of the weight-gradient
+# kernel, 20-column runs) and a scale above it (whole-row runs), both small enough for the oracle
+TRAIN_S8 = WL.ReslimConfig("trs8", batch=1, in_vars=16, out_vars=16, H=8, W=16, scale=8, patch=2, embed_dim=32, heads=2,
+                           mlp_ratio=2, depth=1, tiles_y=2, tiles_x=2, halo=1, dtype=0, seed=54)
+TRAIN_S16 = WL.ReslimConfig("trs16", batch=2, in_vars=3, out_vars=2, H=6, W=8, scale=16, patch=2, embed_dim=32, heads=2,
+                            mlp_ratio=2, depth=1, tiles_y=1, tiles_x=2, halo=1, dtype=0, seed=55)
 FRONT = ("w_pe", "b_pe", "var_emb", "agg_q0", "agg_wq", "agg_bq", "agg_wk", "agg_bk", "agg_wv", "agg_bv", "agg_wo", "agg_bo",
          "pos_emb", "res_emb")
 BACK = ("lnf_g", "lnf_b", "w_head", "b_head", "w_res", "b_res")
@@ -87,7 +93,7 @@ def test_loss_gradient_parity(shape):
     assert_parity(d.cpu().numpy(), ref, 1e-5, f"loss gradient {shape}", say, k_elem=1e-4)
 
 
-@pytest.mark.parametrize("cfg", [TRAIN_F32, TRAIN_BF16, TRAIN_BF16_DH128], ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", [TRAIN_F32, TRAIN_BF16, TRAIN_BF16_DH128, TRAIN_S8, TRAIN_S16], ids=lambda c: c.name)
 def test_model_ends_stage_by_stage(cfg):
     """Each end of the model from the ORACLE's intermediates, so errors do not compound."""
     w, x, target, lat_w = case(cfg, 0.1)
@@ -135,7 +141,7 @@ def run_step(m, cfg, w, x, target, lat_w, tv, scale):
     return g, y.cpu().numpy(), loss3.cpu().numpy(), int(flag.item())
 
 
-@pytest.mark.parametrize("cfg", [TRAIN_F32, TRAIN_BF16, TRAIN_BF16_DH128], ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", [TRAIN_F32, TRAIN_BF16, TRAIN_BF16_DH128, TRAIN_S8, TRAIN_S16], ids=lambda c: c.name)
 def test_train_step_parity(cfg):
     """Forward, loss and every one of the 32 gradients end to end, the loss scaled by 1024 and the
     gradients unscaled again; a second call gives the same bits."""
