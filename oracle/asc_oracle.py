@@ -348,6 +348,24 @@ def compress_tiles(z, table, Wp: int, T: int):
     return out
 
 
+def compress_tiles_bwd(dZc, table, B: int, N: int, Wp: int, T: int):
+    """Gradient of `compress_tiles`: every leaf hands 1/(s*s) of its gradient to each of its
+    patches; with tiles a patch lies in the leaves of every box whose haloed region holds it, so
+    the contributions add up.  dZc[L, D] -> [B, N, D].  (`decompress` and `decompress_bwd` need
+    no tiled form: they follow patch_leaf, which already names the owning tile's leaf.)"""
+    dZc = np.asarray(dZc, F64)
+    out = np.zeros((B, N, dZc.shape[1]), F64)
+    off = table["sample_off"]
+    for q in range(len(off) - 1):
+        b = q // T
+        for i in range(int(off[q]), int(off[q + 1])):
+            y0, x0, s = int(table["leaf_y0"][i]), int(table["leaf_x0"][i]), int(table["leaf_s"][i])
+            for yy in range(y0, y0 + s):
+                for xx in range(x0, x0 + s):
+                    out[b, yy * Wp + xx] += dZc[i] / float(s * s)
+    return out
+
+
 def forward_compressed_tiles(x, w, cfg, table):
     """Batched form of the tiled forward with compression: embed once, one leaf set per
     (sample, tile), blocks with attention inside a leaf set, each patch decompressed from

@@ -356,3 +356,35 @@ def test_tiled_compressed_forward_special_cases():
     t1 = tiles[1]
     np.testing.assert_allclose(y2[..., t1["x0"] * ps:], y[..., t1["x0"] * ps:], atol=1e-12)
     assert np.abs(y2[..., :8 * cfg.scale] - y[..., :8 * cfg.scale]).max() > 1e-3
+
+
+def test_tiled_compression_gradients_are_the_adjoint_maps():
+    """The gradient maps under TILES against the forward maps they transpose (which the pins above
+    hold): <A z, g> = <z, A^T g> for compression per box and for decompression from the owning tile;
+    one tile: the untiled gradient; the halo's share: a patch in k boxes collects k contributions."""
+    cfg, w, x, tiles = _tiled_case()
+    T, N, D = len(tiles), cfg.Hp * cfg.Wp, 5
+    tab = A.build_tiles(x[:, 0], cfg.patch, tiles, Wp=cfg.Wp, **PRM)
+    L = len(tab["leaf_s"])
+    r = np.random.default_rng(12)
+    z, g_c = r.standard_normal((cfg.batch, N, D)), r.standard_normal((L, D))
+    lhs = (A.compress_tiles(z, tab, cfg.Wp, T) * g_c).sum()
+    assert abs(lhs - (z * A.compress_tiles_bwd(g_c, tab, cfg.batch, N, cfg.Wp, T)).sum()) < 1e-10
+    zc, g = r.standard_normal((L, D)), r.standard_normal((cfg.batch, N, D))
+    assert abs((A.decompress(zc, tab) * g).sum() - (zc * A.decompress_bwd(g, tab)).sum()) < 1e-10
+    # leaves that only cover halo patches of their box receive nothing from decompression
+    used = np.zeros(L, bool)
+    used[np.unique(tab["patch_leaf"])] = True
+    assert not used.all() and not A.decompress_bwd(g, tab)[~used].any()
+    # all-ones leaf gradient: a patch gets 1 per box that holds it (the number of its tile-major copies)
+    copies = np.bincount(O.tiles_partition(cfg.Hp, cfg.Wp, cfg.tiles_y, cfg.tiles_x, cfg.halo)[1], minlength=N)
+    ones = A.compress_tiles_bwd(np.ones((L, 1)) * (tab["leaf_s"][:, None] ** 2), tab, cfg.batch, N, cfg.Wp, T)
+    # (scaled by s*s so that each leaf hands exactly 1 to each of its patches)
+    assert np.array_equal(ones[0, :, 0], copies) and copies.max() > 1
+    # one tile: the untiled map
+    cfg1, w1, x1, tiles1 = _tiled_case(tiles_y=1, tiles_x=1, halo=3)
+    tab1 = A.build_tiles(x1[:, 0], cfg1.patch, tiles1, Wp=cfg1.Wp, **PRM)
+    g1 = r.standard_normal((len(tab1["leaf_s"]), D))
+    np.testing.assert_allclose(A.compress_tiles_bwd(g1, tab1, cfg1.batch, cfg1.Hp * cfg1.Wp, cfg1.Wp, 1),
+                               A.compress_bwd(g1, tab1, cfg1.batch, cfg1.Hp * cfg1.Wp), atol=1e-14)
+
