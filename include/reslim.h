@@ -421,8 +421,9 @@ int reslim_bayes_loss_fwd_static(const float *pred, const float *target, const f
  * checks and uploads it, reslim_asc_forward runs the model on the leaves.  The
  * paper gives no thresholds, filter sizes or merge rule; the readings are stated at
  * each function.  With a tiled context every (sample, tile) pair has its own leaf set
- * (reslim_asc_build_tiles); the gradients of compression and decompression
- * (reslim_asc_compress_bwd, reslim_asc_decompress_bwd) need a one-tile context. */
+ * (reslim_asc_build_tiles); a patch then lies in one leaf of every box that holds it and
+ * is decompressed from the leaf of the tile that owns it, which the gradients of the two
+ * maps (reslim_asc_compress_bwd, reslim_asc_decompress_bwd) follow. */
 typedef struct reslim_asc_plan reslim_asc_plan;
 
 /* HOST function, no HIP call.  images: host fp32 [batch, H, W].  Per sample:
@@ -510,7 +511,10 @@ int reslim_asc_compress(reslim_ctx *ctx, const reslim_asc_plan *plan, const floa
  * maps: reslim_asc_compress_bwd gives every patch its leaf's gradient divided by the
  * leaf's patch count (d_tokens_c [n_leaves, D] -> d_tokens [batch*N, D]);
  * reslim_asc_decompress_bwd adds up the gradients of a leaf's patches (d_tokens
- * [batch*N, D] -> d_tokens_c [n_leaves, D], fixed summation order).  All dev fp32. */
+ * [batch*N, D] -> d_tokens_c [n_leaves, D], fixed summation order).  With tiles the first
+ * adds the shares of all leaves that hold the patch (its tile's and those of the boxes whose
+ * halo it lies in, increasing leaf index), the second only the patches the leaf's tile owns (a
+ * leaf made of halo patches alone gets zero).  All dev fp32. */
 int reslim_asc_decompress(reslim_ctx *ctx, const reslim_asc_plan *plan, const float *tokens_c, float *tokens, void *hip_stream);
 int reslim_asc_compress_bwd(reslim_ctx *ctx, const reslim_asc_plan *plan, const float *d_tokens_c, float *d_tokens, void *hip_stream);
 int reslim_asc_decompress_bwd(reslim_ctx *ctx, const reslim_asc_plan *plan, const float *d_tokens, float *d_tokens_c, void *hip_stream);

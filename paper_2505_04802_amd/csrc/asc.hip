@@ -73,6 +73,63 @@ __global__ __launch_bounds__(256) void asc_expand_kernel(const float *__restrict
   }
 }
 
+// Gradient of compression where tiles overlap: one wave per patch adds gradient / (side * side) of
+// every leaf that holds the patch (one per box whose haloed region contains it), in increasing
+// leaf order: a fixed order, deterministic.
+__global__ __launch_bounds__(256) void asc_cover_sum_kernel(const float *__restrict__ d_leaf_tok, const int32_t *__restrict__ cover_off,
+                                                            const int32_t *__restrict__ cover_leaf, const int32_t *__restrict__ leaf,
+                                                            float *__restrict__ dst, int64_t patches, int D) {
+  const int lane = threadIdx.x & 63;
+  const int64_t p = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  if (p >= patches) return;
+  const int lo = cover_off[p], hi = cover_off[p + 1];
+  float4 *out = reinterpret_cast<float4 *>(dst + static_cast<size_t>(p) * D);
+  for (int d = lane; d < D / 4; d += 64) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int k = lo; k < hi; ++k) {
+      const int l = cover_leaf[k], s = leaf[4 * static_cast<int64_t>(l) + 1];
+      const float f = 1.0f / static_cast<float>(s * s);
+      const float4 v = reinterpret_cast<const float4 *>(d_leaf_tok + static_cast<size_t>(l) * D)[d];
+      acc.x = fmaf(v.x, f, acc.x); acc.y = fmaf(v.y, f, acc.y); acc.z = fmaf(v.z, f, acc.z); acc.w = fmaf(v.w, f, acc.w);
+    }
+    out[d] = acc;
+  }
+}
+
+// Gradient of decompression where tiles overlap: a leaf collects the gradients of the patches that
+// were decompressed from it, i.e. of those of its patches that its tile owns (patch_leaf names this
+// leaf); its halo patches took their tokens from other tiles' leaves.  One work-group per leaf,
+// rows in increasing order per wave, the four waves' sums added in wave order.
+__global__ __launch_bounds__(256) void asc_owned_sum_kernel(const float *__restrict__ z, const int32_t *__restrict__ leaf,
+                                                            const int32_t *__restrict__ patch_leaf, float *__restrict__ out, int Wp, int D) {
+  __shared__ float4 part[3][64];
+  const int64_t l = blockIdx.x;
+  const int first = leaf[4 * l], s = leaf[4 * l + 1];
+  const int rows = s * s;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int d0 = 0; d0 < D; d0 += 256) {              // uniform over the work-group
+    const int d = d0 + lane * 4;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (d < D) {
+      for (int r = wave; r < rows; r += 4) {
+        const int dy = r / s, dx = r - dy * s;
+        const size_t row = static_cast<size_t>(first) + static_cast<size_t>(dy) * Wp + dx;
+        if (patch_leaf[row] != l) continue;          // uniform over the wave
+        const float4 v = *reinterpret_cast<const float4 *>(z + row * D + d);
+        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+      }
+    }
+    if (wave > 0) part[wave - 1][lane] = acc;
+    __syncthreads();
+    if (wave == 0 && d < D) {
+#pragma unroll
+      for (int w = 0; w < 3; ++w) { const float4 q = part[w][lane]; acc.x += q.x; acc.y += q.y; acc.z += q.z; acc.w += q.w; }
+      *reinterpret_cast<float4 *>(out + static_cast<size_t>(l) * D + d) = acc;
+    }
+    __syncthreads();
+  }
+}
+
 // One wave per token: p*p dot products of length D, written to the token's pixels.
 __global__ __launch_bounds__(256) void asc_image_kernel(const float *__restrict__ z, const float *__restrict__ w_img,
                                                         const float *__restrict__ b_img, float *__restrict__ img,
@@ -98,6 +155,8 @@ static void asc_free(reslim_asc_plan *pl) {
   if (pl->d_seq_of_leaf) (void)hipFree(pl->d_seq_of_leaf);
   if (pl->d_leaf) (void)hipFree(pl->d_leaf);
   if (pl->d_patch_leaf) (void)hipFree(pl->d_patch_leaf);
+  if (pl->d_cover_off) (void)hipFree(pl->d_cover_off);
+  if (pl->d_cover_leaf) (void)hipFree(pl->d_cover_leaf);
   delete pl;
 }
 
@@ -169,6 +228,21 @@ extern "C" int reslim_asc_plan_create(reslim_ctx *c, int32_t batch, const int32_
     max_n = std::max(max_n, seq[q].n_tok);
     pairs += static_cast<double>(hi - lo) * static_cast<double>(hi - lo);
   }
+  // leaves of every patch (tiled contexts): counting pass, prefix sums, fill in increasing leaf order
+  std::vector<int32_t> cover_off, cover_leaf;
+  if (T != 1) {
+    cover_off.assign(static_cast<size_t>(batch) * N + 1, 0);
+    for (int64_t l = 0; l < n_leaves; ++l)
+      for (int dy = 0; dy < leaf[4 * l + 1]; ++dy)
+        for (int dx = 0; dx < leaf[4 * l + 1]; ++dx) ++cover_off[static_cast<size_t>(leaf[4 * l]) + static_cast<size_t>(dy) * c->Wp + dx + 1];
+    for (size_t i = 1; i < cover_off.size(); ++i) cover_off[i] += cover_off[i - 1];
+    cover_leaf.resize(static_cast<size_t>(cover_off.back()));
+    std::vector<int32_t> fill(cover_off.begin(), cover_off.end() - 1);
+    for (int64_t l = 0; l < n_leaves; ++l)
+      for (int dy = 0; dy < leaf[4 * l + 1]; ++dy)
+        for (int dx = 0; dx < leaf[4 * l + 1]; ++dx)
+          cover_leaf[static_cast<size_t>(fill[static_cast<size_t>(leaf[4 * l]) + static_cast<size_t>(dy) * c->Wp + dx]++)] = static_cast<int32_t>(l);
+  }
   reslim_asc_plan *pl = new (std::nothrow) reslim_asc_plan;
   if (!pl) return set_error(c, RESLIM_ENOMEM, std::string(fn) + ": host allocation failed");
   pl->ctx = c; pl->batch = batch; pl->L = n_leaves; pl->seq = seq;
@@ -180,6 +254,12 @@ extern "C" int reslim_asc_plan_create(reslim_ctx *c, int32_t batch, const int32_
   if (e == hipSuccess) e = hipMemcpy(pl->d_seq_of_leaf, seq_of.data(), n_leaves * 4, hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy(pl->d_leaf, leaf.data(), n_leaves * 16, hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy(pl->d_patch_leaf, patch_leaf, batch * N * 4, hipMemcpyHostToDevice);
+  if (e == hipSuccess && T != 1) {
+    e = hipMalloc(reinterpret_cast<void **>(&pl->d_cover_off), cover_off.size() * 4);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&pl->d_cover_leaf), std::max<size_t>(cover_leaf.size() * 4, 256));
+    if (e == hipSuccess) e = hipMemcpy(pl->d_cover_off, cover_off.data(), cover_off.size() * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(pl->d_cover_leaf, cover_leaf.data(), cover_leaf.size() * 4, hipMemcpyHostToDevice);
+  }
   if (e != hipSuccess) {
     asc_free(pl);
     return set_error(c, e == hipErrorOutOfMemory ? RESLIM_ENOMEM : RESLIM_EHIP, std::string(fn) + ": " + hipGetErrorString(e));
@@ -228,16 +308,19 @@ static int asc_move(reslim_ctx *c, const reslim_asc_plan *plan, const char *fn, 
   int rc = asc_check(c, plan, fn);
   if (rc != RESLIM_OK) return rc;
   if (!src || !dst) return set_error(c, RESLIM_EINVAL, std::string(fn) + ": null buffer");
-  // with tiles a patch sits in the leaves of several boxes and a leaf decompresses only into its
-  // tile's interior: the two gradient maps below assume one leaf per patch
-  if (mode != 0 && c->T != 1) return set_error(c, RESLIM_ESHAPE, std::string(fn) + ": needs a context with one tile");
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const int D = c->cfg.embed_dim;
   const int64_t patches = static_cast<int64_t>(plan->batch) * c->N;
   const dim3 pg(static_cast<unsigned>((patches + 3) / 4));
+  // With tiles a patch sits in the leaves of several boxes and a leaf decompresses only into its
+  // tile's interior: the gradient of compression adds over a patch's leaves, the gradient of
+  // decompression over the patches a leaf's tile owns.  One tile: one leaf per patch, every patch owned.
+  const bool tiled = c->T != 1;
   if (mode == 0) asc_expand_kernel<false><<<pg, dim3(256), 0, st>>>(src, plan->d_patch_leaf, plan->d_leaf, dst, patches, D);
-  else if (mode == 1) asc_expand_kernel<true><<<pg, dim3(256), 0, st>>>(src, plan->d_patch_leaf, plan->d_leaf, dst, patches, D);
-  else asc_compress_kernel<false><<<dim3(static_cast<unsigned>(plan->L)), dim3(256), 0, st>>>(src, plan->d_leaf, dst, c->Wp, D);
+  else if (mode == 1 && !tiled) asc_expand_kernel<true><<<pg, dim3(256), 0, st>>>(src, plan->d_patch_leaf, plan->d_leaf, dst, patches, D);
+  else if (mode == 1) asc_cover_sum_kernel<<<pg, dim3(256), 0, st>>>(src, plan->d_cover_off, plan->d_cover_leaf, plan->d_leaf, dst, patches, D);
+  else if (!tiled) asc_compress_kernel<false><<<dim3(static_cast<unsigned>(plan->L)), dim3(256), 0, st>>>(src, plan->d_leaf, dst, c->Wp, D);
+  else asc_owned_sum_kernel<<<dim3(static_cast<unsigned>(plan->L)), dim3(256), 0, st>>>(src, plan->d_leaf, plan->d_patch_leaf, dst, c->Wp, D);
   RESLIM_TRY("launch", hipGetLastError());
   return RESLIM_OK;
 }

@@ -205,6 +205,9 @@ struct reslim_asc_plan {
   int32_t *d_seq_of_leaf = nullptr;      // [L]
   int32_t *d_leaf = nullptr;             // [L][4]: first patch row (b*N + y0*Wp + x0), side, unused, unused
   int32_t *d_patch_leaf = nullptr;       // [batch * N]
+  // contexts with tiles: a patch lies in one leaf of every box that holds it (its tile's and the neighbours' halos)
+  int32_t *d_cover_off = nullptr;        // [batch * N + 1]
+  int32_t *d_cover_leaf = nullptr;       // [cover_off[batch * N]] leaves of each patch, increasing
 };
 
 

@@ -442,8 +442,23 @@ def test_tiled_plan_errors():
             L, D = len(tab["leaf_s"]), cfg.embed_dim
             a = torch.zeros((L, D), dtype=torch.float32, device="cuda")
             b = torch.zeros((cfg.batch * cfg.n_tokens, D), dtype=torch.float32, device="cuda")
-            assert lib.reslim_asc_compress_bwd(m.ctx, plan, a.data_ptr(), b.data_ptr(), None) == B.RESLIM_ESHAPE
-            assert lib.reslim_asc_decompress_bwd(m.ctx, plan, b.data_ptr(), a.data_ptr(), None) == B.RESLIM_ESHAPE
-            B.reslim_asc_decompress(m.ctx, plan, a, b)                    # the forward map itself is fine
+            B.reslim_asc_decompress(m.ctx, plan, a, b)
+            # the two gradient maps under TILES against the oracle (fp32: the same sums in another order)
+            r = np.random.default_rng(5)
+            N, T = cfg.n_tokens, len(tiles)
+            g_c = r.standard_normal((L, D)).astype(np.float32)
+            B.reslim_asc_compress_bwd(m.ctx, plan, cuda(g_c), b)
+            ref = A.compress_tiles_bwd(g_c, tab, cfg.batch, N, cfg.Wp, T)
+            assert_parity(b.cpu().numpy().reshape(cfg.batch, N, D), ref, 1e-6, "compress_bwd under tiles", say, k_elem=1e-5)
+            g = r.standard_normal((cfg.batch, N, D)).astype(np.float32)
+            B.reslim_asc_decompress_bwd(m.ctx, plan, cuda(g.reshape(-1, D)), a)
+            ref = A.decompress_bwd(g, tab)
+            got = a.cpu().numpy()
+            assert_parity(got[None], ref[None], 1e-6, "decompress_bwd under tiles", say, k_elem=1e-5)
+            unused = np.setdiff1d(np.arange(L), np.unique(tab["patch_leaf"]))
+            assert len(unused) and not got[unused].any()                  # leaves of halo patches alone receive nothing
+            a2 = torch.full_like(a, float("nan"))
+            B.reslim_asc_decompress_bwd(m.ctx, plan, cuda(g.reshape(-1, D)), a2)
+            assert torch.equal(a, a2)                                     # deterministic
         finally:
             B.reslim_asc_plan_destroy(plan)
