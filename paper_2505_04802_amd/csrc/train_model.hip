@@ -819,7 +819,7 @@ static int head_bwd_impl(reslim_ctx *c, const char *fn, const float *x, const fl
     int co = C > 8 ? 16 : C > 4 ? 8 : 4;
     while (co > 4 && residual_wgrad_lds_floats(C, co, a.cwh, a.cww) * sizeof(float) > kResGradLds) co /= 2;
     const size_t lds = residual_wgrad_lds_floats(C, co, a.cwh, a.cww) * sizeof(float);
-    if (lds > kResGradLds)
+    if (lds > kResGradLds || C > 64)                      // 64: the kernel's table of input variable indices
       return set_error(c, RESLIM_ESHAPE, std::string(fn) + ": the residual-path gradient's arrays do not fit in LDS (scale too small or too many variables)");
     const double win = static_cast<double>(a.cwh) * a.cww * a.nbx * a.nby * c->T * batch;   // coarse-window pixels over all blocks
     const double res_flop = 2.0 * (12.0 * fine + 9.0 * (C + 2.0) * C * win);
