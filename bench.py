@@ -151,7 +151,12 @@ def train_step(B, torch, np, model, cfg, w, x_host, K, verbose):
                tflops=round(a["flop"] / (a["ms"] * 1e-3) / 1e12, 2) if a["flop"] and a["ms"] > 0 else None,
                gbs=round(a["bytes"] / (a["ms"] * 1e-3) / 1e9, 1) if a["ms"] > 0 else None) for n, a in agg.items()]
     ks.sort(key=lambda k: -k["ms"])
-    gflop, aflop, hflop = B.reslim_flop_counts(model.ctx, cfg.batch)
+    # the training forward runs every block on every token (the inference forward's counts do not apply)
+    D, Rm = cfg.embed_dim, cfg.embed_dim * cfg.mlp_ratio
+    gflop = 2.0 * cfg.batch * model.n_h * D * (4.0 * D + 2.0 * Rm) * cfg.depth
+    tiles = B.tiles_partition(cfg.Hp, cfg.Wp, cfg.tiles_y, cfg.tiles_x, cfg.halo)[0]
+    aflop = 4.0 * sum(float(t["n_tok"]) ** 2 for t in tiles) * D * cfg.depth * cfg.batch
+    hflop = 2.0 * cfg.batch * cfg.n_tokens * D * cfg.out_vars * (cfg.patch * cfg.scale) ** 2
     flop = 3.0 * (gflop + hflop) + 3.5 * aflop          # forward + input and weight gradients; attention gradient 2.5 x forward
     if verbose:
         for k in ks:
@@ -300,11 +305,17 @@ def measure(B, torch, cfg, w, x_host, K, W, verbose, want_train, note, want_step
     B.reslim_profile_enable(model.ctx, 0)
     agg = {}
     for name, ms, flop, nbytes in recs:
-        a = agg.setdefault(name, dict(calls=0, ms=0.0, flop=flop, bytes=nbytes))
+        a = agg.setdefault(name, dict(calls=0, ms=0.0, flop=0.0, bytes=0.0))
         a["calls"] += 1
         a["ms"] += ms
+        a["flop"] += flop
+        a["bytes"] += nbytes
     kernels = []
     for name, a in agg.items():
+        # per launch, averaged over the launches of that name (the last block's are smaller: it runs
+        # its projection and MLP on the rows the tiles own)
+        a["flop"] /= a["calls"]
+        a["bytes"] /= a["calls"]
         avg = a["ms"] / a["calls"]
         tfl = a["flop"] / (avg * 1e-3) / 1e12 if a["flop"] else None
         gbs = a["bytes"] / (avg * 1e-3) / 1e9

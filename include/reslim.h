@@ -344,13 +344,18 @@ int reslim_head_fwd(reslim_ctx *ctx, const float *x, const float *tokens, float 
                     int32_t batch, void *workspace, size_t ws_bytes, void *hip_stream);
 
 /* The whole forward: embed, `depth` blocks, head.  Coarse multi-variable grid in,
- * fine grid out. */
+ * fine grid out.  In bf16 mode with halo tokens the last block keeps only what
+ * the head reads: its attention computes the queries their tiles own (halo
+ * tokens remain keys and values), and its projection and MLP run on those rows
+ * alone; per kept row the arithmetic is that of reslim_block_fwd, so y equals
+ * the chained entry points' bit for bit. */
 int reslim_forward(reslim_ctx *ctx, const float *x, float *y, int32_t batch,
                    void *workspace, size_t ws_bytes, void *hip_stream);
 
-/* Algorithmic work of one forward for `batch` samples, for reporting: flop of
- * the block GEMMs, of tile attention (4*n_t^2*D per tile, block and sample) and
- * of the head GEMM.  Any pointer may be NULL. */
+/* Work of one reslim_forward for `batch` samples, for reporting: flop of the
+ * block GEMMs, of tile attention (4*queries*n_t*D per tile, block and sample;
+ * queries = n_t except in a last block that keeps the owned rows only) and of
+ * the head GEMM.  Any pointer may be NULL. */
 int reslim_flop_counts(const reslim_ctx *ctx, int32_t batch, double *gemm_flop,
                        double *attn_flop, double *head_flop);
 

@@ -56,7 +56,10 @@ namespace reslim {
 // registers with 8-byte stores, one query row per lane (no staging, no extra
 // barrier).  Measured on MI355X (c1, dh = 64): 64-key blocks with three waves per
 // SIMD (156 VGPRs) beat 128-key blocks with two (0.097 vs 0.102 ms per launch).
-template <int DH, int BKV, bool QS, int MINW = 2>
+// ST: stitched output -- a query that its tile owns writes its patch's row of a [batch, N, D]
+// output, halo queries write nothing, and units or waves without an owned query are skipped (they
+// still take part in the loads and barriers of their work-group).
+template <int DH, int BKV, bool QS, int MINW = 2, bool ST = false>
 __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArgs a) {
   constexpr int BQ = 128;
   constexpr int ROWB = DH * 2;            // bytes per K/V row in LDS
@@ -81,7 +84,15 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
   };
 
   // ---- work units (all of this is uniform over the work-group)
-  struct Unit { int n_t, q0, nkb; const bf16_t *base; bf16_t *out; float *lse; };
+  struct Unit { int n_t, q0, nkb, tile; const bf16_t *base; bf16_t *out; float *lse; };
+  // stitched output: first and last query of a tile that the tile owns (its tokens are row-major
+  // over the haloed box)
+  auto owned_range = [&](int tile, int &lo, int &up) {
+    const tile_desc &td = a.tiles[tile];
+    const int bw = td.X1 - td.X0;
+    lo = (td.y0 - td.Y0) * bw + (td.x0 - td.X0);
+    up = (td.y1 - 1 - td.Y0) * bw + (td.x1 - 1 - td.X0);
+  };
   auto decode = [&](int vb, Unit &u) -> int {      // first non-empty unit at or after vb (stride G), or >= total
     while (vb < a.total) {
       const int logical = xcd_remap_attn(vb, a.total);
@@ -92,14 +103,21 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
       const int tile = rest % a.T;
       const int b = rest / a.T;
       const int n_t = a.tiles[tile].n_tok;
-      if (qb * BQ < n_t) {
+      bool wanted = qb * BQ < n_t;
+      if constexpr (ST) {
+        int lo, up;
+        owned_range(tile, lo, up);
+        wanted = wanted && qb * BQ <= up && qb * BQ + BQ - 1 >= lo;
+      }
+      if (wanted) {
         const size_t row0 = static_cast<size_t>(b) * a.n_h + a.tiles[tile].tok_off;
         u.n_t = n_t;
+        u.tile = tile;
         u.q0 = qb * BQ;
         u.nkb = (n_t + BKV - 1) / BKV;
         u.base = static_cast<const bf16_t *>(a.qkv) + row0 * ld + head * DH;
-        u.out = static_cast<bf16_t *>(a.out) + row0 * a.D + head * DH;
-        u.lse = a.lse ? a.lse + (static_cast<size_t>(b) * a.heads + head) * a.n_h + a.tiles[tile].tok_off : nullptr;
+        u.out = static_cast<bf16_t *>(a.out) + (ST ? static_cast<size_t>(b) * a.N : row0) * a.D + head * DH;
+        u.lse = (ST || !a.lse) ? nullptr : a.lse + (static_cast<size_t>(b) * a.heads + head) * a.n_h + a.tiles[tile].tok_off;
         return vb;
       }
       vb += G;
@@ -109,6 +127,17 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
   Unit cur, nxt;
   int vb = decode(blockIdx.x, cur);
   if (vb >= a.total) return;
+  // stitched output: a wave whose 32 queries are all halo copies does no arithmetic
+  bool wave_owns = true;
+  auto set_wave_owns = [&]() {
+    if constexpr (ST) {
+      int lo, up;
+      owned_range(cur.tile, lo, up);
+      const int wq0 = cur.q0 + wave * 32;
+      wave_owns = wq0 <= up && wq0 + 31 >= lo;
+    }
+  };
+  set_wave_owns();
   vb = decode(vb + G, nxt);
   bool has_next = vb < a.total;
 
@@ -211,7 +240,7 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
     else if (has_next) issue(nxt, 0, (g + 1) & 1);
     const unsigned char *st = smem + (g & 1) * STAGE;
     const int kv0 = kb * BKV;
-    const bool active = cur.q0 + wave * 32 < cur.n_t;   // wave-uniform
+    const bool active = cur.q0 + wave * 32 < cur.n_t && wave_owns;   // wave-uniform
 
     f32x16 s[NKT];
     if (active) {
@@ -456,6 +485,15 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
 
     // ---- end of a unit: normalise and store this lane's query row, then move on
     const int qrow = cur.q0 + wave * 32 + l32;
+    int orow = qrow;
+    bool keep = true;
+    if constexpr (ST) {                    // the query's patch, if this tile owns it
+      const tile_desc &td = a.tiles[cur.tile];
+      const int bw = td.X1 - td.X0;
+      const int yy = td.Y0 + qrow / bw, xx = td.X0 + qrow % bw;
+      keep = yy >= td.y0 && yy < td.y1 && xx >= td.x0 && xx < td.x1;
+      orow = yy * a.Wp + xx;
+    }
     if (active && qrow < cur.n_t) {
       // lanes l and l + 32 hold the two key halves of query l: full sum = own + partner
       unsigned l_lo, l_up;
@@ -463,21 +501,24 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
       const float ltot = __builtin_bit_cast(float, l_lo) + __builtin_bit_cast(float, l_up);
       const float inv = 1.0f / ltot;
       // log-sum-exp of the logits (kept for the gradient): reference + log of the sum
-      if (cur.lse && hi == 0) cur.lse[qrow] = (__builtin_amdgcn_logf(ltot) - minit[0] * c) * 0.69314718055994531f;
-      bf16_t *op = cur.out + static_cast<size_t>(qrow) * a.D + hi * 4;
+      if (!ST && cur.lse && hi == 0) cur.lse[qrow] = (__builtin_amdgcn_logf(ltot) - minit[0] * c) * 0.69314718055994531f;
+      bf16_t *op = cur.out + static_cast<size_t>(orow) * a.D + hi * 4;
+      if (keep) {
 #pragma unroll
-      for (int d = 0; d < NDT; ++d)
+        for (int d = 0; d < NDT; ++d)
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          // registers 4*r4 .. 4*r4+3 hold features 32d + 8*r4 + 4*hi + (0..3) of query l32
-          bf16x4 tmp;
+          for (int r4 = 0; r4 < 4; ++r4) {
+            // registers 4*r4 .. 4*r4+3 hold features 32d + 8*r4 + 4*hi + (0..3) of query l32
+            bf16x4 tmp;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) tmp[e] = static_cast<__bf16>(o[d][4 * r4 + e] * inv);
-          *reinterpret_cast<u32x2 *>(op + d * 32 + r4 * 8) = __builtin_bit_cast(u32x2, tmp);
-        }
+            for (int e = 0; e < 4; ++e) tmp[e] = static_cast<__bf16>(o[d][4 * r4 + e] * inv);
+            *reinterpret_cast<u32x2 *>(op + d * 32 + r4 * 8) = __builtin_bit_cast(u32x2, tmp);
+          }
+      }
     }
     if (!has_next) break;
     cur = nxt;
+    set_wave_owns();
     vb = decode(vb + G, nxt);
     has_next = vb < a.total;
     kb = 0;
@@ -569,8 +610,19 @@ SeqGeom ctx_geom(const reslim_ctx *c) {
   return g;
 }
 
+template <int DH, int BKV, int MINW>
+static void launch_bf16_variant(const AttnArgs &a, bool q_prescaled, bool stitched, int grid, hipStream_t st) {
+  if (stitched) {
+    if (q_prescaled) tiles_attention_bf16_kernel<DH, BKV, true, MINW, true><<<dim3(grid), dim3(256), 0, st>>>(a);
+    else tiles_attention_bf16_kernel<DH, BKV, false, MINW, true><<<dim3(grid), dim3(256), 0, st>>>(a);
+  } else {
+    if (q_prescaled) tiles_attention_bf16_kernel<DH, BKV, true, MINW, false><<<dim3(grid), dim3(256), 0, st>>>(a);
+    else tiles_attention_bf16_kernel<DH, BKV, false, MINW, false><<<dim3(grid), dim3(256), 0, st>>>(a);
+  }
+}
+
 hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *out, int batch, bool q_prescaled,
-                                  hipStream_t st, float *lse, const SeqGeom *geom) {
+                                  hipStream_t st, float *lse, const SeqGeom *geom, bool stitched) {
   const SeqGeom own = geom ? *geom : ctx_geom(c);
   const SeqGeom &sg = own;
   AttnArgs a;
@@ -583,6 +635,13 @@ hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *ou
   a.D = c->cfg.embed_dim;
   a.n_h = sg.n_h;
   a.scale_log2 = 1.4426950408889634f / sqrtf(static_cast<float>(c->dh));
+  a.Wp = 0;
+  a.N = 0;
+  if (stitched) {                          // the context's own tiling, bf16 kernel, no log-sum-exp rows
+    if (geom || lse || c->cfg.dtype != RESLIM_BF16) return hipErrorInvalidValue;
+    a.Wp = c->Wp;
+    a.N = c->N;
+  }
   if (c->cfg.dtype == RESLIM_BF16) {
     a.QB = (sg.max_n_tok + 127) / 128;
     const int64_t total = static_cast<int64_t>(batch) * sg.T * a.heads * a.QB;
@@ -592,20 +651,13 @@ hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *ou
     if (g_attn_cus <= 0) return hipErrorInvalidValue;
     const int pg2 = a.total < 2 * g_attn_cus ? a.total : 2 * g_attn_cus;   // persistent grids
     const int pg3 = a.total < 3 * g_attn_cus ? a.total : 3 * g_attn_cus;
-    if (c->dh == 64 && g_attn_variant == 0) {
-      if (q_prescaled) tiles_attention_bf16_kernel<64, 64, true, 3><<<dim3(pg3), dim3(256), 0, st>>>(a);
-      else tiles_attention_bf16_kernel<64, 64, false, 3><<<dim3(pg3), dim3(256), 0, st>>>(a);
-    } else if (c->dh == 64) {
-      if (q_prescaled) tiles_attention_bf16_kernel<64, 128, true, 2><<<dim3(pg2), dim3(256), 0, st>>>(a);
-      else tiles_attention_bf16_kernel<64, 128, false, 2><<<dim3(pg2), dim3(256), 0, st>>>(a);
-    } else if (c->dh == 128) {
-      if (q_prescaled) tiles_attention_bf16_kernel<128, 64, true, 2><<<dim3(pg2), dim3(256), 0, st>>>(a);
-      else tiles_attention_bf16_kernel<128, 64, false, 2><<<dim3(pg2), dim3(256), 0, st>>>(a);
-    } else if (c->dh == 256) {
+    if (c->dh == 64 && g_attn_variant == 0) launch_bf16_variant<64, 64, 3>(a, q_prescaled, stitched, pg3, st);
+    else if (c->dh == 64) launch_bf16_variant<64, 128, 2>(a, q_prescaled, stitched, pg2, st);
+    else if (c->dh == 128) launch_bf16_variant<128, 64, 2>(a, q_prescaled, stitched, pg2, st);
+    else if (c->dh == 256) {
       // 128 output-accumulator and 64 query-fragment registers per lane: one work-group per CU
       const int pg1 = a.total < g_attn_cus ? a.total : g_attn_cus;
-      if (q_prescaled) tiles_attention_bf16_kernel<256, 32, true, 1><<<dim3(pg1), dim3(256), 0, st>>>(a);
-      else tiles_attention_bf16_kernel<256, 32, false, 1><<<dim3(pg1), dim3(256), 0, st>>>(a);
+      launch_bf16_variant<256, 32, 1>(a, q_prescaled, stitched, pg1, st);
     } else {
       return hipErrorInvalidValue;
     }

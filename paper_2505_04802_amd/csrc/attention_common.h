@@ -21,6 +21,11 @@ struct AttnArgs {
   int64_t n_h;
   float scale_log2;   // log2(e) / sqrt(dh)
   float *lse;         // optional [batch, heads, n_h]: natural log of each query's softmax denominator
+  // Stitched output (bf16 kernel only): with Wp > 0 a query that its tile owns writes row
+  // b * N + y * Wp + x of `out` (its patch), halo queries write nothing, and units or waves
+  // without an owned query do no arithmetic.  Wp == 0: tile-major rows as usual.
+  int Wp;
+  int64_t N;
 };
 
 __device__ __forceinline__ int xcd_remap_attn(int pid, int total) {

@@ -120,8 +120,13 @@ struct Workspace {
   float *X;        // [M, D] residual stream (forward only)
   void *A;         // act [M, D]
   void *big;       // act [M, max(3D, R)] or head staging
+  float *Xc;       // [batch * N, D] residual stream of the patches alone (last block of a forward with halos), else null
   size_t total;
 };
+// The last block of a whole forward feeds only the head, which reads the rows their tiles own: after
+// that block's attention (where halo tokens still serve as keys and values) every per-token step
+// runs on those rows only.  Same arithmetic per kept row, so the output does not change.
+bool last_block_on_patches(const reslim_ctx *c);
 Workspace plan_workspace(const reslim_ctx *c, int batch, void *base);
 // one transformer block on X [batch * geom.n_h, D] in place (geom == nullptr: the context's tiles)
 int block_impl(reslim_ctx *c, const char *fn, int layer, float *X, int batch, const Workspace &w, hipStream_t st,
@@ -141,10 +146,14 @@ enum Epilogue {
   EPI_BIAS_RES_F32 = 8    // out(f32)  = res[m, n] + acc + bias                       (skip connection from another buffer)
 };
 // C[M, N] (+)= A[M, K] * W[N, K]^T ; A, W act type (bf16 -> MFMA path, float -> fp32 path)
+// Row map for the skip input of EPI_BIAS_RES_F32 (bf16 path): output row b*rows_out + r adds row
+// b*rows_in + map[r] of aux (e.g. the tile-major row that holds patch r).
+struct ResRowMap { const int32_t *map; int rows_out; int64_t rows_in; };
 hipError_t launch_gemm(int dtype, Epilogue epi, const void *A, const void *W, const float *bias,
                        void *out, int ldo, const float *tab, int tab_rows, int M, int N, int K,
-                       hipStream_t st, float qscale = 1.0f, int qcols = 0, const void *aux = nullptr, void *out2 = nullptr);
-// aux: EPI_BIAS_RES_F32: float [M, ldo] skip input.  out2: EPI_BIAS_ACT_GELU2: act [M, ldo].
+                       hipStream_t st, float qscale = 1.0f, int qcols = 0, const void *aux = nullptr, void *out2 = nullptr,
+                       const ResRowMap *res_map = nullptr);
+// aux: EPI_BIAS_RES_F32: float skip input, [M, ldo] or the rows res_map names.  out2: EPI_BIAS_ACT_GELU2: act [M, ldo].
 hipError_t gemm_init();
 
 hipError_t launch_layernorm(int dtype, const float *x, const int32_t *row_src, int rows_per_sample_out,
@@ -154,9 +163,11 @@ hipError_t launch_gather_rows(const float *z, const int32_t *gather, float *X, i
                               int N, int D, hipStream_t st);
 hipError_t launch_embed_agg(const reslim_ctx *c, const float *x, void *o, int batch, hipStream_t st);
 // q_prescaled: q already carries the factor log2(e)/sqrt(dh) (bf16 path only)
+// stitched: out is [batch, N, D] in patch order, written by the owning tile's queries only (bf16
+// path, the context's own tiling, no lse)
 hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *out, int batch, bool q_prescaled,
                                   hipStream_t st, float *lse = nullptr,
-                                  const SeqGeom *geom = nullptr);
+                                  const SeqGeom *geom = nullptr, bool stitched = false);
 bool attention_accepts_prescaled_q();
 // gradient of tile attention: d_qkv from qkv, the forward's out and lse, and d_out; ws as sized below
 hipError_t launch_tiles_attention_bwd(const reslim_ctx *c, const void *qkv, const void *out, const float *lse,

@@ -22,13 +22,19 @@ Workspace plan_workspace(const reslim_ctx *c, int batch, void *base) {
   big_b = std::max(big_b, Mi * D * sizeof(float));
   big_b = std::max(big_b, Mi * static_cast<size_t>(c->head_out) * sizeof(float));
   big_b = align256(big_b);
+  const size_t xc_b = last_block_on_patches(c) ? align256(Mi * D * sizeof(float)) : 0;
   Workspace w;
   unsigned char *p = static_cast<unsigned char *>(base);
   w.X = reinterpret_cast<float *>(p);
   w.A = p + x_b;
   w.big = p + x_b + a_b;
-  w.total = x_b + a_b + big_b;
+  w.Xc = xc_b ? reinterpret_cast<float *>(p + x_b + a_b + big_b) : nullptr;
+  w.total = x_b + a_b + big_b + xc_b;
   return w;
+}
+
+bool last_block_on_patches(const reslim_ctx *c) {
+  return c->cfg.dtype == RESLIM_BF16 && c->cfg.depth >= 1 && c->n_h > c->N;
 }
 
 
@@ -102,13 +108,43 @@ int block_impl(reslim_ctx *c, const char *fn, int layer, float *X, int batch, co
   return RESLIM_OK;
 }
 
-static int head_impl(reslim_ctx *c, const char *fn, const float *x, const float *tokens, float *y, int batch, const Workspace &w, hipStream_t st) {
+// The last block of a whole forward, when some tokens are halo copies: X is read (tile-major), the
+// block's output for the patches goes to w.Xc [batch * N, D] in patch order.
+static int last_block_impl(reslim_ctx *c, const char *fn, const float *X, int batch, const Workspace &w, hipStream_t st) {
+  const int D = c->cfg.embed_dim, R = c->R, dt = c->cfg.dtype;
+  const SeqGeom sg = ctx_geom(c);
+  const int M = static_cast<int>(batch * sg.n_h), Mi = batch * c->N;
+  const LayerWeights &lw = c->layers[c->cfg.depth - 1];
+  const double es = static_cast<double>(act_size(c)), dM = M, dMi = Mi, dD = D, dR = R;
+  RESLIM_LAUNCH("layernorm", 0, dM * dD * (4.0 + es), launch_layernorm(dt, X, nullptr, 0, 0, lw.ln1_g, lw.ln1_b, w.A, M, D, st));
+  const bool qs = attention_accepts_prescaled_q();
+  const float qscale = 1.4426950408889634f / sqrtf(static_cast<float>(c->dh));
+  RESLIM_LAUNCH("gemm_qkv", 6.0 * dM * dD * dD, dM * dD * es + 3.0 * dD * dD * es + 3.0 * dM * dD * es,
+                launch_gemm(dt, qs ? EPI_BIAS_QSCALE_ACT : EPI_BIAS_ACT, w.A, lw.w_qkv, lw.b_qkv, w.big, 3 * D, nullptr, 0, M,
+                            3 * D, D, st, qscale, D));
+  // queries: the owned tokens (about); keys and values: the whole haloed tile
+  RESLIM_LAUNCH("tiles_attention", 4.0 * sg.pairs * dD * batch * (dMi / dM), 3.0 * dM * dD * es + dMi * dD * es,
+                launch_tiles_attention(c, w.big, w.A, batch, qs, st, nullptr, nullptr, true));
+  const ResRowMap skip = {c->d_interior_src, c->N, sg.n_h};
+  RESLIM_LAUNCH("gemm_proj", 2.0 * dMi * dD * dD, dMi * dD * es + dD * dD * es + 8.0 * dMi * dD,
+                launch_gemm(dt, EPI_BIAS_RES_F32, w.A, lw.w_proj, lw.b_proj, w.Xc, D, nullptr, 0, Mi, D, D, st, 1.0f, 0, X, nullptr, &skip));
+  RESLIM_LAUNCH("layernorm", 0, dMi * dD * (4.0 + es), launch_layernorm(dt, w.Xc, nullptr, 0, 0, lw.ln2_g, lw.ln2_b, w.A, Mi, D, st));
+  RESLIM_LAUNCH("gemm_fc1", 2.0 * dMi * dD * dR, dMi * dD * es + dD * dR * es + dMi * dR * es,
+                launch_gemm(dt, EPI_BIAS_GELU_ACT, w.A, lw.w_fc1, lw.b_fc1, w.big, R, nullptr, 0, Mi, R, D, st));
+  RESLIM_LAUNCH("gemm_fc2", 2.0 * dMi * dD * dR, dMi * dR * es + dD * dR * es + 8.0 * dMi * dD,
+                launch_gemm(dt, EPI_BIAS_RESADD_F32, w.big, lw.w_fc2, lw.b_fc2, w.Xc, D, nullptr, 0, Mi, D, R, st));
+  return RESLIM_OK;
+}
+
+// tokens: tile-major [batch * n_h, D], or with `stitched` the patches' rows [batch * N, D] in patch order
+static int head_impl(reslim_ctx *c, const char *fn, const float *x, const float *tokens, float *y, int batch, const Workspace &w, hipStream_t st,
+                     bool stitched = false) {
   const int D = c->cfg.embed_dim, dt = c->cfg.dtype;
   const int Mi = batch * c->N;
   const double es = static_cast<double>(act_size(c)), dMi = Mi, dD = D, dO = c->head_out;
   const double fine = static_cast<double>(batch) * c->cfg.out_vars * c->cfg.H * c->cfg.W * c->cfg.scale * c->cfg.scale;
   RESLIM_LAUNCH("layernorm_final", 0, dMi * dD * (4.0 + es),
-                launch_layernorm(dt, tokens, c->d_interior_src, c->N, c->n_h, c->d_lnf_g, c->d_lnf_b, w.A, Mi, D, st));
+                launch_layernorm(dt, tokens, stitched ? nullptr : c->d_interior_src, c->N, c->n_h, c->d_lnf_g, c->d_lnf_b, w.A, Mi, D, st));
   RESLIM_LAUNCH("gemm_head", 2.0 * dMi * dD * dO, dMi * dD * es + dD * dO * es + 4.0 * dMi * dO,
                 launch_gemm(dt, EPI_BIAS_F32, w.A, c->d_w_head, c->d_b_head, w.big, c->head_out, nullptr, 0, Mi, c->head_out, D, st));
   RESLIM_LAUNCH("residual_unpatchify", 0,
@@ -180,12 +216,21 @@ extern "C" int reslim_workspace_bytes(const reslim_ctx *ctx, int32_t batch, size
 extern "C" int reslim_flop_counts(const reslim_ctx *ctx, int32_t batch, double *gemm_flop, double *attn_flop, double *head_flop) {
   if (!ctx || batch < 1) return RESLIM_EINVAL;
   const double D = ctx->cfg.embed_dim, L = ctx->cfg.depth, B = batch;
-  const double M = B * static_cast<double>(ctx->n_h);
-  if (gemm_flop) *gemm_flop = 2.0 * M * D * (3.0 * D + D + 2.0 * ctx->R) * L;
+  const double M = B * static_cast<double>(ctx->n_h), Mi = B * static_cast<double>(ctx->N);
+  // what reslim_forward executes: with halo tokens its last block projects and runs the MLP on the
+  // patches' rows only, and only the queries their tiles own attend
+  const bool stitch = last_block_on_patches(ctx);
+  if (gemm_flop) {
+    *gemm_flop = 2.0 * M * D * (3.0 * D + D + 2.0 * ctx->R) * L;
+    if (stitch) *gemm_flop -= 2.0 * (M - Mi) * D * (D + 2.0 * ctx->R);
+  }
   if (attn_flop) {
-    double s = 0;
-    for (const tile_desc &t : ctx->tiles) s += static_cast<double>(t.n_tok) * t.n_tok;
-    *attn_flop = 4.0 * s * D * L * B;
+    double s = 0, own = 0;
+    for (const tile_desc &t : ctx->tiles) {
+      s += static_cast<double>(t.n_tok) * t.n_tok;
+      own += static_cast<double>(t.y1 - t.y0) * (t.x1 - t.x0) * t.n_tok;
+    }
+    *attn_flop = 4.0 * D * B * (stitch ? s * (L - 1) + own : s * L);
   }
   if (head_flop) *head_flop = 2.0 * B * ctx->N * D * ctx->head_out;
   return RESLIM_OK;
@@ -248,7 +293,10 @@ extern "C" int reslim_forward(reslim_ctx *c, const float *x, float *y, int32_t b
   const Workspace w = plan_workspace(c, batch, workspace);
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   if ((rc = embed_impl(c, fn, x, w.X, batch, w, st)) != RESLIM_OK) return rc;
-  for (int l = 0; l < c->cfg.depth; ++l)
+  const bool stitch = last_block_on_patches(c);
+  for (int l = 0; l < c->cfg.depth - (stitch ? 1 : 0); ++l)
     if ((rc = block_impl(c, fn, l, w.X, batch, w, st)) != RESLIM_OK) return rc;
-  return head_impl(c, fn, x, w.X, y, batch, w, st);
+  if (!stitch) return head_impl(c, fn, x, w.X, y, batch, w, st);
+  if ((rc = last_block_impl(c, fn, w.X, batch, w, st)) != RESLIM_OK) return rc;
+  return head_impl(c, fn, x, w.Xc, y, batch, w, st, true);
 }

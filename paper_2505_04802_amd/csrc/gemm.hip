@@ -32,7 +32,10 @@ struct GemmArgs {
   float qscale;   // EPI_BIAS_QSCALE_ACT: factor applied to output columns n < qcols
   int qcols;
   int col_fast;            // one-tile-per-work-group kernel: tile order inside a band
-  const void *aux;         // EPI_BIAS_RES_F32: skip input (fp32), layout of out
+  const void *aux;         // EPI_BIAS_RES_F32: skip input (fp32), layout of out unless res_map is set
+  const int32_t *res_map;  // EPI_BIAS_RES_F32, optional: output row b*res_out + r reads skip row b*res_in + res_map[r]
+  int res_out;
+  int64_t res_in;
   void *out2;              // EPI_BIAS_ACT_GELU2: second output (act), layout of out
 };
 
@@ -174,7 +177,12 @@ __device__ __forceinline__ void epilogue_wave_impl(const GemmArgs &g, const f32x
         const size_t row = static_cast<size_t>(mc) * g.ldo;
         float *orow = static_cast<float *>(g.out) + row;
         // row the skip connection is read from: the output itself (in place) or another buffer
-        const float *rrow = (EPI == EPI_BIAS_RES_F32) ? static_cast<const float *>(g.aux) + row : orow;
+        const float *rrow = orow;
+        if constexpr (EPI == EPI_BIAS_RES_F32) {
+          const size_t src = g.res_map ? static_cast<size_t>(mc / g.res_out) * g.res_in + g.res_map[mc % g.res_out]
+                                       : static_cast<size_t>(mc);
+          rrow = static_cast<const float *>(g.aux) + src * g.ldo;
+        }
         const float *trow = (EPI == EPI_BIAS_TAB_F32) ? g.tab + static_cast<size_t>(mc % g.tab_rows) * g.N : nullptr;
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj) {
@@ -520,7 +528,7 @@ hipError_t gemm_init() {
 
 hipError_t launch_gemm(int dtype, Epilogue epi, const void *A, const void *W, const float *bias,
                        void *out, int ldo, const float *tab, int tab_rows, int M, int N, int K,
-                       hipStream_t st, float qscale, int qcols, const void *aux, void *out2) {
+                       hipStream_t st, float qscale, int qcols, const void *aux, void *out2, const ResRowMap *res_map) {
   if (M <= 0 || N <= 0 || K <= 0) return hipErrorInvalidValue;
   GemmArgs g;
   g.A = A; g.W = W; g.bias = bias; g.out = out; g.tab = tab;
@@ -528,6 +536,11 @@ hipError_t launch_gemm(int dtype, Epilogue epi, const void *A, const void *W, co
   g.M = M; g.N = N; g.K = K; g.grid_m = g.grid_n = 0; g.col_fast = g_col_fast;
   g.qscale = qscale; g.qcols = qcols; g.aux = aux; g.out2 = out2;
   if (epi == EPI_BIAS_RES_F32 && !aux) return hipErrorInvalidValue;
+  g.res_map = nullptr; g.res_out = 1; g.res_in = 1;
+  if (res_map) {   // bf16 path only: the fp32 kernel reads the skip input at the output's own index
+    if (epi != EPI_BIAS_RES_F32 || dtype != RESLIM_BF16 || !res_map->map || res_map->rows_out < 1) return hipErrorInvalidValue;
+    g.res_map = res_map->map; g.res_out = res_map->rows_out; g.res_in = res_map->rows_in;
+  }
   if (epi == EPI_BIAS_ACT_GELU2 && !out2) return hipErrorInvalidValue;
   if (dtype == RESLIM_BF16) {
     if (K % 64 != 0) return hipErrorInvalidValue;   // slabs are 64 deep; create() enforces D % 64 == 0

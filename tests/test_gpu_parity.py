@@ -215,6 +215,25 @@ def test_stage_by_stage_parity(cfg):
         assert np.array_equal(y, y2)                 # same input, same bits
 
 
+@pytest.mark.parametrize("cfg", [SMALL_BF16, SMALL_BF16_DH128, SMALL_BF16_DH256, WL.CONFIGS["c1"]], ids=lambda c: c.name)
+def test_forward_equals_its_entry_points_chained(cfg):
+    """The whole forward runs its last block on the rows the tiles own (halo tokens serve that
+    block's attention as keys and values only); the entry points chained run every block on every
+    token.  Row by row the arithmetic is the same, so the outputs agree bit for bit."""
+    say(f"forward vs chained entry points {cfg.name}")
+    w = weights_for(cfg, std=0.1)
+    x = WL.make_fields(cfg)
+    with B.Reslim(cfg, w) as m:
+        assert m.n_h > cfg.Hp * cfg.Wp, "the case needs halo tokens"
+        xd = cuda(x)
+        tok = m.embed(xd)
+        for l in range(cfg.depth):
+            m.block(l, tok)
+        y_chain = m.head(xd, tok).cpu().numpy()
+        y = m.forward(xd).cpu().numpy()
+    assert np.array_equal(y, y_chain)
+
+
 def test_forward_c0_fp32():
     cfg = WL.CONFIGS["c0"]
     w, x = WL.make_weights(cfg), WL.make_fields(cfg)
