@@ -24,9 +24,6 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_FP32_VECTOR_TFLOPS = 157.3  # MI355X fp32 vector (packed); plain fp32 instructions reach half of it
 ALU_BOUND = ("embed_agg",)      # kernels whose time is plain fp32 vector arithmetic, not HBM or MFMA
-# fp32 vector arithmetic AND a stream of HBM bytes: quoted against whichever roof they are nearer to
-# (the residual path at C = 16 and scale 8 does 294 flop per 12 bytes)
-ALU_OR_HBM = ("residual_unpatchify",)
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see
 # profiles/), keyed by (workload, kernel label); None where not measured.
@@ -322,26 +319,21 @@ def measure(B, torch, cfg, w, x_host, K, W, verbose, want_train, note, want_step
         avg = a["ms"] / a["calls"]
         tfl = a["flop"] / (avg * 1e-3) / 1e12 if a["flop"] else None
         gbs = a["bytes"] / (avg * 1e-3) / 1e9
-        if name in ALU_OR_HBM:
-            alu_frac, hbm_frac = tfl / PEAK_FP32_VECTOR_TFLOPS, gbs / PEAK_HBM_GBS
-            bound, frac = ("alu", alu_frac) if alu_frac >= hbm_frac else ("hbm", hbm_frac)
-        elif name in ALU_BOUND:
-            bound, frac = "alu", tfl / PEAK_FP32_VECTOR_TFLOPS
-        elif tfl:
-            bound, frac = "mfma", tfl / PEAK_BF16_TFLOPS
-        else:
-            bound, frac = "hbm", gbs / PEAK_HBM_GBS
         kernels.append(dict(kernel=name, launches_per_step=a["calls"] // K, avg_ms=round(avg, 5),
                             ms_per_step=round(a["ms"] / K, 5),
-                            tflops=round(tfl, 2) if tfl else None, gbs=round(gbs, 1), bound=bound, frac=round(frac, 4)))
+                            tflops=round(tfl, 2) if tfl else None, gbs=round(gbs, 1),
+                            bound="alu" if name in ALU_BOUND else "mfma" if tfl else "hbm",
+                            frac=round(tfl / (PEAK_FP32_VECTOR_TFLOPS if name in ALU_BOUND else PEAK_BF16_TFLOPS), 4) if tfl
+                            else round(gbs / PEAK_HBM_GBS, 4)))
     kernels.sort(key=lambda k: -k["ms_per_step"])
     dom = kernels[0]
     a = agg[dom["kernel"]]
     avg_s = a["ms"] / a["calls"] * 1e-3
-    if dom["bound"] in ("alu", "mfma"):
+    if a["flop"] > 0:
         achieved = a["flop"] / avg_s / 1e12
-        peak = PEAK_FP32_VECTOR_TFLOPS if dom["bound"] == "alu" else PEAK_BF16_TFLOPS
-        roof = dict(bound=dom["bound"], kernel=dom["kernel"], achieved=round(achieved, 2), peak=peak,
+        alu = dom["kernel"] in ALU_BOUND
+        peak = PEAK_FP32_VECTOR_TFLOPS if alu else PEAK_BF16_TFLOPS
+        roof = dict(bound="alu" if alu else "mfma", kernel=dom["kernel"], achieved=round(achieved, 2), peak=peak,
                     unit="TFLOP/s", frac=round(achieved / peak, 4),
                     traffic=MEASURED_TRAFFIC.get((cfg.name, dom["kernel"])), avg_launch_ms=round(avg_s * 1e3, 5),
                     flop_per_launch=a["flop"])

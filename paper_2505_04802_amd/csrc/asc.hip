@@ -370,8 +370,7 @@ extern "C" int reslim_asc_forward(reslim_ctx *c, const reslim_asc_plan *plan, co
   RESLIM_LAUNCH("gemm_head", 2.0 * dMi * dD * dO, dMi * dD * es + dD * dO * es + 4.0 * dMi * dO,
                 launch_gemm(dt, EPI_BIAS_F32, w.A, c->d_w_head, c->d_b_head, w.big, c->head_out, nullptr, 0, Mi, c->head_out, D, st));
   const double fine = static_cast<double>(batch) * c->cfg.out_vars * c->cfg.H * c->cfg.W * c->cfg.scale * c->cfg.scale;
-  // per fine value: a 3 x 3 convolution over the C upsampled variables (2 * 9 * C flop) and its share of the bilinear weights
-  RESLIM_LAUNCH("residual_unpatchify", fine * (18.0 * c->cfg.out_vars + 6.0),
+  RESLIM_LAUNCH("residual_unpatchify", 0,
                 4.0 * batch * c->cfg.out_vars * c->cfg.H * c->cfg.W + 4.0 * dMi * dO + 4.0 * fine,
                 launch_residual_unpatchify(c, x, w.big, 0, y, batch, st));
   return RESLIM_OK;
