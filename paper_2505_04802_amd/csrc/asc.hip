@@ -270,6 +270,7 @@ extern "C" int reslim_asc_plan_create(reslim_ctx *c, int32_t batch, const int32_
   pl->geom.n_h = n_leaves;
   pl->geom.max_n_tok = max_n;
   pl->geom.pairs = pairs;
+  pl->geom.pairs_owned = pairs;   // no stitched launches on compressed sequences
   *out = pl;
   return RESLIM_OK;
 }

@@ -606,7 +606,11 @@ SeqGeom ctx_geom(const reslim_ctx *c) {
   g.n_h = c->n_h;
   g.max_n_tok = c->max_n_tok;
   g.pairs = 0;
-  for (const tile_desc &t : c->tiles) g.pairs += static_cast<double>(t.n_tok) * t.n_tok;
+  g.pairs_owned = 0;
+  for (const tile_desc &t : c->tiles) {
+    g.pairs += static_cast<double>(t.n_tok) * t.n_tok;
+    g.pairs_owned += static_cast<double>(t.y1 - t.y0) * (t.x1 - t.x0) * t.n_tok;
+  }
   return g;
 }
 

@@ -112,6 +112,7 @@ struct SeqGeom {
   int64_t n_h;
   int max_n_tok;
   double pairs;                    // sum over entries of n_tok^2 (flop accounting)
+  double pairs_owned;              // sum of (owned tokens) * n_tok: the pairs of a stitched attention launch
 };
 SeqGeom ctx_geom(const reslim_ctx *c);
 

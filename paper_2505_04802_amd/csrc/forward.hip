@@ -122,8 +122,8 @@ static int last_block_impl(reslim_ctx *c, const char *fn, const float *X, int ba
   RESLIM_LAUNCH("gemm_qkv", 6.0 * dM * dD * dD, dM * dD * es + 3.0 * dD * dD * es + 3.0 * dM * dD * es,
                 launch_gemm(dt, qs ? EPI_BIAS_QSCALE_ACT : EPI_BIAS_ACT, w.A, lw.w_qkv, lw.b_qkv, w.big, 3 * D, nullptr, 0, M,
                             3 * D, D, st, qscale, D));
-  // queries: the owned tokens (about); keys and values: the whole haloed tile
-  RESLIM_LAUNCH("tiles_attention", 4.0 * sg.pairs * dD * batch * (dMi / dM), 3.0 * dM * dD * es + dMi * dD * es,
+  // queries: the owned tokens; keys and values: the whole haloed tile
+  RESLIM_LAUNCH("tiles_attention", 4.0 * sg.pairs_owned * dD * batch, 3.0 * dM * dD * es + dMi * dD * es,
                 launch_tiles_attention(c, w.big, w.A, batch, qs, st, nullptr, nullptr, true));
   const ResRowMap skip = {c->d_interior_src, c->N, sg.n_h};
   RESLIM_LAUNCH("gemm_proj", 2.0 * dMi * dD * dD, dMi * dD * es + dD * dD * es + 8.0 * dMi * dD,

@@ -234,6 +234,28 @@ def test_forward_equals_its_entry_points_chained(cfg):
     assert np.array_equal(y, y_chain)
 
 
+@pytest.mark.parametrize("cfg", [SMALL_BF16, SMALL_F32, WL.CONFIGS["c1"]], ids=lambda c: c.name)
+def test_flop_counts_are_the_sum_of_the_launch_records(cfg):
+    """reslim_flop_counts (the numerator of the bench line's TFLOP/s) against the per-launch
+    records of one forward: block GEMMs, tile attention and head GEMM each add up exactly."""
+    w = weights_for(cfg)
+    with B.Reslim(cfg, w) as m:
+        xd = cuda(WL.make_fields(cfg))
+        B.reslim_profile_enable(m.ctx, 256)
+        m.forward(xd)
+        torch.cuda.synchronize()
+        recs = B.reslim_profile_read(m.ctx)
+        B.reslim_profile_enable(m.ctx, 0)
+        gflop, aflop, hflop = B.reslim_flop_counts(m.ctx, cfg.batch)
+    by = {}
+    for name, _, flop, _ in recs:
+        by[name] = by.get(name, 0.0) + flop
+    assert len(recs) == 3 + 7 * cfg.depth + 3
+    assert np.isclose(by["gemm_qkv"] + by["gemm_proj"] + by["gemm_fc1"] + by["gemm_fc2"], gflop, rtol=1e-12)
+    assert np.isclose(by["tiles_attention"], aflop, rtol=1e-12)
+    assert np.isclose(by["gemm_head"], hflop, rtol=1e-12)
+
+
 def test_forward_c0_fp32():
     cfg = WL.CONFIGS["c0"]
     w, x = WL.make_weights(cfg), WL.make_fields(cfg)
