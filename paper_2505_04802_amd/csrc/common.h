@@ -130,9 +130,12 @@ struct Workspace {
 bool last_block_on_patches(const reslim_ctx *c);
 Workspace plan_workspace(const reslim_ctx *c, int batch, void *base);
 // one transformer block on X [batch * geom.n_h, D] in place (geom == nullptr: the context's tiles)
+// z_first: the embedding in patch order [batch * N, D] when X does not hold the stream yet (the
+// first block of a whole forward; bf16 path, the context's own tiles)
 int block_impl(reslim_ctx *c, const char *fn, int layer, float *X, int batch, const Workspace &w, hipStream_t st,
-               const SeqGeom *geom = nullptr);
-int embed_full_impl(reslim_ctx *c, const char *fn, const float *x, int batch, const Workspace &w, hipStream_t st);
+               const SeqGeom *geom = nullptr, const float *z_first = nullptr);
+int embed_full_impl(reslim_ctx *c, const char *fn, const float *x, int batch, const Workspace &w, hipStream_t st,
+                    float *dst = nullptr);
 
 // ---- kernels (host launchers; all enqueue on `st` and return hipError_t) ------
 enum Epilogue {

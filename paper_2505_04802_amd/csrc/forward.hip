@@ -54,8 +54,8 @@ int check_common(reslim_ctx *c, const char *fn, int batch, const void *ws, size_
   return RESLIM_OK;
 }
 
-// tokenisation + aggregation + position/resolution terms: w.big <- float [batch * N, D] in patch order
-int embed_full_impl(reslim_ctx *c, const char *fn, const float *x, int batch, const Workspace &w, hipStream_t st) {
+// tokenisation + aggregation + position/resolution terms: dst (w.big if null) <- float [batch * N, D] in patch order
+int embed_full_impl(reslim_ctx *c, const char *fn, const float *x, int batch, const Workspace &w, hipStream_t st, float *dst) {
   const int D = c->cfg.embed_dim, dt = c->cfg.dtype;
   const int Mi = batch * c->N;
   const double es = static_cast<double>(act_size(c)), dMi = Mi, dD = D;
@@ -65,7 +65,8 @@ int embed_full_impl(reslim_ctx *c, const char *fn, const float *x, int batch, co
                 4.0 * batch * c->cfg.in_vars * c->cfg.H * c->cfg.W + dMi * dD * es,
                 launch_embed_agg(c, x, w.A, batch, st));
   RESLIM_LAUNCH("gemm_agg_out", 2.0 * dMi * dD * dD, dMi * dD * es + dD * dD * es + 4.0 * c->N * dD + 4.0 * dMi * dD,
-                launch_gemm(dt, EPI_BIAS_TAB_F32, w.A, c->d_agg_wo, c->d_zero_bias, w.big, D, c->d_pos_res, c->N, Mi, D, D, st));
+                launch_gemm(dt, EPI_BIAS_TAB_F32, w.A, c->d_agg_wo, c->d_zero_bias, dst ? static_cast<void *>(dst) : w.big, D, c->d_pos_res, c->N,
+                            Mi, D, D, st));
   return RESLIM_OK;
 }
 
@@ -73,7 +74,7 @@ static int embed_impl(reslim_ctx *c, const char *fn, const float *x, float *toke
   const int D = c->cfg.embed_dim;
   const int Mi = batch * c->N;
   const double dMi = Mi, dD = D, dM = static_cast<double>(batch) * c->n_h;
-  const int rc = embed_full_impl(c, fn, x, batch, w, st);
+  const int rc = embed_full_impl(c, fn, x, batch, w, st, nullptr);
   if (rc != RESLIM_OK) return rc;
   RESLIM_LAUNCH("gather", 0, 4.0 * dMi * dD + 4.0 * dM * dD,
                 launch_gather_rows(static_cast<const float *>(w.big), c->d_gather, tokens, batch, c->n_h, c->N, D, st));
@@ -81,14 +82,21 @@ static int embed_impl(reslim_ctx *c, const char *fn, const float *x, float *toke
 }
 
 int block_impl(reslim_ctx *c, const char *fn, int layer, float *X, int batch, const Workspace &w, hipStream_t st,
-               const SeqGeom *geom) {
+               const SeqGeom *geom, const float *z_first) {
   const int D = c->cfg.embed_dim, R = c->R, dt = c->cfg.dtype;
   const SeqGeom sg = geom ? *geom : ctx_geom(c);
   const int M = static_cast<int>(batch * sg.n_h);
   const LayerWeights &lw = c->layers[layer];
   const double es = static_cast<double>(act_size(c)), dM = M, dD = D, dR = R;
   const double pairs = sg.pairs;
-  RESLIM_LAUNCH("layernorm", 0, dM * dD * (4.0 + es), launch_layernorm(dt, X, nullptr, 0, 0, lw.ln1_g, lw.ln1_b, w.A, M, D, st));
+  // z_first (first block of a whole forward): the stream is still the embedding in patch order;
+  // the tile-major rows, halo copies included, are read from it through the gather list here and
+  // by the projection's skip connection, which is what writes X for the first time
+  if (z_first)
+    RESLIM_LAUNCH("layernorm", 0, dM * dD * (4.0 + es),
+                  launch_layernorm(dt, z_first, c->d_gather, static_cast<int>(sg.n_h), c->N, lw.ln1_g, lw.ln1_b, w.A, M, D, st));
+  else
+    RESLIM_LAUNCH("layernorm", 0, dM * dD * (4.0 + es), launch_layernorm(dt, X, nullptr, 0, 0, lw.ln1_g, lw.ln1_b, w.A, M, D, st));
   // bf16 path: the QKV epilogue multiplies q by log2(e)/sqrt(dh) before its one
   // rounding to bf16, and the attention kernel then exponentiates in base 2 directly
   const bool qs = dt == RESLIM_BF16 && attention_accepts_prescaled_q();
@@ -98,8 +106,14 @@ int block_impl(reslim_ctx *c, const char *fn, int layer, float *X, int batch, co
                             3 * D, D, st, qscale, D));
   RESLIM_LAUNCH("tiles_attention", 4.0 * pairs * dD * batch, 4.0 * dM * dD * es,
                 launch_tiles_attention(c, w.big, w.A, batch, qs, st, nullptr, &sg));
-  RESLIM_LAUNCH("gemm_proj", 2.0 * dM * dD * dD, dM * dD * es + dD * dD * es + 8.0 * dM * dD,
-                launch_gemm(dt, EPI_BIAS_RESADD_F32, w.A, lw.w_proj, lw.b_proj, X, D, nullptr, 0, M, D, D, st));
+  if (z_first) {
+    const ResRowMap skip = {c->d_gather, static_cast<int>(sg.n_h), c->N};
+    RESLIM_LAUNCH("gemm_proj", 2.0 * dM * dD * dD, dM * dD * es + dD * dD * es + 8.0 * dM * dD,
+                  launch_gemm(dt, EPI_BIAS_RES_F32, w.A, lw.w_proj, lw.b_proj, X, D, nullptr, 0, M, D, D, st, 1.0f, 0, z_first, nullptr, &skip));
+  } else {
+    RESLIM_LAUNCH("gemm_proj", 2.0 * dM * dD * dD, dM * dD * es + dD * dD * es + 8.0 * dM * dD,
+                  launch_gemm(dt, EPI_BIAS_RESADD_F32, w.A, lw.w_proj, lw.b_proj, X, D, nullptr, 0, M, D, D, st));
+  }
   RESLIM_LAUNCH("layernorm", 0, dM * dD * (4.0 + es), launch_layernorm(dt, X, nullptr, 0, 0, lw.ln2_g, lw.ln2_b, w.A, M, D, st));
   RESLIM_LAUNCH("gemm_fc1", 2.0 * dM * dD * dR, dM * dD * es + dD * dR * es + dM * dR * es,
                 launch_gemm(dt, EPI_BIAS_GELU_ACT, w.A, lw.w_fc1, lw.b_fc1, w.big, R, nullptr, 0, M, R, D, st));
@@ -292,10 +306,16 @@ extern "C" int reslim_forward(reslim_ctx *c, const float *x, float *y, int32_t b
   if (rc != RESLIM_OK) return rc;
   const Workspace w = plan_workspace(c, batch, workspace);
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  if ((rc = embed_impl(c, fn, x, w.X, batch, w, st)) != RESLIM_OK) return rc;
   const bool stitch = last_block_on_patches(c);
+  // With halo tokens and at least two blocks the gather pass is folded into the first block: the
+  // embedding stays in patch order (in w.Xc, which only the last block needs again) and the first
+  // block reads its rows through the gather list.  Same values, same arithmetic per row.
+  const bool fold_gather = stitch && c->cfg.depth >= 2;
+  if (fold_gather) rc = embed_full_impl(c, fn, x, batch, w, st, w.Xc);
+  else rc = embed_impl(c, fn, x, w.X, batch, w, st);
+  if (rc != RESLIM_OK) return rc;
   for (int l = 0; l < c->cfg.depth - (stitch ? 1 : 0); ++l)
-    if ((rc = block_impl(c, fn, l, w.X, batch, w, st)) != RESLIM_OK) return rc;
+    if ((rc = block_impl(c, fn, l, w.X, batch, w, st, nullptr, l == 0 && fold_gather ? w.Xc : nullptr)) != RESLIM_OK) return rc;
   if (!stitch) return head_impl(c, fn, x, w.X, y, batch, w, st);
   if ((rc = last_block_impl(c, fn, w.X, batch, w, st)) != RESLIM_OK) return rc;
   return head_impl(c, fn, x, w.Xc, y, batch, w, st, true);

@@ -218,8 +218,10 @@ def test_stage_by_stage_parity(cfg):
 @pytest.mark.parametrize("cfg", [SMALL_BF16, SMALL_BF16_DH128, SMALL_BF16_DH256, WL.CONFIGS["c1"]], ids=lambda c: c.name)
 def test_forward_equals_its_entry_points_chained(cfg):
     """The whole forward runs its last block on the rows the tiles own (halo tokens serve that
-    block's attention as keys and values only); the entry points chained run every block on every
-    token.  Row by row the arithmetic is the same, so the outputs agree bit for bit."""
+    block's attention as keys and values only) and lets its first block read the embedding
+    through the gather list instead of a gathered copy; the entry points chained gather first and
+    run every block on every token.  Row by row the arithmetic is the same, so the outputs agree
+    bit for bit."""
     say(f"forward vs chained entry points {cfg.name}")
     w = weights_for(cfg, std=0.1)
     x = WL.make_fields(cfg)
@@ -250,7 +252,11 @@ def test_flop_counts_are_the_sum_of_the_launch_records(cfg):
     by = {}
     for name, _, flop, _ in recs:
         by[name] = by.get(name, 0.0) + flop
-    assert len(recs) == 3 + 7 * cfg.depth + 3
+    # embed (2 launches) + gather + 7 per block + head (3); the gather is folded into the first
+    # block when the forward keeps a patch-order stream for its last block (bf16, halo tokens, >= 2 blocks)
+    folded = cfg.dtype == 1 and cfg.depth >= 2 and m.n_h > cfg.Hp * cfg.Wp
+    assert len(recs) == 3 + 7 * cfg.depth + 3 - (1 if folded else 0)
+    assert ("gather" in by) == (not folded)
     assert np.isclose(by["gemm_qkv"] + by["gemm_proj"] + by["gemm_fc1"] + by["gemm_fc2"], gflop, rtol=1e-12)
     assert np.isclose(by["tiles_attention"], aflop, rtol=1e-12)
     assert np.isclose(by["gemm_head"], hflop, rtol=1e-12)
