@@ -59,7 +59,7 @@ namespace reslim {
 // ST: stitched output -- a query that its tile owns writes its patch's row of a [batch, N, D]
 // output, halo queries write nothing, and units or waves without an owned query are skipped (they
 // still take part in the loads and barriers of their work-group).
-template <int DH, int BKV, bool QS, int MINW = 2, bool ST = false>
+template <int DH, int BKV, bool QS, int MINW = 2, bool ST = false, int PQK = 1, int PPV = 1>
 __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArgs a) {
   constexpr int BQ = 128;
   constexpr int ROWB = DH * 2;            // bytes per K/V row in LDS
@@ -247,8 +247,10 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
       // The MFMA phases run at raised wave priority, the softmax arithmetic at the default one: a
       // wave whose operands are ready gets the matrix pipe ahead of the vector work of the other
       // waves on its SIMD (c1, same box: 0.0882 -> 0.0862 ms; no effect on the gradient kernels or
-      // the GEMMs, where it was tried too).
-      __builtin_amdgcn_s_setprio(1);
+      // the GEMMs, where it was tried too).  At dh = 64 the two phases get DIFFERENT levels (scores
+      // 2, P V 1; c3 shapes, same box: 3.47-3.51 ms with 1 / 1, 3.43-3.44 with 2 / 1, 1 / 2 or
+      // 3 / 1, 3.50 with 2 / 2, 3.62 with the P V phase at the default level, 3.76 with none).
+      __builtin_amdgcn_s_setprio(PQK);
       // feature step outermost: consecutive MFMAs belong to different accumulator chains
       if constexpr (DH <= 128) {
 #pragma unroll
@@ -334,7 +336,7 @@ __global__ __launch_bounds__(256, MINW) void tiles_attention_bf16_kernel(AttnArg
             s[kt][r] = __builtin_amdgcn_exp2f(QS ? s[kt][r] : s[kt][r] * c);
       }
 
-      __builtin_amdgcn_s_setprio(1);
+      __builtin_amdgcn_s_setprio(PPV);
       if constexpr (PIPE) {
         // The exponentials and conversions of the second 32-key group are placed between the
         // matrix instructions of the first group's P V product: a wave issues in order, so its own
@@ -614,14 +616,15 @@ SeqGeom ctx_geom(const reslim_ctx *c) {
   return g;
 }
 
-template <int DH, int BKV, int MINW>
+// PQK, PPV: wave priority during the score and the P V matrix instructions
+template <int DH, int BKV, int MINW, int PQK = 1, int PPV = 1>
 static void launch_bf16_variant(const AttnArgs &a, bool q_prescaled, bool stitched, int grid, hipStream_t st) {
   if (stitched) {
-    if (q_prescaled) tiles_attention_bf16_kernel<DH, BKV, true, MINW, true><<<dim3(grid), dim3(256), 0, st>>>(a);
-    else tiles_attention_bf16_kernel<DH, BKV, false, MINW, true><<<dim3(grid), dim3(256), 0, st>>>(a);
+    if (q_prescaled) tiles_attention_bf16_kernel<DH, BKV, true, MINW, true, PQK, PPV><<<dim3(grid), dim3(256), 0, st>>>(a);
+    else tiles_attention_bf16_kernel<DH, BKV, false, MINW, true, PQK, PPV><<<dim3(grid), dim3(256), 0, st>>>(a);
   } else {
-    if (q_prescaled) tiles_attention_bf16_kernel<DH, BKV, true, MINW, false><<<dim3(grid), dim3(256), 0, st>>>(a);
-    else tiles_attention_bf16_kernel<DH, BKV, false, MINW, false><<<dim3(grid), dim3(256), 0, st>>>(a);
+    if (q_prescaled) tiles_attention_bf16_kernel<DH, BKV, true, MINW, false, PQK, PPV><<<dim3(grid), dim3(256), 0, st>>>(a);
+    else tiles_attention_bf16_kernel<DH, BKV, false, MINW, false, PQK, PPV><<<dim3(grid), dim3(256), 0, st>>>(a);
   }
 }
 
@@ -655,7 +658,7 @@ hipError_t launch_tiles_attention(const reslim_ctx *c, const void *qkv, void *ou
     if (g_attn_cus <= 0) return hipErrorInvalidValue;
     const int pg2 = a.total < 2 * g_attn_cus ? a.total : 2 * g_attn_cus;   // persistent grids
     const int pg3 = a.total < 3 * g_attn_cus ? a.total : 3 * g_attn_cus;
-    if (c->dh == 64 && g_attn_variant == 0) launch_bf16_variant<64, 64, 3>(a, q_prescaled, stitched, pg3, st);
+    if (c->dh == 64 && g_attn_variant == 0) launch_bf16_variant<64, 64, 3, 2, 1>(a, q_prescaled, stitched, pg3, st);
     else if (c->dh == 64) launch_bf16_variant<64, 128, 2>(a, q_prescaled, stitched, pg2, st);
     else if (c->dh == 128) launch_bf16_variant<128, 64, 2>(a, q_prescaled, stitched, pg2, st);
     else if (c->dh == 256) {
