@@ -236,6 +236,25 @@ def test_forward_equals_its_entry_points_chained(cfg):
     assert np.array_equal(y, y_chain)
 
 
+def test_forward_equals_its_entry_points_chained_with_128_key_blocks(kernel_hooks):
+    """The same identity with the other launch shape of the head-dimension-64 kernel (128-key
+    blocks, two work-groups per compute unit), whose stitched form no other test reaches."""
+    cfg = SMALL_BF16
+    w = weights_for(cfg, std=0.1)
+    x = WL.make_fields(cfg)
+    y_ref = O.reslim_forward(x, w, cfg)
+    with B.Reslim(cfg, w) as m:
+        kernel_hooks.reslim_debug_set_attention_variant(1)
+        xd = cuda(x)
+        tok = m.embed(xd)
+        for l in range(cfg.depth):
+            m.block(l, tok)
+        y_chain = m.head(xd, tok).cpu().numpy()
+        y = m.forward(xd).cpu().numpy()
+    assert np.array_equal(y, y_chain)
+    assert_parity(y, y_ref, TOL[1], "forward, 128-key blocks", say)
+
+
 @pytest.mark.parametrize("cfg", [SMALL_BF16, SMALL_F32, WL.CONFIGS["c1"]], ids=lambda c: c.name)
 def test_flop_counts_are_the_sum_of_the_launch_records(cfg):
     """reslim_flop_counts (the numerator of the bench line's TFLOP/s) against the per-launch
