@@ -227,7 +227,11 @@ struct EmbedArgs {
 };
 
 // P2 = p*p when known at compile time (4 for the paper's 2x2 patches), 0 = run-time.
-template <class T, int P2>
+// PPI: patches per work item of the P2 = 4 path.  An item reads the value tables of its four
+// features for every variable (80 bytes per variable, from L2) and uses them for PPI patches, so
+// the table traffic per patch goes with 1 / PPI: at c3 1.24 ms with 4, 0.84 with 8, 0.82 with 16
+// (c4: 1.57 / 1.27 / 1.10); 16 leaves half the threads without an item below 1024 features.
+template <class T, int P2, int PPI_ = 8>
 __global__ __launch_bounds__(256) void embed_agg_kernel(EmbedArgs e) {
   constexpr int TP = 16;                      // patches per work-group
   extern __shared__ float sm[];
@@ -279,9 +283,9 @@ __global__ __launch_bounds__(256) void embed_agg_kernel(EmbedArgs e) {
   T *out = static_cast<T *>(e.o);
   if constexpr (P2 == 4) {
     if (e.dh % 4 == 0) {
-      // A work item is four adjacent features (one head) of four patches: the pixel and
-      // weight reads from LDS (broadcast over the wave) are shared by 16 outputs.
-      constexpr int PPI = 4;
+      // A work item is four adjacent features (one head) of PPI patches: the pixel and
+      // weight reads from LDS (broadcast over the wave) are shared by 4 PPI outputs.
+      constexpr int PPI = PPI_;
       const int Q = e.D / 4;
       for (int item = t; item < Q * (TP / PPI); item += 256) {
         const int dq = item % Q, p0 = (item / Q) * PPI;
@@ -352,6 +356,7 @@ hipError_t elementwise_init() {
   const int lim = 160 * 1024;
 #define RESLIM_ATTR(K) if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(&K), hipFuncAttributeMaxDynamicSharedMemorySize, lim)
   RESLIM_ATTR((embed_agg_kernel<bf16_t, 4>));
+  RESLIM_ATTR((embed_agg_kernel<bf16_t, 4, 16>));
   RESLIM_ATTR((embed_agg_kernel<bf16_t, 0>));
   RESLIM_ATTR((embed_agg_kernel<float, 4>));
   RESLIM_ATTR((embed_agg_kernel<float, 0>));
@@ -372,7 +377,8 @@ hipError_t launch_embed_agg(const reslim_ctx *c, const float *x, void *o, int ba
   if (blocks > INT32_MAX) return hipErrorInvalidValue;
   const dim3 grid(static_cast<unsigned>(blocks)), blk(256);
   const bool bf = c->cfg.dtype == RESLIM_BF16, p4 = e.p == 2;
-  if (bf && p4) embed_agg_kernel<bf16_t, 4><<<grid, blk, lds, st>>>(e);
+  if (bf && p4 && e.D >= 1024) embed_agg_kernel<bf16_t, 4, 16><<<grid, blk, lds, st>>>(e);
+  else if (bf && p4) embed_agg_kernel<bf16_t, 4><<<grid, blk, lds, st>>>(e);
   else if (bf) embed_agg_kernel<bf16_t, 0><<<grid, blk, lds, st>>>(e);
   else if (p4) embed_agg_kernel<float, 4><<<grid, blk, lds, st>>>(e);
   else embed_agg_kernel<float, 0><<<grid, blk, lds, st>>>(e);
