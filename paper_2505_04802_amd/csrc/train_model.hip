@@ -52,6 +52,61 @@ __global__ __launch_bounds__(256) void bayes_loss_bwd_kernel(const float *__rest
   d_pred[plane + static_cast<size_t>(r) * Wf + c] = data_f * lat_w[r] * (x - t) + tv_f * (ax + dg * 0.70710678118654752440f);
 }
 
+// The same for row lengths that are multiples of four: a thread owns four neighbouring columns and
+// walks down RB rows with the three rows it needs in registers, so a pixel costs a quarter of a
+// 16-byte load and half a 4-byte load of the prediction instead of nine 4-byte loads (c3: 9.2 ms
+// with one thread per pixel).  A neighbour outside the plane is held as NaN: every comparison with
+// it is false, so its sign term is zero, which is what leaving it out means.  The sums of signs are
+// small integers, exact in any order.
+template <int RB>
+__global__ __launch_bounds__(256) void bayes_loss_bwd4_kernel(const float *__restrict__ pred, const float *__restrict__ target,
+                                                              const float *__restrict__ lat_w, float *__restrict__ d_pred,
+                                                              int Hf, int Wf, float data_f, float tv_f) {
+  const int c0 = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (c0 >= Wf) return;
+  const size_t plane = static_cast<size_t>(blockIdx.z) * Hf * Wf;
+  const float *xp = pred + plane;
+  const int r_begin = blockIdx.y * RB, r_end = min(Hf, r_begin + RB);
+  const float out_of_plane = __builtin_nanf("");
+  auto sgn = [](float v) { return static_cast<float>((v > 0.f) - (v < 0.f)); };
+  auto load_row = [&](int r, float (&v)[6]) {      // columns c0 - 1 .. c0 + 4 of row r
+    if (r < 0 || r >= Hf) {
+#pragma unroll
+      for (int k = 0; k < 6; ++k) v[k] = out_of_plane;
+      return;
+    }
+    const float *row = xp + static_cast<size_t>(r) * Wf;
+    const float4 m = *reinterpret_cast<const float4 *>(row + c0);
+    v[1] = m.x; v[2] = m.y; v[3] = m.z; v[4] = m.w;
+    v[0] = c0 > 0 ? row[c0 - 1] : out_of_plane;
+    v[5] = c0 + 4 < Wf ? row[c0 + 4] : out_of_plane;
+  };
+  float up[6], mid[6], dn[6];
+  load_row(r_begin - 1, up);
+  load_row(r_begin, mid);
+#pragma unroll
+  for (int i = 0; i < RB; ++i) {
+    const int r = r_begin + i;
+    if (r >= r_end) break;
+    load_row(r + 1, dn);
+    const size_t at = plane + static_cast<size_t>(r) * Wf + c0;
+    const float4 t4 = *reinterpret_cast<const float4 *>(target + at);
+    const float t[4] = {t4.x, t4.y, t4.z, t4.w};
+    const float lw = data_f * lat_w[r];
+    float o[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float x = mid[k + 1];
+      const float ax = sgn(x - up[k + 1]) + sgn(x - dn[k + 1]) + sgn(x - mid[k]) + sgn(x - mid[k + 2]);
+      const float dg = sgn(x - up[k]) + sgn(x - up[k + 2]) + sgn(x - dn[k]) + sgn(x - dn[k + 2]);
+      o[k] = lw * (x - t[k]) + tv_f * (ax + dg * 0.70710678118654752440f);
+    }
+    *reinterpret_cast<float4 *>(d_pred + at) = make_float4(o[0], o[1], o[2], o[3]);
+#pragma unroll
+    for (int k = 0; k < 6; ++k) { up[k] = mid[k]; mid[k] = dn[k]; }
+  }
+}
+
 // ------------------------------------------------------------------ back end
 // d_P[b, n, (c, i, j)] = d_y[b, c, py ps + i, px ps + j]  (transpose of un-patchify), stored as activation type
 template <typename T>
@@ -995,8 +1050,15 @@ extern "C" int reslim_bayes_loss_bwd(const float *pred, const float *target, con
   const double norm = 4.0 + 4.0 / 1.4142135623730951;
   const float data_f = static_cast<float>(2.0 * upstream / count);
   const float tv_f = static_cast<float>(2.0 * static_cast<double>(upstream) * tv_weight / (norm * count));
-  const dim3 grid((Wf + 255) / 256, Hf, batch * vars);
-  bayes_loss_bwd_kernel<<<grid, dim3(256), 0, static_cast<hipStream_t>(hip_stream)>>>(pred, target, lat_w, d_pred, Hf, Wf, data_f, tv_f);
+  const bool aligned = Wf % 4 == 0 && (reinterpret_cast<uintptr_t>(pred) | reinterpret_cast<uintptr_t>(target) | reinterpret_cast<uintptr_t>(d_pred)) % 16 == 0;
+  if (aligned) {
+    constexpr int RB = 8;
+    const dim3 grid((Wf / 4 + 255) / 256, (Hf + RB - 1) / RB, batch * vars);
+    bayes_loss_bwd4_kernel<RB><<<grid, dim3(256), 0, static_cast<hipStream_t>(hip_stream)>>>(pred, target, lat_w, d_pred, Hf, Wf, data_f, tv_f);
+  } else {
+    const dim3 grid((Wf + 255) / 256, Hf, batch * vars);
+    bayes_loss_bwd_kernel<<<grid, dim3(256), 0, static_cast<hipStream_t>(hip_stream)>>>(pred, target, lat_w, d_pred, Hf, Wf, data_f, tv_f);
+  }
   return hipGetLastError() == hipSuccess ? RESLIM_OK : RESLIM_EHIP;
 }
 
