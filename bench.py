@@ -30,22 +30,22 @@ ALU_BOUND = ("embed_agg",)      # kernels whose time is plain fp32 vector arithm
 # Source: profiles/forward_and_train_block_c1_all_kernels.md (fetched + written, scaled by the copy kernel).
 # FC2 and the projection share one kernel symbol in every profile: no separate figure for them.
 MEASURED_TRAFFIC = {
-    ("c1", "gemm_fc1"): 140.6e6 + 167.6e6,
-    ("c1", "tiles_attention"): 203.4e6,            # both kernel symbols (five launches of six, the last block's one), weighted
+    ("c1", "gemm_fc1"): 140.5e6 + 167.6e6,
+    ("c1", "tiles_attention"): 203.8e6,            # both kernel symbols (five launches of six, the last block's one), weighted
     ("c1", "gemm_qkv"): 98.2e6 + 130.7e6,
     ("c1", "layernorm"): 84.7e6 + 42.3e6,
     # profiles/forward_and_train_block_c2_all_kernels.md
-    ("c2", "gemm_fc1"): 1961.1e6 + 1300.5e6,
-    ("c2", "gemm_qkv"): 1496.9e6 + 991.7e6,
-    ("c2", "tiles_attention"): 2323.2e6,           # both kernel symbols, weighted 11 : 1
+    ("c2", "gemm_fc1"): 1961.5e6 + 1300.5e6,
+    ("c2", "gemm_qkv"): 1504.2e6 + 991.7e6,
+    ("c2", "tiles_attention"): 2321.4e6,           # both kernel symbols, weighted 11 : 1
     ("c2", "layernorm"): 651.8e6 + 325.9e6,
     # profiles/forward_c3_all_kernels.md
-    ("c3", "gemm_fc1"): 4747.3e6 + 3155.6e6,
-    ("c3", "gemm_qkv"): 3779.2e6 + 2477.3e6,
-    ("c3", "tiles_attention"): 8630.6e6,          # both kernel symbols (seven launches of eight, the last block's one), weighted
-    ("c3", "layernorm"): 1580.1e6 + 791.1e6,
-    ("c3", "residual_unpatchify"): 4860.0e6 + 4246.7e6,
-    ("c3", "gemm_head"): 3222.9e6 + 4252.4e6,
+    ("c3", "gemm_fc1"): 4749.4e6 + 3155.6e6,
+    ("c3", "gemm_qkv"): 3812.2e6 + 2477.3e6,
+    ("c3", "tiles_attention"): 8763.7e6,          # both kernel symbols (seven launches of eight, the last block's one), weighted
+    ("c3", "layernorm"): 1580.0e6 + 791.1e6,
+    ("c3", "residual_unpatchify"): 4860.3e6 + 4246.7e6,
+    ("c3", "gemm_head"): 3278.1e6 + 4252.4e6,
 }
 
 
